@@ -1,0 +1,239 @@
+/*
+ * actionstudio.h -- C interface of the MI355X (gfx950) fine-tuning step.
+ *
+ * The library computes the hot path of the ActionStudio training pipeline
+ * (paper Section 3.2): trajectories are turned into packed token rows with a
+ * role-derived loss mask (Section 3.2.1, Universal Data Parser), and one
+ * supervised fine-tuning step -- forward and backward of a decoder-only
+ * transformer under LoRA or full fine-tuning (Section 3.2.2; LoRA setting of
+ * Section 4.5) -- is run on them, followed by an AdamW update (learning-rate
+ * range and schedule: Section 4.1).
+ *
+ * General rules
+ *  - Every pointer is marked [host] or [device].  Device buffers are
+ *    allocated and freed by the caller; the library keeps no device pointer
+ *    after a call returns.  The only device memory the library owns is a
+ *    staging buffer inside as_ctx used by as_pack (grown on demand).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls enqueue work and return without waiting, except as_pack, which
+ *    waits for its own upload; results are valid once the stream has been
+ *    synchronised.
+ *  - Matrices are row-major.  A linear map y = W x stores W as [out, in].
+ *  - Every function returns AS_OK (0) or a negative as_status.  Conditions
+ *    that can be checked on the host are checked before anything is
+ *    launched; after an error no output is defined.  as_last_error() gives a
+ *    message for the last failing call on that context (or, for a NULL
+ *    context, the last failing call of the calling thread).
+ *  - Same inputs give bit-identical outputs: no floating-point atomics.
+ *  - Element type "T" below is float in AS_FP32 mode and bfloat16 in AS_BF16
+ *    mode.  LoRA matrices and all gradients are always float.
+ */
+#ifndef ACTIONSTUDIO_H
+#define ACTIONSTUDIO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  AS_OK = 0,
+  AS_ERR_NULL = -1,        /* a required pointer is NULL                         */
+  AS_ERR_CONFIG = -2,      /* as_model_config is inconsistent or unsupported     */
+  AS_ERR_SHAPE = -3,       /* sizes do not fit each other or the configuration   */
+  AS_ERR_CU_SEQLENS = -4,  /* segment table is not a valid partition             */
+  AS_ERR_TOKEN_RANGE = -5, /* token id outside [0, vocab)                        */
+  AS_ERR_ROLE = -6,        /* role code outside 0..3                             */
+  AS_ERR_TOO_LONG = -7,    /* trajectory longer than a row, truncation disabled  */
+  AS_ERR_WORKSPACE = -8,   /* workspace missing, misaligned or too small         */
+  AS_ERR_HIP = -9          /* a HIP runtime call failed                          */
+} as_status;
+
+/* Roles of Unified Format 2.0 (paper, Appendix "Unified Format 2.0").  Only
+ * assistant tokens bear loss. */
+enum { AS_ROLE_SYSTEM = 0, AS_ROLE_USER = 1, AS_ROLE_ASSISTANT = 2, AS_ROLE_TOOL = 3 };
+
+enum { AS_FP32 = 0, AS_BF16 = 1 };            /* as_model_config.mode        */
+enum { AS_LORA = 0, AS_FULL = 1 };            /* as_model_config.train_mode  */
+
+/* LoRA targets: index into the a[]/b[] arrays below and bit position in
+ * as_model_config.lora_targets. */
+enum { AS_T_Q = 0, AS_T_K, AS_T_V, AS_T_O, AS_T_GATE, AS_T_UP, AS_T_DOWN, AS_T_ROUTER, AS_N_TARGETS };
+
+typedef struct as_ctx as_ctx;
+
+typedef struct {
+  uint32_t struct_size;            /* sizeof(as_model_config), for versioning    */
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  int32_t n_experts, top_k;        /* 0, 0 for a dense FFN                       */
+  float rms_eps, rope_base;
+  int32_t lora_rank;               /* 0 when train_mode == AS_FULL               */
+  float lora_alpha;                /* scale = lora_alpha / lora_rank             */
+  uint32_t lora_targets;           /* bit i set: target i carries an adapter     */
+  int32_t mode;                    /* AS_FP32 | AS_BF16                          */
+  int32_t train_mode;              /* AS_LORA | AS_FULL                          */
+  int32_t recompute;               /* 1: keep only layer inputs, re-run a layer's
+                                      forward before its backward                */
+} as_model_config;
+
+/* Frozen (LoRA) or trainable (full) weights of one layer.  [device], type T.
+ * g1,g2 [d_model]; wq [Hq*dh, d]; wk,wv [Hkv*dh, d]; wo [d, Hq*dh];
+ * wgate,wup [ffn, d]; wdown [d, ffn]  (MoE: [n_experts, ...] stacked);
+ * wrouter [n_experts, d] or NULL. */
+typedef struct {
+  const void *g1, *wq, *wk, *wv, *wo, *g2, *wgate, *wup, *wdown, *wrouter;
+} as_layer_weights;
+
+typedef struct {
+  const void* embed;               /* [device] T [vocab, d]                      */
+  const void* g_final;             /* [device] T [d]                             */
+  const void* head;                /* [device] T [vocab, d] (not tied to embed)  */
+  const as_layer_weights* layers;  /* [host] array of n_layers                   */
+} as_weights;
+
+/* Adapters of one layer: a[i] is A_i [rank, d_in], b[i] is B_i [d_out, rank],
+ * [device] float, NULL for targets without an adapter. */
+typedef struct {
+  const float* a[AS_N_TARGETS];
+  const float* b[AS_N_TARGETS];
+} as_layer_lora;
+
+typedef struct {
+  const as_layer_lora* layers;     /* [host] array of n_layers                   */
+} as_lora;
+
+/* Gradient outputs, all [device] float, same shapes as what they belong to.
+ * LoRA mode fills lora_layers; full mode fills the weight gradients. */
+typedef struct {
+  float* a[AS_N_TARGETS];
+  float* b[AS_N_TARGETS];
+} as_layer_lora_grads;
+
+typedef struct {
+  float *g1, *wq, *wk, *wv, *wo, *g2, *wgate, *wup, *wdown, *wrouter;
+} as_layer_weight_grads;
+
+typedef struct {
+  const as_layer_lora_grads* lora_layers;    /* [host] n_layers, LoRA mode       */
+  const as_layer_weight_grads* w_layers;     /* [host] n_layers, full mode       */
+  float *embed, *g_final, *head;             /* [device], full mode              */
+} as_grads;
+
+/* ---- context ------------------------------------------------------------ */
+
+/* Validates the configuration and binds the context to HIP device `device`.
+ * Supported: head_dim in {32, 64, 128}; n_q_heads a multiple of n_kv_heads;
+ * d_model, ffn, head counts positive; lora_rank in [1, 256] with at least one
+ * target bit in LoRA mode.  AS_ERR_CONFIG otherwise. */
+int as_create(as_ctx** out, const as_model_config* cfg, int device);
+void as_destroy(as_ctx* ctx);
+const char* as_last_error(const as_ctx* ctx);
+
+/* Bytes of device workspace as_train_step needs for up to max_rows rows of
+ * row_len tokens.  The workspace must be 256-byte aligned. */
+int as_workspace_bytes(const as_ctx* ctx, int64_t max_rows, int64_t row_len, size_t* bytes);
+
+/* ---- pack (Section 3.2.1) ----------------------------------------------- */
+
+/* Packs trajectories into rows of row_len tokens.
+ *  turn_tokens  [host] int32, all turns back to back
+ *  turn_offsets [host] int32 [n_turns+1], token offset of each turn
+ *  turn_roles   [host] uint8 [n_turns]
+ *  traj_offsets [host] int32 [n_traj+1], first turn of each trajectory
+ * Policy: trajectories in input order; a trajectory that does not fit behind
+ * the current fill of the open row closes it (tail filled with pad_id) and
+ * opens the next; a trajectory longer than row_len keeps its first row_len
+ * tokens if `truncate`, else AS_ERR_TOO_LONG; empty trajectories are consumed
+ * and leave nothing; packing stops after max_rows rows.
+ * Outputs: d_tokens [device] int32 [max_rows*row_len] (first n_rows*row_len
+ * written), d_loss_mask [device] uint8 likewise (1 = token of an assistant
+ * turn), d_cu_seqlens [device] int32 with room for n_traj + max_rows + 1
+ * entries: boundaries of all segments of the flat stream, every trajectory
+ * and every non-empty pad tail being one segment.  The three counters are
+ * [host].  Token ids are checked against the context's vocab. */
+int as_pack(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* turn_offsets,
+            const uint8_t* turn_roles, const int32_t* traj_offsets, int32_t n_traj,
+            int32_t row_len, int32_t max_rows, int32_t pad_id, int32_t truncate,
+            int32_t* d_tokens, int32_t* d_cu_seqlens, uint8_t* d_loss_mask,
+            int32_t* n_rows_out, int32_t* n_segments_out, int32_t* n_traj_consumed_out,
+            void* stream);
+
+/* ---- one training step (Sections 3.2.2, 4.5) ---------------------------- */
+
+/* Forward and backward of the masked next-token loss over n_rows*row_len
+ * packed tokens.  Position t is a target when token t+1 lies in the same
+ * segment and d_loss_mask[t+1] == 1; the loss is the mean over targets of
+ * logsumexp(z_t) - z_t[token_{t+1}].  Attention is causal inside a segment
+ * and never crosses a boundary of d_cu_seqlens; rotary positions restart at
+ * each segment.
+ *  h_cu_seqlens [host] copy of the segment table, checked before launch
+ *               (starts at 0, strictly increasing, ends at n_rows*row_len, no
+ *               segment crossing a row end) -- AS_ERR_CU_SEQLENS otherwise.
+ *  d_loss, d_loss_sum [device] float[1]; d_count [device] int32[1].
+ *  lora NULL in full mode.  Gradients are overwritten.  With no target at
+ *  all, the loss and every gradient are exactly zero. */
+int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lora* lora,
+                  const int32_t* d_tokens, const int32_t* d_cu_seqlens,
+                  const int32_t* h_cu_seqlens, int32_t n_segments,
+                  const uint8_t* d_loss_mask, int32_t n_rows, int32_t row_len,
+                  float* d_loss, float* d_loss_sum, int32_t* d_count,
+                  const as_grads* grads, void* d_workspace, size_t workspace_bytes,
+                  void* stream);
+
+/* ---- AdamW (Section 4.1 hyper-parameters) -------------------------------- */
+
+/* m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
+ * w <- w - lr * ( m/(1-b1^step) / (sqrt(v/(1-b2^step)) + eps) + wd * w ),
+ * the decay using w before the update, skipped where apply_wd[i] == 0.
+ * Arrays of n_tensors [host] entries holding [device] pointers:
+ *  d_master float (the fp32 weights that are updated); d_params_lowp either
+ *  NULL or, per tensor, NULL or a bfloat16 copy rewritten from the master
+ *  (round to nearest even); d_grads, d_m, d_v float.  step counts from 1. */
+int as_adamw_update(as_ctx* ctx, float* const* d_master, void* const* d_params_lowp,
+                    const float* const* d_grads, float* const* d_m, float* const* d_v,
+                    const int64_t* numel, const uint8_t* apply_wd, int32_t n_tensors,
+                    int64_t step, float lr, float beta1, float beta2, float eps,
+                    float weight_decay, void* stream);
+
+/* ---- building blocks (the kernels of as_train_step, one at a time) ------- *
+ * All pointers [device] unless marked.  `mode` picks T as above.            */
+
+/* C[M,N] = alpha * ( A1[M,K1] B1[N,K1]^T + A2[M,K2] B2[N,K2]^T ) (+ R[M,N]),
+ * the second product being the low-rank LoRA term folded into the same
+ * accumulation (Section 4.5); A2 may be NULL.  A, B, R of type T; C of type T,
+ * or float when c_is_f32.  variant: 0 = pick, 1 = plain FMA kernel,
+ * 2 = MFMA kernel (bf16 only; K1, K2, lda, ldb multiples of 8). */
+int as_op_gemm(as_ctx* ctx, int mode, int variant, int64_t M, int64_t N,
+               const void* A1, int64_t lda1, const void* B1, int64_t ldb1, int64_t K1,
+               const void* A2, int64_t lda2, const void* B2, int64_t ldb2, int64_t K2,
+               float alpha, const void* R, int64_t ldr, void* C, int64_t ldc, int c_is_f32,
+               void* stream);
+
+/* y = x * rstd * g with rstd = (mean x^2 + eps)^-1/2 per row; rstd float[n]. */
+int as_op_rmsnorm_fwd(as_ctx* ctx, int mode, int64_t n, int64_t d, const void* x, const void* g,
+                      float eps, void* y, float* rstd, void* stream);
+/* dx = rstd g dy - x rstd^3/d sum_j(g_j dy_j x_j) (+ add, type T, may be NULL). */
+int as_op_rmsnorm_bwd(as_ctx* ctx, int mode, int64_t n, int64_t d, const void* dy, const void* x,
+                      const void* g, const float* rstd, const void* add, void* dx, void* stream);
+
+/* Varlen causal attention with grouped KV heads over packed rows.  q [n,Hq,dh]
+ * with row stride ldq elements, k, v [n,Hkv,dh] with stride ldkv, o [n,Hq,dh]
+ * dense, lse float [n,Hq].  seg_start [n] int32: first token of each token's
+ * segment.  variant: 0 = pick, 1 = plain kernel, 2 = MFMA kernel (bf16). */
+int as_op_attention_fwd(as_ctx* ctx, int mode, int variant, int64_t n, const int32_t* seg_start,
+                        const void* q, int64_t ldq, const void* k, const void* v, int64_t ldkv,
+                        void* o, float* lse, void* stream);
+/* seg_end [n] int32: one past the last token of each token's segment.
+ * dq, dk, dv have the layout of q, k, v (strides ldq, ldkv). */
+int as_op_attention_bwd(as_ctx* ctx, int mode, int variant, int64_t n, const int32_t* seg_start,
+                        const int32_t* seg_end, const void* q, int64_t ldq, const void* k,
+                        const void* v, int64_t ldkv, const void* o, const float* lse,
+                        const void* d_o, void* dq, void* dk, void* dv, float* delta_scratch,
+                        void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ACTIONSTUDIO_H */

@@ -1,0 +1,779 @@
+// C interface: argument checks, the host half of packing, the workspace plan
+// and the launch sequence of one training step.
+#include "common.h"
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+#include <vector>
+#include <algorithm>
+
+static thread_local std::string g_tls_err;
+
+int as_fail(as_ctx* ctx, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap; va_start(ap, fmt); vsnprintf(buf, sizeof buf, fmt, ap); va_end(ap);
+  g_tls_err = buf;
+  if (ctx) ctx->err = buf;
+  return code;
+}
+
+// ------------------------------------------------------------------ context
+static const char* kTargetName[AS_N_TARGETS] = {"q", "k", "v", "o", "gate", "up", "down", "router"};
+
+static int check_config(const as_model_config* c) {
+  if (c->struct_size != sizeof(as_model_config)) return as_fail(nullptr, AS_ERR_CONFIG, "struct_size %u != %zu", c->struct_size, sizeof(as_model_config));
+  if (c->n_layers < 1 || c->d_model < 1 || c->ffn < 1 || c->vocab < 2) return as_fail(nullptr, AS_ERR_CONFIG, "non-positive model size");
+  if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads) return as_fail(nullptr, AS_ERR_CONFIG, "n_q_heads must be a positive multiple of n_kv_heads");
+  if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return as_fail(nullptr, AS_ERR_CONFIG, "head_dim must be 32, 64 or 128");
+  if (c->mode != AS_FP32 && c->mode != AS_BF16) return as_fail(nullptr, AS_ERR_CONFIG, "mode");
+  if (c->train_mode != AS_LORA && c->train_mode != AS_FULL) return as_fail(nullptr, AS_ERR_CONFIG, "train_mode");
+  if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f)) return as_fail(nullptr, AS_ERR_CONFIG, "rms_eps / rope_base");
+  if (c->n_experts != 0 || c->top_k != 0) return as_fail(nullptr, AS_ERR_CONFIG, "mixture-of-experts layers are not supported by this build");
+  if (c->train_mode == AS_LORA) {
+    if (c->lora_rank < 1 || c->lora_rank > 256) return as_fail(nullptr, AS_ERR_CONFIG, "lora_rank must be in [1, 256]");
+    if (!(c->lora_targets & 0x7f)) return as_fail(nullptr, AS_ERR_CONFIG, "LoRA mode needs at least one target");
+    if (c->lora_targets & ~0x7fu) return as_fail(nullptr, AS_ERR_CONFIG, "router adapters need a mixture-of-experts model");
+  } else if (c->lora_rank != 0 || c->lora_targets != 0) {
+    return as_fail(nullptr, AS_ERR_CONFIG, "full fine-tuning takes no adapters");
+  }
+  if (c->recompute != 0 && c->recompute != 1) return as_fail(nullptr, AS_ERR_CONFIG, "recompute must be 0 or 1");
+  return AS_OK;
+}
+
+extern "C" int as_create(as_ctx** out, const as_model_config* cfg, int device) {
+  if (!out || !cfg) return as_fail(nullptr, AS_ERR_NULL, "as_create: NULL argument");
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  as_ctx* c = new as_ctx();
+  c->cfg = *cfg;
+  c->device = device;
+  *out = c;
+  return AS_OK;
+}
+
+extern "C" void as_destroy(as_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->d_stage) (void)hipFree(ctx->d_stage);
+  if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
+  delete ctx;
+}
+
+extern "C" const char* as_last_error(const as_ctx* ctx) {
+  return ctx ? ctx->err.c_str() : g_tls_err.c_str();
+}
+
+// ------------------------------------------------------------------- pack
+struct Piece { int32_t dst, src; uint8_t mask; };
+
+static int ensure_stage(as_ctx* ctx, size_t bytes) {
+  if (bytes > ctx->d_stage_bytes) {
+    if (ctx->d_stage) (void)hipFree(ctx->d_stage);
+    ctx->d_stage = nullptr; ctx->d_stage_bytes = 0;
+    AS_HIP(ctx, hipMalloc(&ctx->d_stage, bytes));
+    ctx->d_stage_bytes = bytes;
+  }
+  if (bytes > ctx->h_stage_bytes) {
+    if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
+    ctx->h_stage = nullptr; ctx->h_stage_bytes = 0;
+    AS_HIP(ctx, hipHostMalloc(&ctx->h_stage, bytes, hipHostMallocDefault));
+    ctx->h_stage_bytes = bytes;
+  }
+  return AS_OK;
+}
+
+// Host half of packing: validation, next-fit row assignment, piece list and
+// segment table.  Touches no GPU state, so it can be tested without one.
+static int pack_plan(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* turn_offsets,
+                     const uint8_t* turn_roles, const int32_t* traj_offsets, int32_t n_traj,
+                     int32_t T, int32_t max_rows, int32_t truncate, std::vector<Piece>& pieces,
+                     std::vector<int32_t>& cu, int32_t* n_rows, int32_t* n_consumed) {
+  const int vocab = ctx->cfg.vocab;
+  if (T <= 0 || max_rows < 0 || n_traj < 0) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: row_len must be positive, counts non-negative");
+  if ((int64_t)T * max_rows > INT32_MAX) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: max_rows*row_len exceeds int32");
+  if (traj_offsets[0] != 0 || turn_offsets[0] != 0) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: offsets must start at 0");
+  pieces.clear(); cu.clear(); cu.push_back(0);
+  int32_t fill = 0, rows = 0, consumed = 0; bool open = false;
+  auto close_row = [&]() {
+    if (fill < T) { pieces.push_back({rows * T + fill, -1, 0}); cu.push_back((rows + 1) * T); }
+    rows++; fill = 0; open = false;
+  };
+  for (int32_t i = 0; i < n_traj && rows < max_rows; i++) {
+    int32_t t0 = traj_offsets[i], t1 = traj_offsets[i + 1];
+    if (t1 < t0) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: traj_offsets must not decrease (trajectory %d)", i);
+    int64_t L = 0;
+    for (int32_t t = t0; t < t1; t++) {
+      if (turn_offsets[t + 1] < turn_offsets[t]) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: turn_offsets must not decrease (turn %d)", t);
+      if (turn_roles[t] > AS_ROLE_TOOL) return as_fail(ctx, AS_ERR_ROLE, "as_pack: role code %d of turn %d is outside 0..3", (int)turn_roles[t], t);
+      for (int32_t k = turn_offsets[t]; k < turn_offsets[t + 1]; k++)
+        if (turn_tokens[k] < 0 || turn_tokens[k] >= vocab)
+          return as_fail(ctx, AS_ERR_TOKEN_RANGE, "as_pack: token %d at offset %d is outside [0, %d)", turn_tokens[k], k, vocab);
+      L += turn_offsets[t + 1] - turn_offsets[t];
+    }
+    if (L == 0) { consumed++; continue; }
+    if (L > T) {
+      if (!truncate) return as_fail(ctx, AS_ERR_TOO_LONG, "as_pack: trajectory %d has %lld tokens, row_len is %d", i, (long long)L, T);
+      L = T;
+    }
+    if (open && fill + L > T) { close_row(); if (rows >= max_rows) break; }
+    open = true;
+    int32_t left = (int32_t)L;
+    for (int32_t t = t0; t < t1 && left > 0; t++) {
+      int32_t len = std::min(turn_offsets[t + 1] - turn_offsets[t], left);
+      if (len <= 0) continue;
+      pieces.push_back({rows * T + fill, turn_offsets[t], (uint8_t)(turn_roles[t] == AS_ROLE_ASSISTANT)});
+      fill += len; left -= len;
+    }
+    cu.push_back(rows * T + fill);
+    consumed++;
+    if (fill == T) { rows++; fill = 0; open = false; }
+  }
+  if (open) close_row();
+  *n_rows = rows; *n_consumed = consumed;
+  return AS_OK;
+}
+
+extern "C" int as_pack(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* turn_offsets,
+                       const uint8_t* turn_roles, const int32_t* traj_offsets, int32_t n_traj,
+                       int32_t row_len, int32_t max_rows, int32_t pad_id, int32_t truncate,
+                       int32_t* d_tokens, int32_t* d_cu_seqlens, uint8_t* d_loss_mask,
+                       int32_t* n_rows_out, int32_t* n_segments_out, int32_t* n_traj_consumed_out,
+                       void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_pack: NULL context");
+  if (!turn_offsets || !traj_offsets || !n_rows_out || !n_segments_out || !n_traj_consumed_out)
+    return as_fail(ctx, AS_ERR_NULL, "as_pack: NULL offsets or counters");
+  if (n_traj > 0 && traj_offsets[n_traj] > 0 && (!turn_roles || (turn_offsets[traj_offsets[n_traj]] > 0 && !turn_tokens)))
+    return as_fail(ctx, AS_ERR_NULL, "as_pack: NULL turn arrays");
+  if (!d_cu_seqlens || (max_rows > 0 && row_len > 0 && (!d_tokens || !d_loss_mask)))
+    return as_fail(ctx, AS_ERR_NULL, "as_pack: NULL output");
+  std::vector<Piece> pieces; std::vector<int32_t> cu;
+  int32_t rows = 0, consumed = 0;
+  int rc = pack_plan(ctx, turn_tokens, turn_offsets, turn_roles, traj_offsets, n_traj, row_len, max_rows,
+                     truncate, pieces, cu, &rows, &consumed);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  const int32_t n_tok = n_traj > 0 ? turn_offsets[traj_offsets[n_traj]] : 0;
+  const size_t np = pieces.size();
+  // staging layout: tokens | piece_dst | piece_src | cu | piece_mask
+  size_t o_tok = 0, o_dst = o_tok + (size_t)n_tok * 4, o_src = o_dst + np * 4, o_cu = o_src + np * 4,
+         o_msk = o_cu + cu.size() * 4, total = o_msk + np;
+  total = (total + 255) & ~(size_t)255;
+  rc = ensure_stage(ctx, total);
+  if (rc) return rc;
+  char* h = (char*)ctx->h_stage; char* d = (char*)ctx->d_stage;
+  if (n_tok) memcpy(h + o_tok, turn_tokens, (size_t)n_tok * 4);
+  for (size_t i = 0; i < np; i++) {
+    ((int32_t*)(h + o_dst))[i] = pieces[i].dst;
+    ((int32_t*)(h + o_src))[i] = pieces[i].src;
+    ((uint8_t*)(h + o_msk))[i] = pieces[i].mask;
+  }
+  memcpy(h + o_cu, cu.data(), cu.size() * 4);
+  AS_HIP(ctx, hipMemcpyAsync(d, h, total, hipMemcpyHostToDevice, st));
+  AS_HIP(ctx, hipMemcpyAsync(d_cu_seqlens, d + o_cu, cu.size() * 4, hipMemcpyDeviceToDevice, st));
+  if (np) {
+    rc = launch_pack(ctx, (const int32_t*)(d + o_tok), (const int32_t*)(d + o_dst), (const int32_t*)(d + o_src),
+                     (const uint8_t*)(d + o_msk), (int)np, rows * row_len, pad_id, d_tokens, d_loss_mask, st);
+    if (rc) return rc;
+  }
+  AS_HIP(ctx, hipStreamSynchronize(st));       // the staging buffer is free again
+  *n_rows_out = rows; *n_segments_out = (int32_t)cu.size() - 1; *n_traj_consumed_out = consumed;
+  return AS_OK;
+}
+
+// --------------------------------------------------------- workspace plan
+struct Bump {
+  char* base; size_t off;
+  void* take(size_t bytes) {
+    off = (off + 255) & ~(size_t)255;
+    void* p = base ? base + off : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+struct LoraSlot {       // prepared copies of one adapter (type T)
+  bool on = false;
+  int din = 0, dout = 0;
+  void *A = nullptr;    // [rp, din]   rows beyond rank are zero   (lives inside a concatenated group)
+  void *At = nullptr;   // [din, group_cols] column block of the group transpose
+  void *Bs = nullptr;   // [dout, rp]  = scale * B, zero padded
+  void *Bst = nullptr;  // [rp, dout]
+  int slot = 0;         // position inside its group (qkv / o / gate-up / down)
+};
+
+struct Acts {           // activations of one layer kept for its backward
+  float *rstd1, *rstd2, *lse;
+  void *a, *qkv, *o, *h_mid, *b, *gu, *m;
+  void *u_qkv, *u_o, *u_gu, *u_d;
+};
+
+struct Plan {
+  int N, d, D, Dkv, QKV, F, V, L, rp, es, Mc;
+  int n_qkv, n_gu;                       // adapters inside the q/k/v and gate/up groups
+  int32_t *seg_start, *seg_end, *tgt_idx, *tgt_pos, *labels, *count, *iscratch;
+  float *rope_cos, *rope_sin, *loss_rows, *rstd_f, *logits, *delta, *partial, *gpart;
+  std::vector<void*> h;                  // L+1 residual-stream snapshots
+  std::vector<Acts> acts;
+  void *hf, *P, *dhf, *headT, *Pt, *hfT;
+  void *dh, *dh2, *dm, *dgu, *db, *d_o, *dqkv, *da;
+  void *du_qkv, *du_o, *du_gu, *du_d;
+  void *wT, *xT, *dyT, *uT, *duT;
+  std::vector<LoraSlot> lora;            // L * 7
+  std::vector<void*> A_qkv, At_qkv, A_gu, At_gu;   // per layer concatenated groups
+  size_t partial_floats;
+};
+
+static int pick_splitk(int mode, int M, int N, int K) {
+  int bm = 64, bn = 64;
+  if (mode == AS_BF16) { if (N <= 128 && M > 128) { bm = 256; bn = 64; } else if (M <= 128) { bm = 64; bn = 256; } else { bm = 256; bn = 256; } }
+  int64_t blocks = cdiv(M, bm) * cdiv(N, bn);
+  int64_t s = cdiv(512, blocks);
+  int64_t smax = std::max<int64_t>(1, K / 256);
+  return (int)std::max<int64_t>(1, std::min(s, smax));
+}
+
+static void target_dims(const as_model_config& c, int t, int* din, int* dout) {
+  int D = c.n_q_heads * c.head_dim, Dkv = c.n_kv_heads * c.head_dim;
+  switch (t) {
+    case AS_T_Q: *din = c.d_model; *dout = D; break;
+    case AS_T_K: case AS_T_V: *din = c.d_model; *dout = Dkv; break;
+    case AS_T_O: *din = D; *dout = c.d_model; break;
+    case AS_T_GATE: case AS_T_UP: *din = c.d_model; *dout = c.ffn; break;
+    default: *din = c.ffn; *dout = c.d_model; break;
+  }
+}
+
+static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w, Plan& P) {
+  const as_model_config& c = ctx->cfg;
+  const bool full = c.train_mode == AS_FULL;
+  P.N = (int)(rows * row_len); P.d = c.d_model; P.D = c.n_q_heads * c.head_dim; P.Dkv = c.n_kv_heads * c.head_dim;
+  P.QKV = P.D + 2 * P.Dkv; P.F = c.ffn; P.V = c.vocab; P.L = c.n_layers;
+  P.es = c.mode == AS_FP32 ? 4 : 2;
+  P.rp = full ? 0 : (int)cdiv(c.lora_rank, 16) * 16;
+  P.Mc = (int)std::min<int64_t>(4096, cdiv(std::max(P.N, 1), 64) * 64);
+  const size_t N = (size_t)P.N, es = (size_t)P.es;
+  auto on = [&](int t) { return !full && ((c.lora_targets >> t) & 1u); };
+  P.n_qkv = on(AS_T_Q) + on(AS_T_K) + on(AS_T_V);
+  P.n_gu = on(AS_T_GATE) + on(AS_T_UP);
+  const size_t rp = (size_t)P.rp;
+
+  P.seg_start = (int32_t*)w.take(N * 4); P.seg_end = (int32_t*)w.take(N * 4);
+  P.tgt_idx = (int32_t*)w.take(N * 4); P.tgt_pos = (int32_t*)w.take(N * 4); P.labels = (int32_t*)w.take(N * 4);
+  P.count = (int32_t*)w.take(256);
+  P.iscratch = (int32_t*)w.take(full ? 2 * N * 4 : 0);
+  P.rope_cos = (float*)w.take((size_t)row_len * (c.head_dim / 2) * 4);
+  P.rope_sin = (float*)w.take((size_t)row_len * (c.head_dim / 2) * 4);
+  P.loss_rows = (float*)w.take(N * 4);
+  P.rstd_f = (float*)w.take(N * 4);
+  P.h.resize(P.L + 1);
+  for (int l = 0; l <= P.L; l++) P.h[l] = w.take(N * P.d * es);
+  const int n_sets = c.recompute ? 1 : P.L;
+  P.acts.resize(n_sets);
+  for (int s = 0; s < n_sets; s++) {
+    Acts& a = P.acts[s];
+    a.rstd1 = (float*)w.take(N * 4); a.rstd2 = (float*)w.take(N * 4);
+    a.lse = (float*)w.take(N * c.n_q_heads * 4);
+    a.a = w.take(N * P.d * es); a.qkv = w.take(N * P.QKV * es); a.o = w.take(N * P.D * es);
+    a.h_mid = w.take(N * P.d * es); a.b = w.take(N * P.d * es);
+    a.gu = w.take(N * 2 * P.F * es); a.m = w.take(N * P.F * es);
+    a.u_qkv = w.take(N * P.n_qkv * rp * es); a.u_o = w.take(on(AS_T_O) ? N * rp * es : 0);
+    a.u_gu = w.take(N * P.n_gu * rp * es); a.u_d = w.take(on(AS_T_DOWN) ? N * rp * es : 0);
+  }
+  P.hf = w.take(N * P.d * es); P.dhf = w.take(N * P.d * es);
+  P.logits = (float*)w.take((size_t)P.Mc * P.V * 4);
+  P.P = w.take((size_t)P.Mc * P.V * es);
+  P.headT = w.take((size_t)P.V * P.d * es);
+  P.Pt = w.take(full ? (size_t)P.Mc * P.V * es : 0);
+  P.hfT = w.take(full ? (size_t)P.Mc * P.d * es : 0);
+  P.delta = (float*)w.take(N * c.n_q_heads * 4);
+  P.dh = w.take(N * P.d * es); P.dh2 = w.take(N * P.d * es);
+  P.dm = w.take(N * P.F * es); P.dgu = w.take(N * 2 * P.F * es); P.db = w.take(N * P.d * es);
+  P.d_o = w.take(N * P.D * es); P.dqkv = w.take(N * P.QKV * es); P.da = w.take(N * P.d * es);
+  P.du_qkv = w.take(N * P.n_qkv * rp * es); P.du_o = w.take(on(AS_T_O) ? N * rp * es : 0);
+  P.du_gu = w.take(N * P.n_gu * rp * es); P.du_d = w.take(on(AS_T_DOWN) ? N * rp * es : 0);
+  size_t wmax = std::max({(size_t)P.QKV * P.d, (size_t)P.d * P.D, (size_t)2 * P.F * P.d, (size_t)P.d * P.F});
+  P.wT = w.take(wmax * es);
+  const bool need_T = full || (c.lora_targets & 0x7f);
+  size_t xmax = std::max({(size_t)P.d, (size_t)P.D, (size_t)P.F});
+  size_t ymax = std::max({(size_t)P.QKV, (size_t)2 * P.F, (size_t)P.d});
+  P.xT = w.take(need_T ? xmax * N * es : 0);
+  P.dyT = w.take(need_T ? ymax * N * es : 0);
+  size_t umax = (size_t)std::max({P.n_qkv, P.n_gu, 1}) * rp;
+  P.uT = w.take(umax * N * es); P.duT = w.take(umax * N * es);
+  P.gpart = (float*)w.take(full ? (size_t)256 * P.d * 4 : 0);
+
+  // prepared adapter copies
+  P.lora.assign((size_t)P.L * 7, LoraSlot());
+  P.A_qkv.assign(P.L, nullptr); P.At_qkv.assign(P.L, nullptr); P.A_gu.assign(P.L, nullptr); P.At_gu.assign(P.L, nullptr);
+  size_t part = 0;
+  for (int l = 0; l < P.L && !full; l++) {
+    P.A_qkv[l] = w.take((size_t)P.n_qkv * rp * P.d * es); P.At_qkv[l] = w.take((size_t)P.d * P.n_qkv * rp * es);
+    P.A_gu[l] = w.take((size_t)P.n_gu * rp * P.d * es); P.At_gu[l] = w.take((size_t)P.d * P.n_gu * rp * es);
+    int sq = 0, sg = 0;
+    for (int t = 0; t < 7; t++) {
+      LoraSlot& s = P.lora[(size_t)l * 7 + t];
+      s.on = on(t);
+      if (!s.on) continue;
+      target_dims(c, t, &s.din, &s.dout);
+      if (t <= AS_T_V) { s.slot = sq++; s.A = P.A_qkv[l] ? (char*)P.A_qkv[l] + (size_t)s.slot * rp * P.d * es : nullptr;
+                         s.At = P.At_qkv[l] ? (char*)P.At_qkv[l] + (size_t)s.slot * rp * es : nullptr; }
+      else if (t == AS_T_GATE || t == AS_T_UP) { s.slot = sg++; s.A = P.A_gu[l] ? (char*)P.A_gu[l] + (size_t)s.slot * rp * P.d * es : nullptr;
+                         s.At = P.At_gu[l] ? (char*)P.At_gu[l] + (size_t)s.slot * rp * es : nullptr; }
+      else { s.slot = 0; s.A = w.take(rp * s.din * es); s.At = w.take((size_t)s.din * rp * es); }
+      s.Bs = w.take((size_t)s.dout * rp * es); s.Bst = w.take(rp * s.dout * es);
+      if (l == 0) {
+        int r = c.lora_rank;
+        part = std::max(part, (size_t)pick_splitk(c.mode, s.dout, r, P.N) * s.dout * r);
+        part = std::max(part, (size_t)pick_splitk(c.mode, r, s.din, P.N) * r * s.din);
+      }
+    }
+  }
+  P.partial_floats = part;
+  P.partial = (float*)w.take(part * 4);
+}
+
+extern "C" int as_workspace_bytes(const as_ctx* ctx, int64_t max_rows, int64_t row_len, size_t* bytes) {
+  if (!ctx || !bytes) return as_fail(nullptr, AS_ERR_NULL, "as_workspace_bytes: NULL argument");
+  if (max_rows < 1 || row_len < 1 || max_rows * row_len > (int64_t)1 << 30)
+    return as_fail(const_cast<as_ctx*>(ctx), AS_ERR_SHAPE, "as_workspace_bytes: rows*row_len must be in [1, 2^30]");
+  Bump w{nullptr, 0}; Plan P;
+  make_plan(ctx, max_rows, row_len, w, P);
+  *bytes = (w.off + 255) & ~(size_t)255;
+  return AS_OK;
+}
+
+// ----------------------------------------------------------- training step
+namespace {
+struct Step {
+  as_ctx* ctx; const as_model_config& c; Plan& P; hipStream_t st; int mode; int gv; int av;
+  const as_weights* W; const as_lora* lora; const as_grads* G; int max_seg;
+  size_t es() const { return (size_t)P.es; }
+  void* off(void* p, size_t elems) const { return (char*)p + elems * es(); }
+  const void* off(const void* p, size_t elems) const { return (const char*)p + elems * es(); }
+
+  // C = A1 B1^T (+ A2 B2^T) (+ R)
+  int gemm(int M, int N, const void* A1, int64_t lda1, const void* B1, int64_t ldb1, int K1,
+           const void* A2, int64_t lda2, const void* B2, int64_t ldb2, int K2,
+           const void* R, int64_t ldr, void* C, int64_t ldc, int c_f32 = 0, float alpha = 1.f,
+           int accumulate = 0, const int* m_dev = nullptr, int m_off = 0, bool allow_split = false) {
+    GemmParams g; memset(&g, 0, sizeof g);
+    g.seg[0] = {A1, B1, lda1, ldb1, K1}; g.nseg = 1;
+    if (A2 && K2 > 0) { g.seg[1] = {A2, B2, lda2, ldb2, K2}; g.nseg = 2; }
+    g.M = M; g.N = N; g.m_dev = m_dev; g.C = C; g.ldc = ldc; g.c_f32 = c_f32; g.alpha = alpha;
+    g.R = R; g.ldr = ldr; g.accumulate = accumulate; g.splitk = 1; g.partial = nullptr;
+    if (allow_split) {
+      int sk = pick_splitk(mode, M, N, K1);
+      if (sk > 1 && (size_t)sk * M * N <= P.partial_floats) { g.splitk = sk; g.partial = P.partial; }
+    }
+    return launch_gemm_off(ctx, mode, gv, g, m_off, st);
+  }
+
+  LoraSlot& slot(int l, int t) { return P.lora[(size_t)l * 7 + t]; }
+
+  int prep_lora(int l) {
+    const as_layer_lora& Lr = lora->layers[l];
+    const float s = c.lora_alpha / (float)c.lora_rank;
+    const int r = c.lora_rank, rp = P.rp;
+    for (int t = 0; t < 7; t++) {
+      LoraSlot& sl = slot(l, t);
+      if (!sl.on) continue;
+      int64_t ld_at = (t <= AS_T_V) ? (int64_t)P.n_qkv * rp : (t == AS_T_GATE || t == AS_T_UP) ? (int64_t)P.n_gu * rp : rp;
+      // A [r, din] -> A copy [rp, din] and its transpose block [din, rp] inside a [din, group] matrix
+      int rc = launch_lora_prep_ex(Lr.a[t], r, sl.din, rp, sl.din, 1.f, sl.A, sl.din, sl.At, ld_at);
+      if (rc) return rc;
+      // B [dout, r] -> s*B [dout, rp] and transpose [rp, dout]
+      rc = launch_lora_prep_ex(Lr.b[t], sl.dout, r, sl.dout, rp, s, sl.Bs, rp, sl.Bst, sl.dout);
+      if (rc) return rc;
+    }
+    return AS_OK;
+  }
+  int launch_lora_prep_ex(const float* in, int rows, int cols, int rows_pad, int cols_pad, float scale,
+                          void* out, int64_t ldo, void* out_t, int64_t ldo_t);
+
+  int forward_layer(int l, Acts& a) {
+    const as_layer_weights& w = W->layers[l];
+    const int N = P.N, d = P.d, D = P.D, Dkv = P.Dkv, QKV = P.QKV, F = P.F, rp = P.rp;
+    const void* h_in = P.h[l]; void* h_out = P.h[l + 1];
+    int rc;
+    if ((rc = launch_rmsnorm_fwd(ctx, mode, N, d, h_in, nullptr, nullptr, w.g1, c.rms_eps, a.a, a.rstd1, st))) return rc;
+    const int ldu = P.n_qkv * rp;
+    if (P.n_qkv && (rc = gemm(N, ldu, a.a, d, P.A_qkv[l], d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_qkv, ldu))) return rc;
+    const void* wq[3] = {w.wq, w.wk, w.wv}; const int nout[3] = {D, Dkv, Dkv}; const int coff[3] = {0, D, D + Dkv};
+    for (int i = 0; i < 3; i++) {
+      LoraSlot& s = slot(l, i);
+      rc = gemm(N, nout[i], a.a, d, wq[i], d, d, s.on ? off(a.u_qkv, (size_t)s.slot * rp) : nullptr, ldu, s.Bs, rp, s.on ? rp : 0,
+                nullptr, 0, off(a.qkv, coff[i]), QKV);
+      if (rc) return rc;
+    }
+    if ((rc = launch_rope(ctx, mode, N, c.n_q_heads + c.n_kv_heads, c.head_dim, a.qkv, QKV, P.seg_start, P.rope_cos, P.rope_sin, 0, st))) return rc;
+    AttnParams ap; memset(&ap, 0, sizeof ap);
+    ap.n = N; ap.Hq = c.n_q_heads; ap.Hkv = c.n_kv_heads; ap.dh = c.head_dim; ap.seg_start = P.seg_start; ap.seg_end = P.seg_end;
+    ap.q = a.qkv; ap.k = off(a.qkv, D); ap.v = off(a.qkv, D + Dkv); ap.ldq = QKV; ap.ldkv = QKV; ap.o = a.o; ap.lse = a.lse; ap.max_seg = max_seg;
+    if ((rc = launch_attention_fwd(ctx, mode, av, ap, st))) return rc;
+    { LoraSlot& s = slot(l, AS_T_O);
+      if (s.on && (rc = gemm(N, rp, a.o, D, s.A, D, D, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_o, rp))) return rc;
+      if ((rc = gemm(N, d, a.o, D, w.wo, D, D, s.on ? a.u_o : nullptr, rp, s.Bs, rp, s.on ? rp : 0, h_in, d, a.h_mid, d))) return rc; }
+    if ((rc = launch_rmsnorm_fwd(ctx, mode, N, d, a.h_mid, nullptr, nullptr, w.g2, c.rms_eps, a.b, a.rstd2, st))) return rc;
+    const int ldg = P.n_gu * rp;
+    if (P.n_gu && (rc = gemm(N, ldg, a.b, d, P.A_gu[l], d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_gu, ldg))) return rc;
+    const void* wg[2] = {w.wgate, w.wup};
+    for (int i = 0; i < 2; i++) {
+      LoraSlot& s = slot(l, AS_T_GATE + i);
+      rc = gemm(N, F, a.b, d, wg[i], d, d, s.on ? off(a.u_gu, (size_t)s.slot * rp) : nullptr, ldg, s.Bs, rp, s.on ? rp : 0,
+                nullptr, 0, off(a.gu, (size_t)i * F), 2 * F);
+      if (rc) return rc;
+    }
+    if ((rc = launch_swiglu_fwd(ctx, mode, N, F, a.gu, a.m, st))) return rc;
+    { LoraSlot& s = slot(l, AS_T_DOWN);
+      if (s.on && (rc = gemm(N, rp, a.m, F, s.A, F, F, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_d, rp))) return rc;
+      if ((rc = gemm(N, d, a.m, F, w.wdown, F, F, s.on ? a.u_d : nullptr, rp, s.Bs, rp, s.on ? rp : 0, a.h_mid, d, h_out, d))) return rc; }
+    return AS_OK;
+  }
+
+  int transpose(int rows, int cols, const void* in, int64_t ldi, void* out, int64_t ldo) {
+    return launch_transpose(ctx, mode, rows, cols, in, ldi, out, ldo, nullptr, 0, st);
+  }
+
+  // adapter gradients of one projection: dB = s dy^T u, dA = du^T x.
+  // dyT [dout, N] (rows roff..), uT/duT [.., N] rows at slot*rp, xT [din, N].
+  int lora_grads(int l, int t, const void* dyT_rows, const void* xT) {
+    LoraSlot& s = slot(l, t);
+    if (!s.on) return AS_OK;
+    const int N = P.N, r = c.lora_rank, rp = P.rp;
+    const float sc = c.lora_alpha / (float)c.lora_rank;
+    const as_layer_lora_grads& g = G->lora_layers[l];
+    int rc = gemm(s.dout, r, dyT_rows, N, off(P.uT, (size_t)s.slot * rp * N), N, N, nullptr, 0, nullptr, 0, 0, nullptr, 0,
+                  g.b[t], r, 1, sc, 0, nullptr, 0, true);
+    if (rc) return rc;
+    return gemm(r, s.din, off(P.duT, (size_t)s.slot * rp * N), N, xT, N, N, nullptr, 0, nullptr, 0, 0, nullptr, 0,
+                g.a[t], s.din, 1, 1.f, 0, nullptr, 0, true);
+  }
+  int weight_grad(float* dW, int dout, int din, const void* dyT_rows, const void* xT) {
+    const int N = P.N;
+    return gemm(dout, din, dyT_rows, N, xT, N, N, nullptr, 0, nullptr, 0, 0, nullptr, 0, dW, din, 1);
+  }
+
+  // dh_out in P.dh -> dh_in in P.dh (P.dh2 holds the mid-layer gradient)
+  int backward_layer(int l, Acts& a) {
+    const as_layer_weights& w = W->layers[l];
+    const bool full = c.train_mode == AS_FULL;
+    const int N = P.N, d = P.d, D = P.D, Dkv = P.Dkv, QKV = P.QKV, F = P.F, rp = P.rp;
+    int rc;
+    // ---- down projection
+    { LoraSlot& s = slot(l, AS_T_DOWN);
+      if ((rc = transpose(d, F, w.wdown, F, P.wT, d))) return rc;                       // [F, d]
+      if (s.on && (rc = gemm(N, rp, P.dh, d, s.Bst, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.du_d, rp))) return rc;
+      if ((rc = gemm(N, F, P.dh, d, P.wT, d, d, s.on ? P.du_d : nullptr, rp, s.At, rp, s.on ? rp : 0, nullptr, 0, P.dm, F))) return rc;
+      if (s.on || full) {
+        if ((rc = transpose(N, d, P.dh, d, P.dyT, N))) return rc;
+        if ((rc = transpose(N, F, a.m, F, P.xT, N))) return rc;
+      }
+      if (s.on) {
+        if ((rc = transpose(N, rp, a.u_d, rp, P.uT, N))) return rc;
+        if ((rc = transpose(N, rp, P.du_d, rp, P.duT, N))) return rc;
+        if ((rc = lora_grads(l, AS_T_DOWN, P.dyT, P.xT))) return rc;
+      }
+      if (full && (rc = weight_grad(G->w_layers[l].wdown, d, F, P.dyT, P.xT))) return rc; }
+    // ---- SwiGLU
+    if ((rc = launch_swiglu_bwd(ctx, mode, N, F, P.dm, a.gu, P.dgu, st))) return rc;
+    // ---- gate / up projections
+    { const int ldg = P.n_gu * rp;
+      const void* wg[2] = {w.wgate, w.wup};
+      for (int i = 0; i < 2; i++) {
+        LoraSlot& s = slot(l, AS_T_GATE + i);
+        if ((rc = transpose(F, d, wg[i], d, off(P.wT, (size_t)i * F), 2 * F))) return rc;        // [d, 2F]
+        if (s.on && (rc = gemm(N, rp, off(P.dgu, (size_t)i * F), 2 * F, s.Bst, F, F, nullptr, 0, nullptr, 0, 0, nullptr, 0,
+                               off(P.du_gu, (size_t)s.slot * rp), ldg))) return rc;
+      }
+      if ((rc = gemm(N, d, P.dgu, 2 * F, P.wT, 2 * F, 2 * F, P.n_gu ? P.du_gu : nullptr, ldg, P.At_gu[l], ldg, ldg,
+                     nullptr, 0, P.db, d))) return rc;
+      if (P.n_gu || full) {
+        if ((rc = transpose(N, 2 * F, P.dgu, 2 * F, P.dyT, N))) return rc;
+        if ((rc = transpose(N, d, a.b, d, P.xT, N))) return rc;
+      }
+      if (P.n_gu) {
+        if ((rc = transpose(N, ldg, a.u_gu, ldg, P.uT, N))) return rc;
+        if ((rc = transpose(N, ldg, P.du_gu, ldg, P.duT, N))) return rc;
+        for (int i = 0; i < 2; i++) if ((rc = lora_grads(l, AS_T_GATE + i, off(P.dyT, (size_t)i * F * N), P.xT))) return rc;
+      }
+      if (full) {
+        if ((rc = weight_grad(G->w_layers[l].wgate, F, d, P.dyT, P.xT))) return rc;
+        if ((rc = weight_grad(G->w_layers[l].wup, F, d, off(P.dyT, (size_t)F * N), P.xT))) return rc;
+      } }
+    // ---- second norm
+    if (full && (rc = launch_rmsnorm_dgain(ctx, mode, N, d, P.db, nullptr, a.h_mid, a.rstd2, P.gpart, 256, G->w_layers[l].g2, st))) return rc;
+    if ((rc = launch_rmsnorm_bwd(ctx, mode, N, d, P.db, nullptr, a.h_mid, w.g2, a.rstd2, P.dh, P.dh2, st))) return rc;
+    // ---- output projection
+    { LoraSlot& s = slot(l, AS_T_O);
+      if ((rc = transpose(d, D, w.wo, D, P.wT, d))) return rc;                          // [D, d]
+      if (s.on && (rc = gemm(N, rp, P.dh2, d, s.Bst, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.du_o, rp))) return rc;
+      if ((rc = gemm(N, D, P.dh2, d, P.wT, d, d, s.on ? P.du_o : nullptr, rp, s.At, rp, s.on ? rp : 0, nullptr, 0, P.d_o, D))) return rc;
+      if (s.on || full) {
+        if ((rc = transpose(N, d, P.dh2, d, P.dyT, N))) return rc;
+        if ((rc = transpose(N, D, a.o, D, P.xT, N))) return rc;
+      }
+      if (s.on) {
+        if ((rc = transpose(N, rp, a.u_o, rp, P.uT, N))) return rc;
+        if ((rc = transpose(N, rp, P.du_o, rp, P.duT, N))) return rc;
+        if ((rc = lora_grads(l, AS_T_O, P.dyT, P.xT))) return rc;
+      }
+      if (full && (rc = weight_grad(G->w_layers[l].wo, d, D, P.dyT, P.xT))) return rc; }
+    // ---- attention
+    { AttnParams ap; memset(&ap, 0, sizeof ap);
+      ap.n = N; ap.Hq = c.n_q_heads; ap.Hkv = c.n_kv_heads; ap.dh = c.head_dim; ap.seg_start = P.seg_start; ap.seg_end = P.seg_end;
+      ap.q = a.qkv; ap.k = off(a.qkv, D); ap.v = off(a.qkv, D + Dkv); ap.ldq = QKV; ap.ldkv = QKV; ap.o = a.o; ap.lse = a.lse;
+      ap.d_o = P.d_o; ap.dq = P.dqkv; ap.dk = off(P.dqkv, D); ap.dv = off(P.dqkv, D + Dkv); ap.delta = P.delta; ap.max_seg = max_seg;
+      if ((rc = launch_attention_bwd(ctx, mode, av, ap, st))) return rc; }
+    if ((rc = launch_rope(ctx, mode, N, c.n_q_heads + c.n_kv_heads, c.head_dim, P.dqkv, QKV, P.seg_start, P.rope_cos, P.rope_sin, 1, st))) return rc;
+    // ---- q / k / v projections
+    { const int ldu = P.n_qkv * rp;
+      const void* wq[3] = {w.wq, w.wk, w.wv}; const int nout[3] = {D, Dkv, Dkv}; const int coff[3] = {0, D, D + Dkv};
+      for (int i = 0; i < 3; i++) {
+        LoraSlot& s = slot(l, i);
+        if ((rc = transpose(nout[i], d, wq[i], d, off(P.wT, coff[i]), QKV))) return rc;          // [d, QKV]
+        if (s.on && (rc = gemm(N, rp, off(P.dqkv, coff[i]), QKV, s.Bst, nout[i], nout[i], nullptr, 0, nullptr, 0, 0, nullptr, 0,
+                               off(P.du_qkv, (size_t)s.slot * rp), ldu))) return rc;
+      }
+      if ((rc = gemm(N, d, P.dqkv, QKV, P.wT, QKV, QKV, P.n_qkv ? P.du_qkv : nullptr, ldu, P.At_qkv[l], ldu, ldu,
+                     nullptr, 0, P.da, d))) return rc;
+      if (P.n_qkv || full) {
+        if ((rc = transpose(N, QKV, P.dqkv, QKV, P.dyT, N))) return rc;
+        if ((rc = transpose(N, d, a.a, d, P.xT, N))) return rc;
+      }
+      if (P.n_qkv) {
+        if ((rc = transpose(N, ldu, a.u_qkv, ldu, P.uT, N))) return rc;
+        if ((rc = transpose(N, ldu, P.du_qkv, ldu, P.duT, N))) return rc;
+        for (int i = 0; i < 3; i++) if ((rc = lora_grads(l, i, off(P.dyT, (size_t)coff[i] * N), P.xT))) return rc;
+      }
+      if (full) {
+        float* gw[3] = {G->w_layers[l].wq, G->w_layers[l].wk, G->w_layers[l].wv};
+        for (int i = 0; i < 3; i++) if ((rc = weight_grad(gw[i], nout[i], d, off(P.dyT, (size_t)coff[i] * N), P.xT))) return rc;
+      } }
+    // ---- first norm
+    if (full && (rc = launch_rmsnorm_dgain(ctx, mode, N, d, P.da, nullptr, P.h[l], a.rstd1, P.gpart, 256, G->w_layers[l].g1, st))) return rc;
+    return launch_rmsnorm_bwd(ctx, mode, N, d, P.da, nullptr, P.h[l], w.g1, a.rstd1, P.dh2, P.dh, st);
+  }
+
+  int head_and_loss(float* d_loss, float* d_loss_sum) {
+    const bool full = c.train_mode == AS_FULL;
+    const int N = P.N, d = P.d, V = P.V, Mc = P.Mc;
+    int rc;
+    // hf = RMSNorm(h_L) on the target rows only
+    if ((rc = launch_rmsnorm_fwd(ctx, mode, N, d, P.h[P.L], P.tgt_idx, P.count, W->g_final, c.rms_eps, P.hf, P.rstd_f, st))) return rc;
+    if ((rc = transpose(V, d, W->head, d, P.headT, V))) return rc;                     // [d, V]
+    const int chunks = (int)cdiv(N, Mc);
+    for (int ch = 0; ch < chunks; ch++) {
+      const int r0 = ch * Mc, rows = std::min(Mc, N - r0);
+      const void* hf_c = off(P.hf, (size_t)r0 * d);
+      if ((rc = gemm(rows, V, hf_c, d, W->head, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.logits, V, 1, 1.f, 0, P.count, r0))) return rc;
+      if ((rc = launch_ce_rows(ctx, mode, P.logits, rows, V, r0, P.labels, P.count, P.loss_rows, P.P, st))) return rc;
+      if ((rc = gemm(rows, d, P.P, V, P.headT, V, V, nullptr, 0, nullptr, 0, 0, nullptr, 0, off(P.dhf, (size_t)r0 * d), d, 0, 1.f, 0, P.count, r0))) return rc;
+      if (full) {
+        // dW_head += P_c^T hf_c  (rows past the live count are read as zero)
+        if ((rc = launch_transpose(ctx, mode, rows, V, P.P, V, P.Pt, Mc, P.count, r0, st))) return rc;
+        if ((rc = launch_transpose(ctx, mode, rows, d, hf_c, d, P.hfT, Mc, P.count, r0, st))) return rc;
+        if ((rc = gemm(V, d, P.Pt, Mc, P.hfT, Mc, rows, nullptr, 0, nullptr, 0, 0, nullptr, 0, G->head, d, 1, 1.f, ch > 0))) return rc;
+      }
+    }
+    if ((rc = launch_loss_finalize(ctx, P.loss_rows, P.count, d_loss, d_loss_sum, st))) return rc;
+    // back through the final norm, scattered to all rows (zero where a row is no target)
+    if (full && (rc = launch_rmsnorm_dgain(ctx, mode, N, d, P.dhf, P.tgt_pos, P.h[P.L], P.rstd_f, P.gpart, 256, G->g_final, st))) return rc;
+    return launch_rmsnorm_bwd(ctx, mode, N, d, P.dhf, P.tgt_pos, P.h[P.L], W->g_final, P.rstd_f, nullptr, P.dh, st);
+  }
+};
+
+int Step::launch_lora_prep_ex(const float* in, int rows, int cols, int rows_pad, int cols_pad, float scale,
+                              void* out, int64_t ldo, void* out_t, int64_t ldo_t) {
+  return launch_lora_prep2(ctx, mode, in, rows, cols, rows_pad, cols_pad, scale, out, ldo, out_t, ldo_t, st);
+}
+}  // namespace
+
+static int check_cu(as_ctx* ctx, const int32_t* cu, int32_t S, int64_t N, int32_t T, int* max_seg) {
+  if (S < 1) return as_fail(ctx, AS_ERR_CU_SEQLENS, "cu_seqlens: at least one segment is needed");
+  if (cu[0] != 0) return as_fail(ctx, AS_ERR_CU_SEQLENS, "cu_seqlens[0] = %d, must be 0", cu[0]);
+  if (cu[S] != N) return as_fail(ctx, AS_ERR_CU_SEQLENS, "cu_seqlens[%d] = %d, must be n_rows*row_len = %lld", S, cu[S], (long long)N);
+  int mx = 0;
+  for (int s = 0; s < S; s++) {
+    if (cu[s + 1] <= cu[s]) return as_fail(ctx, AS_ERR_CU_SEQLENS, "cu_seqlens not strictly increasing at %d", s);
+    if (cu[s] / T != (cu[s + 1] - 1) / T) return as_fail(ctx, AS_ERR_CU_SEQLENS, "segment %d crosses a row end", s);
+    mx = std::max(mx, cu[s + 1] - cu[s]);
+  }
+  *max_seg = mx;
+  return AS_OK;
+}
+
+extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lora* lora,
+                             const int32_t* d_tokens, const int32_t* d_cu_seqlens,
+                             const int32_t* h_cu_seqlens, int32_t n_segments,
+                             const uint8_t* d_loss_mask, int32_t n_rows, int32_t row_len,
+                             float* d_loss, float* d_loss_sum, int32_t* d_count,
+                             const as_grads* grads, void* d_workspace, size_t workspace_bytes,
+                             void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_train_step: NULL context");
+  const as_model_config& c = ctx->cfg;
+  const bool full = c.train_mode == AS_FULL;
+  if (!weights || !weights->layers || !weights->embed || !weights->head || !weights->g_final)
+    return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL weights");
+  if (!d_tokens || !d_cu_seqlens || !h_cu_seqlens || !d_loss_mask || !d_loss || !d_loss_sum || !d_count || !grads)
+    return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL argument");
+  if (n_rows < 1 || row_len < 1 || (int64_t)n_rows * row_len > (int64_t)1 << 30)
+    return as_fail(ctx, AS_ERR_SHAPE, "as_train_step: n_rows*row_len must be in [1, 2^30]");
+  for (int l = 0; l < c.n_layers; l++) {
+    const as_layer_weights& w = weights->layers[l];
+    if (!w.g1 || !w.wq || !w.wk || !w.wv || !w.wo || !w.g2 || !w.wgate || !w.wup || !w.wdown)
+      return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL weight in layer %d", l);
+  }
+  if (!full) {
+    if (!lora || !lora->layers || !grads->lora_layers) return as_fail(ctx, AS_ERR_NULL, "as_train_step: LoRA mode needs adapters and their gradient buffers");
+    for (int l = 0; l < c.n_layers; l++)
+      for (int t = 0; t < 7; t++)
+        if ((c.lora_targets >> t) & 1u)
+          if (!lora->layers[l].a[t] || !lora->layers[l].b[t] || !grads->lora_layers[l].a[t] || !grads->lora_layers[l].b[t])
+            return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL adapter or gradient for target %s in layer %d", kTargetName[t], l);
+  } else {
+    if (!grads->w_layers || !grads->embed || !grads->head || !grads->g_final) return as_fail(ctx, AS_ERR_NULL, "as_train_step: full mode needs weight gradient buffers");
+    for (int l = 0; l < c.n_layers; l++) {
+      const as_layer_weight_grads& g = grads->w_layers[l];
+      if (!g.g1 || !g.wq || !g.wk || !g.wv || !g.wo || !g.g2 || !g.wgate || !g.wup || !g.wdown)
+        return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL weight gradient in layer %d", l);
+    }
+  }
+  const int64_t N = (int64_t)n_rows * row_len;
+  int max_seg = 0;
+  int rc = check_cu(ctx, h_cu_seqlens, n_segments, N, row_len, &max_seg);
+  if (rc) return rc;
+  if (!d_workspace || ((uintptr_t)d_workspace & 255)) return as_fail(ctx, AS_ERR_WORKSPACE, "as_train_step: workspace must be non-NULL and 256-byte aligned");
+  Bump wsp{(char*)d_workspace, 0}; Plan P;
+  make_plan(ctx, n_rows, row_len, wsp, P);
+  if (wsp.off > workspace_bytes) return as_fail(ctx, AS_ERR_WORKSPACE, "as_train_step: workspace has %zu bytes, %zu needed", workspace_bytes, wsp.off);
+
+  hipStream_t st = (hipStream_t)stream;
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  Step S{ctx, c, P, st, c.mode, 0, 0, weights, lora, grads, max_seg};
+  const int n = (int)N;
+  if ((rc = launch_segment_info(ctx, d_cu_seqlens, n_segments, n, P.seg_start, P.seg_end, st))) return rc;
+  if ((rc = launch_rope_table(ctx, max_seg, c.head_dim, c.rope_base, P.rope_cos, P.rope_sin, st))) return rc;
+  if ((rc = launch_select_targets(ctx, P.seg_start, d_loss_mask, d_tokens, n, P.tgt_idx, P.tgt_pos, P.labels, d_count, st))) return rc;
+  P.count = d_count;
+  if (!full) for (int l = 0; l < c.n_layers; l++) if ((rc = S.prep_lora(l))) return rc;
+  if ((rc = launch_embed(ctx, c.mode, d_tokens, n, c.d_model, weights->embed, P.h[0], st))) return rc;
+  for (int l = 0; l < c.n_layers; l++)
+    if ((rc = S.forward_layer(l, P.acts[c.recompute ? 0 : l]))) return rc;
+  if ((rc = S.head_and_loss(d_loss, d_loss_sum))) return rc;
+  for (int l = c.n_layers - 1; l >= 0; l--) {
+    Acts& a = P.acts[c.recompute ? 0 : l];
+    if (c.recompute && l != c.n_layers - 1 && (rc = S.forward_layer(l, a))) return rc;   // re-run the layer from its saved input
+    if ((rc = S.backward_layer(l, a))) return rc;
+  }
+  if (full && (rc = launch_embed_bwd(ctx, c.mode, d_tokens, n, c.d_model, c.vocab, P.dh, P.iscratch, grads->embed, st))) return rc;
+  return AS_OK;
+}
+
+// -------------------------------------------------------------------- AdamW
+extern "C" int as_adamw_update(as_ctx* ctx, float* const* d_master, void* const* d_params_lowp,
+                               const float* const* d_grads, float* const* d_m, float* const* d_v,
+                               const int64_t* numel, const uint8_t* apply_wd, int32_t n_tensors,
+                               int64_t step, float lr, float beta1, float beta2, float eps,
+                               float weight_decay, void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_adamw_update: NULL context");
+  if (n_tensors < 0) return as_fail(ctx, AS_ERR_SHAPE, "as_adamw_update: n_tensors < 0");
+  if (n_tensors && (!d_master || !d_grads || !d_m || !d_v || !numel || !apply_wd)) return as_fail(ctx, AS_ERR_NULL, "as_adamw_update: NULL table");
+  if (step < 1) return as_fail(ctx, AS_ERR_SHAPE, "as_adamw_update: step counts from 1");
+  if (!(beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f)) return as_fail(ctx, AS_ERR_SHAPE, "as_adamw_update: betas must be in [0,1), eps >= 0");
+  for (int i = 0; i < n_tensors; i++) {
+    if (numel[i] < 0) return as_fail(ctx, AS_ERR_SHAPE, "as_adamw_update: negative numel for tensor %d", i);
+    if (numel[i] && (!d_master[i] || !d_grads[i] || !d_m[i] || !d_v[i])) return as_fail(ctx, AS_ERR_NULL, "as_adamw_update: NULL buffer for tensor %d", i);
+  }
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  const float bc1 = (float)(1.0 - pow((double)beta1, (double)step)), bc2 = (float)(1.0 - pow((double)beta2, (double)step));
+  for (int i = 0; i < n_tensors; i++) {
+    int rc = launch_adamw(ctx, d_master[i], d_params_lowp ? d_params_lowp[i] : nullptr, d_grads[i], d_m[i], d_v[i], numel[i],
+                          lr, beta1, beta2, eps, apply_wd[i] ? weight_decay : 0.f, bc1, bc2, (hipStream_t)stream);
+    if (rc) return rc;
+  }
+  return AS_OK;
+}
+
+// ---------------------------------------------------------- building blocks
+static int check_mode(as_ctx* ctx, int mode) {
+  if (mode != AS_FP32 && mode != AS_BF16) return as_fail(ctx, AS_ERR_CONFIG, "mode must be AS_FP32 or AS_BF16");
+  return AS_OK;
+}
+
+extern "C" int as_op_gemm(as_ctx* ctx, int mode, int variant, int64_t M, int64_t N,
+                          const void* A1, int64_t lda1, const void* B1, int64_t ldb1, int64_t K1,
+                          const void* A2, int64_t lda2, const void* B2, int64_t ldb2, int64_t K2,
+                          float alpha, const void* R, int64_t ldr, void* C, int64_t ldc, int c_is_f32,
+                          void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_op_gemm: NULL context");
+  int rc = check_mode(ctx, mode); if (rc) return rc;
+  if (!A1 || !B1 || !C) return as_fail(ctx, AS_ERR_NULL, "as_op_gemm: NULL operand");
+  if (M < 0 || N < 0 || K1 < 0 || K2 < 0 || M > INT32_MAX || N > INT32_MAX || K1 > INT32_MAX || K2 > INT32_MAX)
+    return as_fail(ctx, AS_ERR_SHAPE, "as_op_gemm: sizes must be in [0, 2^31)");
+  if (lda1 < K1 || ldb1 < K1 || ldc < N || (R && ldr < N) || (A2 && (lda2 < K2 || ldb2 < K2 || !B2)))
+    return as_fail(ctx, AS_ERR_SHAPE, "as_op_gemm: leading dimension smaller than the row length");
+  GemmParams g; memset(&g, 0, sizeof g);
+  g.seg[0] = {A1, B1, lda1, ldb1, (int)K1}; g.nseg = 1;
+  if (A2 && K2 > 0) { g.seg[1] = {A2, B2, lda2, ldb2, (int)K2}; g.nseg = 2; }
+  g.M = (int)M; g.N = (int)N; g.C = C; g.ldc = ldc; g.c_f32 = c_is_f32; g.alpha = alpha; g.R = R; g.ldr = ldr; g.splitk = 1;
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  return launch_gemm(ctx, mode, variant, g, (hipStream_t)stream);
+}
+
+extern "C" int as_op_rmsnorm_fwd(as_ctx* ctx, int mode, int64_t n, int64_t d, const void* x, const void* g,
+                                 float eps, void* y, float* rstd, void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_op_rmsnorm_fwd: NULL context");
+  int rc = check_mode(ctx, mode); if (rc) return rc;
+  if (!x || !g || !y || !rstd) return as_fail(ctx, AS_ERR_NULL, "as_op_rmsnorm_fwd: NULL operand");
+  if (n < 0 || d < 1 || n > INT32_MAX || d > INT32_MAX) return as_fail(ctx, AS_ERR_SHAPE, "as_op_rmsnorm_fwd: bad sizes");
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  return launch_rmsnorm_fwd(ctx, mode, (int)n, (int)d, x, nullptr, nullptr, g, eps, y, rstd, (hipStream_t)stream);
+}
+
+extern "C" int as_op_rmsnorm_bwd(as_ctx* ctx, int mode, int64_t n, int64_t d, const void* dy, const void* x,
+                                 const void* g, const float* rstd, const void* add, void* dx, void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_op_rmsnorm_bwd: NULL context");
+  int rc = check_mode(ctx, mode); if (rc) return rc;
+  if (!dy || !x || !g || !rstd || !dx) return as_fail(ctx, AS_ERR_NULL, "as_op_rmsnorm_bwd: NULL operand");
+  if (n < 0 || d < 1 || n > INT32_MAX || d > INT32_MAX) return as_fail(ctx, AS_ERR_SHAPE, "as_op_rmsnorm_bwd: bad sizes");
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  return launch_rmsnorm_bwd(ctx, mode, (int)n, (int)d, dy, nullptr, x, g, rstd, add, dx, (hipStream_t)stream);
+}
+
+static int attn_common(as_ctx* ctx, int mode, int64_t n, int64_t ldq, int64_t ldkv, AttnParams* ap) {
+  int rc = check_mode(ctx, mode); if (rc) return rc;
+  const as_model_config& c = ctx->cfg;
+  if (n < 0 || n > INT32_MAX) return as_fail(ctx, AS_ERR_SHAPE, "attention: bad token count");
+  if (ldq < (int64_t)c.n_q_heads * c.head_dim || ldkv < (int64_t)c.n_kv_heads * c.head_dim)
+    return as_fail(ctx, AS_ERR_SHAPE, "attention: row stride smaller than heads*head_dim");
+  memset(ap, 0, sizeof *ap);
+  ap->n = (int)n; ap->Hq = c.n_q_heads; ap->Hkv = c.n_kv_heads; ap->dh = c.head_dim; ap->ldq = ldq; ap->ldkv = ldkv;
+  ap->max_seg = (int)std::min<int64_t>(n, 16384);
+  return AS_OK;
+}
+
+extern "C" int as_op_attention_fwd(as_ctx* ctx, int mode, int variant, int64_t n, const int32_t* seg_start,
+                                   const void* q, int64_t ldq, const void* k, const void* v, int64_t ldkv,
+                                   void* o, float* lse, void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_op_attention_fwd: NULL context");
+  if (!seg_start || !q || !k || !v || !o || !lse) return as_fail(ctx, AS_ERR_NULL, "as_op_attention_fwd: NULL operand");
+  AttnParams ap; int rc = attn_common(ctx, mode, n, ldq, ldkv, &ap); if (rc) return rc;
+  ap.seg_start = seg_start; ap.q = q; ap.k = k; ap.v = v; ap.o = o; ap.lse = lse;
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  return launch_attention_fwd(ctx, mode, variant, ap, (hipStream_t)stream);
+}
+
+extern "C" int as_op_attention_bwd(as_ctx* ctx, int mode, int variant, int64_t n, const int32_t* seg_start,
+                                   const int32_t* seg_end, const void* q, int64_t ldq, const void* k,
+                                   const void* v, int64_t ldkv, const void* o, const float* lse,
+                                   const void* d_o, void* dq, void* dk, void* dv, float* delta_scratch,
+                                   void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_op_attention_bwd: NULL context");
+  if (!seg_start || !seg_end || !q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !delta_scratch)
+    return as_fail(ctx, AS_ERR_NULL, "as_op_attention_bwd: NULL operand");
+  AttnParams ap; int rc = attn_common(ctx, mode, n, ldq, ldkv, &ap); if (rc) return rc;
+  ap.seg_start = seg_start; ap.seg_end = seg_end; ap.q = q; ap.k = k; ap.v = v; ap.o = const_cast<void*>(o); ap.lse = const_cast<float*>(lse);
+  ap.d_o = d_o; ap.dq = dq; ap.dk = dk; ap.dv = dv; ap.delta = delta_scratch;
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  return launch_attention_bwd(ctx, mode, variant, ap, (hipStream_t)stream);
+}

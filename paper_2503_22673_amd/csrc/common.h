@@ -1,0 +1,125 @@
+// Shared declarations of the gfx950 fine-tuning library: element types,
+// error plumbing, the context, and the launchers each .hip file exports to
+// the C interface in api.hip.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <string>
+#include "actionstudio.h"
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+#define AS_WAVE 64
+
+struct as_ctx {
+  as_model_config cfg;
+  int device;
+  std::string err;
+  // staging owned by the context (as_pack only)
+  void* d_stage = nullptr; size_t d_stage_bytes = 0;
+  void* h_stage = nullptr; size_t h_stage_bytes = 0;
+};
+
+int as_fail(as_ctx* ctx, int code, const char* fmt, ...);
+#define AS_HIP(ctx, call) do { hipError_t e_ = (call); if (e_ != hipSuccess) \
+  return as_fail((ctx), AS_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); } while (0)
+#define AS_LAUNCH_CHECK(ctx) AS_HIP(ctx, hipGetLastError())
+
+static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+template <typename T> __device__ __forceinline__ float to_f(T x);
+template <> __device__ __forceinline__ float to_f<float>(float x) { return x; }
+template <> __device__ __forceinline__ float to_f<bf16_t>(bf16_t x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_f(float x);
+template <> __device__ __forceinline__ float from_f<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float x) { return (bf16_t)x; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ---- GEMM (gemm.hip) ------------------------------------------------------
+// C[M,N] = alpha * sum_s A_s[M,K_s] B_s[N,K_s]^T (+ R), optional split over K.
+struct GemmSeg { const void* A; const void* B; int64_t lda, ldb; int K; };
+struct GemmParams {
+  GemmSeg seg[2]; int nseg;
+  int M, N;
+  const int* m_dev;        // if set, the row count is read from the device (<= M)
+  void* C; int64_t ldc; int c_f32;
+  float alpha;
+  const void* R; int64_t ldr;
+  int accumulate;          // C += result (float output only)
+  int splitk; float* partial;   // splitk > 1: partial [splitk, M, N] float, reduced afterwards
+};
+int launch_gemm(as_ctx* ctx, int mode, int variant, const GemmParams& p, hipStream_t st);
+// live rows = *p.m_dev - m_off, clamped to [0, p.M]
+int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p, int m_off, hipStream_t st);
+
+// ---- attention (attention.hip) -----------------------------------------------
+struct AttnParams {
+  int n, Hq, Hkv, dh;
+  const int32_t* seg_start; const int32_t* seg_end;
+  const void *q, *k, *v; int64_t ldq, ldkv;
+  void* o; float* lse;
+  const void* d_o; void *dq, *dk, *dv; float* delta;
+  int max_seg;             // longest segment (host knowledge, sizes LDS of the plain kernels)
+};
+int launch_attention_fwd(as_ctx* ctx, int mode, int variant, const AttnParams& p, hipStream_t st);
+int launch_attention_bwd(as_ctx* ctx, int mode, int variant, const AttnParams& p, hipStream_t st);
+
+// ---- element-wise and friends (elementwise.hip) ---------------------------------
+int launch_pack(as_ctx* ctx, const int32_t* d_src_tokens, const int32_t* d_piece_dst,
+                const int32_t* d_piece_src, const uint8_t* d_piece_mask, int n_pieces, int n_out,
+                int pad_id, int32_t* d_tokens, uint8_t* d_mask, hipStream_t st);
+int launch_segment_info(as_ctx* ctx, const int32_t* d_cu, int n_seg, int n, int32_t* seg_start,
+                        int32_t* seg_end, hipStream_t st);
+int launch_rope_table(as_ctx* ctx, int max_pos, int dh, float base, float* cosb, float* sinb, hipStream_t st);
+int launch_embed(as_ctx* ctx, int mode, const int32_t* tok, int n, int d, const void* E, void* h, hipStream_t st);
+int launch_rmsnorm_fwd(as_ctx* ctx, int mode, int n, int d, const void* x, const int32_t* row_idx,
+                       const int* n_dev, const void* g, float eps, void* y, float* rstd, hipStream_t st);
+// dx[t] = vjp(dy[row_of(t)]) + add[t]; src_pos (optional) maps t -> row of dy or -1 (then dx = add or 0)
+int launch_rmsnorm_bwd(as_ctx* ctx, int mode, int n, int d, const void* dy, const int32_t* src_pos,
+                       const void* x, const void* g, const float* rstd, const void* add, void* dx,
+                       hipStream_t st);
+int launch_rmsnorm_dgain(as_ctx* ctx, int mode, int n, int d, const void* dy, const int32_t* src_pos,
+                         const void* x, const float* rstd, float* partial, int n_part, float* dg,
+                         hipStream_t st);
+int launch_rope(as_ctx* ctx, int mode, int n, int n_heads, int dh, void* x, int64_t ldx,
+                const int32_t* seg_start, const float* cosb, const float* sinb, int inverse, hipStream_t st);
+int launch_swiglu_fwd(as_ctx* ctx, int mode, int64_t n, int F, const void* gu, void* m, hipStream_t st);
+int launch_swiglu_bwd(as_ctx* ctx, int mode, int64_t n, int F, const void* dm, const void* gu, void* dgu, hipStream_t st);
+// out[c, r] = in[r, c]; with rows_dev, rows at or past *rows_dev - row_off read as zero
+int launch_transpose(as_ctx* ctx, int mode, int rows, int cols, const void* in, int64_t ldi, void* out,
+                     int64_t ldo, const int* rows_dev, int row_off, hipStream_t st);
+// out[rows_pad, cols_pad] (type T, row stride ldo) = scale * in[rows, cols] (float), zero in the
+// padding; out_t (row stride ldo_t) receives the transpose.  Either output may be NULL.
+int launch_lora_prep2(as_ctx* ctx, int mode, const float* in, int rows, int cols, int rows_pad, int cols_pad,
+                      float scale, void* out, int64_t ldo, void* out_t, int64_t ldo_t, hipStream_t st);
+int launch_fill_zero(as_ctx* ctx, void* p, size_t bytes, hipStream_t st);
+int launch_select_targets(as_ctx* ctx, const int32_t* seg_start, const uint8_t* mask, const int32_t* tok,
+                          int n, int32_t* tgt_idx, int32_t* tgt_pos, int32_t* labels, int32_t* count,
+                          hipStream_t st);
+// one row of logits per target: loss_t, and P = (softmax - onehot) / count written as T
+int launch_ce_rows(as_ctx* ctx, int mode, const float* logits, int rows_cap, int V, int row0,
+                   const int32_t* labels, const int32_t* count, float* loss_rows, void* P, hipStream_t st);
+int launch_loss_finalize(as_ctx* ctx, const float* loss_rows, const int32_t* count, float* loss,
+                         float* loss_sum, hipStream_t st);
+int launch_splitk_reduce(as_ctx* ctx, const float* partial, int splitk, int64_t mn, int N, float alpha,
+                         float* C, int64_t ldc, hipStream_t st);
+int launch_adamw(as_ctx* ctx, float* w, void* w_lowp, const float* g, float* m, float* v, int64_t n,
+                 float lr, float b1, float b2, float eps, float wd, float bc1, float bc2, hipStream_t st);
+int launch_embed_bwd(as_ctx* ctx, int mode, const int32_t* tok, int n, int d, int V, const void* dh,
+                     int32_t* scratch, float* dE, hipStream_t st);

@@ -1,0 +1,255 @@
+// C[M,N] = alpha * sum_s A_s[M,K_s] * B_s[N,K_s]^T (+ R): the projection GEMMs
+// of the fine-tuning step.  The second K segment carries the low-rank LoRA
+// product (x A^T)(s B)^T, so the adapter costs one extra pass over r columns
+// inside the same accumulators instead of a second GEMM and an add.
+//
+// Two kernels:
+//  * gemm_fma_kernel   -- any type, any shape; 64x64 tile, fp32 FMAs.  The
+//    fp32 tier runs on it.
+//  * gemm_mfma_kernel  -- bf16 in, fp32 accumulate, v_mfma_f32_32x32x16_bf16.
+//    Tiles are staged global -> registers -> LDS (two LDS stages, one barrier
+//    per 64-wide K step), rows padded by 16 bytes so that the 16-byte fragment
+//    reads of 16 lanes hit 64 distinct banks.  Workgroup ids are first
+//    de-interleaved over the 8 XCDs (ids are dealt round-robin to XCDs, each
+//    with a private L2) and then walked in groups of 8 row-tiles so that the
+//    tiles resident on one XCD share A and B panels.
+#include "common.h"
+
+// ------------------------------------------------------------------ helpers
+struct KRange { int beg, end; };   // k-tile range of one segment for this split
+__device__ __forceinline__ KRange split_range(int K, int BK, int splitk, int z) {
+  int tiles = (K + BK - 1) / BK;
+  int per = (tiles + splitk - 1) / splitk;
+  KRange r; r.beg = min(tiles, z * per); r.end = min(tiles, r.beg + per);
+  return r;
+}
+
+template <typename T>
+__device__ __forceinline__ void store_out(const GemmParams& p, int z, int row, int col, float v) {
+  if (p.splitk > 1) { p.partial[((int64_t)z * p.M + row) * p.N + col] = v; return; }
+  v *= p.alpha;
+  if (p.R) v += to_f<T>(((const T*)p.R)[(int64_t)row * p.ldr + col]);
+  if (p.c_f32) {
+    float* c = (float*)p.C + (int64_t)row * p.ldc + col;
+    *c = p.accumulate ? *c + v : v;
+  } else {
+    ((T*)p.C)[(int64_t)row * p.ldc + col] = from_f<T>(v);
+  }
+}
+
+// ------------------------------------------------------------- plain kernel
+template <typename T>
+__global__ __launch_bounds__(256) void gemm_fma_kernel(GemmParams p, int m_off) {
+  constexpr int BM = 64, BN = 64, BK = 16;
+  __shared__ float As[BK][BM + 4];
+  __shared__ float Bs[BK][BN + 4];
+  int M = p.m_dev ? min(p.M, *p.m_dev - m_off) : p.M;
+  int row0 = blockIdx.y * BM, col0 = blockIdx.x * BN, z = blockIdx.z;
+  if (row0 >= M) return;
+  int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+  float acc[4][4] = {};
+  int lr = tid / 4, lk = (tid % 4) * 4;                 // loader: one row, 4 consecutive k
+  for (int s = 0; s < p.nseg; s++) {
+    const T* A = (const T*)p.seg[s].A; const T* B = (const T*)p.seg[s].B;
+    int64_t lda = p.seg[s].lda, ldb = p.seg[s].ldb; int K = p.seg[s].K;
+    KRange kr = split_range(K, BK, p.splitk, z);
+    for (int kt = kr.beg; kt < kr.end; kt++) {
+      int k0 = kt * BK;
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        int k = k0 + lk + q;
+        int ar = row0 + lr, br = col0 + lr;
+        As[lk + q][lr] = (ar < M && k < K) ? to_f<T>(A[(int64_t)ar * lda + k]) : 0.f;
+        Bs[lk + q][lr] = (br < p.N && k < K) ? to_f<T>(B[(int64_t)br * ldb + k]) : 0.f;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < BK; k++) {
+        float a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) { a[i] = As[k][ty * 4 + i]; b[i] = Bs[k][tx * 4 + i]; }
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+          for (int j = 0; j < 4; j++) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+      }
+      __syncthreads();
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      int r = row0 + ty * 4 + i, c = col0 + tx * 4 + j;
+      if (r < M && c < p.N) store_out<T>(p, z, r, c, acc[i][j]);
+    }
+}
+
+// -------------------------------------------------------------- MFMA kernel
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p, int m_off, int tiles_m, int tiles_n) {
+  constexpr int BK = 64, LS = BK + 8, NT = WM * WN * 64;
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int CA = BM * 8 / NT, CB = BN * 8 / NT;      // 16-byte chunks per thread and tile
+  static_assert(CA >= 1 && CB >= 1, "tile too small for the thread count");
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t* sA = (bf16_t*)smem;                            // [2][BM][LS]
+  bf16_t* sB = sA + 2 * BM * LS;                         // [2][BN][LS]
+
+  const int M = p.m_dev ? min(p.M, *p.m_dev - m_off) : p.M;
+  // XCD de-interleave, then grouped walk over the tile grid
+  int nblk = tiles_m * tiles_n, pid = blockIdx.x, z = blockIdx.y;
+  int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
+  int logical = xcd * q8 + min(xcd, rem) + loc;
+  constexpr int GROUP = 8;
+  int in_group = GROUP * tiles_n, grp = logical / in_group, first_m = grp * GROUP;
+  int gsize = min(tiles_m - first_m, GROUP);
+  int tile_m = first_m + (logical % in_group) % gsize, tile_n = (logical % in_group) / gsize;
+  const int row0 = tile_m * BM, col0 = tile_n * BN;
+  if (row0 >= M) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+
+  KRange kr0 = split_range(p.seg[0].K, BK, p.splitk, z);
+  KRange kr1 = {0, 0};
+  if (p.nseg > 1) kr1 = split_range(p.seg[1].K, BK, p.splitk, z);
+  const int nt0 = kr0.end - kr0.beg, nt = nt0 + (kr1.end - kr1.beg);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  uint4 ra[CA], rb[CB];
+  const int mclamp = p.M - 1, nclamp = p.N - 1;
+
+  auto fetch = [&](int it) {
+    const bool first = it < nt0;
+    const bf16_t* A = (const bf16_t*)(first ? p.seg[0].A : p.seg[1].A);
+    const bf16_t* B = (const bf16_t*)(first ? p.seg[0].B : p.seg[1].B);
+    const int64_t lda = first ? p.seg[0].lda : p.seg[1].lda, ldb = first ? p.seg[0].ldb : p.seg[1].ldb;
+    const int K = first ? p.seg[0].K : p.seg[1].K;
+    const int k0 = (first ? kr0.beg + it : kr1.beg + it - nt0) * BK;
+#pragma unroll
+    for (int i = 0; i < CA; i++) {
+      int c = tid + i * NT, r = c >> 3, k = k0 + (c & 7) * 8;
+      int gr = min(row0 + r, mclamp);
+      ra[i] = (k < K) ? *reinterpret_cast<const uint4*>(A + (int64_t)gr * lda + k) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < CB; i++) {
+      int c = tid + i * NT, r = c >> 3, k = k0 + (c & 7) * 8;
+      int gr = min(col0 + r, nclamp);
+      rb[i] = (k < K) ? *reinterpret_cast<const uint4*>(B + (int64_t)gr * ldb + k) : make_uint4(0, 0, 0, 0);
+    }
+  };
+  auto stash = [&](int buf) {
+    bf16_t* a = sA + buf * BM * LS; bf16_t* b = sB + buf * BN * LS;
+#pragma unroll
+    for (int i = 0; i < CA; i++) { int c = tid + i * NT; *reinterpret_cast<uint4*>(a + (c >> 3) * LS + (c & 7) * 8) = ra[i]; }
+#pragma unroll
+    for (int i = 0; i < CB; i++) { int c = tid + i * NT; *reinterpret_cast<uint4*>(b + (c >> 3) * LS + (c & 7) * 8) = rb[i]; }
+  };
+
+  if (nt > 0) { fetch(0); stash(0); }
+  __syncthreads();
+  for (int it = 0; it < nt; it++) {
+    const int buf = it & 1;
+    if (it + 1 < nt) fetch(it + 1);
+    const bf16_t* a = sA + buf * BM * LS + (wm * TM * 32 + (lane & 31)) * LS + (lane >> 5) * 8;
+    const bf16_t* b = sB + buf * BN * LS + (wn * TN * 32 + (lane & 31)) * LS + (lane >> 5) * 8;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ks++) {
+      bf16x8 af[TM], bfr[TN];
+#pragma unroll
+      for (int i = 0; i < TM; i++) af[i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * LS + ks * 16);
+#pragma unroll
+      for (int j = 0; j < TN; j++) bfr[j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * LS + ks * 16);
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (it + 1 < nt) stash(buf ^ 1);
+    __syncthreads();
+  }
+
+  // lane l holds column l%32 and rows 8*(e/4) + 4*(l/32) + e%4 of each 32x32 block
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      int c = col0 + wn * TN * 32 + j * 32 + (lane & 31);
+      if (c >= p.N) continue;
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        int r = row0 + wm * TM * 32 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        if (r < M) store_out<bf16_t>(p, z, r, c, acc[i][j][e]);
+      }
+    }
+}
+
+template <int BM, int BN, int WM, int WN>
+static int launch_mfma_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_t st) {
+  constexpr int LS = 72;
+  size_t smem = (size_t)2 * (BM + BN) * LS * sizeof(bf16_t);
+  auto kern = gemm_mfma_kernel<BM, BN, WM, WN>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    attr_set = true;
+  }
+  int tm = (int)cdiv(p.M, BM), tn = (int)cdiv(p.N, BN);
+  dim3 grid(tm * tn, p.splitk > 1 ? p.splitk : 1);
+  kern<<<grid, WM * WN * 64, smem, st>>>(p, m_off, tm, tn);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}
+
+static bool mfma_ok(const GemmParams& p) {
+  for (int s = 0; s < p.nseg; s++) {
+    const GemmSeg& g = p.seg[s];
+    if (g.K % 8 || g.lda % 8 || g.ldb % 8) return false;
+    if (((uintptr_t)g.A | (uintptr_t)g.B) % 16) return false;
+  }
+  return true;
+}
+
+// m_dev semantics: the live row count is *m_dev - m_off (clamped to [0, M]).
+int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, int m_off, hipStream_t st) {
+  GemmParams p = p_in;
+  if (p.M <= 0 || p.N <= 0) return AS_OK;
+  if (p.nseg < 1 || p.nseg > 2) return as_fail(ctx, AS_ERR_SHAPE, "gemm: 1 or 2 K segments");
+  if (p.splitk < 1) p.splitk = 1;
+  if (p.splitk > 1 && !p.partial) return as_fail(ctx, AS_ERR_WORKSPACE, "gemm: split-K needs a partial buffer");
+  if (p.accumulate && !p.c_f32) return as_fail(ctx, AS_ERR_SHAPE, "gemm: accumulate needs float output");
+  bool use_mfma = (mode == AS_BF16) && variant != 1 && mfma_ok(p);
+  if (variant == 2 && !use_mfma) return as_fail(ctx, AS_ERR_SHAPE, "gemm: MFMA kernel needs bf16 and 8-element alignment");
+  int rc = AS_OK;
+  if (use_mfma) {
+    if (p.N <= 128 && p.M > 128) rc = launch_mfma_cfg<256, 64, 4, 1>(ctx, p, m_off, st);
+    else if (p.M <= 128) rc = launch_mfma_cfg<64, 256, 1, 4>(ctx, p, m_off, st);
+    else if ((int64_t)cdiv(p.M, 256) * cdiv(p.N, 256) * p.splitk < 128) rc = launch_mfma_cfg<128, 128, 2, 2>(ctx, p, m_off, st);
+    else rc = launch_mfma_cfg<256, 256, 2, 4>(ctx, p, m_off, st);
+  } else {
+    dim3 grid((unsigned)cdiv(p.N, 64), (unsigned)cdiv(p.M, 64), (unsigned)p.splitk);
+    if (mode == AS_FP32) gemm_fma_kernel<float><<<grid, 256, 0, st>>>(p, m_off);
+    else gemm_fma_kernel<bf16_t><<<grid, 256, 0, st>>>(p, m_off);
+    AS_LAUNCH_CHECK(ctx);
+  }
+  if (rc) return rc;
+  if (p.splitk > 1) {
+    if (!p.c_f32) return as_fail(ctx, AS_ERR_SHAPE, "gemm: split-K writes float output");
+    rc = launch_splitk_reduce(ctx, p.partial, p.splitk, (int64_t)p.M * p.N, p.N, p.alpha, (float*)p.C, p.ldc, st);
+  }
+  return rc;
+}
+
+int launch_gemm(as_ctx* ctx, int mode, int variant, const GemmParams& p, hipStream_t st) {
+  return launch_gemm_off(ctx, mode, variant, p, 0, st);
+}

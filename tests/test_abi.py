@@ -1,0 +1,158 @@
+"""The C interface without a GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments on the host before any launch."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2503_22673_amd import binding
+    return binding
+
+
+def test_every_declared_symbol_is_exported(B):
+    header = open(os.path.join(ROOT, "include", "actionstudio.h")).read()
+    declared = set(re.findall(r"\b(as_[a-z0-9_]+)\s*\(", header))
+    declared -= {"as_status"}
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(B.lib, name), name
+
+
+def test_config_validation(B):
+    sh = synth.CONFIGS[1]
+    ok = B.make_config(sh)
+    ctx = B.Context(ok)
+    ctx.close()
+    bad = [dict(head_dim=48), dict(n_q_heads=3), dict(struct_size=4), dict(lora_rank=0), dict(lora_targets=0),
+           dict(mode=7), dict(n_experts=8, top_k=2), dict(recompute=5), dict(vocab=1), dict(lora_rank=1000)]
+    for kw in bad:
+        c = B.make_config(sh)
+        for k, v in kw.items():
+            setattr(c, k, v)
+        with pytest.raises(B.ASError) as e:
+            B.Context(c)
+        assert e.value.code == B.ERR["CONFIG"], kw
+    h = C.c_void_p()
+    assert B.lib.as_create(C.byref(h), None, 0) == B.ERR["NULL"]
+    assert b"NULL" in B.lib.as_last_error(None)
+
+
+def test_workspace_query(B):
+    ctx = B.Context(B.make_config(synth.CONFIGS[1]))
+    small = ctx.workspace_bytes(1, 512)
+    big = ctx.workspace_bytes(4, 512)
+    assert 0 < small < big and small % 256 == 0
+    with pytest.raises(B.ASError) as e:
+        ctx.workspace_bytes(0, 512)
+    assert e.value.code == B.ERR["SHAPE"]
+    # config 3 with recompute must fit one MI355X (288 GB) with room for weights
+    c3 = B.Context(B.make_config(synth.CONFIGS[3]))
+    gb = c3.workspace_bytes(4, 16384) / 2 ** 30
+    assert gb < 200, gb
+
+
+def _pack_args(trajs):
+    return synth.flatten_trajectories(trajs)
+
+
+def test_pack_rejects_bad_input_on_the_host(B):
+    """None of these reaches a HIP call, so they run without a GPU."""
+    ctx = B.Context(B.make_config(synth.CONFIGS[1]))
+    U, A = 1, 2
+    good = [[(U, np.array([1, 2, 3])), (A, np.array([4, 5]))]]
+    cases = [
+        ([[(7, np.array([1]))]], dict(), "ROLE"),
+        ([[(U, np.array([5000]))]], dict(), "TOKEN_RANGE"),
+        ([[(U, np.array([-1]))]], dict(), "TOKEN_RANGE"),
+        ([[(U, np.arange(20))]], dict(row_len=8, truncate=False), "TOO_LONG"),
+        (good, dict(row_len=0), "SHAPE"),
+        (good, dict(max_rows=-1), "SHAPE"),
+    ]
+    for trajs, kw, code in cases:
+        tt, to, tr, jo = _pack_args(trajs)
+        with pytest.raises(B.ASError) as e:
+            ctx.pack(tt, to, tr, jo, kw.get("row_len", 16), kw.get("max_rows", 2), truncate=kw.get("truncate", True),
+                     outputs=(None, None, None))
+        assert e.value.code in (B.ERR[code], B.ERR["NULL"]), (code, str(e.value))
+    # with dummy non-NULL outputs the specific code must come back
+    class Fake:
+        is_cuda = False
+        def data_ptr(self):
+            return 4096
+    for trajs, kw, code in cases:
+        tt, to, tr, jo = _pack_args(trajs)
+        with pytest.raises(B.ASError) as e:
+            ctx.pack(tt, to, tr, jo, kw.get("row_len", 16), kw.get("max_rows", 2), truncate=kw.get("truncate", True),
+                     outputs=(Fake(), Fake(), Fake()))
+        assert e.value.code == B.ERR[code], (code, str(e.value))
+    tt, to, tr, jo = _pack_args(good)
+    bad_off = to.copy(); bad_off[1] = 9; bad_off[2] = 3
+    with pytest.raises(B.ASError) as e:
+        ctx.pack(tt, bad_off, tr, jo, 16, 2, outputs=(Fake(), Fake(), Fake()))
+    assert e.value.code == B.ERR["SHAPE"]
+
+
+def test_train_step_rejects_bad_segment_tables_on_the_host(B):
+    sh = synth.CONFIGS[1]
+    ctx = B.Context(B.make_config(sh))
+    L = sh.n_layers
+    lw = (B.LayerWeights * L)()
+    for l in range(L):
+        for f, _ in B.LayerWeights._fields_:
+            setattr(lw[l], f, 4096)
+    W = B.Weights(4096, 4096, 4096, lw)
+    ll, lg = (B.LayerLora * L)(), (B.LayerLora * L)()
+    for l in range(L):
+        for i in range(4):
+            ll[l].a[i] = ll[l].b[i] = lg[l].a[i] = lg[l].b[i] = 4096
+    lora, grads = B.Lora(ll), B.Grads()
+    grads.lora_layers = lg
+    p = C.c_void_p(4096)
+
+    def call(cu, n_rows=1, row_len=512, ws=p, ws_bytes=1 << 40, lora_=lora):
+        cu = np.asarray(cu, dtype=np.int32)
+        return B.lib.as_train_step(ctx.handle, C.byref(W), C.byref(lora_) if lora_ is not None else None, p, p,
+                                   cu.ctypes.data_as(C.c_void_p), len(cu) - 1, p, n_rows, row_len, p, p, p,
+                                   C.byref(grads), ws, ws_bytes, None)
+
+    E = B.ERR
+    assert call([1, 512]) == E["CU_SEQLENS"]                       # does not start at 0
+    assert call([0, 100, 100, 512]) == E["CU_SEQLENS"]             # not strictly increasing
+    assert call([0, 100, 500]) == E["CU_SEQLENS"]                  # does not end at N
+    assert call([0, 300, 700, 1024], n_rows=2) == E["CU_SEQLENS"]  # crosses a row end
+    assert b"row end" in B.lib.as_last_error(ctx.handle)
+    assert call([0, 512], ws=None) == E["WORKSPACE"]
+    assert call([0, 512], ws=C.c_void_p(4097)) == E["WORKSPACE"]   # misaligned
+    assert call([0, 512], ws_bytes=1024) == E["WORKSPACE"]         # too small
+    assert call([0, 512], lora_=None) == E["NULL"]
+    assert call([0, 512], n_rows=0) == E["SHAPE"]
+    ll[1].b[2] = None
+    assert call([0, 512]) == E["NULL"]
+    assert b"target v in layer 1" in B.lib.as_last_error(ctx.handle)
+
+
+def test_adamw_and_op_argument_checks(B):
+    ctx = B.Context(B.make_config(synth.CONFIGS[1]))
+    one = (C.c_void_p * 1)(4096)
+    numel = (C.c_int64 * 1)(16)
+    wd = (C.c_uint8 * 1)(1)
+    f = B.lib.as_adamw_update
+    assert f(ctx.handle, one, None, one, one, one, numel, wd, 1, 0, 1e-3, 0.9, 0.95, 1e-8, 0.0, None) == B.ERR["SHAPE"]
+    assert f(ctx.handle, one, None, one, one, one, numel, wd, 1, 1, 1e-3, 1.0, 0.95, 1e-8, 0.0, None) == B.ERR["SHAPE"]
+    assert f(ctx.handle, None, None, one, one, one, numel, wd, 1, 1, 1e-3, 0.9, 0.95, 1e-8, 0.0, None) == B.ERR["NULL"]
+    nul = (C.c_void_p * 1)(None)
+    assert f(ctx.handle, one, None, nul, one, one, numel, wd, 1, 1, 1e-3, 0.9, 0.95, 1e-8, 0.0, None) == B.ERR["NULL"]
+    g = B.lib.as_op_gemm
+    p = C.c_void_p(4096)
+    assert g(ctx.handle, 0, 0, 4, 4, None, 4, p, 4, 4, None, 0, None, 0, 0, 1.0, None, 0, p, 4, 0, None) == B.ERR["NULL"]
+    assert g(ctx.handle, 0, 0, 4, 4, p, 2, p, 4, 4, None, 0, None, 0, 0, 1.0, None, 0, p, 4, 0, None) == B.ERR["SHAPE"]
+    assert g(ctx.handle, 9, 0, 4, 4, p, 4, p, 4, 4, None, 0, None, 0, 0, 1.0, None, 0, p, 4, 0, None) == B.ERR["CONFIG"]

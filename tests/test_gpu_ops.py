@@ -1,0 +1,136 @@
+"""Kernel-by-kernel parity through the C interface against the float64
+reference functions, in the fp32 tier (1e-4) and the bf16 tier."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import model as om
+import synth
+from helpers import grad_norm_err
+
+pytestmark = pytest.mark.gpu
+FP32_TOL, BF16_TOL = 1e-4, 3e-2
+
+
+def _env(**kw):
+    from paper_2503_22673_amd import binding as B
+    import gpu_util as G
+    sh = synth.CONFIGS[1].replace(**kw)
+    return B, G, B.Context(B.make_config(sh)), sh
+
+
+# (M, N, K1, K2): several tiles + ragged tails, and the shapes of the tiny config
+GEMM_SHAPES = [(512, 128, 128, 64), (512, 344, 128, 0), (512, 128, 344, 64), (300, 200, 72, 0), (1, 7, 8, 8),
+               (700, 1024, 256, 64), (64, 520, 1024, 0)]
+
+
+@pytest.mark.parametrize("shape", GEMM_SHAPES)
+@pytest.mark.parametrize("tier", ["fp32", "bf16_fma", "bf16_mfma"])
+def test_gemm_with_lora_segment_and_residual(shape, tier):
+    B, G, ctx, _ = _env()
+    M, N, K1, K2 = shape
+    bf16 = tier != "fp32"
+    dt = torch.bfloat16 if bf16 else torch.float32
+    g = synth.rng(1, 20)
+    A1, B1 = G.quantise(g.standard_normal((M, K1)), bf16), G.quantise(g.standard_normal((N, K1)), bf16)
+    R = G.quantise(g.standard_normal((M, N)), bf16)
+    ref = A1 @ B1.T
+    A2 = B2 = None
+    if K2:
+        A2, B2 = G.quantise(g.standard_normal((M, K2)), bf16), G.quantise(g.standard_normal((N, K2)), bf16)
+        ref = ref + A2 @ B2.T
+    ref = 0.5 * ref + R
+    variant = {"fp32": 1, "bf16_fma": 1, "bf16_mfma": 2}[tier]
+    out = ctx.op_gemm(G.to_dev(A1, dt), G.to_dev(B1, dt), G.to_dev(A2, dt) if K2 else None,
+                      G.to_dev(B2, dt) if K2 else None, alpha=0.5, R=G.to_dev(R, dt), out_f32=True, variant=variant,
+                      mode=B.AS_BF16 if bf16 else B.AS_FP32)
+    torch.cuda.synchronize()
+    # float accumulation of exact products: only summation rounding remains
+    assert grad_norm_err(G.to_np(out), ref) < 2e-6 * max(1, (K1 + K2)) ** 0.5 + 1e-6
+
+
+def test_gemm_mfma_typed_output_and_strides():
+    B, G, ctx, _ = _env()
+    g = synth.rng(2, 20)
+    M, N, K = 520, 300, 128
+    big = G.to_dev(G.quantise(g.standard_normal((M, 3 * K)), True), torch.bfloat16)
+    A = big[:, K:2 * K]                                   # row stride 3K
+    Bm = G.to_dev(G.quantise(g.standard_normal((N, K)), True), torch.bfloat16)
+    out = ctx.op_gemm(A, Bm, variant=2, mode=B.AS_BF16)
+    torch.cuda.synchronize()
+    ref = G.to_np(A) @ G.to_np(Bm).T
+    assert out.dtype == torch.bfloat16
+    assert grad_norm_err(G.to_np(out), ref) < 2 ** -8
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("n,d", [(512, 128), (37, 344), (5, 12), (130, 4096)])
+def test_rmsnorm_forward_and_backward(bf16, n, d):
+    B, G, ctx, _ = _env()
+    dt = torch.bfloat16 if bf16 else torch.float32
+    g = synth.rng(3, 21)
+    x, gain, dy = (G.quantise(g.standard_normal((n, d)), bf16), G.quantise(1 + 0.1 * g.standard_normal(d), bf16),
+                   G.quantise(g.standard_normal((n, d)), bf16))
+    add = G.quantise(g.standard_normal((n, d)), bf16)
+    y_ref, rho = om.rmsnorm(x, gain, 1e-5)
+    dx_ref, _ = om.rmsnorm_bwd(dy, x, gain, rho)
+    mode = B.AS_BF16 if bf16 else B.AS_FP32
+    y, rstd = ctx.op_rmsnorm_fwd(G.to_dev(x, dt), G.to_dev(gain, dt), 1e-5, mode=mode)
+    dx = ctx.op_rmsnorm_bwd(G.to_dev(dy, dt), G.to_dev(x, dt), G.to_dev(gain, dt), rstd, add=G.to_dev(add, dt), mode=mode)
+    torch.cuda.synchronize()
+    tol = 2 ** -8 if bf16 else 1e-6
+    assert grad_norm_err(G.to_np(rstd), rho) < 1e-6
+    assert grad_norm_err(G.to_np(y), y_ref) < tol
+    assert grad_norm_err(G.to_np(dx), dx_ref + add) < tol
+
+
+def _attn_case(seed, n_seg, Hq, Hkv, dh, lens):
+    g = synth.rng(seed, 22)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    n = int(cu[-1])
+    return g, cu, n
+
+
+@pytest.mark.parametrize("tier", ["fp32", "bf16_plain", "bf16_mfma"])
+@pytest.mark.parametrize("Hq,Hkv,dh,lens", [(4, 4, 32, [100, 1, 63, 200, 148]), (8, 2, 64, [130, 257, 64, 5]),
+                                            (4, 1, 128, [300, 70, 129])])
+def test_attention_forward_and_backward(tier, Hq, Hkv, dh, lens):
+    B, G, ctx, sh = _env(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=dh)
+    bf16 = tier != "fp32"
+    variant = {"fp32": 1, "bf16_plain": 1, "bf16_mfma": 2}[tier]
+    if tier == "bf16_mfma" and dh == 32:
+        pytest.skip("the MFMA attention kernels cover head_dim 64 and 128")
+    dt = torch.bfloat16 if bf16 else torch.float32
+    g, cu, n = _attn_case(4, len(lens), Hq, Hkv, dh, lens)
+    q = G.quantise(g.standard_normal((n, Hq, dh)), bf16)
+    k = G.quantise(g.standard_normal((n, Hkv, dh)), bf16)
+    v = G.quantise(g.standard_normal((n, Hkv, dh)), bf16)
+    do = G.quantise(g.standard_normal((n, Hq, dh)), bf16)
+    o_ref, probs = om.attention(q, k, v, cu, Hq // Hkv)
+    dq_ref, dk_ref, dv_ref = om.attention_bwd(do, q, k, v, o_ref, probs, cu, Hq // Hkv)
+    qkv = np.concatenate([q.reshape(n, -1), k.reshape(n, -1), v.reshape(n, -1)], axis=1)
+    seg = om.segment_ids(cu, n)
+    seg_start = torch.from_numpy(cu[seg].astype(np.int32)).cuda()
+    seg_end = torch.from_numpy(cu[seg + 1].astype(np.int32)).cuda()
+    mode = B.AS_BF16 if bf16 else B.AS_FP32
+    qkv_d = G.to_dev(qkv, dt)
+    o, lse = ctx.op_attention_fwd(qkv_d, seg_start, variant=variant, mode=mode)
+    # feed the backward the reference output rounded to the device type, so
+    # the two checks are independent
+    o_in = G.to_dev(o_ref.reshape(n, -1), dt)
+    dqkv = ctx.op_attention_bwd(qkv_d, seg_start, seg_end, o_in, lse, G.to_dev(do.reshape(n, -1), dt), variant=variant, mode=mode)
+    torch.cuda.synchronize()
+    tol = 2e-2 if bf16 else 1e-5
+    assert grad_norm_err(G.to_np(o), o_ref.reshape(n, -1)) < tol
+    D, Dkv = Hq * dh, Hkv * dh
+    got = G.to_np(dqkv)
+    assert grad_norm_err(got[:, :D], dq_ref.reshape(n, -1)) < tol
+    assert grad_norm_err(got[:, D:D + Dkv], dk_ref.reshape(n, -1)) < tol
+    assert grad_norm_err(got[:, D + Dkv:], dv_ref.reshape(n, -1)) < tol
+    # lse against the definition on a few rows
+    for t in (0, n // 2, n - 1):
+        s0 = cu[seg[t]]
+        sc = (k[s0:t + 1, 0] @ q[t, 0]) / np.sqrt(dh)
+        ref = sc.max() + np.log(np.exp(sc - sc.max()).sum())
+        assert abs(float(lse[t, 0]) - ref) < (2e-2 if bf16 else 1e-4)

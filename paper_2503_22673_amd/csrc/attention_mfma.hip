@@ -1,11 +1,441 @@
-// MFMA flash-style attention kernels (bf16).  Placeholder translation unit:
-// until the kernels are in, every shape is routed to the plain kernels.
+// Flash-style varlen causal attention on the matrix cores (bf16 in, fp32
+// accumulate), head_dim 64 or 128, grouped KV heads.
+//
+// Orientation.  Scores are produced transposed, S^T = K Q^T, so that in the
+// accumulator layout of v_mfma_f32_32x32x16_bf16 a lane owns ONE query (its
+// column) and 16 keys (its registers): the running max / sum of the online
+// softmax are per-lane scalars plus one exchange between the two lane halves,
+// and the probabilities, rounded to bf16, are already laid out as the B
+// operand of the next product O^T = V^T P^T (contraction over the keys a lane
+// holds).  The same holds in the backward kernels for dS.  The operand that is
+// contracted over its row index (V in forward; K, Q, dO in backward) is read
+// from its row-major LDS tile column-wise, eight 16-bit reads per fragment.
+//
+// Tiles are cut on the flat token stream (64 keys per step); a query t sees
+// key u iff seg_start[t] <= u <= t, equivalently u <= t < seg_end[u], so no
+// tile logic depends on where trajectories begin.
+//
+// Backward is split in two kernels so that every gradient has one owner and
+// is summed in a fixed order: dQ per query tile (loop over key tiles), dK/dV
+// per key tile (loop over the query heads of the group, then query tiles).
 #include "common.h"
 
-bool attention_mfma_ok(const AttnParams& p) { (void)p; return false; }
-int launch_attention_fwd_mfma(as_ctx* ctx, const AttnParams& p, hipStream_t st) {
-  (void)p; (void)st; return as_fail(ctx, AS_ERR_SHAPE, "attention: MFMA kernel not available");
+namespace {
+
+constexpr int BKEY = 64;      // keys (or queries) per staged tile
+
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int e = 0; e < 16; e++) z[e] = 0.f;
+  return z;
 }
+
+// rows (token indices row0 .. row0+63, clamped to n-1) x DH columns starting at `col`
+template <int DH>
+struct TileIO {
+  static constexpr int LS = DH + 8;            // LDS row stride in elements: 16 B pad keeps 16 lanes on 64 banks
+  static constexpr int CPR = DH / 8;           // 16-byte chunks per row
+  static constexpr int PER = BKEY * CPR / 256; // chunks per thread
+  uint4 r[PER];
+  __device__ __forceinline__ void fetch(const bf16_t* base, int64_t ld, int col, int row0, int n, int tid) {
+#pragma unroll
+    for (int i = 0; i < PER; i++) {
+      int c = tid + i * 256, row = c / CPR, cc = c % CPR;
+      int t = min(row0 + row, n - 1);
+      r[i] = *reinterpret_cast<const uint4*>(base + (int64_t)t * ld + col + cc * 8);
+    }
+  }
+  __device__ __forceinline__ void stash(bf16_t* s, int tid) const {
+#pragma unroll
+    for (int i = 0; i < PER; i++) {
+      int c = tid + i * 256, row = c / CPR, cc = c % CPR;
+      *reinterpret_cast<uint4*>(s + row * LS + cc * 8) = r[i];
+    }
+  }
+};
+
+// fragment with the contraction index along the LDS row (16-byte read)
+template <int LS>
+__device__ __forceinline__ bf16x8 frag_row(const bf16_t* s, int row, int k0) {
+  return *reinterpret_cast<const bf16x8*>(s + row * LS + k0);
+}
+// fragment with the contraction index down the LDS column: element j comes from
+// row rbase + 8*(j/4) + j%4 (the rows a lane half owns in the accumulator layout)
+template <int LS>
+__device__ __forceinline__ bf16x8 frag_col(const bf16_t* s, int rbase, int col) {
+  bf16x8 v;
+#pragma unroll
+  for (int j = 0; j < 8; j++) v[j] = s[(rbase + 8 * (j >> 2) + (j & 3)) * LS + col];
+  return v;
+}
+__device__ __forceinline__ bf16x8 pack8(const f32x16& a, int sl) {
+  bf16x8 v;
+#pragma unroll
+  for (int j = 0; j < 8; j++) v[j] = (bf16_t)a[8 * sl + j];
+  return v;
+}
+
+// ------------------------------------------------------------------ forward
+// Workgroup: 4 waves = HPW query heads of one KV group x (4/HPW) blocks of 64
+// queries; all waves share the staged K and V tiles.
+template <int DH, int HPW>
+__global__ __launch_bounds__(256) void attn_fwd_mfma(AttnParams p, float sl2) {
+  constexpr int LS = DH + 8, KS = DH / 16, CB = DH / 32, QT = 64 * (4 / HPW);
+  __shared__ __align__(16) bf16_t sK[BKEY * LS];
+  __shared__ __align__(16) bf16_t sV[BKEY * LS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, h = lane >> 5;
+  const int n = p.n, grp = p.Hq / p.Hkv;
+  const int j = blockIdx.y * HPW + (wave % HPW), g = j / grp;
+  const int t_wg = blockIdx.x * QT, t_base = t_wg + (wave / HPW) * 64;
+  const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* V = (const bf16_t*)p.v;
+
+  bf16x8 qf[2][KS];
+  int tq[2], ss[2];
+#pragma unroll
+  for (int qb = 0; qb < 2; qb++) {
+    tq[qb] = t_base + qb * 32 + l31;
+    int tc = min(tq[qb], n - 1);
+    ss[qb] = p.seg_start[tc];
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+      qf[qb][ks] = *reinterpret_cast<const bf16x8*>(Q + (int64_t)tc * p.ldq + j * DH + ks * 16 + h * 8);
+  }
+  f32x16 o[2][CB];
+  float m[2], l[2];
+#pragma unroll
+  for (int qb = 0; qb < 2; qb++) { m[qb] = -INFINITY; l[qb] = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++) o[qb][cb] = zero16(); }
+
+  const int kv_first = p.seg_start[min(t_wg, n - 1)] / BKEY;
+  const int kv_last = min(t_wg + QT - 1, n - 1) / BKEY;
+  TileIO<DH> ioK, ioV;
+  ioK.fetch(K, p.ldkv, g * DH, kv_first * BKEY, n, tid);
+  ioV.fetch(V, p.ldkv, g * DH, kv_first * BKEY, n, tid);
+  for (int kt = kv_first; kt <= kv_last; kt++) {
+    __syncthreads();                       // everyone is done with the previous tile
+    ioK.stash(sK, tid); ioV.stash(sV, tid);
+    __syncthreads();
+    if (kt < kv_last) { ioK.fetch(K, p.ldkv, g * DH, (kt + 1) * BKEY, n, tid); ioV.fetch(V, p.ldkv, g * DH, (kt + 1) * BKEY, n, tid); }
+    const int k0 = kt * BKEY;
+    if (k0 > t_base + 63 || t_base >= n) continue;          // tile lies after every query of this wave
+    f32x16 s[2][2];
+#pragma unroll
+    for (int qb = 0; qb < 2; qb++) { s[qb][0] = zero16(); s[qb][1] = zero16(); }
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++) {
+        bf16x8 a = frag_row<LS>(sK, kb * 32 + l31, ks * 16 + h * 8);
+#pragma unroll
+        for (int qb = 0; qb < 2; qb++) s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s[qb][kb], 0, 0, 0);
+      }
+    bf16x8 pb[2][4];
+#pragma unroll
+    for (int qb = 0; qb < 2; qb++) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          int key = k0 + kb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+          float v = (key >= ss[qb] && key <= tq[qb]) ? s[qb][kb][e] * sl2 : -INFINITY;
+          s[qb][kb][e] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      float m_new = fmaxf(m[qb], mx);
+      float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      float alpha = exp2f(m[qb] - m_use);
+      m[qb] = m_new;
+      float rs = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) { float pv = exp2f(s[qb][kb][e] - m_use); s[qb][kb][e] = pv; rs += pv; }
+      rs += __shfl_xor(rs, 32, 64);
+      l[qb] = l[qb] * alpha + rs;
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) o[qb][cb][e] *= alpha;
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++) { pb[qb][kb * 2] = pack8(s[qb][kb], 0); pb[qb][kb * 2 + 1] = pack8(s[qb][kb], 1); }
+    }
+#pragma unroll
+    for (int x = 0; x < 4; x++) {                            // x = kb*2 + sl: 16 keys each
+      const int rbase = (x >> 1) * 32 + (x & 1) * 16 + 4 * h;
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++) {
+        bf16x8 a = frag_col<LS>(sV, rbase, cb * 32 + l31);
+#pragma unroll
+        for (int qb = 0; qb < 2; qb++) o[qb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb][x], o[qb][cb], 0, 0, 0);
+      }
+    }
+  }
+  bf16_t* O = (bf16_t*)p.o;
+#pragma unroll
+  for (int qb = 0; qb < 2; qb++) {
+    if (tq[qb] >= n) continue;
+    float inv = 1.f / l[qb];
+    bf16_t* orow = O + ((int64_t)tq[qb] * p.Hq + j) * DH;
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+      for (int b4 = 0; b4 < 4; b4++) {
+        bf16x4 w;
+#pragma unroll
+        for (int i = 0; i < 4; i++) w[i] = (bf16_t)(o[qb][cb][b4 * 4 + i] * inv);
+        *reinterpret_cast<bf16x4*>(orow + cb * 32 + 8 * b4 + 4 * h) = w;
+      }
+    if (h == 0) p.lse[(int64_t)tq[qb] * p.Hq + j] = (m[qb] + log2f(l[qb])) * 0.6931471805599453f;
+  }
+}
+
+// ---------------------------------------------------------- backward: delta
+__global__ void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o, int64_t rows, int dh,
+                                  float* __restrict__ delta) {
+  int64_t r = (int64_t)blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
+  int lane = threadIdx.x & 63;
+  if (r >= rows) return;
+  float acc = 0.f;
+  for (int c = lane; c < dh; c += 64) acc += (float)o[r * dh + c] * (float)d_o[r * dh + c];
+  acc = wave_sum(acc);
+  if (lane == 0) delta[r] = acc;
+}
+
+// ------------------------------------------------------------- backward: dQ
+// Wave = 32 queries of one head; workgroup = HPW heads x (4/HPW) query blocks.
+template <int DH, int HPW>
+__global__ __launch_bounds__(256) void attn_bwd_dq_mfma(AttnParams p, float scale, float sl2) {
+  constexpr int LS = DH + 8, KS = DH / 16, CB = DH / 32, QT = 32 * (4 / HPW);
+  __shared__ __align__(16) bf16_t sK[BKEY * LS];
+  __shared__ __align__(16) bf16_t sV[BKEY * LS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, h = lane >> 5;
+  const int n = p.n, grp = p.Hq / p.Hkv;
+  const int j = blockIdx.y * HPW + (wave % HPW), g = j / grp;
+  const int t_wg = blockIdx.x * QT, t_base = t_wg + (wave / HPW) * 32;
+  const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* V = (const bf16_t*)p.v;
+  const bf16_t* dO = (const bf16_t*)p.d_o;
+  const int tq = t_base + l31, tc = min(tq, n - 1), ss = p.seg_start[tc];
+  bf16x8 qf[KS], dof[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) {
+    qf[ks] = *reinterpret_cast<const bf16x8*>(Q + (int64_t)tc * p.ldq + j * DH + ks * 16 + h * 8);
+    dof[ks] = *reinterpret_cast<const bf16x8*>(dO + ((int64_t)tc * p.Hq + j) * DH + ks * 16 + h * 8);
+  }
+  const float lse2 = p.lse[(int64_t)tc * p.Hq + j] * 1.4426950408889634f;
+  const float dl = p.delta[(int64_t)tc * p.Hq + j];
+  f32x16 dq[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; cb++) dq[cb] = zero16();
+
+  const int kv_first = p.seg_start[min(t_wg, n - 1)] / BKEY;
+  const int kv_last = min(t_wg + QT - 1, n - 1) / BKEY;
+  TileIO<DH> ioK, ioV;
+  ioK.fetch(K, p.ldkv, g * DH, kv_first * BKEY, n, tid);
+  ioV.fetch(V, p.ldkv, g * DH, kv_first * BKEY, n, tid);
+  for (int kt = kv_first; kt <= kv_last; kt++) {
+    __syncthreads();
+    ioK.stash(sK, tid); ioV.stash(sV, tid);
+    __syncthreads();
+    if (kt < kv_last) { ioK.fetch(K, p.ldkv, g * DH, (kt + 1) * BKEY, n, tid); ioV.fetch(V, p.ldkv, g * DH, (kt + 1) * BKEY, n, tid); }
+    const int k0 = kt * BKEY;
+    if (k0 > t_base + 31 || t_base >= n) continue;
+    f32x16 s[2], dp[2];
+    s[0] = zero16(); s[1] = zero16(); dp[0] = zero16(); dp[1] = zero16();
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++) {
+        bf16x8 a = frag_row<LS>(sK, kb * 32 + l31, ks * 16 + h * 8);
+        bf16x8 b = frag_row<LS>(sV, kb * 32 + l31, ks * 16 + h * 8);
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
+        dp[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, dof[ks], dp[kb], 0, 0, 0);
+      }
+    bf16x8 dsb[4];
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) {
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        int key = k0 + kb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+        float pr = (key >= ss && key <= tq) ? exp2f(s[kb][e] * sl2 - lse2) : 0.f;
+        s[kb][e] = pr * (dp[kb][e] - dl);
+      }
+      dsb[kb * 2] = pack8(s[kb], 0); dsb[kb * 2 + 1] = pack8(s[kb], 1);
+    }
+#pragma unroll
+    for (int x = 0; x < 4; x++) {
+      const int rbase = (x >> 1) * 32 + (x & 1) * 16 + 4 * h;
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++) {
+        bf16x8 a = frag_col<LS>(sK, rbase, cb * 32 + l31);
+        dq[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsb[x], dq[cb], 0, 0, 0);
+      }
+    }
+  }
+  if (tq < n) {
+    bf16_t* row = (bf16_t*)p.dq + (int64_t)tq * p.ldq + j * DH;
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+      for (int b4 = 0; b4 < 4; b4++) {
+        bf16x4 w;
+#pragma unroll
+        for (int i = 0; i < 4; i++) w[i] = (bf16_t)(dq[cb][b4 * 4 + i] * scale);
+        *reinterpret_cast<bf16x4*>(row + cb * 32 + 8 * b4 + 4 * h) = w;
+      }
+  }
+}
+
+// ---------------------------------------------------------- backward: dK, dV
+// Workgroup = 128 keys of one KV head, wave = 32 of them (a lane owns one key);
+// loops over the query heads of the group and over 64-query tiles.
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(AttnParams p, float scale, float sl2) {
+  constexpr int LS = DH + 8, KS = DH / 16, CB = DH / 32;
+  __shared__ __align__(16) bf16_t sQ[BKEY * LS];
+  __shared__ __align__(16) bf16_t sdO[BKEY * LS];
+  __shared__ float sLse[BKEY], sDel[BKEY];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, h = lane >> 5;
+  const int n = p.n, grp = p.Hq / p.Hkv, g = blockIdx.y;
+  const int u_wg = blockIdx.x * 128, u_base = u_wg + wave * 32;
+  const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* V = (const bf16_t*)p.v;
+  const bf16_t* dO = (const bf16_t*)p.d_o;
+  const int u = u_base + l31, uc = min(u, n - 1);
+  const int uend = (u < n) ? p.seg_end[uc] : 0;                 // queries u <= t < uend see this key
+  bf16x8 kf[KS], vf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) {
+    kf[ks] = *reinterpret_cast<const bf16x8*>(K + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
+    vf[ks] = *reinterpret_cast<const bf16x8*>(V + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
+  }
+  f32x16 dk[CB], dv[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; cb++) { dk[cb] = zero16(); dv[cb] = zero16(); }
+  // query tiles that can see any key of this workgroup
+  const int q_first = u_wg / BKEY;
+  const int q_last = (p.seg_end[min(u_wg + 127, n - 1)] - 1) / BKEY;
+  // this wave's keys are visible from queries in [u_base, w_end)
+  const int w_end = (u_base < n) ? p.seg_end[min(u_base + 31, n - 1)] : 0;
+  const int ntile = q_last - q_first + 1, total = ntile * grp;
+  TileIO<DH> ioQ, ioD;
+  float r_lse = 0.f, r_del = 0.f;
+  auto fetch = [&](int it) {
+    const int jj = g * grp + it / ntile, t0 = (q_first + it % ntile) * BKEY;
+    ioQ.fetch(Q, p.ldq, jj * DH, t0, n, tid);
+    ioD.fetch(dO, (int64_t)p.Hq * DH, jj * DH, t0, n, tid);
+    if (tid < BKEY) { int t = min(t0 + tid, n - 1); r_lse = p.lse[(int64_t)t * p.Hq + jj] * 1.4426950408889634f; r_del = p.delta[(int64_t)t * p.Hq + jj]; }
+  };
+  if (total > 0) fetch(0);
+  for (int it = 0; it < total; it++) {
+    __syncthreads();
+    ioQ.stash(sQ, tid); ioD.stash(sdO, tid);
+    if (tid < BKEY) { sLse[tid] = r_lse; sDel[tid] = r_del; }
+    __syncthreads();
+    if (it + 1 < total) fetch(it + 1);
+    const int t0 = (q_first + it % ntile) * BKEY;
+    if (t0 + 63 < u_base || t0 >= w_end) continue;             // no query of the tile sees a key of this wave
+    f32x16 s[2], dp[2];
+    s[0] = zero16(); s[1] = zero16(); dp[0] = zero16(); dp[1] = zero16();
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+      for (int qb = 0; qb < 2; qb++) {
+        bf16x8 a = frag_row<LS>(sQ, qb * 32 + l31, ks * 16 + h * 8);
+        bf16x8 b = frag_row<LS>(sdO, qb * 32 + l31, ks * 16 + h * 8);
+        s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[ks], s[qb], 0, 0, 0);
+        dp[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, vf[ks], dp[qb], 0, 0, 0);
+      }
+    bf16x8 pbv[4], dsb[4];
+#pragma unroll
+    for (int qb = 0; qb < 2; qb++) {
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        int qi = qb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+        int t = t0 + qi;
+        float pr = (t >= u && t < uend) ? exp2f(s[qb][e] * sl2 - sLse[qi]) : 0.f;
+        s[qb][e] = pr;
+        dp[qb][e] = pr * (dp[qb][e] - sDel[qi]);
+      }
+      pbv[qb * 2] = pack8(s[qb], 0); pbv[qb * 2 + 1] = pack8(s[qb], 1);
+      dsb[qb * 2] = pack8(dp[qb], 0); dsb[qb * 2 + 1] = pack8(dp[qb], 1);
+    }
+#pragma unroll
+    for (int x = 0; x < 4; x++) {
+      const int rbase = (x >> 1) * 32 + (x & 1) * 16 + 4 * h;
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++) {
+        bf16x8 a = frag_col<LS>(sdO, rbase, cb * 32 + l31);
+        bf16x8 b = frag_col<LS>(sQ, rbase, cb * 32 + l31);
+        dv[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pbv[x], dv[cb], 0, 0, 0);
+        dk[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, dsb[x], dk[cb], 0, 0, 0);
+      }
+    }
+  }
+  if (u < n) {
+    bf16_t* krow = (bf16_t*)p.dk + (int64_t)u * p.ldkv + g * DH;
+    bf16_t* vrow = (bf16_t*)p.dv + (int64_t)u * p.ldkv + g * DH;
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+      for (int b4 = 0; b4 < 4; b4++) {
+        bf16x4 wk, wv;
+#pragma unroll
+        for (int i = 0; i < 4; i++) { wk[i] = (bf16_t)(dk[cb][b4 * 4 + i] * scale); wv[i] = (bf16_t)dv[cb][b4 * 4 + i]; }
+        *reinterpret_cast<bf16x4*>(krow + cb * 32 + 8 * b4 + 4 * h) = wk;
+        *reinterpret_cast<bf16x4*>(vrow + cb * 32 + 8 * b4 + 4 * h) = wv;
+      }
+  }
+}
+
+int heads_per_wg(const AttnParams& p) {
+  int grp = p.Hq / p.Hkv;
+  return grp % 4 == 0 ? 4 : (grp % 2 == 0 ? 2 : 1);
+}
+
+template <int DH>
+int fwd_dh(as_ctx* ctx, const AttnParams& p, hipStream_t st) {
+  const float sl2 = 1.4426950408889634f / sqrtf((float)DH);
+  const int hpw = heads_per_wg(p);
+  if (hpw == 4) attn_fwd_mfma<DH, 4><<<dim3((unsigned)cdiv(p.n, 64), p.Hq / 4), 256, 0, st>>>(p, sl2);
+  else if (hpw == 2) attn_fwd_mfma<DH, 2><<<dim3((unsigned)cdiv(p.n, 128), p.Hq / 2), 256, 0, st>>>(p, sl2);
+  else attn_fwd_mfma<DH, 1><<<dim3((unsigned)cdiv(p.n, 256), p.Hq), 256, 0, st>>>(p, sl2);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}
+
+template <int DH>
+int bwd_dh(as_ctx* ctx, const AttnParams& p, hipStream_t st) {
+  const float scale = 1.f / sqrtf((float)DH), sl2 = 1.4426950408889634f * scale;
+  const int64_t rows = (int64_t)p.n * p.Hq;
+  attn_delta_kernel<<<(unsigned)cdiv(rows, 4), 256, 0, st>>>((const bf16_t*)p.o, (const bf16_t*)p.d_o, rows, DH, p.delta);
+  AS_LAUNCH_CHECK(ctx);
+  const int hpw = heads_per_wg(p);
+  if (hpw == 4) attn_bwd_dq_mfma<DH, 4><<<dim3((unsigned)cdiv(p.n, 32), p.Hq / 4), 256, 0, st>>>(p, scale, sl2);
+  else if (hpw == 2) attn_bwd_dq_mfma<DH, 2><<<dim3((unsigned)cdiv(p.n, 64), p.Hq / 2), 256, 0, st>>>(p, scale, sl2);
+  else attn_bwd_dq_mfma<DH, 1><<<dim3((unsigned)cdiv(p.n, 128), p.Hq), 256, 0, st>>>(p, scale, sl2);
+  AS_LAUNCH_CHECK(ctx);
+  attn_bwd_dkv_mfma<DH><<<dim3((unsigned)cdiv(p.n, 128), p.Hkv), 256, 0, st>>>(p, scale, sl2);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}
+
+}  // namespace
+
+bool attention_mfma_ok(const AttnParams& p) {
+  if (p.dh != 64 && p.dh != 128) return false;
+  if (p.ldq % 8 || p.ldkv % 8) return false;
+  uintptr_t a = (uintptr_t)p.q | (uintptr_t)p.k | (uintptr_t)p.v | (uintptr_t)p.o | (uintptr_t)p.d_o |
+                (uintptr_t)p.dq | (uintptr_t)p.dk | (uintptr_t)p.dv;
+  return a % 16 == 0;
+}
+
+int launch_attention_fwd_mfma(as_ctx* ctx, const AttnParams& p, hipStream_t st) {
+  return p.dh == 128 ? fwd_dh<128>(ctx, p, st) : fwd_dh<64>(ctx, p, st);
+}
+
 int launch_attention_bwd_mfma(as_ctx* ctx, const AttnParams& p, hipStream_t st) {
-  (void)p; (void)st; return as_fail(ctx, AS_ERR_SHAPE, "attention: MFMA kernel not available");
+  return p.dh == 128 ? bwd_dh<128>(ctx, p, st) : bwd_dh<64>(ctx, p, st);
 }

@@ -94,7 +94,8 @@ def _attn_case(seed, n_seg, Hq, Hkv, dh, lens):
 
 @pytest.mark.parametrize("tier", ["fp32", "bf16_plain", "bf16_mfma"])
 @pytest.mark.parametrize("Hq,Hkv,dh,lens", [(4, 4, 32, [100, 1, 63, 200, 148]), (8, 2, 64, [130, 257, 64, 5]),
-                                            (4, 1, 128, [300, 70, 129])])
+                                            (4, 1, 128, [300, 70, 129]), (2, 2, 64, [200, 90]),
+                                            (4, 2, 128, [65, 190])])
 def test_attention_forward_and_backward(tier, Hq, Hkv, dh, lens):
     B, G, ctx, sh = _env(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=dh)
     bf16 = tier != "fp32"

@@ -74,8 +74,12 @@ typedef struct {
   uint32_t lora_targets;           /* bit i set: target i carries an adapter     */
   int32_t mode;                    /* AS_FP32 | AS_BF16                          */
   int32_t train_mode;              /* AS_LORA | AS_FULL                          */
-  int32_t recompute;               /* 1: keep only layer inputs, re-run a layer's
-                                      forward before its backward                */
+  int32_t recompute;               /* activation recompute: 0 keep everything;
+                                      1 keep only layer inputs and re-run a layer's
+                                      forward before its backward; 2 keep GEMM and
+                                      attention outputs, rebuild only the norm
+                                      outputs and the SwiGLU product (fits 8B
+                                      shapes at 4 x 16k tokens in 288 GB)        */
 } as_model_config;
 
 /* Frozen (LoRA) or trainable (full) weights of one layer.  [device], type T.
@@ -134,6 +138,23 @@ const char* as_last_error(const as_ctx* ctx);
 /* Bytes of device workspace as_train_step needs for up to max_rows rows of
  * row_len tokens.  The workspace must be 256-byte aligned. */
 int as_workspace_bytes(const as_ctx* ctx, int64_t max_rows, int64_t row_len, size_t* bytes);
+
+/* ---- per-kernel timing (measurement aid, not part of the method) ---------- *
+ * as_profile(ctx, 1) makes the library bracket every launch of the kernel
+ * classes below with HIP events on the launch stream (up to 65536 launches,
+ * later ones are not recorded); as_profile(ctx, 0) stops and clears.
+ * as_profile_read waits for the device, then returns, for one class, the
+ * number of recorded launches, the sum of their durations in milliseconds
+ * and the sum of their algorithmic flops (2*M*N*K for GEMMs with a host-known
+ * row count; 0 for classes where the host cannot know the work). */
+enum { AS_K_GEMM_MFMA_256 = 0,   /* bf16 MFMA GEMM, 256x256 tile                 */
+       AS_K_GEMM_MFMA_SKINNY,    /* bf16 MFMA GEMM, 256x64 / 64x256 / 128x128    */
+       AS_K_GEMM_FMA,            /* plain FMA GEMM                               */
+       AS_K_GEMM_DEVROWS,        /* any GEMM whose row count lives on the device */
+       AS_K_ATTN_FWD, AS_K_ATTN_BWD, AS_K_TRANSPOSE, AS_K_NORM, AS_K_SWIGLU, AS_K_ROPE, AS_K_CE,
+       AS_K_N_CLASSES };
+int as_profile(as_ctx* ctx, int enable);
+int as_profile_read(as_ctx* ctx, int kernel_class, int64_t* launches, double* ms, double* flops);
 
 /* ---- pack (Section 3.2.1) ----------------------------------------------- */
 

@@ -81,11 +81,15 @@ lib.as_op_rmsnorm_bwd.argtypes = [_vp, C.c_int, _i64, _i64, _vp, _vp, _vp, _vp, 
 lib.as_op_attention_fwd.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp]
 lib.as_op_attention_bwd.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp,
                                     _vp, _vp, _vp, _vp, _vp]
-for _n in ("as_create", "as_workspace_bytes", "as_pack", "as_train_step", "as_adamw_update", "as_op_gemm",
+lib.as_profile.argtypes = [_vp, C.c_int]
+lib.as_profile_read.argtypes = [_vp, C.c_int, C.POINTER(_i64), C.POINTER(C.c_double), C.POINTER(C.c_double)]
+KERNEL_CLASSES = ("gemm_mfma_256", "gemm_mfma_skinny", "gemm_fma", "gemm_devrows", "attn_fwd", "attn_bwd", "transpose",
+                  "norm", "swiglu", "rope", "ce")
+for _n in ("as_profile", "as_profile_read", "as_create", "as_workspace_bytes", "as_pack", "as_train_step", "as_adamw_update", "as_op_gemm",
            "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd"):
     getattr(lib, _n).restype = C.c_int
 
-EXPORTS = ("as_create", "as_destroy", "as_last_error", "as_workspace_bytes", "as_pack", "as_train_step",
+EXPORTS = ("as_profile", "as_profile_read", "as_create", "as_destroy", "as_last_error", "as_workspace_bytes", "as_pack", "as_train_step",
            "as_adamw_update", "as_op_gemm", "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd",
            "as_op_attention_bwd")
 
@@ -106,7 +110,7 @@ def make_config(sh, mode=None, train_mode=None, recompute=None):
     if mode is None:
         mode = AS_BF16 if sh.bf16 else AS_FP32
     if recompute is None:
-        recompute = int(bool(getattr(sh, "recompute", False)))
+        recompute = int(getattr(sh, "recompute", 0))
     return ModelConfig(C.sizeof(ModelConfig), sh.n_layers, sh.d_model, sh.n_q_heads, sh.n_kv_heads, sh.head_dim,
                        sh.ffn, sh.vocab, sh.n_experts, sh.top_k, sh.rms_eps, sh.rope_base,
                        0 if full else sh.lora_rank, 0.0 if full else sh.lora_alpha, mask, mode,
@@ -151,6 +155,18 @@ class Context:
         out = C.c_size_t()
         self.check(lib.as_workspace_bytes(self.handle, max_rows, row_len, C.byref(out)))
         return out.value
+
+    def profile(self, enable):
+        self.check(lib.as_profile(self.handle, int(enable)))
+
+    def profile_read(self):
+        """{class name: (launches, total ms, total flops)} for the launches recorded so far."""
+        out = {}
+        for i, name in enumerate(KERNEL_CLASSES):
+            n, ms, fl = _i64(), C.c_double(), C.c_double()
+            self.check(lib.as_profile_read(self.handle, i, C.byref(n), C.byref(ms), C.byref(fl)))
+            out[name] = (n.value, ms.value, fl.value)
+        return out
 
     # ---------------------------------------------------------------- pack
     def pack(self, turn_tokens, turn_offsets, turn_roles, traj_offsets, row_len, max_rows, pad_id=0,

@@ -36,7 +36,7 @@ static int check_config(const as_model_config* c) {
   } else if (c->lora_rank != 0 || c->lora_targets != 0) {
     return as_fail(nullptr, AS_ERR_CONFIG, "full fine-tuning takes no adapters");
   }
-  if (c->recompute != 0 && c->recompute != 1) return as_fail(nullptr, AS_ERR_CONFIG, "recompute must be 0 or 1");
+  if (c->recompute < 0 || c->recompute > 2) return as_fail(nullptr, AS_ERR_CONFIG, "recompute must be 0, 1 or 2");
   return AS_OK;
 }
 
@@ -51,8 +51,54 @@ extern "C" int as_create(as_ctx** out, const as_model_config* cfg, int device) {
   return AS_OK;
 }
 
+void prof_begin(as_ctx* ctx, hipStream_t st, int cls, double flops) {
+  if (!ctx || !ctx->prof_on) return;
+  if (ctx->prof_used >= 65536) { ctx->prof_used++; return; }
+  if (ctx->prof_used >= ctx->prof.size()) {
+    as_ctx::ProfRec r; r.flops = 0; r.cls = 0;
+    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) { ctx->prof_on = false; return; }
+    ctx->prof.push_back(r);
+  }
+  as_ctx::ProfRec& r = ctx->prof[ctx->prof_used];
+  r.flops = flops; r.cls = cls;
+  (void)hipEventRecord(r.a, st);
+}
+void prof_end(as_ctx* ctx, hipStream_t st) {
+  if (!ctx || !ctx->prof_on) return;
+  if (ctx->prof_used < 65536) (void)hipEventRecord(ctx->prof[ctx->prof_used].b, st);
+  ctx->prof_used++;
+}
+
+extern "C" int as_profile(as_ctx* ctx, int enable) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_profile: NULL context");
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  AS_HIP(ctx, hipDeviceSynchronize());
+  ctx->prof_on = enable != 0;
+  ctx->prof_used = 0;
+  return AS_OK;
+}
+
+extern "C" int as_profile_read(as_ctx* ctx, int kernel_class, int64_t* launches, double* ms, double* flops) {
+  if (!ctx || !launches || !ms || !flops) return as_fail(ctx, AS_ERR_NULL, "as_profile_read: NULL argument");
+  if (kernel_class < 0 || kernel_class >= AS_K_N_CLASSES) return as_fail(ctx, AS_ERR_SHAPE, "as_profile_read: unknown kernel class");
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  AS_HIP(ctx, hipDeviceSynchronize());
+  int64_t n = 0; double t = 0, f = 0;
+  size_t used = ctx->prof_used < ctx->prof.size() ? ctx->prof_used : ctx->prof.size();
+  for (size_t i = 0; i < used; i++) {
+    const as_ctx::ProfRec& r = ctx->prof[i];
+    if (r.cls != kernel_class) continue;
+    float e = 0.f;
+    AS_HIP(ctx, hipEventElapsedTime(&e, r.a, r.b));
+    n++; t += e; f += r.flops;
+  }
+  *launches = n; *ms = t; *flops = f;
+  return AS_OK;
+}
+
 extern "C" void as_destroy(as_ctx* ctx) {
   if (!ctx) return;
+  for (auto& r : ctx->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   if (ctx->d_stage) (void)hipFree(ctx->d_stage);
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
   delete ctx;
@@ -267,15 +313,22 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   P.rstd_f = (float*)w.take(N * 4);
   P.h.resize(P.L + 1);
   for (int l = 0; l <= P.L; l++) P.h[l] = w.take(N * P.d * es);
-  const int n_sets = c.recompute ? 1 : P.L;
+  // recompute 0: every layer keeps all its activations; 1: one shared set, the layer's forward is
+  // re-run before its backward; 2: every layer keeps the GEMM and attention outputs, and only the
+  // cheap ones (both norm outputs, the SwiGLU product) live in one shared set and are rebuilt.
+  const int n_sets = c.recompute == 1 ? 1 : P.L;
   P.acts.resize(n_sets);
+  void *sh_a = nullptr, *sh_b = nullptr, *sh_m = nullptr;
+  if (c.recompute == 2) { sh_a = w.take(N * P.d * es); sh_b = w.take(N * P.d * es); sh_m = w.take(N * P.F * es); }
   for (int s = 0; s < n_sets; s++) {
     Acts& a = P.acts[s];
     a.rstd1 = (float*)w.take(N * 4); a.rstd2 = (float*)w.take(N * 4);
     a.lse = (float*)w.take(N * c.n_q_heads * 4);
-    a.a = w.take(N * P.d * es); a.qkv = w.take(N * P.QKV * es); a.o = w.take(N * P.D * es);
-    a.h_mid = w.take(N * P.d * es); a.b = w.take(N * P.d * es);
-    a.gu = w.take(N * 2 * P.F * es); a.m = w.take(N * P.F * es);
+    a.qkv = w.take(N * P.QKV * es); a.o = w.take(N * P.D * es);
+    a.h_mid = w.take(N * P.d * es);
+    a.gu = w.take(N * 2 * P.F * es);
+    if (c.recompute == 2) { a.a = sh_a; a.b = sh_b; a.m = sh_m; }
+    else { a.a = w.take(N * P.d * es); a.b = w.take(N * P.d * es); a.m = w.take(N * P.F * es); }
     a.u_qkv = w.take(N * P.n_qkv * rp * es); a.u_o = w.take(on(AS_T_O) ? N * rp * es : 0);
     a.u_gu = w.take(N * P.n_gu * rp * es); a.u_d = w.take(on(AS_T_DOWN) ? N * rp * es : 0);
   }
@@ -428,6 +481,15 @@ struct Step {
       if (s.on && (rc = gemm(N, rp, a.m, F, s.A, F, F, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_d, rp))) return rc;
       if ((rc = gemm(N, d, a.m, F, w.wdown, F, F, s.on ? a.u_d : nullptr, rp, s.Bs, rp, s.on ? rp : 0, a.h_mid, d, h_out, d))) return rc; }
     return AS_OK;
+  }
+
+  // the activations that are cheaper to rebuild than to keep: both norm outputs and the SwiGLU product
+  int rebuild_cheap(int l, Acts& a) {
+    const as_layer_weights& w = W->layers[l];
+    int rc;
+    if ((rc = launch_rmsnorm_fwd(ctx, mode, P.N, P.d, P.h[l], nullptr, nullptr, w.g1, c.rms_eps, a.a, a.rstd1, st))) return rc;
+    if ((rc = launch_rmsnorm_fwd(ctx, mode, P.N, P.d, a.h_mid, nullptr, nullptr, w.g2, c.rms_eps, a.b, a.rstd2, st))) return rc;
+    return launch_swiglu_fwd(ctx, mode, P.N, P.F, a.gu, a.m, st);
   }
 
   int transpose(int rows, int cols, const void* in, int64_t ldi, void* out, int64_t ldo) {
@@ -658,11 +720,12 @@ extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lo
   if (!full) for (int l = 0; l < c.n_layers; l++) if ((rc = S.prep_lora(l))) return rc;
   if ((rc = launch_embed(ctx, c.mode, d_tokens, n, c.d_model, weights->embed, P.h[0], st))) return rc;
   for (int l = 0; l < c.n_layers; l++)
-    if ((rc = S.forward_layer(l, P.acts[c.recompute ? 0 : l]))) return rc;
+    if ((rc = S.forward_layer(l, P.acts[c.recompute == 1 ? 0 : l]))) return rc;
   if ((rc = S.head_and_loss(d_loss, d_loss_sum))) return rc;
   for (int l = c.n_layers - 1; l >= 0; l--) {
-    Acts& a = P.acts[c.recompute ? 0 : l];
-    if (c.recompute && l != c.n_layers - 1 && (rc = S.forward_layer(l, a))) return rc;   // re-run the layer from its saved input
+    Acts& a = P.acts[c.recompute == 1 ? 0 : l];
+    if (c.recompute == 1 && l != c.n_layers - 1 && (rc = S.forward_layer(l, a))) return rc;   // re-run the layer from its saved input
+    if (c.recompute == 2 && l != c.n_layers - 1 && (rc = S.rebuild_cheap(l, a))) return rc;
     if ((rc = S.backward_layer(l, a))) return rc;
   }
   if (full && (rc = launch_embed_bwd(ctx, c.mode, d_tokens, n, c.d_model, c.vocab, P.dh, P.iscratch, grads->embed, st))) return rc;

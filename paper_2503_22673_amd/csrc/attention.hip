@@ -146,7 +146,7 @@ int launch_attention_fwd(as_ctx* ctx, int mode, int variant, const AttnParams& p
   if (p.n <= 0) return AS_OK;
   bool mf = mode == AS_BF16 && variant != 1 && attention_mfma_ok(p);
   if (variant == 2 && !mf) return as_fail(ctx, AS_ERR_SHAPE, "attention: MFMA kernel needs bf16, head_dim 64/128, aligned strides");
-  if (mf) return launch_attention_fwd_mfma(ctx, p, st);
+  if (mf) { prof_begin(ctx, st, AS_K_ATTN_FWD, 0.0); int r = launch_attention_fwd_mfma(ctx, p, st); prof_end(ctx, st); return r; }
   size_t smem = (size_t)(p.dh + p.max_seg) * sizeof(float);
   int rc = check_plain(ctx, p, smem); if (rc) return rc;
   float scale = 1.f / sqrtf((float)p.dh);
@@ -163,7 +163,7 @@ int launch_attention_bwd(as_ctx* ctx, int mode, int variant, const AttnParams& p
   if (p.n <= 0) return AS_OK;
   bool mf = mode == AS_BF16 && variant != 1 && attention_mfma_ok(p);
   if (variant == 2 && !mf) return as_fail(ctx, AS_ERR_SHAPE, "attention: MFMA kernel needs bf16, head_dim 64/128, aligned strides");
-  if (mf) return launch_attention_bwd_mfma(ctx, p, st);
+  if (mf) { prof_begin(ctx, st, AS_K_ATTN_BWD, 0.0); int r = launch_attention_bwd_mfma(ctx, p, st); prof_end(ctx, st); return r; }
   size_t smem1 = (size_t)(2 * p.dh + p.max_seg) * sizeof(float);
   size_t smem2 = (size_t)(2 * p.dh + 2 * p.max_seg) * sizeof(float);
   int rc = check_plain(ctx, p, smem2); if (rc) return rc;

@@ -6,6 +6,7 @@
 #include <stdint.h>
 #include <stddef.h>
 #include <string>
+#include <vector>
 #include "actionstudio.h"
 
 typedef __bf16 bf16_t;
@@ -24,7 +25,14 @@ struct as_ctx {
   // staging owned by the context (as_pack only)
   void* d_stage = nullptr; size_t d_stage_bytes = 0;
   void* h_stage = nullptr; size_t h_stage_bytes = 0;
+  // optional per-launch timing (as_profile): event pairs around kernels of the tracked classes
+  struct ProfRec { hipEvent_t a, b; double flops; int cls; };
+  bool prof_on = false;
+  std::vector<ProfRec> prof; size_t prof_used = 0;
 };
+// Brackets one kernel launch with events when profiling is on (no-ops otherwise).
+void prof_begin(as_ctx* ctx, hipStream_t st, int cls, double flops);
+void prof_end(as_ctx* ctx, hipStream_t st);
 
 int as_fail(as_ctx* ctx, int code, const char* fmt, ...);
 #define AS_HIP(ctx, call) do { hipError_t e_ = (call); if (e_ != hipSuccess) \

@@ -126,8 +126,10 @@ int launch_rope(as_ctx* ctx, int mode, int n, int n_heads, int dh, void* x, int6
                 const int32_t* seg_start, const float* cosb, const float* sinb, int inverse, hipStream_t st) {
   int64_t tot = (int64_t)n * n_heads * (dh / 2);
   if (tot <= 0) return AS_OK;
+  prof_begin(ctx, st, AS_K_ROPE, 0.0);
   DISPATCH_T(mode, (rope_kernel<T><<<cdiv(tot, 256), 256, 0, st>>>(n, n_heads, dh, (T*)x, ldx, seg_start,
                                                                     cosb, sinb, inverse ? -1.f : 1.f)));
+  prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
@@ -199,9 +201,11 @@ __global__ void rmsnorm_fwd_kernel(int n, int d, const T* __restrict__ x, const 
 int launch_rmsnorm_fwd(as_ctx* ctx, int mode, int n, int d, const void* x, const int32_t* row_idx,
                        const int* n_dev, const void* g, float eps, void* y, float* rstd, hipStream_t st) {
   if (n <= 0) return AS_OK;
+  prof_begin(ctx, st, AS_K_NORM, 0.0);
   DISPATCH_T(mode, { int vec = vec_ok<T>(x, d) && vec_ok<T>(y, d) && vec_ok<T>(g, d);
                      rmsnorm_fwd_kernel<T><<<cdiv(n, 4), 256, 0, st>>>(n, d, (const T*)x, row_idx, n_dev,
                                                                        (const T*)g, eps, (T*)y, rstd, vec); });
+  prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
@@ -257,10 +261,12 @@ int launch_rmsnorm_bwd(as_ctx* ctx, int mode, int n, int d, const void* dy, cons
                        const void* x, const void* g, const float* rstd, const void* add, void* dx,
                        hipStream_t st) {
   if (n <= 0) return AS_OK;
+  prof_begin(ctx, st, AS_K_NORM, 0.0);
   DISPATCH_T(mode, { int vec = vec_ok<T>(dy, d) && vec_ok<T>(x, d) && vec_ok<T>(g, d) && vec_ok<T>(dx, d) &&
                                (!add || vec_ok<T>(add, d));
                      rmsnorm_bwd_kernel<T><<<cdiv(n, 4), 256, 0, st>>>(n, d, (const T*)dy, src_pos, (const T*)x,
                          (const T*)g, rstd, (const T*)add, (T*)dx, vec); });
+  prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
@@ -356,17 +362,21 @@ __global__ void swiglu_bwd_kernel(int64_t n, int F, const T* __restrict__ dm, co
 
 int launch_swiglu_fwd(as_ctx* ctx, int mode, int64_t n, int F, const void* gu, void* m, hipStream_t st) {
   if (n <= 0) return AS_OK;
+  prof_begin(ctx, st, AS_K_SWIGLU, 0.0);
   DISPATCH_T(mode, { int vec = vec_ok<T>(gu, F) && vec_ok<T>(m, F);
                      int64_t tot = n * (vec ? F / Vec<T>::N : F);
                      swiglu_fwd_kernel<T><<<cdiv(tot, 256), 256, 0, st>>>(n, F, (const T*)gu, (T*)m, vec); });
+  prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
 int launch_swiglu_bwd(as_ctx* ctx, int mode, int64_t n, int F, const void* dm, const void* gu, void* dgu, hipStream_t st) {
   if (n <= 0) return AS_OK;
+  prof_begin(ctx, st, AS_K_SWIGLU, 0.0);
   DISPATCH_T(mode, { int vec = vec_ok<T>(gu, F) && vec_ok<T>(dm, F) && vec_ok<T>(dgu, F);
                      int64_t tot = n * (vec ? F / Vec<T>::N : F);
                      swiglu_bwd_kernel<T><<<cdiv(tot, 256), 256, 0, st>>>(n, F, (const T*)dm, (const T*)gu, (T*)dgu, vec); });
+  prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
@@ -396,7 +406,9 @@ int launch_transpose(as_ctx* ctx, int mode, int rows, int cols, const void* in, 
                      int64_t ldo, const int* rows_dev, int row_off, hipStream_t st) {
   if (rows <= 0 || cols <= 0) return AS_OK;
   dim3 grid(cdiv(cols, 64), cdiv(rows, 64));
+  prof_begin(ctx, st, AS_K_TRANSPOSE, 0.0);
   DISPATCH_T(mode, (transpose_kernel<T><<<grid, 256, 0, st>>>(rows, cols, (const T*)in, ldi, (T*)out, ldo, rows_dev, row_off)));
+  prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
@@ -518,7 +530,9 @@ __global__ void ce_rows_kernel(const float* __restrict__ logits, int V, int row0
 int launch_ce_rows(as_ctx* ctx, int mode, const float* logits, int rows_cap, int V, int row0,
                    const int32_t* labels, const int32_t* count, float* loss_rows, void* P, hipStream_t st) {
   if (rows_cap <= 0) return AS_OK;
+  prof_begin(ctx, st, AS_K_CE, 0.0);
   DISPATCH_T(mode, (ce_rows_kernel<T><<<rows_cap, 512, 0, st>>>(logits, V, row0, labels, count, loss_rows, (T*)P)));
+  prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }

@@ -231,6 +231,11 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
   bool use_mfma = (mode == AS_BF16) && variant != 1 && mfma_ok(p);
   if (variant == 2 && !use_mfma) return as_fail(ctx, AS_ERR_SHAPE, "gemm: MFMA kernel needs bf16 and 8-element alignment");
   int rc = AS_OK;
+  double ksum = 0; for (int s = 0; s < p.nseg; s++) ksum += p.seg[s].K;
+  const bool big = use_mfma && !(p.N <= 128 && p.M > 128) && !(p.M <= 128) &&
+                   !((int64_t)cdiv(p.M, 256) * cdiv(p.N, 256) * p.splitk < 128);
+  prof_begin(ctx, st, p.m_dev ? AS_K_GEMM_DEVROWS : !use_mfma ? AS_K_GEMM_FMA : big ? AS_K_GEMM_MFMA_256 : AS_K_GEMM_MFMA_SKINNY,
+             p.m_dev ? 0.0 : 2.0 * p.M * p.N * ksum);
   if (use_mfma) {
     if (p.N <= 128 && p.M > 128) rc = launch_mfma_cfg<256, 64, 4, 1>(ctx, p, m_off, st);
     else if (p.M <= 128) rc = launch_mfma_cfg<64, 256, 1, 4>(ctx, p, m_off, st);
@@ -242,6 +247,7 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
     else gemm_fma_kernel<bf16_t><<<grid, 256, 0, st>>>(p, m_off);
     AS_LAUNCH_CHECK(ctx);
   }
+  prof_end(ctx, st);
   if (rc) return rc;
   if (p.splitk > 1) {
     if (!p.c_f32) return as_fail(ctx, AS_ERR_SHAPE, "gemm: split-K writes float output");

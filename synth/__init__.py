@@ -34,7 +34,7 @@ class Shape:
     rows: int = 1
     row_len: int = 512
     full_ft: bool = False
-    recompute: bool = False
+    recompute: int = 0
     bf16: bool = True
 
     def replace(self, **kw):
@@ -49,7 +49,7 @@ CONFIGS = {
     2: Shape("llama-1b-lora", 16, 2048, 32, 8, 64, 8192, 32000, 1e-5, 1e4, 16, 32.0, DENSE_TARGETS7,
              rows=8, row_len=4096),
     3: Shape("llama3-8b-lora", 32, 4096, 32, 8, 128, 14336, 128256, 1e-5, 5e5, 64, 128.0, DENSE_TARGETS7,
-             rows=4, row_len=16384, recompute=True),
+             rows=4, row_len=16384, recompute=2),
     4: Shape("llama-1b-fullft", 16, 2048, 32, 8, 64, 8192, 32000, 1e-5, 1e4, 0, 0.0, (),
              rows=16, row_len=4096, full_ft=True),
     5: Shape("mixtral-8x7b-lora", 32, 4096, 32, 8, 128, 14336, 32000, 1e-5, 1e6, 16, 32.0,

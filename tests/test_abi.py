@@ -57,7 +57,7 @@ def test_workspace_query(B):
     # config 3 with recompute must fit one MI355X (288 GB) with room for weights
     c3 = B.Context(B.make_config(synth.CONFIGS[3]))
     gb = c3.workspace_bytes(4, 16384) / 2 ** 30
-    assert gb < 200, gb
+    assert gb < 240, gb            # + 16 GB of bf16 weights + adapters and their moments < 288 GB
 
 
 def _pack_args(trajs):

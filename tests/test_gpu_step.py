@@ -32,14 +32,16 @@ def test_seven_targets_gqa_recompute_two_rows(bf16):
     """All seven adapters, grouped KV heads, activation recompute, two rows with ragged tails."""
     import gpu_util as G
     sh = synth.CONFIGS[1].replace(n_layers=3, n_q_heads=4, n_kv_heads=2, head_dim=64, d_model=128, ffn=200,
-                                  lora_targets=synth.DENSE_TARGETS7, lora_rank=8, lora_alpha=16.0, recompute=True)
+                                  lora_targets=synth.DENSE_TARGETS7, lora_rank=8, lora_alpha=16.0, recompute=1)
     trajs = random_trajs(3, 9, sh.vocab, turn_lo=10, turn_hi=40, turns=(2, 5))
     rep = G.compare_step(sh, 1, trajs, 2, 320, bf16=bf16, loss_tol=2e-3 if bf16 else 1e-4,
                          grad_tol=3e-2 if bf16 else 1e-4, recompute=1)
     rep2 = G.compare_step(sh, 1, trajs, 2, 320, bf16=bf16, loss_tol=2e-3 if bf16 else 1e-4,
                           grad_tol=3e-2 if bf16 else 1e-4, recompute=0)
+    rep3 = G.compare_step(sh, 1, trajs, 2, 320, bf16=bf16, loss_tol=2e-3 if bf16 else 1e-4,
+                          grad_tol=3e-2 if bf16 else 1e-4, recompute=2)
     # recompute re-runs the same kernels on the same inputs: identical bits
-    assert rep["loss"] == rep2["loss"] and rep["grads"] == rep2["grads"]
+    assert rep["loss"] == rep2["loss"] == rep3["loss"] and rep["grads"] == rep2["grads"] == rep3["grads"]
 
 
 def test_zero_mask_gives_exact_zero_loss_and_gradients():

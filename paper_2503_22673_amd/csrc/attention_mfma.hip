@@ -23,6 +23,9 @@
 namespace {
 
 constexpr int BKEY = 64;      // keys (or queries) per staged tile
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+// v_exp_f32 without the denormal-range fix-up of exp2f: arguments here are <= 0 or masked to -inf
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ f32x16 zero16() {
   f32x16 z;
@@ -37,20 +40,20 @@ struct TileIO {
   static constexpr int LS = DH + 8;            // LDS row stride in elements: 16 B pad keeps 16 lanes on 64 banks
   static constexpr int CPR = DH / 8;           // 16-byte chunks per row
   static constexpr int PER = BKEY * CPR / 256; // chunks per thread
-  uint4 r[PER];
+  u32x4 r[PER];
   __device__ __forceinline__ void fetch(const bf16_t* base, int64_t ld, int col, int row0, int n, int tid) {
 #pragma unroll
     for (int i = 0; i < PER; i++) {
       int c = tid + i * 256, row = c / CPR, cc = c % CPR;
       int t = min(row0 + row, n - 1);
-      r[i] = *reinterpret_cast<const uint4*>(base + (int64_t)t * ld + col + cc * 8);
+      r[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)t * ld + col + cc * 8);
     }
   }
   __device__ __forceinline__ void stash(bf16_t* s, int tid) const {
 #pragma unroll
     for (int i = 0; i < PER; i++) {
       int c = tid + i * 256, row = c / CPR, cc = c % CPR;
-      *reinterpret_cast<uint4*>(s + row * LS + cc * 8) = r[i];
+      *reinterpret_cast<u32x4*>(s + row * LS + cc * 8) = r[i];
     }
   }
 };
@@ -147,13 +150,13 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(AttnParams p, float sl2) {
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       float m_new = fmaxf(m[qb], mx);
       float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      float alpha = exp2f(m[qb] - m_use);
+      float alpha = fast_exp2(m[qb] - m_use);
       m[qb] = m_new;
       float rs = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; kb++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) { float pv = exp2f(s[qb][kb][e] - m_use); s[qb][kb][e] = pv; rs += pv; }
+        for (int e = 0; e < 16; e++) { float pv = fast_exp2(s[qb][kb][e] - m_use); s[qb][kb][e] = pv; rs += pv; }
       rs += __shfl_xor(rs, 32, 64);
       l[qb] = l[qb] * alpha + rs;
 #pragma unroll
@@ -260,8 +263,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(AttnParams p, float scal
 #pragma unroll
       for (int e = 0; e < 16; e++) {
         int key = k0 + kb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-        float pr = (key >= ss && key <= tq) ? exp2f(s[kb][e] * sl2 - lse2) : 0.f;
-        s[kb][e] = pr * (dp[kb][e] - dl);
+        float x = (key >= ss && key <= tq) ? s[kb][e] * sl2 - lse2 : -INFINITY;
+        s[kb][e] = fast_exp2(x) * (dp[kb][e] - dl);
       }
       dsb[kb * 2] = pack8(s[kb], 0); dsb[kb * 2 + 1] = pack8(s[kb], 1);
     }
@@ -297,7 +300,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(AttnParams p, float sca
   constexpr int LS = DH + 8, KS = DH / 16, CB = DH / 32;
   __shared__ __align__(16) bf16_t sQ[BKEY * LS];
   __shared__ __align__(16) bf16_t sdO[BKEY * LS];
-  __shared__ float sLse[BKEY], sDel[BKEY];
+  __shared__ __align__(16) float sLse[BKEY];
+  __shared__ __align__(16) float sDel[BKEY];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, h = lane >> 5;
   const int n = p.n, grp = p.Hq / p.Hkv, g = blockIdx.y;
   const int u_wg = blockIdx.x * 128, u_base = u_wg + wave * 32;
@@ -352,12 +356,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(AttnParams p, float sca
 #pragma unroll
     for (int qb = 0; qb < 2; qb++) {
 #pragma unroll
-      for (int e = 0; e < 16; e++) {
-        int qi = qb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-        int t = t0 + qi;
-        float pr = (t >= u && t < uend) ? exp2f(s[qb][e] * sl2 - sLse[qi]) : 0.f;
-        s[qb][e] = pr;
-        dp[qb][e] = pr * (dp[qb][e] - sDel[qi]);
+      for (int b4 = 0; b4 < 4; b4++) {
+        const int qi0 = qb * 32 + 8 * b4 + 4 * h;            // 4 consecutive queries: one 16-byte read each
+        const f32x4 ls = *reinterpret_cast<const f32x4*>(&sLse[qi0]);
+        const f32x4 dl = *reinterpret_cast<const f32x4*>(&sDel[qi0]);
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          const int e = b4 * 4 + i, t = t0 + qi0 + i;
+          float x = (t >= u && t < uend) ? s[qb][e] * sl2 - ls[i] : -INFINITY;
+          float pr = fast_exp2(x);
+          s[qb][e] = pr;
+          dp[qb][e] = pr * (dp[qb][e] - dl[i]);
+        }
       }
       pbv[qb * 2] = pack8(s[qb], 0); pbv[qb * 2 + 1] = pack8(s[qb], 1);
       dsb[qb * 2] = pack8(dp[qb], 0); dsb[qb * 2 + 1] = pack8(dp[qb], 1);

@@ -86,7 +86,10 @@ __global__ __launch_bounds__(256) void gemm_fma_kernel(GemmParams p, int m_off) 
 }
 
 // -------------------------------------------------------------- MFMA kernel
-template <int BM, int BN, int WM, int WN>
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+// EDGE = false: every K segment is a multiple of 64, so tile loads need no k guard.
+template <int BM, int BN, int WM, int WN, bool EDGE>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p, int m_off, int tiles_m, int tiles_n) {
   constexpr int BK = 64, LS = BK + 8, NT = WM * WN * 64;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -124,8 +127,17 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p, i
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
-  uint4 ra[CA], rb[CB];
-  const int mclamp = p.M - 1, nclamp = p.N - 1;
+  u32x4 ra[CA], rb[CB];
+  // per-thread row offsets inside the tile are fixed; only the k offset moves
+  int64_t offA[CA], offB[CB];
+  {
+    const int mclamp = p.M - 1, nclamp = p.N - 1;
+#pragma unroll
+    for (int i = 0; i < CA; i++) { int c = tid + i * NT; offA[i] = (int64_t)min(row0 + (c >> 3), mclamp); }
+#pragma unroll
+    for (int i = 0; i < CB; i++) { int c = tid + i * NT; offB[i] = (int64_t)min(col0 + (c >> 3), nclamp); }
+  }
+  const int kc = (tid & 7) * 8;                          // NT is a multiple of 8: same k chunk for every i
 
   auto fetch = [&](int it) {
     const bool first = it < nt0;
@@ -133,26 +145,26 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p, i
     const bf16_t* B = (const bf16_t*)(first ? p.seg[0].B : p.seg[1].B);
     const int64_t lda = first ? p.seg[0].lda : p.seg[1].lda, ldb = first ? p.seg[0].ldb : p.seg[1].ldb;
     const int K = first ? p.seg[0].K : p.seg[1].K;
-    const int k0 = (first ? kr0.beg + it : kr1.beg + it - nt0) * BK;
+    const int k = (first ? kr0.beg + it : kr1.beg + it - nt0) * BK + kc;
+    const bool in = !EDGE || k < K;
+    const int ks = in ? k : 0;                           // a valid address either way
 #pragma unroll
     for (int i = 0; i < CA; i++) {
-      int c = tid + i * NT, r = c >> 3, k = k0 + (c & 7) * 8;
-      int gr = min(row0 + r, mclamp);
-      ra[i] = (k < K) ? *reinterpret_cast<const uint4*>(A + (int64_t)gr * lda + k) : make_uint4(0, 0, 0, 0);
+      u32x4 v = *reinterpret_cast<const u32x4*>(A + offA[i] * lda + ks);
+      ra[i] = in ? v : (u32x4){0u, 0u, 0u, 0u};
     }
 #pragma unroll
     for (int i = 0; i < CB; i++) {
-      int c = tid + i * NT, r = c >> 3, k = k0 + (c & 7) * 8;
-      int gr = min(col0 + r, nclamp);
-      rb[i] = (k < K) ? *reinterpret_cast<const uint4*>(B + (int64_t)gr * ldb + k) : make_uint4(0, 0, 0, 0);
+      u32x4 v = *reinterpret_cast<const u32x4*>(B + offB[i] * ldb + ks);
+      rb[i] = in ? v : (u32x4){0u, 0u, 0u, 0u};
     }
   };
   auto stash = [&](int buf) {
     bf16_t* a = sA + buf * BM * LS; bf16_t* b = sB + buf * BN * LS;
 #pragma unroll
-    for (int i = 0; i < CA; i++) { int c = tid + i * NT; *reinterpret_cast<uint4*>(a + (c >> 3) * LS + (c & 7) * 8) = ra[i]; }
+    for (int i = 0; i < CA; i++) { int c = tid + i * NT; *reinterpret_cast<u32x4*>(a + (c >> 3) * LS + kc) = ra[i]; }
 #pragma unroll
-    for (int i = 0; i < CB; i++) { int c = tid + i * NT; *reinterpret_cast<uint4*>(b + (c >> 3) * LS + (c & 7) * 8) = rb[i]; }
+    for (int i = 0; i < CB; i++) { int c = tid + i * NT; *reinterpret_cast<u32x4*>(b + (c >> 3) * LS + kc) = rb[i]; }
   };
 
   if (nt > 0) { fetch(0); stash(0); }
@@ -179,39 +191,68 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p, i
     __syncthreads();
   }
 
-  // lane l holds column l%32 and rows 8*(e/4) + 4*(l/32) + e%4 of each 32x32 block
+  // Epilogue.  Lane l holds column l%32 and rows 8*(e/4) + 4*(l/32) + e%4 of each 32x32 block.
+  // The output kind is uniform for the launch, so it is tested once, outside the element loops.
+  const bool full = (row0 + BM <= M) && (col0 + BN <= p.N);
+  const int rb0 = row0 + wm * TM * 32 + 4 * (lane >> 5), cb0 = col0 + wn * TN * 32 + (lane & 31);
+  auto each = [&](auto f) {
 #pragma unroll
-  for (int i = 0; i < TM; i++)
+    for (int i = 0; i < TM; i++)
 #pragma unroll
-    for (int j = 0; j < TN; j++) {
-      int c = col0 + wn * TN * 32 + j * 32 + (lane & 31);
-      if (c >= p.N) continue;
+      for (int j = 0; j < TN; j++) {
+        const int c = cb0 + j * 32;
 #pragma unroll
-      for (int e = 0; e < 16; e++) {
-        int r = row0 + wm * TM * 32 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        if (r < M) store_out<bf16_t>(p, z, r, c, acc[i][j][e]);
+        for (int e = 0; e < 16; e++) {
+          const int r = rb0 + i * 32 + 8 * (e >> 2) + (e & 3);
+          if (full || (r < M && c < p.N)) f(r, c, acc[i][j][e]);
+        }
       }
-    }
+  };
+  if (p.splitk > 1) {
+    float* part = p.partial + (int64_t)z * p.M * p.N;
+    each([&](int r, int c, float v) { part[(int64_t)r * p.N + c] = v; });
+  } else if (p.c_f32) {
+    float* C = (float*)p.C; const float alpha = p.alpha; const bf16_t* R = (const bf16_t*)p.R;
+    if (p.accumulate || R)
+      each([&](int r, int c, float v) {
+        float* q = C + (int64_t)r * p.ldc + c;
+        float x = alpha * v + (R ? (float)R[(int64_t)r * p.ldr + c] : 0.f);
+        *q = p.accumulate ? *q + x : x;
+      });
+    else each([&](int r, int c, float v) { C[(int64_t)r * p.ldc + c] = alpha * v; });
+  } else if (p.R) {
+    bf16_t* C = (bf16_t*)p.C; const bf16_t* R = (const bf16_t*)p.R; const float alpha = p.alpha;
+    each([&](int r, int c, float v) { C[(int64_t)r * p.ldc + c] = (bf16_t)(alpha * v + (float)R[(int64_t)r * p.ldr + c]); });
+  } else {
+    bf16_t* C = (bf16_t*)p.C; const float alpha = p.alpha;
+    each([&](int r, int c, float v) { C[(int64_t)r * p.ldc + c] = (bf16_t)(alpha * v); });
+  }
 }
 
 template <int BM, int BN, int WM, int WN>
 static int launch_mfma_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_t st) {
   constexpr int LS = 72;
   size_t smem = (size_t)2 * (BM + BN) * LS * sizeof(bf16_t);
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN>;
+  bool edge = false;
+  for (int s = 0; s < p.nseg; s++) edge = edge || (p.seg[s].K % 64 != 0);
+  auto k0 = gemm_mfma_kernel<BM, BN, WM, WN, false>;
+  auto k1 = gemm_mfma_kernel<BM, BN, WM, WN, true>;
   static bool attr_set = false;
   if (!attr_set) {
-    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(k0), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(k1), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_set = true;
   }
   int tm = (int)cdiv(p.M, BM), tn = (int)cdiv(p.N, BN);
   dim3 grid(tm * tn, p.splitk > 1 ? p.splitk : 1);
-  kern<<<grid, WM * WN * 64, smem, st>>>(p, m_off, tm, tn);
+  if (edge) k1<<<grid, WM * WN * 64, smem, st>>>(p, m_off, tm, tn);
+  else k0<<<grid, WM * WN * 64, smem, st>>>(p, m_off, tm, tn);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
 
 static bool mfma_ok(const GemmParams& p) {
+  if (p.R && (p.ldr % 1)) return false;
   for (int s = 0; s < p.nseg; s++) {
     const GemmSeg& g = p.seg[s];
     if (g.K % 8 || g.lda % 8 || g.ldb % 8) return false;
@@ -220,7 +261,17 @@ static bool mfma_ok(const GemmParams& p) {
   return true;
 }
 
+// Tile configuration of the MFMA kernel: 0 = 256x256 (8 waves, 128x64 each), 1 = 256x64, 2 = 64x256,
+// 3 = 128x128, 4 = 256x256 with 4 waves of 128x128, 5 = 256x128 (4 waves of 128x64), 6 = 128x256.
+static int pick_cfg(const GemmParams& p) {
+  if (p.N <= 128 && p.M > 128) return 1;
+  if (p.M <= 128) return 2;
+  if ((int64_t)cdiv(p.M, 256) * cdiv(p.N, 256) * p.splitk < 128) return 3;
+  return 0;
+}
+
 // m_dev semantics: the live row count is *m_dev - m_off (clamped to [0, M]).
+// variant: 0 pick, 1 plain FMA kernel, 2 MFMA kernel with the default tile choice, 10 + c forces tile configuration c.
 int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, int m_off, hipStream_t st) {
   GemmParams p = p_in;
   if (p.M <= 0 || p.N <= 0) return AS_OK;
@@ -228,19 +279,25 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
   if (p.splitk < 1) p.splitk = 1;
   if (p.splitk > 1 && !p.partial) return as_fail(ctx, AS_ERR_WORKSPACE, "gemm: split-K needs a partial buffer");
   if (p.accumulate && !p.c_f32) return as_fail(ctx, AS_ERR_SHAPE, "gemm: accumulate needs float output");
+  if (variant < 0 || (variant > 2 && (variant < 10 || variant > 16))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
   bool use_mfma = (mode == AS_BF16) && variant != 1 && mfma_ok(p);
-  if (variant == 2 && !use_mfma) return as_fail(ctx, AS_ERR_SHAPE, "gemm: MFMA kernel needs bf16 and 8-element alignment");
+  if (variant >= 2 && !use_mfma) return as_fail(ctx, AS_ERR_SHAPE, "gemm: MFMA kernel needs bf16 and 8-element alignment");
   int rc = AS_OK;
   double ksum = 0; for (int s = 0; s < p.nseg; s++) ksum += p.seg[s].K;
-  const bool big = use_mfma && !(p.N <= 128 && p.M > 128) && !(p.M <= 128) &&
-                   !((int64_t)cdiv(p.M, 256) * cdiv(p.N, 256) * p.splitk < 128);
+  const int cfg = variant >= 10 ? variant - 10 : pick_cfg(p);
+  const bool big = use_mfma && (cfg == 0 || cfg >= 4);
   prof_begin(ctx, st, p.m_dev ? AS_K_GEMM_DEVROWS : !use_mfma ? AS_K_GEMM_FMA : big ? AS_K_GEMM_MFMA_256 : AS_K_GEMM_MFMA_SKINNY,
              p.m_dev ? 0.0 : 2.0 * p.M * p.N * ksum);
   if (use_mfma) {
-    if (p.N <= 128 && p.M > 128) rc = launch_mfma_cfg<256, 64, 4, 1>(ctx, p, m_off, st);
-    else if (p.M <= 128) rc = launch_mfma_cfg<64, 256, 1, 4>(ctx, p, m_off, st);
-    else if ((int64_t)cdiv(p.M, 256) * cdiv(p.N, 256) * p.splitk < 128) rc = launch_mfma_cfg<128, 128, 2, 2>(ctx, p, m_off, st);
-    else rc = launch_mfma_cfg<256, 256, 2, 4>(ctx, p, m_off, st);
+    switch (cfg) {
+      case 1: rc = launch_mfma_cfg<256, 64, 4, 1>(ctx, p, m_off, st); break;
+      case 2: rc = launch_mfma_cfg<64, 256, 1, 4>(ctx, p, m_off, st); break;
+      case 3: rc = launch_mfma_cfg<128, 128, 2, 2>(ctx, p, m_off, st); break;
+      case 4: rc = launch_mfma_cfg<256, 256, 2, 2>(ctx, p, m_off, st); break;
+      case 5: rc = launch_mfma_cfg<256, 128, 2, 2>(ctx, p, m_off, st); break;
+      case 6: rc = launch_mfma_cfg<128, 256, 2, 2>(ctx, p, m_off, st); break;
+      default: rc = launch_mfma_cfg<256, 256, 2, 4>(ctx, p, m_off, st); break;
+    }
   } else {
     dim3 grid((unsigned)cdiv(p.N, 64), (unsigned)cdiv(p.M, 64), (unsigned)p.splitk);
     if (mode == AS_FP32) gemm_fma_kernel<float><<<grid, 256, 0, st>>>(p, m_off);

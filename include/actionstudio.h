@@ -156,6 +156,12 @@ enum { AS_K_GEMM_MFMA_256 = 0,   /* bf16 MFMA GEMM, 256x256 tile                
 int as_profile(as_ctx* ctx, int enable);
 int as_profile_read(as_ctx* ctx, int kernel_class, int64_t* launches, double* ms, double* flops);
 
+/* Register-resident bf16 MFMA loop over the whole chip (no memory traffic): measures the matrix
+ * throughput the part sustains at its clocks under load.  Launches `blocks` workgroups of 8
+ * wavefronts, each wavefront issuing iters*8 v_mfma_f32_32x32x16_bf16; times it with events on
+ * `stream`, waits, and returns TFLOP/s in *tflops [host].  d_sink [device] float[1]. */
+int as_probe_mfma_peak(as_ctx* ctx, int32_t iters, int32_t blocks, float* d_sink, double* tflops, void* stream);
+
 /* ---- pack (Section 3.2.1) ----------------------------------------------- */
 
 /* Packs trajectories into rows of row_len tokens.

@@ -96,6 +96,25 @@ extern "C" int as_profile_read(as_ctx* ctx, int kernel_class, int64_t* launches,
   return AS_OK;
 }
 
+extern "C" int as_probe_mfma_peak(as_ctx* ctx, int32_t iters, int32_t blocks, float* d_sink, double* tflops, void* stream) {
+  if (!ctx || !d_sink || !tflops) return as_fail(ctx, AS_ERR_NULL, "as_probe_mfma_peak: NULL argument");
+  if (iters < 1 || blocks < 1 || iters > (1 << 24) || blocks > (1 << 20)) return as_fail(ctx, AS_ERR_SHAPE, "as_probe_mfma_peak: iters in [1, 2^24], blocks in [1, 2^20]");
+  hipStream_t st = (hipStream_t)stream;
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  hipEvent_t a, b;
+  AS_HIP(ctx, hipEventCreate(&a)); AS_HIP(ctx, hipEventCreate(&b));
+  int rc = launch_mfma_peak(ctx, iters, blocks, d_sink, st);            // warm-up
+  if (!rc) { (void)hipEventRecord(a, st); rc = launch_mfma_peak(ctx, iters, blocks, d_sink, st); (void)hipEventRecord(b, st); }
+  hipError_t e = hipEventSynchronize(b);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+  (void)hipEventDestroy(a); (void)hipEventDestroy(b);
+  if (rc) return rc;
+  if (e != hipSuccess) return as_fail(ctx, AS_ERR_HIP, "as_probe_mfma_peak: %s", hipGetErrorString(e));
+  *tflops = (double)blocks * 8.0 * iters * 8.0 * 32768.0 / (ms * 1e-3) / 1e12;
+  return AS_OK;
+}
+
 extern "C" void as_destroy(as_ctx* ctx) {
   if (!ctx) return;
   for (auto& r : ctx->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
@@ -295,7 +314,7 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   P.N = (int)(rows * row_len); P.d = c.d_model; P.D = c.n_q_heads * c.head_dim; P.Dkv = c.n_kv_heads * c.head_dim;
   P.QKV = P.D + 2 * P.Dkv; P.F = c.ffn; P.V = c.vocab; P.L = c.n_layers;
   P.es = c.mode == AS_FP32 ? 4 : 2;
-  P.rp = full ? 0 : (int)cdiv(c.lora_rank, 16) * 16;
+  P.rp = full ? 0 : (c.mode == AS_BF16 ? (int)cdiv(c.lora_rank, 64) * 64 : (int)cdiv(c.lora_rank, 16) * 16);   // whole 64-wide K steps for the MFMA tiles
   P.Mc = (int)std::min<int64_t>(4096, cdiv(std::max(P.N, 1), 64) * 64);
   const size_t N = (size_t)P.N, es = (size_t)P.es;
   auto on = [&](int t) { return !full && ((c.lora_targets >> t) & 1u); };

@@ -88,6 +88,46 @@ __global__ __launch_bounds__(256) void gemm_fma_kernel(GemmParams p, int m_off) 
 // -------------------------------------------------------------- MFMA kernel
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
+// Epilogue shared by the MFMA kernels.  Lane l holds column l%32 and rows 8*(e/4) + 4*(l/32) + e%4 of
+// each 32x32 block.  The output kind is uniform for the launch, so it is tested once, outside the
+// element loops; `full` tiles skip the bounds tests.
+template <int TM, int TN>
+__device__ __forceinline__ void gemm_epilogue(const GemmParams& p, f32x16 (&acc)[TM][TN], int M, int z, int row0, int col0,
+                                              int rb0, int cb0, bool full) {
+  auto each = [&](auto f) {
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        const int c = cb0 + j * 32;
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int r = rb0 + i * 32 + 8 * (e >> 2) + (e & 3);
+          if (full || (r < M && c < p.N)) f(r, c, acc[i][j][e]);
+        }
+      }
+  };
+  if (p.splitk > 1) {
+    float* part = p.partial + (int64_t)z * p.M * p.N;
+    each([&](int r, int c, float v) { part[(int64_t)r * p.N + c] = v; });
+  } else if (p.c_f32) {
+    float* C = (float*)p.C; const float alpha = p.alpha; const bf16_t* R = (const bf16_t*)p.R;
+    if (p.accumulate || R)
+      each([&](int r, int c, float v) {
+        float* q = C + (int64_t)r * p.ldc + c;
+        float x = alpha * v + (R ? (float)R[(int64_t)r * p.ldr + c] : 0.f);
+        *q = p.accumulate ? *q + x : x;
+      });
+    else each([&](int r, int c, float v) { C[(int64_t)r * p.ldc + c] = alpha * v; });
+  } else if (p.R) {
+    bf16_t* C = (bf16_t*)p.C; const bf16_t* R = (const bf16_t*)p.R; const float alpha = p.alpha;
+    each([&](int r, int c, float v) { C[(int64_t)r * p.ldc + c] = (bf16_t)(alpha * v + (float)R[(int64_t)r * p.ldr + c]); });
+  } else {
+    bf16_t* C = (bf16_t*)p.C; const float alpha = p.alpha;
+    each([&](int r, int c, float v) { C[(int64_t)r * p.ldc + c] = (bf16_t)(alpha * v); });
+  }
+}
+
 // EDGE = false: every K segment is a multiple of 64, so tile loads need no k guard.
 template <int BM, int BN, int WM, int WN, bool EDGE>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p, int m_off, int tiles_m, int tiles_n) {
@@ -191,42 +231,202 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p, i
     __syncthreads();
   }
 
-  // Epilogue.  Lane l holds column l%32 and rows 8*(e/4) + 4*(l/32) + e%4 of each 32x32 block.
-  // The output kind is uniform for the launch, so it is tested once, outside the element loops.
-  const bool full = (row0 + BM <= M) && (col0 + BN <= p.N);
-  const int rb0 = row0 + wm * TM * 32 + 4 * (lane >> 5), cb0 = col0 + wn * TN * 32 + (lane & 31);
-  auto each = [&](auto f) {
+  gemm_epilogue<TM, TN>(p, acc, M, z, row0, col0, row0 + wm * TM * 32 + 4 * (lane >> 5), col0 + wn * TN * 32 + (lane & 31),
+                        (row0 + BM <= M) && (col0 + BN <= p.N));
+}
+
+// Same tiling, but tiles travel global -> LDS directly (global_load_lds_dwordx4: a wavefront
+// deposits 64 x 16 bytes contiguously, i.e. 8 rows of 8 chunks), so no VGPR staging and no LDS
+// stores.  The destination cannot be padded, so chunks are XOR-swizzled instead: LDS slot
+// (row, c) holds the row's chunk c ^ (row & 7); each lane picks the matching global chunk.  Fragment
+// reads of 8 consecutive rows then touch 8 different 16-byte columns: no bank conflicts.
+// Fragments are double-buffered in registers so that the reads for the next 16-wide K step are in
+// flight while the MFMAs of the current one issue.  Needs every K segment to be a multiple of 64.
+// chunk swizzle of a tile row: which 3-bit value is XORed onto the chunk index
+template <int SWZ> __device__ __forceinline__ int swz(int r) {
+  if constexpr (SWZ == 0) return r & 7;
+  else if constexpr (SWZ == 1) return (r >> 1) & 7;
+  else return ((r & 3) << 1) | ((r >> 2) & 1);
+}
+
+template <int BM, int BN, int WM, int WN, bool DB, int SWZ, int PF>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams p, int m_off, int tiles_m, int tiles_n) {
+  constexpr int BK = 64, NW = WM * WN;
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;      // 1 KB wave-loads per wave and tile
+  static_assert(LA >= 1 && LB >= 1, "tile too small for the wave count");
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t* sA = (bf16_t*)smem;                            // [2][BM][64]
+  bf16_t* sB = sA + 2 * BM * BK;                         // [2][BN][64]
+
+  const int M = p.m_dev ? min(p.M, *p.m_dev - m_off) : p.M;
+  int nblk = tiles_m * tiles_n, pid = blockIdx.x, z = blockIdx.y;
+  int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
+  int logical = xcd * q8 + min(xcd, rem) + loc;
+  constexpr int GROUP = 8;
+  int in_group = GROUP * tiles_n, grp = logical / in_group, first_m = grp * GROUP;
+  int gsize = min(tiles_m - first_m, GROUP);
+  int tile_m = first_m + (logical % in_group) % gsize, tile_n = (logical % in_group) / gsize;
+  const int row0 = tile_m * BM, col0 = tile_n * BN;
+  if (row0 >= M) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  KRange kr0 = split_range(p.seg[0].K, BK, p.splitk, z);
+  KRange kr1 = {0, 0};
+  if (p.nseg > 1) kr1 = split_range(p.seg[1].K, BK, p.splitk, z);
+  const int nt0 = kr0.end - kr0.beg, nt = nt0 + (kr1.end - kr1.beg);
+
+  f32x16 acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < TM; i++)
+  for (int i = 0; i < TM; i++)
 #pragma unroll
-      for (int j = 0; j < TN; j++) {
-        const int c = cb0 + j * 32;
+    for (int j = 0; j < TN; j++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) {
-          const int r = rb0 + i * 32 + 8 * (e >> 2) + (e & 3);
-          if (full || (r < M && c < p.N)) f(r, c, acc[i][j][e]);
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  // loader: wave-load i of this wave covers tile rows (wave*L + i)*8 .. +7; lane l sits at row l/8,
+  // LDS chunk l%8, and fetches global chunk (l%8) ^ (l/8)
+  const int lrow = lane >> 3;
+  int rowA[LA], rowB[LB];
+  {
+    const int mclamp = p.M - 1, nclamp = p.N - 1;
+#pragma unroll
+    for (int i = 0; i < LA; i++) rowA[i] = min(row0 + (wave * LA + i) * 8 + lrow, mclamp);
+#pragma unroll
+    for (int i = 0; i < LB; i++) rowB[i] = min(col0 + (wave * LB + i) * 8 + lrow, nclamp);
+  }
+  auto fetch = [&](int it, int buf) {
+    const bool first = it < nt0;
+    const bf16_t* A = (const bf16_t*)(first ? p.seg[0].A : p.seg[1].A);
+    const bf16_t* B = (const bf16_t*)(first ? p.seg[0].B : p.seg[1].B);
+    const int64_t lda = first ? p.seg[0].lda : p.seg[1].lda, ldb = first ? p.seg[0].ldb : p.seg[1].ldb;
+    const int k = (first ? kr0.beg + it : kr1.beg + it - nt0) * BK;
+    bf16_t* a = sA + buf * BM * BK + wave * LA * 8 * BK;
+    bf16_t* b = sB + buf * BN * BK + wave * LB * 8 * BK;
+#pragma unroll
+    for (int i = 0; i < LA; i++)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(A + (int64_t)rowA[i] * lda + k + (((lane & 7) ^ swz<SWZ>((wave * LA + i) * 8 + lrow)) * 8)),
+                                       (__attribute__((address_space(3))) void*)(a + i * 8 * BK), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < LB; i++)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(B + (int64_t)rowB[i] * ldb + k + (((lane & 7) ^ swz<SWZ>((wave * LB + i) * 8 + lrow)) * 8)),
+                                       (__attribute__((address_space(3))) void*)(b + i * 8 * BK), 16, 0, 0);
+  };
+
+  // reader: row = base + l%32, logical chunk 2*ks + l/32 lives at chunk (2*ks + l/32) ^ (row & 7)
+  const int x7 = swz<SWZ>(lane & 31), hh = lane >> 5;
+  int coff[BK / 16];
+#pragma unroll
+  for (int ks = 0; ks < BK / 16; ks++) coff[ks] = ((2 * ks + hh) ^ x7) * 8;
+
+  // L2 warm-up: every tile step needs data nobody has asked for yet, so its latency is the
+  // fabric's; one 4-byte load per 128-byte line of the tile PF steps ahead makes the real tile
+  // loads hit in L2.  The load is issued through inline asm so that no wait is attached to it; its
+  // destination register is tied in and out of the asm, which keeps it reserved while loads are in
+  // flight, and it is only waited for after the loop.
+  unsigned pf_reg = 0;
+  auto warm = [&](int it) {
+    const bool first = it < nt0;
+    const bf16_t* A = (const bf16_t*)(first ? p.seg[0].A : p.seg[1].A);
+    const bf16_t* B = (const bf16_t*)(first ? p.seg[0].B : p.seg[1].B);
+    const int64_t lda = first ? p.seg[0].lda : p.seg[1].lda, ldb = first ? p.seg[0].ldb : p.seg[1].ldb;
+    const int k = (first ? kr0.beg + it : kr1.beg + it - nt0) * BK;
+    const int r = tid % BM;                              // thread -> one row of A, then one row of B
+    const bf16_t* ptr = (tid < BM) ? A + (int64_t)min(row0 + r, p.M - 1) * lda + k
+                                   : B + (int64_t)min(col0 + (tid - BM) % BN, p.N - 1) * ldb + k;
+    asm volatile("global_load_dword %0, %1, off" : "+v"(pf_reg) : "v"(ptr) : "memory");
+  };
+
+  if (nt > 0) fetch(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0f70);                    // vmcnt(0): the first tile has landed
+  __syncthreads();
+  for (int it = 0; it < nt; it++) {
+    const int buf = it & 1;
+    if constexpr (PF > 0) {
+      // fixed instruction pattern per step (the last steps re-request tiles already seen), so that
+      // the wait counts are static: 8 tile loads, then one warm-up load that may stay in flight
+      fetch(min(it + 1, nt - 1), buf ^ 1);
+      warm(min(it + PF, nt - 1));
+    } else {
+      if (it + 1 < nt) fetch(it + 1, buf ^ 1);
+    }
+    const bf16_t* a = sA + buf * BM * BK + (wm * TM * 32 + (lane & 31)) * BK;
+    const bf16_t* b = sB + buf * BN * BK + (wn * TN * 32 + (lane & 31)) * BK;
+    if constexpr (DB) {
+      bf16x8 af[2][TM], bfr[2][TN];
+#pragma unroll
+      for (int i = 0; i < TM; i++) af[0][i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * BK + coff[0]);
+#pragma unroll
+      for (int j = 0; j < TN; j++) bfr[0][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * BK + coff[0]);
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ks++) {
+        const int cur = ks & 1, nxt = cur ^ 1;
+        if (ks + 1 < BK / 16) {
+#pragma unroll
+          for (int i = 0; i < TM; i++) af[nxt][i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * BK + coff[ks + 1]);
+#pragma unroll
+          for (int j = 0; j < TN; j++) bfr[nxt][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * BK + coff[ks + 1]);
+        }
+#pragma unroll
+        for (int i = 0; i < TM; i++)
+#pragma unroll
+          for (int j = 0; j < TN; j++)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+        // ask the scheduler to keep this order: one LDS read of the next step between MFMAs of this one
+        if (ks + 1 < BK / 16) {
+#pragma unroll
+          for (int r = 0; r < TM + TN; r++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+        } else {
+          __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
         }
       }
-  };
-  if (p.splitk > 1) {
-    float* part = p.partial + (int64_t)z * p.M * p.N;
-    each([&](int r, int c, float v) { part[(int64_t)r * p.N + c] = v; });
-  } else if (p.c_f32) {
-    float* C = (float*)p.C; const float alpha = p.alpha; const bf16_t* R = (const bf16_t*)p.R;
-    if (p.accumulate || R)
-      each([&](int r, int c, float v) {
-        float* q = C + (int64_t)r * p.ldc + c;
-        float x = alpha * v + (R ? (float)R[(int64_t)r * p.ldr + c] : 0.f);
-        *q = p.accumulate ? *q + x : x;
-      });
-    else each([&](int r, int c, float v) { C[(int64_t)r * p.ldc + c] = alpha * v; });
-  } else if (p.R) {
-    bf16_t* C = (bf16_t*)p.C; const bf16_t* R = (const bf16_t*)p.R; const float alpha = p.alpha;
-    each([&](int r, int c, float v) { C[(int64_t)r * p.ldc + c] = (bf16_t)(alpha * v + (float)R[(int64_t)r * p.ldr + c]); });
-  } else {
-    bf16_t* C = (bf16_t*)p.C; const float alpha = p.alpha;
-    each([&](int r, int c, float v) { C[(int64_t)r * p.ldc + c] = (bf16_t)(alpha * v); });
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ks++) {
+        bf16x8 af[TM], bfr[TN];
+#pragma unroll
+        for (int i = 0; i < TM; i++) af[i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * BK + coff[ks]);
+#pragma unroll
+        for (int j = 0; j < TN; j++) bfr[j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * BK + coff[ks]);
+#pragma unroll
+        for (int i = 0; i < TM; i++)
+#pragma unroll
+          for (int j = 0; j < TN; j++)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      }
+    }
+    // plain s_barrier: __syncthreads() would add a fence that waits for every outstanding load,
+    // the warm-up one included.  The tile loads are waited for explicitly; nothing else is shared.
+    if constexpr (PF > 0) { __builtin_amdgcn_s_waitcnt(0x0f71); __builtin_amdgcn_s_barrier(); }   // vmcnt(1)
+    else { __builtin_amdgcn_s_waitcnt(0x0f70); __syncthreads(); }                                 // vmcnt(0)
   }
+  if constexpr (PF > 0) {
+    __builtin_amdgcn_s_waitcnt(0x0f70);                  // the last warm-up load must land before its register is reused
+    asm volatile("" : "+v"(pf_reg));
+  }
+  gemm_epilogue<TM, TN>(p, acc, M, z, row0, col0, row0 + wm * TM * 32 + 4 * (lane >> 5), col0 + wn * TN * 32 + (lane & 31),
+                        (row0 + BM <= M) && (col0 + BN <= p.N));
+}
+
+template <int BM, int BN, int WM, int WN, bool DB, int SWZ, int PF = 0>
+static int launch_dlds_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_t st) {
+  size_t smem = (size_t)2 * (BM + BN) * 64 * sizeof(bf16_t);
+  auto k0 = gemm_mfma_dlds_kernel<BM, BN, WM, WN, DB, SWZ, PF>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(k0), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    attr_set = true;
+  }
+  int tm = (int)cdiv(p.M, BM), tn = (int)cdiv(p.N, BN);
+  dim3 grid(tm * tn, p.splitk > 1 ? p.splitk : 1);
+  k0<<<grid, WM * WN * 64, smem, st>>>(p, m_off, tm, tn);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
 }
 
 template <int BM, int BN, int WM, int WN>
@@ -261,13 +461,14 @@ static bool mfma_ok(const GemmParams& p) {
   return true;
 }
 
-// Tile configuration of the MFMA kernel: 0 = 256x256 (8 waves, 128x64 each), 1 = 256x64, 2 = 64x256,
-// 3 = 128x128, 4 = 256x256 with 4 waves of 128x128, 5 = 256x128 (4 waves of 128x64), 6 = 128x256.
+// Tile configuration of the MFMA kernels.  Register-staged: 0 = 256x256 (8 waves, 128x64 each), 1 = 256x64,
+// 2 = 64x256, 3 = 128x128, 4 = 256x256 with 4 waves of 128x128, 5 = 256x128, 6 = 128x256.  Direct-to-LDS 256x256
+// with 8 waves: 7, 8, 9 = chunk swizzle 0, 1, 2; 10, 11, 12 = swizzle 1 plus an L2 warm-up load 2, 3, 4 steps ahead.
 static int pick_cfg(const GemmParams& p) {
   if (p.N <= 128 && p.M > 128) return 1;
   if (p.M <= 128) return 2;
   if ((int64_t)cdiv(p.M, 256) * cdiv(p.N, 256) * p.splitk < 128) return 3;
-  return 0;
+  return 8;                                              // direct-to-LDS tiles when K allows, else staged (0)
 }
 
 // m_dev semantics: the live row count is *m_dev - m_off (clamped to [0, M]).
@@ -279,12 +480,13 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
   if (p.splitk < 1) p.splitk = 1;
   if (p.splitk > 1 && !p.partial) return as_fail(ctx, AS_ERR_WORKSPACE, "gemm: split-K needs a partial buffer");
   if (p.accumulate && !p.c_f32) return as_fail(ctx, AS_ERR_SHAPE, "gemm: accumulate needs float output");
-  if (variant < 0 || (variant > 2 && (variant < 10 || variant > 16))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
+  if (variant < 0 || (variant > 2 && (variant < 10 || variant > 22))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
   bool use_mfma = (mode == AS_BF16) && variant != 1 && mfma_ok(p);
   if (variant >= 2 && !use_mfma) return as_fail(ctx, AS_ERR_SHAPE, "gemm: MFMA kernel needs bf16 and 8-element alignment");
   int rc = AS_OK;
   double ksum = 0; for (int s = 0; s < p.nseg; s++) ksum += p.seg[s].K;
-  const int cfg = variant >= 10 ? variant - 10 : pick_cfg(p);
+  int cfg = variant >= 10 ? variant - 10 : pick_cfg(p);
+  if (cfg >= 7) for (int s = 0; s < p.nseg; s++) if (p.seg[s].K % 64) cfg = 0;     // direct-to-LDS tiles need whole 64-wide K steps
   const bool big = use_mfma && (cfg == 0 || cfg >= 4);
   prof_begin(ctx, st, p.m_dev ? AS_K_GEMM_DEVROWS : !use_mfma ? AS_K_GEMM_FMA : big ? AS_K_GEMM_MFMA_256 : AS_K_GEMM_MFMA_SKINNY,
              p.m_dev ? 0.0 : 2.0 * p.M * p.N * ksum);
@@ -296,6 +498,12 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
       case 4: rc = launch_mfma_cfg<256, 256, 2, 2>(ctx, p, m_off, st); break;
       case 5: rc = launch_mfma_cfg<256, 128, 2, 2>(ctx, p, m_off, st); break;
       case 6: rc = launch_mfma_cfg<128, 256, 2, 2>(ctx, p, m_off, st); break;
+      case 7: rc = launch_dlds_cfg<256, 256, 2, 4, true, 0>(ctx, p, m_off, st); break;
+      case 8: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1>(ctx, p, m_off, st); break;
+      case 9: rc = launch_dlds_cfg<256, 256, 2, 4, true, 2>(ctx, p, m_off, st); break;
+      case 10: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 2>(ctx, p, m_off, st); break;
+      case 11: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 3>(ctx, p, m_off, st); break;
+      case 12: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 4>(ctx, p, m_off, st); break;
       default: rc = launch_mfma_cfg<256, 256, 2, 4>(ctx, p, m_off, st); break;
     }
   } else {
@@ -315,4 +523,33 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
 
 int launch_gemm(as_ctx* ctx, int mode, int variant, const GemmParams& p, hipStream_t st) {
   return launch_gemm_off(ctx, mode, variant, p, 0, st);
+}
+
+// ------------------------------------------------- matrix-core peak probe
+// Register-resident MFMA loop: no memory traffic at all, eight independent accumulators per
+// wavefront, two wavefronts per SIMD.  What this sustains is the ceiling any GEMM on the chip can
+// reach at the clocks the part holds under matrix load.
+__global__ __launch_bounds__(512) void mfma_peak_kernel(int iters, float* sink) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int j = 0; j < 8; j++) { a[j] = (bf16_t)(0.001f * (threadIdx.x + j)); b[j] = (bf16_t)(0.002f * (threadIdx.x - j)); }
+  f32x16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; i++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) acc[i][e] = 0.f;
+  for (int it = 0; it < iters; it++) {
+#pragma unroll
+    for (int i = 0; i < 8; i++) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; i++) s += acc[i][0] + acc[i][15];
+  if (s == 123.456f) sink[0] = s;          // never true; keeps the loop alive
+}
+
+int launch_mfma_peak(as_ctx* ctx, int iters, int blocks, float* sink, hipStream_t st) {
+  mfma_peak_kernel<<<blocks, 512, 0, st>>>(iters, sink);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
 }

@@ -180,7 +180,8 @@ def main():
 
     def step():
         nonlocal out
-        out = ctx.train_step(model, pk["tokens"], pk["cu_seqlens"], hcu, pk["loss_mask"], sh.rows, sh.row_len, ws, out)
+        out = ctx.train_step(model, pk["tokens"], pk["cu_seqlens"], hcu, pk["loss_mask"], sh.rows, sh.row_len, ws, out,
+                             seg_skip=pk["seg_skip"])
 
     for _ in range(args.warmup):
         step()

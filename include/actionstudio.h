@@ -179,13 +179,16 @@ int as_probe_mfma_peak(as_ctx* ctx, int32_t iters, int32_t blocks, float* d_sink
  * turn), d_cu_seqlens [device] int32 with room for n_traj + max_rows + 1
  * entries: boundaries of all segments of the flat stream, every trajectory
  * and every non-empty pad tail being one segment.  The three counters are
- * [host].  Token ids are checked against the context's vocab. */
+ * [host].  h_seg_skip_out [host] uint8 with room for n_traj + max_rows
+ * entries, or NULL: 1 for segments that hold no loss-bearing token (pad
+ * tails, trajectories without a kept assistant token), for as_train_step.
+ * Token ids are checked against the context's vocab. */
 int as_pack(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* turn_offsets,
             const uint8_t* turn_roles, const int32_t* traj_offsets, int32_t n_traj,
             int32_t row_len, int32_t max_rows, int32_t pad_id, int32_t truncate,
             int32_t* d_tokens, int32_t* d_cu_seqlens, uint8_t* d_loss_mask,
             int32_t* n_rows_out, int32_t* n_segments_out, int32_t* n_traj_consumed_out,
-            void* stream);
+            uint8_t* h_seg_skip_out, void* stream);
 
 /* ---- one training step (Sections 3.2.2, 4.5) ---------------------------- */
 
@@ -198,12 +201,17 @@ int as_pack(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* turn_offsets
  *  h_cu_seqlens [host] copy of the segment table, checked before launch
  *               (starts at 0, strictly increasing, ends at n_rows*row_len, no
  *               segment crossing a row end) -- AS_ERR_CU_SEQLENS otherwise.
+ *  h_seg_skip   [host] uint8 [n_segments] or NULL.  A 1 is the caller's
+ *               statement that the segment holds no loss-bearing token (as
+ *               as_pack reports it); such a segment cannot influence the loss
+ *               or any gradient and is left out of the computation.  Marking
+ *               a segment that does hold mask bits drops its loss terms.
  *  d_loss, d_loss_sum [device] float[1]; d_count [device] int32[1].
  *  lora NULL in full mode.  Gradients are overwritten.  With no target at
  *  all, the loss and every gradient are exactly zero. */
 int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lora* lora,
                   const int32_t* d_tokens, const int32_t* d_cu_seqlens,
-                  const int32_t* h_cu_seqlens, int32_t n_segments,
+                  const int32_t* h_cu_seqlens, int32_t n_segments, const uint8_t* h_seg_skip,
                   const uint8_t* d_loss_mask, int32_t n_rows, int32_t row_len,
                   float* d_loss, float* d_loss_sum, int32_t* d_count,
                   const as_grads* grads, void* d_workspace, size_t workspace_bytes,

@@ -70,8 +70,8 @@ lib.as_last_error.argtypes = [_vp]
 lib.as_last_error.restype = C.c_char_p
 lib.as_workspace_bytes.argtypes = [_vp, _i64, _i64, C.POINTER(C.c_size_t)]
 lib.as_pack.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp,
-                        C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32), _vp]
-lib.as_train_step.argtypes = [_vp, C.POINTER(Weights), C.POINTER(Lora), _vp, _vp, _vp, _i32, _vp, _i32, _i32,
+                        C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32), _vp, _vp]
+lib.as_train_step.argtypes = [_vp, C.POINTER(Weights), C.POINTER(Lora), _vp, _vp, _vp, _i32, _vp, _vp, _i32, _i32,
                               _vp, _vp, _vp, C.POINTER(Grads), _vp, C.c_size_t, _vp]
 lib.as_adamw_update.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _f32, _f32, _f32, _f32, _f32, _vp]
 lib.as_op_gemm.argtypes = [_vp, C.c_int, C.c_int, _i64, _i64, _vp, _i64, _vp, _i64, _i64, _vp, _i64, _vp, _i64, _i64,
@@ -193,16 +193,18 @@ class Context:
                        torch.empty(n_out, dtype=torch.uint8, device=dev))
         tok, cu, msk = outputs
         nr, ns, nc = _i32(), _i32(), _i32()
+        skip = np.zeros(max(1, n_traj + max(max_rows, 0)), dtype=np.uint8)
         hp = lambda a: a.ctypes.data_as(C.c_void_p) if a.size else None
         self.check(lib.as_pack(self.handle, hp(tt), hp(to), hp(tr), hp(jo), n_traj, row_len, max_rows, pad_id,
                                int(truncate), _ptr(tok), _ptr(cu), _ptr(msk), C.byref(nr), C.byref(ns), C.byref(nc),
-                               _stream() if tok is not None and tok.is_cuda else None))
+                               hp(skip), _stream() if tok is not None and tok.is_cuda else None))
         n = nr.value * row_len
         return dict(tokens=tok[:n], cu_seqlens=cu[:ns.value + 1], loss_mask=msk[:n], n_rows=nr.value,
-                    n_segments=ns.value, n_traj_consumed=nc.value)
+                    n_segments=ns.value, n_traj_consumed=nc.value, seg_skip=skip[:ns.value].copy())
 
     # ----------------------------------------------------------- train step
-    def train_step(self, model, tokens, cu_seqlens, h_cu_seqlens, loss_mask, n_rows, row_len, workspace, out=None):
+    def train_step(self, model, tokens, cu_seqlens, h_cu_seqlens, loss_mask, n_rows, row_len, workspace, out=None,
+                   seg_skip=None):
         """model: DeviceModel.  Returns dict of device scalars (loss, loss_sum, count)."""
         dev = tokens.device
         if out is None:
@@ -210,10 +212,14 @@ class Context:
                        loss_sum=torch.zeros(1, dtype=torch.float32, device=dev),
                        count=torch.zeros(1, dtype=torch.int32, device=dev))
         hcu = np.ascontiguousarray(h_cu_seqlens, dtype=np.int32)
+        hskip = None
+        if seg_skip is not None:
+            hskip = np.ascontiguousarray(seg_skip, dtype=np.uint8)
+            assert len(hskip) == len(hcu) - 1
         self.check(lib.as_train_step(self.handle, C.byref(model.c_weights),
                                      C.byref(model.c_lora) if model.c_lora is not None else None,
                                      _ptr(tokens), _ptr(cu_seqlens), hcu.ctypes.data_as(C.c_void_p), len(hcu) - 1,
-                                     _ptr(loss_mask), n_rows, row_len, _ptr(out["loss"]), _ptr(out["loss_sum"]),
+                                     hskip.ctypes.data_as(C.c_void_p) if hskip is not None else None, _ptr(loss_mask), n_rows, row_len, _ptr(out["loss"]), _ptr(out["loss_sum"]),
                                      _ptr(out["count"]), C.byref(model.c_grads), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _stream()))
         return out

@@ -118,6 +118,9 @@ extern "C" int as_probe_mfma_peak(as_ctx* ctx, int32_t iters, int32_t blocks, fl
 extern "C" void as_destroy(as_ctx* ctx) {
   if (!ctx) return;
   for (auto& r : ctx->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  if (ctx->step_ev) { (void)hipEventSynchronize(ctx->step_ev); (void)hipEventDestroy(ctx->step_ev); }
+  if (ctx->d_step) (void)hipFree(ctx->d_step);
+  if (ctx->h_step) (void)hipHostFree(ctx->h_step);
   if (ctx->d_stage) (void)hipFree(ctx->d_stage);
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
   delete ctx;
@@ -151,15 +154,15 @@ static int ensure_stage(as_ctx* ctx, size_t bytes) {
 static int pack_plan(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* turn_offsets,
                      const uint8_t* turn_roles, const int32_t* traj_offsets, int32_t n_traj,
                      int32_t T, int32_t max_rows, int32_t truncate, std::vector<Piece>& pieces,
-                     std::vector<int32_t>& cu, int32_t* n_rows, int32_t* n_consumed) {
+                     std::vector<int32_t>& cu, std::vector<uint8_t>& skip, int32_t* n_rows, int32_t* n_consumed) {
   const int vocab = ctx->cfg.vocab;
   if (T <= 0 || max_rows < 0 || n_traj < 0) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: row_len must be positive, counts non-negative");
   if ((int64_t)T * max_rows > INT32_MAX) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: max_rows*row_len exceeds int32");
   if (traj_offsets[0] != 0 || turn_offsets[0] != 0) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: offsets must start at 0");
-  pieces.clear(); cu.clear(); cu.push_back(0);
+  pieces.clear(); cu.clear(); cu.push_back(0); skip.clear();
   int32_t fill = 0, rows = 0, consumed = 0; bool open = false;
   auto close_row = [&]() {
-    if (fill < T) { pieces.push_back({rows * T + fill, -1, 0}); cu.push_back((rows + 1) * T); }
+    if (fill < T) { pieces.push_back({rows * T + fill, -1, 0}); cu.push_back((rows + 1) * T); skip.push_back(1); }
     rows++; fill = 0; open = false;
   };
   for (int32_t i = 0; i < n_traj && rows < max_rows; i++) {
@@ -181,14 +184,15 @@ static int pack_plan(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* tur
     }
     if (open && fill + L > T) { close_row(); if (rows >= max_rows) break; }
     open = true;
-    int32_t left = (int32_t)L;
+    int32_t left = (int32_t)L; bool any_loss = false;
     for (int32_t t = t0; t < t1 && left > 0; t++) {
       int32_t len = std::min(turn_offsets[t + 1] - turn_offsets[t], left);
       if (len <= 0) continue;
       pieces.push_back({rows * T + fill, turn_offsets[t], (uint8_t)(turn_roles[t] == AS_ROLE_ASSISTANT)});
+      any_loss = any_loss || turn_roles[t] == AS_ROLE_ASSISTANT;
       fill += len; left -= len;
     }
-    cu.push_back(rows * T + fill);
+    cu.push_back(rows * T + fill); skip.push_back(any_loss ? 0 : 1);
     consumed++;
     if (fill == T) { rows++; fill = 0; open = false; }
   }
@@ -202,7 +206,7 @@ extern "C" int as_pack(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* t
                        int32_t row_len, int32_t max_rows, int32_t pad_id, int32_t truncate,
                        int32_t* d_tokens, int32_t* d_cu_seqlens, uint8_t* d_loss_mask,
                        int32_t* n_rows_out, int32_t* n_segments_out, int32_t* n_traj_consumed_out,
-                       void* stream) {
+                       uint8_t* h_seg_skip_out, void* stream) {
   if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_pack: NULL context");
   if (!turn_offsets || !traj_offsets || !n_rows_out || !n_segments_out || !n_traj_consumed_out)
     return as_fail(ctx, AS_ERR_NULL, "as_pack: NULL offsets or counters");
@@ -210,10 +214,10 @@ extern "C" int as_pack(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* t
     return as_fail(ctx, AS_ERR_NULL, "as_pack: NULL turn arrays");
   if (!d_cu_seqlens || (max_rows > 0 && row_len > 0 && (!d_tokens || !d_loss_mask)))
     return as_fail(ctx, AS_ERR_NULL, "as_pack: NULL output");
-  std::vector<Piece> pieces; std::vector<int32_t> cu;
+  std::vector<Piece> pieces; std::vector<int32_t> cu; std::vector<uint8_t> skip;
   int32_t rows = 0, consumed = 0;
   int rc = pack_plan(ctx, turn_tokens, turn_offsets, turn_roles, traj_offsets, n_traj, row_len, max_rows,
-                     truncate, pieces, cu, &rows, &consumed);
+                     truncate, pieces, cu, skip, &rows, &consumed);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
   AS_HIP(ctx, hipSetDevice(ctx->device));
@@ -242,6 +246,7 @@ extern "C" int as_pack(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* t
   }
   AS_HIP(ctx, hipStreamSynchronize(st));       // the staging buffer is free again
   *n_rows_out = rows; *n_segments_out = (int32_t)cu.size() - 1; *n_traj_consumed_out = consumed;
+  if (h_seg_skip_out && !skip.empty()) memcpy(h_seg_skip_out, skip.data(), skip.size());
   return AS_OK;
 }
 
@@ -273,9 +278,10 @@ struct Acts {           // activations of one layer kept for its backward
 };
 
 struct Plan {
-  int N, d, D, Dkv, QKV, F, V, L, rp, es, Mc;
+  int N, Np, d, D, Dkv, QKV, F, V, L, rp, es, Mc;   // Np: token count rounded up to 64 (row length of token-major transposes)
   int n_qkv, n_gu;                       // adapters inside the q/k/v and gate/up groups
   int32_t *seg_start, *seg_end, *tgt_idx, *tgt_pos, *labels, *count, *iscratch;
+  int32_t *tok_c; uint8_t* mask_c;       // tokens and mask with the skipped segments squeezed out
   float *rope_cos, *rope_sin, *loss_rows, *rstd_f, *logits, *delta, *partial, *gpart;
   std::vector<void*> h;                  // L+1 residual-stream snapshots
   std::vector<Acts> acts;
@@ -316,6 +322,7 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   P.es = c.mode == AS_FP32 ? 4 : 2;
   P.rp = full ? 0 : (c.mode == AS_BF16 ? (int)cdiv(c.lora_rank, 64) * 64 : (int)cdiv(c.lora_rank, 16) * 16);   // whole 64-wide K steps for the MFMA tiles
   P.Mc = (int)std::min<int64_t>(4096, cdiv(std::max(P.N, 1), 64) * 64);
+  P.Np = (int)cdiv(P.N, 64) * 64;
   const size_t N = (size_t)P.N, es = (size_t)P.es;
   auto on = [&](int t) { return !full && ((c.lora_targets >> t) & 1u); };
   P.n_qkv = on(AS_T_Q) + on(AS_T_K) + on(AS_T_V);
@@ -325,6 +332,7 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   P.seg_start = (int32_t*)w.take(N * 4); P.seg_end = (int32_t*)w.take(N * 4);
   P.tgt_idx = (int32_t*)w.take(N * 4); P.tgt_pos = (int32_t*)w.take(N * 4); P.labels = (int32_t*)w.take(N * 4);
   P.count = (int32_t*)w.take(256);
+  P.tok_c = (int32_t*)w.take(N * 4); P.mask_c = (uint8_t*)w.take(N);
   P.iscratch = (int32_t*)w.take(full ? 2 * N * 4 : 0);
   P.rope_cos = (float*)w.take((size_t)row_len * (c.head_dim / 2) * 4);
   P.rope_sin = (float*)w.take((size_t)row_len * (c.head_dim / 2) * 4);
@@ -368,10 +376,11 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   const bool need_T = full || (c.lora_targets & 0x7f);
   size_t xmax = std::max({(size_t)P.d, (size_t)P.D, (size_t)P.F});
   size_t ymax = std::max({(size_t)P.QKV, (size_t)2 * P.F, (size_t)P.d});
-  P.xT = w.take(need_T ? xmax * N * es : 0);
-  P.dyT = w.take(need_T ? ymax * N * es : 0);
+  const size_t Np = (size_t)P.Np;
+  P.xT = w.take(need_T ? xmax * Np * es : 0);
+  P.dyT = w.take(need_T ? ymax * Np * es : 0);
   size_t umax = (size_t)std::max({P.n_qkv, P.n_gu, 1}) * rp;
-  P.uT = w.take(umax * N * es); P.duT = w.take(umax * N * es);
+  P.uT = w.take(umax * Np * es); P.duT = w.take(umax * Np * es);
   P.gpart = (float*)w.take(full ? (size_t)256 * P.d * 4 : 0);
 
   // prepared adapter copies
@@ -511,8 +520,39 @@ struct Step {
     return launch_swiglu_fwd(ctx, mode, P.N, P.F, a.gu, a.m, st);
   }
 
+  // nothing to compute: loss, count and every gradient are exactly zero
+  int zero_outputs(float* d_loss, float* d_loss_sum, int32_t* d_count) {
+    int rc;
+    if ((rc = launch_fill_zero(ctx, d_loss, 4, st)) || (rc = launch_fill_zero(ctx, d_loss_sum, 4, st)) || (rc = launch_fill_zero(ctx, d_count, 4, st))) return rc;
+    const size_t d = P.d, D = P.D, Dkv = P.Dkv, F = P.F;
+    for (int l = 0; l < P.L; l++) {
+      if (c.train_mode == AS_LORA) {
+        for (int t = 0; t < 7; t++) {
+          if (!((c.lora_targets >> t) & 1u)) continue;
+          int din, dout; target_dims(c, t, &din, &dout);
+          if ((rc = launch_fill_zero(ctx, G->lora_layers[l].a[t], (size_t)c.lora_rank * din * 4, st))) return rc;
+          if ((rc = launch_fill_zero(ctx, G->lora_layers[l].b[t], (size_t)dout * c.lora_rank * 4, st))) return rc;
+        }
+      } else {
+        const as_layer_weight_grads& g = G->w_layers[l];
+        float* ptr[9] = {g.g1, g.wq, g.wk, g.wv, g.wo, g.g2, g.wgate, g.wup, g.wdown};
+        size_t cnt[9] = {d, D * d, Dkv * d, Dkv * d, d * D, d, F * d, F * d, d * F};
+        for (int i = 0; i < 9; i++) if ((rc = launch_fill_zero(ctx, ptr[i], cnt[i] * 4, st))) return rc;
+      }
+    }
+    if (c.train_mode == AS_FULL) {
+      if ((rc = launch_fill_zero(ctx, G->embed, (size_t)P.V * d * 4, st)) || (rc = launch_fill_zero(ctx, G->head, (size_t)P.V * d * 4, st)) ||
+          (rc = launch_fill_zero(ctx, G->g_final, d * 4, st))) return rc;
+    }
+    return AS_OK;
+  }
+
   int transpose(int rows, int cols, const void* in, int64_t ldi, void* out, int64_t ldo) {
-    return launch_transpose(ctx, mode, rows, cols, in, ldi, out, ldo, nullptr, 0, st);
+    return launch_transpose(ctx, mode, rows, rows, cols, in, ldi, out, ldo, nullptr, 0, st);
+  }
+  // [N tokens, cols] -> [cols, Np]: token-major copy whose rows are padded with zeros to Np
+  int transpose_tok(int cols, const void* in, int64_t ldi, void* out) {
+    return launch_transpose(ctx, mode, P.N, P.Np, cols, in, ldi, out, P.Np, nullptr, 0, st);
   }
 
   // adapter gradients of one projection: dB = s dy^T u, dA = du^T x.
@@ -520,7 +560,7 @@ struct Step {
   int lora_grads(int l, int t, const void* dyT_rows, const void* xT) {
     LoraSlot& s = slot(l, t);
     if (!s.on) return AS_OK;
-    const int N = P.N, r = c.lora_rank, rp = P.rp;
+    const int N = P.Np, r = c.lora_rank, rp = P.rp;        // token-major operands: rows of Np tokens, zero past the live ones
     const float sc = c.lora_alpha / (float)c.lora_rank;
     const as_layer_lora_grads& g = G->lora_layers[l];
     int rc = gemm(s.dout, r, dyT_rows, N, off(P.uT, (size_t)s.slot * rp * N), N, N, nullptr, 0, nullptr, 0, 0, nullptr, 0,
@@ -530,7 +570,7 @@ struct Step {
                 g.a[t], s.din, 1, 1.f, 0, nullptr, 0, true);
   }
   int weight_grad(float* dW, int dout, int din, const void* dyT_rows, const void* xT) {
-    const int N = P.N;
+    const int N = P.Np;
     return gemm(dout, din, dyT_rows, N, xT, N, N, nullptr, 0, nullptr, 0, 0, nullptr, 0, dW, din, 1);
   }
 
@@ -546,12 +586,12 @@ struct Step {
       if (s.on && (rc = gemm(N, rp, P.dh, d, s.Bst, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.du_d, rp))) return rc;
       if ((rc = gemm(N, F, P.dh, d, P.wT, d, d, s.on ? P.du_d : nullptr, rp, s.At, rp, s.on ? rp : 0, nullptr, 0, P.dm, F))) return rc;
       if (s.on || full) {
-        if ((rc = transpose(N, d, P.dh, d, P.dyT, N))) return rc;
-        if ((rc = transpose(N, F, a.m, F, P.xT, N))) return rc;
+        if ((rc = transpose_tok(d, P.dh, d, P.dyT))) return rc;
+        if ((rc = transpose_tok(F, a.m, F, P.xT))) return rc;
       }
       if (s.on) {
-        if ((rc = transpose(N, rp, a.u_d, rp, P.uT, N))) return rc;
-        if ((rc = transpose(N, rp, P.du_d, rp, P.duT, N))) return rc;
+        if ((rc = transpose_tok(rp, a.u_d, rp, P.uT))) return rc;
+        if ((rc = transpose_tok(rp, P.du_d, rp, P.duT))) return rc;
         if ((rc = lora_grads(l, AS_T_DOWN, P.dyT, P.xT))) return rc;
       }
       if (full && (rc = weight_grad(G->w_layers[l].wdown, d, F, P.dyT, P.xT))) return rc; }
@@ -569,17 +609,17 @@ struct Step {
       if ((rc = gemm(N, d, P.dgu, 2 * F, P.wT, 2 * F, 2 * F, P.n_gu ? P.du_gu : nullptr, ldg, P.At_gu[l], ldg, ldg,
                      nullptr, 0, P.db, d))) return rc;
       if (P.n_gu || full) {
-        if ((rc = transpose(N, 2 * F, P.dgu, 2 * F, P.dyT, N))) return rc;
-        if ((rc = transpose(N, d, a.b, d, P.xT, N))) return rc;
+        if ((rc = transpose_tok(2 * F, P.dgu, 2 * F, P.dyT))) return rc;
+        if ((rc = transpose_tok(d, a.b, d, P.xT))) return rc;
       }
       if (P.n_gu) {
-        if ((rc = transpose(N, ldg, a.u_gu, ldg, P.uT, N))) return rc;
-        if ((rc = transpose(N, ldg, P.du_gu, ldg, P.duT, N))) return rc;
-        for (int i = 0; i < 2; i++) if ((rc = lora_grads(l, AS_T_GATE + i, off(P.dyT, (size_t)i * F * N), P.xT))) return rc;
+        if ((rc = transpose_tok(ldg, a.u_gu, ldg, P.uT))) return rc;
+        if ((rc = transpose_tok(ldg, P.du_gu, ldg, P.duT))) return rc;
+        for (int i = 0; i < 2; i++) if ((rc = lora_grads(l, AS_T_GATE + i, off(P.dyT, (size_t)i * F * P.Np), P.xT))) return rc;
       }
       if (full) {
         if ((rc = weight_grad(G->w_layers[l].wgate, F, d, P.dyT, P.xT))) return rc;
-        if ((rc = weight_grad(G->w_layers[l].wup, F, d, off(P.dyT, (size_t)F * N), P.xT))) return rc;
+        if ((rc = weight_grad(G->w_layers[l].wup, F, d, off(P.dyT, (size_t)F * P.Np), P.xT))) return rc;
       } }
     // ---- second norm
     if (full && (rc = launch_rmsnorm_dgain(ctx, mode, N, d, P.db, nullptr, a.h_mid, a.rstd2, P.gpart, 256, G->w_layers[l].g2, st))) return rc;
@@ -590,12 +630,12 @@ struct Step {
       if (s.on && (rc = gemm(N, rp, P.dh2, d, s.Bst, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.du_o, rp))) return rc;
       if ((rc = gemm(N, D, P.dh2, d, P.wT, d, d, s.on ? P.du_o : nullptr, rp, s.At, rp, s.on ? rp : 0, nullptr, 0, P.d_o, D))) return rc;
       if (s.on || full) {
-        if ((rc = transpose(N, d, P.dh2, d, P.dyT, N))) return rc;
-        if ((rc = transpose(N, D, a.o, D, P.xT, N))) return rc;
+        if ((rc = transpose_tok(d, P.dh2, d, P.dyT))) return rc;
+        if ((rc = transpose_tok(D, a.o, D, P.xT))) return rc;
       }
       if (s.on) {
-        if ((rc = transpose(N, rp, a.u_o, rp, P.uT, N))) return rc;
-        if ((rc = transpose(N, rp, P.du_o, rp, P.duT, N))) return rc;
+        if ((rc = transpose_tok(rp, a.u_o, rp, P.uT))) return rc;
+        if ((rc = transpose_tok(rp, P.du_o, rp, P.duT))) return rc;
         if ((rc = lora_grads(l, AS_T_O, P.dyT, P.xT))) return rc;
       }
       if (full && (rc = weight_grad(G->w_layers[l].wo, d, D, P.dyT, P.xT))) return rc; }
@@ -618,17 +658,17 @@ struct Step {
       if ((rc = gemm(N, d, P.dqkv, QKV, P.wT, QKV, QKV, P.n_qkv ? P.du_qkv : nullptr, ldu, P.At_qkv[l], ldu, ldu,
                      nullptr, 0, P.da, d))) return rc;
       if (P.n_qkv || full) {
-        if ((rc = transpose(N, QKV, P.dqkv, QKV, P.dyT, N))) return rc;
-        if ((rc = transpose(N, d, a.a, d, P.xT, N))) return rc;
+        if ((rc = transpose_tok(QKV, P.dqkv, QKV, P.dyT))) return rc;
+        if ((rc = transpose_tok(d, a.a, d, P.xT))) return rc;
       }
       if (P.n_qkv) {
-        if ((rc = transpose(N, ldu, a.u_qkv, ldu, P.uT, N))) return rc;
-        if ((rc = transpose(N, ldu, P.du_qkv, ldu, P.duT, N))) return rc;
-        for (int i = 0; i < 3; i++) if ((rc = lora_grads(l, i, off(P.dyT, (size_t)coff[i] * N), P.xT))) return rc;
+        if ((rc = transpose_tok(ldu, a.u_qkv, ldu, P.uT))) return rc;
+        if ((rc = transpose_tok(ldu, P.du_qkv, ldu, P.duT))) return rc;
+        for (int i = 0; i < 3; i++) if ((rc = lora_grads(l, i, off(P.dyT, (size_t)coff[i] * P.Np), P.xT))) return rc;
       }
       if (full) {
         float* gw[3] = {G->w_layers[l].wq, G->w_layers[l].wk, G->w_layers[l].wv};
-        for (int i = 0; i < 3; i++) if ((rc = weight_grad(gw[i], nout[i], d, off(P.dyT, (size_t)coff[i] * N), P.xT))) return rc;
+        for (int i = 0; i < 3; i++) if ((rc = weight_grad(gw[i], nout[i], d, off(P.dyT, (size_t)coff[i] * P.Np), P.xT))) return rc;
       } }
     // ---- first norm
     if (full && (rc = launch_rmsnorm_dgain(ctx, mode, N, d, P.da, nullptr, P.h[l], a.rstd1, P.gpart, 256, G->w_layers[l].g1, st))) return rc;
@@ -651,8 +691,8 @@ struct Step {
       if ((rc = gemm(rows, d, P.P, V, P.headT, V, V, nullptr, 0, nullptr, 0, 0, nullptr, 0, off(P.dhf, (size_t)r0 * d), d, 0, 1.f, 0, P.count, r0))) return rc;
       if (full) {
         // dW_head += P_c^T hf_c  (rows past the live count are read as zero)
-        if ((rc = launch_transpose(ctx, mode, rows, V, P.P, V, P.Pt, Mc, P.count, r0, st))) return rc;
-        if ((rc = launch_transpose(ctx, mode, rows, d, hf_c, d, P.hfT, Mc, P.count, r0, st))) return rc;
+        if ((rc = launch_transpose(ctx, mode, rows, rows, V, P.P, V, P.Pt, Mc, P.count, r0, st))) return rc;
+        if ((rc = launch_transpose(ctx, mode, rows, rows, d, hf_c, d, P.hfT, Mc, P.count, r0, st))) return rc;
         if ((rc = gemm(V, d, P.Pt, Mc, P.hfT, Mc, rows, nullptr, 0, nullptr, 0, 0, nullptr, 0, G->head, d, 1, 1.f, ch > 0))) return rc;
       }
     }
@@ -668,6 +708,27 @@ int Step::launch_lora_prep_ex(const float* in, int rows, int cols, int rows_pad,
   return launch_lora_prep2(ctx, mode, in, rows, cols, rows_pad, cols_pad, scale, out, ldo, out_t, ldo_t, st);
 }
 }  // namespace
+
+// Small per-step table (compacted segment boundaries) host -> device through pinned memory the
+// context owns.  The previous step's copy is waited for before the pinned buffer is rewritten.
+static int stage_step_table(as_ctx* ctx, const void* src, size_t bytes, hipStream_t st) {
+  if (bytes > ctx->step_bytes) {
+    if (ctx->step_ev) (void)hipEventSynchronize(ctx->step_ev);
+    if (ctx->d_step) (void)hipFree(ctx->d_step);
+    if (ctx->h_step) (void)hipHostFree(ctx->h_step);
+    ctx->d_step = ctx->h_step = nullptr; ctx->step_bytes = 0;
+    size_t cap = std::max<size_t>(4096, bytes * 2);
+    AS_HIP(ctx, hipMalloc(&ctx->d_step, cap));
+    AS_HIP(ctx, hipHostMalloc(&ctx->h_step, cap, hipHostMallocDefault));
+    ctx->step_bytes = cap;
+  }
+  if (!ctx->step_ev) AS_HIP(ctx, hipEventCreateWithFlags(&ctx->step_ev, hipEventDisableTiming));
+  else AS_HIP(ctx, hipEventSynchronize(ctx->step_ev));
+  memcpy(ctx->h_step, src, bytes);
+  AS_HIP(ctx, hipMemcpyAsync(ctx->d_step, ctx->h_step, bytes, hipMemcpyHostToDevice, st));
+  AS_HIP(ctx, hipEventRecord(ctx->step_ev, st));
+  return AS_OK;
+}
 
 static int check_cu(as_ctx* ctx, const int32_t* cu, int32_t S, int64_t N, int32_t T, int* max_seg) {
   if (S < 1) return as_fail(ctx, AS_ERR_CU_SEQLENS, "cu_seqlens: at least one segment is needed");
@@ -685,7 +746,7 @@ static int check_cu(as_ctx* ctx, const int32_t* cu, int32_t S, int64_t N, int32_
 
 extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lora* lora,
                              const int32_t* d_tokens, const int32_t* d_cu_seqlens,
-                             const int32_t* h_cu_seqlens, int32_t n_segments,
+                             const int32_t* h_cu_seqlens, int32_t n_segments, const uint8_t* h_seg_skip,
                              const uint8_t* d_loss_mask, int32_t n_rows, int32_t row_len,
                              float* d_loss, float* d_loss_sum, int32_t* d_count,
                              const as_grads* grads, void* d_workspace, size_t workspace_bytes,
@@ -730,9 +791,38 @@ extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lo
 
   hipStream_t st = (hipStream_t)stream;
   AS_HIP(ctx, hipSetDevice(ctx->device));
+  // Segments the caller marks as carrying no loss-bearing token (pad tails, trajectories without an
+  // assistant turn) cannot touch the loss or any gradient: segments never see each other and the
+  // weights they would read are not being differentiated through them.  They are squeezed out.
+  int n = (int)N, n_seg_eff = n_segments;
+  const int32_t* d_cu_eff = d_cu_seqlens;
+  if (h_seg_skip) {
+    bool any = false;
+    for (int s = 0; s < n_segments; s++) any = any || h_seg_skip[s];
+    if (any) {
+      std::vector<int32_t> tab;                          // [cu_c (S'+1) | src_start (S')]
+      std::vector<int32_t> cu_c(1, 0), src;
+      max_seg = 0;
+      for (int s = 0; s < n_segments; s++) {
+        if (h_seg_skip[s]) continue;
+        const int len = h_cu_seqlens[s + 1] - h_cu_seqlens[s];
+        src.push_back(h_cu_seqlens[s]); cu_c.push_back(cu_c.back() + len); max_seg = std::max(max_seg, len);
+      }
+      n_seg_eff = (int)src.size(); n = cu_c.back();
+      if (n_seg_eff > 0) {
+        tab = cu_c; tab.insert(tab.end(), src.begin(), src.end());
+        rc = stage_step_table(ctx, tab.data(), tab.size() * 4, st);
+        if (rc) return rc;
+        const int32_t* d_tab = (const int32_t*)ctx->d_step;
+        if ((rc = launch_compact(ctx, d_tokens, d_loss_mask, d_tab, d_tab + n_seg_eff + 1, n_seg_eff, n, P.tok_c, P.mask_c, st))) return rc;
+        d_tokens = P.tok_c; d_loss_mask = P.mask_c; d_cu_eff = d_tab;
+      }
+    }
+  }
+  P.N = n; P.Np = (int)cdiv(n, 64) * 64;
   Step S{ctx, c, P, st, c.mode, 0, 0, weights, lora, grads, max_seg};
-  const int n = (int)N;
-  if ((rc = launch_segment_info(ctx, d_cu_seqlens, n_segments, n, P.seg_start, P.seg_end, st))) return rc;
+  if (n == 0) return S.zero_outputs(d_loss, d_loss_sum, d_count);
+  if ((rc = launch_segment_info(ctx, d_cu_eff, n_seg_eff, n, P.seg_start, P.seg_end, st))) return rc;
   if ((rc = launch_rope_table(ctx, max_seg, c.head_dim, c.rope_base, P.rope_cos, P.rope_sin, st))) return rc;
   if ((rc = launch_select_targets(ctx, P.seg_start, d_loss_mask, d_tokens, n, P.tgt_idx, P.tgt_pos, P.labels, d_count, st))) return rc;
   P.count = d_count;

@@ -25,6 +25,8 @@ struct as_ctx {
   // staging owned by the context (as_pack only)
   void* d_stage = nullptr; size_t d_stage_bytes = 0;
   void* h_stage = nullptr; size_t h_stage_bytes = 0;
+  // small per-step table (as_train_step with skipped segments): pinned host + device copy
+  void* d_step = nullptr; void* h_step = nullptr; size_t step_bytes = 0; hipEvent_t step_ev = nullptr;
   // optional per-launch timing (as_profile): event pairs around kernels of the tracked classes
   struct ProfRec { hipEvent_t a, b; double flops; int cls; };
   bool prof_on = false;
@@ -94,6 +96,9 @@ int launch_attention_bwd(as_ctx* ctx, int mode, int variant, const AttnParams& p
 int launch_pack(as_ctx* ctx, const int32_t* d_src_tokens, const int32_t* d_piece_dst,
                 const int32_t* d_piece_src, const uint8_t* d_piece_mask, int n_pieces, int n_out,
                 int pad_id, int32_t* d_tokens, uint8_t* d_mask, hipStream_t st);
+// tok_c[i], mask_c[i] = tok[src], mask[src] with src = src_start[s] + (i - cu_c[s]) for the kept segment s holding i
+int launch_compact(as_ctx* ctx, const int32_t* tok, const uint8_t* mask, const int32_t* cu_c, const int32_t* src_start,
+                   int n_seg, int n, int32_t* tok_c, uint8_t* mask_c, hipStream_t st);
 int launch_segment_info(as_ctx* ctx, const int32_t* d_cu, int n_seg, int n, int32_t* seg_start,
                         int32_t* seg_end, hipStream_t st);
 int launch_rope_table(as_ctx* ctx, int max_pos, int dh, float base, float* cosb, float* sinb, hipStream_t st);
@@ -111,8 +116,9 @@ int launch_rope(as_ctx* ctx, int mode, int n, int n_heads, int dh, void* x, int6
                 const int32_t* seg_start, const float* cosb, const float* sinb, int inverse, hipStream_t st);
 int launch_swiglu_fwd(as_ctx* ctx, int mode, int64_t n, int F, const void* gu, void* m, hipStream_t st);
 int launch_swiglu_bwd(as_ctx* ctx, int mode, int64_t n, int F, const void* dm, const void* gu, void* dgu, hipStream_t st);
-// out[c, r] = in[r, c]; with rows_dev, rows at or past *rows_dev - row_off read as zero
-int launch_transpose(as_ctx* ctx, int mode, int rows, int cols, const void* in, int64_t ldi, void* out,
+// out[c, r] = in[r, c] for r < rows_pad, reading zero for r >= rows (and, with rows_dev, for rows at
+// or past *rows_dev - row_off)
+int launch_transpose(as_ctx* ctx, int mode, int rows, int rows_pad, int cols, const void* in, int64_t ldi, void* out,
                      int64_t ldo, const int* rows_dev, int row_off, hipStream_t st);
 // out[rows_pad, cols_pad] (type T, row stride ldo) = scale * in[rows, cols] (float), zero in the
 // padding; out_t (row stride ldo_t) receives the transpose.  Either output may be NULL.

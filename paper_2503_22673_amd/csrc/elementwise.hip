@@ -56,6 +56,29 @@ int launch_pack(as_ctx* ctx, const int32_t* d_src_tokens, const int32_t* d_piece
   return AS_OK;
 }
 
+__global__ void compact_kernel(const int32_t* __restrict__ tok, const uint8_t* __restrict__ mask,
+                               const int32_t* __restrict__ cu_c, const int32_t* __restrict__ src_start, int n_seg, int n,
+                               int32_t* __restrict__ tok_c, uint8_t* __restrict__ mask_c) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  int lo = 0, hi = n_seg - 1;               // last s with cu_c[s] <= i
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (cu_c[mid] <= i) lo = mid; else hi = mid - 1;
+  }
+  int src = src_start[lo] + (i - cu_c[lo]);
+  tok_c[i] = tok[src];
+  mask_c[i] = mask[src];
+}
+
+int launch_compact(as_ctx* ctx, const int32_t* tok, const uint8_t* mask, const int32_t* cu_c, const int32_t* src_start,
+                   int n_seg, int n, int32_t* tok_c, uint8_t* mask_c, hipStream_t st) {
+  if (n <= 0) return AS_OK;
+  compact_kernel<<<cdiv(n, 256), 256, 0, st>>>(tok, mask, cu_c, src_start, n_seg, n, tok_c, mask_c);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}
+
 __global__ void segment_info_kernel(const int32_t* __restrict__ cu, int n_seg, int n,
                                     int32_t* __restrict__ seg_start, int32_t* __restrict__ seg_end) {
   int t = blockIdx.x * blockDim.x + threadIdx.x;
@@ -385,7 +408,7 @@ int launch_swiglu_bwd(as_ctx* ctx, int mode, int64_t n, int F, const void* dm, c
 // out[c, r] = in[r, c] through a padded 64x64 LDS tile; rows past the
 // device-side row count (if given) read as zero.
 template <typename T>
-__global__ void transpose_kernel(int rows, int cols, const T* __restrict__ in, int64_t ldi,
+__global__ void transpose_kernel(int rows, int rows_pad, int cols, const T* __restrict__ in, int64_t ldi,
                                  T* __restrict__ out, int64_t ldo, const int* __restrict__ rows_dev, int row_off) {
   __shared__ T tile[64][65];
   int live = rows_dev ? min(rows, *rows_dev - row_off) : rows;
@@ -398,16 +421,16 @@ __global__ void transpose_kernel(int rows, int cols, const T* __restrict__ in, i
   __syncthreads();
   for (int i = ty; i < 64; i += 4) {
     int c = c0 + i, r = r0 + tx;
-    if (c < cols && r < rows) out[(int64_t)c * ldo + r] = tile[tx][i];
+    if (c < cols && r < rows_pad) out[(int64_t)c * ldo + r] = tile[tx][i];
   }
 }
 
-int launch_transpose(as_ctx* ctx, int mode, int rows, int cols, const void* in, int64_t ldi, void* out,
+int launch_transpose(as_ctx* ctx, int mode, int rows, int rows_pad, int cols, const void* in, int64_t ldi, void* out,
                      int64_t ldo, const int* rows_dev, int row_off, hipStream_t st) {
   if (rows <= 0 || cols <= 0) return AS_OK;
-  dim3 grid(cdiv(cols, 64), cdiv(rows, 64));
+  dim3 grid(cdiv(cols, 64), cdiv(rows_pad, 64));
   prof_begin(ctx, st, AS_K_TRANSPOSE, 0.0);
-  DISPATCH_T(mode, (transpose_kernel<T><<<grid, 256, 0, st>>>(rows, cols, (const T*)in, ldi, (T*)out, ldo, rows_dev, row_off)));
+  DISPATCH_T(mode, (transpose_kernel<T><<<grid, 256, 0, st>>>(rows, rows_pad, cols, (const T*)in, ldi, (T*)out, ldo, rows_dev, row_off)));
   prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;

@@ -37,7 +37,7 @@ def quantise_lora(Lo):
     return [{k: (quantise(A, False), quantise(B_, False)) for k, (A, B_) in L.items()} for L in Lo]
 
 
-def run_step(sh, params, lora, trajs, rows, row_len, mode=None, recompute=None, train_mode=None):
+def run_step(sh, params, lora, trajs, rows, row_len, mode=None, recompute=None, train_mode=None, skip=True):
     """Packs on the GPU, runs one step, returns (out dict on host, model, pack dict, ctx)."""
     ctx = B.Context(B.make_config(sh, mode=mode, recompute=recompute, train_mode=train_mode))
     pk = ctx.pack(*synth.flatten_trajectories(trajs), row_len, rows)
@@ -46,19 +46,20 @@ def run_step(sh, params, lora, trajs, rows, row_len, mode=None, recompute=None, 
     hcu = pk["cu_seqlens"].cpu().numpy()
     model = B.DeviceModel(ctx, params, lora)
     ws = torch.empty(ctx.workspace_bytes(n_rows, row_len), dtype=torch.uint8, device=DEV)
-    out = ctx.train_step(model, pk["tokens"], pk["cu_seqlens"], hcu, pk["loss_mask"], n_rows, row_len, ws)
+    out = ctx.train_step(model, pk["tokens"], pk["cu_seqlens"], hcu, pk["loss_mask"], n_rows, row_len, ws,
+                         seg_skip=pk["seg_skip"] if skip else None)
     torch.cuda.synchronize()
     res = dict(loss=float(out["loss"].item()), loss_sum=float(out["loss_sum"].item()), count=int(out["count"].item()))
     return res, model, pk, ctx
 
 
-def compare_step(sh, seed, trajs, rows, row_len, bf16, loss_tol, grad_tol, recompute=None, full=False):
+def compare_step(sh, seed, trajs, rows, row_len, bf16, loss_tol, grad_tol, recompute=None, full=False, skip=True):
     """Whole-step parity against the float64 reference on the same (rounded) inputs."""
     params = quantise_params(synth.weights(sh, seed), bf16)
     lora = None if full else quantise_lora(synth.lora_weights(sh, seed))
     mode = B.AS_BF16 if bf16 else B.AS_FP32
     res, model, pk, ctx = run_step(sh, params, lora, trajs, rows, row_len, mode=mode, recompute=recompute,
-                                   train_mode=B.AS_FULL if full else B.AS_LORA)
+                                   train_mode=B.AS_FULL if full else B.AS_LORA, skip=skip)
     ref_pk = oracle.pack(trajs, row_len, rows)
     assert np.array_equal(pk["tokens"].cpu().numpy(), ref_pk["tokens"])
     assert np.array_equal(pk["loss_mask"].cpu().numpy(), ref_pk["loss_mask"])

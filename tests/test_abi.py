@@ -121,7 +121,7 @@ def test_train_step_rejects_bad_segment_tables_on_the_host(B):
     def call(cu, n_rows=1, row_len=512, ws=p, ws_bytes=1 << 40, lora_=lora):
         cu = np.asarray(cu, dtype=np.int32)
         return B.lib.as_train_step(ctx.handle, C.byref(W), C.byref(lora_) if lora_ is not None else None, p, p,
-                                   cu.ctypes.data_as(C.c_void_p), len(cu) - 1, p, n_rows, row_len, p, p, p,
+                                   cu.ctypes.data_as(C.c_void_p), len(cu) - 1, None, p, n_rows, row_len, p, p, p,
                                    C.byref(grads), ws, ws_bytes, None)
 
     E = B.ERR

@@ -94,3 +94,29 @@ def test_same_inputs_same_bits():
     for La, Lb in zip(ma.lora_grads, mb.lora_grads):
         for k in La:
             assert torch.equal(La[k][0], Lb[k][0]) and torch.equal(La[k][1], Lb[k][1])
+
+
+def test_skipping_loss_free_segments_changes_nothing():
+    """Pad tails and trajectories without an assistant turn are squeezed out when the caller passes the
+    flags as_pack reports; loss and gradients must agree with the run that computes everything."""
+    import gpu_util as G
+    sh = synth.CONFIGS[1].replace(n_layers=2, lora_targets=synth.DENSE_TARGETS7)
+    trajs = random_trajs(5, 7, sh.vocab, turn_lo=10, turn_hi=30, turns=(2, 5))
+    trajs[2] = [(1, t) for _, t in trajs[2]]                    # no assistant turn at all
+    trajs[4] = [(0, trajs[4][0][1])]                            # a lone system turn
+    params, lora = synth.weights(sh, 2), synth.lora_weights(sh, 2)
+    a, ma, pk, _ = G.run_step(sh, params, lora, trajs, 3, 256, skip=True)
+    b, mb, _, _ = G.run_step(sh, params, lora, trajs, 3, 256, skip=False)
+    assert pk["seg_skip"].sum() >= 3 and pk["seg_skip"].sum() < len(pk["seg_skip"])
+    ref = oracle.pack(trajs, 256, 3)
+    lens = np.diff(ref["cu_seqlens"])
+    expect = [int(ref["loss_mask"][ref["cu_seqlens"][s]:ref["cu_seqlens"][s + 1]].sum() == 0) for s in range(len(lens))]
+    assert pk["seg_skip"].tolist() == expect
+    assert a["count"] == b["count"] and abs(a["loss"] - b["loss"]) <= 1e-6 * abs(b["loss"])
+    for La, Lb in zip(ma.lora_grads, mb.lora_grads):
+        for k in La:
+            for x, y in zip(La[k], Lb[k]):
+                d = (x - y).abs().max().item()
+                assert d <= 1e-5 * y.abs().max().item()
+    rep = G.compare_step(sh, 2, trajs, 3, 256, bf16=False, loss_tol=1e-4, grad_tol=1e-4, skip=True)
+    assert rep["worst_grad"] <= 1e-4

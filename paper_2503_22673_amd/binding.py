@@ -78,9 +78,9 @@ lib.as_op_gemm.argtypes = [_vp, C.c_int, C.c_int, _i64, _i64, _vp, _i64, _vp, _i
                            _f32, _vp, _i64, _vp, _i64, C.c_int, _vp]
 lib.as_op_rmsnorm_fwd.argtypes = [_vp, C.c_int, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _vp]
 lib.as_op_rmsnorm_bwd.argtypes = [_vp, C.c_int, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
-lib.as_op_attention_fwd.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp]
+lib.as_op_attention_fwd.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _vp]
 lib.as_op_attention_bwd.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp,
-                                    _vp, _vp, _vp, _vp, _vp]
+                                    _vp, _vp, _vp, _vp, _vp, _vp]
 lib.as_probe_mfma_peak.argtypes = [_vp, _i32, _i32, _vp, C.POINTER(C.c_double), _vp]
 lib.as_probe_mfma_peak.restype = C.c_int
 lib.as_profile.argtypes = [_vp, C.c_int]
@@ -273,9 +273,11 @@ class Context:
         o = torch.empty(n, D, dtype=qkv.dtype, device=qkv.device)
         lse = torch.empty(n, c.n_q_heads, dtype=torch.float32, device=qkv.device)
         base = qkv.data_ptr()
+        n64 = (n + 63) // 64 * 64
+        ts = torch.empty(Dkv * n64, dtype=qkv.dtype, device=qkv.device)
         self.check(lib.as_op_attention_fwd(self.handle, mode, variant, n, _ptr(seg_start), C.c_void_p(base), qkv.stride(0),
                                            C.c_void_p(base + D * es), C.c_void_p(base + (D + Dkv) * es), qkv.stride(0),
-                                           _ptr(o), _ptr(lse), _stream()))
+                                           _ptr(o), _ptr(lse), _ptr(ts), _stream()))
         return o, lse
 
     def op_attention_bwd(self, qkv, seg_start, seg_end, o, lse, d_o, variant=0, mode=None):
@@ -287,10 +289,12 @@ class Context:
         dqkv = torch.empty_like(qkv)
         delta = torch.empty(n, c.n_q_heads, dtype=torch.float32, device=qkv.device)
         b, g = qkv.data_ptr(), dqkv.data_ptr()
+        n64 = (n + 63) // 64 * 64
+        ts = torch.empty((2 * D + Dkv) * n64, dtype=qkv.dtype, device=qkv.device)
         self.check(lib.as_op_attention_bwd(self.handle, mode, variant, n, _ptr(seg_start), _ptr(seg_end), C.c_void_p(b),
                                            qkv.stride(0), C.c_void_p(b + D * es), C.c_void_p(b + (D + Dkv) * es),
                                            qkv.stride(0), _ptr(o), _ptr(lse), _ptr(d_o), C.c_void_p(g),
-                                           C.c_void_p(g + D * es), C.c_void_p(g + (D + Dkv) * es), _ptr(delta), _stream()))
+                                           C.c_void_p(g + D * es), C.c_void_p(g + (D + Dkv) * es), _ptr(delta), _ptr(ts), _stream()))
         return dqkv
 
 

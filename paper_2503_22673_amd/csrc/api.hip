@@ -288,7 +288,7 @@ struct Plan {
   void *hf, *P, *dhf, *headT, *Pt, *hfT;
   void *dh, *dh2, *dm, *dgu, *db, *d_o, *dqkv, *da;
   void *du_qkv, *du_o, *du_gu, *du_d;
-  void *wT, *xT, *dyT, *uT, *duT;
+  void *wT, *xT, *dyT, *uT, *duT, *attT;
   std::vector<LoraSlot> lora;            // L * 7
   std::vector<void*> A_qkv, At_qkv, A_gu, At_gu;   // per layer concatenated groups
   size_t partial_floats;
@@ -382,6 +382,7 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   size_t umax = (size_t)std::max({P.n_qkv, P.n_gu, 1}) * rp;
   P.uT = w.take(umax * Np * es); P.duT = w.take(umax * Np * es);
   P.gpart = (float*)w.take(full ? (size_t)256 * P.d * 4 : 0);
+  P.attT = w.take(c.mode == AS_BF16 ? (size_t)(2 * P.D + P.Dkv) * Np * es : 0);   // token-major K, Q, dO (V in forward)
 
   // prepared adapter copies
   P.lora.assign((size_t)P.L * 7, LoraSlot());
@@ -489,7 +490,7 @@ struct Step {
     if ((rc = launch_rope(ctx, mode, N, c.n_q_heads + c.n_kv_heads, c.head_dim, a.qkv, QKV, P.seg_start, P.rope_cos, P.rope_sin, 0, st))) return rc;
     AttnParams ap; memset(&ap, 0, sizeof ap);
     ap.n = N; ap.Hq = c.n_q_heads; ap.Hkv = c.n_kv_heads; ap.dh = c.head_dim; ap.seg_start = P.seg_start; ap.seg_end = P.seg_end;
-    ap.q = a.qkv; ap.k = off(a.qkv, D); ap.v = off(a.qkv, D + Dkv); ap.ldq = QKV; ap.ldkv = QKV; ap.o = a.o; ap.lse = a.lse; ap.max_seg = max_seg;
+    ap.q = a.qkv; ap.k = off(a.qkv, D); ap.v = off(a.qkv, D + Dkv); ap.ldq = QKV; ap.ldkv = QKV; ap.o = a.o; ap.lse = a.lse; ap.max_seg = max_seg; ap.t_scratch = P.attT;
     if ((rc = launch_attention_fwd(ctx, mode, av, ap, st))) return rc;
     { LoraSlot& s = slot(l, AS_T_O);
       if (s.on && (rc = gemm(N, rp, a.o, D, s.A, D, D, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_o, rp))) return rc;
@@ -643,7 +644,7 @@ struct Step {
     { AttnParams ap; memset(&ap, 0, sizeof ap);
       ap.n = N; ap.Hq = c.n_q_heads; ap.Hkv = c.n_kv_heads; ap.dh = c.head_dim; ap.seg_start = P.seg_start; ap.seg_end = P.seg_end;
       ap.q = a.qkv; ap.k = off(a.qkv, D); ap.v = off(a.qkv, D + Dkv); ap.ldq = QKV; ap.ldkv = QKV; ap.o = a.o; ap.lse = a.lse;
-      ap.d_o = P.d_o; ap.dq = P.dqkv; ap.dk = off(P.dqkv, D); ap.dv = off(P.dqkv, D + Dkv); ap.delta = P.delta; ap.max_seg = max_seg;
+      ap.d_o = P.d_o; ap.dq = P.dqkv; ap.dk = off(P.dqkv, D); ap.dv = off(P.dqkv, D + Dkv); ap.delta = P.delta; ap.max_seg = max_seg; ap.t_scratch = P.attT;
       if ((rc = launch_attention_bwd(ctx, mode, av, ap, st))) return rc; }
     if ((rc = launch_rope(ctx, mode, N, c.n_q_heads + c.n_kv_heads, c.head_dim, P.dqkv, QKV, P.seg_start, P.rope_cos, P.rope_sin, 1, st))) return rc;
     // ---- q / k / v projections
@@ -926,11 +927,11 @@ static int attn_common(as_ctx* ctx, int mode, int64_t n, int64_t ldq, int64_t ld
 
 extern "C" int as_op_attention_fwd(as_ctx* ctx, int mode, int variant, int64_t n, const int32_t* seg_start,
                                    const void* q, int64_t ldq, const void* k, const void* v, int64_t ldkv,
-                                   void* o, float* lse, void* stream) {
+                                   void* o, float* lse, void* t_scratch, void* stream) {
   if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_op_attention_fwd: NULL context");
   if (!seg_start || !q || !k || !v || !o || !lse) return as_fail(ctx, AS_ERR_NULL, "as_op_attention_fwd: NULL operand");
   AttnParams ap; int rc = attn_common(ctx, mode, n, ldq, ldkv, &ap); if (rc) return rc;
-  ap.seg_start = seg_start; ap.q = q; ap.k = k; ap.v = v; ap.o = o; ap.lse = lse;
+  ap.seg_start = seg_start; ap.q = q; ap.k = k; ap.v = v; ap.o = o; ap.lse = lse; ap.t_scratch = t_scratch;
   AS_HIP(ctx, hipSetDevice(ctx->device));
   return launch_attention_fwd(ctx, mode, variant, ap, (hipStream_t)stream);
 }
@@ -939,13 +940,13 @@ extern "C" int as_op_attention_bwd(as_ctx* ctx, int mode, int variant, int64_t n
                                    const int32_t* seg_end, const void* q, int64_t ldq, const void* k,
                                    const void* v, int64_t ldkv, const void* o, const float* lse,
                                    const void* d_o, void* dq, void* dk, void* dv, float* delta_scratch,
-                                   void* stream) {
+                                   void* t_scratch, void* stream) {
   if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_op_attention_bwd: NULL context");
   if (!seg_start || !seg_end || !q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !delta_scratch)
     return as_fail(ctx, AS_ERR_NULL, "as_op_attention_bwd: NULL operand");
   AttnParams ap; int rc = attn_common(ctx, mode, n, ldq, ldkv, &ap); if (rc) return rc;
   ap.seg_start = seg_start; ap.seg_end = seg_end; ap.q = q; ap.k = k; ap.v = v; ap.o = const_cast<void*>(o); ap.lse = const_cast<float*>(lse);
-  ap.d_o = d_o; ap.dq = dq; ap.dk = dk; ap.dv = dv; ap.delta = delta_scratch;
+  ap.d_o = d_o; ap.dq = dq; ap.dk = dk; ap.dv = dv; ap.delta = delta_scratch; ap.t_scratch = t_scratch;
   AS_HIP(ctx, hipSetDevice(ctx->device));
   return launch_attention_bwd(ctx, mode, variant, ap, (hipStream_t)stream);
 }

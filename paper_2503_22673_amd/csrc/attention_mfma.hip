@@ -8,8 +8,9 @@
 // and the probabilities, rounded to bf16, are already laid out as the B
 // operand of the next product O^T = V^T P^T (contraction over the keys a lane
 // holds).  The same holds in the backward kernels for dS.  The operand that is
-// contracted over its row index (V in forward; K, Q, dO in backward) is read
-// from its row-major LDS tile column-wise, eight 16-bit reads per fragment.
+// contracted over its row index (V in forward; K, Q, dO in backward) is taken
+// from a token-major copy ([column][token], made by a transpose pass right
+// before the launch) so that its fragments are two 8-byte LDS reads.
 //
 // Tiles are cut on the flat token stream (64 keys per step); a query t sees
 // key u iff seg_start[t] <= u <= t, equivalently u <= t < seg_end[u], so no
@@ -58,6 +59,38 @@ struct TileIO {
   }
 };
 
+// token-major tile: DH rows (columns of the original tensor) x 64 tokens starting at t0
+template <int DH>
+struct TileIOT {
+  static constexpr int LST = BKEY + 8;         // LDS row stride in elements
+  static constexpr int PER = DH * 8 / 256;     // 16-byte chunks per thread
+  u32x4 r[PER];
+  __device__ __forceinline__ void fetch(const bf16_t* baseT, int64_t ldT, int c0, int t0, int tid) {
+#pragma unroll
+    for (int i = 0; i < PER; i++) {
+      int c = tid + i * 256, row = c >> 3, cc = c & 7;
+      r[i] = *reinterpret_cast<const u32x4*>(baseT + (int64_t)(c0 + row) * ldT + t0 + cc * 8);
+    }
+  }
+  __device__ __forceinline__ void stash(bf16_t* s, int tid) const {
+#pragma unroll
+    for (int i = 0; i < PER; i++) {
+      int c = tid + i * 256, row = c >> 3, cc = c & 7;
+      *reinterpret_cast<u32x4*>(s + row * LST + cc * 8) = r[i];
+    }
+  }
+};
+// fragment from a token-major tile: element j is token rbase + 8*(j/4) + j%4 of row `row`
+__device__ __forceinline__ bf16x8 frag_t(const bf16_t* s, int row, int rbase) {
+  constexpr int LST = BKEY + 8;
+  const bf16x4 lo = *reinterpret_cast<const bf16x4*>(s + row * LST + rbase);
+  const bf16x4 hi = *reinterpret_cast<const bf16x4*>(s + row * LST + rbase + 8);
+  bf16x8 v;
+#pragma unroll
+  for (int j = 0; j < 4; j++) { v[j] = lo[j]; v[4 + j] = hi[j]; }
+  return v;
+}
+
 // fragment with the contraction index along the LDS row (16-byte read)
 template <int LS>
 __device__ __forceinline__ bf16x8 frag_row(const bf16_t* s, int row, int k0) {
@@ -86,12 +119,12 @@ template <int DH, int HPW>
 __global__ __launch_bounds__(256) void attn_fwd_mfma(AttnParams p, float sl2) {
   constexpr int LS = DH + 8, KS = DH / 16, CB = DH / 32, QT = 64 * (4 / HPW);
   __shared__ __align__(16) bf16_t sK[BKEY * LS];
-  __shared__ __align__(16) bf16_t sV[BKEY * LS];
+  __shared__ __align__(16) bf16_t sVt[DH * (BKEY + 8)];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, h = lane >> 5;
   const int n = p.n, grp = p.Hq / p.Hkv;
   const int j = blockIdx.y * HPW + (wave % HPW), g = j / grp;
   const int t_wg = blockIdx.x * QT, t_base = t_wg + (wave / HPW) * 64;
-  const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* V = (const bf16_t*)p.v;
+  const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* VT = (const bf16_t*)p.vT;
 
   bf16x8 qf[2][KS];
   int tq[2], ss[2];
@@ -113,14 +146,14 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(AttnParams p, float sl2) {
 
   const int kv_first = p.seg_start[min(t_wg, n - 1)] / BKEY;
   const int kv_last = min(t_wg + QT - 1, n - 1) / BKEY;
-  TileIO<DH> ioK, ioV;
+  TileIO<DH> ioK; TileIOT<DH> ioV;
   ioK.fetch(K, p.ldkv, g * DH, kv_first * BKEY, n, tid);
-  ioV.fetch(V, p.ldkv, g * DH, kv_first * BKEY, n, tid);
+  ioV.fetch(VT, p.ldT, g * DH, kv_first * BKEY, tid);
   for (int kt = kv_first; kt <= kv_last; kt++) {
     __syncthreads();                       // everyone is done with the previous tile
-    ioK.stash(sK, tid); ioV.stash(sV, tid);
+    ioK.stash(sK, tid); ioV.stash(sVt, tid);
     __syncthreads();
-    if (kt < kv_last) { ioK.fetch(K, p.ldkv, g * DH, (kt + 1) * BKEY, n, tid); ioV.fetch(V, p.ldkv, g * DH, (kt + 1) * BKEY, n, tid); }
+    if (kt < kv_last) { ioK.fetch(K, p.ldkv, g * DH, (kt + 1) * BKEY, n, tid); ioV.fetch(VT, p.ldT, g * DH, (kt + 1) * BKEY, tid); }
     const int k0 = kt * BKEY;
     if (k0 > t_base + 63 || t_base >= n) continue;          // tile lies after every query of this wave
     f32x16 s[2][2];
@@ -171,7 +204,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(AttnParams p, float sl2) {
       const int rbase = (x >> 1) * 32 + (x & 1) * 16 + 4 * h;
 #pragma unroll
       for (int cb = 0; cb < CB; cb++) {
-        bf16x8 a = frag_col<LS>(sV, rbase, cb * 32 + l31);
+        bf16x8 a = frag_t(sVt, cb * 32 + l31, rbase);
 #pragma unroll
         for (int qb = 0; qb < 2; qb++) o[qb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb][x], o[qb][cb], 0, 0, 0);
       }
@@ -215,6 +248,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(AttnParams p, float scal
   constexpr int LS = DH + 8, KS = DH / 16, CB = DH / 32, QT = 32 * (4 / HPW);
   __shared__ __align__(16) bf16_t sK[BKEY * LS];
   __shared__ __align__(16) bf16_t sV[BKEY * LS];
+  __shared__ __align__(16) bf16_t sKt[DH * (BKEY + 8)];
+  const bf16_t* KT = (const bf16_t*)p.kT;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, h = lane >> 5;
   const int n = p.n, grp = p.Hq / p.Hkv;
   const int j = blockIdx.y * HPW + (wave % HPW), g = j / grp;
@@ -236,14 +271,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(AttnParams p, float scal
 
   const int kv_first = p.seg_start[min(t_wg, n - 1)] / BKEY;
   const int kv_last = min(t_wg + QT - 1, n - 1) / BKEY;
-  TileIO<DH> ioK, ioV;
+  TileIO<DH> ioK, ioV; TileIOT<DH> ioKt;
   ioK.fetch(K, p.ldkv, g * DH, kv_first * BKEY, n, tid);
   ioV.fetch(V, p.ldkv, g * DH, kv_first * BKEY, n, tid);
+  ioKt.fetch(KT, p.ldT, g * DH, kv_first * BKEY, tid);
   for (int kt = kv_first; kt <= kv_last; kt++) {
     __syncthreads();
-    ioK.stash(sK, tid); ioV.stash(sV, tid);
+    ioK.stash(sK, tid); ioV.stash(sV, tid); ioKt.stash(sKt, tid);
     __syncthreads();
-    if (kt < kv_last) { ioK.fetch(K, p.ldkv, g * DH, (kt + 1) * BKEY, n, tid); ioV.fetch(V, p.ldkv, g * DH, (kt + 1) * BKEY, n, tid); }
+    if (kt < kv_last) {
+      ioK.fetch(K, p.ldkv, g * DH, (kt + 1) * BKEY, n, tid); ioV.fetch(V, p.ldkv, g * DH, (kt + 1) * BKEY, n, tid);
+      ioKt.fetch(KT, p.ldT, g * DH, (kt + 1) * BKEY, tid);
+    }
     const int k0 = kt * BKEY;
     if (k0 > t_base + 31 || t_base >= n) continue;
     f32x16 s[2], dp[2];
@@ -273,7 +312,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(AttnParams p, float scal
       const int rbase = (x >> 1) * 32 + (x & 1) * 16 + 4 * h;
 #pragma unroll
       for (int cb = 0; cb < CB; cb++) {
-        bf16x8 a = frag_col<LS>(sK, rbase, cb * 32 + l31);
+        bf16x8 a = frag_t(sKt, cb * 32 + l31, rbase);
         dq[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsb[x], dq[cb], 0, 0, 0);
       }
     }
@@ -298,10 +337,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(AttnParams p, float scal
 template <int DH>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(AttnParams p, float scale, float sl2) {
   constexpr int LS = DH + 8, KS = DH / 16, CB = DH / 32;
-  __shared__ __align__(16) bf16_t sQ[BKEY * LS];
-  __shared__ __align__(16) bf16_t sdO[BKEY * LS];
-  __shared__ __align__(16) float sLse[BKEY];
-  __shared__ __align__(16) float sDel[BKEY];
+  extern __shared__ __align__(16) unsigned char dyn_smem[];
+  bf16_t* sQ = (bf16_t*)dyn_smem;                         // [64][LS]
+  bf16_t* sdO = sQ + BKEY * LS;                           // [64][LS]
+  bf16_t* sQt = sdO + BKEY * LS;                          // [DH][72]
+  bf16_t* sdOt = sQt + DH * (BKEY + 8);                   // [DH][72]
+  float* sLse = (float*)(sdOt + DH * (BKEY + 8));         // [64]
+  float* sDel = sLse + BKEY;                              // [64]
+  const bf16_t* QT = (const bf16_t*)p.qT; const bf16_t* DOT = (const bf16_t*)p.doT;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, h = lane >> 5;
   const int n = p.n, grp = p.Hq / p.Hkv, g = blockIdx.y;
   const int u_wg = blockIdx.x * 128, u_base = u_wg + wave * 32;
@@ -324,18 +367,20 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(AttnParams p, float sca
   // this wave's keys are visible from queries in [u_base, w_end)
   const int w_end = (u_base < n) ? p.seg_end[min(u_base + 31, n - 1)] : 0;
   const int ntile = q_last - q_first + 1, total = ntile * grp;
-  TileIO<DH> ioQ, ioD;
+  TileIO<DH> ioQ, ioD; TileIOT<DH> ioQt, ioDt;
   float r_lse = 0.f, r_del = 0.f;
   auto fetch = [&](int it) {
     const int jj = g * grp + it / ntile, t0 = (q_first + it % ntile) * BKEY;
     ioQ.fetch(Q, p.ldq, jj * DH, t0, n, tid);
     ioD.fetch(dO, (int64_t)p.Hq * DH, jj * DH, t0, n, tid);
+    ioQt.fetch(QT, p.ldT, jj * DH, t0, tid);
+    ioDt.fetch(DOT, p.ldT, jj * DH, t0, tid);
     if (tid < BKEY) { int t = min(t0 + tid, n - 1); r_lse = p.lse[(int64_t)t * p.Hq + jj] * 1.4426950408889634f; r_del = p.delta[(int64_t)t * p.Hq + jj]; }
   };
   if (total > 0) fetch(0);
   for (int it = 0; it < total; it++) {
     __syncthreads();
-    ioQ.stash(sQ, tid); ioD.stash(sdO, tid);
+    ioQ.stash(sQ, tid); ioD.stash(sdO, tid); ioQt.stash(sQt, tid); ioDt.stash(sdOt, tid);
     if (tid < BKEY) { sLse[tid] = r_lse; sDel[tid] = r_del; }
     __syncthreads();
     if (it + 1 < total) fetch(it + 1);
@@ -377,8 +422,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(AttnParams p, float sca
       const int rbase = (x >> 1) * 32 + (x & 1) * 16 + 4 * h;
 #pragma unroll
       for (int cb = 0; cb < CB; cb++) {
-        bf16x8 a = frag_col<LS>(sdO, rbase, cb * 32 + l31);
-        bf16x8 b = frag_col<LS>(sQ, rbase, cb * 32 + l31);
+        bf16x8 a = frag_t(sdOt, cb * 32 + l31, rbase);
+        bf16x8 b = frag_t(sQt, cb * 32 + l31, rbase);
         dv[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pbv[x], dv[cb], 0, 0, 0);
         dk[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, dsb[x], dk[cb], 0, 0, 0);
       }
@@ -406,7 +451,13 @@ int heads_per_wg(const AttnParams& p) {
 }
 
 template <int DH>
-int fwd_dh(as_ctx* ctx, const AttnParams& p, hipStream_t st) {
+int fwd_dh(as_ctx* ctx, const AttnParams& p_in, hipStream_t st) {
+  AttnParams p = p_in;
+  const int Np = (int)cdiv(p.n, 64) * 64, Dkv = p.Hkv * DH;
+  if (!p.t_scratch) return as_fail(ctx, AS_ERR_WORKSPACE, "attention: the MFMA kernels need the token-major scratch buffer");
+  p.ldT = Np; p.vT = p.t_scratch;
+  int rc = launch_transpose(ctx, AS_BF16, p.n, Np, Dkv, p.v, p.ldkv, p.t_scratch, Np, nullptr, 0, st);   // V^T [Dkv, Np]
+  if (rc) return rc;
   const float sl2 = 1.4426950408889634f / sqrtf((float)DH);
   const int hpw = heads_per_wg(p);
   if (hpw == 4) attn_fwd_mfma<DH, 4><<<dim3((unsigned)cdiv(p.n, 64), p.Hq / 4), 256, 0, st>>>(p, sl2);
@@ -417,7 +468,16 @@ int fwd_dh(as_ctx* ctx, const AttnParams& p, hipStream_t st) {
 }
 
 template <int DH>
-int bwd_dh(as_ctx* ctx, const AttnParams& p, hipStream_t st) {
+int bwd_dh(as_ctx* ctx, const AttnParams& p_in, hipStream_t st) {
+  AttnParams p = p_in;
+  const int Np = (int)cdiv(p.n, 64) * 64, Dkv = p.Hkv * DH, D = p.Hq * DH;
+  if (!p.t_scratch) return as_fail(ctx, AS_ERR_WORKSPACE, "attention: the MFMA kernels need the token-major scratch buffer");
+  bf16_t* ts = (bf16_t*)p.t_scratch;
+  p.ldT = Np; p.kT = ts; p.qT = ts + (size_t)Dkv * Np; p.doT = ts + (size_t)(Dkv + D) * Np;
+  int rc;
+  if ((rc = launch_transpose(ctx, AS_BF16, p.n, Np, Dkv, p.k, p.ldkv, ts, Np, nullptr, 0, st))) return rc;                       // K^T
+  if ((rc = launch_transpose(ctx, AS_BF16, p.n, Np, D, p.q, p.ldq, ts + (size_t)Dkv * Np, Np, nullptr, 0, st))) return rc;       // Q^T
+  if ((rc = launch_transpose(ctx, AS_BF16, p.n, Np, D, p.d_o, D, ts + (size_t)(Dkv + D) * Np, Np, nullptr, 0, st))) return rc;   // dO^T
   const float scale = 1.f / sqrtf((float)DH), sl2 = 1.4426950408889634f * scale;
   const int64_t rows = (int64_t)p.n * p.Hq;
   attn_delta_kernel<<<(unsigned)cdiv(rows, 4), 256, 0, st>>>((const bf16_t*)p.o, (const bf16_t*)p.d_o, rows, DH, p.delta);
@@ -427,7 +487,15 @@ int bwd_dh(as_ctx* ctx, const AttnParams& p, hipStream_t st) {
   else if (hpw == 2) attn_bwd_dq_mfma<DH, 2><<<dim3((unsigned)cdiv(p.n, 64), p.Hq / 2), 256, 0, st>>>(p, scale, sl2);
   else attn_bwd_dq_mfma<DH, 1><<<dim3((unsigned)cdiv(p.n, 128), p.Hq), 256, 0, st>>>(p, scale, sl2);
   AS_LAUNCH_CHECK(ctx);
-  attn_bwd_dkv_mfma<DH><<<dim3((unsigned)cdiv(p.n, 128), p.Hkv), 256, 0, st>>>(p, scale, sl2);
+  {
+    constexpr size_t smem = (size_t)(2 * BKEY * (DH + 8) + 2 * DH * (BKEY + 8)) * sizeof(bf16_t) + 2 * BKEY * sizeof(float);
+    static bool attr_set = false;
+    if (!attr_set) {
+      AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv_mfma<DH>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      attr_set = true;
+    }
+    attn_bwd_dkv_mfma<DH><<<dim3((unsigned)cdiv(p.n, 128), p.Hkv), 256, smem, st>>>(p, scale, sl2);
+  }
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }

@@ -88,6 +88,10 @@ struct AttnParams {
   void* o; float* lse;
   const void* d_o; void *dq, *dk, *dv; float* delta;
   int max_seg;             // longest segment (host knowledge, sizes LDS of the plain kernels)
+  // MFMA kernels: scratch for token-major copies ([column][token], row length ldT = tokens rounded up
+  // to 64): forward needs Hkv*dh rows (V^T), backward (2*Hq + Hkv)*dh rows (K^T, Q^T, dO^T)
+  void* t_scratch;
+  const void *qT, *kT, *vT, *doT; int64_t ldT;   // filled by the launchers
 };
 int launch_attention_fwd(as_ctx* ctx, int mode, int variant, const AttnParams& p, hipStream_t st);
 int launch_attention_bwd(as_ctx* ctx, int mode, int variant, const AttnParams& p, hipStream_t st);

@@ -51,9 +51,11 @@ extern "C" int as_create(as_ctx** out, const as_model_config* cfg, int device) {
   return AS_OK;
 }
 
+// Brackets may nest (a launcher that calls other launchers): only the outermost pair records.
 void prof_begin(as_ctx* ctx, hipStream_t st, int cls, double flops) {
   if (!ctx || !ctx->prof_on) return;
-  if (ctx->prof_used >= 65536) { ctx->prof_used++; return; }
+  if (ctx->prof_depth++ > 0) return;
+  if (ctx->prof_used >= 65536) return;
   if (ctx->prof_used >= ctx->prof.size()) {
     as_ctx::ProfRec r; r.flops = 0; r.cls = 0;
     if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) { ctx->prof_on = false; return; }
@@ -65,7 +67,9 @@ void prof_begin(as_ctx* ctx, hipStream_t st, int cls, double flops) {
 }
 void prof_end(as_ctx* ctx, hipStream_t st) {
   if (!ctx || !ctx->prof_on) return;
-  if (ctx->prof_used < 65536) (void)hipEventRecord(ctx->prof[ctx->prof_used].b, st);
+  if (--ctx->prof_depth > 0) return;
+  if (ctx->prof_used >= 65536 || ctx->prof_used >= ctx->prof.size()) return;
+  (void)hipEventRecord(ctx->prof[ctx->prof_used].b, st);
   ctx->prof_used++;
 }
 
@@ -74,7 +78,7 @@ extern "C" int as_profile(as_ctx* ctx, int enable) {
   AS_HIP(ctx, hipSetDevice(ctx->device));
   AS_HIP(ctx, hipDeviceSynchronize());
   ctx->prof_on = enable != 0;
-  ctx->prof_used = 0;
+  ctx->prof_used = 0; ctx->prof_depth = 0;
   return AS_OK;
 }
 
@@ -407,6 +411,10 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
         int r = c.lora_rank;
         part = std::max(part, (size_t)pick_splitk(c.mode, s.dout, r, P.N) * s.dout * r);
         part = std::max(part, (size_t)pick_splitk(c.mode, r, s.din, P.N) * r * s.din);
+        if (c.mode == AS_BF16 && r <= 64) {
+          part = std::max(part, lora_grad_tn_partial_floats(P.N, s.dout, r));
+          part = std::max(part, lora_grad_tn_partial_floats(P.N, s.din, r));
+        }
       }
     }
   }
@@ -556,19 +564,26 @@ struct Step {
     return launch_transpose(ctx, mode, P.N, P.Np, cols, in, ldi, out, P.Np, nullptr, 0, st);
   }
 
-  // adapter gradients of one projection: dB = s dy^T u, dA = du^T x.
-  // dyT [dout, N] (rows roff..), uT/duT [.., N] rows at slot*rp, xT [din, N].
-  int lora_grads(int l, int t, const void* dyT_rows, const void* xT) {
+  // adapter gradients of one projection: dB = s dy^T u, dA = du^T x.  bf16 with rank <= 64: one
+  // streaming pass over dy and over x (row-major, as they are) against the token-major copies of u
+  // and du.  Otherwise: GEMMs on the token-major copies dyT [dout, Np], xT [din, Np].
+  bool tn_path() const { return mode == AS_BF16 && c.lora_rank <= 64; }
+  int lora_grads(int l, int t, const void* dy, int64_t lddy, const void* x, int64_t ldx, const void* dyT_rows, const void* xT) {
     LoraSlot& s = slot(l, t);
     if (!s.on) return AS_OK;
-    const int N = P.Np, r = c.lora_rank, rp = P.rp;        // token-major operands: rows of Np tokens, zero past the live ones
+    const int Np = P.Np, r = c.lora_rank, rp = P.rp;
     const float sc = c.lora_alpha / (float)c.lora_rank;
     const as_layer_lora_grads& g = G->lora_layers[l];
-    int rc = gemm(s.dout, r, dyT_rows, N, off(P.uT, (size_t)s.slot * rp * N), N, N, nullptr, 0, nullptr, 0, 0, nullptr, 0,
-                  g.b[t], r, 1, sc, 0, nullptr, 0, true);
+    const void* uT = off(P.uT, (size_t)s.slot * rp * Np);
+    const void* duT = off(P.duT, (size_t)s.slot * rp * Np);
+    if (tn_path()) {
+      int rc = launch_lora_grad_tn(ctx, dy, lddy, uT, Np, P.N, s.dout, r, sc, g.b[t], r, 1, P.partial, P.partial_floats, st);
+      if (rc) return rc;
+      return launch_lora_grad_tn(ctx, x, ldx, duT, Np, P.N, s.din, r, 1.f, g.a[t], 1, s.din, P.partial, P.partial_floats, st);
+    }
+    int rc = gemm(s.dout, r, dyT_rows, Np, uT, Np, Np, nullptr, 0, nullptr, 0, 0, nullptr, 0, g.b[t], r, 1, sc, 0, nullptr, 0, true);
     if (rc) return rc;
-    return gemm(r, s.din, off(P.duT, (size_t)s.slot * rp * N), N, xT, N, N, nullptr, 0, nullptr, 0, 0, nullptr, 0,
-                g.a[t], s.din, 1, 1.f, 0, nullptr, 0, true);
+    return gemm(r, s.din, duT, Np, xT, Np, Np, nullptr, 0, nullptr, 0, 0, nullptr, 0, g.a[t], s.din, 1, 1.f, 0, nullptr, 0, true);
   }
   int weight_grad(float* dW, int dout, int din, const void* dyT_rows, const void* xT) {
     const int N = P.Np;
@@ -586,14 +601,14 @@ struct Step {
       if ((rc = transpose(d, F, w.wdown, F, P.wT, d))) return rc;                       // [F, d]
       if (s.on && (rc = gemm(N, rp, P.dh, d, s.Bst, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.du_d, rp))) return rc;
       if ((rc = gemm(N, F, P.dh, d, P.wT, d, d, s.on ? P.du_d : nullptr, rp, s.At, rp, s.on ? rp : 0, nullptr, 0, P.dm, F))) return rc;
-      if (s.on || full) {
+      if (full || (s.on && !tn_path())) {
         if ((rc = transpose_tok(d, P.dh, d, P.dyT))) return rc;
         if ((rc = transpose_tok(F, a.m, F, P.xT))) return rc;
       }
       if (s.on) {
         if ((rc = transpose_tok(rp, a.u_d, rp, P.uT))) return rc;
         if ((rc = transpose_tok(rp, P.du_d, rp, P.duT))) return rc;
-        if ((rc = lora_grads(l, AS_T_DOWN, P.dyT, P.xT))) return rc;
+        if ((rc = lora_grads(l, AS_T_DOWN, P.dh, d, a.m, F, P.dyT, P.xT))) return rc;
       }
       if (full && (rc = weight_grad(G->w_layers[l].wdown, d, F, P.dyT, P.xT))) return rc; }
     // ---- SwiGLU
@@ -609,14 +624,15 @@ struct Step {
       }
       if ((rc = gemm(N, d, P.dgu, 2 * F, P.wT, 2 * F, 2 * F, P.n_gu ? P.du_gu : nullptr, ldg, P.At_gu[l], ldg, ldg,
                      nullptr, 0, P.db, d))) return rc;
-      if (P.n_gu || full) {
+      if (full || (P.n_gu && !tn_path())) {
         if ((rc = transpose_tok(2 * F, P.dgu, 2 * F, P.dyT))) return rc;
         if ((rc = transpose_tok(d, a.b, d, P.xT))) return rc;
       }
       if (P.n_gu) {
         if ((rc = transpose_tok(ldg, a.u_gu, ldg, P.uT))) return rc;
         if ((rc = transpose_tok(ldg, P.du_gu, ldg, P.duT))) return rc;
-        for (int i = 0; i < 2; i++) if ((rc = lora_grads(l, AS_T_GATE + i, off(P.dyT, (size_t)i * F * P.Np), P.xT))) return rc;
+        for (int i = 0; i < 2; i++)
+          if ((rc = lora_grads(l, AS_T_GATE + i, off(P.dgu, (size_t)i * F), 2 * F, a.b, d, off(P.dyT, (size_t)i * F * P.Np), P.xT))) return rc;
       }
       if (full) {
         if ((rc = weight_grad(G->w_layers[l].wgate, F, d, P.dyT, P.xT))) return rc;
@@ -630,14 +646,14 @@ struct Step {
       if ((rc = transpose(d, D, w.wo, D, P.wT, d))) return rc;                          // [D, d]
       if (s.on && (rc = gemm(N, rp, P.dh2, d, s.Bst, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.du_o, rp))) return rc;
       if ((rc = gemm(N, D, P.dh2, d, P.wT, d, d, s.on ? P.du_o : nullptr, rp, s.At, rp, s.on ? rp : 0, nullptr, 0, P.d_o, D))) return rc;
-      if (s.on || full) {
+      if (full || (s.on && !tn_path())) {
         if ((rc = transpose_tok(d, P.dh2, d, P.dyT))) return rc;
         if ((rc = transpose_tok(D, a.o, D, P.xT))) return rc;
       }
       if (s.on) {
         if ((rc = transpose_tok(rp, a.u_o, rp, P.uT))) return rc;
         if ((rc = transpose_tok(rp, P.du_o, rp, P.duT))) return rc;
-        if ((rc = lora_grads(l, AS_T_O, P.dyT, P.xT))) return rc;
+        if ((rc = lora_grads(l, AS_T_O, P.dh2, d, a.o, D, P.dyT, P.xT))) return rc;
       }
       if (full && (rc = weight_grad(G->w_layers[l].wo, d, D, P.dyT, P.xT))) return rc; }
     // ---- attention
@@ -658,14 +674,15 @@ struct Step {
       }
       if ((rc = gemm(N, d, P.dqkv, QKV, P.wT, QKV, QKV, P.n_qkv ? P.du_qkv : nullptr, ldu, P.At_qkv[l], ldu, ldu,
                      nullptr, 0, P.da, d))) return rc;
-      if (P.n_qkv || full) {
+      if (full || (P.n_qkv && !tn_path())) {
         if ((rc = transpose_tok(QKV, P.dqkv, QKV, P.dyT))) return rc;
         if ((rc = transpose_tok(d, a.a, d, P.xT))) return rc;
       }
       if (P.n_qkv) {
         if ((rc = transpose_tok(ldu, a.u_qkv, ldu, P.uT))) return rc;
         if ((rc = transpose_tok(ldu, P.du_qkv, ldu, P.duT))) return rc;
-        for (int i = 0; i < 3; i++) if ((rc = lora_grads(l, i, off(P.dyT, (size_t)coff[i] * P.Np), P.xT))) return rc;
+        for (int i = 0; i < 3; i++)
+          if ((rc = lora_grads(l, i, off(P.dqkv, coff[i]), QKV, a.a, d, off(P.dyT, (size_t)coff[i] * P.Np), P.xT))) return rc;
       }
       if (full) {
         float* gw[3] = {G->w_layers[l].wq, G->w_layers[l].wk, G->w_layers[l].wv};

@@ -7,6 +7,7 @@
 #include <stddef.h>
 #include <string>
 #include <vector>
+#include <algorithm>
 #include "actionstudio.h"
 
 typedef __bf16 bf16_t;
@@ -29,7 +30,7 @@ struct as_ctx {
   void* d_step = nullptr; void* h_step = nullptr; size_t step_bytes = 0; hipEvent_t step_ev = nullptr;
   // optional per-launch timing (as_profile): event pairs around kernels of the tracked classes
   struct ProfRec { hipEvent_t a, b; double flops; int cls; };
-  bool prof_on = false;
+  bool prof_on = false; int prof_depth = 0;
   std::vector<ProfRec> prof; size_t prof_used = 0;
 };
 // Brackets one kernel launch with events when profiling is on (no-ops otherwise).
@@ -79,6 +80,12 @@ int launch_gemm(as_ctx* ctx, int mode, int variant, const GemmParams& p, hipStre
 int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p, int m_off, hipStream_t st);
 
 int launch_mfma_peak(as_ctx* ctx, int iters, int blocks, float* sink, hipStream_t st);
+
+// ---- adapter gradients (lora_grad.hip) ---------------------------------------
+// C[m*sm + j*sj] = alpha * sum_t X[t, m] * UT[j, t]  (bf16 X row-major, UT token-major, float C)
+size_t lora_grad_tn_partial_floats(int n, int M, int r);
+int launch_lora_grad_tn(as_ctx* ctx, const void* X, int64_t ldx, const void* UT, int64_t ldu, int n, int M, int r,
+                        float alpha, float* C, int64_t sm, int64_t sj, float* partial, size_t partial_floats, hipStream_t st);
 
 // ---- attention (attention.hip) -----------------------------------------------
 struct AttnParams {

@@ -1,0 +1,142 @@
+// Adapter gradients: C[m, j] = alpha * sum_t X[t, m] * U[t, j], a product contracted over TOKENS,
+// i.e. over the row index of both operands (dB = s dy^T u with X = dy, U = u; dA^T = x^T du with
+// X = x, U = du).  X is a big row-major activation ([tokens, M] bf16, up to 14336 columns), U is
+// 64 columns wide at most, so the kernel is a single streaming pass over X at HBM speed.
+//
+// Matrix cores want the contraction index contiguous per lane.  Instead of transposing X through
+// memory, each lane loads an 8-token x 8-column block (eight 16-byte loads, 256 B contiguous per
+// 16 lanes and token) and transposes it in registers (v_perm), which yields the A operands of eight
+// v_mfma_f32_16x16x32_bf16 -- one per column of the block; MFMA row m then stands for column
+// c0 + 8 m + q of X.  U comes from its small token-major copy ([j][token]), one 16-byte load per
+// lane and 16-column block.  Waves of a workgroup take interleaved 32-token steps and are summed
+// through LDS in a fixed order; token splits go to a partial buffer reduced in split order.
+#include "common.h"
+
+namespace {
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+struct TnParams {
+  const bf16_t* X; int64_t ldx;      // [n, M] row-major
+  const bf16_t* UT; int64_t ldu;     // [>= 16*NB rows, tokens rounded up to 64] token-major, zero past n and past r
+  int n, M, r;
+  float* partial;                    // [splits, M, r]
+  int steps_per_split, total_steps;  // 32-token steps
+};
+
+template <int NB>
+__global__ __launch_bounds__(256) void lora_grad_tn_kernel(TnParams p) {
+  extern __shared__ __align__(16) float red[];               // 2 slots x (8*NB*64*4) floats
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lm = lane & 15, lg = lane >> 4;
+  const int slab = blockIdx.x, split = blockIdx.y;
+  const int col = slab * 128 + 8 * lm;
+  const bool col_ok = col < p.M;
+  f32x4 acc[8][NB];
+#pragma unroll
+  for (int q = 0; q < 8; q++)
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++) acc[q][nb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  const int s_end = min((split + 1) * p.steps_per_split, p.total_steps);
+  for (int step = split * p.steps_per_split + wave; step < s_end; step += 4) {
+    const int t0 = step * 32 + 8 * lg;
+    u32x4 x[8];
+#pragma unroll
+    for (int r = 0; r < 8; r++) {
+      const int t = t0 + r;
+      const bool ok = col_ok && t < p.n;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(p.X + (int64_t)(ok ? t : 0) * p.ldx + (ok ? col : 0));
+      x[r] = ok ? v : (u32x4){0u, 0u, 0u, 0u};
+    }
+    bf16x8 b[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++) b[nb] = *reinterpret_cast<const bf16x8*>(p.UT + (int64_t)(nb * 16 + lm) * p.ldu + t0);
+#pragma unroll
+    for (int q = 0; q < 8; q++) {
+      // column q of the 8x8 block: dword d of the operand = (x[2d][q], x[2d+1][q])
+      u32x4 a;
+#pragma unroll
+      for (int d = 0; d < 4; d++)
+        a[d] = __builtin_amdgcn_perm(x[2 * d + 1][q >> 1], x[2 * d][q >> 1], (q & 1) ? 0x07060302u : 0x05040100u);
+      const bf16x8 av = __builtin_bit_cast(bf16x8, a);
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++) acc[q][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b[nb], acc[q][nb], 0, 0, 0);
+    }
+  }
+  // waves 2,3 -> slots; waves 0,1 add; wave 1 -> slot 0; wave 0 adds: (w0 + w2) + (w1 + w3)
+  constexpr int PER_WAVE = 8 * NB * 64;                       // f32x4 elements per wave
+  f32x4* slot = reinterpret_cast<f32x4*>(red);
+  auto put = [&](int s) {
+#pragma unroll
+    for (int q = 0; q < 8; q++)
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++) slot[s * PER_WAVE + (q * NB + nb) * 64 + lane] = acc[q][nb];
+  };
+  auto add = [&](int s) {
+#pragma unroll
+    for (int q = 0; q < 8; q++)
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++) acc[q][nb] += slot[s * PER_WAVE + (q * NB + nb) * 64 + lane];
+  };
+  if (wave >= 2) put(wave - 2);
+  __syncthreads();
+  if (wave < 2) add(wave);
+  __syncthreads();
+  if (wave == 1) put(0);
+  __syncthreads();
+  if (wave == 0) {
+    add(0);
+    // accumulator row 4*lg + i of MFMA q is column c0 + 8*(4*lg + i) + q; its column is j = nb*16 + lm
+    float* out = p.partial + (int64_t)split * p.M * p.r;
+#pragma unroll
+    for (int q = 0; q < 8; q++)
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++) {
+        const int j = nb * 16 + lm;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          const int m = slab * 128 + 8 * (4 * lg + i) + q;
+          if (m < p.M && j < p.r) out[(int64_t)m * p.r + j] = acc[q][nb][i];
+        }
+      }
+  }
+}
+
+__global__ void tn_reduce_kernel(const float* __restrict__ partial, int splits, int M, int r, float alpha,
+                                 float* __restrict__ C, int64_t sm, int64_t sj) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)M * r) return;
+  float acc = 0.f;
+  for (int s = 0; s < splits; s++) acc += partial[(int64_t)s * M * r + i];
+  C[(i / r) * sm + (i % r) * sj] = alpha * acc;
+}
+}  // namespace
+
+size_t lora_grad_tn_partial_floats(int n, int M, int r) {
+  const int steps = (int)cdiv(n, 32), slabs = (int)cdiv(M, 128);
+  int splits = (int)std::max<int64_t>(1, std::min<int64_t>(cdiv(1024, slabs), cdiv(steps, 16)));
+  return (size_t)splits * M * r;
+}
+
+// C[m * sm + j * sj] = alpha * sum_t X[t, m] * UT[j, t];  r <= 64, M a multiple of 8, ldx a multiple of 8.
+int launch_lora_grad_tn(as_ctx* ctx, const void* X, int64_t ldx, const void* UT, int64_t ldu, int n, int M, int r,
+                        float alpha, float* C, int64_t sm, int64_t sj, float* partial, size_t partial_floats, hipStream_t st) {
+  if (n <= 0 || M <= 0 || r <= 0) return AS_OK;
+  if (r > 64 || (M % 8) || (ldx % 8) || (ldu % 8) || ((uintptr_t)X % 16) || ((uintptr_t)UT % 16))
+    return as_fail(ctx, AS_ERR_SHAPE, "lora_grad_tn: rank <= 64 and 8-element alignment needed");
+  const int steps = (int)cdiv(n, 32), slabs = (int)cdiv(M, 128);
+  int splits = (int)std::max<int64_t>(1, std::min<int64_t>(cdiv(1024, slabs), cdiv(steps, 16)));
+  if ((size_t)splits * M * r > partial_floats) return as_fail(ctx, AS_ERR_WORKSPACE, "lora_grad_tn: partial buffer too small");
+  TnParams p{(const bf16_t*)X, ldx, (const bf16_t*)UT, ldu, n, M, r, partial, (int)cdiv(steps, splits), steps};
+  const int nb = (int)cdiv(r, 16);
+  dim3 grid(slabs, splits);
+  prof_begin(ctx, st, AS_K_LORA_GRAD, 2.0 * n * (double)M * r);
+#define TN_LAUNCH(NB) { size_t smem = (size_t)2 * 8 * NB * 64 * 16; \
+    static bool attr = false; if (!attr) { AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(lora_grad_tn_kernel<NB>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem)); attr = true; } \
+    lora_grad_tn_kernel<NB><<<grid, 256, smem, st>>>(p); }
+  switch (nb) { case 1: TN_LAUNCH(1) break; case 2: TN_LAUNCH(2) break; case 3: TN_LAUNCH(3) break; default: TN_LAUNCH(4) break; }
+#undef TN_LAUNCH
+  AS_LAUNCH_CHECK(ctx);
+  tn_reduce_kernel<<<(unsigned)cdiv((int64_t)M * r, 256), 256, 0, st>>>(partial, splits, M, r, alpha, C, sm, sj);
+  prof_end(ctx, st);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}

@@ -120,3 +120,23 @@ def test_skipping_loss_free_segments_changes_nothing():
                 assert d <= 1e-5 * y.abs().max().item()
     rep = G.compare_step(sh, 2, trajs, 3, 256, bf16=False, loss_tol=1e-4, grad_tol=1e-4, skip=True)
     assert rep["worst_grad"] <= 1e-4
+
+
+def test_per_kernel_timing_brackets_nested_launchers():
+    """With per-launch timing on, a bf16 step (MFMA attention calls the transpose launcher inside its
+    own bracket) must run, give the same bits, and report every class it used."""
+    import gpu_util as G
+    from paper_2503_22673_amd import binding as B
+    sh = synth.CONFIGS[1].replace(n_q_heads=2, n_kv_heads=1, head_dim=64, lora_targets=synth.DENSE_TARGETS7)
+    params, lora = synth.weights(sh, 0), synth.lora_weights(sh, 0)
+    trajs = synth.workload(1, 0)
+    a, ma, pk, ctx = G.run_step(sh, params, lora, trajs, 1, 512, mode=1)
+    ctx.profile(True)
+    ws = torch.empty(ctx.workspace_bytes(1, 512), dtype=torch.uint8, device="cuda")
+    out = ctx.train_step(ma, pk["tokens"], pk["cu_seqlens"], pk["cu_seqlens"].cpu().numpy(), pk["loss_mask"], 1, 512, ws,
+                         seg_skip=pk["seg_skip"])
+    prof = ctx.profile_read()
+    ctx.profile(False)
+    assert float(out["loss"].item()) == a["loss"]
+    for k in ("attn_fwd", "attn_bwd", "norm", "swiglu", "rope", "lora_grad"):
+        assert prof[k][0] > 0 and prof[k][1] > 0.0, (k, prof[k])

@@ -244,7 +244,7 @@ def main():
         "loss": round(loss, 5), "pack_ms": round(pack_ms, 2), "adamw_ms": None if adam_ms is None else round(adam_ms, 3),
         "wall_s_timed_region": round(wall, 3),
         "kernel_ms_per_step": breakdown,
-        "roofline": {"kernel": "gemm_mfma_kernel<256,256,2,4> (projection GEMMs, forward + dX, LoRA term fused)",
+        "roofline": {"kernel": "gemm_mfma_dlds_kernel<256,256,2,4,...> (projection GEMMs forward + dX, LoRA term as second K segment)",
                      "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
                      "launches_per_step": n_l // max(args.steps, 1), "avg_launch_ms": round(ms_l / max(n_l, 1), 4)},

@@ -163,6 +163,14 @@ int as_profile_read(as_ctx* ctx, int kernel_class, int64_t* launches, double* ms
  * `stream`, waits, and returns TFLOP/s in *tflops [host].  d_sink [device] float[1]. */
 int as_probe_mfma_peak(as_ctx* ctx, int32_t iters, int32_t blocks, float* d_sink, double* tflops, void* stream);
 
+/* Global -> LDS feed rate: `blocks` workgroups of 8 wavefronts, each wavefront keeping
+ * `loads_in_flight` (1, 2, 4 or 8) direct-to-LDS loads of 1 KB in flight, walking the first `span_bytes`
+ * (a power of two, at most the size of d_buf) of d_buf [device] for `iters` rounds.  Waits, and returns
+ * GB/s in *gbps [host].  A small span measures the L2 -> LDS path, a large one the MALL / HBM mix.
+ * d_sink [device] int32[1]. */
+int as_probe_lds_feed(as_ctx* ctx, int32_t loads_in_flight, const void* d_buf, size_t span_bytes, int32_t iters,
+                      int32_t blocks, int32_t* d_sink, double* gbps, void* stream);
+
 /* ---- pack (Section 3.2.1) ----------------------------------------------- */
 
 /* Packs trajectories into rows of row_len tokens.

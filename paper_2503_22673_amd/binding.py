@@ -81,6 +81,8 @@ lib.as_op_rmsnorm_bwd.argtypes = [_vp, C.c_int, _i64, _i64, _vp, _vp, _vp, _vp, 
 lib.as_op_attention_fwd.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _vp]
 lib.as_op_attention_bwd.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp,
                                     _vp, _vp, _vp, _vp, _vp, _vp]
+lib.as_probe_lds_feed.argtypes = [_vp, _i32, _vp, C.c_size_t, _i32, _i32, _vp, C.POINTER(C.c_double), _vp]
+lib.as_probe_lds_feed.restype = C.c_int
 lib.as_probe_mfma_peak.argtypes = [_vp, _i32, _i32, _vp, C.POINTER(C.c_double), _vp]
 lib.as_probe_mfma_peak.restype = C.c_int
 lib.as_profile.argtypes = [_vp, C.c_int]
@@ -91,7 +93,7 @@ for _n in ("as_profile", "as_profile_read", "as_create", "as_workspace_bytes", "
            "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd"):
     getattr(lib, _n).restype = C.c_int
 
-EXPORTS = ("as_probe_mfma_peak", "as_profile", "as_profile_read", "as_create", "as_destroy", "as_last_error", "as_workspace_bytes", "as_pack", "as_train_step",
+EXPORTS = ("as_probe_lds_feed", "as_probe_mfma_peak", "as_profile", "as_profile_read", "as_create", "as_destroy", "as_last_error", "as_workspace_bytes", "as_pack", "as_train_step",
            "as_adamw_update", "as_op_gemm", "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd",
            "as_op_attention_bwd")
 
@@ -156,6 +158,16 @@ class Context:
     def workspace_bytes(self, max_rows, row_len):
         out = C.c_size_t()
         self.check(lib.as_workspace_bytes(self.handle, max_rows, row_len, C.byref(out)))
+        return out.value
+
+    def probe_lds_feed(self, loads_in_flight, span_bytes, iters=2000, blocks=256, buf=None):
+        dev = torch.device("cuda", self.device)
+        if buf is None:
+            buf = torch.ones(span_bytes, dtype=torch.uint8, device=dev)
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        out = C.c_double()
+        self.check(lib.as_probe_lds_feed(self.handle, loads_in_flight, _ptr(buf), span_bytes, iters, blocks, _ptr(sink),
+                                         C.byref(out), _stream()))
         return out.value
 
     def probe_mfma_peak(self, iters=20000, blocks=2048):

@@ -100,6 +100,27 @@ extern "C" int as_profile_read(as_ctx* ctx, int kernel_class, int64_t* launches,
   return AS_OK;
 }
 
+extern "C" int as_probe_lds_feed(as_ctx* ctx, int32_t loads_in_flight, const void* d_buf, size_t span_bytes, int32_t iters,
+                                 int32_t blocks, int32_t* d_sink, double* gbps, void* stream) {
+  if (!ctx || !d_buf || !d_sink || !gbps) return as_fail(ctx, AS_ERR_NULL, "as_probe_lds_feed: NULL argument");
+  if (span_bytes < 65536 || (span_bytes & (span_bytes - 1)) || iters < 1 || blocks < 1 || iters > (1 << 20) || blocks > (1 << 16))
+    return as_fail(ctx, AS_ERR_SHAPE, "as_probe_lds_feed: span a power of two >= 64 KB, iters in [1, 2^20], blocks in [1, 2^16]");
+  hipStream_t st = (hipStream_t)stream;
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  hipEvent_t a, b;
+  AS_HIP(ctx, hipEventCreate(&a)); AS_HIP(ctx, hipEventCreate(&b));
+  int rc = launch_feed_probe(ctx, loads_in_flight, d_buf, span_bytes, iters / 8 + 1, blocks, d_sink, st);   // warm-up
+  if (!rc) { (void)hipEventRecord(a, st); rc = launch_feed_probe(ctx, loads_in_flight, d_buf, span_bytes, iters, blocks, d_sink, st); (void)hipEventRecord(b, st); }
+  hipError_t e = hipEventSynchronize(b);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+  (void)hipEventDestroy(a); (void)hipEventDestroy(b);
+  if (rc) return rc;
+  if (e != hipSuccess) return as_fail(ctx, AS_ERR_HIP, "as_probe_lds_feed: %s", hipGetErrorString(e));
+  *gbps = (double)blocks * iters * 8.0 * loads_in_flight * 1024.0 / (ms * 1e-3) / 1e9;
+  return AS_OK;
+}
+
 extern "C" int as_probe_mfma_peak(as_ctx* ctx, int32_t iters, int32_t blocks, float* d_sink, double* tflops, void* stream) {
   if (!ctx || !d_sink || !tflops) return as_fail(ctx, AS_ERR_NULL, "as_probe_mfma_peak: NULL argument");
   if (iters < 1 || blocks < 1 || iters > (1 << 24) || blocks > (1 << 20)) return as_fail(ctx, AS_ERR_SHAPE, "as_probe_mfma_peak: iters in [1, 2^24], blocks in [1, 2^20]");

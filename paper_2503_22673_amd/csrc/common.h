@@ -79,6 +79,7 @@ int launch_gemm(as_ctx* ctx, int mode, int variant, const GemmParams& p, hipStre
 // live rows = *p.m_dev - m_off, clamped to [0, p.M]
 int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p, int m_off, hipStream_t st);
 
+int launch_feed_probe(as_ctx* ctx, int k, const void* buf, size_t span, int iters, int blocks, int* sink, hipStream_t st);
 int launch_mfma_peak(as_ctx* ctx, int iters, int blocks, float* sink, hipStream_t st);
 
 // ---- adapter gradients (lora_grad.hip) ---------------------------------------

@@ -249,7 +249,9 @@ template <int SWZ> __device__ __forceinline__ int swz(int r) {
   else return ((r & 3) << 1) | ((r >> 2) & 1);
 }
 
-template <int BM, int BN, int WM, int WN, bool DB, int SWZ, int PF>
+// MAP: workgroup id -> tile.  0: de-interleave over the 8 XCDs, then groups of 8 row-tiles; 1: groups of 8 row-tiles
+// without the XCD step; 2: XCD step with groups of 4; 3: XCD step with groups of 16.
+template <int BM, int BN, int WM, int WN, bool DB, int SWZ, int PF, int MAP = 0>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams p, int m_off, int tiles_m, int tiles_n) {
   constexpr int BK = 64, NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -262,8 +264,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
   const int M = p.m_dev ? min(p.M, *p.m_dev - m_off) : p.M;
   int nblk = tiles_m * tiles_n, pid = blockIdx.x, z = blockIdx.y;
   int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
-  int logical = xcd * q8 + min(xcd, rem) + loc;
-  constexpr int GROUP = 8;
+  int logical = (MAP == 1) ? pid : xcd * q8 + min(xcd, rem) + loc;
+  constexpr int GROUP = (MAP == 2) ? 4 : (MAP == 3) ? 16 : 8;
   int in_group = GROUP * tiles_n, grp = logical / in_group, first_m = grp * GROUP;
   int gsize = min(tiles_m - first_m, GROUP);
   int tile_m = first_m + (logical % in_group) % gsize, tile_n = (logical % in_group) / gsize;
@@ -413,10 +415,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
                         (row0 + BM <= M) && (col0 + BN <= p.N));
 }
 
-template <int BM, int BN, int WM, int WN, bool DB, int SWZ, int PF = 0>
+template <int BM, int BN, int WM, int WN, bool DB, int SWZ, int PF = 0, int MAP = 0>
 static int launch_dlds_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_t st) {
   size_t smem = (size_t)2 * (BM + BN) * 64 * sizeof(bf16_t);
-  auto k0 = gemm_mfma_dlds_kernel<BM, BN, WM, WN, DB, SWZ, PF>;
+  auto k0 = gemm_mfma_dlds_kernel<BM, BN, WM, WN, DB, SWZ, PF, MAP>;
   static bool attr_set = false;
   if (!attr_set) {
     AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(k0), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
@@ -480,7 +482,7 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
   if (p.splitk < 1) p.splitk = 1;
   if (p.splitk > 1 && !p.partial) return as_fail(ctx, AS_ERR_WORKSPACE, "gemm: split-K needs a partial buffer");
   if (p.accumulate && !p.c_f32) return as_fail(ctx, AS_ERR_SHAPE, "gemm: accumulate needs float output");
-  if (variant < 0 || (variant > 2 && (variant < 10 || variant > 22))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
+  if (variant < 0 || (variant > 2 && (variant < 10 || variant > 25))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
   bool use_mfma = (mode == AS_BF16) && variant != 1 && mfma_ok(p);
   if (variant >= 2 && !use_mfma) return as_fail(ctx, AS_ERR_SHAPE, "gemm: MFMA kernel needs bf16 and 8-element alignment");
   int rc = AS_OK;
@@ -504,6 +506,9 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
       case 10: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 2>(ctx, p, m_off, st); break;
       case 11: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 3>(ctx, p, m_off, st); break;
       case 12: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 4>(ctx, p, m_off, st); break;
+      case 13: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 0, 1>(ctx, p, m_off, st); break;
+      case 14: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 0, 2>(ctx, p, m_off, st); break;
+      case 15: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 0, 3>(ctx, p, m_off, st); break;
       default: rc = launch_mfma_cfg<256, 256, 2, 4>(ctx, p, m_off, st); break;
     }
   } else {
@@ -550,6 +555,39 @@ __global__ __launch_bounds__(512) void mfma_peak_kernel(int iters, float* sink) 
 
 int launch_mfma_peak(as_ctx* ctx, int iters, int blocks, float* sink, hipStream_t st) {
   mfma_peak_kernel<<<blocks, 512, 0, st>>>(iters, sink);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}
+
+// ------------------------------------------------ global -> LDS feed probe
+// Every wavefront keeps K 1-KB direct-to-LDS loads in flight, waits for them, and repeats, walking a
+// region of `span` bytes (power of two).  With a span that fits L2 this measures the L2 -> LDS path,
+// with a larger one the MALL / HBM mix.  A 256x256x64 bf16 GEMM tile step needs 64 KB per CU.
+template <int K>
+__global__ __launch_bounds__(512) void feed_probe_kernel(const char* src, size_t span_mask, int iters, int* sink) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const size_t base = (size_t)blockIdx.x * 7919u * 65536u;
+  for (int it = 0; it < iters; it++) {
+#pragma unroll
+    for (int i = 0; i < K; i++) {
+      const size_t off = (base + ((size_t)it * 8 * K + wave * K + i) * 1024 + lane * 16) & span_mask;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + off),
+                                       (__attribute__((address_space(3))) void*)(smem + (wave * K + i) * 1024), 16, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+    __builtin_amdgcn_s_barrier();
+  }
+  if (iters < 0 && smem[threadIdx.x] == 123) sink[0] = 1;
+}
+
+int launch_feed_probe(as_ctx* ctx, int k, const void* buf, size_t span, int iters, int blocks, int* sink, hipStream_t st) {
+  const size_t mask = (span - 1) & ~(size_t)15;
+#define FEED(K) { AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(feed_probe_kernel<K>), hipFuncAttributeMaxDynamicSharedMemorySize, 8 * K * 1024)); \
+                  feed_probe_kernel<K><<<blocks, 512, 8 * K * 1024, st>>>((const char*)buf, mask, iters, sink); }
+  switch (k) { case 1: FEED(1) break; case 2: FEED(2) break; case 4: FEED(4) break; case 8: FEED(8) break;
+               default: return as_fail(ctx, AS_ERR_SHAPE, "feed probe: loads in flight per wave must be 1, 2, 4 or 8"); }
+#undef FEED
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }

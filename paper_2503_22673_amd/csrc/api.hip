@@ -28,11 +28,18 @@ static int check_config(const as_model_config* c) {
   if (c->mode != AS_FP32 && c->mode != AS_BF16) return as_fail(nullptr, AS_ERR_CONFIG, "mode");
   if (c->train_mode != AS_LORA && c->train_mode != AS_FULL) return as_fail(nullptr, AS_ERR_CONFIG, "train_mode");
   if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f)) return as_fail(nullptr, AS_ERR_CONFIG, "rms_eps / rope_base");
-  if (c->n_experts != 0 || c->top_k != 0) return as_fail(nullptr, AS_ERR_CONFIG, "mixture-of-experts layers are not supported by this build");
+  const bool moe = c->n_experts != 0 || c->top_k != 0;
+  if (moe) {
+    if (c->n_experts < 8 || c->n_experts > 64 || c->n_experts % 8) return as_fail(nullptr, AS_ERR_CONFIG, "n_experts must be a multiple of 8 in [8, 64]");
+    if (c->top_k != 2) return as_fail(nullptr, AS_ERR_CONFIG, "top_k must be 2");
+    if (c->train_mode != AS_LORA) return as_fail(nullptr, AS_ERR_CONFIG, "mixture-of-experts models are trained with adapters only");
+    if (c->lora_targets & 0x70u) return as_fail(nullptr, AS_ERR_CONFIG, "adapters on expert projections are not supported");
+  }
   if (c->train_mode == AS_LORA) {
     if (c->lora_rank < 1 || c->lora_rank > 256) return as_fail(nullptr, AS_ERR_CONFIG, "lora_rank must be in [1, 256]");
-    if (!(c->lora_targets & 0x7f)) return as_fail(nullptr, AS_ERR_CONFIG, "LoRA mode needs at least one target");
-    if (c->lora_targets & ~0x7fu) return as_fail(nullptr, AS_ERR_CONFIG, "router adapters need a mixture-of-experts model");
+    if (!(c->lora_targets & 0xff)) return as_fail(nullptr, AS_ERR_CONFIG, "LoRA mode needs at least one target");
+    if (c->lora_targets & ~0xffu) return as_fail(nullptr, AS_ERR_CONFIG, "unknown adapter target");
+    if (!moe && (c->lora_targets & 0x80u)) return as_fail(nullptr, AS_ERR_CONFIG, "router adapters need a mixture-of-experts model");
   } else if (c->lora_rank != 0 || c->lora_targets != 0) {
     return as_fail(nullptr, AS_ERR_CONFIG, "full fine-tuning takes no adapters");
   }
@@ -300,6 +307,10 @@ struct Acts {           // activations of one layer kept for its backward
   float *rstd1, *rstd2, *lse;
   void *a, *qkv, *o, *h_mid, *b, *gu, *m;
   void *u_qkv, *u_o, *u_gu, *u_d;
+  // mixture-of-experts layers: gu / m hold the 2N (token, slot) rows grouped by expert
+  float *rl, *wsel;                      // router logits [N, E], routing weights [N, 2]
+  int32_t *sel, *eoff, *pos, *perm;      // chosen experts [N, 2], expert row offsets [E+1], pair -> row, row -> pair
+  void *y_perm, *u_r;                    // expert outputs [2N, d], router adapter activations [N, rp]
 };
 
 struct Plan {
@@ -314,7 +325,8 @@ struct Plan {
   void *dh, *dh2, *dm, *dgu, *db, *d_o, *dqkv, *da;
   void *du_qkv, *du_o, *du_gu, *du_d;
   void *wT, *xT, *dyT, *uT, *duT, *attT;
-  std::vector<LoraSlot> lora;            // L * 7
+  void *xbp, *dlogit, *du_r, *wrT;       // MoE scratch: permuted rows [2N, d], router logit gradient [N, E], [N, rp], router weight transpose [d, E]
+  std::vector<LoraSlot> lora;            // L * AS_N_TARGETS
   std::vector<void*> A_qkv, At_qkv, A_gu, At_gu;   // per layer concatenated groups
   size_t partial_floats;
 };
@@ -335,6 +347,7 @@ static void target_dims(const as_model_config& c, int t, int* din, int* dout) {
     case AS_T_K: case AS_T_V: *din = c.d_model; *dout = Dkv; break;
     case AS_T_O: *din = D; *dout = c.d_model; break;
     case AS_T_GATE: case AS_T_UP: *din = c.d_model; *dout = c.ffn; break;
+    case AS_T_ROUTER: *din = c.d_model; *dout = c.n_experts; break;
     default: *din = c.ffn; *dout = c.d_model; break;
   }
 }
@@ -349,6 +362,8 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   P.Mc = (int)std::min<int64_t>(4096, cdiv(std::max(P.N, 1), 64) * 64);
   P.Np = (int)cdiv(P.N, 64) * 64;
   const size_t N = (size_t)P.N, es = (size_t)P.es;
+  const bool moe = c.n_experts > 0;
+  const size_t NF = moe ? 2 * N : N, E = (size_t)c.n_experts;      // rows of the FFN intermediates
   auto on = [&](int t) { return !full && ((c.lora_targets >> t) & 1u); };
   P.n_qkv = on(AS_T_Q) + on(AS_T_K) + on(AS_T_V);
   P.n_gu = on(AS_T_GATE) + on(AS_T_UP);
@@ -371,18 +386,22 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   const int n_sets = c.recompute == 1 ? 1 : P.L;
   P.acts.resize(n_sets);
   void *sh_a = nullptr, *sh_b = nullptr, *sh_m = nullptr;
-  if (c.recompute == 2) { sh_a = w.take(N * P.d * es); sh_b = w.take(N * P.d * es); sh_m = w.take(N * P.F * es); }
+  if (c.recompute == 2) { sh_a = w.take(N * P.d * es); sh_b = w.take(N * P.d * es); sh_m = w.take(NF * P.F * es); }
   for (int s = 0; s < n_sets; s++) {
     Acts& a = P.acts[s];
     a.rstd1 = (float*)w.take(N * 4); a.rstd2 = (float*)w.take(N * 4);
     a.lse = (float*)w.take(N * c.n_q_heads * 4);
     a.qkv = w.take(N * P.QKV * es); a.o = w.take(N * P.D * es);
     a.h_mid = w.take(N * P.d * es);
-    a.gu = w.take(N * 2 * P.F * es);
+    a.gu = w.take(NF * 2 * P.F * es);
     if (c.recompute == 2) { a.a = sh_a; a.b = sh_b; a.m = sh_m; }
-    else { a.a = w.take(N * P.d * es); a.b = w.take(N * P.d * es); a.m = w.take(N * P.F * es); }
+    else { a.a = w.take(N * P.d * es); a.b = w.take(N * P.d * es); a.m = w.take(NF * P.F * es); }
     a.u_qkv = w.take(N * P.n_qkv * rp * es); a.u_o = w.take(on(AS_T_O) ? N * rp * es : 0);
     a.u_gu = w.take(N * P.n_gu * rp * es); a.u_d = w.take(on(AS_T_DOWN) ? N * rp * es : 0);
+    a.rl = (float*)w.take(N * E * 4); a.wsel = (float*)w.take(moe ? N * 2 * 4 : 0);
+    a.sel = (int32_t*)w.take(moe ? N * 2 * 4 : 0); a.eoff = (int32_t*)w.take(moe ? (E + 1) * 4 : 0);
+    a.pos = (int32_t*)w.take(moe ? N * 2 * 4 : 0); a.perm = (int32_t*)w.take(moe ? N * 2 * 4 : 0);
+    a.y_perm = w.take(moe ? 2 * N * P.d * es : 0); a.u_r = w.take(on(AS_T_ROUTER) ? N * rp * es : 0);
   }
   P.hf = w.take(N * P.d * es); P.dhf = w.take(N * P.d * es);
   P.logits = (float*)w.take((size_t)P.Mc * P.V * 4);
@@ -392,15 +411,17 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   P.hfT = w.take(full ? (size_t)P.Mc * P.d * es : 0);
   P.delta = (float*)w.take(N * c.n_q_heads * 4);
   P.dh = w.take(N * P.d * es); P.dh2 = w.take(N * P.d * es);
-  P.dm = w.take(N * P.F * es); P.dgu = w.take(N * 2 * P.F * es); P.db = w.take(N * P.d * es);
+  P.dm = w.take(NF * P.F * es); P.dgu = w.take(NF * 2 * P.F * es); P.db = w.take(N * P.d * es);
   P.d_o = w.take(N * P.D * es); P.dqkv = w.take(N * P.QKV * es); P.da = w.take(N * P.d * es);
   P.du_qkv = w.take(N * P.n_qkv * rp * es); P.du_o = w.take(on(AS_T_O) ? N * rp * es : 0);
   P.du_gu = w.take(N * P.n_gu * rp * es); P.du_d = w.take(on(AS_T_DOWN) ? N * rp * es : 0);
   size_t wmax = std::max({(size_t)P.QKV * P.d, (size_t)P.d * P.D, (size_t)2 * P.F * P.d, (size_t)P.d * P.F});
   P.wT = w.take(wmax * es);
-  const bool need_T = full || (c.lora_targets & 0x7f);
+  P.xbp = w.take(moe ? 2 * N * P.d * es : 0); P.dlogit = w.take(N * E * es);
+  P.du_r = w.take(on(AS_T_ROUTER) ? N * rp * es : 0); P.wrT = w.take((size_t)P.d * E * es);
+  const bool need_T = full || (c.lora_targets & 0xff);
   size_t xmax = std::max({(size_t)P.d, (size_t)P.D, (size_t)P.F});
-  size_t ymax = std::max({(size_t)P.QKV, (size_t)2 * P.F, (size_t)P.d});
+  size_t ymax = std::max({(size_t)P.QKV, moe ? E : (size_t)2 * P.F, (size_t)P.d});
   const size_t Np = (size_t)P.Np;
   P.xT = w.take(need_T ? xmax * Np * es : 0);
   P.dyT = w.take(need_T ? ymax * Np * es : 0);
@@ -410,15 +431,15 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   P.attT = w.take(c.mode == AS_BF16 ? (size_t)(2 * P.D + P.Dkv) * Np * es : 0);   // token-major K, Q, dO (V in forward)
 
   // prepared adapter copies
-  P.lora.assign((size_t)P.L * 7, LoraSlot());
+  P.lora.assign((size_t)P.L * AS_N_TARGETS, LoraSlot());
   P.A_qkv.assign(P.L, nullptr); P.At_qkv.assign(P.L, nullptr); P.A_gu.assign(P.L, nullptr); P.At_gu.assign(P.L, nullptr);
   size_t part = 0;
   for (int l = 0; l < P.L && !full; l++) {
     P.A_qkv[l] = w.take((size_t)P.n_qkv * rp * P.d * es); P.At_qkv[l] = w.take((size_t)P.d * P.n_qkv * rp * es);
     P.A_gu[l] = w.take((size_t)P.n_gu * rp * P.d * es); P.At_gu[l] = w.take((size_t)P.d * P.n_gu * rp * es);
     int sq = 0, sg = 0;
-    for (int t = 0; t < 7; t++) {
-      LoraSlot& s = P.lora[(size_t)l * 7 + t];
+    for (int t = 0; t < AS_N_TARGETS; t++) {
+      LoraSlot& s = P.lora[(size_t)l * AS_N_TARGETS + t];
       s.on = on(t);
       if (!s.on) continue;
       target_dims(c, t, &s.din, &s.dout);
@@ -479,13 +500,13 @@ struct Step {
     return launch_gemm_off(ctx, mode, gv, g, m_off, st);
   }
 
-  LoraSlot& slot(int l, int t) { return P.lora[(size_t)l * 7 + t]; }
+  LoraSlot& slot(int l, int t) { return P.lora[(size_t)l * AS_N_TARGETS + t]; }
 
   int prep_lora(int l) {
     const as_layer_lora& Lr = lora->layers[l];
     const float s = c.lora_alpha / (float)c.lora_rank;
     const int r = c.lora_rank, rp = P.rp;
-    for (int t = 0; t < 7; t++) {
+    for (int t = 0; t < AS_N_TARGETS; t++) {
       LoraSlot& sl = slot(l, t);
       if (!sl.on) continue;
       int64_t ld_at = (t <= AS_T_V) ? (int64_t)P.n_qkv * rp : (t == AS_T_GATE || t == AS_T_UP) ? (int64_t)P.n_gu * rp : rp;
@@ -525,6 +546,7 @@ struct Step {
       if (s.on && (rc = gemm(N, rp, a.o, D, s.A, D, D, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_o, rp))) return rc;
       if ((rc = gemm(N, d, a.o, D, w.wo, D, D, s.on ? a.u_o : nullptr, rp, s.Bs, rp, s.on ? rp : 0, h_in, d, a.h_mid, d))) return rc; }
     if ((rc = launch_rmsnorm_fwd(ctx, mode, N, d, a.h_mid, nullptr, nullptr, w.g2, c.rms_eps, a.b, a.rstd2, st))) return rc;
+    if (c.n_experts) return forward_moe(l, a);
     const int ldg = P.n_gu * rp;
     if (P.n_gu && (rc = gemm(N, ldg, a.b, d, P.A_gu[l], d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_gu, ldg))) return rc;
     const void* wg[2] = {w.wgate, w.wup};
@@ -541,13 +563,79 @@ struct Step {
     return AS_OK;
   }
 
+  // one product over the rows of expert e only: rows eoff[e] .. eoff[e+1] of A and C
+  int gemm_expert(const int32_t* eoff, int e, int N, const void* A, int64_t lda, const void* B, int64_t ldb, int K, void* C, int64_t ldc) {
+    GemmParams g; memset(&g, 0, sizeof g);
+    g.seg[0] = {A, B, lda, ldb, K}; g.nseg = 1;
+    g.M = P.N; g.N = N; g.C = C; g.ldc = ldc; g.alpha = 1.f; g.splitk = 1;
+    g.grp_off = eoff; g.grp = e;
+    return launch_gemm_off(ctx, mode, gv, g, 0, st);
+  }
+
+  // Sparse FFN (top-2 of E experts): router, grouping of the (token, slot) pairs by expert, one
+  // SwiGLU FFN per expert over its rows, weighted sum back in token order on top of the residual.
+  int forward_moe(int l, Acts& a) {
+    const as_layer_weights& w = W->layers[l];
+    const int N = P.N, d = P.d, F = P.F, rp = P.rp, E = c.n_experts;
+    int rc;
+    LoraSlot& s = slot(l, AS_T_ROUTER);
+    if (s.on && (rc = gemm(N, rp, a.b, d, s.A, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_r, rp))) return rc;
+    if ((rc = gemm(N, E, a.b, d, w.wrouter, d, d, s.on ? a.u_r : nullptr, rp, s.Bs, rp, s.on ? rp : 0, nullptr, 0, a.rl, E, 1))) return rc;
+    if ((rc = launch_moe_route(ctx, a.rl, N, E, a.sel, a.wsel, st))) return rc;
+    if ((rc = launch_moe_permute(ctx, a.sel, N, E, a.eoff, a.pos, a.perm, st))) return rc;
+    if ((rc = launch_moe_gather(ctx, mode, a.b, a.perm, nullptr, 2 * N, d, P.xbp, st))) return rc;
+    const void* wg[2] = {w.wgate, w.wup};
+    for (int e = 0; e < E; e++)
+      for (int i = 0; i < 2; i++)
+        if ((rc = gemm_expert(a.eoff, e, F, P.xbp, d, off(wg[i], (size_t)e * F * d), d, d, off(a.gu, (size_t)i * F), 2 * F))) return rc;
+    if ((rc = launch_swiglu_fwd(ctx, mode, 2 * N, F, a.gu, a.m, st))) return rc;
+    for (int e = 0; e < E; e++)
+      if ((rc = gemm_expert(a.eoff, e, d, a.m, F, off(w.wdown, (size_t)e * d * F), F, F, a.y_perm, d))) return rc;
+    return launch_moe_combine(ctx, mode, a.h_mid, a.y_perm, a.pos, a.wsel, N, d, P.h[l + 1], st);
+  }
+
+  // P.dh (gradient of the layer output) -> P.db (gradient of the second norm's output)
+  int backward_moe(int l, Acts& a) {
+    const as_layer_weights& w = W->layers[l];
+    const int N = P.N, d = P.d, F = P.F, rp = P.rp, E = c.n_experts;
+    int rc;
+    if ((rc = launch_moe_dlogit(ctx, mode, P.dh, a.y_perm, a.pos, a.sel, a.wsel, N, d, E, P.dlogit, st))) return rc;
+    if ((rc = launch_moe_gather(ctx, mode, P.dh, a.perm, a.wsel, 2 * N, d, P.xbp, st))) return rc;        // w * dy, grouped
+    for (int e = 0; e < E; e++) {
+      if ((rc = transpose(d, F, off(w.wdown, (size_t)e * d * F), F, P.wT, d))) return rc;                 // [F, d]
+      if ((rc = gemm_expert(a.eoff, e, F, P.xbp, d, P.wT, d, d, P.dm, F))) return rc;
+    }
+    if ((rc = launch_swiglu_bwd(ctx, mode, 2 * N, F, P.dm, a.gu, P.dgu, st))) return rc;
+    for (int e = 0; e < E; e++) {
+      if ((rc = transpose(F, d, off(w.wgate, (size_t)e * F * d), d, P.wT, 2 * F))) return rc;             // [d, 2F]
+      if ((rc = transpose(F, d, off(w.wup, (size_t)e * F * d), d, off(P.wT, (size_t)F), 2 * F))) return rc;
+      if ((rc = gemm_expert(a.eoff, e, d, P.dgu, 2 * F, P.wT, 2 * F, 2 * F, P.xbp, d))) return rc;        // grouped gradient of the expert inputs
+    }
+    if ((rc = launch_moe_combine(ctx, mode, nullptr, P.xbp, a.pos, nullptr, N, d, P.da, st))) return rc;  // back to token order
+    // router: db = (expert part) + dlogit Wr + du_r A
+    LoraSlot& s = slot(l, AS_T_ROUTER);
+    if ((rc = transpose(E, d, w.wrouter, d, P.wrT, E))) return rc;                                        // [d, E]
+    if (s.on && (rc = gemm(N, rp, P.dlogit, E, s.Bst, E, E, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.du_r, rp))) return rc;
+    if ((rc = gemm(N, d, P.dlogit, E, P.wrT, E, E, s.on ? P.du_r : nullptr, rp, s.At, rp, s.on ? rp : 0, P.da, d, P.db, d))) return rc;
+    if (s.on) {
+      if (!tn_path()) {
+        if ((rc = transpose_tok(E, P.dlogit, E, P.dyT))) return rc;
+        if ((rc = transpose_tok(d, a.b, d, P.xT))) return rc;
+      }
+      if ((rc = transpose_tok(rp, a.u_r, rp, P.uT))) return rc;
+      if ((rc = transpose_tok(rp, P.du_r, rp, P.duT))) return rc;
+      if ((rc = lora_grads(l, AS_T_ROUTER, P.dlogit, E, a.b, d, P.dyT, P.xT))) return rc;
+    }
+    return AS_OK;
+  }
+
   // the activations that are cheaper to rebuild than to keep: both norm outputs and the SwiGLU product
   int rebuild_cheap(int l, Acts& a) {
     const as_layer_weights& w = W->layers[l];
     int rc;
     if ((rc = launch_rmsnorm_fwd(ctx, mode, P.N, P.d, P.h[l], nullptr, nullptr, w.g1, c.rms_eps, a.a, a.rstd1, st))) return rc;
     if ((rc = launch_rmsnorm_fwd(ctx, mode, P.N, P.d, a.h_mid, nullptr, nullptr, w.g2, c.rms_eps, a.b, a.rstd2, st))) return rc;
-    return launch_swiglu_fwd(ctx, mode, P.N, P.F, a.gu, a.m, st);
+    return launch_swiglu_fwd(ctx, mode, c.n_experts ? 2 * P.N : P.N, P.F, a.gu, a.m, st);
   }
 
   // nothing to compute: loss, count and every gradient are exactly zero
@@ -557,7 +645,7 @@ struct Step {
     const size_t d = P.d, D = P.D, Dkv = P.Dkv, F = P.F;
     for (int l = 0; l < P.L; l++) {
       if (c.train_mode == AS_LORA) {
-        for (int t = 0; t < 7; t++) {
+        for (int t = 0; t < AS_N_TARGETS; t++) {
           if (!((c.lora_targets >> t) & 1u)) continue;
           int din, dout; target_dims(c, t, &din, &dout);
           if ((rc = launch_fill_zero(ctx, G->lora_layers[l].a[t], (size_t)c.lora_rank * din * 4, st))) return rc;
@@ -617,6 +705,8 @@ struct Step {
     const bool full = c.train_mode == AS_FULL;
     const int N = P.N, d = P.d, D = P.D, Dkv = P.Dkv, QKV = P.QKV, F = P.F, rp = P.rp;
     int rc;
+    if (c.n_experts) { if ((rc = backward_moe(l, a))) return rc; }
+    else {
     // ---- down projection
     { LoraSlot& s = slot(l, AS_T_DOWN);
       if ((rc = transpose(d, F, w.wdown, F, P.wT, d))) return rc;                       // [F, d]
@@ -659,6 +749,7 @@ struct Step {
         if ((rc = weight_grad(G->w_layers[l].wgate, F, d, P.dyT, P.xT))) return rc;
         if ((rc = weight_grad(G->w_layers[l].wup, F, d, off(P.dyT, (size_t)F * P.Np), P.xT))) return rc;
       } }
+    }
     // ---- second norm
     if (full && (rc = launch_rmsnorm_dgain(ctx, mode, N, d, P.db, nullptr, a.h_mid, a.rstd2, P.gpart, 256, G->w_layers[l].g2, st))) return rc;
     if ((rc = launch_rmsnorm_bwd(ctx, mode, N, d, P.db, nullptr, a.h_mid, w.g2, a.rstd2, P.dh, P.dh2, st))) return rc;
@@ -803,11 +894,12 @@ extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lo
     const as_layer_weights& w = weights->layers[l];
     if (!w.g1 || !w.wq || !w.wk || !w.wv || !w.wo || !w.g2 || !w.wgate || !w.wup || !w.wdown)
       return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL weight in layer %d", l);
+    if (c.n_experts && !w.wrouter) return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL router weight in layer %d", l);
   }
   if (!full) {
     if (!lora || !lora->layers || !grads->lora_layers) return as_fail(ctx, AS_ERR_NULL, "as_train_step: LoRA mode needs adapters and their gradient buffers");
     for (int l = 0; l < c.n_layers; l++)
-      for (int t = 0; t < 7; t++)
+      for (int t = 0; t < AS_N_TARGETS; t++)
         if ((c.lora_targets >> t) & 1u)
           if (!lora->layers[l].a[t] || !lora->layers[l].b[t] || !grads->lora_layers[l].a[t] || !grads->lora_layers[l].b[t])
             return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL adapter or gradient for target %s in layer %d", kTargetName[t], l);

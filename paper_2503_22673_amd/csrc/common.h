@@ -74,6 +74,9 @@ struct GemmParams {
   const void* R; int64_t ldr;
   int accumulate;          // C += result (float output only)
   int splitk; float* partial;   // splitk > 1: partial [splitk, M, N] float, reduced afterwards
+  // grouped rows (mixture of experts): with grp_off set, the product covers rows
+  // [grp_off[grp], grp_off[grp+1]) of A, R and C (device-side table), at most M of them
+  const int* grp_off; int grp;
 };
 int launch_gemm(as_ctx* ctx, int mode, int variant, const GemmParams& p, hipStream_t st);
 // live rows = *p.m_dev - m_off, clamped to [0, p.M]
@@ -126,6 +129,14 @@ int launch_rmsnorm_dgain(as_ctx* ctx, int mode, int n, int d, const void* dy, co
                          hipStream_t st);
 int launch_rope(as_ctx* ctx, int mode, int n, int n_heads, int dh, void* x, int64_t ldx,
                 const int32_t* seg_start, const float* cosb, const float* sinb, int inverse, hipStream_t st);
+// mixture-of-experts routing and row grouping (moe.hip)
+int launch_moe_route(as_ctx* ctx, const float* logit, int n, int E, int32_t* sel, float* w, hipStream_t st);
+int launch_moe_permute(as_ctx* ctx, const int32_t* sel, int n, int E, int32_t* eoff, int32_t* pos, int32_t* perm, hipStream_t st);
+int launch_moe_gather(as_ctx* ctx, int mode, const void* src, const int32_t* perm, const float* w, int rows, int d, void* out, hipStream_t st);
+int launch_moe_combine(as_ctx* ctx, int mode, const void* res, const void* y, const int32_t* pos, const float* w, int n, int d,
+                       void* out, hipStream_t st);
+int launch_moe_dlogit(as_ctx* ctx, int mode, const void* dy, const void* y, const int32_t* pos, const int32_t* sel, const float* w,
+                      int n, int d, int Epad, void* dlogit, hipStream_t st);
 int launch_swiglu_fwd(as_ctx* ctx, int mode, int64_t n, int F, const void* gu, void* m, hipStream_t st);
 int launch_swiglu_bwd(as_ctx* ctx, int mode, int64_t n, int F, const void* dm, const void* gu, void* dgu, hipStream_t st);
 // out[c, r] = in[r, c] for r < rows_pad, reading zero for r >= rows (and, with rows_dev, for rows at

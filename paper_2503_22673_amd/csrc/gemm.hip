@@ -24,10 +24,24 @@ __device__ __forceinline__ KRange split_range(int K, int BK, int splitk, int z) 
   return r;
 }
 
+// Live row count of this launch and, for grouped rows, the first row of the group (rb): rows of A, R
+// and C are then rb + (0 .. M-1).  mmax is the largest row index a clamped load may touch.
+__device__ __forceinline__ int gemm_rows(const GemmParams& p, int m_off, int& rb, int& mmax) {
+  int M = p.m_dev ? min(p.M, *p.m_dev - m_off) : p.M;
+  rb = 0; mmax = p.M - 1;
+  if (p.grp_off) {
+    rb = p.grp_off[p.grp];
+    M = min(M, p.grp_off[p.grp + 1] - rb);
+    mmax = max(M, 1) - 1;
+  }
+  return M;
+}
+
 template <typename T>
-__device__ __forceinline__ void store_out(const GemmParams& p, int z, int row, int col, float v) {
+__device__ __forceinline__ void store_out(const GemmParams& p, int z, int row, int col, float v, int rb) {
   if (p.splitk > 1) { p.partial[((int64_t)z * p.M + row) * p.N + col] = v; return; }
   v *= p.alpha;
+  row += rb;
   if (p.R) v += to_f<T>(((const T*)p.R)[(int64_t)row * p.ldr + col]);
   if (p.c_f32) {
     float* c = (float*)p.C + (int64_t)row * p.ldc + col;
@@ -43,7 +57,8 @@ __global__ __launch_bounds__(256) void gemm_fma_kernel(GemmParams p, int m_off) 
   constexpr int BM = 64, BN = 64, BK = 16;
   __shared__ float As[BK][BM + 4];
   __shared__ float Bs[BK][BN + 4];
-  int M = p.m_dev ? min(p.M, *p.m_dev - m_off) : p.M;
+  int rb, mmax;
+  int M = gemm_rows(p, m_off, rb, mmax);
   int row0 = blockIdx.y * BM, col0 = blockIdx.x * BN, z = blockIdx.z;
   if (row0 >= M) return;
   int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
@@ -59,7 +74,7 @@ __global__ __launch_bounds__(256) void gemm_fma_kernel(GemmParams p, int m_off) 
       for (int q = 0; q < 4; q++) {
         int k = k0 + lk + q;
         int ar = row0 + lr, br = col0 + lr;
-        As[lk + q][lr] = (ar < M && k < K) ? to_f<T>(A[(int64_t)ar * lda + k]) : 0.f;
+        As[lk + q][lr] = (ar < M && k < K) ? to_f<T>(A[(int64_t)(rb + ar) * lda + k]) : 0.f;
         Bs[lk + q][lr] = (br < p.N && k < K) ? to_f<T>(B[(int64_t)br * ldb + k]) : 0.f;
       }
       __syncthreads();
@@ -81,7 +96,7 @@ __global__ __launch_bounds__(256) void gemm_fma_kernel(GemmParams p, int m_off) 
 #pragma unroll
     for (int j = 0; j < 4; j++) {
       int r = row0 + ty * 4 + i, c = col0 + tx * 4 + j;
-      if (r < M && c < p.N) store_out<T>(p, z, r, c, acc[i][j]);
+      if (r < M && c < p.N) store_out<T>(p, z, r, c, acc[i][j], rb);
     }
 }
 
@@ -93,7 +108,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 // element loops; `full` tiles skip the bounds tests.
 template <int TM, int TN>
 __device__ __forceinline__ void gemm_epilogue(const GemmParams& p, f32x16 (&acc)[TM][TN], int M, int z, int row0, int col0,
-                                              int rb0, int cb0, bool full) {
+                                              int rb0, int cb0, bool full, int rb) {
   auto each = [&](auto f) {
 #pragma unroll
     for (int i = 0; i < TM; i++)
@@ -103,13 +118,13 @@ __device__ __forceinline__ void gemm_epilogue(const GemmParams& p, f32x16 (&acc)
 #pragma unroll
         for (int e = 0; e < 16; e++) {
           const int r = rb0 + i * 32 + 8 * (e >> 2) + (e & 3);
-          if (full || (r < M && c < p.N)) f(r, c, acc[i][j][e]);
+          if (full || (r < M && c < p.N)) f(r + rb, c, acc[i][j][e]);
         }
       }
   };
   if (p.splitk > 1) {
     float* part = p.partial + (int64_t)z * p.M * p.N;
-    each([&](int r, int c, float v) { part[(int64_t)r * p.N + c] = v; });
+    each([&](int r, int c, float v) { part[(int64_t)(r - rb) * p.N + c] = v; });
   } else if (p.c_f32) {
     float* C = (float*)p.C; const float alpha = p.alpha; const bf16_t* R = (const bf16_t*)p.R;
     if (p.accumulate || R)
@@ -139,7 +154,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p, i
   bf16_t* sA = (bf16_t*)smem;                            // [2][BM][LS]
   bf16_t* sB = sA + 2 * BM * LS;                         // [2][BN][LS]
 
-  const int M = p.m_dev ? min(p.M, *p.m_dev - m_off) : p.M;
+  int rb, mmax;
+  const int M = gemm_rows(p, m_off, rb, mmax);
   // XCD de-interleave, then grouped walk over the tile grid
   int nblk = tiles_m * tiles_n, pid = blockIdx.x, z = blockIdx.y;
   int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
@@ -167,13 +183,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p, i
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
-  u32x4 ra[CA], rb[CB];
+  u32x4 ra[CA], rbv[CB];
   // per-thread row offsets inside the tile are fixed; only the k offset moves
   int64_t offA[CA], offB[CB];
   {
-    const int mclamp = p.M - 1, nclamp = p.N - 1;
+    const int mclamp = mmax, nclamp = p.N - 1;
 #pragma unroll
-    for (int i = 0; i < CA; i++) { int c = tid + i * NT; offA[i] = (int64_t)min(row0 + (c >> 3), mclamp); }
+    for (int i = 0; i < CA; i++) { int c = tid + i * NT; offA[i] = (int64_t)(rb + min(row0 + (c >> 3), mclamp)); }
 #pragma unroll
     for (int i = 0; i < CB; i++) { int c = tid + i * NT; offB[i] = (int64_t)min(col0 + (c >> 3), nclamp); }
   }
@@ -196,7 +212,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p, i
 #pragma unroll
     for (int i = 0; i < CB; i++) {
       u32x4 v = *reinterpret_cast<const u32x4*>(B + offB[i] * ldb + ks);
-      rb[i] = in ? v : (u32x4){0u, 0u, 0u, 0u};
+      rbv[i] = in ? v : (u32x4){0u, 0u, 0u, 0u};
     }
   };
   auto stash = [&](int buf) {
@@ -204,7 +220,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p, i
 #pragma unroll
     for (int i = 0; i < CA; i++) { int c = tid + i * NT; *reinterpret_cast<u32x4*>(a + (c >> 3) * LS + kc) = ra[i]; }
 #pragma unroll
-    for (int i = 0; i < CB; i++) { int c = tid + i * NT; *reinterpret_cast<u32x4*>(b + (c >> 3) * LS + kc) = rb[i]; }
+    for (int i = 0; i < CB; i++) { int c = tid + i * NT; *reinterpret_cast<u32x4*>(b + (c >> 3) * LS + kc) = rbv[i]; }
   };
 
   if (nt > 0) { fetch(0); stash(0); }
@@ -232,7 +248,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p, i
   }
 
   gemm_epilogue<TM, TN>(p, acc, M, z, row0, col0, row0 + wm * TM * 32 + 4 * (lane >> 5), col0 + wn * TN * 32 + (lane & 31),
-                        (row0 + BM <= M) && (col0 + BN <= p.N));
+                        (row0 + BM <= M) && (col0 + BN <= p.N), rb);
 }
 
 // Same tiling, but tiles travel global -> LDS directly (global_load_lds_dwordx4: a wavefront
@@ -261,7 +277,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
   bf16_t* sA = (bf16_t*)smem;                            // [2][BM][64]
   bf16_t* sB = sA + 2 * BM * BK;                         // [2][BN][64]
 
-  const int M = p.m_dev ? min(p.M, *p.m_dev - m_off) : p.M;
+  int rb, mmax;
+  const int M = gemm_rows(p, m_off, rb, mmax);
   int nblk = tiles_m * tiles_n, pid = blockIdx.x, z = blockIdx.y;
   int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
   int logical = (MAP == 1) ? pid : xcd * q8 + min(xcd, rem) + loc;
@@ -292,9 +309,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
   const int lrow = lane >> 3;
   int rowA[LA], rowB[LB];
   {
-    const int mclamp = p.M - 1, nclamp = p.N - 1;
+    const int mclamp = mmax, nclamp = p.N - 1;
 #pragma unroll
-    for (int i = 0; i < LA; i++) rowA[i] = min(row0 + (wave * LA + i) * 8 + lrow, mclamp);
+    for (int i = 0; i < LA; i++) rowA[i] = rb + min(row0 + (wave * LA + i) * 8 + lrow, mclamp);
 #pragma unroll
     for (int i = 0; i < LB; i++) rowB[i] = min(col0 + (wave * LB + i) * 8 + lrow, nclamp);
   }
@@ -335,7 +352,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
     const int64_t lda = first ? p.seg[0].lda : p.seg[1].lda, ldb = first ? p.seg[0].ldb : p.seg[1].ldb;
     const int k = (first ? kr0.beg + it : kr1.beg + it - nt0) * BK;
     const int r = tid % BM;                              // thread -> one row of A, then one row of B
-    const bf16_t* ptr = (tid < BM) ? A + (int64_t)min(row0 + r, p.M - 1) * lda + k
+    const bf16_t* ptr = (tid < BM) ? A + (int64_t)(rb + min(row0 + r, mmax)) * lda + k
                                    : B + (int64_t)min(col0 + (tid - BM) % BN, p.N - 1) * ldb + k;
     asm volatile("global_load_dword %0, %1, off" : "+v"(pf_reg) : "v"(ptr) : "memory");
   };
@@ -412,7 +429,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
     asm volatile("" : "+v"(pf_reg));
   }
   gemm_epilogue<TM, TN>(p, acc, M, z, row0, col0, row0 + wm * TM * 32 + 4 * (lane >> 5), col0 + wn * TN * 32 + (lane & 31),
-                        (row0 + BM <= M) && (col0 + BN <= p.N));
+                        (row0 + BM <= M) && (col0 + BN <= p.N), rb);
 }
 
 template <int BM, int BN, int WM, int WN, bool DB, int SWZ, int PF = 0, int MAP = 0>
@@ -482,6 +499,7 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
   if (p.splitk < 1) p.splitk = 1;
   if (p.splitk > 1 && !p.partial) return as_fail(ctx, AS_ERR_WORKSPACE, "gemm: split-K needs a partial buffer");
   if (p.accumulate && !p.c_f32) return as_fail(ctx, AS_ERR_SHAPE, "gemm: accumulate needs float output");
+  if (p.grp_off && p.splitk > 1) return as_fail(ctx, AS_ERR_SHAPE, "gemm: grouped rows and split-K do not combine");
   if (variant < 0 || (variant > 2 && (variant < 10 || variant > 25))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
   bool use_mfma = (mode == AS_BF16) && variant != 1 && mfma_ok(p);
   if (variant >= 2 && !use_mfma) return as_fail(ctx, AS_ERR_SHAPE, "gemm: MFMA kernel needs bf16 and 8-element alignment");

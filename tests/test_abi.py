@@ -33,7 +33,8 @@ def test_config_validation(B):
     ctx = B.Context(ok)
     ctx.close()
     bad = [dict(head_dim=48), dict(n_q_heads=3), dict(struct_size=4), dict(lora_rank=0), dict(lora_targets=0),
-           dict(mode=7), dict(n_experts=8, top_k=2), dict(recompute=5), dict(vocab=1), dict(lora_rank=1000)]
+           dict(mode=7), dict(n_experts=8, top_k=1), dict(n_experts=6, top_k=2), dict(n_experts=8, top_k=2, lora_targets=0x1f),
+           dict(lora_targets=0x81), dict(n_experts=8, top_k=2, train_mode=1, lora_rank=0, lora_targets=0), dict(recompute=5), dict(vocab=1), dict(lora_rank=1000)]
     for kw in bad:
         c = B.make_config(sh)
         for k, v in kw.items():
@@ -41,6 +42,8 @@ def test_config_validation(B):
         with pytest.raises(B.ASError) as e:
             B.Context(c)
         assert e.value.code == B.ERR["CONFIG"], kw
+    moe = B.make_config(synth.CONFIGS[5])
+    B.Context(moe).close()
     h = C.c_void_p()
     assert B.lib.as_create(C.byref(h), None, 0) == B.ERR["NULL"]
     assert b"NULL" in B.lib.as_last_error(None)
@@ -58,6 +61,10 @@ def test_workspace_query(B):
     c3 = B.Context(B.make_config(synth.CONFIGS[3]))
     gb = c3.workspace_bytes(4, 16384) / 2 ** 30
     assert gb < 240, gb            # + 16 GB of bf16 weights + adapters and their moments < 288 GB
+    # config 5 (sparse layers, 2 x 8192 tokens): + 93 GB of bf16 weights
+    c5 = B.Context(B.make_config(synth.CONFIGS[5]))
+    gb5 = c5.workspace_bytes(2, 8192) / 2 ** 30
+    assert gb5 < 170, gb5
 
 
 def _pack_args(trajs):

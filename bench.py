@@ -36,9 +36,14 @@ def device_weights(sh, seed, dtype):
         return torch.ones(d, dtype=dtype, device="cuda")
 
     P = dict(embed=mat(sh.vocab, d), head=mat(sh.vocab, d), g_final=ones(), layers=[])
+    E = sh.n_experts
     for _ in range(sh.n_layers):
-        P["layers"].append(dict(g1=ones(), wq=mat(D, d), wk=mat(Dkv, d), wv=mat(Dkv, d), wo=mat(d, D), g2=ones(),
-                                wgate=mat(F, d), wup=mat(F, d), wdown=mat(d, F)))
+        W = dict(g1=ones(), wq=mat(D, d), wk=mat(Dkv, d), wv=mat(Dkv, d), wo=mat(d, D), g2=ones())
+        if E:
+            W.update(wgate=mat(E, F, d), wup=mat(E, F, d), wdown=mat(E, d, F), wrouter=mat(E, d))
+        else:
+            W.update(wgate=mat(F, d), wup=mat(F, d), wdown=mat(d, F))
+        P["layers"].append(W)
     return P
 
 
@@ -65,7 +70,8 @@ def algorithmic_flops(sh, seg_lens_nonpad, n_nonpad, n_targets):
     target rows only, no recompute, nothing for pad tokens."""
     D, Dkv, d, F, L, V, r = (sh.n_q_heads * sh.head_dim, sh.n_kv_heads * sh.head_dim, sh.d_model, sh.ffn, sh.n_layers,
                              sh.vocab, sh.lora_rank)
-    p_layer = d * (D + 2 * Dkv) + D * d + 3 * d * F
+    # a sparse layer runs top_k expert FFNs and the router per token
+    p_layer = d * (D + 2 * Dkv) + D * d + (sh.top_k * 3 * d * F + d * sh.n_experts if sh.n_experts else 3 * d * F)
     dense = (6.0 if sh.full_ft else 4.0) * L * p_layer * n_nonpad
     attn = 7.0 * D * L * float(sum(x * x for x in seg_lens_nonpad))
     import synth
@@ -133,7 +139,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=3, help="benchmark configuration (2, 3 or 4); 3 is the headline")
+    ap.add_argument("--config", type=int, default=3, help="benchmark configuration (2..5); 3 is the headline")
     ap.add_argument("--layers", type=int, default=0, help="override the depth (bring-up only; the result is then not the headline)")
     ap.add_argument("--recompute", type=int, default=-1, help="override the recompute mode (0, 1, 2)")
     ap.add_argument("--seed", type=int, default=0)
@@ -206,7 +212,8 @@ def main():
     tokens_per_s = n_nonpad / (ms_per_step * 1e-3)
     mfu = fl["total"] / (ms_per_step * 1e-3) / (PEAK_BF16_TFLOPS * 1e12)
     hfu = (fl["total"] + fl["recompute"]) / (ms_per_step * 1e-3) / (PEAK_BF16_TFLOPS * 1e12)
-    n_l, ms_l, fl_l = prof["gemm_mfma_256"]
+    dom = "gemm_grouped" if sh.n_experts else "gemm_mfma_256"
+    n_l, ms_l, fl_l = prof[dom]
     ach = fl_l / (ms_l * 1e-3) / 1e12 if ms_l > 0 else 0.0
     breakdown = {k: round(v[1] / args.steps, 2) for k, v in prof.items() if v[0]}
     breakdown["untracked"] = round(ms_per_step - sum(breakdown.values()), 2)
@@ -231,7 +238,8 @@ def main():
         adam_ms = a0.elapsed_time(a1)
 
     rec = {
-        "metric": "trained tokens/s per MI355X (LoRA step, 8B shapes, 16k packed); % bf16 MFMA peak",
+        "metric": "trained tokens/s per MI355X (LoRA step, 8B shapes, 16k packed); % bf16 MFMA peak" if args.config == 3 else
+                  "trained tokens/s per MI355X (one fine-tuning step, config %d)" % args.config,
         "value": round(tokens_per_s, 1), "unit": "trained tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 2), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if sh.bf16 else "f32", "data": "synthetic",
@@ -244,12 +252,13 @@ def main():
         "loss": round(loss, 5), "pack_ms": round(pack_ms, 2), "adamw_ms": None if adam_ms is None else round(adam_ms, 3),
         "wall_s_timed_region": round(wall, 3),
         "kernel_ms_per_step": breakdown,
-        "roofline": {"kernel": "gemm_mfma_dlds_kernel<256,256,2,4,...> (projection GEMMs forward + dX, LoRA term as second K segment)",
+        "roofline": {"kernel": "gemm_mfma_dlds_kernel<256,256,2,4,...> (expert GEMMs over grouped rows, forward + dX)" if sh.n_experts else
+                     "gemm_mfma_dlds_kernel<256,256,2,4,...> (projection GEMMs forward + dX, LoRA term as second K segment)",
                      "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
                      "launches_per_step": n_l // max(args.steps, 1), "avg_launch_ms": round(ms_l / max(n_l, 1), 4)},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not sh.n_experts:     # the sparse model's float64 weights do not fit the sample budget
         rec["cpu_baseline"] = cpu_baseline(sh, args.seed)
     print(json.dumps(rec))
 

@@ -568,7 +568,7 @@ struct Step {
     GemmParams g; memset(&g, 0, sizeof g);
     g.seg[0] = {A, B, lda, ldb, K}; g.nseg = 1;
     g.M = P.N; g.N = N; g.C = C; g.ldc = ldc; g.alpha = 1.f; g.splitk = 1;
-    g.grp_off = eoff; g.grp = e;
+    g.grp_off = eoff; g.grp = e; g.grp_rows = 2.0 * P.N / c.n_experts;
     return launch_gemm_off(ctx, mode, gv, g, 0, st);
   }
 

@@ -77,6 +77,7 @@ struct GemmParams {
   // grouped rows (mixture of experts): with grp_off set, the product covers rows
   // [grp_off[grp], grp_off[grp+1]) of A, R and C (device-side table), at most M of them
   const int* grp_off; int grp;
+  double grp_rows;            // expected live rows of the group (timing records only)
 };
 int launch_gemm(as_ctx* ctx, int mode, int variant, const GemmParams& p, hipStream_t st);
 // live rows = *p.m_dev - m_off, clamped to [0, p.M]

@@ -156,8 +156,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p, i
 
   int rb, mmax;
   const int M = gemm_rows(p, m_off, rb, mmax);
-  // XCD de-interleave, then grouped walk over the tile grid
+  // XCD de-interleave, then grouped walk over the tile grid (over the live row tiles only when
+  // the row count is a device-side value)
+  if (p.m_dev || p.grp_off) tiles_m = min(tiles_m, (max(M, 0) + BM - 1) / BM);
   int nblk = tiles_m * tiles_n, pid = blockIdx.x, z = blockIdx.y;
+  if (pid >= nblk) return;
   int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
   int logical = xcd * q8 + min(xcd, rem) + loc;
   constexpr int GROUP = 8;
@@ -279,7 +282,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
 
   int rb, mmax;
   const int M = gemm_rows(p, m_off, rb, mmax);
+  // the row count may live on the device (target rows, rows of one expert): map the workgroups
+  // over the live row tiles only, so that they still spread over all XCDs
+  if (p.m_dev || p.grp_off) tiles_m = min(tiles_m, (max(M, 0) + BM - 1) / BM);
   int nblk = tiles_m * tiles_n, pid = blockIdx.x, z = blockIdx.y;
+  if (pid >= nblk) return;
   int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
   int logical = (MAP == 1) ? pid : xcd * q8 + min(xcd, rem) + loc;
   constexpr int GROUP = (MAP == 2) ? 4 : (MAP == 3) ? 16 : 8;
@@ -508,8 +515,8 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
   int cfg = variant >= 10 ? variant - 10 : pick_cfg(p);
   if (cfg >= 7) for (int s = 0; s < p.nseg; s++) if (p.seg[s].K % 64) cfg = 0;     // direct-to-LDS tiles need whole 64-wide K steps
   const bool big = use_mfma && (cfg == 0 || cfg >= 4);
-  prof_begin(ctx, st, p.m_dev ? AS_K_GEMM_DEVROWS : !use_mfma ? AS_K_GEMM_FMA : big ? AS_K_GEMM_MFMA_256 : AS_K_GEMM_MFMA_SKINNY,
-             p.m_dev ? 0.0 : 2.0 * p.M * p.N * ksum);
+  prof_begin(ctx, st, p.grp_off ? AS_K_GEMM_GROUPED : p.m_dev ? AS_K_GEMM_DEVROWS : !use_mfma ? AS_K_GEMM_FMA : big ? AS_K_GEMM_MFMA_256 : AS_K_GEMM_MFMA_SKINNY,
+             p.grp_off ? 2.0 * p.grp_rows * p.N * ksum : p.m_dev ? 0.0 : 2.0 * p.M * p.N * ksum);
   if (use_mfma) {
     switch (cfg) {
       case 1: rc = launch_mfma_cfg<256, 64, 4, 1>(ctx, p, m_off, st); break;

@@ -117,7 +117,9 @@ __global__ void moe_dlogit_kernel(const T* __restrict__ dy, const T* __restrict_
 
 int launch_moe_route(as_ctx* ctx, const float* logit, int n, int E, int32_t* sel, float* w, hipStream_t st) {
   if (n <= 0) return AS_OK;
+  prof_begin(ctx, st, AS_K_MOE, 0.0);
   moe_route_kernel<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(logit, n, E, sel, w);
+  prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
@@ -127,14 +129,18 @@ int launch_moe_permute(as_ctx* ctx, const int32_t* sel, int n, int E, int32_t* e
   if (smem > 160 * 1024) return as_fail(ctx, AS_ERR_SHAPE, "moe: too many experts for the permutation kernel");
   if (smem > 48 * 1024)
     AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(moe_permute_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+  prof_begin(ctx, st, AS_K_MOE, 0.0);
   moe_permute_kernel<<<1, 1024, smem, st>>>(sel, n, E, eoff, pos, perm);
+  prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
 
 int launch_moe_gather(as_ctx* ctx, int mode, const void* src, const int32_t* perm, const float* w, int rows, int d, void* out, hipStream_t st) {
   if (rows <= 0) return AS_OK;
+  prof_begin(ctx, st, AS_K_MOE, 0.0);
   DISPATCH_T(mode, (moe_gather_kernel<T><<<rows, 256, 0, st>>>((const T*)src, perm, w, rows, d, (T*)out)));
+  prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
@@ -142,7 +148,9 @@ int launch_moe_gather(as_ctx* ctx, int mode, const void* src, const int32_t* per
 int launch_moe_combine(as_ctx* ctx, int mode, const void* res, const void* y, const int32_t* pos, const float* w, int n, int d,
                        void* out, hipStream_t st) {
   if (n <= 0) return AS_OK;
+  prof_begin(ctx, st, AS_K_MOE, 0.0);
   DISPATCH_T(mode, (moe_combine_kernel<T><<<n, 256, 0, st>>>((const T*)res, (const T*)y, pos, w, n, d, (T*)out)));
+  prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
@@ -150,7 +158,9 @@ int launch_moe_combine(as_ctx* ctx, int mode, const void* res, const void* y, co
 int launch_moe_dlogit(as_ctx* ctx, int mode, const void* dy, const void* y, const int32_t* pos, const int32_t* sel, const float* w,
                       int n, int d, int Epad, void* dlogit, hipStream_t st) {
   if (n <= 0) return AS_OK;
+  prof_begin(ctx, st, AS_K_MOE, 0.0);
   DISPATCH_T(mode, (moe_dlogit_kernel<T><<<(unsigned)cdiv(n, 4), 256, 0, st>>>((const T*)dy, (const T*)y, pos, sel, w, n, d, Epad, (T*)dlogit)));
+  prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }

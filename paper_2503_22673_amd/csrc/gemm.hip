@@ -274,8 +274,21 @@ template <int BM, int BN, int WM, int WN, bool DB, int SWZ, int PF, int MAP = 0>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams p, int m_off, int tiles_m, int tiles_n) {
   constexpr int BK = 64, NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-  constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;      // 1 KB wave-loads per wave and tile
+  // PF >= 100: split roles.  The first half of the waves issues every tile load; the other half only
+  // touches, PF - 100 steps ahead, one word of each 128-byte line the tiles will need, and never waits
+  // for those loads.  Loads complete in issue order within a wave, so a wave that must wait for its
+  // tile loads cannot also have such a long-latency load outstanding; a wave of its own can.
+  // PF == 200: the barrier sits before the last 16-wide K slice of a step instead of after it: by then
+  // every fragment of the current tile is in registers, so the next tile's loads can be issued into the
+  // buffer just released and the first fragments of the next tile are read while the last slice's MFMAs
+  // run, instead of right after a barrier with nothing to overlap them.
+  constexpr bool EARLY = PF == 200;
+  constexpr bool SPLIT = PF >= 100 && !EARLY;
+  constexpr int PFD = SPLIT ? PF - 100 : EARLY ? 0 : PF;
+  constexpr int NLW = SPLIT ? NW / 2 : NW;               // waves that issue tile loads
+  constexpr int LA = BM / 8 / NLW, LB = BN / 8 / NLW;    // 1 KB wave-loads per loading wave and tile
   static_assert(LA >= 1 && LB >= 1, "tile too small for the wave count");
+  static_assert(!SPLIT || (BM == BN && (NW - NLW) * 64 == BM), "split roles: one warm-up lane per tile row");
   extern __shared__ __align__(16) unsigned char smem[];
   bf16_t* sA = (bf16_t*)smem;                            // [2][BM][64]
   bf16_t* sB = sA + 2 * BM * BK;                         // [2][BN][64]
@@ -314,13 +327,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
   // loader: wave-load i of this wave covers tile rows (wave*L + i)*8 .. +7; lane l sits at row l/8,
   // LDS chunk l%8, and fetches global chunk (l%8) ^ (l/8)
   const int lrow = lane >> 3;
+  const bool loader = !SPLIT || wave < NLW;
+  const int lw = loader ? wave : 0;
   int rowA[LA], rowB[LB];
   {
     const int mclamp = mmax, nclamp = p.N - 1;
 #pragma unroll
-    for (int i = 0; i < LA; i++) rowA[i] = rb + min(row0 + (wave * LA + i) * 8 + lrow, mclamp);
+    for (int i = 0; i < LA; i++) rowA[i] = rb + min(row0 + (lw * LA + i) * 8 + lrow, mclamp);
 #pragma unroll
-    for (int i = 0; i < LB; i++) rowB[i] = min(col0 + (wave * LB + i) * 8 + lrow, nclamp);
+    for (int i = 0; i < LB; i++) rowB[i] = min(col0 + (lw * LB + i) * 8 + lrow, nclamp);
   }
   auto fetch = [&](int it, int buf) {
     const bool first = it < nt0;
@@ -328,15 +343,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
     const bf16_t* B = (const bf16_t*)(first ? p.seg[0].B : p.seg[1].B);
     const int64_t lda = first ? p.seg[0].lda : p.seg[1].lda, ldb = first ? p.seg[0].ldb : p.seg[1].ldb;
     const int k = (first ? kr0.beg + it : kr1.beg + it - nt0) * BK;
-    bf16_t* a = sA + buf * BM * BK + wave * LA * 8 * BK;
-    bf16_t* b = sB + buf * BN * BK + wave * LB * 8 * BK;
+    bf16_t* a = sA + buf * BM * BK + lw * LA * 8 * BK;
+    bf16_t* b = sB + buf * BN * BK + lw * LB * 8 * BK;
 #pragma unroll
     for (int i = 0; i < LA; i++)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(A + (int64_t)rowA[i] * lda + k + (((lane & 7) ^ swz<SWZ>((wave * LA + i) * 8 + lrow)) * 8)),
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(A + (int64_t)rowA[i] * lda + k + (((lane & 7) ^ swz<SWZ>((lw * LA + i) * 8 + lrow)) * 8)),
                                        (__attribute__((address_space(3))) void*)(a + i * 8 * BK), 16, 0, 0);
 #pragma unroll
     for (int i = 0; i < LB; i++)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(B + (int64_t)rowB[i] * ldb + k + (((lane & 7) ^ swz<SWZ>((wave * LB + i) * 8 + lrow)) * 8)),
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(B + (int64_t)rowB[i] * ldb + k + (((lane & 7) ^ swz<SWZ>((lw * LB + i) * 8 + lrow)) * 8)),
                                        (__attribute__((address_space(3))) void*)(b + i * 8 * BK), 16, 0, 0);
   };
 
@@ -363,17 +378,84 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
                                    : B + (int64_t)min(col0 + (tid - BM) % BN, p.N - 1) * ldb + k;
     asm volatile("global_load_dword %0, %1, off" : "+v"(pf_reg) : "v"(ptr) : "memory");
   };
+  unsigned pf_reg2 = 0;
+  const int wrow = SPLIT ? (wave - NLW) * 64 + lane : 0;   // split roles: this lane's tile row
+  const int64_t wrowA = rb + min(row0 + wrow, mmax), wrowB = min(col0 + wrow, p.N - 1);
+  auto warm2 = [&](int it) {
+    const bool first = it < nt0;
+    const bf16_t* A = (const bf16_t*)(first ? p.seg[0].A : p.seg[1].A);
+    const bf16_t* B = (const bf16_t*)(first ? p.seg[0].B : p.seg[1].B);
+    const int64_t lda = first ? p.seg[0].lda : p.seg[1].lda, ldb = first ? p.seg[0].ldb : p.seg[1].ldb;
+    const int k = (first ? kr0.beg + it : kr1.beg + it - nt0) * BK;
+    const bf16_t* pa = A + wrowA * lda + k;
+    const bf16_t* pb = B + wrowB * ldb + k;
+    asm volatile("global_load_dword %0, %1, off" : "+v"(pf_reg) : "v"(pa) : "memory");
+    asm volatile("global_load_dword %0, %1, off" : "+v"(pf_reg2) : "v"(pb) : "memory");
+  };
 
-  if (nt > 0) fetch(0, 0);
+  if (nt > 0 && loader) fetch(0, 0);
   __builtin_amdgcn_s_waitcnt(0x0f70);                    // vmcnt(0): the first tile has landed
   __syncthreads();
+  if constexpr (EARLY) {
+    static_assert(!EARLY || (DB && BK / 16 == 4), "early-barrier loop is written for four K slices");
+    bf16x8 af[2][TM], bfr[2][TN];
+    auto rd = [&](int buf, int ks, int slot) {
+      const bf16_t* a = sA + buf * BM * BK + (wm * TM * 32 + (lane & 31)) * BK;
+      const bf16_t* b = sB + buf * BN * BK + (wn * TN * 32 + (lane & 31)) * BK;
+#pragma unroll
+      for (int i = 0; i < TM; i++) af[slot][i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * BK + coff[ks]);
+#pragma unroll
+      for (int j = 0; j < TN; j++) bfr[slot][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * BK + coff[ks]);
+    };
+    auto mm = [&](int slot) {
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
+    };
+    auto weave = [&]() {                                   // one LDS read between MFMAs, then the rest of the MFMAs
+#pragma unroll
+      for (int r = 0; r < TM + TN; r++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+    };
+    if (nt > 1) fetch(1, 1);
+    if (nt > 0) rd(0, 0, 0);
+    for (int it = 0; it < nt; it++) {
+      const int buf = it & 1;
+      rd(buf, 1, 1); mm(0); weave();
+      rd(buf, 2, 0); mm(1); weave();
+      rd(buf, 3, 1); mm(0); weave();
+      __builtin_amdgcn_s_waitcnt(0x0070);                  // vmcnt(0) lgkmcnt(0)
+      __syncthreads();                                     // tile it is in registers everywhere, tile it+1 has landed
+      // straight-line tail (the last two steps re-request the final tile into a buffer nobody reads
+      // again, and read fragments nobody uses), so that loads, LDS reads and MFMAs can interleave
+      fetch(min(it + 2, nt - 1), buf);
+      rd(buf ^ 1, 0, 0);
+      mm(1);
+#pragma unroll
+      for (int r = 0; r < TM + TN; r++) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x020, LA + LB, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0f70);                    // the re-requested tile must land before the workgroup's LDS is released
+  } else
   for (int it = 0; it < nt; it++) {
     const int buf = it & 1;
-    if constexpr (PF > 0) {
+    if constexpr (SPLIT) {
+      if (loader) { if (it + 1 < nt) fetch(it + 1, buf ^ 1); }
+      else if (it + PFD < nt) warm2(it + PFD);
+    } else if constexpr (PF > 0) {
       // fixed instruction pattern per step (the last steps re-request tiles already seen), so that
       // the wait counts are static: 8 tile loads, then one warm-up load that may stay in flight
       fetch(min(it + 1, nt - 1), buf ^ 1);
-      warm(min(it + PF, nt - 1));
+      warm(min(it + PFD, nt - 1));
     } else {
       if (it + 1 < nt) fetch(it + 1, buf ^ 1);
     }
@@ -428,12 +510,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
     }
     // plain s_barrier: __syncthreads() would add a fence that waits for every outstanding load,
     // the warm-up one included.  The tile loads are waited for explicitly; nothing else is shared.
-    if constexpr (PF > 0) { __builtin_amdgcn_s_waitcnt(0x0f71); __builtin_amdgcn_s_barrier(); }   // vmcnt(1)
+    if constexpr (SPLIT) { if (loader) __builtin_amdgcn_s_waitcnt(0x0f70); __builtin_amdgcn_s_barrier(); }
+    else if constexpr (PF > 0) { __builtin_amdgcn_s_waitcnt(0x0f71); __builtin_amdgcn_s_barrier(); }   // vmcnt(1)
     else { __builtin_amdgcn_s_waitcnt(0x0f70); __syncthreads(); }                                 // vmcnt(0)
   }
   if constexpr (PF > 0) {
     __builtin_amdgcn_s_waitcnt(0x0f70);                  // the last warm-up load must land before its register is reused
     asm volatile("" : "+v"(pf_reg));
+    asm volatile("" : "+v"(pf_reg2));
   }
   gemm_epilogue<TM, TN>(p, acc, M, z, row0, col0, row0 + wm * TM * 32 + 4 * (lane >> 5), col0 + wn * TN * 32 + (lane & 31),
                         (row0 + BM <= M) && (col0 + BN <= p.N), rb);
@@ -494,7 +578,7 @@ static int pick_cfg(const GemmParams& p) {
   if (p.N <= 128 && p.M > 128) return 1;
   if (p.M <= 128) return 2;
   if ((int64_t)cdiv(p.M, 256) * cdiv(p.N, 256) * p.splitk < 128) return 3;
-  return 8;                                              // direct-to-LDS tiles when K allows, else staged (0)
+  return 20;                                             // direct-to-LDS tiles when K allows, else staged (0)
 }
 
 // m_dev semantics: the live row count is *m_dev - m_off (clamped to [0, M]).
@@ -507,7 +591,7 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
   if (p.splitk > 1 && !p.partial) return as_fail(ctx, AS_ERR_WORKSPACE, "gemm: split-K needs a partial buffer");
   if (p.accumulate && !p.c_f32) return as_fail(ctx, AS_ERR_SHAPE, "gemm: accumulate needs float output");
   if (p.grp_off && p.splitk > 1) return as_fail(ctx, AS_ERR_SHAPE, "gemm: grouped rows and split-K do not combine");
-  if (variant < 0 || (variant > 2 && (variant < 10 || variant > 25))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
+  if (variant < 0 || (variant > 2 && (variant < 10 || variant > 30))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
   bool use_mfma = (mode == AS_BF16) && variant != 1 && mfma_ok(p);
   if (variant >= 2 && !use_mfma) return as_fail(ctx, AS_ERR_SHAPE, "gemm: MFMA kernel needs bf16 and 8-element alignment");
   int rc = AS_OK;
@@ -534,6 +618,11 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
       case 13: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 0, 1>(ctx, p, m_off, st); break;
       case 14: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 0, 2>(ctx, p, m_off, st); break;
       case 15: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 0, 3>(ctx, p, m_off, st); break;
+      case 16: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 102>(ctx, p, m_off, st); break;
+      case 17: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 103>(ctx, p, m_off, st); break;
+      case 18: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 104>(ctx, p, m_off, st); break;
+      case 19: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 106>(ctx, p, m_off, st); break;
+      case 20: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 200>(ctx, p, m_off, st); break;
       default: rc = launch_mfma_cfg<256, 256, 2, 4>(ctx, p, m_off, st); break;
     }
   } else {

@@ -267,10 +267,12 @@ int as_op_rmsnorm_bwd(as_ctx* ctx, int mode, int64_t n, int64_t d, const void* d
 /* Varlen causal attention with grouped KV heads over packed rows.  q [n,Hq,dh]
  * with row stride ldq elements, k, v [n,Hkv,dh] with stride ldkv, o [n,Hq,dh]
  * dense, lse float [n,Hq].  seg_start [n] int32: first token of each token's
- * segment.  variant: 0 = pick, 1 = plain kernel, 2 = MFMA kernel (bf16).
+ * segment.  variant: 0 = pick, 1 = plain kernel, 2 / 3 / 4 = MFMA kernels (bf16:
+ * first generation, second with 64-query waves, second with 32-query waves).
  * t_scratch: type T, only read by the MFMA kernels (may be NULL otherwise):
- * room for Hkv*dh * n64 elements in forward and (2*Hq + Hkv)*dh * n64 in
- * backward, n64 = n rounded up to 64 (token-major copies of V, resp. K, Q, dO). */
+ * room for Hkv*dh * n64 elements in forward and (6*Hq + Hkv)*dh * n64 in
+ * backward, n64 = n rounded up to 64 (token-major copies of V, resp. K, Q, dO,
+ * followed in backward by float dK / dV partials per query head). */
 int as_op_attention_fwd(as_ctx* ctx, int mode, int variant, int64_t n, const int32_t* seg_start,
                         const void* q, int64_t ldq, const void* k, const void* v, int64_t ldkv,
                         void* o, float* lse, void* t_scratch, void* stream);

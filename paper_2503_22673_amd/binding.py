@@ -302,7 +302,7 @@ class Context:
         delta = torch.empty(n, c.n_q_heads, dtype=torch.float32, device=qkv.device)
         b, g = qkv.data_ptr(), dqkv.data_ptr()
         n64 = (n + 63) // 64 * 64
-        ts = torch.empty((2 * D + Dkv) * n64, dtype=qkv.dtype, device=qkv.device)
+        ts = torch.empty((6 * D + Dkv) * n64, dtype=qkv.dtype, device=qkv.device)
         self.check(lib.as_op_attention_bwd(self.handle, mode, variant, n, _ptr(seg_start), _ptr(seg_end), C.c_void_p(b),
                                            qkv.stride(0), C.c_void_p(b + D * es), C.c_void_p(b + (D + Dkv) * es),
                                            qkv.stride(0), _ptr(o), _ptr(lse), _ptr(d_o), C.c_void_p(g),

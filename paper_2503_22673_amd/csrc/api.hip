@@ -318,6 +318,7 @@ struct Plan {
   int n_qkv, n_gu;                       // adapters inside the q/k/v and gate/up groups
   int32_t *seg_start, *seg_end, *tgt_idx, *tgt_pos, *labels, *count, *iscratch;
   int32_t *tok_c; uint8_t* mask_c;       // tokens and mask with the skipped segments squeezed out
+  const int32_t *order_q = nullptr, *order_k = nullptr;   // attention launch orders of this step (longest workgroups first)
   float *rope_cos, *rope_sin, *loss_rows, *rstd_f, *logits, *delta, *partial, *gpart;
   std::vector<void*> h;                  // L+1 residual-stream snapshots
   std::vector<Acts> acts;
@@ -428,7 +429,8 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   size_t umax = (size_t)std::max({P.n_qkv, P.n_gu, 1}) * rp;
   P.uT = w.take(umax * Np * es); P.duT = w.take(umax * Np * es);
   P.gpart = (float*)w.take(full ? (size_t)256 * P.d * 4 : 0);
-  P.attT = w.take(c.mode == AS_BF16 ? (size_t)(2 * P.D + P.Dkv) * Np * es : 0);   // token-major K, Q, dO (V in forward)
+  // token-major K, Q, dO (V in forward), then the per-query-head float partials of dK and dV
+  P.attT = w.take(c.mode == AS_BF16 ? (size_t)(2 * P.D + P.Dkv) * Np * es + (size_t)2 * P.D * Np * 4 : 0);
 
   // prepared adapter copies
   P.lora.assign((size_t)P.L * AS_N_TARGETS, LoraSlot());
@@ -541,6 +543,7 @@ struct Step {
     AttnParams ap; memset(&ap, 0, sizeof ap);
     ap.n = N; ap.Hq = c.n_q_heads; ap.Hkv = c.n_kv_heads; ap.dh = c.head_dim; ap.seg_start = P.seg_start; ap.seg_end = P.seg_end;
     ap.q = a.qkv; ap.k = off(a.qkv, D); ap.v = off(a.qkv, D + Dkv); ap.ldq = QKV; ap.ldkv = QKV; ap.o = a.o; ap.lse = a.lse; ap.max_seg = max_seg; ap.t_scratch = P.attT;
+    ap.order_q = P.order_q; ap.order_k = P.order_k;
     if ((rc = launch_attention_fwd(ctx, mode, av, ap, st))) return rc;
     { LoraSlot& s = slot(l, AS_T_O);
       if (s.on && (rc = gemm(N, rp, a.o, D, s.A, D, D, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_o, rp))) return rc;
@@ -773,6 +776,7 @@ struct Step {
       ap.n = N; ap.Hq = c.n_q_heads; ap.Hkv = c.n_kv_heads; ap.dh = c.head_dim; ap.seg_start = P.seg_start; ap.seg_end = P.seg_end;
       ap.q = a.qkv; ap.k = off(a.qkv, D); ap.v = off(a.qkv, D + Dkv); ap.ldq = QKV; ap.ldkv = QKV; ap.o = a.o; ap.lse = a.lse;
       ap.d_o = P.d_o; ap.dq = P.dqkv; ap.dk = off(P.dqkv, D); ap.dv = off(P.dqkv, D + Dkv); ap.delta = P.delta; ap.max_seg = max_seg; ap.t_scratch = P.attT;
+      ap.order_q = P.order_q; ap.order_k = P.order_k;
       if ((rc = launch_attention_bwd(ctx, mode, av, ap, st))) return rc; }
     if ((rc = launch_rope(ctx, mode, N, c.n_q_heads + c.n_kv_heads, c.head_dim, P.dqkv, QKV, P.seg_start, P.rope_cos, P.rope_sin, 1, st))) return rc;
     // ---- q / k / v projections
@@ -927,28 +931,49 @@ extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lo
   // weights they would read are not being differentiated through them.  They are squeezed out.
   int n = (int)N, n_seg_eff = n_segments;
   const int32_t* d_cu_eff = d_cu_seqlens;
+  std::vector<int32_t> cu_h(h_cu_seqlens, h_cu_seqlens + n_segments + 1), src;   // segment table the kernels will see
+  bool compact = false;
   if (h_seg_skip) {
-    bool any = false;
-    for (int s = 0; s < n_segments; s++) any = any || h_seg_skip[s];
-    if (any) {
-      std::vector<int32_t> tab;                          // [cu_c (S'+1) | src_start (S')]
-      std::vector<int32_t> cu_c(1, 0), src;
+    for (int s = 0; s < n_segments; s++) compact = compact || h_seg_skip[s];
+    if (compact) {
+      cu_h.assign(1, 0);
       max_seg = 0;
       for (int s = 0; s < n_segments; s++) {
         if (h_seg_skip[s]) continue;
         const int len = h_cu_seqlens[s + 1] - h_cu_seqlens[s];
-        src.push_back(h_cu_seqlens[s]); cu_c.push_back(cu_c.back() + len); max_seg = std::max(max_seg, len);
+        src.push_back(h_cu_seqlens[s]); cu_h.push_back(cu_h.back() + len); max_seg = std::max(max_seg, len);
       }
-      n_seg_eff = (int)src.size(); n = cu_c.back();
-      if (n_seg_eff > 0) {
-        tab = cu_c; tab.insert(tab.end(), src.begin(), src.end());
-        rc = stage_step_table(ctx, tab.data(), tab.size() * 4, st);
-        if (rc) return rc;
-        const int32_t* d_tab = (const int32_t*)ctx->d_step;
-        if ((rc = launch_compact(ctx, d_tokens, d_loss_mask, d_tab, d_tab + n_seg_eff + 1, n_seg_eff, n, P.tok_c, P.mask_c, st))) return rc;
-        d_tokens = P.tok_c; d_loss_mask = P.mask_c; d_cu_eff = d_tab;
-      }
+      n_seg_eff = (int)src.size(); n = cu_h.back();
     }
+  }
+  // The attention kernels' workgroups differ in length by the position of their rows inside a segment
+  // (a late query tile visits many key tiles, an early key block is visited by many query tiles); the
+  // launch is as long as its last workgroup, so the long ones are listed first.
+  const bool orders = c.mode == AS_BF16 && (c.head_dim == 64 || c.head_dim == 128) && n > 0;
+  if (n_seg_eff > 0 && (compact || orders)) {
+    std::vector<int32_t> tab = cu_h;                       // [cu (S'+1) | src_start (S') | order_q | order_k]
+    tab.insert(tab.end(), src.begin(), src.end());
+    size_t off_q = 0, off_k = 0;
+    if (orders) {
+      const int QT = attention_query_tile(c.n_q_heads, c.n_kv_heads), KPB = 256;
+      const int nq = (int)cdiv(n, QT), nk = (int)cdiv(n, KPB);
+      auto seg_of = [&](int t) { return (int)(std::upper_bound(cu_h.begin(), cu_h.end(), t) - cu_h.begin()) - 1; };
+      std::vector<int32_t> wq(nq), wk(nk), oq(nq), ok(nk);
+      for (int i = 0; i < nq; i++) { wq[i] = std::min(i * QT + QT - 1, n - 1) / 64 - cu_h[seg_of(i * QT)] / 64 + 1; oq[i] = i; }
+      for (int i = 0; i < nk; i++) { wk[i] = (cu_h[seg_of(std::min(i * KPB + KPB - 1, n - 1)) + 1] - 1) / 64 - (i * KPB) / 64 + 1; ok[i] = i; }
+      std::stable_sort(oq.begin(), oq.end(), [&](int a, int b) { return wq[a] > wq[b]; });
+      std::stable_sort(ok.begin(), ok.end(), [&](int a, int b) { return wk[a] > wk[b]; });
+      off_q = tab.size(); tab.insert(tab.end(), oq.begin(), oq.end());
+      off_k = tab.size(); tab.insert(tab.end(), ok.begin(), ok.end());
+    }
+    rc = stage_step_table(ctx, tab.data(), tab.size() * 4, st);
+    if (rc) return rc;
+    const int32_t* d_tab = (const int32_t*)ctx->d_step;
+    if (compact) {
+      if ((rc = launch_compact(ctx, d_tokens, d_loss_mask, d_tab, d_tab + n_seg_eff + 1, n_seg_eff, n, P.tok_c, P.mask_c, st))) return rc;
+      d_tokens = P.tok_c; d_loss_mask = P.mask_c; d_cu_eff = d_tab;
+    }
+    if (orders) { P.order_q = d_tab + off_q; P.order_k = d_tab + off_k; }
   }
   P.N = n; P.Np = (int)cdiv(n, 64) * 64;
   Step S{ctx, c, P, st, c.mode, 0, 0, weights, lora, grads, max_seg};

@@ -138,15 +138,15 @@ static int set_smem(as_ctx* ctx, K kern, size_t smem) {
   return AS_OK;
 }
 
-int launch_attention_fwd_mfma(as_ctx* ctx, const AttnParams& p, hipStream_t st);
-int launch_attention_bwd_mfma(as_ctx* ctx, const AttnParams& p, hipStream_t st);
+int launch_attention_fwd_mfma(as_ctx* ctx, const AttnParams& p, int variant, hipStream_t st);
+int launch_attention_bwd_mfma(as_ctx* ctx, const AttnParams& p, int variant, hipStream_t st);
 bool attention_mfma_ok(const AttnParams& p);
 
 int launch_attention_fwd(as_ctx* ctx, int mode, int variant, const AttnParams& p, hipStream_t st) {
   if (p.n <= 0) return AS_OK;
   bool mf = mode == AS_BF16 && variant != 1 && attention_mfma_ok(p);
-  if (variant == 2 && !mf) return as_fail(ctx, AS_ERR_SHAPE, "attention: MFMA kernel needs bf16, head_dim 64/128, aligned strides");
-  if (mf) { prof_begin(ctx, st, AS_K_ATTN_FWD, 0.0); int r = launch_attention_fwd_mfma(ctx, p, st); prof_end(ctx, st); return r; }
+  if (variant >= 2 && !mf) return as_fail(ctx, AS_ERR_SHAPE, "attention: MFMA kernel needs bf16, head_dim 64/128, aligned strides");
+  if (mf) { prof_begin(ctx, st, AS_K_ATTN_FWD, 0.0); int r = launch_attention_fwd_mfma(ctx, p, variant, st); prof_end(ctx, st); return r; }
   size_t smem = (size_t)(p.dh + p.max_seg) * sizeof(float);
   int rc = check_plain(ctx, p, smem); if (rc) return rc;
   float scale = 1.f / sqrtf((float)p.dh);
@@ -162,8 +162,8 @@ int launch_attention_fwd(as_ctx* ctx, int mode, int variant, const AttnParams& p
 int launch_attention_bwd(as_ctx* ctx, int mode, int variant, const AttnParams& p, hipStream_t st) {
   if (p.n <= 0) return AS_OK;
   bool mf = mode == AS_BF16 && variant != 1 && attention_mfma_ok(p);
-  if (variant == 2 && !mf) return as_fail(ctx, AS_ERR_SHAPE, "attention: MFMA kernel needs bf16, head_dim 64/128, aligned strides");
-  if (mf) { prof_begin(ctx, st, AS_K_ATTN_BWD, 0.0); int r = launch_attention_bwd_mfma(ctx, p, st); prof_end(ctx, st); return r; }
+  if (variant >= 2 && !mf) return as_fail(ctx, AS_ERR_SHAPE, "attention: MFMA kernel needs bf16, head_dim 64/128, aligned strides");
+  if (mf) { prof_begin(ctx, st, AS_K_ATTN_BWD, 0.0); int r = launch_attention_bwd_mfma(ctx, p, variant, st); prof_end(ctx, st); return r; }
   size_t smem1 = (size_t)(2 * p.dh + p.max_seg) * sizeof(float);
   size_t smem2 = (size_t)(2 * p.dh + 2 * p.max_seg) * sizeof(float);
   int rc = check_plain(ctx, p, smem2); if (rc) return rc;

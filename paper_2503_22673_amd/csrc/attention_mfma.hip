@@ -229,6 +229,167 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(AttnParams p, float sl2) {
   }
 }
 
+// ------------------------------------------------- forward, second generation
+// Same orientation and tile sizes as above.  What differs:
+//  * K and V^T tiles go from global memory straight into LDS (no staging registers, no store pass), two
+//    stages deep, so a step costs one barrier; rows are unpadded and the 16-byte chunks of a row are
+//    XOR-swizzled with the row index so that fragment reads stay spread over the banks;
+//  * the causal / segment mask is evaluated only on tiles that touch the diagonal or a segment start
+//    (a wave-uniform test), every other tile takes a mask-free path;
+//  * the 1/sqrt(d) log2(e) factor is folded into the exponent's fused multiply-add;
+//  * the running maximum is only raised when a tile exceeds it by more than 2^8 (the accumulators are
+//    float, the probabilities stay below 256), so rescaling the output accumulators is rare and sits
+//    behind a wave-uniform branch.
+template <int ROWBYTES> __device__ __forceinline__ int swz_row(int row) { return ROWBYTES == 256 ? (row & 15) : ((row >> 1) & 7); }
+
+// [ROWS][COLS] bf16 tile -> LDS, 1 KB per wave instruction; source rows row0 + r are clamped to row_max
+template <int ROWS, int COLS, int NW>
+__device__ __forceinline__ void tile_to_lds(const bf16_t* base, int64_t ld, int row0, int row_max, bf16_t* s, int wave, int lane) {
+  constexpr int CPR = COLS / 8, RPL = 64 / CPR, NL = ROWS / RPL;
+  static_assert(NL % NW == 0, "tile rows must split evenly over the waves");
+#pragma unroll
+  for (int i = 0; i < NL / NW; i++) {
+    const int w = wave * (NL / NW) + i;
+    const int row = w * RPL + lane / CPR, c = lane % CPR;
+    const bf16_t* src = base + (int64_t)min(row0 + row, row_max) * ld + ((c ^ swz_row<COLS * 2>(row)) * 8);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)(s + w * 512), 16, 0, 0);
+  }
+}
+
+// Wave = QB blocks of 32 queries of one head; workgroup = HPW heads x (NWV / HPW) query groups, NWV = 8 / QB waves.
+// QB = 1 keeps a wave under 256 registers, so two waves share a SIMD and one's softmax runs under the other's MFMAs.
+template <int DH, int HPW, int QB>
+__global__ __launch_bounds__(512 / QB) void attn_fwd2_mfma(AttnParams p, float sl2) {
+  constexpr int KS = DH / 16, CB = DH / 32, NWV = 8 / QB, WQ = 32 * QB, QT = WQ * (NWV / HPW);
+  constexpr int KT_E = BKEY * DH, ST_E = 2 * KT_E;        // elements of one tile / of one stage (K tile + V^T tile)
+  extern __shared__ __align__(16) unsigned char dyn_smem[];
+  bf16_t* sm = (bf16_t*)dyn_smem;
+  const int tid = threadIdx.x, lane = tid & 63, l31 = lane & 31, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform values stay in scalar registers and branches on them are real branches
+  const int n = p.n, grp = p.Hq / p.Hkv;
+  const int j = blockIdx.y * HPW + (wave % HPW), g = j / grp;
+  const int t_wg = (p.order_q ? p.order_q[blockIdx.x] : (int)(gridDim.x - 1 - blockIdx.x)) * QT;   // long rows first
+  const int t_base = t_wg + (wave / HPW) * WQ;
+  const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* VT = (const bf16_t*)p.vT;
+
+  bf16x8 qf[QB][KS];
+  int tq[QB], ss[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; qb++) {
+    tq[qb] = t_base + qb * 32 + l31;
+    int tc = min(tq[qb], n - 1);
+    ss[qb] = p.seg_start[tc];
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+      qf[qb][ks] = *reinterpret_cast<const bf16x8*>(Q + (int64_t)tc * p.ldq + j * DH + ks * 16 + h * 8);
+  }
+  const int ss_hi = __builtin_amdgcn_readfirstlane(p.seg_start[min(t_base + WQ - 1, n - 1)]);  // the latest segment start any query of this wave has
+  f32x16 o[QB][CB];
+  float mref[QB], l[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; qb++) { mref[qb] = -INFINITY; l[qb] = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++) o[qb][cb] = zero16(); }
+
+  const int kv_first = p.seg_start[min(t_wg, n - 1)] / BKEY;
+  const int kv_last = min(t_wg + QT - 1, n - 1) / BKEY;
+  auto stage = [&](int kt, int b) {
+    tile_to_lds<BKEY, DH, NWV>(K + g * DH, p.ldkv, kt * BKEY, n - 1, sm + b * ST_E, wave, lane);
+    tile_to_lds<DH, BKEY, NWV>(VT + (int64_t)g * DH * p.ldT + kt * BKEY, p.ldT, 0, DH - 1, sm + b * ST_E + KT_E, wave, lane);
+  };
+  const int swK = swz_row<DH * 2>(l31), swV = swz_row<128>(l31);
+  stage(kv_first, 0);
+  for (int kt = kv_first; kt <= kv_last; kt++) {
+    const int b = (kt - kv_first) & 1;
+    __builtin_amdgcn_s_waitcnt(0x0f70);      // this wave's part of tile kt has landed
+    __syncthreads();                         // ... everyone's has, and everyone is done with tile kt-1
+    if (kt < kv_last) stage(kt + 1, b ^ 1);
+    const int k0 = kt * BKEY;
+    if (k0 > t_base + WQ - 1 || t_base >= n) continue;          // tile lies after every query of this wave
+    const bf16_t* sK = sm + b * ST_E; const bf16_t* sVt = sK + KT_E;
+    f32x16 s[QB][2];
+#pragma unroll
+    for (int qb = 0; qb < QB; qb++) { s[qb][0] = zero16(); s[qb][1] = zero16(); }
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++) {
+        bf16x8 a = *reinterpret_cast<const bf16x8*>(sK + (kb * 32 + l31) * DH + (((ks * 2 + h) ^ swK) * 8));
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++) s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s[qb][kb], 0, 0, 0);
+      }
+    const bool full = (k0 + 63 <= t_base) && (k0 >= ss_hi);  // every key of the tile is visible to every query of the wave
+    bf16x8 pb[QB][4];
+#pragma unroll
+    for (int qb = 0; qb < QB; qb++) {
+      if (!full) {
+#pragma unroll
+        for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+          for (int e = 0; e < 16; e++) {
+            int key = k0 + kb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+            s[qb][kb][e] = (key >= ss[qb] && key <= tq[qb]) ? s[qb][kb][e] : -INFINITY;
+          }
+      }
+      float mx = s[qb][0][0];
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) mx = fmaxf(mx, s[qb][kb][e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sl2;
+      const bool raise = mx > mref[qb] + 8.f;
+      if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+        const float m_new = raise ? mx : mref[qb];
+        const float alpha = raise ? fast_exp2(mref[qb] - m_new) : 1.f;
+        mref[qb] = m_new;
+        l[qb] *= alpha;
+#pragma unroll
+        for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+          for (int e = 0; e < 16; e++) o[qb][cb][e] *= alpha;
+      }
+      const float neg_m = (mref[qb] == -INFINITY) ? 0.f : -mref[qb];
+      float rs = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) { float pv = fast_exp2(fmaf(s[qb][kb][e], sl2, neg_m)); s[qb][kb][e] = pv; rs += pv; }
+      rs += __shfl_xor(rs, 32, 64);
+      l[qb] += rs;
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++) { pb[qb][kb * 2] = pack8(s[qb][kb], 0); pb[qb][kb * 2 + 1] = pack8(s[qb][kb], 1); }
+    }
+#pragma unroll
+    for (int x = 0; x < 4; x++) {                            // x = kb*2 + sl: 16 keys each
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++) {
+        // quad-swapped token order: the 8 keys this lane half contracts over are chunk 2x + h of the row
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(sVt + (cb * 32 + l31) * BKEY + (((2 * x + h) ^ swV) * 8));
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++) o[qb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb][x], o[qb][cb], 0, 0, 0);
+      }
+    }
+  }
+  bf16_t* O = (bf16_t*)p.o;
+#pragma unroll
+  for (int qb = 0; qb < QB; qb++) {
+    if (tq[qb] >= n) continue;
+    float inv = 1.f / l[qb];
+    bf16_t* orow = O + ((int64_t)tq[qb] * p.Hq + j) * DH;
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+      for (int b4 = 0; b4 < 4; b4++) {
+        bf16x4 w;
+#pragma unroll
+        for (int i = 0; i < 4; i++) w[i] = (bf16_t)(o[qb][cb][b4 * 4 + i] * inv);
+        *reinterpret_cast<bf16x4*>(orow + cb * 32 + 8 * b4 + 4 * h) = w;
+      }
+    if (h == 0) p.lse[(int64_t)tq[qb] * p.Hq + j] = (mref[qb] + log2f(l[qb])) * 0.6931471805599453f;
+  }
+}
+
 // ---------------------------------------------------------- backward: delta
 __global__ void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o, int64_t rows, int dh,
                                   float* __restrict__ delta) {
@@ -445,21 +606,309 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(AttnParams p, float sca
   }
 }
 
+// ----------------------------------------------- backward, second generation
+// Same split and orientation as the kernels above, with the changes of attn_fwd2_mfma: tiles straight
+// into LDS, two stages, one barrier per step; token-major copies in quad-swapped order (16-byte fragment
+// reads); mask only on tiles that touch the diagonal or a segment boundary; scale folded into the
+// exponent's multiply-add.
+template <int DH, int HPW>
+__global__ __launch_bounds__(512) void attn_bwd_dq2_mfma(AttnParams p, float scale, float sl2) {
+  constexpr int KS = DH / 16, CB = DH / 32, NWV = 8, QT = 32 * (NWV / HPW);
+  constexpr int KT_E = BKEY * DH, ST_E = 3 * KT_E;        // K tile, V tile, K^T tile
+  extern __shared__ __align__(16) unsigned char dyn_smem[];
+  bf16_t* sm = (bf16_t*)dyn_smem;
+  const int tid = threadIdx.x, lane = tid & 63, l31 = lane & 31, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = p.n, grp = p.Hq / p.Hkv;
+  const int j = blockIdx.y * HPW + (wave % HPW), g = j / grp;
+  const int t_wg = (p.order_q ? p.order_q[blockIdx.x] : (int)(gridDim.x - 1 - blockIdx.x)) * QT;   // long rows first
+  const int t_base = t_wg + (wave / HPW) * 32;
+  const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* V = (const bf16_t*)p.v;
+  const bf16_t* dO = (const bf16_t*)p.d_o; const bf16_t* KT = (const bf16_t*)p.kT;
+  const int tq = t_base + l31, tc = min(tq, n - 1), ss = p.seg_start[tc];
+  bf16x8 qf[KS], dof[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) {
+    qf[ks] = *reinterpret_cast<const bf16x8*>(Q + (int64_t)tc * p.ldq + j * DH + ks * 16 + h * 8);
+    dof[ks] = *reinterpret_cast<const bf16x8*>(dO + ((int64_t)tc * p.Hq + j) * DH + ks * 16 + h * 8);
+  }
+  const float neg_lse2 = -p.lse[(int64_t)tc * p.Hq + j] * 1.4426950408889634f;
+  const float dl = p.delta[(int64_t)tc * p.Hq + j];
+  const int ss_hi = __builtin_amdgcn_readfirstlane(p.seg_start[min(t_base + 31, n - 1)]);
+  f32x16 dq[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; cb++) dq[cb] = zero16();
+
+  const int kv_first = __builtin_amdgcn_readfirstlane(p.seg_start[min(t_wg, n - 1)] / BKEY);
+  const int kv_last = min(t_wg + QT - 1, n - 1) / BKEY;
+  auto stage = [&](int kt, int b) {
+    bf16_t* d = sm + b * ST_E;
+    tile_to_lds<BKEY, DH, NWV>(K + g * DH, p.ldkv, kt * BKEY, n - 1, d, wave, lane);
+    tile_to_lds<BKEY, DH, NWV>(V + g * DH, p.ldkv, kt * BKEY, n - 1, d + KT_E, wave, lane);
+    tile_to_lds<DH, BKEY, NWV>(KT + (int64_t)g * DH * p.ldT + kt * BKEY, p.ldT, 0, DH - 1, d + 2 * KT_E, wave, lane);
+  };
+  const int swK = swz_row<DH * 2>(l31), swT = swz_row<128>(l31);
+  stage(kv_first, 0);
+  for (int kt = kv_first; kt <= kv_last; kt++) {
+    const int b = (kt - kv_first) & 1;
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();
+    if (kt < kv_last) stage(kt + 1, b ^ 1);
+    const int k0 = kt * BKEY;
+    if (k0 > t_base + 31 || t_base >= n) continue;
+    const bf16_t* sK = sm + b * ST_E; const bf16_t* sV = sK + KT_E; const bf16_t* sKt = sK + 2 * KT_E;
+    f32x16 s[2], dp[2];
+    s[0] = zero16(); s[1] = zero16(); dp[0] = zero16(); dp[1] = zero16();
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++) {
+        const int off = (kb * 32 + l31) * DH + (((ks * 2 + h) ^ swK) * 8);
+        bf16x8 a = *reinterpret_cast<const bf16x8*>(sK + off);
+        bf16x8 bb = *reinterpret_cast<const bf16x8*>(sV + off);
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
+        dp[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb, dof[ks], dp[kb], 0, 0, 0);
+      }
+    if (!((k0 + 63 <= t_base) && (k0 >= ss_hi))) {          // the tile touches the diagonal or a segment start
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          int key = k0 + kb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+          s[kb][e] = (key >= ss && key <= tq) ? s[kb][e] : -INFINITY;
+        }
+    }
+    bf16x8 dsb[4];
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) {
+#pragma unroll
+      for (int e = 0; e < 16; e++) s[kb][e] = fast_exp2(fmaf(s[kb][e], sl2, neg_lse2)) * (dp[kb][e] - dl);
+      dsb[kb * 2] = pack8(s[kb], 0); dsb[kb * 2 + 1] = pack8(s[kb], 1);
+    }
+#pragma unroll
+    for (int x = 0; x < 4; x++)
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(sKt + (cb * 32 + l31) * BKEY + (((2 * x + h) ^ swT) * 8));
+        dq[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsb[x], dq[cb], 0, 0, 0);
+      }
+  }
+  if (tq < n) {
+    bf16_t* row = (bf16_t*)p.dq + (int64_t)tq * p.ldq + j * DH;
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+      for (int b4 = 0; b4 < 4; b4++) {
+        bf16x4 w;
+#pragma unroll
+        for (int i = 0; i < 4; i++) w[i] = (bf16_t)(dq[cb][b4 * 4 + i] * scale);
+        *reinterpret_cast<bf16x4*>(row + cb * 32 + 8 * b4 + 4 * h) = w;
+      }
+  }
+}
+
+// Wave = 32 keys of one KV head (a lane owns one key), workgroup = 8 waves = 256 keys and ONE query head of
+// the group (blockIdx.z); loops over 64-query tiles.  With several query heads per KV head each launch
+// writes float partials [query head][token][dh] that a second pass sums in head order: one workgroup
+// looping over all heads of the group would be several times longer than the average workgroup, and the
+// launch as long as its longest workgroup.  dK and dV come from two launches (WHICH = 0: dK,
+// needs S, dP and the dK product; WHICH = 1: dV, needs S and the dV product): with both sets of
+// accumulators in one wave the kernel needs more than 256 registers, which costs the second wave per
+// SIMD and a stream of accumulator-register copies; recomputing S in a second launch is cheaper.
+template <int DH, int WHICH>
+__global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float scale, float sl2, float* __restrict__ part) {
+  constexpr int KS = DH / 16, CB = DH / 32, NWV = 8, KPB = 32 * NWV;
+  constexpr int KT_E = BKEY * DH;
+  constexpr int NT = WHICH == 0 ? 3 : 2;                  // dK: Q, dO, Q^T tiles; dV: Q, dO^T tiles
+  constexpr int ST_E = NT * KT_E + 4 * BKEY;              // + 64 lse and 64 delta floats (2 bf16 slots each)
+  extern __shared__ __align__(16) unsigned char dyn_smem[];
+  bf16_t* sm = (bf16_t*)dyn_smem;
+  const int tid = threadIdx.x, lane = tid & 63, l31 = lane & 31, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = p.n, grp = p.Hq / p.Hkv, g = blockIdx.y;
+  const int u_wg = (p.order_k ? p.order_k[blockIdx.x] : (int)blockIdx.x) * KPB, u_base = u_wg + wave * 32;
+  const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* V = (const bf16_t*)p.v;
+  const bf16_t* dO = (const bf16_t*)p.d_o; const bf16_t* QTm = (const bf16_t*)p.qT; const bf16_t* DOT = (const bf16_t*)p.doT;
+  const int u = u_base + l31, uc = min(u, n - 1);
+  const int uend = (u < n) ? p.seg_end[uc] : 0;                 // queries u <= t < uend see this key
+  bf16x8 kf[KS], vf[WHICH == 0 ? KS : 1];
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) {
+    kf[ks] = *reinterpret_cast<const bf16x8*>(K + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
+    if constexpr (WHICH == 0) vf[ks] = *reinterpret_cast<const bf16x8*>(V + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
+  }
+  f32x16 acc[CB];                                               // dK^T or dV^T, [dh rows, key lane]
+#pragma unroll
+  for (int cb = 0; cb < CB; cb++) acc[cb] = zero16();
+  const int q_first = u_wg / BKEY;
+  const int q_last = __builtin_amdgcn_readfirstlane((p.seg_end[min(u_wg + KPB - 1, n - 1)] - 1) / BKEY);
+  // this wave's keys are visible from queries in [u_base, w_end); all of them from queries in [u_base + 31, w_end_min)
+  const int w_end = (u_base < n) ? __builtin_amdgcn_readfirstlane(p.seg_end[min(u_base + 31, n - 1)]) : 0;
+  const int w_end_min = (u_base < n) ? __builtin_amdgcn_readfirstlane(p.seg_end[min(u_base, n - 1)]) : 0;
+  const int total = q_last - q_first + 1;
+  const int jj = g * grp + blockIdx.z;
+  auto stage = [&](int it, int b) {
+    const int t0 = (q_first + it) * BKEY;
+    bf16_t* d = sm + b * ST_E;
+    tile_to_lds<BKEY, DH, NWV>(Q + jj * DH, p.ldq, t0, n - 1, d, wave, lane);
+    if constexpr (WHICH == 0) {
+      tile_to_lds<BKEY, DH, NWV>(dO + jj * DH, (int64_t)p.Hq * DH, t0, n - 1, d + KT_E, wave, lane);
+      tile_to_lds<DH, BKEY, NWV>(QTm + (int64_t)jj * DH * p.ldT + t0, p.ldT, 0, DH - 1, d + 2 * KT_E, wave, lane);
+    } else {
+      tile_to_lds<DH, BKEY, NWV>(DOT + (int64_t)jj * DH * p.ldT + t0, p.ldT, 0, DH - 1, d + KT_E, wave, lane);
+    }
+    if (wave < (WHICH == 0 ? 2 : 1)) {                           // 64 lse (wave 0) and 64 delta (wave 1) values, 4 bytes a lane
+      const float* src = (wave == 0 ? p.lse : p.delta) + (int64_t)min(t0 + lane, n - 1) * p.Hq + jj;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)(d + NT * KT_E + wave * 2 * BKEY), 4, 0, 0);
+    }
+  };
+  const int swR = swz_row<DH * 2>(l31), swT = swz_row<128>(l31);
+  if (total > 0) stage(0, 0);
+  for (int it = 0; it < total; it++) {
+    const int b = it & 1;
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();
+    if (it + 1 < total) stage(it + 1, b ^ 1);
+    const int t0 = (q_first + it) * BKEY;
+    if (t0 + 63 < u_base || t0 >= w_end) continue;             // no query of the tile sees a key of this wave
+    const bf16_t* sQ = sm + b * ST_E;
+    const bf16_t* sdO = sQ + KT_E;                              // WHICH == 0 only
+    const bf16_t* sT = sQ + (NT - 1) * KT_E;                    // Q^T (dK) or dO^T (dV)
+    const float* sLse = (const float*)(sQ + NT * KT_E); const float* sDel = sLse + BKEY;
+    f32x16 s[2], dp[WHICH == 0 ? 2 : 1];
+    s[0] = zero16(); s[1] = zero16();
+    if constexpr (WHICH == 0) { dp[0] = zero16(); dp[1] = zero16(); }
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+      for (int qb = 0; qb < 2; qb++) {
+        const int off = (qb * 32 + l31) * DH + (((ks * 2 + h) ^ swR) * 8);
+        bf16x8 a = *reinterpret_cast<const bf16x8*>(sQ + off);
+        s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[ks], s[qb], 0, 0, 0);
+        if constexpr (WHICH == 0) {
+          bf16x8 bb = *reinterpret_cast<const bf16x8*>(sdO + off);
+          dp[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb, vf[ks], dp[qb], 0, 0, 0);
+        }
+      }
+    if (!((t0 >= u_base + 31) && (t0 + 63 < w_end_min))) {     // the tile touches the diagonal or a segment end
+#pragma unroll
+      for (int qb = 0; qb < 2; qb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int t = t0 + qb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+          s[qb][e] = (t >= u && t < uend) ? s[qb][e] : -INFINITY;
+        }
+    }
+    bf16x8 bop[4];                                              // dS (dK) or P (dV) as B operands
+#pragma unroll
+    for (int qb = 0; qb < 2; qb++) {
+#pragma unroll
+      for (int b4 = 0; b4 < 4; b4++) {
+        const int qi0 = qb * 32 + 8 * b4 + 4 * h;            // 4 consecutive queries: one 16-byte read each
+        const f32x4 ls = *reinterpret_cast<const f32x4*>(&sLse[qi0]);
+        f32x4 dl;
+        if constexpr (WHICH == 0) dl = *reinterpret_cast<const f32x4*>(&sDel[qi0]);
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          const int e = b4 * 4 + i;
+          const float pr = fast_exp2(fmaf(s[qb][e], sl2, -1.4426950408889634f * ls[i]));
+          if constexpr (WHICH == 0) s[qb][e] = pr * (dp[qb][e] - dl[i]); else s[qb][e] = pr;
+        }
+      }
+      bop[qb * 2] = pack8(s[qb], 0); bop[qb * 2 + 1] = pack8(s[qb], 1);
+    }
+#pragma unroll
+    for (int x = 0; x < 4; x++)
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(sT + (cb * 32 + l31) * BKEY + (((2 * x + h) ^ swT) * 8));
+        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bop[x], acc[cb], 0, 0, 0);
+      }
+  }
+  if (u >= n) return;
+  if (grp > 1) {
+    float* row = part + (((int64_t)WHICH * p.Hq + jj) * n + u) * DH;
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+      for (int b4 = 0; b4 < 4; b4++) {
+        f32x4 w;
+#pragma unroll
+        for (int i = 0; i < 4; i++) w[i] = acc[cb][b4 * 4 + i];
+        *reinterpret_cast<f32x4*>(row + cb * 32 + 8 * b4 + 4 * h) = w;
+      }
+  } else {
+    bf16_t* row = (bf16_t*)(WHICH == 0 ? p.dk : p.dv) + (int64_t)u * p.ldkv + g * DH;
+    const float sc = WHICH == 0 ? scale : 1.f;
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+      for (int b4 = 0; b4 < 4; b4++) {
+        bf16x4 w;
+#pragma unroll
+        for (int i = 0; i < 4; i++) w[i] = (bf16_t)(acc[cb][b4 * 4 + i] * sc);
+        *reinterpret_cast<bf16x4*>(row + cb * 32 + 8 * b4 + 4 * h) = w;
+      }
+  }
+}
+
+// dk[u, g, :] = scale * sum over the query heads of group g, in head order, of the dK partials; dv likewise (scale 1)
+__global__ void attn_dkv_reduce_kernel(const float* __restrict__ part, int n, int Hq, int Hkv, int dh, float scale,
+                                       bf16_t* __restrict__ dk, bf16_t* __restrict__ dv, int64_t ldkv) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;        // one thread: 4 columns of one (which, token, kv head)
+  const int c4 = dh / 4, grp = Hq / Hkv;
+  const int64_t per = (int64_t)n * Hkv * c4;
+  if (idx >= 2 * per) return;
+  const int which = (int)(idx / per);
+  const int64_t r = idx % per;
+  const int c = (int)(r % c4) * 4, g = (int)((r / c4) % Hkv);
+  const int64_t u = r / ((int64_t)c4 * Hkv);
+  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+  for (int z = 0; z < grp; z++) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(part + (((int64_t)which * Hq + g * grp + z) * n + u) * dh + c);
+    sum += v;
+  }
+  const float sc = which == 0 ? scale : 1.f;
+  bf16x4 w;
+#pragma unroll
+  for (int i = 0; i < 4; i++) w[i] = (bf16_t)(sum[i] * sc);
+  *reinterpret_cast<bf16x4*>((which == 0 ? dk : dv) + u * ldkv + g * dh + c) = w;
+}
+
+int heads_per_group(int grp) { return grp % 4 == 0 ? 4 : (grp % 2 == 0 ? 2 : 1); }
 int heads_per_wg(const AttnParams& p) {
   int grp = p.Hq / p.Hkv;
   return grp % 4 == 0 ? 4 : (grp % 2 == 0 ? 2 : 1);
 }
 
+template <int DH, int HPW, int QB>
+int launch_fwd2(as_ctx* ctx, const AttnParams& p, float sl2, hipStream_t st) {
+  constexpr size_t smem = (size_t)2 * 2 * BKEY * DH * sizeof(bf16_t);       // two stages of a K tile and a V^T tile
+  static bool attr_set = false;
+  if (!attr_set) {
+    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd2_mfma<DH, HPW, QB>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    attr_set = true;
+  }
+  constexpr int NWV = 8 / QB, QT = 32 * QB * (NWV / HPW);
+  attn_fwd2_mfma<DH, HPW, QB><<<dim3((unsigned)cdiv(p.n, QT), p.Hq / HPW), NWV * 64, smem, st>>>(p, sl2);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}
+
 template <int DH>
-int fwd_dh(as_ctx* ctx, const AttnParams& p_in, hipStream_t st) {
+int fwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
   AttnParams p = p_in;
   const int Np = (int)cdiv(p.n, 64) * 64, Dkv = p.Hkv * DH;
   if (!p.t_scratch) return as_fail(ctx, AS_ERR_WORKSPACE, "attention: the MFMA kernels need the token-major scratch buffer");
   p.ldT = Np; p.vT = p.t_scratch;
-  int rc = launch_transpose(ctx, AS_BF16, p.n, Np, Dkv, p.v, p.ldkv, p.t_scratch, Np, nullptr, 0, st);   // V^T [Dkv, Np]
+  int rc = variant >= 3 ? launch_transpose_qs(ctx, AS_BF16, p.n, Np, Dkv, p.v, p.ldkv, p.t_scratch, Np, st)
+                        : launch_transpose(ctx, AS_BF16, p.n, Np, Dkv, p.v, p.ldkv, p.t_scratch, Np, nullptr, 0, st);   // V^T [Dkv, Np]
   if (rc) return rc;
   const float sl2 = 1.4426950408889634f / sqrtf((float)DH);
   const int hpw = heads_per_wg(p);
+  if (variant == 3) return hpw == 4 ? launch_fwd2<DH, 4, 2>(ctx, p, sl2, st) : hpw == 2 ? launch_fwd2<DH, 2, 2>(ctx, p, sl2, st) : launch_fwd2<DH, 1, 2>(ctx, p, sl2, st);
+  if (variant == 4) return hpw == 4 ? launch_fwd2<DH, 4, 1>(ctx, p, sl2, st) : hpw == 2 ? launch_fwd2<DH, 2, 1>(ctx, p, sl2, st) : launch_fwd2<DH, 1, 1>(ctx, p, sl2, st);
   if (hpw == 4) attn_fwd_mfma<DH, 4><<<dim3((unsigned)cdiv(p.n, 64), p.Hq / 4), 256, 0, st>>>(p, sl2);
   else if (hpw == 2) attn_fwd_mfma<DH, 2><<<dim3((unsigned)cdiv(p.n, 128), p.Hq / 2), 256, 0, st>>>(p, sl2);
   else attn_fwd_mfma<DH, 1><<<dim3((unsigned)cdiv(p.n, 256), p.Hq), 256, 0, st>>>(p, sl2);
@@ -467,19 +916,64 @@ int fwd_dh(as_ctx* ctx, const AttnParams& p_in, hipStream_t st) {
   return AS_OK;
 }
 
+template <int DH, int HPW>
+int launch_dq2(as_ctx* ctx, const AttnParams& p, float scale, float sl2, hipStream_t st) {
+  constexpr size_t smem = (size_t)2 * 3 * BKEY * DH * sizeof(bf16_t);       // two stages of K, V and K^T tiles
+  static bool attr_set = false;
+  if (!attr_set) {
+    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dq2_mfma<DH, HPW>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    attr_set = true;
+  }
+  attn_bwd_dq2_mfma<DH, HPW><<<dim3((unsigned)cdiv(p.n, 32 * (8 / HPW)), p.Hq / HPW), 512, smem, st>>>(p, scale, sl2);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}
+
+template <int DH, int WHICH>
+int launch_dkv2(as_ctx* ctx, const AttnParams& p, float scale, float sl2, float* part, hipStream_t st) {
+  constexpr size_t smem = (size_t)2 * ((WHICH == 0 ? 3 : 2) * BKEY * DH + 4 * BKEY) * sizeof(bf16_t);
+  static bool attr_set = false;
+  if (!attr_set) {
+    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv2_mfma<DH, WHICH>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    attr_set = true;
+  }
+  attn_bwd_dkv2_mfma<DH, WHICH><<<dim3((unsigned)cdiv(p.n, 256), p.Hkv, p.Hq / p.Hkv), 512, smem, st>>>(p, scale, sl2, part);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}
+
 template <int DH>
-int bwd_dh(as_ctx* ctx, const AttnParams& p_in, hipStream_t st) {
+int bwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
   AttnParams p = p_in;
   const int Np = (int)cdiv(p.n, 64) * 64, Dkv = p.Hkv * DH, D = p.Hq * DH;
   if (!p.t_scratch) return as_fail(ctx, AS_ERR_WORKSPACE, "attention: the MFMA kernels need the token-major scratch buffer");
   bf16_t* ts = (bf16_t*)p.t_scratch;
   p.ldT = Np; p.kT = ts; p.qT = ts + (size_t)Dkv * Np; p.doT = ts + (size_t)(Dkv + D) * Np;
   int rc;
+  const float scale = 1.f / sqrtf((float)DH), sl2 = 1.4426950408889634f * scale;
+  const int64_t rows = (int64_t)p.n * p.Hq;
+  if (variant >= 3) {
+    if ((rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, Dkv, p.k, p.ldkv, ts, Np, st))) return rc;                       // K^T
+    if ((rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, D, p.q, p.ldq, ts + (size_t)Dkv * Np, Np, st))) return rc;       // Q^T
+    if ((rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, D, p.d_o, D, ts + (size_t)(Dkv + D) * Np, Np, st))) return rc;   // dO^T
+    attn_delta_kernel<<<(unsigned)cdiv(rows, 4), 256, 0, st>>>((const bf16_t*)p.o, (const bf16_t*)p.d_o, rows, DH, p.delta);
+    AS_LAUNCH_CHECK(ctx);
+    const int hpw = heads_per_wg(p);
+    if (hpw == 4) rc = launch_dq2<DH, 4>(ctx, p, scale, sl2, st); else if (hpw == 2) rc = launch_dq2<DH, 2>(ctx, p, scale, sl2, st);
+    else rc = launch_dq2<DH, 1>(ctx, p, scale, sl2, st);
+    if (rc) return rc;
+    float* part = (float*)(ts + (size_t)(Dkv + 2 * D) * Np);       // [2][Hq][n][dh] floats behind the token-major copies
+    if ((rc = launch_dkv2<DH, 0>(ctx, p, scale, sl2, part, st)) || (rc = launch_dkv2<DH, 1>(ctx, p, scale, sl2, part, st))) return rc;
+    if (p.Hq > p.Hkv) {
+      const int64_t threads = 2 * (int64_t)p.n * p.Hkv * (DH / 4);
+      attn_dkv_reduce_kernel<<<(unsigned)cdiv(threads, 256), 256, 0, st>>>(part, p.n, p.Hq, p.Hkv, DH, scale, (bf16_t*)p.dk, (bf16_t*)p.dv, p.ldkv);
+      AS_LAUNCH_CHECK(ctx);
+    }
+    return AS_OK;
+  }
   if ((rc = launch_transpose(ctx, AS_BF16, p.n, Np, Dkv, p.k, p.ldkv, ts, Np, nullptr, 0, st))) return rc;                       // K^T
   if ((rc = launch_transpose(ctx, AS_BF16, p.n, Np, D, p.q, p.ldq, ts + (size_t)Dkv * Np, Np, nullptr, 0, st))) return rc;       // Q^T
   if ((rc = launch_transpose(ctx, AS_BF16, p.n, Np, D, p.d_o, D, ts + (size_t)(Dkv + D) * Np, Np, nullptr, 0, st))) return rc;   // dO^T
-  const float scale = 1.f / sqrtf((float)DH), sl2 = 1.4426950408889634f * scale;
-  const int64_t rows = (int64_t)p.n * p.Hq;
   attn_delta_kernel<<<(unsigned)cdiv(rows, 4), 256, 0, st>>>((const bf16_t*)p.o, (const bf16_t*)p.d_o, rows, DH, p.delta);
   AS_LAUNCH_CHECK(ctx);
   const int hpw = heads_per_wg(p);
@@ -502,6 +996,8 @@ int bwd_dh(as_ctx* ctx, const AttnParams& p_in, hipStream_t st) {
 
 }  // namespace
 
+int attention_query_tile(int n_q_heads, int n_kv_heads) { return 32 * (8 / heads_per_group(n_q_heads / n_kv_heads)); }
+
 bool attention_mfma_ok(const AttnParams& p) {
   if (p.dh != 64 && p.dh != 128) return false;
   if (p.ldq % 8 || p.ldkv % 8) return false;
@@ -510,10 +1006,14 @@ bool attention_mfma_ok(const AttnParams& p) {
   return a % 16 == 0;
 }
 
-int launch_attention_fwd_mfma(as_ctx* ctx, const AttnParams& p, hipStream_t st) {
-  return p.dh == 128 ? fwd_dh<128>(ctx, p, st) : fwd_dh<64>(ctx, p, st);
+// variant: 0 = default (4), 2 = first-generation kernels, 3 = second generation with 64-query waves (forward),
+// 4 = second generation with 32-query waves
+int launch_attention_fwd_mfma(as_ctx* ctx, const AttnParams& p, int variant, hipStream_t st) {
+  if (variant == 0) variant = 4;
+  return p.dh == 128 ? fwd_dh<128>(ctx, p, variant, st) : fwd_dh<64>(ctx, p, variant, st);
 }
 
-int launch_attention_bwd_mfma(as_ctx* ctx, const AttnParams& p, hipStream_t st) {
-  return p.dh == 128 ? bwd_dh<128>(ctx, p, st) : bwd_dh<64>(ctx, p, st);
+int launch_attention_bwd_mfma(as_ctx* ctx, const AttnParams& p, int variant, hipStream_t st) {
+  if (variant == 0) variant = 4;
+  return p.dh == 128 ? bwd_dh<128>(ctx, p, variant, st) : bwd_dh<64>(ctx, p, variant, st);
 }

@@ -104,8 +104,12 @@ struct AttnParams {
   // to 64): forward needs Hkv*dh rows (V^T), backward (2*Hq + Hkv)*dh rows (K^T, Q^T, dO^T)
   void* t_scratch;
   const void *qT, *kT, *vT, *doT; int64_t ldT;   // filled by the launchers
+  // optional launch orders (device arrays, longest workgroups first): order_q[i] = query tile of workgroup i
+  // (tiles of attention_query_tile() tokens), order_k[i] = key block (256 keys) of workgroup i in the dK / dV launches
+  const int32_t* order_q; const int32_t* order_k;
 };
 int launch_attention_fwd(as_ctx* ctx, int mode, int variant, const AttnParams& p, hipStream_t st);
+int attention_query_tile(int n_q_heads, int n_kv_heads);   // tokens per workgroup of the forward and dQ MFMA kernels
 int launch_attention_bwd(as_ctx* ctx, int mode, int variant, const AttnParams& p, hipStream_t st);
 
 // ---- element-wise and friends (elementwise.hip) ---------------------------------
@@ -144,6 +148,8 @@ int launch_swiglu_bwd(as_ctx* ctx, int mode, int64_t n, int F, const void* dm, c
 // or past *rows_dev - row_off)
 int launch_transpose(as_ctx* ctx, int mode, int rows, int rows_pad, int cols, const void* in, int64_t ldi, void* out,
                      int64_t ldo, const int* rows_dev, int row_off, hipStream_t st);
+int launch_transpose_qs(as_ctx* ctx, int mode, int rows, int rows_pad, int cols, const void* in, int64_t ldi, void* out,
+                        int64_t ldo, hipStream_t st);
 // out[rows_pad, cols_pad] (type T, row stride ldo) = scale * in[rows, cols] (float), zero in the
 // padding; out_t (row stride ldo_t) receives the transpose.  Either output may be NULL.
 int launch_lora_prep2(as_ctx* ctx, int mode, const float* in, int rows, int cols, int rows_pad, int cols_pad,

@@ -407,7 +407,10 @@ int launch_swiglu_bwd(as_ctx* ctx, int mode, int64_t n, int F, const void* dm, c
 // --------------------------------------------------------------- transpose
 // out[c, r] = in[r, c] through a padded 64x64 LDS tile; rows past the
 // device-side row count (if given) read as zero.
-template <typename T>
+// QS: inside every group of 16 output positions the two middle quads are exchanged (position order
+// 0-3, 8-11, 4-7, 12-15 of the source rows), which is the order one lane half of a 32x32x16 MFMA
+// holds its 8 contraction indices in: such a fragment is then one 16-byte read.
+template <typename T, bool QS>
 __global__ void transpose_kernel(int rows, int rows_pad, int cols, const T* __restrict__ in, int64_t ldi,
                                  T* __restrict__ out, int64_t ldo, const int* __restrict__ rows_dev, int row_off) {
   __shared__ T tile[64][65];
@@ -421,7 +424,8 @@ __global__ void transpose_kernel(int rows, int rows_pad, int cols, const T* __re
   __syncthreads();
   for (int i = ty; i < 64; i += 4) {
     int c = c0 + i, r = r0 + tx;
-    if (c < cols && r < rows_pad) out[(int64_t)c * ldo + r] = tile[tx][i];
+    const int src = QS ? ((tx & ~12) | ((tx & 4) << 1) | ((tx & 8) >> 1)) : tx;
+    if (c < cols && r < rows_pad) out[(int64_t)c * ldo + r] = tile[src][i];
   }
 }
 
@@ -430,7 +434,20 @@ int launch_transpose(as_ctx* ctx, int mode, int rows, int rows_pad, int cols, co
   if (rows <= 0 || cols <= 0) return AS_OK;
   dim3 grid(cdiv(cols, 64), cdiv(rows_pad, 64));
   prof_begin(ctx, st, AS_K_TRANSPOSE, 0.0);
-  DISPATCH_T(mode, (transpose_kernel<T><<<grid, 256, 0, st>>>(rows, rows_pad, cols, (const T*)in, ldi, (T*)out, ldo, rows_dev, row_off)));
+  DISPATCH_T(mode, (transpose_kernel<T, false><<<grid, 256, 0, st>>>(rows, rows_pad, cols, (const T*)in, ldi, (T*)out, ldo, rows_dev, row_off)));
+  prof_end(ctx, st);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}
+
+// the quad-swapped variant (rows_pad must be a multiple of 16)
+int launch_transpose_qs(as_ctx* ctx, int mode, int rows, int rows_pad, int cols, const void* in, int64_t ldi, void* out,
+                        int64_t ldo, hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return AS_OK;
+  if (rows_pad % 16) return as_fail(ctx, AS_ERR_SHAPE, "transpose: the quad-swapped layout needs a row count padded to 16");
+  dim3 grid(cdiv(cols, 64), cdiv(rows_pad, 64));
+  prof_begin(ctx, st, AS_K_TRANSPOSE, 0.0);
+  DISPATCH_T(mode, (transpose_kernel<T, true><<<grid, 256, 0, st>>>(rows, rows_pad, cols, (const T*)in, ldi, (T*)out, ldo, nullptr, 0)));
   prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;

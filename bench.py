@@ -6,7 +6,7 @@ adapter gradients.  Inputs (weights, adapters, packed tokens, masks) are in
 HBM before the timed region; packing and AdamW are timed separately and
 reported beside the headline value.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line (the README lists the fields).
 """
 import argparse
 import json
@@ -20,6 +20,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+# HBM-side bytes per launch of the dominant kernel at config 3 (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, two counter
+# runs over one bench step, see profiles/gemm_256_counters.md); only valid for the kernel those runs saw
+TRAFFIC_BYTES_PER_LAUNCH = {(3, "gemm_mfma_dlds_kernel<256,256,2,4,true,1,200,0>"): 8.0e9}
+DOMINANT_KERNEL = "gemm_mfma_dlds_kernel<256,256,2,4,true,1,200,0>"
 
 
 def device_weights(sh, seed, dtype):
@@ -252,10 +256,12 @@ def main():
         "loss": round(loss, 5), "pack_ms": round(pack_ms, 2), "adamw_ms": None if adam_ms is None else round(adam_ms, 3),
         "wall_s_timed_region": round(wall, 3),
         "kernel_ms_per_step": breakdown,
-        "roofline": {"kernel": "gemm_mfma_dlds_kernel<256,256,2,4,...> (expert GEMMs over grouped rows, forward + dX)" if sh.n_experts else
-                     "gemm_mfma_dlds_kernel<256,256,2,4,...> (projection GEMMs forward + dX, LoRA term as second K segment)",
+        "roofline": {"kernel": DOMINANT_KERNEL + (" (expert GEMMs over grouped rows, forward + dX)" if sh.n_experts else
+                                                  " (projection GEMMs forward + dX, LoRA term as second K segment)"),
                      "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None if sh.n_experts else TRAFFIC_BYTES_PER_LAUNCH.get((args.config, DOMINANT_KERNEL)),
+                     "traffic_unit": "HBM-side bytes per launch (counters)",
                      "launches_per_step": n_l // max(args.steps, 1), "avg_launch_ms": round(ms_l / max(n_l, 1), 4)},
     }
     if not args.no_cpu_baseline and not sh.n_experts:     # the sparse model's float64 weights do not fit the sample budget

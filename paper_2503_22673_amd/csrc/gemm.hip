@@ -591,7 +591,7 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
   if (p.splitk > 1 && !p.partial) return as_fail(ctx, AS_ERR_WORKSPACE, "gemm: split-K needs a partial buffer");
   if (p.accumulate && !p.c_f32) return as_fail(ctx, AS_ERR_SHAPE, "gemm: accumulate needs float output");
   if (p.grp_off && p.splitk > 1) return as_fail(ctx, AS_ERR_SHAPE, "gemm: grouped rows and split-K do not combine");
-  if (variant < 0 || (variant > 2 && (variant < 10 || variant > 30))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
+  if (variant < 0 || (variant > 2 && (variant < 10 || variant > 31))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
   bool use_mfma = (mode == AS_BF16) && variant != 1 && mfma_ok(p);
   if (variant >= 2 && !use_mfma) return as_fail(ctx, AS_ERR_SHAPE, "gemm: MFMA kernel needs bf16 and 8-element alignment");
   int rc = AS_OK;
@@ -623,6 +623,7 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
       case 18: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 104>(ctx, p, m_off, st); break;
       case 19: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 106>(ctx, p, m_off, st); break;
       case 20: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 200>(ctx, p, m_off, st); break;
+      case 21: rc = launch_dlds_cfg<256, 256, 2, 2, true, 1, 200>(ctx, p, m_off, st); break;
       default: rc = launch_mfma_cfg<256, 256, 2, 4>(ctx, p, m_off, st); break;
     }
   } else {

@@ -259,9 +259,11 @@ __device__ __forceinline__ void tile_to_lds(const bf16_t* base, int64_t ld, int 
 
 // Wave = QB blocks of 32 queries of one head; workgroup = HPW heads x (NWV / HPW) query groups, NWV = 8 / QB waves.
 // QB = 1 keeps a wave under 256 registers, so two waves share a SIMD and one's softmax runs under the other's MFMAs.
-template <int DH, int HPW, int QB>
-__global__ __launch_bounds__(512 / QB) void attn_fwd2_mfma(AttnParams p, float sl2) {
-  constexpr int KS = DH / 16, CB = DH / 32, NWV = 8 / QB, WQ = 32 * QB, QT = WQ * (NWV / HPW);
+// NWV = 4 with QB = 1: two independent 4-wave workgroups per CU instead of one of eight waves; the register cap
+// (two waves per SIMD) then has to be asked for explicitly.
+template <int DH, int HPW, int QB, int NWV>
+__global__ __launch_bounds__(NWV * 64, QB == 1 ? 2 : 1) void attn_fwd2_mfma(AttnParams p, float sl2) {
+  constexpr int KS = DH / 16, CB = DH / 32, WQ = 32 * QB, QT = WQ * (NWV / HPW);
   constexpr int KT_E = BKEY * DH, ST_E = 2 * KT_E;        // elements of one tile / of one stage (K tile + V^T tile)
   extern __shared__ __align__(16) unsigned char dyn_smem[];
   bf16_t* sm = (bf16_t*)dyn_smem;
@@ -311,14 +313,34 @@ __global__ __launch_bounds__(512 / QB) void attn_fwd2_mfma(AttnParams p, float s
     f32x16 s[QB][2];
 #pragma unroll
     for (int qb = 0; qb < QB; qb++) { s[qb][0] = zero16(); s[qb][1] = zero16(); }
+    // fragments are read PFD MFMA steps ahead of their use (LDS latency is several MFMA times)
+    constexpr int PFD = 6, NQK = 2 * KS, NPV = 4 * CB;
+    auto kfrag = [&](int i) { const int ks = i >> 1, kb = i & 1;
+      return *reinterpret_cast<const bf16x8*>(sK + (kb * 32 + l31) * DH + (((ks * 2 + h) ^ swK) * 8)); };
+    auto vfrag = [&](int i) { const int x = i / CB, cb = i % CB;   // quad-swapped token order: chunk 2x + h of the row holds this lane half's 8 keys
+      return *reinterpret_cast<const bf16x8*>(sVt + (cb * 32 + l31) * BKEY + (((2 * x + h) ^ swV) * 8)); };
+    {
+      bf16x8 kq[PFD];
 #pragma unroll
-    for (int ks = 0; ks < KS; ks++)
+      for (int i = 0; i < PFD; i++) kq[i] = kfrag(i);
 #pragma unroll
-      for (int kb = 0; kb < 2; kb++) {
-        bf16x8 a = *reinterpret_cast<const bf16x8*>(sK + (kb * 32 + l31) * DH + (((ks * 2 + h) ^ swK) * 8));
+      for (int i = 0; i < NQK; i++) {
+        const bf16x8 a = kq[i % PFD];
+        if (i + PFD < NQK) kq[i % PFD] = kfrag(i + PFD);
 #pragma unroll
-        for (int qb = 0; qb < QB; qb++) s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s[qb][kb], 0, 0, 0);
+        for (int qb = 0; qb < QB; qb++) s[qb][i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][i >> 1], s[qb][i & 1], 0, 0, 0);
       }
+      __builtin_amdgcn_sched_group_barrier(0x100, PFD, 0);
+#pragma unroll
+      for (int i = 0; i < NQK - PFD; i++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, PFD * QB, 0);
+    }
+    bf16x8 vq[PFD];                                          // the first V fragments do not depend on the softmax
+#pragma unroll
+    for (int i = 0; i < PFD; i++) vq[i] = vfrag(i);
     const bool full = (k0 + 63 <= t_base) && (k0 >= ss_hi);  // every key of the tile is visible to every query of the wave
     bf16x8 pb[QB][4];
 #pragma unroll
@@ -361,15 +383,18 @@ __global__ __launch_bounds__(512 / QB) void attn_fwd2_mfma(AttnParams p, float s
       for (int kb = 0; kb < 2; kb++) { pb[qb][kb * 2] = pack8(s[qb][kb], 0); pb[qb][kb * 2 + 1] = pack8(s[qb][kb], 1); }
     }
 #pragma unroll
-    for (int x = 0; x < 4; x++) {                            // x = kb*2 + sl: 16 keys each
+    for (int i = 0; i < NPV; i++) {                          // i = x * CB + cb, x = kb*2 + sl: 16 keys each
+      const bf16x8 a = vq[i % PFD];
+      if (i + PFD < NPV) vq[i % PFD] = vfrag(i + PFD);
 #pragma unroll
-      for (int cb = 0; cb < CB; cb++) {
-        // quad-swapped token order: the 8 keys this lane half contracts over are chunk 2x + h of the row
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(sVt + (cb * 32 + l31) * BKEY + (((2 * x + h) ^ swV) * 8));
-#pragma unroll
-        for (int qb = 0; qb < QB; qb++) o[qb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb][x], o[qb][cb], 0, 0, 0);
-      }
+      for (int qb = 0; qb < QB; qb++) o[qb][i % CB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb][i / CB], o[qb][i % CB], 0, 0, 0);
     }
+#pragma unroll
+    for (int i = 0; i < NPV - PFD; i++) {
+      __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, PFD * QB, 0);
   }
   bf16_t* O = (bf16_t*)p.o;
 #pragma unroll
@@ -882,16 +907,18 @@ int heads_per_wg(const AttnParams& p) {
   return grp % 4 == 0 ? 4 : (grp % 2 == 0 ? 2 : 1);
 }
 
-template <int DH, int HPW, int QB>
-int launch_fwd2(as_ctx* ctx, const AttnParams& p, float sl2, hipStream_t st) {
+template <int DH, int HPW, int QB, int NWV = 8 / QB>
+int launch_fwd2(as_ctx* ctx, const AttnParams& p_in, float sl2, hipStream_t st) {
+  AttnParams p = p_in;
+  if (32 * QB * (NWV / HPW) != attention_query_tile(p.Hq, p.Hkv)) p.order_q = nullptr;   // the order table is cut for another tile size
   constexpr size_t smem = (size_t)2 * 2 * BKEY * DH * sizeof(bf16_t);       // two stages of a K tile and a V^T tile
   static bool attr_set = false;
   if (!attr_set) {
-    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd2_mfma<DH, HPW, QB>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd2_mfma<DH, HPW, QB, NWV>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_set = true;
   }
-  constexpr int NWV = 8 / QB, QT = 32 * QB * (NWV / HPW);
-  attn_fwd2_mfma<DH, HPW, QB><<<dim3((unsigned)cdiv(p.n, QT), p.Hq / HPW), NWV * 64, smem, st>>>(p, sl2);
+  constexpr int QT = 32 * QB * (NWV / HPW);
+  attn_fwd2_mfma<DH, HPW, QB, NWV><<<dim3((unsigned)cdiv(p.n, QT), p.Hq / HPW), NWV * 64, smem, st>>>(p, sl2);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
@@ -908,6 +935,7 @@ int fwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
   const float sl2 = 1.4426950408889634f / sqrtf((float)DH);
   const int hpw = heads_per_wg(p);
   if (variant == 3) return hpw == 4 ? launch_fwd2<DH, 4, 2>(ctx, p, sl2, st) : hpw == 2 ? launch_fwd2<DH, 2, 2>(ctx, p, sl2, st) : launch_fwd2<DH, 1, 2>(ctx, p, sl2, st);
+  if (variant == 5) return hpw == 4 ? launch_fwd2<DH, 4, 1, 4>(ctx, p, sl2, st) : hpw == 2 ? launch_fwd2<DH, 2, 1, 4>(ctx, p, sl2, st) : launch_fwd2<DH, 1, 1, 4>(ctx, p, sl2, st);
   if (variant == 4) return hpw == 4 ? launch_fwd2<DH, 4, 1>(ctx, p, sl2, st) : hpw == 2 ? launch_fwd2<DH, 2, 1>(ctx, p, sl2, st) : launch_fwd2<DH, 1, 1>(ctx, p, sl2, st);
   if (hpw == 4) attn_fwd_mfma<DH, 4><<<dim3((unsigned)cdiv(p.n, 64), p.Hq / 4), 256, 0, st>>>(p, sl2);
   else if (hpw == 2) attn_fwd_mfma<DH, 2><<<dim3((unsigned)cdiv(p.n, 128), p.Hq / 2), 256, 0, st>>>(p, sl2);

@@ -523,6 +523,156 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
                         (row0 + BM <= M) && (col0 + BN <= p.N), rb);
 }
 
+// Deep-pipeline variant: K steps of 32 (64-byte tile rows) and NS LDS stages, so that NS - 1 steps of tile loads
+// are in flight while one is consumed.  In the two-stage kernel above the loads of a step have one step's time
+// to arrive; measured with cycle stamps, its waves spend a third of every step at the barrier waiting for
+// the one wave whose loads came back late.  Same tile, wave layout, fragment order and epilogue.
+// Rows of 64 bytes hold four 16-byte chunks; chunk c of row r sits at chunk c ^ ((r >> 2) & 3).
+// With 4 waves per workgroup (256x128 or 128x256 tiles) two workgroups share a CU: their barriers are independent,
+// so one's waves keep the matrix cores busy while the other's wait.
+constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (lgkm << 8); }
+template <int BM, int BN, int WM, int WN, int NS>
+__global__ __launch_bounds__(WM * WN * 64, WM * WN == 4 ? 2 : 1) void gemm_mfma_deep_kernel(GemmParams p, int m_off, int tiles_m, int tiles_n) {
+  constexpr int BK = 32, NW = WM * WN;
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int LA = BM / 16 / NW, LB = BN / 16 / NW;    // 1 KB wave-loads (16 rows) per wave and tile
+  constexpr int ST_E = (BM + BN) * BK;                   // elements per stage
+  static_assert(LA >= 1 && LB >= 1, "tile too small for the wave count");
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t* sm = (bf16_t*)smem;
+
+  int rb, mmax;
+  const int M = gemm_rows(p, m_off, rb, mmax);
+  if (p.m_dev || p.grp_off) tiles_m = min(tiles_m, (max(M, 0) + BM - 1) / BM);
+  int nblk = tiles_m * tiles_n, pid = blockIdx.x, z = blockIdx.y;
+  if (pid >= nblk) return;
+  int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
+  int logical = xcd * q8 + min(xcd, rem) + loc;
+  constexpr int GROUP = 8;
+  int in_group = GROUP * tiles_n, grp = logical / in_group, first_m = grp * GROUP;
+  int gsize = min(tiles_m - first_m, GROUP);
+  int tile_m = first_m + (logical % in_group) % gsize, tile_n = (logical % in_group) / gsize;
+  const int row0 = tile_m * BM, col0 = tile_n * BN;
+  if (row0 >= M) return;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  KRange kr0 = split_range(p.seg[0].K, BK, p.splitk, z);
+  KRange kr1 = {0, 0};
+  if (p.nseg > 1) kr1 = split_range(p.seg[1].K, BK, p.splitk, z);
+  const int nt0 = kr0.end - kr0.beg, nt = nt0 + (kr1.end - kr1.beg);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  // loader: wave-load i of this wave covers tile rows (wave*L + i)*16 .. +15; lane l sits at row l/4, LDS chunk l%4
+  const int lrow = lane >> 2;
+  int rowA[LA], rowB[LB];
+#pragma unroll
+  for (int i = 0; i < LA; i++) rowA[i] = rb + min(row0 + (wave * LA + i) * 16 + lrow, mmax);
+#pragma unroll
+  for (int i = 0; i < LB; i++) rowB[i] = min(col0 + (wave * LB + i) * 16 + lrow, p.N - 1);
+  const int gch = ((lane & 3) ^ ((lrow >> 2) & 3)) * 8;  // (tile row >> 2) & 3 == (lrow >> 2) & 3: loads start at multiples of 16 rows
+  auto fetch = [&](int it, int st) {
+    const bool first = it < nt0;
+    const bf16_t* A = (const bf16_t*)(first ? p.seg[0].A : p.seg[1].A);
+    const bf16_t* B = (const bf16_t*)(first ? p.seg[0].B : p.seg[1].B);
+    const int64_t lda = first ? p.seg[0].lda : p.seg[1].lda, ldb = first ? p.seg[0].ldb : p.seg[1].ldb;
+    const int k = (first ? kr0.beg + it : kr1.beg + it - nt0) * BK;
+    bf16_t* a = sm + st * ST_E + wave * LA * 16 * BK;
+    bf16_t* b = sm + st * ST_E + BM * BK + wave * LB * 16 * BK;
+#pragma unroll
+    for (int i = 0; i < LA; i++)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(A + (int64_t)rowA[i] * lda + k + gch),
+                                       (__attribute__((address_space(3))) void*)(a + i * 16 * BK), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < LB; i++)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(B + (int64_t)rowB[i] * ldb + k + gch),
+                                       (__attribute__((address_space(3))) void*)(b + i * 16 * BK), 16, 0, 0);
+  };
+
+  // reader: row = base + l%32, logical chunk 2*ks + l/32
+  const int l31 = lane & 31, hh = lane >> 5, x3 = (l31 >> 2) & 3;
+  const int coff0 = ((0 + hh) ^ x3) * 8, coff1 = ((2 + hh) ^ x3) * 8;
+  bf16x8 af[2][TM], bfr[2][TN];
+  auto rd = [&](int st, int ks, int slot) {
+    const bf16_t* a = sm + st * ST_E + (wm * TM * 32 + l31) * BK + (ks ? coff1 : coff0);
+    const bf16_t* b = sm + st * ST_E + BM * BK + (wn * TN * 32 + l31) * BK + (ks ? coff1 : coff0);
+#pragma unroll
+    for (int i = 0; i < TM; i++) af[slot][i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * BK);
+#pragma unroll
+    for (int j = 0; j < TN; j++) bfr[slot][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * BK);
+  };
+  auto mm = [&](int slot) {
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
+  };
+  auto weave = [&]() {
+#pragma unroll
+    for (int r = 0; r < TM + TN; r++) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+  };
+
+  // NS - 1 steps in flight; every step issues the same LA + LB loads (the last ones re-request the final
+  // step into a stage nobody reads again), so the wait counts are static
+  constexpr int NL = LA + LB;
+  if (nt > 0) {
+#pragma unroll
+  for (int i = 0; i < NS - 1; i++) fetch(min(i, nt - 1), i);
+  // step 0 has landed when at most (NS - 2) * NL loads are outstanding
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm((NS - 2) * NL, 15));
+  __syncthreads();
+  rd(0, 0, 0);
+  for (int it = 0; it < nt; it++) {
+    const int st = it % NS;
+    fetch(min(it + NS - 1, nt - 1), (it + NS - 1) % NS);   // into the stage of step it-1: every wave left it before the last barrier
+    rd(st, 1, 1); mm(0); weave();
+    // step it+1 must have landed: the loads of steps it+2 .. it+NS-1 may stay in flight
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm((NS - 2) * NL, 0));
+    __builtin_amdgcn_s_barrier();
+    rd((it + 1) % NS, 0, 0);
+    mm(1);
+#pragma unroll
+    for (int r = 0; r < TM + TN; r++) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0f70);                    // re-requested steps must land before the workgroup's LDS is released
+  }
+  gemm_epilogue<TM, TN>(p, acc, M, z, row0, col0, row0 + wm * TM * 32 + 4 * (lane >> 5), col0 + wn * TN * 32 + (lane & 31),
+                        (row0 + BM <= M) && (col0 + BN <= p.N), rb);
+}
+
+template <int BM, int BN, int WM, int WN, int NS>
+static int launch_deep_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_t st) {
+  size_t smem = (size_t)NS * (BM + BN) * 32 * sizeof(bf16_t);
+  auto k0 = gemm_mfma_deep_kernel<BM, BN, WM, WN, NS>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(k0), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    attr_set = true;
+  }
+  int tm = (int)cdiv(p.M, BM), tn = (int)cdiv(p.N, BN);
+  dim3 grid(tm * tn, p.splitk > 1 ? p.splitk : 1);
+  k0<<<grid, WM * WN * 64, smem, st>>>(p, m_off, tm, tn);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}
+
 template <int BM, int BN, int WM, int WN, bool DB, int SWZ, int PF = 0, int MAP = 0>
 static int launch_dlds_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_t st) {
   size_t smem = (size_t)2 * (BM + BN) * 64 * sizeof(bf16_t);
@@ -591,7 +741,7 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
   if (p.splitk > 1 && !p.partial) return as_fail(ctx, AS_ERR_WORKSPACE, "gemm: split-K needs a partial buffer");
   if (p.accumulate && !p.c_f32) return as_fail(ctx, AS_ERR_SHAPE, "gemm: accumulate needs float output");
   if (p.grp_off && p.splitk > 1) return as_fail(ctx, AS_ERR_SHAPE, "gemm: grouped rows and split-K do not combine");
-  if (variant < 0 || (variant > 2 && (variant < 10 || variant > 31))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
+  if (variant < 0 || (variant > 2 && (variant < 10 || variant > 33))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
   bool use_mfma = (mode == AS_BF16) && variant != 1 && mfma_ok(p);
   if (variant >= 2 && !use_mfma) return as_fail(ctx, AS_ERR_SHAPE, "gemm: MFMA kernel needs bf16 and 8-element alignment");
   int rc = AS_OK;
@@ -624,6 +774,8 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
       case 19: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 106>(ctx, p, m_off, st); break;
       case 20: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 200>(ctx, p, m_off, st); break;
       case 21: rc = launch_dlds_cfg<256, 256, 2, 2, true, 1, 200>(ctx, p, m_off, st); break;
+      case 22: rc = launch_deep_cfg<256, 256, 2, 4, 4>(ctx, p, m_off, st); break;
+      case 23: rc = launch_deep_cfg<256, 128, 2, 2, 3>(ctx, p, m_off, st); break;
       default: rc = launch_mfma_cfg<256, 256, 2, 4>(ctx, p, m_off, st); break;
     }
   } else {

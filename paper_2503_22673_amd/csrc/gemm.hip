@@ -337,14 +337,36 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
 #pragma unroll
     for (int i = 0; i < LB; i++) rowB[i] = min(col0 + (lw * LB + i) * 8 + lrow, nclamp);
   }
+  // EARLY: per-lane row pointers of the first K segment are kept in registers (no 64-bit multiplies per step)
+  const bf16_t* pA[EARLY ? LA : 1]; const bf16_t* pB[EARLY ? LB : 1];
+  if constexpr (EARLY) {
+#pragma unroll
+    for (int i = 0; i < LA; i++) pA[i] = (const bf16_t*)p.seg[0].A + (int64_t)rowA[i] * p.seg[0].lda + (((lane & 7) ^ swz<SWZ>((lw * LA + i) * 8 + lrow)) * 8);
+#pragma unroll
+    for (int i = 0; i < LB; i++) pB[i] = (const bf16_t*)p.seg[0].B + (int64_t)rowB[i] * p.seg[0].ldb + (((lane & 7) ^ swz<SWZ>((lw * LB + i) * 8 + lrow)) * 8);
+  }
   auto fetch = [&](int it, int buf) {
     const bool first = it < nt0;
+    bf16_t* a = sA + buf * BM * BK + lw * LA * 8 * BK;
+    bf16_t* b = sB + buf * BN * BK + lw * LB * 8 * BK;
+    if constexpr (EARLY) {
+      if (first) {
+        const int k1 = (kr0.beg + it) * BK;
+#pragma unroll
+        for (int i = 0; i < LA; i++)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pA[i] + k1),
+                                           (__attribute__((address_space(3))) void*)(a + i * 8 * BK), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < LB; i++)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pB[i] + k1),
+                                           (__attribute__((address_space(3))) void*)(b + i * 8 * BK), 16, 0, 0);
+        return;
+      }
+    }
     const bf16_t* A = (const bf16_t*)(first ? p.seg[0].A : p.seg[1].A);
     const bf16_t* B = (const bf16_t*)(first ? p.seg[0].B : p.seg[1].B);
     const int64_t lda = first ? p.seg[0].lda : p.seg[1].lda, ldb = first ? p.seg[0].ldb : p.seg[1].ldb;
     const int k = (first ? kr0.beg + it : kr1.beg + it - nt0) * BK;
-    bf16_t* a = sA + buf * BM * BK + lw * LA * 8 * BK;
-    bf16_t* b = sB + buf * BN * BK + lw * LB * 8 * BK;
 #pragma unroll
     for (int i = 0; i < LA; i++)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(A + (int64_t)rowA[i] * lda + k + (((lane & 7) ^ swz<SWZ>((lw * LA + i) * 8 + lrow)) * 8)),
@@ -579,22 +601,38 @@ __global__ __launch_bounds__(WM * WN * 64, WM * WN == 4 ? 2 : 1) void gemm_mfma_
 #pragma unroll
   for (int i = 0; i < LB; i++) rowB[i] = min(col0 + (wave * LB + i) * 16 + lrow, p.N - 1);
   const int gch = ((lane & 3) ^ ((lrow >> 2) & 3)) * 8;  // (tile row >> 2) & 3 == (lrow >> 2) & 3: loads start at multiples of 16 rows
+  // per-lane row pointers of the first K segment are kept (the second, short one recomputes them)
+  const bf16_t* pA[LA]; const bf16_t* pB[LB];
+#pragma unroll
+  for (int i = 0; i < LA; i++) pA[i] = (const bf16_t*)p.seg[0].A + (int64_t)rowA[i] * p.seg[0].lda + gch;
+#pragma unroll
+  for (int i = 0; i < LB; i++) pB[i] = (const bf16_t*)p.seg[0].B + (int64_t)rowB[i] * p.seg[0].ldb + gch;
   auto fetch = [&](int it, int st) {
     const bool first = it < nt0;
-    const bf16_t* A = (const bf16_t*)(first ? p.seg[0].A : p.seg[1].A);
-    const bf16_t* B = (const bf16_t*)(first ? p.seg[0].B : p.seg[1].B);
-    const int64_t lda = first ? p.seg[0].lda : p.seg[1].lda, ldb = first ? p.seg[0].ldb : p.seg[1].ldb;
-    const int k = (first ? kr0.beg + it : kr1.beg + it - nt0) * BK;
     bf16_t* a = sm + st * ST_E + wave * LA * 16 * BK;
     bf16_t* b = sm + st * ST_E + BM * BK + wave * LB * 16 * BK;
+    if (first) {
+      const int k = (kr0.beg + it) * BK;
 #pragma unroll
-    for (int i = 0; i < LA; i++)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(A + (int64_t)rowA[i] * lda + k + gch),
-                                       (__attribute__((address_space(3))) void*)(a + i * 16 * BK), 16, 0, 0);
+      for (int i = 0; i < LA; i++)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pA[i] + k),
+                                         (__attribute__((address_space(3))) void*)(a + i * 16 * BK), 16, 0, 0);
 #pragma unroll
-    for (int i = 0; i < LB; i++)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(B + (int64_t)rowB[i] * ldb + k + gch),
-                                       (__attribute__((address_space(3))) void*)(b + i * 16 * BK), 16, 0, 0);
+      for (int i = 0; i < LB; i++)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pB[i] + k),
+                                         (__attribute__((address_space(3))) void*)(b + i * 16 * BK), 16, 0, 0);
+    } else {
+      const bf16_t* A = (const bf16_t*)p.seg[1].A; const bf16_t* B = (const bf16_t*)p.seg[1].B;
+      const int k = (kr1.beg + it - nt0) * BK;
+#pragma unroll
+      for (int i = 0; i < LA; i++)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(A + (int64_t)rowA[i] * p.seg[1].lda + k + gch),
+                                         (__attribute__((address_space(3))) void*)(a + i * 16 * BK), 16, 0, 0);
+#pragma unroll
+      for (int i = 0; i < LB; i++)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(B + (int64_t)rowB[i] * p.seg[1].ldb + k + gch),
+                                         (__attribute__((address_space(3))) void*)(b + i * 16 * BK), 16, 0, 0);
+    }
   };
 
   // reader: row = base + l%32, logical chunk 2*ks + l/32

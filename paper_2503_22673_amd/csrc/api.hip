@@ -608,7 +608,7 @@ struct Step {
       if ((rc = transpose(d, F, off(w.wdown, (size_t)e * d * F), F, P.wT, d))) return rc;                 // [F, d]
       if ((rc = gemm_expert(a.eoff, e, F, P.xbp, d, P.wT, d, d, P.dm, F))) return rc;
     }
-    if ((rc = launch_swiglu_bwd(ctx, mode, 2 * N, F, P.dm, a.gu, P.dgu, st))) return rc;
+    if ((rc = launch_swiglu_bwd(ctx, mode, 2 * N, F, P.dm, a.gu, P.dgu, nullptr, st))) return rc;
     for (int e = 0; e < E; e++) {
       if ((rc = transpose(F, d, off(w.wgate, (size_t)e * F * d), d, P.wT, 2 * F))) return rc;             // [d, 2F]
       if ((rc = transpose(F, d, off(w.wup, (size_t)e * F * d), d, off(P.wT, (size_t)F), 2 * F))) return rc;
@@ -632,13 +632,13 @@ struct Step {
     return AS_OK;
   }
 
-  // the activations that are cheaper to rebuild than to keep: both norm outputs and the SwiGLU product
+  // the activations that are cheaper to rebuild than to keep: both norm outputs here; the SwiGLU product
+  // is rewritten by the layer's SwiGLU backward kernel, which reads gate | up anyway
   int rebuild_cheap(int l, Acts& a) {
     const as_layer_weights& w = W->layers[l];
     int rc;
     if ((rc = launch_rmsnorm_fwd(ctx, mode, P.N, P.d, P.h[l], nullptr, nullptr, w.g1, c.rms_eps, a.a, a.rstd1, st))) return rc;
-    if ((rc = launch_rmsnorm_fwd(ctx, mode, P.N, P.d, a.h_mid, nullptr, nullptr, w.g2, c.rms_eps, a.b, a.rstd2, st))) return rc;
-    return launch_swiglu_fwd(ctx, mode, c.n_experts ? 2 * P.N : P.N, P.F, a.gu, a.m, st);
+    return launch_rmsnorm_fwd(ctx, mode, P.N, P.d, a.h_mid, nullptr, nullptr, w.g2, c.rms_eps, a.b, a.rstd2, st);
   }
 
   // nothing to compute: loss, count and every gradient are exactly zero
@@ -715,6 +715,9 @@ struct Step {
       if ((rc = transpose(d, F, w.wdown, F, P.wT, d))) return rc;                       // [F, d]
       if (s.on && (rc = gemm(N, rp, P.dh, d, s.Bst, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.du_d, rp))) return rc;
       if ((rc = gemm(N, F, P.dh, d, P.wT, d, d, s.on ? P.du_d : nullptr, rp, s.At, rp, s.on ? rp : 0, nullptr, 0, P.dm, F))) return rc;
+      // ---- SwiGLU (in recompute mode 2 it also rewrites the forward product, which the gradients below need)
+      const bool rewrite_m = c.recompute == 2 && l != c.n_layers - 1 && (full || s.on);
+      if ((rc = launch_swiglu_bwd(ctx, mode, N, F, P.dm, a.gu, P.dgu, rewrite_m ? a.m : nullptr, st))) return rc;
       if (full || (s.on && !tn_path())) {
         if ((rc = transpose_tok(d, P.dh, d, P.dyT))) return rc;
         if ((rc = transpose_tok(F, a.m, F, P.xT))) return rc;
@@ -725,8 +728,6 @@ struct Step {
         if ((rc = lora_grads(l, AS_T_DOWN, P.dh, d, a.m, F, P.dyT, P.xT))) return rc;
       }
       if (full && (rc = weight_grad(G->w_layers[l].wdown, d, F, P.dyT, P.xT))) return rc; }
-    // ---- SwiGLU
-    if ((rc = launch_swiglu_bwd(ctx, mode, N, F, P.dm, a.gu, P.dgu, st))) return rc;
     // ---- gate / up projections
     { const int ldg = P.n_gu * rp;
       const void* wg[2] = {w.wgate, w.wup};
@@ -782,14 +783,16 @@ struct Step {
     // ---- q / k / v projections
     { const int ldu = P.n_qkv * rp;
       const void* wq[3] = {w.wq, w.wk, w.wv}; const int nout[3] = {D, Dkv, Dkv}; const int coff[3] = {0, D, D + Dkv};
+      // with frozen embeddings nothing below the first layer's first norm takes a gradient
+      const bool need_da = full || l > 0;
       for (int i = 0; i < 3; i++) {
         LoraSlot& s = slot(l, i);
-        if ((rc = transpose(nout[i], d, wq[i], d, off(P.wT, coff[i]), QKV))) return rc;          // [d, QKV]
+        if (need_da && (rc = transpose(nout[i], d, wq[i], d, off(P.wT, coff[i]), QKV))) return rc;          // [d, QKV]
         if (s.on && (rc = gemm(N, rp, off(P.dqkv, coff[i]), QKV, s.Bst, nout[i], nout[i], nullptr, 0, nullptr, 0, 0, nullptr, 0,
                                off(P.du_qkv, (size_t)s.slot * rp), ldu))) return rc;
       }
-      if ((rc = gemm(N, d, P.dqkv, QKV, P.wT, QKV, QKV, P.n_qkv ? P.du_qkv : nullptr, ldu, P.At_qkv[l], ldu, ldu,
-                     nullptr, 0, P.da, d))) return rc;
+      if (need_da && (rc = gemm(N, d, P.dqkv, QKV, P.wT, QKV, QKV, P.n_qkv ? P.du_qkv : nullptr, ldu, P.At_qkv[l], ldu, ldu,
+                                nullptr, 0, P.da, d))) return rc;
       if (full || (P.n_qkv && !tn_path())) {
         if ((rc = transpose_tok(QKV, P.dqkv, QKV, P.dyT))) return rc;
         if ((rc = transpose_tok(d, a.a, d, P.xT))) return rc;
@@ -805,6 +808,7 @@ struct Step {
         for (int i = 0; i < 3; i++) if ((rc = weight_grad(gw[i], nout[i], d, off(P.dyT, (size_t)coff[i] * P.Np), P.xT))) return rc;
       } }
     // ---- first norm
+    if (!full && l == 0) return AS_OK;
     if (full && (rc = launch_rmsnorm_dgain(ctx, mode, N, d, P.da, nullptr, P.h[l], a.rstd1, P.gpart, 256, G->w_layers[l].g1, st))) return rc;
     return launch_rmsnorm_bwd(ctx, mode, N, d, P.da, nullptr, P.h[l], w.g1, a.rstd1, P.dh2, P.dh, st);
   }

@@ -143,7 +143,7 @@ int launch_moe_combine(as_ctx* ctx, int mode, const void* res, const void* y, co
 int launch_moe_dlogit(as_ctx* ctx, int mode, const void* dy, const void* y, const int32_t* pos, const int32_t* sel, const float* w,
                       int n, int d, int Epad, void* dlogit, hipStream_t st);
 int launch_swiglu_fwd(as_ctx* ctx, int mode, int64_t n, int F, const void* gu, void* m, hipStream_t st);
-int launch_swiglu_bwd(as_ctx* ctx, int mode, int64_t n, int F, const void* dm, const void* gu, void* dgu, hipStream_t st);
+int launch_swiglu_bwd(as_ctx* ctx, int mode, int64_t n, int F, const void* dm, const void* gu, void* dgu, void* m_out, hipStream_t st);
 // out[c, r] = in[r, c] for r < rows_pad, reading zero for r >= rows (and, with rows_dev, for rows at
 // or past *rows_dev - row_off)
 int launch_transpose(as_ctx* ctx, int mode, int rows, int rows_pad, int cols, const void* in, int64_t ldi, void* out,

@@ -357,7 +357,7 @@ __global__ void swiglu_fwd_kernel(int64_t n, int F, const T* __restrict__ gu, T*
 
 template <typename T>
 __global__ void swiglu_bwd_kernel(int64_t n, int F, const T* __restrict__ dm, const T* __restrict__ gu,
-                                  T* __restrict__ dgu, int vec) {
+                                  T* __restrict__ dgu, T* __restrict__ m_out, int vec) {
   constexpr int VN = Vec<T>::N;
   int64_t per_row = vec ? F / VN : F;
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -375,11 +375,18 @@ __global__ void swiglu_bwd_kernel(int64_t n, int F, const T* __restrict__ dm, co
       ou[i] = c[i] * a[i] * sg;
     }
     store_vec<T>(dr + j, og); store_vec<T>(dr + F + j, ou);
+    if (m_out) {                                       // the forward product again, in the forward kernel's arithmetic
+      float o[VN];
+#pragma unroll
+      for (int i = 0; i < VN; i++) o[i] = a[i] / (1.f + __expf(-a[i])) * b[i];
+      store_vec<T>(m_out + t * F + j, o);
+    }
   } else {
     float a = to_f<T>(gr[j]), b = to_f<T>(gr[F + j]), c = to_f<T>(dm[t * F + j]);
     float sg = 1.f / (1.f + __expf(-a));
     dr[j] = from_f<T>(c * b * sg * (1.f + a * (1.f - sg)));
     dr[F + j] = from_f<T>(c * a * sg);
+    if (m_out) m_out[t * F + j] = from_f<T>(a / (1.f + __expf(-a)) * b);
   }
 }
 
@@ -393,12 +400,13 @@ int launch_swiglu_fwd(as_ctx* ctx, int mode, int64_t n, int F, const void* gu, v
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
-int launch_swiglu_bwd(as_ctx* ctx, int mode, int64_t n, int F, const void* dm, const void* gu, void* dgu, hipStream_t st) {
+// m_out (may be NULL): also writes silu(gate) * up, bit for bit what launch_swiglu_fwd writes
+int launch_swiglu_bwd(as_ctx* ctx, int mode, int64_t n, int F, const void* dm, const void* gu, void* dgu, void* m_out, hipStream_t st) {
   if (n <= 0) return AS_OK;
   prof_begin(ctx, st, AS_K_SWIGLU, 0.0);
-  DISPATCH_T(mode, { int vec = vec_ok<T>(gu, F) && vec_ok<T>(dm, F) && vec_ok<T>(dgu, F);
+  DISPATCH_T(mode, { int vec = vec_ok<T>(gu, F) && vec_ok<T>(dm, F) && vec_ok<T>(dgu, F) && (!m_out || vec_ok<T>(m_out, F));
                      int64_t tot = n * (vec ? F / Vec<T>::N : F);
-                     swiglu_bwd_kernel<T><<<cdiv(tot, 256), 256, 0, st>>>(n, F, (const T*)dm, (const T*)gu, (T*)dgu, vec); });
+                     swiglu_bwd_kernel<T><<<cdiv(tot, 256), 256, 0, st>>>(n, F, (const T*)dm, (const T*)gu, (T*)dgu, (T*)m_out, vec); });
   prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;

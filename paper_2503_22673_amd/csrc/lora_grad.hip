@@ -8,8 +8,7 @@
 // 16 lanes and token) and transposes it in registers (v_perm), which yields the A operands of eight
 // v_mfma_f32_16x16x32_bf16 -- one per column of the block; MFMA row m then stands for column
 // c0 + 8 m + q of X.  U comes from its small token-major copy ([j][token]), one 16-byte load per
-// lane and 16-column block.  Waves of a workgroup take interleaved 32-token steps and are summed
-// through LDS in a fixed order; token splits go to a partial buffer reduced in split order.
+// lane and 16-column block.  Token ranges (splits) go to a partial buffer reduced in split order.
 #include "common.h"
 
 namespace {
@@ -25,9 +24,12 @@ struct TnParams {
 
 template <int NB>
 __global__ __launch_bounds__(256) void lora_grad_tn_kernel(TnParams p) {
-  extern __shared__ __align__(16) float red[];               // 2 slots x (8*NB*64*4) floats
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lm = lane & 15, lg = lane >> 4;
-  const int slab = blockIdx.x, split = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, lm = lane & 15, lg = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // the four waves of a workgroup take four neighbouring 128-column slabs and the same tokens, so that
+  // the workgroup reads 1 KB of every token row at a time
+  const int slab = blockIdx.x * 4 + wave, split = blockIdx.y;
+  if (slab * 128 >= p.M) return;
   const int col = slab * 128 + 8 * lm;
   const bool col_ok = col < p.M;
   f32x4 acc[8][NB];
@@ -36,9 +38,8 @@ __global__ __launch_bounds__(256) void lora_grad_tn_kernel(TnParams p) {
 #pragma unroll
     for (int nb = 0; nb < NB; nb++) acc[q][nb] = (f32x4){0.f, 0.f, 0.f, 0.f};
   const int s_end = min((split + 1) * p.steps_per_split, p.total_steps);
-  for (int step = split * p.steps_per_split + wave; step < s_end; step += 4) {
+  auto load = [&](int step, u32x4 (&x)[8], bf16x8 (&b)[NB]) {
     const int t0 = step * 32 + 8 * lg;
-    u32x4 x[8];
 #pragma unroll
     for (int r = 0; r < 8; r++) {
       const int t = t0 + r;
@@ -46,9 +47,10 @@ __global__ __launch_bounds__(256) void lora_grad_tn_kernel(TnParams p) {
       const u32x4 v = *reinterpret_cast<const u32x4*>(p.X + (int64_t)(ok ? t : 0) * p.ldx + (ok ? col : 0));
       x[r] = ok ? v : (u32x4){0u, 0u, 0u, 0u};
     }
-    bf16x8 b[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; nb++) b[nb] = *reinterpret_cast<const bf16x8*>(p.UT + (int64_t)(nb * 16 + lm) * p.ldu + t0);
+  };
+  auto compute = [&](const u32x4 (&x)[8], const bf16x8 (&b)[NB]) {
 #pragma unroll
     for (int q = 0; q < 8; q++) {
       // column q of the 8x8 block: dword d of the operand = (x[2d][q], x[2d+1][q])
@@ -60,44 +62,32 @@ __global__ __launch_bounds__(256) void lora_grad_tn_kernel(TnParams p) {
 #pragma unroll
       for (int nb = 0; nb < NB; nb++) acc[q][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b[nb], acc[q][nb], 0, 0, 0);
     }
+  };
+  // two register sets: the block of the next step is in flight while this one is multiplied
+  u32x4 xa[8], xb[8];
+  bf16x8 ba[NB], bb[NB];
+  int step = split * p.steps_per_split;
+  if (step < s_end) load(step, xa, ba);
+  for (; step < s_end; step += 2) {
+    if (step + 1 < s_end) load(step + 1, xb, bb);
+    compute(xa, ba);
+    if (step + 1 >= s_end) break;
+    if (step + 2 < s_end) load(step + 2, xa, ba);
+    compute(xb, bb);
   }
-  // waves 2,3 -> slots; waves 0,1 add; wave 1 -> slot 0; wave 0 adds: (w0 + w2) + (w1 + w3)
-  constexpr int PER_WAVE = 8 * NB * 64;                       // f32x4 elements per wave
-  f32x4* slot = reinterpret_cast<f32x4*>(red);
-  auto put = [&](int s) {
+  // accumulator row 4*lg + i of MFMA q is column c0 + 8*(4*lg + i) + q; its column is j = nb*16 + lm
+  float* out = p.partial + (int64_t)split * p.M * p.r;
 #pragma unroll
-    for (int q = 0; q < 8; q++)
+  for (int q = 0; q < 8; q++)
 #pragma unroll
-      for (int nb = 0; nb < NB; nb++) slot[s * PER_WAVE + (q * NB + nb) * 64 + lane] = acc[q][nb];
-  };
-  auto add = [&](int s) {
+    for (int nb = 0; nb < NB; nb++) {
+      const int j = nb * 16 + lm;
 #pragma unroll
-    for (int q = 0; q < 8; q++)
-#pragma unroll
-      for (int nb = 0; nb < NB; nb++) acc[q][nb] += slot[s * PER_WAVE + (q * NB + nb) * 64 + lane];
-  };
-  if (wave >= 2) put(wave - 2);
-  __syncthreads();
-  if (wave < 2) add(wave);
-  __syncthreads();
-  if (wave == 1) put(0);
-  __syncthreads();
-  if (wave == 0) {
-    add(0);
-    // accumulator row 4*lg + i of MFMA q is column c0 + 8*(4*lg + i) + q; its column is j = nb*16 + lm
-    float* out = p.partial + (int64_t)split * p.M * p.r;
-#pragma unroll
-    for (int q = 0; q < 8; q++)
-#pragma unroll
-      for (int nb = 0; nb < NB; nb++) {
-        const int j = nb * 16 + lm;
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-          const int m = slab * 128 + 8 * (4 * lg + i) + q;
-          if (m < p.M && j < p.r) out[(int64_t)m * p.r + j] = acc[q][nb][i];
-        }
+      for (int i = 0; i < 4; i++) {
+        const int m = slab * 128 + 8 * (4 * lg + i) + q;
+        if (m < p.M && j < p.r) out[(int64_t)m * p.r + j] = acc[q][nb][i];
       }
-  }
+    }
 }
 
 __global__ void tn_reduce_kernel(const float* __restrict__ partial, int splits, int M, int r, float alpha,
@@ -127,11 +117,9 @@ int launch_lora_grad_tn(as_ctx* ctx, const void* X, int64_t ldx, const void* UT,
   if ((size_t)splits * M * r > partial_floats) return as_fail(ctx, AS_ERR_WORKSPACE, "lora_grad_tn: partial buffer too small");
   TnParams p{(const bf16_t*)X, ldx, (const bf16_t*)UT, ldu, n, M, r, partial, (int)cdiv(steps, splits), steps};
   const int nb = (int)cdiv(r, 16);
-  dim3 grid(slabs, splits);
+  dim3 grid((unsigned)cdiv(slabs, 4), splits);
   prof_begin(ctx, st, AS_K_LORA_GRAD, 2.0 * n * (double)M * r);
-#define TN_LAUNCH(NB) { size_t smem = (size_t)2 * 8 * NB * 64 * 16; \
-    static bool attr = false; if (!attr) { AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(lora_grad_tn_kernel<NB>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem)); attr = true; } \
-    lora_grad_tn_kernel<NB><<<grid, 256, smem, st>>>(p); }
+#define TN_LAUNCH(NB) { lora_grad_tn_kernel<NB><<<grid, 256, 0, st>>>(p); }
   switch (nb) { case 1: TN_LAUNCH(1) break; case 2: TN_LAUNCH(2) break; case 3: TN_LAUNCH(3) break; default: TN_LAUNCH(4) break; }
 #undef TN_LAUNCH
   AS_LAUNCH_CHECK(ctx);

@@ -145,13 +145,47 @@ __global__ void rope_kernel(int n, int n_heads, int dh, T* __restrict__ x, int64
   row[i + half] = from_f<T>(x1 * s + x2 * c);
 }
 
+// Same rotation, one thread per (token, head, Vec<T>::N adjacent i): 16-byte loads and stores.
+template <typename T>
+__global__ void rope_vec_kernel(int n, int n_heads, int dh, T* __restrict__ x, int64_t ldx,
+                                const int32_t* __restrict__ seg_start, const float* __restrict__ cosb,
+                                const float* __restrict__ sinb, float sign) {
+  constexpr int VN = Vec<T>::N;
+  const int half = dh >> 1, per = half / VN;
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)n * n_heads * per) return;
+  const int i = (int)(idx % per) * VN;
+  const int64_t r = idx / per;
+  const int hd = (int)(r % n_heads), t = (int)(r / n_heads);
+  const int p = t - seg_start[t];
+  T* row = x + (int64_t)t * ldx + (int64_t)hd * dh;
+  float x1[VN], x2[VN], o1[VN], o2[VN];
+  load_vec<T>(row + i, x1); load_vec<T>(row + i + half, x2);
+#pragma unroll
+  for (int k = 0; k < VN; k += 4) {
+    const f32x4 c = *reinterpret_cast<const f32x4*>(cosb + (int64_t)p * half + i + k);
+    const f32x4 s = *reinterpret_cast<const f32x4*>(sinb + (int64_t)p * half + i + k);
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const float sq = sign * s[q];
+      o1[k + q] = x1[k + q] * c[q] - x2[k + q] * sq;
+      o2[k + q] = x1[k + q] * sq + x2[k + q] * c[q];
+    }
+  }
+  store_vec<T>(row + i, o1); store_vec<T>(row + i + half, o2);
+}
+
 int launch_rope(as_ctx* ctx, int mode, int n, int n_heads, int dh, void* x, int64_t ldx,
                 const int32_t* seg_start, const float* cosb, const float* sinb, int inverse, hipStream_t st) {
   int64_t tot = (int64_t)n * n_heads * (dh / 2);
   if (tot <= 0) return AS_OK;
   prof_begin(ctx, st, AS_K_ROPE, 0.0);
-  DISPATCH_T(mode, (rope_kernel<T><<<cdiv(tot, 256), 256, 0, st>>>(n, n_heads, dh, (T*)x, ldx, seg_start,
-                                                                    cosb, sinb, inverse ? -1.f : 1.f)));
+  DISPATCH_T(mode, {
+    constexpr int VN = Vec<T>::N;
+    if ((dh / 2) % VN == 0 && vec_ok<T>(x, ldx) && ((uintptr_t)cosb % 16) == 0 && ((uintptr_t)sinb % 16) == 0)
+      rope_vec_kernel<T><<<cdiv(tot / VN, 256), 256, 0, st>>>(n, n_heads, dh, (T*)x, ldx, seg_start, cosb, sinb, inverse ? -1.f : 1.f);
+    else
+      rope_kernel<T><<<cdiv(tot, 256), 256, 0, st>>>(n, n_heads, dh, (T*)x, ldx, seg_start, cosb, sinb, inverse ? -1.f : 1.f); });
   prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;

@@ -471,11 +471,53 @@ __global__ void transpose_kernel(int rows, int rows_pad, int cols, const T* __re
   }
 }
 
+// bf16, 16-byte accesses on both sides: a 64x64 tile is read as 8-element row chunks and written as
+// 8-element chunks of the output rows (gathered from an LDS tile column).  Needs cols, ldi, ldo, rows_pad
+// multiples of 8 (rows_pad of 64 in fact: whole output chunks) and 16-byte aligned bases.
+template <bool QS>
+__global__ void transpose_vec_kernel(int rows, int rows_pad, int cols, const bf16_t* __restrict__ in, int64_t ldi,
+                                     bf16_t* __restrict__ out, int64_t ldo, const int* __restrict__ rows_dev, int row_off) {
+  __shared__ bf16_t tile[64][72];                          // [source row][source col], padded
+  const int live = rows_dev ? min(rows, *rows_dev - row_off) : rows;
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  for (int k = threadIdx.x; k < 512; k += 256) {           // 64 rows x 8 chunks
+    const int i = k >> 3, cc = (k & 7) * 8;
+    const int r = r0 + i, c = c0 + cc;
+    bf16x8 v;
+#pragma unroll
+    for (int e = 0; e < 8; e++) v[e] = (bf16_t)0.f;
+    if (r < live && c < cols) v = *reinterpret_cast<const bf16x8*>(in + (int64_t)r * ldi + c);   // cols % 8 == 0: whole chunks
+    *reinterpret_cast<bf16x8*>(&tile[i][cc]) = v;
+  }
+  __syncthreads();
+  for (int k = threadIdx.x; k < 512; k += 256) {           // 64 output rows (source cols) x 8 chunks of 8 source rows
+    const int oc = k & 63, ch = k >> 6;                    // consecutive threads: consecutive output rows, same chunk
+    const int c = c0 + oc, rr = r0 + ch * 8;
+    if (c >= cols || rr >= rows_pad) continue;
+    bf16x8 v;
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      const int pos = ch * 8 + e;                          // output position inside the tile
+      const int src = QS ? ((pos & ~12) | ((pos & 4) << 1) | ((pos & 8) >> 1)) : pos;
+      v[e] = tile[src][oc];
+    }
+    *reinterpret_cast<bf16x8*>(out + (int64_t)c * ldo + rr) = v;
+  }
+}
+
+static bool transpose_vec_ok(int mode, int rows_pad, int cols, const void* in, int64_t ldi, const void* out, int64_t ldo) {
+  return mode == AS_BF16 && rows_pad % 64 == 0 && cols % 8 == 0 && ldi % 8 == 0 && ldo % 8 == 0 &&
+         (uintptr_t)in % 16 == 0 && (uintptr_t)out % 16 == 0;
+}
+
 int launch_transpose(as_ctx* ctx, int mode, int rows, int rows_pad, int cols, const void* in, int64_t ldi, void* out,
                      int64_t ldo, const int* rows_dev, int row_off, hipStream_t st) {
   if (rows <= 0 || cols <= 0) return AS_OK;
   dim3 grid(cdiv(cols, 64), cdiv(rows_pad, 64));
   prof_begin(ctx, st, AS_K_TRANSPOSE, 0.0);
+  if (transpose_vec_ok(mode, rows_pad, cols, in, ldi, out, ldo))
+    transpose_vec_kernel<false><<<grid, 256, 0, st>>>(rows, rows_pad, cols, (const bf16_t*)in, ldi, (bf16_t*)out, ldo, rows_dev, row_off);
+  else
   DISPATCH_T(mode, (transpose_kernel<T, false><<<grid, 256, 0, st>>>(rows, rows_pad, cols, (const T*)in, ldi, (T*)out, ldo, rows_dev, row_off)));
   prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
@@ -489,6 +531,9 @@ int launch_transpose_qs(as_ctx* ctx, int mode, int rows, int rows_pad, int cols,
   if (rows_pad % 16) return as_fail(ctx, AS_ERR_SHAPE, "transpose: the quad-swapped layout needs a row count padded to 16");
   dim3 grid(cdiv(cols, 64), cdiv(rows_pad, 64));
   prof_begin(ctx, st, AS_K_TRANSPOSE, 0.0);
+  if (transpose_vec_ok(mode, rows_pad, cols, in, ldi, out, ldo))
+    transpose_vec_kernel<true><<<grid, 256, 0, st>>>(rows, rows_pad, cols, (const bf16_t*)in, ldi, (bf16_t*)out, ldo, nullptr, 0);
+  else
   DISPATCH_T(mode, (transpose_kernel<T, true><<<grid, 256, 0, st>>>(rows, rows_pad, cols, (const T*)in, ldi, (T*)out, ldo, nullptr, 0)));
   prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);

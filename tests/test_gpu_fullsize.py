@@ -1,0 +1,156 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The float64 reference cannot run 8B shapes on 65,536 tokens, so the kernels are checked on sampled
+outputs that can be computed one by one from their definitions (a GEMM entry is a dot product, an
+attention row is a softmax over its segment prefix), and the whole step on properties that hold at any
+size: two runs give the same bits, the target count is the mask's, and the packed batch equals the sum
+of its rows (loss sum, count, count-weighted adapter gradients)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from helpers import grad_norm_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _f64(t):
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def test_gemm_config3_shape_sampled_entries():
+    """gate / up projection of config 3 after segment skipping: M = 58,971 (ragged against the 256 tile),
+    N = 14,336, K = 4,096 plus the 64-wide adapter segment."""
+    from paper_2503_22673_amd import binding as B
+    ctx = B.Context(B.make_config(synth.CONFIGS[3]))
+    M, N, K, K2 = 58971, 14336, 4096, 64
+    g = torch.Generator(device="cuda"); g.manual_seed(11)
+    rnd = lambda *s: torch.empty(s, dtype=torch.bfloat16, device="cuda").normal_(0, 1.0, generator=g)
+    A1, B1, A2, B2 = rnd(M, K), rnd(N, K), rnd(M, K2), rnd(N, K2)
+    out = ctx.op_gemm(A1, B1, A2, B2, alpha=1.0, out_f32=True, variant=0, mode=B.AS_BF16)
+    torch.cuda.synchronize()
+    rs = np.random.default_rng(0)
+    rows = np.concatenate([rs.integers(0, M, 60), [0, 255, 256, M - 1, M - 2, 58880]])      # 58880 = first row of the ragged last tile
+    cols = np.concatenate([rs.integers(0, N, 60), [0, 255, 256, N - 1, 14080, 7]])
+    a1, a2 = _f64(A1[torch.from_numpy(rows).cuda()]), _f64(A2[torch.from_numpy(rows).cuda()])
+    b1, b2 = _f64(B1[torch.from_numpy(cols).cuda()]), _f64(B2[torch.from_numpy(cols).cuda()])
+    ref = np.einsum("ik,ik->i", a1, b1) + np.einsum("ik,ik->i", a2, b2)
+    got = out[torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()].double().cpu().numpy()
+    # exact products, float accumulation: only summation rounding remains
+    assert np.abs(got - ref).max() <= (2e-6 * np.sqrt(K + K2) + 1e-6) * np.abs(ref).max()
+
+
+def _attn_row(q, k, v, s0, t, scale):
+    """float64 attention row of query t over keys s0..t: probabilities, output, lse."""
+    sc = (k[s0:t + 1] @ q[t]) * scale
+    m = sc.max()
+    e = np.exp(sc - m)
+    return e / e.sum(), (e / e.sum()) @ v[s0:t + 1], m + np.log(e.sum())
+
+
+def test_attention_config3_layout_sampled_rows():
+    """Forward and backward MFMA attention on the packed layout of config 3 (4 x 16384 tokens, the real
+    segment table with its pad tails), 32 query / 8 KV heads of 128; sampled rows against the definition."""
+    from paper_2503_22673_amd import binding as B
+    sh = synth.CONFIGS[3]
+    ctx = B.Context(B.make_config(sh))
+    pk = oracle.pack(synth.workload(3, 0), sh.row_len, sh.rows)
+    cu = pk["cu_seqlens"].astype(np.int64); n = int(cu[-1])
+    assert n == sh.rows * sh.row_len
+    seg = np.searchsorted(cu, np.arange(n), side="right") - 1
+    ss = torch.from_numpy(cu[seg].astype(np.int32)).cuda(); se = torch.from_numpy(cu[seg + 1].astype(np.int32)).cuda()
+    Hq, Hkv, dh = sh.n_q_heads, sh.n_kv_heads, sh.head_dim
+    D, Dkv, grp, scale = Hq * dh, Hkv * dh, Hq // Hkv, 1.0 / np.sqrt(dh)
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    qkv = torch.empty(n, D + 2 * Dkv, dtype=torch.bfloat16, device="cuda").normal_(0, 1.0, generator=g)
+    do = torch.empty(n, D, dtype=torch.bfloat16, device="cuda").normal_(0, 1.0, generator=g)
+    o, lse = ctx.op_attention_fwd(qkv, ss, variant=0, mode=B.AS_BF16)
+    dqkv = ctx.op_attention_bwd(qkv, ss, se, o, lse, do, variant=0, mode=B.AS_BF16)
+    torch.cuda.synchronize()
+    lens = np.diff(cu); longest = int(np.argmax(lens)); short = int(np.argmin(np.where(lens > 70, lens, 1 << 30)))
+    s_long, e_long = int(cu[longest]), int(cu[longest + 1])
+    # queries: last and first token of the longest segment, tile boundaries inside it, a short segment, the last token
+    qs = [(e_long - 1, 0), (s_long, 5), (s_long + 63, 31), (s_long + 64, 17), (s_long + 4097, 9),
+          (int(cu[short + 1]) - 1, 12), (int(cu[short]) + 1, 3), (n - 1, 30)]
+    for t, h in qs:
+        s0, gk = int(cu[seg[t]]), h // grp
+        q = _f64(qkv[s0:t + 1, h * dh:(h + 1) * dh]); k = _f64(qkv[s0:t + 1, D + gk * dh:D + (gk + 1) * dh])
+        v = _f64(qkv[s0:t + 1, D + Dkv + gk * dh:D + Dkv + (gk + 1) * dh])
+        p, o_ref, lse_ref = _attn_row(q, k, v, 0, t - s0, scale)
+        assert grad_norm_err(_f64(o[t, h * dh:(h + 1) * dh]), o_ref) < 2e-2, (t, h)
+        assert abs(float(lse[t, h]) - lse_ref) < 2e-2, (t, h)
+        # dq row: dS = P * (dP - delta), dq = scale * dS K
+        dO = _f64(do[t, h * dh:(h + 1) * dh]); dP = v @ dO
+        dS = p * (dP - float(dO @ o_ref))
+        dq_ref = scale * (dS @ k)                           # exactly 0 for the first token of a segment (one key, dS = 0)
+        assert np.abs(_f64(dqkv[t, h * dh:(h + 1) * dh]) - dq_ref).max() <= 2e-2 * max(np.abs(dq_ref).max(), 1e-3), (t, h)
+    # keys: one 150 tokens before the end of the longest segment (150 queries x 4 heads see it), one in the short segment
+    for u, gk in [(e_long - 150, 2), (int(cu[short]) + 2, 6)]:
+        s0, e0 = int(cu[seg[u]]), int(cu[seg[u] + 1])
+        k = _f64(qkv[s0:e0, D + gk * dh:D + (gk + 1) * dh]); v = _f64(qkv[s0:e0, D + Dkv + gk * dh:D + Dkv + (gk + 1) * dh])
+        dk, dv = np.zeros(dh), np.zeros(dh)
+        for h in range(gk * grp, (gk + 1) * grp):
+            q = _f64(qkv[s0:e0, h * dh:(h + 1) * dh]); dO = _f64(do[s0:e0, h * dh:(h + 1) * dh])
+            for t in range(u - s0, e0 - s0):
+                p, o_ref, _ = _attn_row(q, k, v, 0, t, scale)
+                pu = p[u - s0]
+                dv += pu * dO[t]
+                dk += scale * pu * (float(v[u - s0] @ dO[t]) - float(dO[t] @ o_ref)) * q[t]
+        assert grad_norm_err(_f64(dqkv[u, D + gk * dh:D + (gk + 1) * dh]), dk) < 2e-2, u
+        assert grad_norm_err(_f64(dqkv[u, D + Dkv + gk * dh:D + Dkv + (gk + 1) * dh]), dv) < 2e-2, u
+
+
+def test_config3_full_step_properties():
+    """The benchmark's step itself (32 layers of 8B shapes, 4 x 16384 packed tokens, rank-64 adapters on the
+    seven projections, selective recompute, loss-free segments skipped)."""
+    import bench
+    from paper_2503_22673_amd import binding as B
+    torch.cuda.empty_cache()                   # this test needs 16 GB of weights and a 210 GB workspace
+    sh = synth.CONFIGS[3]
+    ctx = B.Context(B.make_config(sh))
+    trajs = synth.workload(3, seed=0)
+    pk = ctx.pack(*synth.flatten_trajectories(trajs), sh.row_len, sh.rows)
+    torch.cuda.synchronize()
+    hcu = pk["cu_seqlens"].cpu().numpy()
+    model = B.DeviceModel(ctx, bench.device_weights(sh, 0, torch.bfloat16), bench.device_lora(sh, 0))
+    ws = torch.empty(ctx.workspace_bytes(sh.rows, sh.row_len), dtype=torch.uint8, device="cuda")
+    probes = [(31, "q", 1), (0, "down", 0), (15, "gate", 1), (7, "v", 0)]            # (layer, target, A or B)
+
+    def run(tokens, cu_d, cu_h, mask, rows, skip):
+        out = ctx.train_step(model, tokens, cu_d, cu_h, mask, rows, sh.row_len, ws, seg_skip=skip)
+        torch.cuda.synchronize()
+        grads = [model.lora_grads[l][t][i].clone() for l, t, i in probes]
+        return float(out["loss"].item()), float(out["loss_sum"].item()), int(out["count"].item()), grads
+
+    a = run(pk["tokens"], pk["cu_seqlens"], hcu, pk["loss_mask"], sh.rows, pk["seg_skip"])
+    b = run(pk["tokens"], pk["cu_seqlens"], hcu, pk["loss_mask"], sh.rows, pk["seg_skip"])
+    assert a[:3] == b[:3] and all(torch.equal(x, y) for x, y in zip(a[3], b[3]))     # same bits
+    mask_h = pk["loss_mask"].cpu().numpy()
+    first = np.zeros(len(mask_h), dtype=bool); first[hcu[:-1]] = True
+    assert a[2] == int((mask_h.astype(bool) & ~first).sum()) and a[2] > 10000
+    assert np.isfinite(a[0]) and abs(a[0] - a[1] / a[2]) <= 1e-5 * abs(a[0])
+    # packed batch = sum of its rows
+    T = sh.row_len
+    tot, cnt, gsum = 0.0, 0, [torch.zeros_like(x, dtype=torch.float64) for x in a[3]]
+    for r in range(sh.rows):
+        segs = [s for s in range(len(hcu) - 1) if hcu[s] // T == r]
+        cu_r = (np.asarray([hcu[s] for s in segs] + [hcu[segs[-1] + 1]]) - r * T).astype(np.int32)
+        res = run(pk["tokens"][r * T:(r + 1) * T], torch.from_numpy(cu_r).cuda(), cu_r, pk["loss_mask"][r * T:(r + 1) * T], 1,
+                  pk["seg_skip"][segs[0]:segs[-1] + 1])
+        tot, cnt = tot + res[1], cnt + res[2]
+        for acc, x in zip(gsum, res[3]):
+            acc += res[2] * x.double()
+    assert cnt == a[2] and abs(tot - a[1]) <= 1e-4 * abs(a[1])
+    errs = {}
+    for (l, t, i), full, parts in zip(probes, a[3], gsum):
+        ref = parts / a[2]
+        errs[(l, t, i)] = ((full.double() - ref).abs().max().item() / ref.abs().max().item(),
+                           ((full.double() - ref).norm() / ref.norm()).item())
+    print("row-additivity errors (max-normalised, L2):", errs)
+    # The row runs scale every backward signal by 1/C_row instead of 1/C (not a power of two apart), so the two
+    # sides are independent bf16 rounding realisations of the same sums: each carries the tier's error (a few
+    # per cent on the q / k adapters, whose signal passes the softmax backward), and this is their difference.
+    # A wrong index, a dropped row or a mis-scaled term would show as an error of order one.
+    assert all(e[0] <= 0.15 and e[1] <= 0.15 for e in errs.values()), errs

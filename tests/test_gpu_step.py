@@ -44,6 +44,24 @@ def test_seven_targets_gqa_recompute_two_rows(bf16):
     assert rep["loss"] == rep2["loss"] == rep3["loss"] and rep["grads"] == rep2["grads"] == rep3["grads"]
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_long_segments_many_tiles(bf16):
+    """Segments of 2048, 1024 and 1017 tokens (32 key tiles, a ragged tail), four layers, all seven adapters:
+    the attention kernels' mask-free path, lazy maximum and longest-first order against the reference."""
+    import gpu_util as G
+    sh = synth.CONFIGS[1].replace(n_layers=4, n_q_heads=4, n_kv_heads=2, head_dim=64, d_model=256, ffn=512, vocab=1024,
+                                  lora_targets=synth.DENSE_TARGETS7, lora_rank=16, lora_alpha=32.0)
+    g = synth.rng(3, 9)
+
+    def traj(n):
+        lens = [n // 6] * 5 + [n - 5 * (n // 6)]
+        return [(r, g.integers(0, sh.vocab, size=l).astype(np.int32)) for r, l in zip(synth.role_pattern(6), lens)]
+
+    trajs = [traj(2048), traj(1024), traj(1017)]
+    rep = G.compare_step(sh, 1, trajs, 2, 2048, bf16=bf16, loss_tol=2e-3 if bf16 else 1e-4, grad_tol=3e-2 if bf16 else 1e-4)
+    print("long segments %s: loss rel %.2e worst grad %.2e" % ("bf16" if bf16 else "fp32", rep["loss_rel"], rep["worst_grad"]))
+
+
 def test_zero_mask_gives_exact_zero_loss_and_gradients():
     import gpu_util as G
     from paper_2503_22673_amd import binding as B

@@ -829,9 +829,11 @@ struct Step {
       if ((rc = gemm(rows, d, P.P, V, P.headT, V, V, nullptr, 0, nullptr, 0, 0, nullptr, 0, off(P.dhf, (size_t)r0 * d), d, 0, 1.f, 0, P.count, r0))) return rc;
       if (full) {
         // dW_head += P_c^T hf_c  (rows past the live count are read as zero)
-        if ((rc = launch_transpose(ctx, mode, rows, rows, V, P.P, V, P.Pt, Mc, P.count, r0, st))) return rc;
-        if ((rc = launch_transpose(ctx, mode, rows, rows, d, hf_c, d, P.hfT, Mc, P.count, r0, st))) return rc;
-        if ((rc = gemm(V, d, P.Pt, Mc, P.hfT, Mc, rows, nullptr, 0, nullptr, 0, 0, nullptr, 0, G->head, d, 1, 1.f, ch > 0))) return rc;
+        // the contraction length is padded to whole 64-token steps (zero rows past the chunk), so that the MFMA kernel takes it
+        const int rows64 = (int)cdiv(rows, 64) * 64;
+        if ((rc = launch_transpose(ctx, mode, rows, rows64, V, P.P, V, P.Pt, Mc, P.count, r0, st))) return rc;
+        if ((rc = launch_transpose(ctx, mode, rows, rows64, d, hf_c, d, P.hfT, Mc, P.count, r0, st))) return rc;
+        if ((rc = gemm(V, d, P.Pt, Mc, P.hfT, Mc, rows64, nullptr, 0, nullptr, 0, 0, nullptr, 0, G->head, d, 1, 1.f, ch > 0))) return rc;
       }
     }
     if ((rc = launch_loss_finalize(ctx, P.loss_rows, P.count, d_loss, d_loss_sum, st))) return rc;

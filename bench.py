@@ -147,6 +147,10 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the depth (bring-up only; the result is then not the headline)")
     ap.add_argument("--recompute", type=int, default=-1, help="override the recompute mode (0, 1, 2)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--rows", type=int, default=0, help="override the number of packed rows")
+    ap.add_argument("--row-len", type=int, default=0, help="override the row length")
+    ap.add_argument("--single-trajectory", action="store_true",
+                    help="long-context stress: every row is ONE trajectory of row_len tokens")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -164,9 +168,17 @@ def main():
         sh = sh.replace(n_layers=args.layers)
     if args.recompute >= 0:
         sh = sh.replace(recompute=args.recompute)
+    if args.rows:
+        sh = sh.replace(rows=args.rows)
+    if args.row_len:
+        sh = sh.replace(row_len=args.row_len)
     torch.cuda.set_device(0)
     ctx = B.Context(B.make_config(sh))
-    trajs = synth.workload(args.config, seed=args.seed)
+    if args.single_trajectory:
+        trajs = synth.trajectories_lognormal(args.seed, sh.rows, sh.row_len, sh.vocab, sh.row_len, 0.0, sh.row_len, sh.row_len,
+                                             turns=(8, 12), assistant_share=0.2)
+    else:
+        trajs = synth.workload(args.config, seed=args.seed, rows=sh.rows, row_len=sh.row_len)
     flat = synth.flatten_trajectories(trajs)
     t0 = time.perf_counter()
     pk = ctx.pack(*flat, sh.row_len, sh.rows)
@@ -242,8 +254,10 @@ def main():
         adam_ms = a0.elapsed_time(a1)
 
     rec = {
-        "metric": "trained tokens/s per MI355X (LoRA step, 8B shapes, 16k packed); % bf16 MFMA peak" if args.config == 3 else
-                  "trained tokens/s per MI355X (one fine-tuning step, config %d)" % args.config,
+        "metric": "trained tokens/s per MI355X (LoRA step, 8B shapes, 16k packed); % bf16 MFMA peak"
+                  if args.config == 3 and not (args.rows or args.row_len or args.single_trajectory or args.layers) else
+                  "trained tokens/s per MI355X (one fine-tuning step, config %d%s)" % (
+                      args.config, ", rows/row_len overridden" if (args.rows or args.row_len or args.single_trajectory) else ""),
         "value": round(tokens_per_s, 1), "unit": "trained tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 2), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if sh.bf16 else "f32", "data": "synthetic",
@@ -260,7 +274,8 @@ def main():
                                                   " (projection GEMMs forward + dX, LoRA term as second K segment)"),
                      "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None if sh.n_experts else TRAFFIC_BYTES_PER_LAUNCH.get((args.config, DOMINANT_KERNEL)),
+                     "traffic": None if (sh.n_experts or args.rows or args.row_len or args.single_trajectory) else
+                                TRAFFIC_BYTES_PER_LAUNCH.get((args.config, DOMINANT_KERNEL)),
                      "traffic_unit": "HBM-side bytes per launch (counters)",
                      "launches_per_step": n_l // max(args.steps, 1), "avg_launch_ms": round(ms_l / max(n_l, 1), 4)},
     }

@@ -149,6 +149,7 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--rows", type=int, default=0, help="override the number of packed rows")
     ap.add_argument("--row-len", type=int, default=0, help="override the row length")
+    ap.add_argument("--nf4", action="store_true", help="frozen base held as NF4 blocks (quantised base + LoRA)")
     ap.add_argument("--single-trajectory", action="store_true",
                     help="long-context stress: every row is ONE trajectory of row_len tokens")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -173,7 +174,7 @@ def main():
     if args.row_len:
         sh = sh.replace(row_len=args.row_len)
     torch.cuda.set_device(0)
-    ctx = B.Context(B.make_config(sh))
+    ctx = B.Context(B.make_config(sh, weight_format=B.AS_W_NF4 if args.nf4 else B.AS_W_DENSE))
     if args.single_trajectory:
         trajs = synth.trajectories_lognormal(args.seed, sh.rows, sh.row_len, sh.vocab, sh.row_len, 0.0, sh.row_len, sh.row_len,
                                              turns=(8, 12), assistant_share=0.2)
@@ -194,6 +195,13 @@ def main():
 
     dt = torch.bfloat16 if sh.bf16 else torch.float32
     params = device_weights(sh, args.seed, dt)
+    weight_bytes = sum(v.numel() * v.element_size() for W in params["layers"] for v in W.values())
+    if args.nf4:                                    # quantise the seven projections of every layer on the device
+        for W in params["layers"]:
+            for k in ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown"):
+                W[k], W["a" + k[1:]] = ctx.nf4_quantize(W[k])
+        torch.cuda.synchronize()
+        weight_bytes = sum(v.numel() * v.element_size() for W in params["layers"] for v in W.values())
     lora = None if sh.full_ft else device_lora(sh, args.seed)
     model = B.DeviceModel(ctx, params, lora)
     del params, lora
@@ -255,9 +263,10 @@ def main():
 
     rec = {
         "metric": "trained tokens/s per MI355X (LoRA step, 8B shapes, 16k packed); % bf16 MFMA peak"
-                  if args.config == 3 and not (args.rows or args.row_len or args.single_trajectory or args.layers) else
+                  if args.config == 3 and not (args.rows or args.row_len or args.single_trajectory or args.layers or args.nf4) else
                   "trained tokens/s per MI355X (one fine-tuning step, config %d%s)" % (
-                      args.config, ", rows/row_len overridden" if (args.rows or args.row_len or args.single_trajectory) else ""),
+                      args.config, ", rows/row_len overridden" if (args.rows or args.row_len or args.single_trajectory) else "") +
+                  (", NF4 base" if args.nf4 else ""),
         "value": round(tokens_per_s, 1), "unit": "trained tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 2), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if sh.bf16 else "f32", "data": "synthetic",
@@ -267,6 +276,7 @@ def main():
             "loss_tokens": count, "mean_sq_len_over_len": round(sum(x * x for x in seg_nonpad) / max(n_nonpad, 1), 1)},
         "mfu_pct_of_bf16_peak": round(100 * mfu, 2), "hfu_pct_of_bf16_peak": round(100 * hfu, 2),
         "algorithmic_gflop_per_token": round(fl["total"] / n_nonpad / 1e9, 2),
+        "layer_weight_gb": round(weight_bytes / 1e9, 2),
         "loss": round(loss, 5), "pack_ms": round(pack_ms, 2), "adamw_ms": None if adam_ms is None else round(adam_ms, 3),
         "wall_s_timed_region": round(wall, 3),
         "kernel_ms_per_step": breakdown,
@@ -274,7 +284,7 @@ def main():
                                                   " (projection GEMMs forward + dX, LoRA term as second K segment)"),
                      "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None if (sh.n_experts or args.rows or args.row_len or args.single_trajectory) else
+                     "traffic": None if (sh.n_experts or args.rows or args.row_len or args.single_trajectory or args.nf4) else
                                 TRAFFIC_BYTES_PER_LAUNCH.get((args.config, DOMINANT_KERNEL)),
                      "traffic_unit": "HBM-side bytes per launch (counters)",
                      "launches_per_step": n_l // max(args.steps, 1), "avg_launch_ms": round(ms_l / max(n_l, 1), 4)},

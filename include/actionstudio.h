@@ -60,6 +60,8 @@ enum { AS_LORA = 0, AS_FULL = 1 };            /* as_model_config.train_mode  */
 
 /* LoRA targets: index into the a[]/b[] arrays below and bit position in
  * as_model_config.lora_targets. */
+enum { AS_W_DENSE = 0, AS_W_NF4 = 1 };
+
 enum { AS_T_Q = 0, AS_T_K, AS_T_V, AS_T_O, AS_T_GATE, AS_T_UP, AS_T_DOWN, AS_T_ROUTER, AS_N_TARGETS };
 
 typedef struct as_ctx as_ctx;
@@ -80,14 +82,22 @@ typedef struct {
                                       attention outputs, rebuild only the norm
                                       outputs and the SwiGLU product (fits 8B
                                       shapes at 4 x 16k tokens in 288 GB)        */
+  int32_t weight_format;           /* AS_W_DENSE: projection weights of type T;
+                                      AS_W_NF4: 4-bit NormalFloat blocks (quantised
+                                      frozen base under LoRA, paper Section 4.5 /
+                                      Table 3 "Q+LoRA"), see as_nf4_quantize      */
 } as_model_config;
 
 /* Frozen (LoRA) or trainable (full) weights of one layer.  [device], type T.
  * g1,g2 [d_model]; wq [Hq*dh, d]; wk,wv [Hkv*dh, d]; wo [d, Hq*dh];
  * wgate,wup [ffn, d]; wdown [d, ffn]  (MoE: [n_experts, ...] stacked);
- * wrouter [n_experts, d] or NULL. */
+ * wrouter [n_experts, d] or NULL.
+ * With weight_format == AS_W_NF4 the seven projection pointers hold packed 4-bit
+ * codes (uint8, numel/2 bytes, row-major element order) and aq .. adown the float
+ * absolute maxima of their 64-element blocks (numel/64 each); gains stay type T. */
 typedef struct {
   const void *g1, *wq, *wk, *wv, *wo, *g2, *wgate, *wup, *wdown, *wrouter;
+  const float *aq, *ak, *av, *ao, *agate, *aup, *adown;
 } as_layer_weights;
 
 typedef struct {
@@ -283,6 +293,16 @@ int as_op_attention_bwd(as_ctx* ctx, int mode, int variant, int64_t n, const int
                         const void* v, int64_t ldkv, const void* o, const float* lse,
                         const void* d_o, void* dq, void* dk, void* dv, float* delta_scratch,
                         void* t_scratch, void* stream);
+
+/* NF4 block quantisation of a frozen weight tensor (the "Q" of the paper's Q+LoRA regime, Section 4.5;
+ * format of the public QLoRA description): numel (a multiple of 64) elements of type T, flattened
+ * row-major, in blocks of 64: absmax[b] = max |w| of block b (float), code = index of the nearest of
+ * the 16 NormalFloat levels to w / absmax (float32 decision, midpoint goes up), two codes per byte
+ * (element 2j in the low nibble).  d_codes: numel/2 bytes, d_absmax: numel/64 floats, all [device].
+ * as_nf4_dequantize writes level[code] * absmax as type T.  as_train_step dequantises one projection
+ * at a time into its workspace, so the resident copy of the base model is 4.5 bits per weight. */
+int as_nf4_quantize(as_ctx* ctx, int mode, const void* d_w, int64_t numel, uint8_t* d_codes, float* d_absmax, void* stream);
+int as_nf4_dequantize(as_ctx* ctx, int mode, const uint8_t* d_codes, const float* d_absmax, int64_t numel, void* d_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -24,6 +24,9 @@ AS_LORA, AS_FULL = 0, 1
 TARGETS = ("q", "k", "v", "o", "gate", "up", "down", "router")
 N_TARGETS = 8
 _WFIELDS = ("g1", "wq", "wk", "wv", "wo", "g2", "wgate", "wup", "wdown", "wrouter")
+_AFIELDS = ("aq", "ak", "av", "ao", "agate", "aup", "adown")      # NF4 block maxima of wq .. wdown
+_QUANT = dict(zip(("wq", "wk", "wv", "wo", "wgate", "wup", "wdown"), _AFIELDS))
+AS_W_DENSE, AS_W_NF4 = 0, 1
 
 
 class ModelConfig(C.Structure):
@@ -33,11 +36,11 @@ class ModelConfig(C.Structure):
                 ("n_experts", C.c_int32), ("top_k", C.c_int32),
                 ("rms_eps", C.c_float), ("rope_base", C.c_float),
                 ("lora_rank", C.c_int32), ("lora_alpha", C.c_float), ("lora_targets", C.c_uint32),
-                ("mode", C.c_int32), ("train_mode", C.c_int32), ("recompute", C.c_int32)]
+                ("mode", C.c_int32), ("train_mode", C.c_int32), ("recompute", C.c_int32), ("weight_format", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
-    _fields_ = [(f, C.c_void_p) for f in _WFIELDS]
+    _fields_ = [(f, C.c_void_p) for f in _WFIELDS + _AFIELDS]
 
 
 class Weights(C.Structure):
@@ -90,12 +93,12 @@ lib.as_profile_read.argtypes = [_vp, C.c_int, C.POINTER(_i64), C.POINTER(C.c_dou
 KERNEL_CLASSES = ("gemm_mfma_256", "gemm_mfma_skinny", "gemm_fma", "gemm_devrows", "attn_fwd", "attn_bwd", "transpose",
                   "norm", "swiglu", "rope", "ce", "lora_grad", "gemm_grouped", "moe")
 for _n in ("as_profile", "as_profile_read", "as_create", "as_workspace_bytes", "as_pack", "as_train_step", "as_adamw_update", "as_op_gemm",
-           "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd"):
+           "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize"):
     getattr(lib, _n).restype = C.c_int
 
 EXPORTS = ("as_probe_lds_feed", "as_probe_mfma_peak", "as_profile", "as_profile_read", "as_create", "as_destroy", "as_last_error", "as_workspace_bytes", "as_pack", "as_train_step",
            "as_adamw_update", "as_op_gemm", "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd",
-           "as_op_attention_bwd")
+           "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize")
 
 
 class ASError(RuntimeError):
@@ -104,7 +107,7 @@ class ASError(RuntimeError):
         self.code = code
 
 
-def make_config(sh, mode=None, train_mode=None, recompute=None):
+def make_config(sh, mode=None, train_mode=None, recompute=None, weight_format=AS_W_DENSE):
     """sh: any object with the attribute names of synth.Shape."""
     full = bool(getattr(sh, "full_ft", False)) if train_mode is None else train_mode == AS_FULL
     mask = 0
@@ -118,7 +121,7 @@ def make_config(sh, mode=None, train_mode=None, recompute=None):
     return ModelConfig(C.sizeof(ModelConfig), sh.n_layers, sh.d_model, sh.n_q_heads, sh.n_kv_heads, sh.head_dim,
                        sh.ffn, sh.vocab, sh.n_experts, sh.top_k, sh.rms_eps, sh.rope_base,
                        0 if full else sh.lora_rank, 0.0 if full else sh.lora_alpha, mask, mode,
-                       AS_FULL if full else AS_LORA, recompute)
+                       AS_FULL if full else AS_LORA, recompute, weight_format)
 
 
 def _ptr(t):
@@ -259,6 +262,21 @@ class Context:
                                   R.stride(0) if R is not None else 0, _ptr(Cm), Cm.stride(0), int(out_f32), _stream()))
         return Cm
 
+    def nf4_quantize(self, w):
+        """w: device tensor (float32 or bfloat16), numel a multiple of 64 -> (packed codes uint8 [numel/2], absmax float32 [numel/64])."""
+        w = w.contiguous()
+        mode = AS_FP32 if w.dtype == torch.float32 else AS_BF16
+        codes = torch.empty(w.numel() // 2, dtype=torch.uint8, device=w.device)
+        absmax = torch.empty(w.numel() // 64, dtype=torch.float32, device=w.device)
+        self.check(lib.as_nf4_quantize(self.handle, mode, _ptr(w), C.c_int64(w.numel()), _ptr(codes), _ptr(absmax), _stream()))
+        return codes, absmax
+
+    def nf4_dequantize(self, codes, absmax, dtype):
+        mode = AS_FP32 if dtype == torch.float32 else AS_BF16
+        out = torch.empty(codes.numel() * 2, dtype=dtype, device=codes.device)
+        self.check(lib.as_nf4_dequantize(self.handle, mode, _ptr(codes), _ptr(absmax), C.c_int64(out.numel()), _ptr(out), _stream()))
+        return out
+
     def op_rmsnorm_fwd(self, x, g, eps, mode=None):
         mode = self.mode if mode is None else mode
         n, d = x.shape
@@ -329,11 +347,16 @@ class DeviceModel:
             return torch.from_numpy(np.ascontiguousarray(x)).to(device=dev, dtype=dt).contiguous()
 
         self.embed, self.head, self.g_final = up(params["embed"], wd), up(params["head"], wd), up(params["g_final"], wd)
-        self.layers = [{k: up(v, wd) for k, v in W.items()} for W in params["layers"]]
+        def up_w(k, v):                      # NF4: codes stay uint8, block maxima float
+            if cfg.weight_format == AS_W_NF4 and k in _QUANT:
+                return up(v, torch.uint8)
+            return up(v, torch.float32 if k in _AFIELDS else wd)
+
+        self.layers = [{k: up_w(k, v) for k, v in W.items()} for W in params["layers"]]
         L = cfg.n_layers
         self._lw = (LayerWeights * L)()
         for l, W in enumerate(self.layers):
-            for f in _WFIELDS:
+            for f in _WFIELDS + _AFIELDS:
                 setattr(self._lw[l], f, W[f].data_ptr() if f in W else None)
         self.c_weights = Weights(self.embed.data_ptr(), self.g_final.data_ptr(), self.head.data_ptr(), self._lw)
         self.c_lora = None

@@ -44,6 +44,12 @@ static int check_config(const as_model_config* c) {
     return as_fail(nullptr, AS_ERR_CONFIG, "full fine-tuning takes no adapters");
   }
   if (c->recompute < 0 || c->recompute > 2) return as_fail(nullptr, AS_ERR_CONFIG, "recompute must be 0, 1 or 2");
+  if (c->weight_format != AS_W_DENSE && c->weight_format != AS_W_NF4) return as_fail(nullptr, AS_ERR_CONFIG, "weight_format");
+  if (c->weight_format == AS_W_NF4) {
+    if (c->train_mode != AS_LORA || moe) return as_fail(nullptr, AS_ERR_CONFIG, "NF4 weights are a frozen dense base: LoRA mode, no experts");
+    if (c->d_model % 64 || c->ffn % 64 || (c->n_q_heads * c->head_dim) % 64 || (c->n_kv_heads * c->head_dim) % 64)
+      return as_fail(nullptr, AS_ERR_CONFIG, "NF4 weights need widths that are multiples of the 64-element block");
+  }
   return AS_OK;
 }
 
@@ -191,6 +197,12 @@ static int pack_plan(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* tur
   if (T <= 0 || max_rows < 0 || n_traj < 0) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: row_len must be positive, counts non-negative");
   if ((int64_t)T * max_rows > INT32_MAX) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: max_rows*row_len exceeds int32");
   if (traj_offsets[0] != 0 || turn_offsets[0] != 0) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: offsets must start at 0");
+  // both offset tables are checked in full before any token is read: the last turn offset is the
+  // length of turn_tokens, and no earlier offset may point past it
+  for (int32_t i = 0; i < n_traj; i++)
+    if (traj_offsets[i + 1] < traj_offsets[i]) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: traj_offsets must not decrease (trajectory %d)", i);
+  for (int32_t t = 0, nt = traj_offsets[n_traj]; t < nt; t++)
+    if (turn_offsets[t + 1] < turn_offsets[t]) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: turn_offsets must not decrease (turn %d)", t);
   pieces.clear(); cu.clear(); cu.push_back(0); skip.clear();
   int32_t fill = 0, rows = 0, consumed = 0; bool open = false;
   auto close_row = [&]() {
@@ -326,6 +338,7 @@ struct Plan {
   void *dh, *dh2, *dm, *dgu, *db, *d_o, *dqkv, *da;
   void *du_qkv, *du_o, *du_gu, *du_d;
   void *wT, *xT, *dyT, *uT, *duT, *attT;
+  void* wdq;                             // one dequantised projection matrix (NF4 base)
   void *xbp, *dlogit, *du_r, *wrT;       // MoE scratch: permuted rows [2N, d], router logit gradient [N, E], [N, rp], router weight transpose [d, E]
   std::vector<LoraSlot> lora;            // L * AS_N_TARGETS
   std::vector<void*> A_qkv, At_qkv, A_gu, At_gu;   // per layer concatenated groups
@@ -418,6 +431,7 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   P.du_gu = w.take(N * P.n_gu * rp * es); P.du_d = w.take(on(AS_T_DOWN) ? N * rp * es : 0);
   size_t wmax = std::max({(size_t)P.QKV * P.d, (size_t)P.d * P.D, (size_t)2 * P.F * P.d, (size_t)P.d * P.F});
   P.wT = w.take(wmax * es);
+  P.wdq = w.take(c.weight_format == AS_W_NF4 ? std::max((size_t)P.F * P.d, (size_t)P.D * P.d) * es : 0);
   P.xbp = w.take(moe ? 2 * N * P.d * es : 0); P.dlogit = w.take(N * E * es);
   P.du_r = w.take(on(AS_T_ROUTER) ? N * rp * es : 0); P.wrT = w.take((size_t)P.d * E * es);
   const bool need_T = full || (c.lora_targets & 0xff);
@@ -504,6 +518,16 @@ struct Step {
 
   LoraSlot& slot(int l, int t) { return P.lora[(size_t)l * AS_N_TARGETS + t]; }
 
+  // The dense [rows, cols] matrix of a frozen projection: the caller's pointer, or, for an NF4 base, the
+  // workspace slot it is dequantised into right before its use (one slot: the stream orders the reuse).
+  int wq_rc = AS_OK;
+  const void* dense(const void* w, const float* absmax, int rows, int cols) {
+    if (c.weight_format != AS_W_NF4) return w;
+    int rc = launch_nf4_dequantize(ctx, mode, (const uint8_t*)w, absmax, (int64_t)rows * cols, P.wdq, st);
+    if (rc && !wq_rc) wq_rc = rc;
+    return P.wdq;
+  }
+
   int prep_lora(int l) {
     const as_layer_lora& Lr = lora->layers[l];
     const float s = c.lora_alpha / (float)c.lora_rank;
@@ -532,10 +556,11 @@ struct Step {
     if ((rc = launch_rmsnorm_fwd(ctx, mode, N, d, h_in, nullptr, nullptr, w.g1, c.rms_eps, a.a, a.rstd1, st))) return rc;
     const int ldu = P.n_qkv * rp;
     if (P.n_qkv && (rc = gemm(N, ldu, a.a, d, P.A_qkv[l], d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_qkv, ldu))) return rc;
-    const void* wq[3] = {w.wq, w.wk, w.wv}; const int nout[3] = {D, Dkv, Dkv}; const int coff[3] = {0, D, D + Dkv};
+    const void* wq[3] = {w.wq, w.wk, w.wv}; const float* aq[3] = {w.aq, w.ak, w.av};
+    const int nout[3] = {D, Dkv, Dkv}; const int coff[3] = {0, D, D + Dkv};
     for (int i = 0; i < 3; i++) {
       LoraSlot& s = slot(l, i);
-      rc = gemm(N, nout[i], a.a, d, wq[i], d, d, s.on ? off(a.u_qkv, (size_t)s.slot * rp) : nullptr, ldu, s.Bs, rp, s.on ? rp : 0,
+      rc = gemm(N, nout[i], a.a, d, dense(wq[i], aq[i], nout[i], d), d, d, s.on ? off(a.u_qkv, (size_t)s.slot * rp) : nullptr, ldu, s.Bs, rp, s.on ? rp : 0,
                 nullptr, 0, off(a.qkv, coff[i]), QKV);
       if (rc) return rc;
     }
@@ -547,22 +572,22 @@ struct Step {
     if ((rc = launch_attention_fwd(ctx, mode, av, ap, st))) return rc;
     { LoraSlot& s = slot(l, AS_T_O);
       if (s.on && (rc = gemm(N, rp, a.o, D, s.A, D, D, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_o, rp))) return rc;
-      if ((rc = gemm(N, d, a.o, D, w.wo, D, D, s.on ? a.u_o : nullptr, rp, s.Bs, rp, s.on ? rp : 0, h_in, d, a.h_mid, d))) return rc; }
+      if ((rc = gemm(N, d, a.o, D, dense(w.wo, w.ao, d, D), D, D, s.on ? a.u_o : nullptr, rp, s.Bs, rp, s.on ? rp : 0, h_in, d, a.h_mid, d))) return rc; }
     if ((rc = launch_rmsnorm_fwd(ctx, mode, N, d, a.h_mid, nullptr, nullptr, w.g2, c.rms_eps, a.b, a.rstd2, st))) return rc;
     if (c.n_experts) return forward_moe(l, a);
     const int ldg = P.n_gu * rp;
     if (P.n_gu && (rc = gemm(N, ldg, a.b, d, P.A_gu[l], d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_gu, ldg))) return rc;
-    const void* wg[2] = {w.wgate, w.wup};
+    const void* wg[2] = {w.wgate, w.wup}; const float* ag[2] = {w.agate, w.aup};
     for (int i = 0; i < 2; i++) {
       LoraSlot& s = slot(l, AS_T_GATE + i);
-      rc = gemm(N, F, a.b, d, wg[i], d, d, s.on ? off(a.u_gu, (size_t)s.slot * rp) : nullptr, ldg, s.Bs, rp, s.on ? rp : 0,
+      rc = gemm(N, F, a.b, d, dense(wg[i], ag[i], F, d), d, d, s.on ? off(a.u_gu, (size_t)s.slot * rp) : nullptr, ldg, s.Bs, rp, s.on ? rp : 0,
                 nullptr, 0, off(a.gu, (size_t)i * F), 2 * F);
       if (rc) return rc;
     }
     if ((rc = launch_swiglu_fwd(ctx, mode, N, F, a.gu, a.m, st))) return rc;
     { LoraSlot& s = slot(l, AS_T_DOWN);
       if (s.on && (rc = gemm(N, rp, a.m, F, s.A, F, F, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_d, rp))) return rc;
-      if ((rc = gemm(N, d, a.m, F, w.wdown, F, F, s.on ? a.u_d : nullptr, rp, s.Bs, rp, s.on ? rp : 0, a.h_mid, d, h_out, d))) return rc; }
+      if ((rc = gemm(N, d, a.m, F, dense(w.wdown, w.adown, d, F), F, F, s.on ? a.u_d : nullptr, rp, s.Bs, rp, s.on ? rp : 0, a.h_mid, d, h_out, d))) return rc; }
     return AS_OK;
   }
 
@@ -712,7 +737,7 @@ struct Step {
     else {
     // ---- down projection
     { LoraSlot& s = slot(l, AS_T_DOWN);
-      if ((rc = transpose(d, F, w.wdown, F, P.wT, d))) return rc;                       // [F, d]
+      if ((rc = transpose(d, F, dense(w.wdown, w.adown, d, F), F, P.wT, d))) return rc;                       // [F, d]
       if (s.on && (rc = gemm(N, rp, P.dh, d, s.Bst, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.du_d, rp))) return rc;
       if ((rc = gemm(N, F, P.dh, d, P.wT, d, d, s.on ? P.du_d : nullptr, rp, s.At, rp, s.on ? rp : 0, nullptr, 0, P.dm, F))) return rc;
       // ---- SwiGLU (in recompute mode 2 it also rewrites the forward product, which the gradients below need)
@@ -730,10 +755,10 @@ struct Step {
       if (full && (rc = weight_grad(G->w_layers[l].wdown, d, F, P.dyT, P.xT))) return rc; }
     // ---- gate / up projections
     { const int ldg = P.n_gu * rp;
-      const void* wg[2] = {w.wgate, w.wup};
+      const void* wg[2] = {w.wgate, w.wup}; const float* ag[2] = {w.agate, w.aup};
       for (int i = 0; i < 2; i++) {
         LoraSlot& s = slot(l, AS_T_GATE + i);
-        if ((rc = transpose(F, d, wg[i], d, off(P.wT, (size_t)i * F), 2 * F))) return rc;        // [d, 2F]
+        if ((rc = transpose(F, d, dense(wg[i], ag[i], F, d), d, off(P.wT, (size_t)i * F), 2 * F))) return rc;        // [d, 2F]
         if (s.on && (rc = gemm(N, rp, off(P.dgu, (size_t)i * F), 2 * F, s.Bst, F, F, nullptr, 0, nullptr, 0, 0, nullptr, 0,
                                off(P.du_gu, (size_t)s.slot * rp), ldg))) return rc;
       }
@@ -759,7 +784,7 @@ struct Step {
     if ((rc = launch_rmsnorm_bwd(ctx, mode, N, d, P.db, nullptr, a.h_mid, w.g2, a.rstd2, P.dh, P.dh2, st))) return rc;
     // ---- output projection
     { LoraSlot& s = slot(l, AS_T_O);
-      if ((rc = transpose(d, D, w.wo, D, P.wT, d))) return rc;                          // [D, d]
+      if ((rc = transpose(d, D, dense(w.wo, w.ao, d, D), D, P.wT, d))) return rc;                          // [D, d]
       if (s.on && (rc = gemm(N, rp, P.dh2, d, s.Bst, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.du_o, rp))) return rc;
       if ((rc = gemm(N, D, P.dh2, d, P.wT, d, d, s.on ? P.du_o : nullptr, rp, s.At, rp, s.on ? rp : 0, nullptr, 0, P.d_o, D))) return rc;
       if (full || (s.on && !tn_path())) {
@@ -782,12 +807,13 @@ struct Step {
     if ((rc = launch_rope(ctx, mode, N, c.n_q_heads + c.n_kv_heads, c.head_dim, P.dqkv, QKV, P.seg_start, P.rope_cos, P.rope_sin, 1, st))) return rc;
     // ---- q / k / v projections
     { const int ldu = P.n_qkv * rp;
-      const void* wq[3] = {w.wq, w.wk, w.wv}; const int nout[3] = {D, Dkv, Dkv}; const int coff[3] = {0, D, D + Dkv};
+      const void* wq[3] = {w.wq, w.wk, w.wv}; const float* aq[3] = {w.aq, w.ak, w.av};
+      const int nout[3] = {D, Dkv, Dkv}; const int coff[3] = {0, D, D + Dkv};
       // with frozen embeddings nothing below the first layer's first norm takes a gradient
       const bool need_da = full || l > 0;
       for (int i = 0; i < 3; i++) {
         LoraSlot& s = slot(l, i);
-        if (need_da && (rc = transpose(nout[i], d, wq[i], d, off(P.wT, coff[i]), QKV))) return rc;          // [d, QKV]
+        if (need_da && (rc = transpose(nout[i], d, dense(wq[i], aq[i], nout[i], d), d, off(P.wT, coff[i]), QKV))) return rc;          // [d, QKV]
         if (s.on && (rc = gemm(N, rp, off(P.dqkv, coff[i]), QKV, s.Bst, nout[i], nout[i], nullptr, 0, nullptr, 0, 0, nullptr, 0,
                                off(P.du_qkv, (size_t)s.slot * rp), ldu))) return rc;
       }
@@ -905,6 +931,8 @@ extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lo
     if (!w.g1 || !w.wq || !w.wk || !w.wv || !w.wo || !w.g2 || !w.wgate || !w.wup || !w.wdown)
       return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL weight in layer %d", l);
     if (c.n_experts && !w.wrouter) return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL router weight in layer %d", l);
+    if (c.weight_format == AS_W_NF4 && (!w.aq || !w.ak || !w.av || !w.ao || !w.agate || !w.aup || !w.adown))
+      return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL block maxima of an NF4 weight in layer %d", l);
   }
   if (!full) {
     if (!lora || !lora->layers || !grads->lora_layers) return as_fail(ctx, AS_ERR_NULL, "as_train_step: LoRA mode needs adapters and their gradient buffers");
@@ -1000,7 +1028,7 @@ extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lo
     if ((rc = S.backward_layer(l, a))) return rc;
   }
   if (full && (rc = launch_embed_bwd(ctx, c.mode, d_tokens, n, c.d_model, c.vocab, P.dh, P.iscratch, grads->embed, st))) return rc;
-  return AS_OK;
+  return S.wq_rc;
 }
 
 // -------------------------------------------------------------------- AdamW
@@ -1032,6 +1060,24 @@ extern "C" int as_adamw_update(as_ctx* ctx, float* const* d_master, void* const*
 static int check_mode(as_ctx* ctx, int mode) {
   if (mode != AS_FP32 && mode != AS_BF16) return as_fail(ctx, AS_ERR_CONFIG, "mode must be AS_FP32 or AS_BF16");
   return AS_OK;
+}
+
+extern "C" int as_nf4_quantize(as_ctx* ctx, int mode, const void* d_w, int64_t numel, uint8_t* d_codes, float* d_absmax, void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_nf4_quantize: NULL context");
+  int rc = check_mode(ctx, mode); if (rc) return rc;
+  if (numel < 0) return as_fail(ctx, AS_ERR_SHAPE, "as_nf4_quantize: negative element count");
+  if (numel && (!d_w || !d_codes || !d_absmax)) return as_fail(ctx, AS_ERR_NULL, "as_nf4_quantize: NULL argument");
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  return launch_nf4_quantize(ctx, mode, d_w, numel, d_codes, d_absmax, (hipStream_t)stream);
+}
+
+extern "C" int as_nf4_dequantize(as_ctx* ctx, int mode, const uint8_t* d_codes, const float* d_absmax, int64_t numel, void* d_out, void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_nf4_dequantize: NULL context");
+  int rc = check_mode(ctx, mode); if (rc) return rc;
+  if (numel < 0) return as_fail(ctx, AS_ERR_SHAPE, "as_nf4_dequantize: negative element count");
+  if (numel && (!d_codes || !d_absmax || !d_out)) return as_fail(ctx, AS_ERR_NULL, "as_nf4_dequantize: NULL argument");
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  return launch_nf4_dequantize(ctx, mode, d_codes, d_absmax, numel, d_out, (hipStream_t)stream);
 }
 
 extern "C" int as_op_gemm(as_ctx* ctx, int mode, int variant, int64_t M, int64_t N,

@@ -134,6 +134,9 @@ int launch_rmsnorm_dgain(as_ctx* ctx, int mode, int n, int d, const void* dy, co
                          hipStream_t st);
 int launch_rope(as_ctx* ctx, int mode, int n, int n_heads, int dh, void* x, int64_t ldx,
                 const int32_t* seg_start, const float* cosb, const float* sinb, int inverse, hipStream_t st);
+// NF4 block quantisation (quant.hip)
+int launch_nf4_quantize(as_ctx* ctx, int mode, const void* w, int64_t numel, uint8_t* codes, float* absmax, hipStream_t st);
+int launch_nf4_dequantize(as_ctx* ctx, int mode, const uint8_t* codes, const float* absmax, int64_t numel, void* out, hipStream_t st);
 // mixture-of-experts routing and row grouping (moe.hip)
 int launch_moe_route(as_ctx* ctx, const float* logit, int n, int E, int32_t* sel, float* w, hipStream_t st);
 int launch_moe_permute(as_ctx* ctx, const int32_t* sel, int n, int E, int32_t* eoff, int32_t* pos, int32_t* perm, hipStream_t st);

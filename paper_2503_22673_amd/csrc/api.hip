@@ -981,8 +981,10 @@ extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lo
     }
   }
   // The attention kernels' workgroups differ in length by the position of their rows inside a segment
-  // (a late query tile visits many key tiles, an early key block is visited by many query tiles); the
-  // launch is as long as its last workgroup, so the long ones are listed first.
+  // (a late query tile visits many key tiles, an early key block is visited by many query tiles), and the
+  // workgroups of one segment stream the same tiles.  The launch order lists the segments longest first and,
+  // inside a segment, the long workgroups first: neighbours in the order then share their operand tiles in
+  // the L2 of the XCD they run on, and the launch ends on the short workgroups of the short segments.
   const bool orders = c.mode == AS_BF16 && (c.head_dim == 64 || c.head_dim == 128) && n > 0;
   if (n_seg_eff > 0 && (compact || orders)) {
     std::vector<int32_t> tab = cu_h;                       // [cu (S'+1) | src_start (S') | order_q | order_k]
@@ -992,11 +994,16 @@ extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lo
       const int QT = attention_query_tile(c.n_q_heads, c.n_kv_heads), KPB = 256;
       const int nq = (int)cdiv(n, QT), nk = (int)cdiv(n, KPB);
       auto seg_of = [&](int t) { return (int)(std::upper_bound(cu_h.begin(), cu_h.end(), t) - cu_h.begin()) - 1; };
-      std::vector<int32_t> wq(nq), wk(nk), oq(nq), ok(nk);
-      for (int i = 0; i < nq; i++) { wq[i] = std::min(i * QT + QT - 1, n - 1) / 64 - cu_h[seg_of(i * QT)] / 64 + 1; oq[i] = i; }
-      for (int i = 0; i < nk; i++) { wk[i] = (cu_h[seg_of(std::min(i * KPB + KPB - 1, n - 1)) + 1] - 1) / 64 - (i * KPB) / 64 + 1; ok[i] = i; }
-      std::stable_sort(oq.begin(), oq.end(), [&](int a, int b) { return wq[a] > wq[b]; });
-      std::stable_sort(ok.begin(), ok.end(), [&](int a, int b) { return wk[a] > wk[b]; });
+      std::vector<int32_t> wq(nq), wk(nk), sq(nq), sk(nk), oq(nq), ok(nk);
+      for (int i = 0; i < nq; i++) { sq[i] = seg_of(i * QT); wq[i] = std::min(i * QT + QT - 1, n - 1) / 64 - cu_h[sq[i]] / 64 + 1; oq[i] = i; }
+      for (int i = 0; i < nk; i++) { sk[i] = seg_of(std::min(i * KPB + KPB - 1, n - 1)); wk[i] = (cu_h[sk[i] + 1] - 1) / 64 - (i * KPB) / 64 + 1; ok[i] = i; }
+      auto seg_len = [&](int s) { return cu_h[s + 1] - cu_h[s]; };
+      auto before = [&](const std::vector<int32_t>& sg, const std::vector<int32_t>& w, int a, int b) {
+        if (sg[a] != sg[b]) { const int la = seg_len(sg[a]), lb = seg_len(sg[b]); return la != lb ? la > lb : sg[a] < sg[b]; }
+        return w[a] > w[b];
+      };
+      std::stable_sort(oq.begin(), oq.end(), [&](int a, int b) { return before(sq, wq, a, b); });
+      std::stable_sort(ok.begin(), ok.end(), [&](int a, int b) { return before(sk, wk, a, b); });
       off_q = tab.size(); tab.insert(tab.end(), oq.begin(), oq.end());
       off_k = tab.size(); tab.insert(tab.end(), ok.begin(), ok.end());
     }

@@ -261,6 +261,16 @@ __device__ __forceinline__ void tile_to_lds(const bf16_t* base, int64_t ld, int 
 // QB = 1 keeps a wave under 256 registers, so two waves share a SIMD and one's softmax runs under the other's MFMAs.
 // NWV = 4 with QB = 1: two independent 4-wave workgroups per CU instead of one of eight waves; the register cap
 // (two waves per SIMD) then has to be asked for explicitly.
+// Workgroups go to the eight XCDs round-robin by linear index, and each XCD has an L2 of its own.  The work
+// items of a launch form `ngrp` groups (a head or a group of heads) of `per` items each; the items of a
+// group stream the same operand tiles, so a whole group is kept on one XCD: XCD x takes the groups x, x + 8, ...
+// one after the other, each in the order given (longest first).  Without a multiple of eight groups the
+// mapping falls back to group-major order.
+__device__ inline void xcd_group_map(int wg, int per, int ngrp, int& group, int& item) {
+  if (ngrp % 8 == 0) { const int slot = wg >> 3; group = (slot / per) * 8 + (wg & 7); item = slot % per; }
+  else { group = wg / per; item = wg % per; }
+}
+
 template <int DH, int HPW, int QB, int NWV>
 __global__ __launch_bounds__(NWV * 64, QB == 1 ? 2 : 1) void attn_fwd2_mfma(AttnParams p, float sl2) {
   constexpr int KS = DH / 16, CB = DH / 32, WQ = 32 * QB, QT = WQ * (NWV / HPW);
@@ -270,8 +280,11 @@ __global__ __launch_bounds__(NWV * 64, QB == 1 ? 2 : 1) void attn_fwd2_mfma(Attn
   const int tid = threadIdx.x, lane = tid & 63, l31 = lane & 31, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform values stay in scalar registers and branches on them are real branches
   const int n = p.n, grp = p.Hq / p.Hkv;
-  const int j = blockIdx.y * HPW + (wave % HPW), g = j / grp;
-  const int t_wg = (p.order_q ? p.order_q[blockIdx.x] : (int)(gridDim.x - 1 - blockIdx.x)) * QT;   // long rows first
+  int hg, qi;
+  const int nqt = (n + QT - 1) / QT;
+  xcd_group_map(blockIdx.x, nqt, p.Hq / HPW, hg, qi);
+  const int j = hg * HPW + (wave % HPW), g = j / grp;
+  const int t_wg = (p.order_q ? p.order_q[qi] : nqt - 1 - qi) * QT;   // long rows first
   const int t_base = t_wg + (wave / HPW) * WQ;
   const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* VT = (const bf16_t*)p.vT;
 
@@ -645,8 +658,11 @@ __global__ __launch_bounds__(512) void attn_bwd_dq2_mfma(AttnParams p, float sca
   const int tid = threadIdx.x, lane = tid & 63, l31 = lane & 31, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = p.n, grp = p.Hq / p.Hkv;
-  const int j = blockIdx.y * HPW + (wave % HPW), g = j / grp;
-  const int t_wg = (p.order_q ? p.order_q[blockIdx.x] : (int)(gridDim.x - 1 - blockIdx.x)) * QT;   // long rows first
+  int hg, qi;
+  const int nqt = (n + QT - 1) / QT;
+  xcd_group_map(blockIdx.x, nqt, p.Hq / HPW, hg, qi);
+  const int j = hg * HPW + (wave % HPW), g = j / grp;
+  const int t_wg = (p.order_q ? p.order_q[qi] : nqt - 1 - qi) * QT;   // long rows first
   const int t_base = t_wg + (wave / HPW) * 32;
   const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* V = (const bf16_t*)p.v;
   const bf16_t* dO = (const bf16_t*)p.d_o; const bf16_t* KT = (const bf16_t*)p.kT;
@@ -733,7 +749,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq2_mfma(AttnParams p, float sca
 }
 
 // Wave = 32 keys of one KV head (a lane owns one key), workgroup = 8 waves = 256 keys and ONE query head of
-// the group (blockIdx.z); loops over 64-query tiles.  With several query heads per KV head each launch
+// the group; loops over 64-query tiles.  With several query heads per KV head each launch
 // writes float partials [query head][token][dh] that a second pass sums in head order: one workgroup
 // looping over all heads of the group would be several times longer than the average workgroup, and the
 // launch as long as its longest workgroup.  dK and dV come from two launches (WHICH = 0: dK,
@@ -750,8 +766,11 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float sc
   bf16_t* sm = (bf16_t*)dyn_smem;
   const int tid = threadIdx.x, lane = tid & 63, l31 = lane & 31, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int n = p.n, grp = p.Hq / p.Hkv, g = blockIdx.y;
-  const int u_wg = (p.order_k ? p.order_k[blockIdx.x] : (int)blockIdx.x) * KPB, u_base = u_wg + wave * 32;
+  const int n = p.n, grp = p.Hq / p.Hkv;
+  int jj, ki;
+  xcd_group_map(blockIdx.x, (n + KPB - 1) / KPB, p.Hq, jj, ki);
+  const int g = jj / grp;
+  const int u_wg = (p.order_k ? p.order_k[ki] : ki) * KPB, u_base = u_wg + wave * 32;
   const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* V = (const bf16_t*)p.v;
   const bf16_t* dO = (const bf16_t*)p.d_o; const bf16_t* QTm = (const bf16_t*)p.qT; const bf16_t* DOT = (const bf16_t*)p.doT;
   const int u = u_base + l31, uc = min(u, n - 1);
@@ -771,9 +790,10 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float sc
   const int w_end = (u_base < n) ? __builtin_amdgcn_readfirstlane(p.seg_end[min(u_base + 31, n - 1)]) : 0;
   const int w_end_min = (u_base < n) ? __builtin_amdgcn_readfirstlane(p.seg_end[min(u_base, n - 1)]) : 0;
   const int total = q_last - q_first + 1;
-  const int jj = g * grp + blockIdx.z;
+  // Query tiles are taken from the segment's end downwards: the workgroups of one head and segment that start
+  // together then read the same tiles at the same time, whatever their own first tile is.
   auto stage = [&](int it, int b) {
-    const int t0 = (q_first + it) * BKEY;
+    const int t0 = (q_last - it) * BKEY;
     bf16_t* d = sm + b * ST_E;
     tile_to_lds<BKEY, DH, NWV>(Q + jj * DH, p.ldq, t0, n - 1, d, wave, lane);
     if constexpr (WHICH == 0) {
@@ -795,7 +815,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float sc
     __builtin_amdgcn_s_waitcnt(0x0f70);
     __syncthreads();
     if (it + 1 < total) stage(it + 1, b ^ 1);
-    const int t0 = (q_first + it) * BKEY;
+    const int t0 = (q_last - it) * BKEY;
     if (t0 + 63 < u_base || t0 >= w_end) continue;             // no query of the tile sees a key of this wave
     const bf16_t* sQ = sm + b * ST_E;
     const bf16_t* sdO = sQ + KT_E;                              // WHICH == 0 only
@@ -918,7 +938,7 @@ int launch_fwd2(as_ctx* ctx, const AttnParams& p_in, float sl2, hipStream_t st) 
     attr_set = true;
   }
   constexpr int QT = 32 * QB * (NWV / HPW);
-  attn_fwd2_mfma<DH, HPW, QB, NWV><<<dim3((unsigned)cdiv(p.n, QT), p.Hq / HPW), NWV * 64, smem, st>>>(p, sl2);
+  attn_fwd2_mfma<DH, HPW, QB, NWV><<<(unsigned)(cdiv(p.n, QT) * (p.Hq / HPW)), NWV * 64, smem, st>>>(p, sl2);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
@@ -952,7 +972,7 @@ int launch_dq2(as_ctx* ctx, const AttnParams& p, float scale, float sl2, hipStre
     AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dq2_mfma<DH, HPW>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_set = true;
   }
-  attn_bwd_dq2_mfma<DH, HPW><<<dim3((unsigned)cdiv(p.n, 32 * (8 / HPW)), p.Hq / HPW), 512, smem, st>>>(p, scale, sl2);
+  attn_bwd_dq2_mfma<DH, HPW><<<(unsigned)(cdiv(p.n, 32 * (8 / HPW)) * (p.Hq / HPW)), 512, smem, st>>>(p, scale, sl2);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
@@ -965,7 +985,7 @@ int launch_dkv2(as_ctx* ctx, const AttnParams& p, float scale, float sl2, float*
     AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv2_mfma<DH, WHICH>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_set = true;
   }
-  attn_bwd_dkv2_mfma<DH, WHICH><<<dim3((unsigned)cdiv(p.n, 256), p.Hkv, p.Hq / p.Hkv), 512, smem, st>>>(p, scale, sl2, part);
+  attn_bwd_dkv2_mfma<DH, WHICH><<<(unsigned)(cdiv(p.n, 256) * p.Hq), 512, smem, st>>>(p, scale, sl2, part);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }

@@ -308,11 +308,16 @@ def forward(cfg, params, lora, tokens, cu_seqlens, loss_mask):
                 per_token_loss=per_token, cache=cache)
 
 
-def backward(cfg, params, lora, fwd):
+def backward(cfg, params, lora, fwd, target_weights=None):
     """Gradients of the masked-mean loss.  Returns dict(weights=..., lora=...)
     where ``weights`` mirrors ``params`` (always filled: the frozen-weight
     gradients are what full fine-tuning uses) and ``lora`` mirrors ``lora``
-    with (dA, dB) pairs."""
+    with (dA, dB) pairs.
+
+    ``target_weights`` (one value per target, in target order) replaces the
+    1/count of the mean: the result is then the gradient of
+    sum_i target_weights[i] * per_token_loss[target i], which is what a loss
+    built on per-sequence log-probabilities needs (oracle/dpo.py)."""
     ca = fwd["cache"]
     N = len(ca["tokens"])
     Hq, Hkv, dh = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
@@ -325,7 +330,7 @@ def backward(cfg, params, lora, fwd):
         tgt, labels = ca["tgt"], ca["labels"]
         sm = np.exp(ca["z"][tgt] - ca["lse"][tgt][:, None])
         sm[np.arange(len(tgt)), labels] -= 1.0
-        dz[tgt] = sm / C
+        dz[tgt] = sm / C if target_weights is None else sm * np.asarray(target_weights, dtype=np.float64)[:, None]
     g_head = dz.T @ ca["hf"]
     dhf = dz @ head
     dres, g_gfinal = rmsnorm_bwd(dhf, ca["h_final"], params["g_final"], ca["rho_f"])

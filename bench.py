@@ -68,7 +68,7 @@ def device_lora(sh, seed):
     return out
 
 
-def algorithmic_flops(sh, seg_lens_nonpad, n_nonpad, n_targets):
+def algorithmic_flops(sh, seg_lens_nonpad, n_nonpad, n_targets, dpo=False):
     """Flops the method must do for this batch: causal half of attention inside
     each trajectory only, no weight gradients for frozen matrices, head on
     target rows only, no recompute, nothing for pad tokens."""
@@ -82,6 +82,10 @@ def algorithmic_flops(sh, seg_lens_nonpad, n_nonpad, n_targets):
     dims = synth.lora_dims(sh)
     lora = 6.0 * r * sum(sum(dims[t]) for t in sh.lora_targets) * L * n_nonpad
     head = (6.0 if sh.full_ft else 4.0) * d * V * n_targets
+    if dpo:     # forward of the frozen reference policy (no adapters), and the first of the two passes over the head
+        dense += 2.0 * L * p_layer * n_nonpad
+        attn += 2.0 * D * L * float(sum(x * x for x in seg_lens_nonpad))
+        head += 2.0 * 2.0 * d * V * n_targets
     recompute = 0.0
     if sh.recompute == 1:
         recompute = (2.0 * p_layer * n_nonpad + 2.0 * D * float(sum(x * x for x in seg_lens_nonpad)) +
@@ -152,6 +156,9 @@ def main():
     ap.add_argument("--nf4", action="store_true", help="frozen base held as NF4 blocks (quantised base + LoRA)")
     ap.add_argument("--single-trajectory", action="store_true",
                     help="long-context stress: every row is ONE trajectory of row_len tokens")
+    ap.add_argument("--dpo", action="store_true",
+                    help="preference step instead of the supervised one: reference pass with the adapters off + "
+                         "DPO step, consecutive trajectories paired as (chosen, rejected)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -208,8 +215,17 @@ def main():
     ws = torch.empty(ctx.workspace_bytes(sh.rows, sh.row_len), dtype=torch.uint8, device="cuda")
     out = None
 
+    live = [s for s in range(len(hcu) - 1) if not pk["seg_skip"][s]]
+    pairs = np.asarray(live[:len(live) // 2 * 2], dtype=np.int32).reshape(-1, 2)
+    dpo_out = None
+
     def step():
-        nonlocal out
+        nonlocal out, dpo_out
+        if args.dpo:
+            a = (model, pk["tokens"], pk["cu_seqlens"], hcu, pk["loss_mask"], sh.rows, sh.row_len, ws)
+            ref = ctx.sequence_logps(*a, seg_skip=pk["seg_skip"], adapters=False)
+            dpo_out = ctx.dpo_step(*a, pairs, ref, 0.1, seg_skip=pk["seg_skip"])
+            return
         out = ctx.train_step(model, pk["tokens"], pk["cu_seqlens"], hcu, pk["loss_mask"], sh.rows, sh.row_len, ws, out,
                              seg_skip=pk["seg_skip"])
 
@@ -229,10 +245,16 @@ def main():
     ms_per_step = e0.elapsed_time(e1) / args.steps
     prof = ctx.profile_read()
     ctx.profile(False)
-    loss, count = float(out["loss"].item()), int(out["count"].item())
+    if args.dpo:
+        loss = float(dpo_out["stats"][0].item())
+        mask_h = pk["loss_mask"].cpu().numpy().astype(bool)
+        first = np.zeros(len(mask_h), dtype=bool); first[hcu[:-1]] = True
+        count = int((mask_h & ~first).sum())
+    else:
+        loss, count = float(out["loss"].item()), int(out["count"].item())
     assert math.isfinite(loss), loss
 
-    fl = algorithmic_flops(sh, seg_nonpad, n_nonpad, count)
+    fl = algorithmic_flops(sh, seg_nonpad, n_nonpad, count, dpo=args.dpo)
     tokens_per_s = n_nonpad / (ms_per_step * 1e-3)
     mfu = fl["total"] / (ms_per_step * 1e-3) / (PEAK_BF16_TFLOPS * 1e12)
     hfu = (fl["total"] + fl["recompute"]) / (ms_per_step * 1e-3) / (PEAK_BF16_TFLOPS * 1e12)
@@ -263,10 +285,10 @@ def main():
 
     rec = {
         "metric": "trained tokens/s per MI355X (LoRA step, 8B shapes, 16k packed); % bf16 MFMA peak"
-                  if args.config == 3 and not (args.rows or args.row_len or args.single_trajectory or args.layers or args.nf4) else
+                  if args.config == 3 and not (args.rows or args.row_len or args.single_trajectory or args.layers or args.nf4 or args.dpo) else
                   "trained tokens/s per MI355X (one fine-tuning step, config %d%s)" % (
                       args.config, ", rows/row_len overridden" if (args.rows or args.row_len or args.single_trajectory) else "") +
-                  (", NF4 base" if args.nf4 else ""),
+                  (", NF4 base" if args.nf4 else "") + (", DPO step incl. reference pass" if args.dpo else ""),
         "value": round(tokens_per_s, 1), "unit": "trained tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 2), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if sh.bf16 else "f32", "data": "synthetic",
@@ -284,12 +306,12 @@ def main():
                                                   " (projection GEMMs forward + dX, LoRA term as second K segment)"),
                      "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None if (sh.n_experts or args.rows or args.row_len or args.single_trajectory or args.nf4) else
+                     "traffic": None if (sh.n_experts or args.rows or args.row_len or args.single_trajectory or args.nf4 or args.dpo) else
                                 TRAFFIC_BYTES_PER_LAUNCH.get((args.config, DOMINANT_KERNEL)),
                      "traffic_unit": "HBM-side bytes per launch (counters)",
                      "launches_per_step": n_l // max(args.steps, 1), "avg_launch_ms": round(ms_l / max(n_l, 1), 4)},
     }
-    if not args.no_cpu_baseline and not sh.n_experts:     # the sparse model's float64 weights do not fit the sample budget
+    if not args.no_cpu_baseline and not sh.n_experts and not args.dpo:     # the sparse model's float64 weights do not fit the sample budget
         rec["cpu_baseline"] = cpu_baseline(sh, args.seed)
     print(json.dumps(rec))
 

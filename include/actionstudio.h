@@ -238,6 +238,44 @@ int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lora* lora,
                   const as_grads* grads, void* d_workspace, size_t workspace_bytes,
                   void* stream);
 
+/* ---- preference learning (Sections 1 and 3.2: DPO beside supervised tuning) */
+
+/* The paper names the paradigm only; the loss is the published DPO objective with a frozen
+ * reference policy.  With pi_s = sum over the targets t of segment s of log p(token_{t+1} | ...)
+ * (the same targets as as_train_step) and ref_s the same sum under the reference policy,
+ *   z_p  = beta * [(pi_c - ref_c) - (pi_r - ref_r)]  for pair p = (chosen segment c, rejected r),
+ *   loss = mean over pairs of log(1 + exp(-z_p)).
+ *
+ * as_sequence_logps: forward pass only; writes pi_s for every segment of the caller's table to
+ *  d_logp [device] float [n_segments] (0 for a segment without target, or marked in h_seg_skip).
+ *  In LoRA mode a NULL `lora` switches the adapters off (the base model: the usual reference
+ *  policy of adapter training); in full mode pass the reference weights as `weights`.
+ *
+ * as_dpo_step: forward, pair loss and backward.
+ *  h_pairs     [host] int32 [n_pairs][2]: chosen and rejected segment index of each pair, two
+ *              different indices in [0, n_segments) -- AS_ERR_SHAPE otherwise.  A segment may
+ *              be in several pairs or in none (then it gets no gradient).
+ *  d_ref_logp  [device] float [n_segments], e.g. from as_sequence_logps.
+ *  beta        finite, >= 0.
+ *  d_stats     [device] float[3]: loss, mean z_p ("reward margin"), fraction of pairs with z_p > 0.
+ *  d_logp      [device] float [n_segments] or NULL: the policy's pi_s.
+ *  Gradients are overwritten; with no pair they are exactly zero and the loss is 0.
+ * All other arguments, the workspace size and the error behaviour are as_train_step's.  The
+ * vocabulary head runs twice (per-target losses first, then the gradient rows, whose factor
+ * depends on all sums); everything else runs once. */
+int as_sequence_logps(as_ctx* ctx, const as_weights* weights, const as_lora* lora,
+                      const int32_t* d_tokens, const int32_t* d_cu_seqlens,
+                      const int32_t* h_cu_seqlens, int32_t n_segments, const uint8_t* h_seg_skip,
+                      const uint8_t* d_loss_mask, int32_t n_rows, int32_t row_len,
+                      float* d_logp, void* d_workspace, size_t workspace_bytes, void* stream);
+int as_dpo_step(as_ctx* ctx, const as_weights* weights, const as_lora* lora,
+                const int32_t* d_tokens, const int32_t* d_cu_seqlens,
+                const int32_t* h_cu_seqlens, int32_t n_segments, const uint8_t* h_seg_skip,
+                const uint8_t* d_loss_mask, int32_t n_rows, int32_t row_len,
+                const int32_t* h_pairs, int32_t n_pairs, const float* d_ref_logp, float beta,
+                float* d_stats, float* d_logp,
+                const as_grads* grads, void* d_workspace, size_t workspace_bytes, void* stream);
+
 /* ---- AdamW (Section 4.1 hyper-parameters) -------------------------------- */
 
 /* m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;

@@ -76,6 +76,10 @@ lib.as_pack.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _
                         C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32), _vp, _vp]
 lib.as_train_step.argtypes = [_vp, C.POINTER(Weights), C.POINTER(Lora), _vp, _vp, _vp, _i32, _vp, _vp, _i32, _i32,
                               _vp, _vp, _vp, C.POINTER(Grads), _vp, C.c_size_t, _vp]
+lib.as_sequence_logps.argtypes = [_vp, C.POINTER(Weights), C.POINTER(Lora), _vp, _vp, _vp, _i32, _vp, _vp, _i32, _i32,
+                                  _vp, _vp, C.c_size_t, _vp]
+lib.as_dpo_step.argtypes = [_vp, C.POINTER(Weights), C.POINTER(Lora), _vp, _vp, _vp, _i32, _vp, _vp, _i32, _i32,
+                            _vp, _i32, _vp, _f32, _vp, _vp, C.POINTER(Grads), _vp, C.c_size_t, _vp]
 lib.as_adamw_update.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _f32, _f32, _f32, _f32, _f32, _vp]
 lib.as_op_gemm.argtypes = [_vp, C.c_int, C.c_int, _i64, _i64, _vp, _i64, _vp, _i64, _i64, _vp, _i64, _vp, _i64, _i64,
                            _f32, _vp, _i64, _vp, _i64, C.c_int, _vp]
@@ -93,12 +97,12 @@ lib.as_profile_read.argtypes = [_vp, C.c_int, C.POINTER(_i64), C.POINTER(C.c_dou
 KERNEL_CLASSES = ("gemm_mfma_256", "gemm_mfma_skinny", "gemm_fma", "gemm_devrows", "attn_fwd", "attn_bwd", "transpose",
                   "norm", "swiglu", "rope", "ce", "lora_grad", "gemm_grouped", "moe")
 for _n in ("as_profile", "as_profile_read", "as_create", "as_workspace_bytes", "as_pack", "as_train_step", "as_adamw_update", "as_op_gemm",
-           "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize"):
+           "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step"):
     getattr(lib, _n).restype = C.c_int
 
 EXPORTS = ("as_probe_lds_feed", "as_probe_mfma_peak", "as_profile", "as_profile_read", "as_create", "as_destroy", "as_last_error", "as_workspace_bytes", "as_pack", "as_train_step",
            "as_adamw_update", "as_op_gemm", "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd",
-           "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize")
+           "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step")
 
 
 class ASError(RuntimeError):
@@ -237,6 +241,44 @@ class Context:
                                      hskip.ctypes.data_as(C.c_void_p) if hskip is not None else None, _ptr(loss_mask), n_rows, row_len, _ptr(out["loss"]), _ptr(out["loss_sum"]),
                                      _ptr(out["count"]), C.byref(model.c_grads), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _stream()))
+        return out
+
+    # ------------------------------------------------- preference learning
+    @staticmethod
+    def _skip(seg_skip, hcu):
+        if seg_skip is None:
+            return None, None
+        hskip = np.ascontiguousarray(seg_skip, dtype=np.uint8)
+        assert len(hskip) == len(hcu) - 1
+        return hskip, hskip.ctypes.data_as(C.c_void_p)
+
+    def sequence_logps(self, model, tokens, cu_seqlens, h_cu_seqlens, loss_mask, n_rows, row_len, workspace,
+                       seg_skip=None, adapters=True):
+        """Per-segment sums of log p over the targets (device float [n_segments]); adapters=False: base model."""
+        hcu = np.ascontiguousarray(h_cu_seqlens, dtype=np.int32)
+        hskip, pskip = self._skip(seg_skip, hcu)
+        logp = torch.empty(len(hcu) - 1, dtype=torch.float32, device=tokens.device)
+        lora = C.byref(model.c_lora) if (adapters and model.c_lora is not None) else None
+        self.check(lib.as_sequence_logps(self.handle, C.byref(model.c_weights), lora, _ptr(tokens), _ptr(cu_seqlens),
+                                         hcu.ctypes.data_as(C.c_void_p), len(hcu) - 1, pskip, _ptr(loss_mask), n_rows, row_len,
+                                         _ptr(logp), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+        return logp
+
+    def dpo_step(self, model, tokens, cu_seqlens, h_cu_seqlens, loss_mask, n_rows, row_len, workspace, pairs, ref_logp,
+                 beta, seg_skip=None):
+        """pairs: [P, 2] (chosen, rejected) segment indices.  Returns dict(stats = device float[3]: loss, margin,
+        accuracy; logp = device float [n_segments]); gradients land in the model's gradient buffers."""
+        hcu = np.ascontiguousarray(h_cu_seqlens, dtype=np.int32)
+        hskip, pskip = self._skip(seg_skip, hcu)
+        hp = np.ascontiguousarray(pairs, dtype=np.int32).reshape(-1, 2)
+        out = dict(stats=torch.zeros(3, dtype=torch.float32, device=tokens.device),
+                   logp=torch.empty(len(hcu) - 1, dtype=torch.float32, device=tokens.device))
+        self.check(lib.as_dpo_step(self.handle, C.byref(model.c_weights),
+                                   C.byref(model.c_lora) if model.c_lora is not None else None, _ptr(tokens),
+                                   _ptr(cu_seqlens), hcu.ctypes.data_as(C.c_void_p), len(hcu) - 1, pskip, _ptr(loss_mask),
+                                   n_rows, row_len, hp.ctypes.data_as(C.c_void_p) if len(hp) else None, len(hp), _ptr(ref_logp), beta,
+                                   _ptr(out["stats"]), _ptr(out["logp"]), C.byref(model.c_grads), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream()))
         return out
 
     # ---------------------------------------------------------------- AdamW

@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libactionstudio.so")
-SOURCES = ["api.hip", "elementwise.hip", "gemm.hip", "attention.hip", "attention_mfma.hip", "lora_grad.hip", "moe.hip", "quant.hip"]
+SOURCES = ["api.hip", "elementwise.hip", "gemm.hip", "attention.hip", "attention_mfma.hip", "lora_grad.hip", "moe.hip", "quant.hip", "dpo.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-Wno-unused-command-line-argument"]

@@ -6,6 +6,7 @@
 #include <string.h>
 #include <vector>
 #include <algorithm>
+#include <cmath>
 
 static thread_local std::string g_tls_err;
 
@@ -332,6 +333,7 @@ struct Plan {
   int32_t *tok_c; uint8_t* mask_c;       // tokens and mask with the skipped segments squeezed out
   const int32_t *order_q = nullptr, *order_k = nullptr;   // attention launch orders of this step (longest workgroups first)
   float *rope_cos, *rope_sin, *loss_rows, *rstd_f, *logits, *delta, *partial, *gpart;
+  float *row_w, *w_kept, *logp_ws;       // preference loss: factor of each target row, of each kept segment; log-probability sums when the caller keeps none
   std::vector<void*> h;                  // L+1 residual-stream snapshots
   std::vector<Acts> acts;
   void *hf, *P, *dhf, *headT, *Pt, *hfT;
@@ -391,6 +393,7 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   P.rope_cos = (float*)w.take((size_t)row_len * (c.head_dim / 2) * 4);
   P.rope_sin = (float*)w.take((size_t)row_len * (c.head_dim / 2) * 4);
   P.loss_rows = (float*)w.take(N * 4);
+  P.row_w = (float*)w.take(N * 4); P.w_kept = (float*)w.take(N * 4); P.logp_ws = (float*)w.take(N * 4);
   P.rstd_f = (float*)w.take(N * 4);
   P.h.resize(P.L + 1);
   for (int l = 0; l <= P.L; l++) P.h[l] = w.take(N * P.d * es);
@@ -492,9 +495,24 @@ extern "C" int as_workspace_bytes(const as_ctx* ctx, int64_t max_rows, int64_t r
 
 // ----------------------------------------------------------- training step
 namespace {
+// What the step computes from the per-target losses -log p.
+enum { LOSS_MEAN = 0,      // their mean over the targets (supervised fine-tuning), forward and backward
+       LOSS_SEQ_LOGP = 1,  // per-segment sums pi_s = sum log p, forward only
+       LOSS_DPO = 2 };     // the pair preference loss on those sums against reference sums, forward and backward
+struct LossSpec {
+  int kind = LOSS_MEAN;
+  const int32_t* h_pairs = nullptr; int n_pairs = 0;
+  const float* d_ref_logp = nullptr; float beta = 0.f;
+  float* d_logp = nullptr; float* d_stats = nullptr;
+  // filled by the step
+  const int32_t *d_pairs = nullptr, *d_kept_of = nullptr, *d_cu = nullptr;   // pair table, caller's segment -> kept segment, kept segment table
+  int n_seg = 0, n_kept = 0;
+};
+
 struct Step {
   as_ctx* ctx; const as_model_config& c; Plan& P; hipStream_t st; int mode; int gv; int av;
   const as_weights* W; const as_lora* lora; const as_grads* G; int max_seg;
+  LossSpec LS;
   size_t es() const { return (size_t)P.es; }
   void* off(void* p, size_t elems) const { return (char*)p + elems * es(); }
   const void* off(const void* p, size_t elems) const { return (const char*)p + elems * es(); }
@@ -669,7 +687,10 @@ struct Step {
   // nothing to compute: loss, count and every gradient are exactly zero
   int zero_outputs(float* d_loss, float* d_loss_sum, int32_t* d_count) {
     int rc;
-    if ((rc = launch_fill_zero(ctx, d_loss, 4, st)) || (rc = launch_fill_zero(ctx, d_loss_sum, 4, st)) || (rc = launch_fill_zero(ctx, d_count, 4, st))) return rc;
+    if (d_loss && (rc = launch_fill_zero(ctx, d_loss, 4, st))) return rc;
+    if (d_loss_sum && (rc = launch_fill_zero(ctx, d_loss_sum, 4, st))) return rc;
+    if (d_count && (rc = launch_fill_zero(ctx, d_count, 4, st))) return rc;
+    if (!G) return AS_OK;
     const size_t d = P.d, D = P.D, Dkv = P.Dkv, F = P.F;
     for (int l = 0; l < P.L; l++) {
       if (c.train_mode == AS_LORA) {
@@ -847,11 +868,27 @@ struct Step {
     if ((rc = launch_rmsnorm_fwd(ctx, mode, N, d, P.h[P.L], P.tgt_idx, P.count, W->g_final, c.rms_eps, P.hf, P.rstd_f, st))) return rc;
     if ((rc = transpose(V, d, W->head, d, P.headT, V))) return rc;                     // [d, V]
     const int chunks = (int)cdiv(N, Mc);
+    const float* row_w = nullptr;
+    if (LS.kind != LOSS_MEAN) {
+      // The factor of a target's gradient row depends on the sums over all targets, and the logits are never
+      // kept: a first pass over the head yields the per-target losses only, a second one (below) the gradient.
+      for (int ch = 0; ch < chunks; ch++) {
+        const int r0 = ch * Mc, rows = std::min(Mc, N - r0);
+        if ((rc = gemm(rows, V, off(P.hf, (size_t)r0 * d), d, W->head, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.logits, V, 1, 1.f, 0, P.count, r0))) return rc;
+        if ((rc = launch_ce_rows(ctx, mode, P.logits, rows, V, r0, P.labels, P.count, P.loss_rows, nullptr, nullptr, st))) return rc;
+      }
+      float* logp = LS.d_logp ? LS.d_logp : P.logp_ws;
+      if ((rc = launch_seq_logp(ctx, P.loss_rows, P.tgt_idx, P.count, LS.d_cu, LS.d_kept_of, LS.n_seg, logp, st))) return rc;
+      if (LS.kind == LOSS_SEQ_LOGP) return AS_OK;
+      if ((rc = launch_dpo_pairs(ctx, LS.d_pairs, LS.n_pairs, logp, LS.d_ref_logp, LS.beta, LS.n_seg, LS.d_kept_of, LS.n_kept, P.w_kept, LS.d_stats, st))) return rc;
+      if ((rc = launch_dpo_row_weights(ctx, P.tgt_idx, P.count, LS.d_cu, LS.n_kept, P.w_kept, N, P.row_w, st))) return rc;
+      row_w = P.row_w;
+    }
     for (int ch = 0; ch < chunks; ch++) {
       const int r0 = ch * Mc, rows = std::min(Mc, N - r0);
       const void* hf_c = off(P.hf, (size_t)r0 * d);
       if ((rc = gemm(rows, V, hf_c, d, W->head, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.logits, V, 1, 1.f, 0, P.count, r0))) return rc;
-      if ((rc = launch_ce_rows(ctx, mode, P.logits, rows, V, r0, P.labels, P.count, P.loss_rows, P.P, st))) return rc;
+      if ((rc = launch_ce_rows(ctx, mode, P.logits, rows, V, r0, P.labels, P.count, P.loss_rows, row_w, P.P, st))) return rc;
       if ((rc = gemm(rows, d, P.P, V, P.headT, V, V, nullptr, 0, nullptr, 0, 0, nullptr, 0, off(P.dhf, (size_t)r0 * d), d, 0, 1.f, 0, P.count, r0))) return rc;
       if (full) {
         // dW_head += P_c^T hf_c  (rows past the live count are read as zero)
@@ -862,7 +899,7 @@ struct Step {
         if ((rc = gemm(V, d, P.Pt, Mc, P.hfT, Mc, rows64, nullptr, 0, nullptr, 0, 0, nullptr, 0, G->head, d, 1, 1.f, ch > 0))) return rc;
       }
     }
-    if ((rc = launch_loss_finalize(ctx, P.loss_rows, P.count, d_loss, d_loss_sum, st))) return rc;
+    if (LS.kind == LOSS_MEAN && (rc = launch_loss_finalize(ctx, P.loss_rows, P.count, d_loss, d_loss_sum, st))) return rc;
     // back through the final norm, scattered to all rows (zero where a row is no target)
     if (full && (rc = launch_rmsnorm_dgain(ctx, mode, N, d, P.dhf, P.tgt_pos, P.h[P.L], P.rstd_f, P.gpart, 256, G->g_final, st))) return rc;
     return launch_rmsnorm_bwd(ctx, mode, N, d, P.dhf, P.tgt_pos, P.h[P.L], W->g_final, P.rstd_f, nullptr, P.dh, st);
@@ -910,53 +947,67 @@ static int check_cu(as_ctx* ctx, const int32_t* cu, int32_t S, int64_t N, int32_
   return AS_OK;
 }
 
-extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lora* lora,
-                             const int32_t* d_tokens, const int32_t* d_cu_seqlens,
-                             const int32_t* h_cu_seqlens, int32_t n_segments, const uint8_t* h_seg_skip,
-                             const uint8_t* d_loss_mask, int32_t n_rows, int32_t row_len,
-                             float* d_loss, float* d_loss_sum, int32_t* d_count,
-                             const as_grads* grads, void* d_workspace, size_t workspace_bytes,
-                             void* stream) {
-  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_train_step: NULL context");
+static int run_step(as_ctx* ctx, const char* who, const as_weights* weights, const as_lora* lora,
+                    const int32_t* d_tokens, const int32_t* d_cu_seqlens,
+                    const int32_t* h_cu_seqlens, int32_t n_segments, const uint8_t* h_seg_skip,
+                    const uint8_t* d_loss_mask, int32_t n_rows, int32_t row_len,
+                    float* d_loss, float* d_loss_sum, int32_t* d_count,
+                    const as_grads* grads, void* d_workspace, size_t workspace_bytes,
+                    void* stream, LossSpec LS) {
   const as_model_config& c = ctx->cfg;
   const bool full = c.train_mode == AS_FULL;
   if (!weights || !weights->layers || !weights->embed || !weights->head || !weights->g_final)
-    return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL weights");
-  if (!d_tokens || !d_cu_seqlens || !h_cu_seqlens || !d_loss_mask || !d_loss || !d_loss_sum || !d_count || !grads)
-    return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL argument");
+    return as_fail(ctx, AS_ERR_NULL, "%s: NULL weights", who);
+  const bool fwd_only = LS.kind == LOSS_SEQ_LOGP;
+  const bool adapters_off = fwd_only && !full && !lora;          // log-probabilities of the base model under the adapters
+  if (!d_tokens || !d_cu_seqlens || !h_cu_seqlens || !d_loss_mask || (!fwd_only && !grads))
+    return as_fail(ctx, AS_ERR_NULL, "%s: NULL argument", who);
+  if (LS.kind == LOSS_MEAN && (!d_loss || !d_loss_sum || !d_count)) return as_fail(ctx, AS_ERR_NULL, "%s: NULL output", who);
+  if (LS.kind == LOSS_SEQ_LOGP && !LS.d_logp) return as_fail(ctx, AS_ERR_NULL, "%s: NULL output", who);
+  if (LS.kind == LOSS_DPO) {
+    if (!LS.d_stats || !LS.d_ref_logp || (LS.n_pairs > 0 && !LS.h_pairs)) return as_fail(ctx, AS_ERR_NULL, "%s: NULL argument", who);
+    if (LS.n_pairs < 0 || (int64_t)LS.n_pairs > (int64_t)n_rows * row_len) return as_fail(ctx, AS_ERR_SHAPE, "%s: n_pairs must be in [0, n_rows*row_len]", who);
+    if (!(LS.beta >= 0.f) || !std::isfinite(LS.beta)) return as_fail(ctx, AS_ERR_SHAPE, "%s: beta must be finite and >= 0", who);
+    for (int p = 0; p < LS.n_pairs; p++) {
+      const int a = LS.h_pairs[2 * p], b = LS.h_pairs[2 * p + 1];
+      if (a < 0 || a >= n_segments || b < 0 || b >= n_segments || a == b)
+        return as_fail(ctx, AS_ERR_SHAPE, "%s: pair %d = (%d, %d) must name two different segments in [0, %d)", who, p, a, b, n_segments);
+    }
+  }
   if (n_rows < 1 || row_len < 1 || (int64_t)n_rows * row_len > (int64_t)1 << 30)
-    return as_fail(ctx, AS_ERR_SHAPE, "as_train_step: n_rows*row_len must be in [1, 2^30]");
+    return as_fail(ctx, AS_ERR_SHAPE, "%s: n_rows*row_len must be in [1, 2^30]", who);
   for (int l = 0; l < c.n_layers; l++) {
     const as_layer_weights& w = weights->layers[l];
     if (!w.g1 || !w.wq || !w.wk || !w.wv || !w.wo || !w.g2 || !w.wgate || !w.wup || !w.wdown)
-      return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL weight in layer %d", l);
-    if (c.n_experts && !w.wrouter) return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL router weight in layer %d", l);
+      return as_fail(ctx, AS_ERR_NULL, "%s: NULL weight in layer %d", who, l);
+    if (c.n_experts && !w.wrouter) return as_fail(ctx, AS_ERR_NULL, "%s: NULL router weight in layer %d", who, l);
     if (c.weight_format == AS_W_NF4 && (!w.aq || !w.ak || !w.av || !w.ao || !w.agate || !w.aup || !w.adown))
-      return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL block maxima of an NF4 weight in layer %d", l);
+      return as_fail(ctx, AS_ERR_NULL, "%s: NULL block maxima of an NF4 weight in layer %d", who, l);
   }
-  if (!full) {
-    if (!lora || !lora->layers || !grads->lora_layers) return as_fail(ctx, AS_ERR_NULL, "as_train_step: LoRA mode needs adapters and their gradient buffers");
+  if (!full && !adapters_off) {
+    if (!lora || !lora->layers || (!fwd_only && !grads->lora_layers)) return as_fail(ctx, AS_ERR_NULL, "%s: LoRA mode needs adapters and their gradient buffers", who);
     for (int l = 0; l < c.n_layers; l++)
       for (int t = 0; t < AS_N_TARGETS; t++)
         if ((c.lora_targets >> t) & 1u)
-          if (!lora->layers[l].a[t] || !lora->layers[l].b[t] || !grads->lora_layers[l].a[t] || !grads->lora_layers[l].b[t])
-            return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL adapter or gradient for target %s in layer %d", kTargetName[t], l);
-  } else {
-    if (!grads->w_layers || !grads->embed || !grads->head || !grads->g_final) return as_fail(ctx, AS_ERR_NULL, "as_train_step: full mode needs weight gradient buffers");
+          if (!lora->layers[l].a[t] || !lora->layers[l].b[t] || (!fwd_only && (!grads->lora_layers[l].a[t] || !grads->lora_layers[l].b[t])))
+            return as_fail(ctx, AS_ERR_NULL, "%s: NULL adapter or gradient for target %s in layer %d", who, kTargetName[t], l);
+  } else if (full && !fwd_only) {
+    if (!grads->w_layers || !grads->embed || !grads->head || !grads->g_final) return as_fail(ctx, AS_ERR_NULL, "%s: full mode needs weight gradient buffers", who);
     for (int l = 0; l < c.n_layers; l++) {
       const as_layer_weight_grads& g = grads->w_layers[l];
       if (!g.g1 || !g.wq || !g.wk || !g.wv || !g.wo || !g.g2 || !g.wgate || !g.wup || !g.wdown)
-        return as_fail(ctx, AS_ERR_NULL, "as_train_step: NULL weight gradient in layer %d", l);
+        return as_fail(ctx, AS_ERR_NULL, "%s: NULL weight gradient in layer %d", who, l);
     }
   }
   const int64_t N = (int64_t)n_rows * row_len;
   int max_seg = 0;
   int rc = check_cu(ctx, h_cu_seqlens, n_segments, N, row_len, &max_seg);
   if (rc) return rc;
-  if (!d_workspace || ((uintptr_t)d_workspace & 255)) return as_fail(ctx, AS_ERR_WORKSPACE, "as_train_step: workspace must be non-NULL and 256-byte aligned");
+  if (!d_workspace || ((uintptr_t)d_workspace & 255)) return as_fail(ctx, AS_ERR_WORKSPACE, "%s: workspace must be non-NULL and 256-byte aligned", who);
   Bump wsp{(char*)d_workspace, 0}; Plan P;
   make_plan(ctx, n_rows, row_len, wsp, P);
-  if (wsp.off > workspace_bytes) return as_fail(ctx, AS_ERR_WORKSPACE, "as_train_step: workspace has %zu bytes, %zu needed", workspace_bytes, wsp.off);
+  if (adapters_off) { P.n_qkv = P.n_gu = 0; for (LoraSlot& sl : P.lora) sl.on = false; }
+  if (wsp.off > workspace_bytes) return as_fail(ctx, AS_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", who, workspace_bytes, wsp.off);
 
   hipStream_t st = (hipStream_t)stream;
   AS_HIP(ctx, hipSetDevice(ctx->device));
@@ -986,8 +1037,9 @@ extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lo
   // inside a segment, the long workgroups first: neighbours in the order then share their operand tiles in
   // the L2 of the XCD they run on, and the launch ends on the short workgroups of the short segments.
   const bool orders = c.mode == AS_BF16 && (c.head_dim == 64 || c.head_dim == 128) && n > 0;
-  if (n_seg_eff > 0 && (compact || orders)) {
-    std::vector<int32_t> tab = cu_h;                       // [cu (S'+1) | src_start (S') | order_q | order_k]
+  const bool seq = LS.kind != LOSS_MEAN;
+  if (seq || (n_seg_eff > 0 && (compact || orders))) {
+    std::vector<int32_t> tab = cu_h;                       // [cu (S'+1) | src_start (S') | order_q | order_k | kept_of (S) | pairs (2P)]
     tab.insert(tab.end(), src.begin(), src.end());
     size_t off_q = 0, off_k = 0;
     if (orders) {
@@ -1007,9 +1059,17 @@ extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lo
       off_q = tab.size(); tab.insert(tab.end(), oq.begin(), oq.end());
       off_k = tab.size(); tab.insert(tab.end(), ok.begin(), ok.end());
     }
+    size_t off_kept = 0, off_pairs = 0;
+    if (seq) {
+      off_kept = tab.size();
+      for (int s = 0, k = 0; s < n_segments; s++) tab.push_back(compact && h_seg_skip[s] ? -1 : k++);
+      off_pairs = tab.size();
+      if (LS.n_pairs > 0) tab.insert(tab.end(), LS.h_pairs, LS.h_pairs + 2 * (size_t)LS.n_pairs);
+    }
     rc = stage_step_table(ctx, tab.data(), tab.size() * 4, st);
     if (rc) return rc;
     const int32_t* d_tab = (const int32_t*)ctx->d_step;
+    if (seq) { LS.d_cu = d_tab; LS.d_kept_of = d_tab + off_kept; LS.d_pairs = d_tab + off_pairs; LS.n_seg = n_segments; LS.n_kept = n_seg_eff; }
     if (compact) {
       if ((rc = launch_compact(ctx, d_tokens, d_loss_mask, d_tab, d_tab + n_seg_eff + 1, n_seg_eff, n, P.tok_c, P.mask_c, st))) return rc;
       d_tokens = P.tok_c; d_loss_mask = P.mask_c; d_cu_eff = d_tab;
@@ -1017,17 +1077,28 @@ extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lo
     if (orders) { P.order_q = d_tab + off_q; P.order_k = d_tab + off_k; }
   }
   P.N = n; P.Np = (int)cdiv(n, 64) * 64;
-  Step S{ctx, c, P, st, c.mode, 0, 0, weights, lora, grads, max_seg};
-  if (n == 0) return S.zero_outputs(d_loss, d_loss_sum, d_count);
+  if (seq) d_count = P.count;
+  Step S{ctx, c, P, st, c.mode, 0, 0, weights, lora, fwd_only ? nullptr : grads, max_seg, LS};
+  if (n == 0) {
+    // nothing to differentiate: every sum is empty (log-probability 0), the pair loss follows from the references alone
+    if (seq) {
+      float* logp = LS.d_logp ? LS.d_logp : P.logp_ws;
+      if ((rc = launch_fill_float(ctx, logp, n_segments, 0.f, st))) return rc;
+      if (LS.kind == LOSS_DPO && (rc = launch_dpo_pairs(ctx, LS.d_pairs, LS.n_pairs, logp, LS.d_ref_logp, LS.beta, n_segments, LS.d_kept_of, 0, P.w_kept, LS.d_stats, st))) return rc;
+      return S.zero_outputs(nullptr, nullptr, nullptr);
+    }
+    return S.zero_outputs(d_loss, d_loss_sum, d_count);
+  }
   if ((rc = launch_segment_info(ctx, d_cu_eff, n_seg_eff, n, P.seg_start, P.seg_end, st))) return rc;
   if ((rc = launch_rope_table(ctx, max_seg, c.head_dim, c.rope_base, P.rope_cos, P.rope_sin, st))) return rc;
   if ((rc = launch_select_targets(ctx, P.seg_start, d_loss_mask, d_tokens, n, P.tgt_idx, P.tgt_pos, P.labels, d_count, st))) return rc;
   P.count = d_count;
-  if (!full) for (int l = 0; l < c.n_layers; l++) if ((rc = S.prep_lora(l))) return rc;
+  if (!full && !adapters_off) for (int l = 0; l < c.n_layers; l++) if ((rc = S.prep_lora(l))) return rc;
   if ((rc = launch_embed(ctx, c.mode, d_tokens, n, c.d_model, weights->embed, P.h[0], st))) return rc;
   for (int l = 0; l < c.n_layers; l++)
     if ((rc = S.forward_layer(l, P.acts[c.recompute == 1 ? 0 : l]))) return rc;
   if ((rc = S.head_and_loss(d_loss, d_loss_sum))) return rc;
+  if (fwd_only) return S.wq_rc;
   for (int l = c.n_layers - 1; l >= 0; l--) {
     Acts& a = P.acts[c.recompute == 1 ? 0 : l];
     if (c.recompute == 1 && l != c.n_layers - 1 && (rc = S.forward_layer(l, a))) return rc;   // re-run the layer from its saved input
@@ -1036,6 +1107,43 @@ extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lo
   }
   if (full && (rc = launch_embed_bwd(ctx, c.mode, d_tokens, n, c.d_model, c.vocab, P.dh, P.iscratch, grads->embed, st))) return rc;
   return S.wq_rc;
+}
+
+extern "C" int as_train_step(as_ctx* ctx, const as_weights* weights, const as_lora* lora,
+                             const int32_t* d_tokens, const int32_t* d_cu_seqlens,
+                             const int32_t* h_cu_seqlens, int32_t n_segments, const uint8_t* h_seg_skip,
+                             const uint8_t* d_loss_mask, int32_t n_rows, int32_t row_len,
+                             float* d_loss, float* d_loss_sum, int32_t* d_count,
+                             const as_grads* grads, void* d_workspace, size_t workspace_bytes,
+                             void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_train_step: NULL context");
+  return run_step(ctx, "as_train_step", weights, lora, d_tokens, d_cu_seqlens, h_cu_seqlens, n_segments, h_seg_skip, d_loss_mask,
+                  n_rows, row_len, d_loss, d_loss_sum, d_count, grads, d_workspace, workspace_bytes, stream, LossSpec());
+}
+
+extern "C" int as_sequence_logps(as_ctx* ctx, const as_weights* weights, const as_lora* lora,
+                                 const int32_t* d_tokens, const int32_t* d_cu_seqlens,
+                                 const int32_t* h_cu_seqlens, int32_t n_segments, const uint8_t* h_seg_skip,
+                                 const uint8_t* d_loss_mask, int32_t n_rows, int32_t row_len,
+                                 float* d_logp, void* d_workspace, size_t workspace_bytes, void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_sequence_logps: NULL context");
+  LossSpec LS; LS.kind = LOSS_SEQ_LOGP; LS.d_logp = d_logp;
+  return run_step(ctx, "as_sequence_logps", weights, lora, d_tokens, d_cu_seqlens, h_cu_seqlens, n_segments, h_seg_skip, d_loss_mask,
+                  n_rows, row_len, nullptr, nullptr, nullptr, nullptr, d_workspace, workspace_bytes, stream, LS);
+}
+
+extern "C" int as_dpo_step(as_ctx* ctx, const as_weights* weights, const as_lora* lora,
+                           const int32_t* d_tokens, const int32_t* d_cu_seqlens,
+                           const int32_t* h_cu_seqlens, int32_t n_segments, const uint8_t* h_seg_skip,
+                           const uint8_t* d_loss_mask, int32_t n_rows, int32_t row_len,
+                           const int32_t* h_pairs, int32_t n_pairs, const float* d_ref_logp, float beta,
+                           float* d_stats, float* d_logp,
+                           const as_grads* grads, void* d_workspace, size_t workspace_bytes, void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_dpo_step: NULL context");
+  LossSpec LS; LS.kind = LOSS_DPO; LS.h_pairs = h_pairs; LS.n_pairs = n_pairs; LS.d_ref_logp = d_ref_logp; LS.beta = beta;
+  LS.d_stats = d_stats; LS.d_logp = d_logp;
+  return run_step(ctx, "as_dpo_step", weights, lora, d_tokens, d_cu_seqlens, h_cu_seqlens, n_segments, h_seg_skip, d_loss_mask,
+                  n_rows, row_len, nullptr, nullptr, nullptr, grads, d_workspace, workspace_bytes, stream, LS);
 }
 
 // -------------------------------------------------------------------- AdamW

@@ -163,7 +163,15 @@ int launch_select_targets(as_ctx* ctx, const int32_t* seg_start, const uint8_t* 
                           hipStream_t st);
 // one row of logits per target: loss_t, and P = (softmax - onehot) / count written as T
 int launch_ce_rows(as_ctx* ctx, int mode, const float* logits, int rows_cap, int V, int row0,
-                   const int32_t* labels, const int32_t* count, float* loss_rows, void* P, hipStream_t st);
+                   const int32_t* labels, const int32_t* count, float* loss_rows, const float* row_w, void* P, hipStream_t st);
+// preference loss (dpo.hip)
+int launch_seq_logp(as_ctx* ctx, const float* loss_rows, const int32_t* tgt_idx, const int32_t* count, const int32_t* cu,
+                    const int32_t* kept_of, int n_seg, float* logp, hipStream_t st);
+int launch_dpo_pairs(as_ctx* ctx, const int32_t* pairs, int n_pairs, const float* logp, const float* ref, float beta, int n_seg,
+                     const int32_t* kept_of, int n_kept, float* w_kept, float* stats, hipStream_t st);
+int launch_dpo_row_weights(as_ctx* ctx, const int32_t* tgt_idx, const int32_t* count, const int32_t* cu, int n_kept,
+                           const float* w_kept, int n, float* row_w, hipStream_t st);
+int launch_fill_float(as_ctx* ctx, float* p, int n, float v, hipStream_t st);
 int launch_loss_finalize(as_ctx* ctx, const float* loss_rows, const int32_t* count, float* loss,
                          float* loss_sum, hipStream_t st);
 int launch_splitk_reduce(as_ctx* ctx, const float* partial, int splitk, int64_t mn, int N, float alpha,

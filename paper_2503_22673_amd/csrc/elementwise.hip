@@ -628,10 +628,12 @@ __device__ __forceinline__ float block_reduce(float v, float* sh, bool is_max) {
 }
 
 // One block per target row of a chunk: logsumexp, the row's loss, and the
-// gradient with respect to the logits, already divided by the target count.
+// gradient with respect to the logits: (softmax - one-hot) times the row's factor,
+// row_w[row] when given, else 1 / target count (the mean loss).  P == nullptr: losses only.
 template <typename T>
 __global__ void ce_rows_kernel(const float* __restrict__ logits, int V, int row0, const int32_t* __restrict__ labels,
-                               const int32_t* __restrict__ count, float* __restrict__ loss_rows, T* __restrict__ P) {
+                               const int32_t* __restrict__ count, float* __restrict__ loss_rows,
+                               const float* __restrict__ row_w, T* __restrict__ P) {
   __shared__ float sh[16];
   int cnt = *count;
   int row = row0 + blockIdx.x;
@@ -646,8 +648,9 @@ __global__ void ce_rows_kernel(const float* __restrict__ logits, int V, int row0
   s = block_reduce(s, sh, false);
   float lse = mx + logf(s);
   int y = labels[row];
-  if (threadIdx.x == 0) loss_rows[row] = lse - z[y];
-  float inv = 1.f / (float)cnt;
+  if (threadIdx.x == 0 && loss_rows) loss_rows[row] = lse - z[y];
+  if (!P) return;
+  float inv = row_w ? row_w[row] : 1.f / (float)cnt;
   for (int v = threadIdx.x; v < V; v += blockDim.x) {
     float g = expf(z[v] - lse) - (v == y ? 1.f : 0.f);
     p[v] = from_f<T>(g * inv);
@@ -655,10 +658,10 @@ __global__ void ce_rows_kernel(const float* __restrict__ logits, int V, int row0
 }
 
 int launch_ce_rows(as_ctx* ctx, int mode, const float* logits, int rows_cap, int V, int row0,
-                   const int32_t* labels, const int32_t* count, float* loss_rows, void* P, hipStream_t st) {
+                   const int32_t* labels, const int32_t* count, float* loss_rows, const float* row_w, void* P, hipStream_t st) {
   if (rows_cap <= 0) return AS_OK;
   prof_begin(ctx, st, AS_K_CE, 0.0);
-  DISPATCH_T(mode, (ce_rows_kernel<T><<<rows_cap, 512, 0, st>>>(logits, V, row0, labels, count, loss_rows, (T*)P)));
+  DISPATCH_T(mode, (ce_rows_kernel<T><<<rows_cap, 512, 0, st>>>(logits, V, row0, labels, count, loss_rows, row_w, (T*)P)));
   prof_end(ctx, st);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;

@@ -130,3 +130,114 @@ def test_synthetic_recipes_have_the_stated_structure():
     nonpad = sum(sum(len(t) for _, t in x) for x in tr)
     assert 0.15 < r["loss_mask"].sum() / nonpad < 0.35
     assert r["tokens"].max() < 32000
+
+
+# ------------------------------------------------- best-fit decreasing
+
+def _bfd_trajs(lens, base=10):
+    """trajectory i: tokens base*i+1 .., the last one an assistant token"""
+    return [[(U, [base * i + k + 1 for k in range(L - 1)]), (A, [base * i + L])] if L > 1 else
+            ([[(A, [base * i + 1])]] if L == 1 else [[(U, [])]])[0] for i, L in enumerate(lens)]
+
+
+def test_best_fit_decreasing_hand_worked_example():
+    gold = _parse_golden(os.path.join(GOLD, "pack_bfd_example.txt"))
+    r = oracle.pack(_bfd_trajs([5, 7, 5, 2, 4, 2, 5, 1, 6]), 10, 4, pad_id=99, policy="best_fit_decreasing")
+    assert r["traj_row"].tolist() == gold["traj_row"]
+    assert r["tokens"].tolist() == gold["tokens"]
+    assert r["loss_mask"].tolist() == gold["loss_mask"]
+    assert r["cu_seqlens"].tolist() == gold["cu_seqlens"]
+    assert [r["n_rows"], r["n_segments"], r["n_traj_consumed"]] == gold["rows_segments_consumed"]
+
+
+def _check_bfd_definition(lens, T, max_rows, traj_row):
+    """Checks a placement against the definition without rebuilding it: replays the sorted order and, for
+    every trajectory, compares the row it got with every alternative that was open at that moment."""
+    order = sorted([i for i, L in enumerate(lens) if L > 0], key=lambda i: (-min(lens[i], T), i))
+    free, opened = {}, 0
+    for i in order:
+        L, r = min(lens[i], T), traj_row[i]
+        fits = [k for k in range(opened) if free[k] >= L]
+        if r == -1:
+            assert not fits and opened == max_rows, (i, "left out although there was room")
+            continue
+        if fits:
+            assert r in fits, (i, "opened a row although one had room")
+            assert all(free[r] < free[k] or (free[r] == free[k] and r <= k) for k in fits), (i, "not the best fit")
+        else:
+            assert r == opened and opened < max_rows, (i, "rows are opened in order")
+            free[r] = T; opened += 1
+        free[r] -= L
+    assert all(v >= 0 for v in free.values())
+    return opened
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_best_fit_decreasing_matches_its_definition_and_keeps_the_content(seed):
+    T, PAD = 50, 49
+    trajs = random_trajs(seed, 30, vocab=49, turn_lo=0, turn_hi=9)
+    lens = [sum(len(t) for _, t in tr) for tr in trajs]
+    max_rows = 100 if seed % 2 == 0 else 6                     # odd seeds: not everything fits
+    r = oracle.pack(trajs, T, max_rows, pad_id=PAD, policy="best_fit_decreasing")
+    rows = _check_bfd_definition(lens, T, max_rows, r["traj_row"].tolist())
+    assert rows == r["n_rows"] <= max_rows
+    if max_rows == 6:
+        assert (r["traj_row"] == -1).any()
+    cu, tok, m = r["cu_seqlens"], r["tokens"], r["loss_mask"]
+    assert cu[0] == 0 and cu[-1] == r["n_rows"] * T and np.all(np.diff(cu) > 0)
+    for k in range(r["n_rows"] + 1):
+        assert k * T in cu
+    # every placed trajectory is one segment holding exactly its tokens and mask, inside its row
+    segs = {(int(a), int(b)) for a, b in zip(cu[:-1], cu[1:])}
+    placed = [i for i in range(len(trajs)) if r["traj_row"][i] >= 0]
+    used = 0
+    for i in placed:
+        flat = [int(x) for _, t in trajs[i] for x in t]
+        msk = [1 if ro == A else 0 for ro, t in trajs[i] for _ in t]
+        row = int(r["traj_row"][i])
+        hits = [(a, b) for a, b in segs if b - a == len(flat) and a // T == row and tok[a:b].tolist() == flat and m[a:b].tolist() == msk]
+        assert hits, i
+        used += len(flat)
+    assert int((tok != PAD).sum()) == used and np.all(m[tok == PAD] == 0)
+    assert r["n_traj_consumed"] == len(placed) + sum(1 for L in lens if L == 0)
+    assert all(r["traj_row"][i] == -2 for i, L in enumerate(lens) if L == 0)
+
+
+def test_best_fit_decreasing_special_cases():
+    # equal lengths: floor(T / L) per row, the first ones by input order are placed
+    r = oracle.pack(_bfd_trajs([3] * 10), 10, 2, policy="best_fit_decreasing")
+    assert r["traj_row"].tolist() == [0, 0, 0, 1, 1, 1, -1, -1, -1, -1] and r["n_rows"] == 2
+    # a perfect partition that next-fit misses: 6 4 6 4 -> two full rows instead of three
+    lens = [6, 6, 4, 4]
+    assert oracle.pack(_bfd_trajs(lens), 10, 9, policy="best_fit_decreasing")["n_rows"] == 2
+    assert oracle.pack(_bfd_trajs(lens), 10, 9)["n_rows"] == 3
+    # over-long trajectories are cut to a full row (or refused), empty ones leave no trace
+    r = oracle.pack(_bfd_trajs([25, 0, 4], base=30), 10, 9, policy="best_fit_decreasing")
+    assert r["traj_row"].tolist() == [0, -2, 1] and r["tokens"][:10].tolist() == list(range(1, 11))
+    with pytest.raises(oracle.PackError):
+        oracle.pack(_bfd_trajs([25], base=30), 10, 9, truncate=False, policy="best_fit_decreasing")
+    r = oracle.pack([], 10, 3, policy="best_fit_decreasing")
+    assert r["n_rows"] == 0 and r["cu_seqlens"].tolist() == [0]
+    with pytest.raises(oracle.PackError):
+        oracle.pack([], 10, 3, policy="first_fit")
+
+
+def test_best_fit_decreasing_never_needs_fewer_rows_than_the_optimum_and_is_close():
+    """Brute force over all assignments on tiny inputs: the heuristic is valid (>= optimum) and within the
+    classical 11/9 OPT + 1 on these sizes."""
+    import itertools
+    rs = np.random.default_rng(4)
+    for _ in range(40):
+        n = int(rs.integers(3, 8)); T = 10
+        lens = [int(x) for x in rs.integers(1, 8, size=n)]
+        best = n
+        for assign in itertools.product(range(n), repeat=n):
+            if max(assign) + 1 >= best:
+                continue
+            load = [0] * n
+            for L, a in zip(lens, assign):
+                load[a] += L
+            if max(load) <= T:
+                best = min(best, len(set(assign)))
+        got = oracle.pack(_bfd_trajs(lens), T, n, policy="best_fit_decreasing")["n_rows"]
+        assert best <= got <= 11 * best / 9 + 1, (lens, best, got)

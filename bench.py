@@ -156,6 +156,8 @@ def main():
     ap.add_argument("--nf4", action="store_true", help="frozen base held as NF4 blocks (quantised base + LoRA)")
     ap.add_argument("--single-trajectory", action="store_true",
                     help="long-context stress: every row is ONE trajectory of row_len tokens")
+    ap.add_argument("--bfd", action="store_true",
+                    help="pack the rows by best fit decreasing from a pool three times the batch (as_pack_policy)")
     ap.add_argument("--dpo", action="store_true",
                     help="preference step instead of the supervised one: reference pass with the adapters off + "
                          "DPO step, consecutive trajectories paired as (chosen, rejected)")
@@ -186,16 +188,16 @@ def main():
         trajs = synth.trajectories_lognormal(args.seed, sh.rows, sh.row_len, sh.vocab, sh.row_len, 0.0, sh.row_len, sh.row_len,
                                              turns=(8, 12), assistant_share=0.2)
     else:
-        trajs = synth.workload(args.config, seed=args.seed, rows=sh.rows, row_len=sh.row_len)
+        trajs = synth.workload(args.config, seed=args.seed, rows=(3 if args.bfd else 1) * sh.rows, row_len=sh.row_len)
     flat = synth.flatten_trajectories(trajs)
     t0 = time.perf_counter()
-    pk = ctx.pack(*flat, sh.row_len, sh.rows)
+    pk = ctx.pack(*flat, sh.row_len, sh.rows, policy=B.AS_PACK_BEST_FIT_DECREASING if args.bfd else None)
     torch.cuda.synchronize()
     pack_ms = (time.perf_counter() - t0) * 1e3
     assert pk["n_rows"] == sh.rows, pk["n_rows"]
     hcu = pk["cu_seqlens"].cpu().numpy()
     tok_h = pk["tokens"].cpu().numpy()
-    consumed = trajs[:pk["n_traj_consumed"]]
+    consumed = trajs[:pk["n_traj_consumed"]] if not args.bfd else [tr for tr, r in zip(trajs, pk["traj_row"]) if r >= 0]
     seg_nonpad = [min(sum(len(t) for _, t in tr), sh.row_len) for tr in consumed if sum(len(t) for _, t in tr) > 0]
     n_nonpad = int(sum(seg_nonpad))
     N = sh.rows * sh.row_len
@@ -285,10 +287,10 @@ def main():
 
     rec = {
         "metric": "trained tokens/s per MI355X (LoRA step, 8B shapes, 16k packed); % bf16 MFMA peak"
-                  if args.config == 3 and not (args.rows or args.row_len or args.single_trajectory or args.layers or args.nf4 or args.dpo) else
+                  if args.config == 3 and not (args.rows or args.row_len or args.single_trajectory or args.layers or args.nf4 or args.dpo or args.bfd) else
                   "trained tokens/s per MI355X (one fine-tuning step, config %d%s)" % (
                       args.config, ", rows/row_len overridden" if (args.rows or args.row_len or args.single_trajectory) else "") +
-                  (", NF4 base" if args.nf4 else "") + (", DPO step incl. reference pass" if args.dpo else ""),
+                  (", NF4 base" if args.nf4 else "") + (", DPO step incl. reference pass" if args.dpo else "") + (", rows packed by best fit decreasing" if args.bfd else ""),
         "value": round(tokens_per_s, 1), "unit": "trained tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 2), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if sh.bf16 else "f32", "data": "synthetic",
@@ -306,7 +308,7 @@ def main():
                                                   " (projection GEMMs forward + dX, LoRA term as second K segment)"),
                      "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None if (sh.n_experts or args.rows or args.row_len or args.single_trajectory or args.nf4 or args.dpo) else
+                     "traffic": None if (sh.n_experts or args.rows or args.row_len or args.single_trajectory or args.nf4 or args.dpo or args.bfd) else
                                 TRAFFIC_BYTES_PER_LAUNCH.get((args.config, DOMINANT_KERNEL)),
                      "traffic_unit": "HBM-side bytes per launch (counters)",
                      "launches_per_step": n_l // max(args.steps, 1), "avg_launch_ms": round(ms_l / max(n_l, 1), 4)},

@@ -211,6 +211,24 @@ int as_pack(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* turn_offsets
             int32_t* n_rows_out, int32_t* n_segments_out, int32_t* n_traj_consumed_out,
             uint8_t* h_seg_skip_out, void* stream);
 
+/* The same with a choice of packing policy (the paper does not fix one).
+ *  AS_PACK_NEXT_FIT: the policy of as_pack.
+ *  AS_PACK_BEST_FIT_DECREASING: for a pool of trajectories larger than one batch.  All trajectories
+ *   are validated; the non-empty ones (cut to row_len first, or AS_ERR_TOO_LONG) are taken by
+ *   non-increasing length, ties in input order; each goes to the open row that it fills best (least
+ *   free space left, ties to the lowest row); a new row is opened only when no open row has room;
+ *   with max_rows rows open and no room the trajectory is left out.  Rows are written in row
+ *   order, the trajectories of a row in the order they were placed.
+ *  h_traj_row_out [host] int32 [n_traj] or NULL: row of each trajectory, -1 = not placed (offer it
+ *   again), -2 = empty.  *n_traj_consumed_out counts placed + empty trajectories. */
+enum { AS_PACK_NEXT_FIT = 0, AS_PACK_BEST_FIT_DECREASING = 1 };
+int as_pack_policy(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* turn_offsets,
+                   const uint8_t* turn_roles, const int32_t* traj_offsets, int32_t n_traj,
+                   int32_t row_len, int32_t max_rows, int32_t pad_id, int32_t truncate, int32_t policy,
+                   int32_t* d_tokens, int32_t* d_cu_seqlens, uint8_t* d_loss_mask,
+                   int32_t* n_rows_out, int32_t* n_segments_out, int32_t* n_traj_consumed_out,
+                   uint8_t* h_seg_skip_out, int32_t* h_traj_row_out, void* stream);
+
 /* ---- one training step (Sections 3.2.2, 4.5) ---------------------------- */
 
 /* Forward and backward of the masked next-token loss over n_rows*row_len

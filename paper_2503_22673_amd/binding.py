@@ -27,6 +27,7 @@ _WFIELDS = ("g1", "wq", "wk", "wv", "wo", "g2", "wgate", "wup", "wdown", "wroute
 _AFIELDS = ("aq", "ak", "av", "ao", "agate", "aup", "adown")      # NF4 block maxima of wq .. wdown
 _QUANT = dict(zip(("wq", "wk", "wv", "wo", "wgate", "wup", "wdown"), _AFIELDS))
 AS_W_DENSE, AS_W_NF4 = 0, 1
+AS_PACK_NEXT_FIT, AS_PACK_BEST_FIT_DECREASING = 0, 1
 
 
 class ModelConfig(C.Structure):
@@ -74,6 +75,8 @@ lib.as_last_error.restype = C.c_char_p
 lib.as_workspace_bytes.argtypes = [_vp, _i64, _i64, C.POINTER(C.c_size_t)]
 lib.as_pack.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp,
                         C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32), _vp, _vp]
+lib.as_pack_policy.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp,
+                               C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32), _vp, _vp, _vp]
 lib.as_train_step.argtypes = [_vp, C.POINTER(Weights), C.POINTER(Lora), _vp, _vp, _vp, _i32, _vp, _vp, _i32, _i32,
                               _vp, _vp, _vp, C.POINTER(Grads), _vp, C.c_size_t, _vp]
 lib.as_sequence_logps.argtypes = [_vp, C.POINTER(Weights), C.POINTER(Lora), _vp, _vp, _vp, _i32, _vp, _vp, _i32, _i32,
@@ -97,12 +100,12 @@ lib.as_profile_read.argtypes = [_vp, C.c_int, C.POINTER(_i64), C.POINTER(C.c_dou
 KERNEL_CLASSES = ("gemm_mfma_256", "gemm_mfma_skinny", "gemm_fma", "gemm_devrows", "attn_fwd", "attn_bwd", "transpose",
                   "norm", "swiglu", "rope", "ce", "lora_grad", "gemm_grouped", "moe")
 for _n in ("as_profile", "as_profile_read", "as_create", "as_workspace_bytes", "as_pack", "as_train_step", "as_adamw_update", "as_op_gemm",
-           "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step"):
+           "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy"):
     getattr(lib, _n).restype = C.c_int
 
 EXPORTS = ("as_probe_lds_feed", "as_probe_mfma_peak", "as_profile", "as_profile_read", "as_create", "as_destroy", "as_last_error", "as_workspace_bytes", "as_pack", "as_train_step",
            "as_adamw_update", "as_op_gemm", "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd",
-           "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step")
+           "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy")
 
 
 class ASError(RuntimeError):
@@ -197,8 +200,9 @@ class Context:
 
     # ---------------------------------------------------------------- pack
     def pack(self, turn_tokens, turn_offsets, turn_roles, traj_offsets, row_len, max_rows, pad_id=0,
-             truncate=True, outputs=None):
-        """Host numpy arrays in; device tensors (tokens, cu_seqlens, loss_mask) out."""
+             truncate=True, outputs=None, policy=None):
+        """Host numpy arrays in; device tensors (tokens, cu_seqlens, loss_mask) out.  policy None: as_pack (next
+        fit); AS_PACK_NEXT_FIT / AS_PACK_BEST_FIT_DECREASING: as_pack_policy, which also reports traj_row."""
         tt = np.ascontiguousarray(turn_tokens, dtype=np.int32)
         to = np.ascontiguousarray(turn_offsets, dtype=np.int32)
         tr = np.ascontiguousarray(turn_roles, dtype=np.uint8)
@@ -214,12 +218,21 @@ class Context:
         nr, ns, nc = _i32(), _i32(), _i32()
         skip = np.zeros(max(1, n_traj + max(max_rows, 0)), dtype=np.uint8)
         hp = lambda a: a.ctypes.data_as(C.c_void_p) if a.size else None
-        self.check(lib.as_pack(self.handle, hp(tt), hp(to), hp(tr), hp(jo), n_traj, row_len, max_rows, pad_id,
-                               int(truncate), _ptr(tok), _ptr(cu), _ptr(msk), C.byref(nr), C.byref(ns), C.byref(nc),
-                               hp(skip), _stream() if tok is not None and tok.is_cuda else None))
+        st = _stream() if tok is not None and tok.is_cuda else None
+        traj_row = None
+        if policy is None:
+            self.check(lib.as_pack(self.handle, hp(tt), hp(to), hp(tr), hp(jo), n_traj, row_len, max_rows, pad_id,
+                                   int(truncate), _ptr(tok), _ptr(cu), _ptr(msk), C.byref(nr), C.byref(ns), C.byref(nc),
+                                   hp(skip), st))
+        else:
+            traj_row = np.full(max(1, n_traj), -1, dtype=np.int32)
+            self.check(lib.as_pack_policy(self.handle, hp(tt), hp(to), hp(tr), hp(jo), n_traj, row_len, max_rows, pad_id,
+                                          int(truncate), int(policy), _ptr(tok), _ptr(cu), _ptr(msk), C.byref(nr), C.byref(ns),
+                                          C.byref(nc), hp(skip), hp(traj_row), st))
+            traj_row = traj_row[:n_traj]
         n = nr.value * row_len
         return dict(tokens=tok[:n], cu_seqlens=cu[:ns.value + 1], loss_mask=msk[:n], n_rows=nr.value,
-                    n_segments=ns.value, n_traj_consumed=nc.value, seg_skip=skip[:ns.value].copy())
+                    n_segments=ns.value, n_traj_consumed=nc.value, seg_skip=skip[:ns.value].copy(), traj_row=traj_row)
 
     # ----------------------------------------------------------- train step
     def train_step(self, model, tokens, cu_seqlens, h_cu_seqlens, loss_mask, n_rows, row_len, workspace, out=None,

@@ -192,10 +192,12 @@ static int ensure_stage(as_ctx* ctx, size_t bytes) {
 // segment table.  Touches no GPU state, so it can be tested without one.
 static int pack_plan(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* turn_offsets,
                      const uint8_t* turn_roles, const int32_t* traj_offsets, int32_t n_traj,
-                     int32_t T, int32_t max_rows, int32_t truncate, std::vector<Piece>& pieces,
-                     std::vector<int32_t>& cu, std::vector<uint8_t>& skip, int32_t* n_rows, int32_t* n_consumed) {
+                     int32_t T, int32_t max_rows, int32_t truncate, int32_t policy, std::vector<Piece>& pieces,
+                     std::vector<int32_t>& cu, std::vector<uint8_t>& skip, int32_t* n_rows, int32_t* n_consumed,
+                     int32_t* traj_row) {
   const int vocab = ctx->cfg.vocab;
   if (T <= 0 || max_rows < 0 || n_traj < 0) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: row_len must be positive, counts non-negative");
+  if (policy != AS_PACK_NEXT_FIT && policy != AS_PACK_BEST_FIT_DECREASING) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: unknown policy %d", policy);
   if ((int64_t)T * max_rows > INT32_MAX) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: max_rows*row_len exceeds int32");
   if (traj_offsets[0] != 0 || turn_offsets[0] != 0) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: offsets must start at 0");
   // both offset tables are checked in full before any token is read: the last turn offset is the
@@ -205,53 +207,96 @@ static int pack_plan(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* tur
   for (int32_t t = 0, nt = traj_offsets[n_traj]; t < nt; t++)
     if (turn_offsets[t + 1] < turn_offsets[t]) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: turn_offsets must not decrease (turn %d)", t);
   pieces.clear(); cu.clear(); cu.push_back(0); skip.clear();
-  int32_t fill = 0, rows = 0, consumed = 0; bool open = false;
-  auto close_row = [&]() {
-    if (fill < T) { pieces.push_back({rows * T + fill, -1, 0}); cu.push_back((rows + 1) * T); skip.push_back(1); }
-    rows++; fill = 0; open = false;
-  };
-  for (int32_t i = 0; i < n_traj && rows < max_rows; i++) {
-    int32_t t0 = traj_offsets[i], t1 = traj_offsets[i + 1];
-    if (t1 < t0) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: traj_offsets must not decrease (trajectory %d)", i);
+  // roles and token ids of trajectory i, and its length cut to a row
+  auto measure = [&](int32_t i, int32_t* len) -> int {
     int64_t L = 0;
-    for (int32_t t = t0; t < t1; t++) {
-      if (turn_offsets[t + 1] < turn_offsets[t]) return as_fail(ctx, AS_ERR_SHAPE, "as_pack: turn_offsets must not decrease (turn %d)", t);
+    for (int32_t t = traj_offsets[i]; t < traj_offsets[i + 1]; t++) {
       if (turn_roles[t] > AS_ROLE_TOOL) return as_fail(ctx, AS_ERR_ROLE, "as_pack: role code %d of turn %d is outside 0..3", (int)turn_roles[t], t);
       for (int32_t k = turn_offsets[t]; k < turn_offsets[t + 1]; k++)
         if (turn_tokens[k] < 0 || turn_tokens[k] >= vocab)
           return as_fail(ctx, AS_ERR_TOKEN_RANGE, "as_pack: token %d at offset %d is outside [0, %d)", turn_tokens[k], k, vocab);
       L += turn_offsets[t + 1] - turn_offsets[t];
     }
-    if (L == 0) { consumed++; continue; }
     if (L > T) {
       if (!truncate) return as_fail(ctx, AS_ERR_TOO_LONG, "as_pack: trajectory %d has %lld tokens, row_len is %d", i, (long long)L, T);
       L = T;
     }
-    if (open && fill + L > T) { close_row(); if (rows >= max_rows) break; }
-    open = true;
-    int32_t left = (int32_t)L; bool any_loss = false;
-    for (int32_t t = t0; t < t1 && left > 0; t++) {
+    *len = (int32_t)L;
+    return AS_OK;
+  };
+  // the first L tokens of trajectory i as one segment at `fill` of row `row`
+  auto emit = [&](int32_t i, int32_t L, int32_t row, int32_t fill) {
+    int32_t left = L; bool any_loss = false;
+    for (int32_t t = traj_offsets[i]; t < traj_offsets[i + 1] && left > 0; t++) {
       int32_t len = std::min(turn_offsets[t + 1] - turn_offsets[t], left);
       if (len <= 0) continue;
-      pieces.push_back({rows * T + fill, turn_offsets[t], (uint8_t)(turn_roles[t] == AS_ROLE_ASSISTANT)});
+      pieces.push_back({row * T + fill, turn_offsets[t], (uint8_t)(turn_roles[t] == AS_ROLE_ASSISTANT)});
       any_loss = any_loss || turn_roles[t] == AS_ROLE_ASSISTANT;
       fill += len; left -= len;
     }
-    cu.push_back(rows * T + fill); skip.push_back(any_loss ? 0 : 1);
-    consumed++;
-    if (fill == T) { rows++; fill = 0; open = false; }
+    cu.push_back(row * T + fill); skip.push_back(any_loss ? 0 : 1);
+  };
+  auto pad_tail = [&](int32_t row, int32_t fill) {
+    if (fill < T) { pieces.push_back({row * T + fill, -1, 0}); cu.push_back((row + 1) * T); skip.push_back(1); }
+  };
+  int rc;
+  if (policy == AS_PACK_NEXT_FIT) {
+    int32_t fill = 0, rows = 0, consumed = 0; bool open = false;
+    for (int32_t i = 0; i < n_traj && rows < max_rows; i++) {
+      int32_t L;
+      if ((rc = measure(i, &L))) return rc;
+      if (L == 0) { consumed++; if (traj_row) traj_row[i] = -2; continue; }
+      if (open && fill + L > T) { pad_tail(rows, fill); rows++; fill = 0; open = false; if (rows >= max_rows) break; }
+      open = true;
+      emit(i, L, rows, fill);
+      if (traj_row) traj_row[i] = rows;
+      fill += L; consumed++;
+      if (fill == T) { rows++; fill = 0; open = false; }
+    }
+    if (open) { pad_tail(rows, fill); rows++; }
+    if (traj_row) for (int32_t i = consumed; i < n_traj; i++) traj_row[i] = -1;
+    *n_rows = rows; *n_consumed = consumed;
+    return AS_OK;
   }
-  if (open) close_row();
-  *n_rows = rows; *n_consumed = consumed;
+  // Best fit decreasing: by non-increasing length (ties in input order), each trajectory into the open row
+  // it fills best (least free space left, ties to the lowest row); a new row only when none has room; with
+  // max_rows rows open and no room the trajectory is left out.
+  std::vector<int32_t> len(n_traj), order, place(n_traj, -1);
+  for (int32_t i = 0; i < n_traj; i++) {
+    if ((rc = measure(i, &len[i]))) return rc;
+    if (len[i] > 0) order.push_back(i); else place[i] = -2;
+  }
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return len[a] > len[b]; });
+  std::vector<std::vector<int32_t>> members;
+  std::vector<int32_t> free_;
+  for (int32_t i : order) {
+    int best = -1;
+    for (int r = 0; r < (int)members.size(); r++)
+      if (free_[r] >= len[i] && (best < 0 || free_[r] < free_[best])) best = r;
+    if (best < 0) {
+      if ((int32_t)members.size() >= max_rows) continue;
+      members.emplace_back(); free_.push_back(T);
+      best = (int)members.size() - 1;
+    }
+    members[best].push_back(i); free_[best] -= len[i]; place[i] = best;
+  }
+  int32_t consumed = 0;
+  for (int32_t i = 0; i < n_traj; i++) { consumed += place[i] != -1; if (traj_row) traj_row[i] = place[i]; }
+  for (int32_t r = 0; r < (int32_t)members.size(); r++) {
+    int32_t fill = 0;
+    for (int32_t i : members[r]) { emit(i, len[i], r, fill); fill += len[i]; }
+    pad_tail(r, fill);
+  }
+  *n_rows = (int32_t)members.size(); *n_consumed = consumed;
   return AS_OK;
 }
 
-extern "C" int as_pack(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* turn_offsets,
-                       const uint8_t* turn_roles, const int32_t* traj_offsets, int32_t n_traj,
-                       int32_t row_len, int32_t max_rows, int32_t pad_id, int32_t truncate,
-                       int32_t* d_tokens, int32_t* d_cu_seqlens, uint8_t* d_loss_mask,
-                       int32_t* n_rows_out, int32_t* n_segments_out, int32_t* n_traj_consumed_out,
-                       uint8_t* h_seg_skip_out, void* stream) {
+extern "C" int as_pack_policy(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* turn_offsets,
+                              const uint8_t* turn_roles, const int32_t* traj_offsets, int32_t n_traj,
+                              int32_t row_len, int32_t max_rows, int32_t pad_id, int32_t truncate, int32_t policy,
+                              int32_t* d_tokens, int32_t* d_cu_seqlens, uint8_t* d_loss_mask,
+                              int32_t* n_rows_out, int32_t* n_segments_out, int32_t* n_traj_consumed_out,
+                              uint8_t* h_seg_skip_out, int32_t* h_traj_row_out, void* stream) {
   if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_pack: NULL context");
   if (!turn_offsets || !traj_offsets || !n_rows_out || !n_segments_out || !n_traj_consumed_out)
     return as_fail(ctx, AS_ERR_NULL, "as_pack: NULL offsets or counters");
@@ -262,7 +307,7 @@ extern "C" int as_pack(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* t
   std::vector<Piece> pieces; std::vector<int32_t> cu; std::vector<uint8_t> skip;
   int32_t rows = 0, consumed = 0;
   int rc = pack_plan(ctx, turn_tokens, turn_offsets, turn_roles, traj_offsets, n_traj, row_len, max_rows,
-                     truncate, pieces, cu, skip, &rows, &consumed);
+                     truncate, policy, pieces, cu, skip, &rows, &consumed, h_traj_row_out);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
   AS_HIP(ctx, hipSetDevice(ctx->device));
@@ -293,6 +338,17 @@ extern "C" int as_pack(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* t
   *n_rows_out = rows; *n_segments_out = (int32_t)cu.size() - 1; *n_traj_consumed_out = consumed;
   if (h_seg_skip_out && !skip.empty()) memcpy(h_seg_skip_out, skip.data(), skip.size());
   return AS_OK;
+}
+
+extern "C" int as_pack(as_ctx* ctx, const int32_t* turn_tokens, const int32_t* turn_offsets,
+                       const uint8_t* turn_roles, const int32_t* traj_offsets, int32_t n_traj,
+                       int32_t row_len, int32_t max_rows, int32_t pad_id, int32_t truncate,
+                       int32_t* d_tokens, int32_t* d_cu_seqlens, uint8_t* d_loss_mask,
+                       int32_t* n_rows_out, int32_t* n_segments_out, int32_t* n_traj_consumed_out,
+                       uint8_t* h_seg_skip_out, void* stream) {
+  return as_pack_policy(ctx, turn_tokens, turn_offsets, turn_roles, traj_offsets, n_traj, row_len, max_rows, pad_id, truncate,
+                        AS_PACK_NEXT_FIT, d_tokens, d_cu_seqlens, d_loss_mask, n_rows_out, n_segments_out, n_traj_consumed_out,
+                        h_seg_skip_out, nullptr, stream);
 }
 
 // --------------------------------------------------------- workspace plan

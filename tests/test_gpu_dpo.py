@@ -174,3 +174,36 @@ def test_no_pair_and_invalid_arguments():
         with pytest.raises(B.ASError) as e:
             ctx.dpo_step(model, *args, bad_pairs, ref, beta)
         assert e.value.code == B.ERR["SHAPE"]
+
+
+def test_batch_without_any_target():
+    """Every turn a user turn: all segments are left out of the computation; log-probabilities are 0, the pair
+    loss follows from the reference sums alone, the gradients are exactly zero."""
+    import math
+    from paper_2503_22673_amd import binding as B
+    sh = synth.CONFIGS[1]
+    trajs = [[(1, t) for _, t in tr] for tr in synth.workload(1, 0)]
+    ctx = B.Context(B.make_config(sh, mode=B.AS_FP32))
+    pk = ctx.pack(*synth.flatten_trajectories(trajs), 512, 1)
+    hcu = pk["cu_seqlens"].cpu().numpy()
+    assert pk["seg_skip"].all()
+    model = B.DeviceModel(ctx, synth.weights(sh, 0), synth.lora_weights(sh, 0))
+    for Lg in model.lora_grads:
+        for dA, dB in Lg.values():
+            dA.fill_(1.0); dB.fill_(1.0)
+    ws = torch.empty(ctx.workspace_bytes(1, 512), dtype=torch.uint8, device="cuda")
+    args = (pk["tokens"], pk["cu_seqlens"], hcu, pk["loss_mask"], 1, 512, ws)
+    lp = ctx.sequence_logps(model, *args, seg_skip=pk["seg_skip"])
+    assert not lp.any().item()
+    ref = torch.tensor([-3.0, -1.0] + [0.0] * (len(hcu) - 3), dtype=torch.float32, device="cuda")
+    out = ctx.dpo_step(model, *args, [(0, 1)], ref, 0.5, seg_skip=pk["seg_skip"])
+    torch.cuda.synchronize()
+    z = 0.5 * ((0.0 - -3.0) - (0.0 - -1.0))                                   # = 1
+    want = dpo.dpo_loss(np.zeros(len(hcu) - 1), ref.cpu().numpy(), [(0, 1)], 0.5)
+    st = out["stats"].cpu().numpy()
+    assert st[0] == pytest.approx(math.log1p(math.exp(-z)), rel=1e-6) and st[0] == pytest.approx(want["loss"], rel=1e-6)
+    assert st[1] == pytest.approx(z) and st[2] == 1.0
+    assert not out["logp"].any().item()
+    for Lg in model.lora_grads:
+        for dA, dB in Lg.values():
+            assert not dA.any().item() and not dB.any().item()

@@ -384,6 +384,7 @@ struct Acts {           // activations of one layer kept for its backward
 
 struct Plan {
   int N, Np, d, D, Dkv, QKV, F, V, L, rp, es, Mc;   // Np: token count rounded up to 64 (row length of token-major transposes)
+  int cap;                               // token rows every activation buffer holds (rows * row_len of the plan)
   int n_qkv, n_gu;                       // adapters inside the q/k/v and gate/up groups
   int32_t *seg_start, *seg_end, *tgt_idx, *tgt_pos, *labels, *count, *iscratch;
   int32_t *tok_c; uint8_t* mask_c;       // tokens and mask with the skipped segments squeezed out
@@ -427,7 +428,7 @@ static void target_dims(const as_model_config& c, int t, int* din, int* dout) {
 static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w, Plan& P) {
   const as_model_config& c = ctx->cfg;
   const bool full = c.train_mode == AS_FULL;
-  P.N = (int)(rows * row_len); P.d = c.d_model; P.D = c.n_q_heads * c.head_dim; P.Dkv = c.n_kv_heads * c.head_dim;
+  P.N = (int)(rows * row_len); P.cap = P.N; P.d = c.d_model; P.D = c.n_q_heads * c.head_dim; P.Dkv = c.n_kv_heads * c.head_dim;
   P.QKV = P.D + 2 * P.Dkv; P.F = c.ffn; P.V = c.vocab; P.L = c.n_layers;
   P.es = c.mode == AS_FP32 ? 4 : 2;
   P.rp = full ? 0 : (c.mode == AS_BF16 ? (int)cdiv(c.lora_rank, 64) * 64 : (int)cdiv(c.lora_rank, 16) * 16);   // whole 64-wide K steps for the MFMA tiles
@@ -582,6 +583,7 @@ struct Step {
     g.seg[0] = {A1, B1, lda1, ldb1, K1}; g.nseg = 1;
     if (A2 && K2 > 0) { g.seg[1] = {A2, B2, lda2, ldb2, K2}; g.nseg = 2; }
     g.M = M; g.N = N; g.m_dev = m_dev; g.C = C; g.ldc = ldc; g.c_f32 = c_f32; g.alpha = alpha;
+    g.rows_cap = rows_cap_once; rows_cap_once = 0;
     g.R = R; g.ldr = ldr; g.accumulate = accumulate; g.splitk = 1; g.partial = nullptr;
     if (allow_split) {
       int sk = pick_splitk(mode, M, N, K1);
@@ -590,6 +592,8 @@ struct Step {
     return launch_gemm_off(ctx, mode, gv, g, m_off, st);
   }
 
+  // set right before a gemm() whose row operands are all token-row workspace buffers (they hold P.cap rows)
+  int rows_cap_once = 0;
   LoraSlot& slot(int l, int t) { return P.lora[(size_t)l * AS_N_TARGETS + t]; }
 
   // The dense [rows, cols] matrix of a frozen projection: the caller's pointer, or, for an NF4 base, the
@@ -661,6 +665,7 @@ struct Step {
     if ((rc = launch_swiglu_fwd(ctx, mode, N, F, a.gu, a.m, st))) return rc;
     { LoraSlot& s = slot(l, AS_T_DOWN);
       if (s.on && (rc = gemm(N, rp, a.m, F, s.A, F, F, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_d, rp))) return rc;
+      rows_cap_once = P.cap;
       if ((rc = gemm(N, d, a.m, F, dense(w.wdown, w.adown, d, F), F, F, s.on ? a.u_d : nullptr, rp, s.Bs, rp, s.on ? rp : 0, a.h_mid, d, h_out, d))) return rc; }
     return AS_OK;
   }
@@ -839,6 +844,7 @@ struct Step {
         if (s.on && (rc = gemm(N, rp, off(P.dgu, (size_t)i * F), 2 * F, s.Bst, F, F, nullptr, 0, nullptr, 0, 0, nullptr, 0,
                                off(P.du_gu, (size_t)s.slot * rp), ldg))) return rc;
       }
+      rows_cap_once = P.cap;
       if ((rc = gemm(N, d, P.dgu, 2 * F, P.wT, 2 * F, 2 * F, P.n_gu ? P.du_gu : nullptr, ldg, P.At_gu[l], ldg, ldg,
                      nullptr, 0, P.db, d))) return rc;
       if (full || (P.n_gu && !tn_path())) {

@@ -78,6 +78,10 @@ struct GemmParams {
   // [grp_off[grp], grp_off[grp+1]) of A, R and C (device-side table), at most M of them
   const int* grp_off; int grp;
   double grp_rows;            // expected live rows of the group (timing records only)
+  // rows that every row operand (A of each segment, R, C) really has allocated, or 0: lets a kernel that works in
+  // whole 256-row tiles run over the ragged last tile too (rows past M are computed from whatever is there and
+  // written to rows past M of C; no row of the result depends on another row)
+  int rows_cap;
 };
 int launch_gemm(as_ctx* ctx, int mode, int variant, const GemmParams& p, hipStream_t st);
 // live rows = *p.m_dev - m_off, clamped to [0, p.M]

@@ -545,6 +545,81 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
                         (row0 + BM <= M) && (col0 + BN <= p.N), rb);
 }
 
+// Register-staged pipeline with a hand-scheduled loop, four waves of 128 x 128 (one per SIMD: the 256 accumulator
+// registers of a wave live in the accumulation half of the register file, the vector half holds two register
+// stages of tile data and two fragment sets).  In the kernels above a tile's loads are issued one K step before
+// the tile is needed, because LDS holds two stages and the landing stage is the only place a direct-to-LDS load
+// can go; a load that misses the L2 comes back later than that, and the workgroup waits for it at the barrier.
+// Here a tile travels global -> registers -> LDS and its loads are issued 1.75 K steps before its LDS store.
+// With one wave per SIMD every wait in the instruction stream idles the matrix pipe, so the loop is written out
+// instruction by instruction (gen_gemm_rs_loop.py -> gemm_rs_loop.inc).  LDS layout and fragment order are those
+// of the direct-to-LDS kernel.  Covers whole 256 x 256 tiles, K segments that are multiples of 64, host-side
+// row counts, no split-K; the launcher sends everything else to the other kernels.
+#include "gemm_rs_loop.inc"
+__global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int tiles_m, int tiles_n) {
+  constexpr int BM = 256, BN = 256, BK = 64, TM = 4, TN = 4;
+  extern __shared__ __align__(16) unsigned char smem[];
+  int nblk = tiles_m * tiles_n, pid = blockIdx.x;
+  if (pid >= nblk) return;
+  int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
+  int logical = xcd * q8 + min(xcd, rem) + loc;
+  constexpr int GROUP = 8;
+  int in_group = GROUP * tiles_n, grp = logical / in_group, first_m = grp * GROUP;
+  int gsize = min(tiles_m - first_m, GROUP);
+  int tile_m = first_m + (logical % in_group) % gsize, tile_n = (logical % in_group) / gsize;
+  const int row0 = tile_m * BM, col0 = tile_n * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, l31 = lane & 31, hh = lane >> 5, lrow = lane >> 3, lch = lane & 7;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int nt0 = p.seg[0].K / BK, nt = nt0 + (p.nseg > 1 ? p.seg[1].K / BK : 0);
+  const GemmSeg s0 = p.seg[0], s1 = p.nseg > 1 ? p.seg[1] : p.seg[0];
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  if (nt > 0) {
+    // per-lane addresses of the loop, handed over through this lane's 64-byte line of LDS scratch
+    const int x7 = (l31 >> 1) & 7;
+    u32x4 line[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) {
+      const unsigned c = (unsigned)(((2 * ks + hh) ^ x7) * 16);
+      line[0][ks] = (unsigned)((wm * 128 + l31) * 128) + c;                    // fragment reads of A
+      line[1][ks] = 65536u + (unsigned)((wn * 128 + l31) * 128) + c;           // ... of B
+    }
+    const unsigned wrow = (unsigned)((wave * 64 + lrow) * 128);
+    line[2][0] = wrow + (unsigned)((lch ^ (lrow >> 1)) * 16);                  // LDS stores, even / odd load
+    line[2][1] = wrow + (unsigned)((lch ^ ((lrow >> 1) | 4)) * 16);
+    line[2][2] = line[2][0] + 65536u; line[2][3] = line[2][1] + 65536u;
+    line[3][0] = (unsigned)((lrow * s0.lda + lch * 8) * 2); line[3][1] = (unsigned)((lrow * s0.ldb + lch * 8) * 2);
+    line[3][2] = (unsigned)((lrow * s1.lda + lch * 8) * 2); line[3][3] = (unsigned)((lrow * s1.ldb + lch * 8) * 2);
+    u32x4* scratch = reinterpret_cast<u32x4*>(smem + 131072 + tid * 64);
+#pragma unroll
+    for (int i = 0; i < 4; i++) scratch[i] = line[i];
+    const unsigned scratch_addr = 131072u + (unsigned)tid * 64u;
+    // wave-uniform operand bases: first of the wave's 64 rows of the tile, first K step
+    const uint64_t A0 = (uint64_t)((const bf16_t*)s0.A + (int64_t)(row0 + wave * 64) * s0.lda);
+    const uint64_t B0 = (uint64_t)((const bf16_t*)s0.B + (int64_t)(col0 + wave * 64) * s0.ldb);
+    const uint64_t A1 = (uint64_t)((const bf16_t*)s1.A + (int64_t)(row0 + wave * 64) * s1.lda);
+    const uint64_t B1 = (uint64_t)((const bf16_t*)s1.B + (int64_t)(col0 + wave * 64) * s1.ldb);
+    const int sA0 = (int)(16 * s0.lda), sB0 = (int)(16 * s0.ldb), sA1 = (int)(16 * s1.lda), sB1 = (int)(16 * s1.ldb);   // 8 rows, bytes
+    asm volatile(GEMM_RS_LOOP_ASM
+                 : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]),
+                   "+a"(acc[1][0]), "+a"(acc[1][1]), "+a"(acc[1][2]), "+a"(acc[1][3]),
+                   "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),
+                   "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3])
+                 : "v"(scratch_addr), "s"(A0), "s"(B0), "s"(A1), "s"(B1), "s"(sA0), "s"(sB0), "s"(sA1), "s"(sB1), "s"(nt0), "s"(nt)
+                 : GEMM_RS_LOOP_CLOBBERS);
+  }
+  gemm_epilogue<TM, TN>(p, acc, p.M, 0, row0, col0, row0 + wm * TM * 32 + 4 * (lane >> 5), col0 + wn * TN * 32 + (lane & 31), true, 0);
+}
+
 // Deep-pipeline variant: K steps of 32 (64-byte tile rows) and NS LDS stages, so that NS - 1 steps of tile loads
 // are in flight while one is consumed.  In the two-stage kernel above the loads of a step have one step's time
 // to arrive; measured with cycle stamps, its waves spend a third of every step at the barrier waiting for
@@ -727,6 +802,29 @@ static int launch_dlds_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStrea
   return AS_OK;
 }
 
+// whole 256 x 256 tiles of a plain launch (host-side row count, no split-K, K segments in 64-wide steps, 16-byte rows)
+static bool rs_ok(const GemmParams& p) {
+  if (p.m_dev || p.grp_off || p.splitk > 1 || p.M < 256 || (p.N % 256)) return false;
+  for (int s = 0; s < p.nseg; s++)
+    if ((p.seg[s].K % 64) || p.seg[s].K < 64 || p.seg[s].lda * 16 > INT32_MAX || p.seg[s].ldb * 16 > INT32_MAX) return false;
+  int nt = 0; for (int s = 0; s < p.nseg; s++) nt += (int)(p.seg[s].K / 64);
+  return nt >= 1;
+}
+
+static int launch_rs_cfg(as_ctx* ctx, const GemmParams& p, hipStream_t st) {
+  constexpr size_t smem = 131072 + 256 * 64;             // two stages of A and B tiles + a 64-byte line per lane
+  static bool attr_set = false;
+  if (!attr_set) {
+    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mfma_rs_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    attr_set = true;
+  }
+  // whole row tiles only: the ragged last one too when the operands have the rows, else the caller handles the rest
+  const int tm = p.rows_cap >= (int)cdiv(p.M, 256) * 256 ? (int)cdiv(p.M, 256) : p.M / 256, tn = p.N / 256;
+  gemm_mfma_rs_kernel<<<dim3(tm * tn), 256, smem, st>>>(p, tm, tn);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}
+
 template <int BM, int BN, int WM, int WN>
 static int launch_mfma_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_t st) {
   constexpr int LS = 72;
@@ -766,6 +864,7 @@ static int pick_cfg(const GemmParams& p) {
   if (p.N <= 128 && p.M > 128) return 1;
   if (p.M <= 128) return 2;
   if ((int64_t)cdiv(p.M, 256) * cdiv(p.N, 256) * p.splitk < 128) return 3;
+  if (rs_ok(p) && p.seg[0].K >= 8192) return 24;         // long contractions: the hand-scheduled register-staged loop is ahead
   return 20;                                             // direct-to-LDS tiles when K allows, else staged (0)
 }
 
@@ -779,7 +878,7 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
   if (p.splitk > 1 && !p.partial) return as_fail(ctx, AS_ERR_WORKSPACE, "gemm: split-K needs a partial buffer");
   if (p.accumulate && !p.c_f32) return as_fail(ctx, AS_ERR_SHAPE, "gemm: accumulate needs float output");
   if (p.grp_off && p.splitk > 1) return as_fail(ctx, AS_ERR_SHAPE, "gemm: grouped rows and split-K do not combine");
-  if (variant < 0 || (variant > 2 && (variant < 10 || variant > 33))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
+  if (variant < 0 || (variant > 2 && (variant < 10 || variant > 34))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
   bool use_mfma = (mode == AS_BF16) && variant != 1 && mfma_ok(p);
   if (variant >= 2 && !use_mfma) return as_fail(ctx, AS_ERR_SHAPE, "gemm: MFMA kernel needs bf16 and 8-element alignment");
   int rc = AS_OK;
@@ -814,6 +913,19 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
       case 21: rc = launch_dlds_cfg<256, 256, 2, 2, true, 1, 200>(ctx, p, m_off, st); break;
       case 22: rc = launch_deep_cfg<256, 256, 2, 4, 4>(ctx, p, m_off, st); break;
       case 23: rc = launch_deep_cfg<256, 128, 2, 2, 3>(ctx, p, m_off, st); break;
+      case 24: {                                           // whole row tiles by the register-staged kernel, the ragged rest by the default one
+        if (!rs_ok(p) || m_off) { rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 200>(ctx, p, m_off, st); break; }
+        rc = launch_rs_cfg(ctx, p, st);
+        const int done = p.rows_cap >= (int)cdiv(p.M, 256) * 256 ? p.M : p.M / 256 * 256;
+        if (!rc && done < p.M) {
+          GemmParams t = p;
+          t.M = p.M - done;
+          for (int s = 0; s < t.nseg; s++) t.seg[s].A = (const bf16_t*)t.seg[s].A + (int64_t)done * t.seg[s].lda;
+          t.C = t.c_f32 ? (void*)((float*)t.C + (int64_t)done * t.ldc) : (void*)((bf16_t*)t.C + (int64_t)done * t.ldc);
+          if (t.R) t.R = (const bf16_t*)t.R + (int64_t)done * t.ldr;
+          rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 200>(ctx, t, 0, st);
+        }
+        break; }
       default: rc = launch_mfma_cfg<256, 256, 2, 4>(ctx, p, m_off, st); break;
     }
   } else {

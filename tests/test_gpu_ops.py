@@ -22,11 +22,12 @@ def _env(**kw):
 
 # (M, N, K1, K2): several tiles + ragged tails, and the shapes of the tiny config
 GEMM_SHAPES = [(512, 128, 128, 64), (512, 344, 128, 0), (512, 128, 344, 64), (300, 200, 72, 0), (1, 7, 8, 8),
-               (700, 1024, 256, 64), (64, 520, 1024, 0), (1000, 520, 192, 64)]
+               (700, 1024, 256, 64), (64, 520, 1024, 0), (1000, 520, 192, 64), (1024, 512, 256, 64), (768, 256, 64, 0),
+               (512, 256, 128, 128), (300, 256, 192, 64)]
 
 
 @pytest.mark.parametrize("shape", GEMM_SHAPES)
-@pytest.mark.parametrize("tier", ["fp32", "bf16_fma", "bf16_mfma", "bf16_mfma_dlds", "bf16_mfma_dlds1", "bf16_mfma_dlds2", "bf16_mfma_dlds_pf", "bf16_mfma_dlds_split", "bf16_mfma_dlds_early", "bf16_mfma_dlds_early4", "bf16_mfma_deep", "bf16_mfma_deep_a"])
+@pytest.mark.parametrize("tier", ["fp32", "bf16_fma", "bf16_mfma", "bf16_mfma_dlds", "bf16_mfma_dlds1", "bf16_mfma_dlds2", "bf16_mfma_dlds_pf", "bf16_mfma_dlds_split", "bf16_mfma_dlds_early", "bf16_mfma_dlds_early4", "bf16_mfma_deep", "bf16_mfma_deep_a", "bf16_mfma_rs"])
 def test_gemm_with_lora_segment_and_residual(shape, tier):
     B, G, ctx, _ = _env()
     M, N, K1, K2 = shape
@@ -41,7 +42,7 @@ def test_gemm_with_lora_segment_and_residual(shape, tier):
         A2, B2 = G.quantise(g.standard_normal((M, K2)), bf16), G.quantise(g.standard_normal((N, K2)), bf16)
         ref = ref + A2 @ B2.T
     ref = 0.5 * ref + R
-    variant = {"fp32": 1, "bf16_fma": 1, "bf16_mfma": 2, "bf16_mfma_dlds": 17, "bf16_mfma_dlds1": 18, "bf16_mfma_dlds2": 19, "bf16_mfma_dlds_pf": 21, "bf16_mfma_dlds_split": 27, "bf16_mfma_dlds_early": 30, "bf16_mfma_dlds_early4": 31, "bf16_mfma_deep": 32, "bf16_mfma_deep_a": 33}[tier]
+    variant = {"fp32": 1, "bf16_fma": 1, "bf16_mfma": 2, "bf16_mfma_dlds": 17, "bf16_mfma_dlds1": 18, "bf16_mfma_dlds2": 19, "bf16_mfma_dlds_pf": 21, "bf16_mfma_dlds_split": 27, "bf16_mfma_dlds_early": 30, "bf16_mfma_dlds_early4": 31, "bf16_mfma_deep": 32, "bf16_mfma_deep_a": 33, "bf16_mfma_rs": 34}[tier]
     out = ctx.op_gemm(G.to_dev(A1, dt), G.to_dev(B1, dt), G.to_dev(A2, dt) if K2 else None,
                       G.to_dev(B2, dt) if K2 else None, alpha=0.5, R=G.to_dev(R, dt), out_f32=True, variant=variant,
                       mode=B.AS_BF16 if bf16 else B.AS_FP32)

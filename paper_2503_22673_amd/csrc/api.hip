@@ -638,6 +638,7 @@ struct Step {
     const int nout[3] = {D, Dkv, Dkv}; const int coff[3] = {0, D, D + Dkv};
     for (int i = 0; i < 3; i++) {
       LoraSlot& s = slot(l, i);
+      rows_cap_once = P.cap;
       rc = gemm(N, nout[i], a.a, d, dense(wq[i], aq[i], nout[i], d), d, d, s.on ? off(a.u_qkv, (size_t)s.slot * rp) : nullptr, ldu, s.Bs, rp, s.on ? rp : 0,
                 nullptr, 0, off(a.qkv, coff[i]), QKV);
       if (rc) return rc;
@@ -650,6 +651,7 @@ struct Step {
     if ((rc = launch_attention_fwd(ctx, mode, av, ap, st))) return rc;
     { LoraSlot& s = slot(l, AS_T_O);
       if (s.on && (rc = gemm(N, rp, a.o, D, s.A, D, D, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_o, rp))) return rc;
+      rows_cap_once = P.cap;
       if ((rc = gemm(N, d, a.o, D, dense(w.wo, w.ao, d, D), D, D, s.on ? a.u_o : nullptr, rp, s.Bs, rp, s.on ? rp : 0, h_in, d, a.h_mid, d))) return rc; }
     if ((rc = launch_rmsnorm_fwd(ctx, mode, N, d, a.h_mid, nullptr, nullptr, w.g2, c.rms_eps, a.b, a.rstd2, st))) return rc;
     if (c.n_experts) return forward_moe(l, a);
@@ -869,6 +871,7 @@ struct Step {
     { LoraSlot& s = slot(l, AS_T_O);
       if ((rc = transpose(d, D, dense(w.wo, w.ao, d, D), D, P.wT, d))) return rc;                          // [D, d]
       if (s.on && (rc = gemm(N, rp, P.dh2, d, s.Bst, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.du_o, rp))) return rc;
+      rows_cap_once = P.cap;
       if ((rc = gemm(N, D, P.dh2, d, P.wT, d, d, s.on ? P.du_o : nullptr, rp, s.At, rp, s.on ? rp : 0, nullptr, 0, P.d_o, D))) return rc;
       if (full || (s.on && !tn_path())) {
         if ((rc = transpose_tok(d, P.dh2, d, P.dyT))) return rc;
@@ -900,6 +903,7 @@ struct Step {
         if (s.on && (rc = gemm(N, rp, off(P.dqkv, coff[i]), QKV, s.Bst, nout[i], nout[i], nullptr, 0, nullptr, 0, 0, nullptr, 0,
                                off(P.du_qkv, (size_t)s.slot * rp), ldu))) return rc;
       }
+      rows_cap_once = P.cap;
       if (need_da && (rc = gemm(N, d, P.dqkv, QKV, P.wT, QKV, QKV, P.n_qkv ? P.du_qkv : nullptr, ldu, P.At_qkv[l], ldu, ldu,
                                 nullptr, 0, P.da, d))) return rc;
       if (full || (P.n_qkv && !tn_path())) {

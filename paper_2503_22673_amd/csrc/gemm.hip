@@ -864,7 +864,10 @@ static int pick_cfg(const GemmParams& p) {
   if (p.N <= 128 && p.M > 128) return 1;
   if (p.M <= 128) return 2;
   if ((int64_t)cdiv(p.M, 256) * cdiv(p.N, 256) * p.splitk < 128) return 3;
-  if (rs_ok(p) && p.seg[0].K >= 8192) return 24;         // long contractions: the hand-scheduled register-staged loop is ahead
+  // The hand-scheduled register-staged loop is ahead on long contractions (in isolation 11 % at K = 28672, 5 % at
+  // 14336).  At K = 4096 .. 6144 it measures 2-4 % ahead in isolation for 4096-wide outputs but lost 2 % inside the
+  // training step, and it is 1-2 % behind for 1024- and 14336-wide outputs: those stay with the eight-wave kernel.
+  if (rs_ok(p) && p.seg[0].K >= 8192) return 24;
   return 20;                                             // direct-to-LDS tiles when K allows, else staged (0)
 }
 

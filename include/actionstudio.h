@@ -165,6 +165,7 @@ enum { AS_K_GEMM_MFMA_256 = 0,   /* bf16 MFMA GEMM, 256x256 tile                
        AS_K_LORA_GRAD,           /* adapter-gradient kernel (contraction over tokens) */
        AS_K_GEMM_GROUPED,        /* expert GEMMs over grouped rows (flops: expected share) */
        AS_K_MOE,                 /* routing, grouping, gather and combine kernels */
+       AS_K_GEMM_RS,             /* 256x256 MFMA GEMMs of the hand-scheduled register-staged kernel (long contractions) */
        AS_K_N_CLASSES };
 int as_profile(as_ctx* ctx, int enable);
 int as_profile_read(as_ctx* ctx, int kernel_class, int64_t* launches, double* ms, double* flops);

@@ -98,7 +98,7 @@ lib.as_probe_mfma_peak.restype = C.c_int
 lib.as_profile.argtypes = [_vp, C.c_int]
 lib.as_profile_read.argtypes = [_vp, C.c_int, C.POINTER(_i64), C.POINTER(C.c_double), C.POINTER(C.c_double)]
 KERNEL_CLASSES = ("gemm_mfma_256", "gemm_mfma_skinny", "gemm_fma", "gemm_devrows", "attn_fwd", "attn_bwd", "transpose",
-                  "norm", "swiglu", "rope", "ce", "lora_grad", "gemm_grouped", "moe")
+                  "norm", "swiglu", "rope", "ce", "lora_grad", "gemm_grouped", "moe", "gemm_mfma_rs")
 for _n in ("as_profile", "as_profile_read", "as_create", "as_workspace_bytes", "as_pack", "as_train_step", "as_adamw_update", "as_op_gemm",
            "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy"):
     getattr(lib, _n).restype = C.c_int

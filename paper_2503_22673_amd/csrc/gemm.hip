@@ -889,7 +889,8 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
   int cfg = variant >= 10 ? variant - 10 : pick_cfg(p);
   if (cfg >= 7) for (int s = 0; s < p.nseg; s++) if (p.seg[s].K % 64) cfg = 0;     // direct-to-LDS tiles need whole 64-wide K steps
   const bool big = use_mfma && (cfg == 0 || cfg >= 4);
-  prof_begin(ctx, st, p.grp_off ? AS_K_GEMM_GROUPED : p.m_dev ? AS_K_GEMM_DEVROWS : !use_mfma ? AS_K_GEMM_FMA : big ? AS_K_GEMM_MFMA_256 : AS_K_GEMM_MFMA_SKINNY,
+  const bool rs = use_mfma && cfg == 24 && rs_ok(p) && !m_off;
+  prof_begin(ctx, st, rs ? AS_K_GEMM_RS : p.grp_off ? AS_K_GEMM_GROUPED : p.m_dev ? AS_K_GEMM_DEVROWS : !use_mfma ? AS_K_GEMM_FMA : big ? AS_K_GEMM_MFMA_256 : AS_K_GEMM_MFMA_SKINNY,
              p.grp_off ? 2.0 * p.grp_rows * p.N * ksum : p.m_dev ? 0.0 : 2.0 * p.M * p.N * ksum);
   if (use_mfma) {
     switch (cfg) {

@@ -158,3 +158,20 @@ def test_per_kernel_timing_brackets_nested_launchers():
     assert float(out["loss"].item()) == a["loss"]
     for k in ("attn_fwd", "attn_bwd", "norm", "swiglu", "rope", "lora_grad"):
         assert prof[k][0] > 0 and prof[k][1] > 0.0, (k, prof[k])
+
+
+@pytest.mark.parametrize("row_len", [384, 320])
+def test_long_contraction_uses_the_hand_scheduled_gemm(row_len):
+    """ffn = 8192: the down projection (K = 8192) and the gate / up input gradient (K = 16384) go through the
+    register-staged hand-scheduled kernel.  With rows of 384 the activation buffers hold 768 rows and the kernel
+    covers the ragged last row tile itself; with rows of 320 (640 rows) the rest goes to the other kernel."""
+    import gpu_util as G
+    sh = synth.CONFIGS[1].replace(n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=64, d_model=256, ffn=8192, vocab=512,
+                                  lora_targets=synth.DENSE_TARGETS7, lora_rank=16, lora_alpha=32.0)
+    trajs = random_trajs(11, 8, sh.vocab, turn_lo=12, turn_hi=30, turns=(3, 5))
+    pk = oracle.pack(trajs, row_len, 2)
+    cu = pk["cu_seqlens"]
+    live = sum(int(b - a) for a, b in zip(cu[:-1], cu[1:]) if pk["loss_mask"][a + 1:b].any())      # rows left after the pad tails are squeezed out
+    assert live > 512 and live % 256 != 0 and (live + 255) // 256 * 256 == 768
+    rep = G.compare_step(sh, 4, trajs, 2, row_len, bf16=True, loss_tol=2e-3, grad_tol=3e-2)
+    print("ffn 8192, rows of %d: loss rel %.2e worst grad %.2e" % (row_len, rep["loss_rel"], rep["worst_grad"]))

@@ -217,7 +217,7 @@ class Emitter:
             self.lines.append(s)
 
 
-def main():
+def main(out_path=None):
     e = Emitter()
     # ---- set-up: per-lane values from the LDS scratch line of this lane, scalars from the operands
     e("ds_read_b128 v[192:195], %%%d" % OP_SCRATCH)
@@ -277,7 +277,7 @@ def main():
     e("s_nop 15")
     e("s_nop 15")
 
-    out = os.path.join(os.path.dirname(os.path.abspath(__file__)), "gemm_rs_loop.inc")
+    out = out_path or os.path.join(os.path.dirname(os.path.abspath(__file__)), "gemm_rs_loop.inc")
     with open(out, "w") as f:
         f.write("// Generated by gen_gemm_rs_loop.py -- do not edit.  Main loop of gemm_mfma_rs_kernel.\n")
         f.write("#define GEMM_RS_LOOP_ASM \\\n")
@@ -291,4 +291,5 @@ def main():
 
 
 if __name__ == "__main__":
-    main()
+    import sys
+    main(sys.argv[1] if len(sys.argv) > 1 else None)

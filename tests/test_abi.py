@@ -163,3 +163,13 @@ def test_adamw_and_op_argument_checks(B):
     assert g(ctx.handle, 0, 0, 4, 4, None, 4, p, 4, 4, None, 0, None, 0, 0, 1.0, None, 0, p, 4, 0, None) == B.ERR["NULL"]
     assert g(ctx.handle, 0, 0, 4, 4, p, 2, p, 4, 4, None, 0, None, 0, 0, 1.0, None, 0, p, 4, 0, None) == B.ERR["SHAPE"]
     assert g(ctx.handle, 9, 0, 4, 4, p, 4, p, 4, 4, None, 0, None, 0, 0, 1.0, None, 0, p, 4, 0, None) == B.ERR["CONFIG"]
+
+
+def test_generated_gemm_loop_is_the_generators_output(tmp_path):
+    """The committed inline-asm loop of the register-staged GEMM is what its generator writes (the generator also
+    checks, while replaying the instruction sequence, that every wait count fits its counter)."""
+    import subprocess, sys
+    csrc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2503_22673_amd", "csrc")
+    out = tmp_path / "loop.inc"
+    subprocess.run([sys.executable, os.path.join(csrc, "gen_gemm_rs_loop.py"), str(out)], check=True, capture_output=True)
+    assert out.read_text() == open(os.path.join(csrc, "gemm_rs_loop.inc")).read()

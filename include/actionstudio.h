@@ -303,7 +303,9 @@ int as_dpo_step(as_ctx* ctx, const as_weights* weights, const as_lora* lora,
  * Arrays of n_tensors [host] entries holding [device] pointers:
  *  d_master float (the fp32 weights that are updated); d_params_lowp either
  *  NULL or, per tensor, NULL or a bfloat16 copy rewritten from the master
- *  (round to nearest even); d_grads, d_m, d_v float.  step counts from 1. */
+ *  (round to nearest even); d_grads, d_m, d_v float.  step counts from 1.
+ *  All tensors are updated by one kernel launch (a table of tensors and 65,536-element chunks is staged through
+ *  pinned memory the context owns; the call waits for the previous call's table copy, not for its kernel). */
 int as_adamw_update(as_ctx* ctx, float* const* d_master, void* const* d_params_lowp,
                     const float* const* d_grads, float* const* d_m, float* const* d_v,
                     const int64_t* numel, const uint8_t* apply_wd, int32_t n_tensors,

@@ -162,6 +162,9 @@ extern "C" void as_destroy(as_ctx* ctx) {
   if (ctx->h_step) (void)hipHostFree(ctx->h_step);
   if (ctx->d_stage) (void)hipFree(ctx->d_stage);
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
+  if (ctx->adam_ev) { (void)hipEventSynchronize(ctx->adam_ev); (void)hipEventDestroy(ctx->adam_ev); }
+  if (ctx->d_adam) (void)hipFree(ctx->d_adam);
+  if (ctx->h_adam) (void)hipHostFree(ctx->h_adam);
   delete ctx;
 }
 
@@ -1229,12 +1232,39 @@ extern "C" int as_adamw_update(as_ctx* ctx, float* const* d_master, void* const*
   }
   AS_HIP(ctx, hipSetDevice(ctx->device));
   const float bc1 = (float)(1.0 - pow((double)beta1, (double)step)), bc2 = (float)(1.0 - pow((double)beta2, (double)step));
+  // one launch over all tensors: a table of tensors and of 65,536-element chunks goes to the device through pinned
+  // memory the context owns (the previous call's copy is waited for before the pinned buffer is rewritten)
+  hipStream_t st = (hipStream_t)stream;
+  std::vector<AdamTensor> tens; std::vector<AdamChunk> chunks;
   for (int i = 0; i < n_tensors; i++) {
-    int rc = launch_adamw(ctx, d_master[i], d_params_lowp ? d_params_lowp[i] : nullptr, d_grads[i], d_m[i], d_v[i], numel[i],
-                          lr, beta1, beta2, eps, apply_wd[i] ? weight_decay : 0.f, bc1, bc2, (hipStream_t)stream);
-    if (rc) return rc;
+    if (numel[i] == 0) continue;
+    if (cdiv(numel[i], 65536) > INT32_MAX) return as_fail(ctx, AS_ERR_SHAPE, "as_adamw_update: tensor %d is too large", i);
+    const int32_t ti = (int32_t)tens.size();
+    tens.push_back({d_master[i], d_params_lowp ? (bf16_t*)d_params_lowp[i] : nullptr, d_grads[i], d_m[i], d_v[i], numel[i],
+                    apply_wd[i] ? weight_decay : 0.f, 0});
+    for (int64_t c = 0, nc = cdiv(numel[i], 65536); c < nc; c++) chunks.push_back({ti, (int32_t)c});
   }
-  return AS_OK;
+  if (chunks.empty()) return AS_OK;
+  if (chunks.size() > (size_t)INT32_MAX) return as_fail(ctx, AS_ERR_SHAPE, "as_adamw_update: too many elements for one call");
+  const size_t tb = tens.size() * sizeof(AdamTensor), cb = chunks.size() * sizeof(AdamChunk), bytes = tb + cb;
+  if (bytes > ctx->adam_bytes) {
+    if (ctx->adam_ev) (void)hipEventSynchronize(ctx->adam_ev);
+    if (ctx->d_adam) (void)hipFree(ctx->d_adam);
+    if (ctx->h_adam) (void)hipHostFree(ctx->h_adam);
+    ctx->d_adam = ctx->h_adam = nullptr; ctx->adam_bytes = 0;
+    const size_t cap = std::max<size_t>(4096, bytes * 2);
+    AS_HIP(ctx, hipMalloc(&ctx->d_adam, cap));
+    AS_HIP(ctx, hipHostMalloc(&ctx->h_adam, cap, hipHostMallocDefault));
+    ctx->adam_bytes = cap;
+  }
+  if (!ctx->adam_ev) AS_HIP(ctx, hipEventCreateWithFlags(&ctx->adam_ev, hipEventDisableTiming));
+  else AS_HIP(ctx, hipEventSynchronize(ctx->adam_ev));
+  memcpy(ctx->h_adam, tens.data(), tb);
+  memcpy((char*)ctx->h_adam + tb, chunks.data(), cb);
+  AS_HIP(ctx, hipMemcpyAsync(ctx->d_adam, ctx->h_adam, bytes, hipMemcpyHostToDevice, st));
+  AS_HIP(ctx, hipEventRecord(ctx->adam_ev, st));
+  return launch_adamw_multi(ctx, (const AdamTensor*)ctx->d_adam, (const AdamChunk*)((const char*)ctx->d_adam + tb), (int)chunks.size(),
+                            lr, beta1, beta2, eps, bc1, bc2, st);
 }
 
 // ---------------------------------------------------------- building blocks

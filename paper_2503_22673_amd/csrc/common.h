@@ -28,6 +28,8 @@ struct as_ctx {
   void* h_stage = nullptr; size_t h_stage_bytes = 0;
   // small per-step table (as_train_step with skipped segments): pinned host + device copy
   void* d_step = nullptr; void* h_step = nullptr; size_t step_bytes = 0; hipEvent_t step_ev = nullptr;
+  // tensor table of as_adamw_update (one launch over all tensors): pinned host + device copy
+  void* d_adam = nullptr; void* h_adam = nullptr; size_t adam_bytes = 0; hipEvent_t adam_ev = nullptr;
   // optional per-launch timing (as_profile): event pairs around kernels of the tracked classes
   struct ProfRec { hipEvent_t a, b; double flops; int cls; };
   bool prof_on = false; int prof_depth = 0;
@@ -180,7 +182,10 @@ int launch_loss_finalize(as_ctx* ctx, const float* loss_rows, const int32_t* cou
                          float* loss_sum, hipStream_t st);
 int launch_splitk_reduce(as_ctx* ctx, const float* partial, int splitk, int64_t mn, int N, float alpha,
                          float* C, int64_t ldc, hipStream_t st);
-int launch_adamw(as_ctx* ctx, float* w, void* w_lowp, const float* g, float* m, float* v, int64_t n,
-                 float lr, float b1, float b2, float eps, float wd, float bc1, float bc2, hipStream_t st);
+// one tensor of a multi-tensor update, and one 64 K-element chunk of work
+struct AdamTensor { float* w; bf16_t* w_lowp; const float* g; float* m; float* v; int64_t n; float wd; int pad; };
+struct AdamChunk { int32_t tensor; int32_t chunk; };
+int launch_adamw_multi(as_ctx* ctx, const AdamTensor* d_tensors, const AdamChunk* d_chunks, int n_chunks,
+                       float lr, float b1, float b2, float eps, float bc1, float bc2, hipStream_t st);
 int launch_embed_bwd(as_ctx* ctx, int mode, const int32_t* tok, int n, int d, int V, const void* dh,
                      int32_t* scratch, float* dE, hipStream_t st);

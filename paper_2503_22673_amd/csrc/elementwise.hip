@@ -714,27 +714,27 @@ int launch_splitk_reduce(as_ctx* ctx, const float* partial, int splitk, int64_t 
 }
 
 // -------------------------------------------------------------------- AdamW
-__global__ void adamw_kernel(float* __restrict__ w, bf16_t* __restrict__ w_lowp, const float* __restrict__ g,
-                             float* __restrict__ m, float* __restrict__ v, int64_t n, float lr, float b1,
-                             float b2, float eps, float wd, float bc1, float bc2) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (; i < n; i += stride) {
-    float gi = g[i], wi = w[i];
-    float mi = b1 * m[i] + (1.f - b1) * gi;
-    float vi = b2 * v[i] + (1.f - b2) * gi * gi;
-    m[i] = mi; v[i] = vi;
-    float upd = (mi / bc1) / (sqrtf(vi / bc2) + eps) + wd * wi;
+// All tensors in one launch: workgroup b takes chunk b of the table (65,536 consecutive elements of one tensor).
+__global__ __launch_bounds__(256) void adamw_multi_kernel(const AdamTensor* __restrict__ tensors, const AdamChunk* __restrict__ chunks,
+                                                          float lr, float b1, float b2, float eps, float bc1, float bc2) {
+  const AdamChunk c = chunks[blockIdx.x];
+  const AdamTensor t = tensors[c.tensor];
+  const int64_t lo = (int64_t)c.chunk * 65536, hi = min(t.n, lo + 65536);
+  for (int64_t i = lo + threadIdx.x; i < hi; i += 256) {
+    float gi = t.g[i], wi = t.w[i];
+    float mi = b1 * t.m[i] + (1.f - b1) * gi;
+    float vi = b2 * t.v[i] + (1.f - b2) * gi * gi;
+    t.m[i] = mi; t.v[i] = vi;
+    float upd = (mi / bc1) / (sqrtf(vi / bc2) + eps) + t.wd * wi;
     wi = wi - lr * upd;
-    w[i] = wi;
-    if (w_lowp) w_lowp[i] = (bf16_t)wi;
+    t.w[i] = wi;
+    if (t.w_lowp) t.w_lowp[i] = (bf16_t)wi;
   }
 }
-int launch_adamw(as_ctx* ctx, float* w, void* w_lowp, const float* g, float* m, float* v, int64_t n,
-                 float lr, float b1, float b2, float eps, float wd, float bc1, float bc2, hipStream_t st) {
-  if (n <= 0) return AS_OK;
-  int64_t blocks = cdiv(n, 256); if (blocks > 16384) blocks = 16384;
-  adamw_kernel<<<(int)blocks, 256, 0, st>>>(w, (bf16_t*)w_lowp, g, m, v, n, lr, b1, b2, eps, wd, bc1, bc2);
+int launch_adamw_multi(as_ctx* ctx, const AdamTensor* d_tensors, const AdamChunk* d_chunks, int n_chunks,
+                       float lr, float b1, float b2, float eps, float bc1, float bc2, hipStream_t st) {
+  if (n_chunks <= 0) return AS_OK;
+  adamw_multi_kernel<<<n_chunks, 256, 0, st>>>(d_tensors, d_chunks, lr, b1, b2, eps, bc1, bc2);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }

@@ -663,6 +663,7 @@ struct Step {
     const void* wg[2] = {w.wgate, w.wup}; const float* ag[2] = {w.agate, w.aup};
     for (int i = 0; i < 2; i++) {
       LoraSlot& s = slot(l, AS_T_GATE + i);
+      rows_cap_once = P.cap;
       rc = gemm(N, F, a.b, d, dense(wg[i], ag[i], F, d), d, d, s.on ? off(a.u_gu, (size_t)s.slot * rp) : nullptr, ldg, s.Bs, rp, s.on ? rp : 0,
                 nullptr, 0, off(a.gu, (size_t)i * F), 2 * F);
       if (rc) return rc;
@@ -826,6 +827,7 @@ struct Step {
     { LoraSlot& s = slot(l, AS_T_DOWN);
       if ((rc = transpose(d, F, dense(w.wdown, w.adown, d, F), F, P.wT, d))) return rc;                       // [F, d]
       if (s.on && (rc = gemm(N, rp, P.dh, d, s.Bst, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.du_d, rp))) return rc;
+      rows_cap_once = P.cap;
       if ((rc = gemm(N, F, P.dh, d, P.wT, d, d, s.on ? P.du_d : nullptr, rp, s.At, rp, s.on ? rp : 0, nullptr, 0, P.dm, F))) return rc;
       // ---- SwiGLU (in recompute mode 2 it also rewrites the forward product, which the gradients below need)
       const bool rewrite_m = c.recompute == 2 && l != c.n_layers - 1 && (full || s.on);

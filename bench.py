@@ -22,8 +22,9 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # HBM-side bytes per launch of the dominant kernel at config 3 (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, two counter
 # runs over one bench step, see profiles/gemm_256_counters.md); only valid for the kernel those runs saw
-TRAFFIC_BYTES_PER_LAUNCH = {(3, "gemm_mfma_dlds_kernel<256,256,2,4,true,1,200,0>"): 6.25e9}
-DOMINANT_KERNEL = "gemm_mfma_dlds_kernel<256,256,2,4,true,1,200,0>"
+TRAFFIC_BYTES_PER_LAUNCH = {(3, "gemm_mfma_rs_kernel"): 9.2e9}
+DOMINANT_KERNEL = "gemm_mfma_rs_kernel"                      # dense models; expert GEMMs: gemm_mfma_dlds_kernel<256,256,2,4,true,1,200,0>
+GROUPED_KERNEL = "gemm_mfma_dlds_kernel<256,256,2,4,true,1,200,0>"
 
 
 def device_weights(sh, seed, dtype):
@@ -260,7 +261,7 @@ def main():
     tokens_per_s = n_nonpad / (ms_per_step * 1e-3)
     mfu = fl["total"] / (ms_per_step * 1e-3) / (PEAK_BF16_TFLOPS * 1e12)
     hfu = (fl["total"] + fl["recompute"]) / (ms_per_step * 1e-3) / (PEAK_BF16_TFLOPS * 1e12)
-    dom = "gemm_grouped" if sh.n_experts else "gemm_mfma_256"
+    dom = "gemm_grouped" if sh.n_experts else "gemm_mfma_rs"
     n_l, ms_l, fl_l = prof[dom]
     ach = fl_l / (ms_l * 1e-3) / 1e12 if ms_l > 0 else 0.0
     breakdown = {k: round(v[1] / args.steps, 2) for k, v in prof.items() if v[0]}
@@ -304,7 +305,7 @@ def main():
         "loss": round(loss, 5), "pack_ms": round(pack_ms, 2), "adamw_ms": None if adam_ms is None else round(adam_ms, 3),
         "wall_s_timed_region": round(wall, 3),
         "kernel_ms_per_step": breakdown,
-        "roofline": {"kernel": DOMINANT_KERNEL + (" (expert GEMMs over grouped rows, forward + dX)" if sh.n_experts else
+        "roofline": {"kernel": (GROUPED_KERNEL + " (expert GEMMs over grouped rows, forward + dX)" if sh.n_experts else DOMINANT_KERNEL +
                                                   " (projection GEMMs forward + dX, LoRA term as second K segment)"),
                      "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_BF16_TFLOPS, 4),

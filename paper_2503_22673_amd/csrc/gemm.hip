@@ -598,6 +598,55 @@ __device__ __forceinline__ void gemm_epilogue_rows(const GemmParams& p, f32x16 (
   }
 }
 
+// The same accumulator layout, bf16 output, through LDS: stored 8 bytes per lane as above, a store instruction touches
+// 32 rows with 16 bytes each, and the epilogue of a 256 x 256 tile costs 8-10 % of a tile with a contraction of 4096.
+// Here every wave writes its 128 x 128 block (with the residual added and rounded once, as above) into its own part of
+// the tile memory, which is free once every wave has left the loop, and reads it back 16 bytes per lane, so that a store
+// instruction writes four whole 256-byte row pieces.  Rows are 272 bytes apart in LDS.  The residual takes the same way
+// in: loaded 16 bytes per lane, parked at the place of the result, picked up by the lane that owns the element.
+template <int TM, int TN>
+__device__ __forceinline__ void gemm_epilogue_staged(const GemmParams& p, f32x16 (&acc)[TM][TN], unsigned char* smem, int wave, int lane,
+                                                     int row_w0, int col_w0) {
+  constexpr int LROW = 272, ROWS = TM * 32;
+  static_assert(TN * 32 == 128, "a block row is 256 bytes: 16 lanes of 16 bytes");
+  unsigned char* my = smem + wave * (ROWS * LROW);
+  const int l31 = lane & 31, hh = lane >> 5, r4 = lane >> 4, c16 = lane & 15;
+  const float alpha = p.alpha;
+  __syncthreads();                                       // the other waves have read their last fragments
+  if (p.R) {
+    const bf16_t* rr = (const bf16_t*)p.R + (int64_t)(row_w0 + r4) * p.ldr + col_w0 + c16 * 8;
+#pragma unroll 8
+    for (int it = 0; it < ROWS / 4; it++)
+      *reinterpret_cast<u32x4*>(my + (4 * it + r4) * LROW + c16 * 16) = *reinterpret_cast<const u32x4*>(rr + (int64_t)(4 * it) * p.ldr);
+    __builtin_amdgcn_s_waitcnt(0xc07f);                  // lgkmcnt(0): LDS operations of a wave complete in order; this is for the compiler's sake
+    asm volatile("" ::: "memory");
+  }
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int b4 = 0; b4 < 4; b4++) {
+        bf16x4_t* q = reinterpret_cast<bf16x4_t*>(my + (32 * i + l31) * LROW + (32 * j + 8 * b4 + 4 * hh) * 2);
+        f32x4 v;
+#pragma unroll
+        for (int k = 0; k < 4; k++) v[k] = alpha * acc[i][j][4 * b4 + k];
+        if (p.R) { const bf16x4_t x = *q;
+#pragma unroll
+          for (int k = 0; k < 4; k++) v[k] += (float)x[k]; }
+        bf16x4_t w;
+#pragma unroll
+        for (int k = 0; k < 4; k++) w[k] = (bf16_t)v[k];
+        *q = w;
+      }
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  asm volatile("" ::: "memory");
+  bf16_t* c = (bf16_t*)p.C + (int64_t)(row_w0 + r4) * p.ldc + col_w0 + c16 * 8;
+#pragma unroll 8
+  for (int it = 0; it < ROWS / 4; it++)
+    *reinterpret_cast<u32x4*>(c + (int64_t)(4 * it) * p.ldc) = *reinterpret_cast<const u32x4*>(my + (4 * it + r4) * LROW + c16 * 16);
+}
+
 // Register-staged pipeline with a hand-scheduled loop, four waves of 128 x 128 (one per SIMD: the 256 accumulator
 // registers of a wave live in the accumulation half of the register file, the vector half holds two register
 // stages of tile data and two fragment sets).  In the kernels above a tile's loads are issued one K step before
@@ -670,7 +719,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int til
                  : "v"(scratch_addr), "s"(A0), "s"(B0), "s"(A1), "s"(B1), "s"(sA0), "s"(sB0), "s"(sA1), "s"(sB1), "s"(nt0), "s"(nt)
                  : GEMM_RS_LOOP_CLOBBERS);
   }
-  gemm_epilogue_rows<TM, TN>(p, acc, row0 + wm * TM * 32 + l31, col0 + wn * TN * 32 + 4 * hh);
+  // bf16 results with 16-byte rows leave through LDS (whole 256-byte row pieces per store), the rest row by row
+  const bool staged = !p.c_f32 && !(p.ldc % 8) && (!p.R || (!(p.ldr % 8) && !((uintptr_t)p.R % 16)));
+  if (staged) gemm_epilogue_staged<TM, TN>(p, acc, smem, wave, lane, row0 + wm * TM * 32, col0 + wn * TN * 32);
+  else gemm_epilogue_rows<TM, TN>(p, acc, row0 + wm * TM * 32 + l31, col0 + wn * TN * 32 + 4 * hh);
 }
 
 // Deep-pipeline variant: K steps of 32 (64-byte tile rows) and NS LDS stages, so that NS - 1 steps of tile loads

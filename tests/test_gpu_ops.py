@@ -51,6 +51,36 @@ def test_gemm_with_lora_segment_and_residual(shape, tier):
     assert grad_norm_err(G.to_np(out), ref) < 2e-6 * max(1, (K1 + K2)) ** 0.5 + 1e-6
 
 
+@pytest.mark.parametrize("with_residual", [False, True])
+@pytest.mark.parametrize("shape", [(512, 512, 256, 64), (768, 256, 128, 0), (1280, 768, 64, 64)])
+def test_hand_scheduled_gemm_bf16_output(shape, with_residual):
+    """bf16 results of the hand-scheduled kernel leave through LDS (residual included): one rounding of alpha * sum + R"""
+    B, G, ctx, _ = _env()
+    M, N, K1, K2 = shape
+    g = synth.rng(5, 20)
+    A1, B1 = G.quantise(g.standard_normal((M, K1)), True), G.quantise(g.standard_normal((N, K1)), True)
+    R = G.quantise(g.standard_normal((M, N)), True) if with_residual else None
+    ref = A1 @ B1.T
+    A2 = B2 = None
+    if K2:
+        A2, B2 = G.quantise(g.standard_normal((M, K2)), True), G.quantise(g.standard_normal((N, K2)), True)
+        ref = ref + A2 @ B2.T
+    ref = 0.25 * ref + (R if with_residual else 0.0)
+    dt = torch.bfloat16
+    args = (G.to_dev(A1, dt), G.to_dev(B1, dt), G.to_dev(A2, dt) if K2 else None, G.to_dev(B2, dt) if K2 else None)
+    kw = dict(alpha=0.25, R=G.to_dev(R, dt) if with_residual else None, mode=B.AS_BF16)
+    out = ctx.op_gemm(*args, variant=34, **kw)
+    torch.cuda.synchronize()
+    assert out.dtype == torch.bfloat16
+    got = G.to_np(out)
+    # one rounding to bf16 of a float sum of exact products: half an ulp plus the summation error
+    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-4 * (K1 + K2) ** 0.5)
+    # same summation order as the eight-wave kernel: the same bits
+    other = ctx.op_gemm(*args, variant=30, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(out, other)
+
+
 def test_gemm_mfma_typed_output_and_strides():
     B, G, ctx, _ = _env()
     g = synth.rng(2, 20)

@@ -665,7 +665,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int til
   if (pid >= nblk) return;
   int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
   int logical = xcd * q8 + min(xcd, rem) + loc;
-  constexpr int GROUP = 8;
+  // the 32 workgroups an XCD runs at a time cover 4 row tiles x 8 column tiles: the row panels (activations, read from
+  // HBM the first time) are the expensive L2 misses, the column panels (weights, hot in the memory-side cache because
+  // every XCD reads them) the cheap ones; measured against 8 x 4: +2..6 %, against 16 x 2: +14 %
+  constexpr int GROUP = 4;
   int in_group = GROUP * tiles_n, grp = logical / in_group, first_m = grp * GROUP;
   int gsize = min(tiles_m - first_m, GROUP);
   int tile_m = first_m + (logical % in_group) % gsize, tile_n = (logical % in_group) / gsize;

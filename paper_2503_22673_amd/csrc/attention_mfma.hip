@@ -440,6 +440,36 @@ __global__ void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __
   if (lane == 0) delta[r] = acc;
 }
 
+// the same with 16 bytes per lane: DH / 8 neighbouring lanes share a row (DH / 8 a power of two, at most 64)
+template <int DH>
+__global__ __launch_bounds__(256) void attn_delta_vec_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o, int64_t rows,
+                                                             float* __restrict__ delta) {
+  constexpr int LPR = DH / 8;
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x, r = t / LPR;
+  float acc = 0.f;
+  if (r < rows) {
+    const u32x4 a = *reinterpret_cast<const u32x4*>(o + t * 8), b = *reinterpret_cast<const u32x4*>(d_o + t * 8);
+#pragma unroll
+    for (int k = 0; k < 4; k++)                          // a bf16 is the upper half of a float
+      acc += __uint_as_float(a[k] << 16) * __uint_as_float(b[k] << 16) + __uint_as_float(a[k] & 0xffff0000u) * __uint_as_float(b[k] & 0xffff0000u);
+  }
+#pragma unroll
+  for (int off = 1; off < LPR; off <<= 1) acc += __shfl_xor(acc, off);
+  if (r < rows && (threadIdx.x & (LPR - 1)) == 0) delta[r] = acc;
+}
+
+template <int DH>
+static void launch_delta(const AttnParams& p, int64_t rows, hipStream_t st) {
+  constexpr int LPR = DH / 8;
+  if constexpr (DH % 8 == 0 && (LPR & (LPR - 1)) == 0 && LPR <= 64) {
+    if (!((uintptr_t)p.o % 16) && !((uintptr_t)p.d_o % 16)) {
+      attn_delta_vec_kernel<DH><<<(unsigned)cdiv(rows * LPR, 256), 256, 0, st>>>((const bf16_t*)p.o, (const bf16_t*)p.d_o, rows, p.delta);
+      return;
+    }
+  }
+  attn_delta_kernel<<<(unsigned)cdiv(rows, 4), 256, 0, st>>>((const bf16_t*)p.o, (const bf16_t*)p.d_o, rows, DH, p.delta);
+}
+
 // ------------------------------------------------------------- backward: dQ
 // Wave = 32 queries of one head; workgroup = HPW heads x (4/HPW) query blocks.
 template <int DH, int HPW>
@@ -1004,7 +1034,7 @@ int bwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
     if ((rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, Dkv, p.k, p.ldkv, ts, Np, st))) return rc;                       // K^T
     if ((rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, D, p.q, p.ldq, ts + (size_t)Dkv * Np, Np, st))) return rc;       // Q^T
     if ((rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, D, p.d_o, D, ts + (size_t)(Dkv + D) * Np, Np, st))) return rc;   // dO^T
-    attn_delta_kernel<<<(unsigned)cdiv(rows, 4), 256, 0, st>>>((const bf16_t*)p.o, (const bf16_t*)p.d_o, rows, DH, p.delta);
+    launch_delta<DH>(p, rows, st);
     AS_LAUNCH_CHECK(ctx);
     const int hpw = heads_per_wg(p);
     if (hpw == 4) rc = launch_dq2<DH, 4>(ctx, p, scale, sl2, st); else if (hpw == 2) rc = launch_dq2<DH, 2>(ctx, p, scale, sl2, st);

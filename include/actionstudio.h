@@ -326,6 +326,28 @@ int as_op_gemm(as_ctx* ctx, int mode, int variant, int64_t M, int64_t N,
                float alpha, const void* R, int64_t ldr, void* C, int64_t ldc, int c_is_f32,
                void* stream);
 
+/* The same product over rows whose number is only known on the device (one K
+ * segment).  The target rows of the vocabulary head (Section 3.2.1: the loss
+ * covers assistant tokens only, their number comes out of the mask on the
+ * device) and the rows of one expert of a sparse model (Section 4.1 names
+ * Mixtral-8x7B/8x22B) are such products.
+ *   d_rows       [device] int32, may be NULL: the product covers rows
+ *                0 .. min(M, *d_rows - row_off) - 1 of A, R and C (the caller
+ *                has already moved the three pointers to row row_off).
+ *   d_group_off  [device] int32 table, may be NULL: the product covers rows
+ *                d_group_off[group] .. d_group_off[group + 1] - 1 (at most M
+ *                of them) of A, R and C.
+ *   rows_cap     with d_group_off: the number of rows A, R and C have (0 = not
+ *                stated; kernels that read whole row tiles then stay out).
+ * Rows outside the live range are neither read into the result nor written.
+ * A, R, C must hold M rows (d_rows) or rows_cap rows (d_group_off).
+ * Errors: AS_ERR_NULL without both tables, AS_ERR_SHAPE as as_op_gemm. */
+int as_op_gemm_rows(as_ctx* ctx, int mode, int variant, int64_t M, int64_t N,
+                    const void* A, int64_t lda, const void* B, int64_t ldb, int64_t K,
+                    float alpha, const void* R, int64_t ldr, void* C, int64_t ldc, int c_is_f32,
+                    const int32_t* d_rows, int64_t row_off, const int32_t* d_group_off, int group, int64_t rows_cap,
+                    void* stream);
+
 /* y = x * rstd * g with rstd = (mean x^2 + eps)^-1/2 per row; rstd float[n]. */
 int as_op_rmsnorm_fwd(as_ctx* ctx, int mode, int64_t n, int64_t d, const void* x, const void* g,
                       float eps, void* y, float* rstd, void* stream);

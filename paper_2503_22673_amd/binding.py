@@ -86,6 +86,8 @@ lib.as_dpo_step.argtypes = [_vp, C.POINTER(Weights), C.POINTER(Lora), _vp, _vp, 
 lib.as_adamw_update.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _f32, _f32, _f32, _f32, _f32, _vp]
 lib.as_op_gemm.argtypes = [_vp, C.c_int, C.c_int, _i64, _i64, _vp, _i64, _vp, _i64, _i64, _vp, _i64, _vp, _i64, _i64,
                            _f32, _vp, _i64, _vp, _i64, C.c_int, _vp]
+lib.as_op_gemm_rows.argtypes = [_vp, C.c_int, C.c_int, _i64, _i64, _vp, _i64, _vp, _i64, _i64, _f32, _vp, _i64, _vp, _i64, C.c_int,
+                                _vp, _i64, _vp, C.c_int, _i64, _vp]
 lib.as_op_rmsnorm_fwd.argtypes = [_vp, C.c_int, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _vp]
 lib.as_op_rmsnorm_bwd.argtypes = [_vp, C.c_int, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.as_op_attention_fwd.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _vp]
@@ -100,12 +102,12 @@ lib.as_profile_read.argtypes = [_vp, C.c_int, C.POINTER(_i64), C.POINTER(C.c_dou
 KERNEL_CLASSES = ("gemm_mfma_256", "gemm_mfma_skinny", "gemm_fma", "gemm_devrows", "attn_fwd", "attn_bwd", "transpose",
                   "norm", "swiglu", "rope", "ce", "lora_grad", "gemm_grouped", "moe", "gemm_mfma_rs")
 for _n in ("as_profile", "as_profile_read", "as_create", "as_workspace_bytes", "as_pack", "as_train_step", "as_adamw_update", "as_op_gemm",
-           "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy"):
+           "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy", "as_op_gemm_rows"):
     getattr(lib, _n).restype = C.c_int
 
 EXPORTS = ("as_probe_lds_feed", "as_probe_mfma_peak", "as_profile", "as_profile_read", "as_create", "as_destroy", "as_last_error", "as_workspace_bytes", "as_pack", "as_train_step",
            "as_adamw_update", "as_op_gemm", "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd",
-           "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy")
+           "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy", "as_op_gemm_rows")
 
 
 class ASError(RuntimeError):
@@ -315,6 +317,16 @@ class Context:
                                   _ptr(A2), A2.stride(0) if A2 is not None else 0, _ptr(B2),
                                   B2.stride(0) if B2 is not None else 0, K2, alpha, _ptr(R),
                                   R.stride(0) if R is not None else 0, _ptr(Cm), Cm.stride(0), int(out_f32), _stream()))
+        return Cm
+
+    def op_gemm_rows(self, A, Bm, Cm, alpha=1.0, R=None, d_rows=None, row_off=0, d_group_off=None, group=0, rows_cap=0, M=None,
+                     variant=0, mode=None):
+        """Cm (caller's buffer, float32 or A's type) receives the live rows of alpha * A Bm^T (+ R); the other rows stay as they are."""
+        mode = self.mode if mode is None else mode
+        M = A.shape[0] if M is None else M
+        self.check(lib.as_op_gemm_rows(self.handle, mode, variant, M, Bm.shape[0], _ptr(A), A.stride(0), _ptr(Bm), Bm.stride(0), A.shape[1],
+                                       alpha, _ptr(R), R.stride(0) if R is not None else 0, _ptr(Cm), Cm.stride(0),
+                                       int(Cm.dtype == torch.float32), _ptr(d_rows), row_off, _ptr(d_group_off), group, rows_cap, _stream()))
         return Cm
 
     def nf4_quantize(self, w):

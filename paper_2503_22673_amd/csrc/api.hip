@@ -682,6 +682,7 @@ struct Step {
     g.seg[0] = {A, B, lda, ldb, K}; g.nseg = 1;
     g.M = P.N; g.N = N; g.C = C; g.ldc = ldc; g.alpha = 1.f; g.splitk = 1;
     g.grp_off = eoff; g.grp = e; g.grp_rows = 2.0 * P.N / c.n_experts;
+    g.rows_cap = 2 * P.N;                                  // A and C are (token, slot) buffers: 2 N rows
     return launch_gemm_off(ctx, mode, gv, g, 0, st);
   }
 
@@ -1311,6 +1312,28 @@ extern "C" int as_op_gemm(as_ctx* ctx, int mode, int variant, int64_t M, int64_t
   g.M = (int)M; g.N = (int)N; g.C = C; g.ldc = ldc; g.c_f32 = c_is_f32; g.alpha = alpha; g.R = R; g.ldr = ldr; g.splitk = 1;
   AS_HIP(ctx, hipSetDevice(ctx->device));
   return launch_gemm(ctx, mode, variant, g, (hipStream_t)stream);
+}
+
+extern "C" int as_op_gemm_rows(as_ctx* ctx, int mode, int variant, int64_t M, int64_t N,
+                               const void* A, int64_t lda, const void* B, int64_t ldb, int64_t K,
+                               float alpha, const void* R, int64_t ldr, void* C, int64_t ldc, int c_is_f32,
+                               const int32_t* d_rows, int64_t row_off, const int32_t* d_group_off, int group, int64_t rows_cap,
+                               void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_op_gemm_rows: NULL context");
+  int rc = check_mode(ctx, mode); if (rc) return rc;
+  if (!A || !B || !C) return as_fail(ctx, AS_ERR_NULL, "as_op_gemm_rows: NULL operand");
+  if (!d_rows && !d_group_off) return as_fail(ctx, AS_ERR_NULL, "as_op_gemm_rows: a device row count or a group table is required");
+  if (M < 0 || N < 0 || K < 0 || M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || row_off < 0 || row_off > INT32_MAX ||
+      rows_cap < 0 || rows_cap > INT32_MAX || group < 0)
+    return as_fail(ctx, AS_ERR_SHAPE, "as_op_gemm_rows: sizes must be in [0, 2^31)");
+  if (lda < K || ldb < K || ldc < N || (R && ldr < N))
+    return as_fail(ctx, AS_ERR_SHAPE, "as_op_gemm_rows: leading dimension smaller than the row length");
+  GemmParams g; memset(&g, 0, sizeof g);
+  g.seg[0] = {A, B, lda, ldb, (int)K}; g.nseg = 1;
+  g.M = (int)M; g.N = (int)N; g.C = C; g.ldc = ldc; g.c_f32 = c_is_f32; g.alpha = alpha; g.R = R; g.ldr = ldr; g.splitk = 1;
+  g.m_dev = d_rows; g.grp_off = d_group_off; g.grp = group; g.rows_cap = (int)rows_cap;
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  return launch_gemm_off(ctx, mode, variant, g, (int)row_off, (hipStream_t)stream);
 }
 
 extern "C" int as_op_rmsnorm_fwd(as_ctx* ctx, int mode, int64_t n, int64_t d, const void* x, const void* g,

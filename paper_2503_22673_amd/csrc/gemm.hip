@@ -551,12 +551,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
 // offsets: nothing to keep in registers besides the accumulators (the element-wise epilogue above, unrolled over
 // 256 accumulators per lane, spills, and on this chip a spill reload waits for every store in flight).
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
-template <int TM, int TN>
-__device__ __forceinline__ void gemm_epilogue_rows(const GemmParams& p, f32x16 (&acc)[TM][TN], int row_lane, int col_lane) {
+template <int TM, int TN, bool MASK = false>
+__device__ __forceinline__ void gemm_epilogue_rows(const GemmParams& p, f32x16 (&acc)[TM][TN], int row_lane, int col_lane,
+                                                   int row_lo = 0, int row_hi = 0) {
   const float alpha = p.alpha;
 #pragma unroll
   for (int i = 0; i < TM; i++) {
     const int64_t r = row_lane + 32 * i;
+    if (MASK && (r < row_lo || r >= row_hi)) continue;   // with MASK only rows row_lo .. row_hi - 1 are written (and read)
     if (p.c_f32) {
       float* c = (float*)p.C + r * p.ldc + col_lane;
       const bf16_t* rr = p.R ? (const bf16_t*)p.R + r * p.ldr + col_lane : nullptr;
@@ -604,9 +606,9 @@ __device__ __forceinline__ void gemm_epilogue_rows(const GemmParams& p, f32x16 (
 // the tile memory, which is free once every wave has left the loop, and reads it back 16 bytes per lane, so that a store
 // instruction writes four whole 256-byte row pieces.  Rows are 272 bytes apart in LDS.  The residual takes the same way
 // in: loaded 16 bytes per lane, parked at the place of the result, picked up by the lane that owns the element.
-template <int TM, int TN>
+template <int TM, int TN, bool MASK = false>
 __device__ __forceinline__ void gemm_epilogue_staged(const GemmParams& p, f32x16 (&acc)[TM][TN], unsigned char* smem, int wave, int lane,
-                                                     int row_w0, int col_w0) {
+                                                     int row_w0, int col_w0, int row_lo = 0, int row_hi = 0) {
   constexpr int LROW = 272, ROWS = TM * 32;
   static_assert(TN * 32 == 128, "a block row is 256 bytes: 16 lanes of 16 bytes");
   unsigned char* my = smem + wave * (ROWS * LROW);
@@ -616,8 +618,11 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmParams& p, f32x16
   if (p.R) {
     const bf16_t* rr = (const bf16_t*)p.R + (int64_t)(row_w0 + r4) * p.ldr + col_w0 + c16 * 8;
 #pragma unroll 8
-    for (int it = 0; it < ROWS / 4; it++)
-      *reinterpret_cast<u32x4*>(my + (4 * it + r4) * LROW + c16 * 16) = *reinterpret_cast<const u32x4*>(rr + (int64_t)(4 * it) * p.ldr);
+    for (int it = 0; it < ROWS / 4; it++) {
+      const int r = row_w0 + 4 * it + r4;
+      if (!MASK || (r >= row_lo && r < row_hi))          // with MASK only rows row_lo .. row_hi - 1 are read and written
+        *reinterpret_cast<u32x4*>(my + (4 * it + r4) * LROW + c16 * 16) = *reinterpret_cast<const u32x4*>(rr + (int64_t)(4 * it) * p.ldr);
+    }
     __builtin_amdgcn_s_waitcnt(0xc07f);                  // lgkmcnt(0): LDS operations of a wave complete in order; this is for the compiler's sake
     asm volatile("" ::: "memory");
   }
@@ -643,8 +648,11 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmParams& p, f32x16
   asm volatile("" ::: "memory");
   bf16_t* c = (bf16_t*)p.C + (int64_t)(row_w0 + r4) * p.ldc + col_w0 + c16 * 8;
 #pragma unroll 8
-  for (int it = 0; it < ROWS / 4; it++)
-    *reinterpret_cast<u32x4*>(c + (int64_t)(4 * it) * p.ldc) = *reinterpret_cast<const u32x4*>(my + (4 * it + r4) * LROW + c16 * 16);
+  for (int it = 0; it < ROWS / 4; it++) {
+    const int r = row_w0 + 4 * it + r4;
+    if (!MASK || (r >= row_lo && r < row_hi))
+      *reinterpret_cast<u32x4*>(c + (int64_t)(4 * it) * p.ldc) = *reinterpret_cast<const u32x4*>(my + (4 * it + r4) * LROW + c16 * 16);
+  }
 }
 
 // Register-staged pipeline with a hand-scheduled loop, four waves of 128 x 128 (one per SIMD: the 256 accumulator
@@ -657,10 +665,20 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmParams& p, f32x16
 // instruction by instruction (gen_gemm_rs_loop.py -> gemm_rs_loop.inc).  LDS layout and fragment order are those
 // of the direct-to-LDS kernel.  Covers whole 256 x 256 tiles, K segments that are multiples of 64, host-side
 // row counts, no split-K; the launcher sends everything else to the other kernels.
+// LIVE = 1: the row count is a device-side value and / or the rows are those of one group (expert).  Tiles past the live
+// rows exit; a tile still computes 256 rows, moved up if need be so that they lie inside the `limit` rows the operands
+// are known to have (M for a plain row count, rows_cap for grouped rows), and writes the rows that are its own and live.
 #include "gemm_rs_loop.inc"
-__global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int tiles_m, int tiles_n) {
+template <int LIVE>
+__global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int m_off, int tiles_m, int tiles_n) {
   constexpr int BM = 256, BN = 256, BK = 64, TM = 4, TN = 4;
   extern __shared__ __align__(16) unsigned char smem[];
+  int rb = 0, mlive = p.M;
+  if (LIVE) {
+    int mmax;
+    mlive = gemm_rows(p, m_off, rb, mmax);
+    tiles_m = min(tiles_m, (max(mlive, 0) + BM - 1) / BM);
+  }
   int nblk = tiles_m * tiles_n, pid = blockIdx.x;
   if (pid >= nblk) return;
   int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
@@ -672,7 +690,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int til
   int in_group = GROUP * tiles_n, grp = logical / in_group, first_m = grp * GROUP;
   int gsize = min(tiles_m - first_m, GROUP);
   int tile_m = first_m + (logical % in_group) % gsize, tile_n = (logical % in_group) / gsize;
-  const int row0 = tile_m * BM, col0 = tile_n * BN;
+  const int row_lo = rb + tile_m * BM, row_hi = rb + mlive;                  // LIVE: the rows this tile writes
+  const int row0 = LIVE ? min(row_lo, (p.grp_off ? p.rows_cap : p.M) - BM) : tile_m * BM, col0 = tile_n * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, l31 = lane & 31, hh = lane >> 5, lrow = lane >> 3, lch = lane & 7;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -724,8 +743,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int til
   }
   // bf16 results with 16-byte rows leave through LDS (whole 256-byte row pieces per store), the rest row by row
   const bool staged = !p.c_f32 && !(p.ldc % 8) && (!p.R || (!(p.ldr % 8) && !((uintptr_t)p.R % 16)));
-  if (staged) gemm_epilogue_staged<TM, TN>(p, acc, smem, wave, lane, row0 + wm * TM * 32, col0 + wn * TN * 32);
-  else gemm_epilogue_rows<TM, TN>(p, acc, row0 + wm * TM * 32 + l31, col0 + wn * TN * 32 + 4 * hh);
+  if (staged) gemm_epilogue_staged<TM, TN, LIVE != 0>(p, acc, smem, wave, lane, row0 + wm * TM * 32, col0 + wn * TN * 32, row_lo, row_hi);
+  else gemm_epilogue_rows<TM, TN, LIVE != 0>(p, acc, row0 + wm * TM * 32 + l31, col0 + wn * TN * 32 + 4 * hh, row_lo, row_hi);
 }
 
 // Deep-pipeline variant: K steps of 32 (64-byte tile rows) and NS LDS stages, so that NS - 1 steps of tile loads
@@ -912,7 +931,8 @@ static int launch_dlds_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStrea
 
 // whole 256 x 256 tiles of a plain launch (host-side row count, no split-K, K segments in 64-wide steps, 16-byte rows)
 static bool rs_ok(const GemmParams& p) {
-  if (p.m_dev || p.grp_off || p.splitk > 1 || p.M < 256 || (p.N % 256)) return false;
+  if (p.splitk > 1 || p.M < 256 || (p.N % 256)) return false;
+  if (p.grp_off && p.rows_cap < 256) return false;       // grouped rows: the caller states how many rows the operands have
   // the epilogue stores four consecutive columns of a row at a time
   if ((p.ldc % 4) || ((uintptr_t)p.C % 16) || (p.R && ((p.ldr % 4) || ((uintptr_t)p.R % 8)))) return false;
   for (int s = 0; s < p.nseg; s++)
@@ -921,16 +941,25 @@ static bool rs_ok(const GemmParams& p) {
   return nt >= 1;
 }
 
-static int launch_rs_cfg(as_ctx* ctx, const GemmParams& p, hipStream_t st) {
-  constexpr size_t smem = 131072 + 256 * 64;             // two stages of A and B tiles + a 64-byte line per lane
+static bool rs_live(const GemmParams& p) { return p.m_dev || p.grp_off; }
+
+static int launch_rs_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_t st) {
+  constexpr size_t smem = 131072 + 256 * 64;             // two stages of A and B tiles + a 64-byte line per lane (the staged epilogue: 4 x 128 rows of 272 bytes)
   static bool attr_set = false;
   if (!attr_set) {
-    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mfma_rs_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mfma_rs_kernel<0>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mfma_rs_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_set = true;
   }
-  // whole row tiles only: the ragged last one too when the operands have the rows, else the caller handles the rest
-  const int tm = p.rows_cap >= (int)cdiv(p.M, 256) * 256 ? (int)cdiv(p.M, 256) : p.M / 256, tn = p.N / 256;
-  gemm_mfma_rs_kernel<<<dim3(tm * tn), 256, smem, st>>>(p, tm, tn);
+  const int tn = p.N / 256;
+  if (rs_live(p)) {                                      // every row tile the live rows can reach; the kernel drops the rest
+    const int tm = (int)cdiv(p.M, 256);
+    gemm_mfma_rs_kernel<1><<<dim3(tm * tn), 256, smem, st>>>(p, m_off, tm, tn);
+  } else {
+    // whole row tiles only: the ragged last one too when the operands have the rows, else the caller handles the rest
+    const int tm = p.rows_cap >= (int)cdiv(p.M, 256) * 256 ? (int)cdiv(p.M, 256) : p.M / 256;
+    gemm_mfma_rs_kernel<0><<<dim3(tm * tn), 256, smem, st>>>(p, 0, tm, tn);
+  }
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
@@ -997,7 +1026,7 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
   int cfg = variant >= 10 ? variant - 10 : pick_cfg(p);
   if (cfg >= 7) for (int s = 0; s < p.nseg; s++) if (p.seg[s].K % 64) cfg = 0;     // direct-to-LDS tiles need whole 64-wide K steps
   const bool big = use_mfma && (cfg == 0 || cfg >= 4);
-  const bool rs = use_mfma && cfg == 24 && rs_ok(p) && !m_off;
+  const bool rs = use_mfma && cfg == 24 && rs_ok(p) && !rs_live(p) && !m_off;     // live-row launches keep their own timing classes
   prof_begin(ctx, st, rs ? AS_K_GEMM_RS : p.grp_off ? AS_K_GEMM_GROUPED : p.m_dev ? AS_K_GEMM_DEVROWS : !use_mfma ? AS_K_GEMM_FMA : big ? AS_K_GEMM_MFMA_256 : AS_K_GEMM_MFMA_SKINNY,
              p.grp_off ? 2.0 * p.grp_rows * p.N * ksum : p.m_dev ? 0.0 : 2.0 * p.M * p.N * ksum);
   if (use_mfma) {
@@ -1026,8 +1055,9 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
       case 22: rc = launch_deep_cfg<256, 256, 2, 4, 4>(ctx, p, m_off, st); break;
       case 23: rc = launch_deep_cfg<256, 128, 2, 2, 3>(ctx, p, m_off, st); break;
       case 24: {                                           // whole row tiles by the register-staged kernel, the ragged rest by the default one
-        if (!rs_ok(p) || m_off) { rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 200>(ctx, p, m_off, st); break; }
-        rc = launch_rs_cfg(ctx, p, st);
+        if (!rs_ok(p) || (m_off && !p.m_dev)) { rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 200>(ctx, p, m_off, st); break; }
+        rc = launch_rs_cfg(ctx, p, m_off, st);
+        if (rs_live(p)) break;                             // covers its ragged tiles itself
         const int done = p.rows_cap >= (int)cdiv(p.M, 256) * 256 ? p.M : p.M / 256 * 256;
         if (!rc && done < p.M) {
           GemmParams t = p;

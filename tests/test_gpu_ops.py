@@ -81,6 +81,62 @@ def test_hand_scheduled_gemm_bf16_output(shape, with_residual):
     assert torch.equal(out, other)
 
 
+@pytest.mark.parametrize("out_f32", [False, True])
+@pytest.mark.parametrize("variant", [0, 30, 34])
+@pytest.mark.parametrize("row_off,live", [(0, 700), (128, 896), (0, 0), (256, 1)])
+def test_gemm_over_a_device_side_row_count(variant, out_f32, row_off, live):
+    """rows row_off .. row_off + live - 1 are computed (the count lives on the device), the others keep their contents;
+    variant 34 is the hand-scheduled kernel, which moves its last, ragged tile up inside the M rows it may read"""
+    B, G, ctx, _ = _env()
+    M, N, K = 1024, 512, 192
+    g = synth.rng(6, 20)
+    A, W, R = (G.quantise(g.standard_normal(s), True) for s in ((M, K), (N, K), (M, N)))
+    dt = torch.bfloat16
+    dA, dW, dR = G.to_dev(A, dt), G.to_dev(W, dt), G.to_dev(R, dt)
+    Cm = torch.full((M, N), 7.0, dtype=torch.float32 if out_f32 else dt, device="cuda")
+    rows = torch.tensor([row_off + live], dtype=torch.int32, device="cuda")
+    ctx.op_gemm_rows(dA[row_off:], dW, Cm[row_off:], alpha=0.5, R=dR[row_off:], d_rows=rows, row_off=row_off, M=M - row_off,
+                     variant=variant, mode=B.AS_BF16)
+    torch.cuda.synchronize()
+    got = G.to_np(Cm)
+    ref = np.full((M, N), 7.0)
+    ref[row_off:row_off + live] = 0.5 * (A[row_off:row_off + live] @ W.T) + R[row_off:row_off + live]
+    assert np.array_equal(got[:row_off], ref[:row_off]) and np.array_equal(got[row_off + live:], ref[row_off + live:])
+    tol = 1e-5 if out_f32 else 2.0 ** -8
+    assert np.all(np.abs(got - ref) <= tol * np.abs(ref) + 1e-4 * K ** 0.5)
+
+
+@pytest.mark.parametrize("out_f32", [False, True])
+@pytest.mark.parametrize("variant", [0, 30, 34])
+def test_gemm_over_the_rows_of_one_group(variant, out_f32):
+    """one launch per group of rows (an expert's rows), the table on the device: an empty group, ragged ones, and a last
+    group whose final tile would reach past the rows_cap rows of the buffers"""
+    B, G, ctx, _ = _env()
+    cap, N, K = 1300, 256, 128
+    off_host = [0, 300, 300, 1000, 1300]
+    g = synth.rng(7, 20)
+    A, R = G.quantise(g.standard_normal((cap, K)), True), G.quantise(g.standard_normal((cap, N)), True)
+    Ws = [G.quantise(g.standard_normal((N, K)), True) for _ in range(4)]
+    dt = torch.bfloat16
+    dA, dR = G.to_dev(A, dt), G.to_dev(R, dt)
+    Cm = torch.full((cap, N), 7.0, dtype=torch.float32 if out_f32 else dt, device="cuda")
+    off = torch.tensor(off_host, dtype=torch.int32, device="cuda")
+    ref = np.full((cap, N), 7.0)
+    for e in (2, 0, 1):                                   # group 3 is left out: its rows must stay untouched
+        ctx.op_gemm_rows(dA, G.to_dev(Ws[e], dt), Cm, R=dR, d_group_off=off, group=e, rows_cap=cap, M=cap, variant=variant, mode=B.AS_BF16)
+        ref[off_host[e]:off_host[e + 1]] = A[off_host[e]:off_host[e + 1]] @ Ws[e].T + R[off_host[e]:off_host[e + 1]]
+    torch.cuda.synchronize()
+    got = G.to_np(Cm)
+    assert np.array_equal(got[1000:], ref[1000:])
+    tol = 1e-5 if out_f32 else 2.0 ** -8
+    assert np.all(np.abs(got - ref) <= tol * np.abs(ref) + 1e-4 * K ** 0.5)
+    ctx.op_gemm_rows(dA, G.to_dev(Ws[3], dt), Cm, R=dR, d_group_off=off, group=3, rows_cap=cap, M=cap, variant=variant, mode=B.AS_BF16)
+    torch.cuda.synchronize()
+    got = G.to_np(Cm)
+    ref[1000:] = A[1000:] @ Ws[3].T + R[1000:]
+    assert np.all(np.abs(got - ref) <= tol * np.abs(ref) + 1e-4 * K ** 0.5)
+
+
 def test_gemm_mfma_typed_output_and_strides():
     B, G, ctx, _ = _env()
     g = synth.rng(2, 20)

@@ -337,6 +337,10 @@ int as_op_gemm(as_ctx* ctx, int mode, int variant, int64_t M, int64_t N,
  *   d_group_off  [device] int32 table, may be NULL: the product covers rows
  *                d_group_off[group] .. d_group_off[group + 1] - 1 (at most M
  *                of them) of A, R and C.
+ *   n_groups     > 0: every group 0 .. n_groups - 1 in one call (`group` is
+ *                ignored, d_rows must be NULL, row_off 0); group e multiplies
+ *                with the matrix that starts group_b_stride elements after
+ *                that of group e - 1, B being that of group 0.
  *   rows_cap     with d_group_off: the number of rows A, R and C have (0 = not
  *                stated; kernels that read whole row tiles then stay out).
  * Rows outside the live range are neither read into the result nor written.
@@ -345,8 +349,8 @@ int as_op_gemm(as_ctx* ctx, int mode, int variant, int64_t M, int64_t N,
 int as_op_gemm_rows(as_ctx* ctx, int mode, int variant, int64_t M, int64_t N,
                     const void* A, int64_t lda, const void* B, int64_t ldb, int64_t K,
                     float alpha, const void* R, int64_t ldr, void* C, int64_t ldc, int c_is_f32,
-                    const int32_t* d_rows, int64_t row_off, const int32_t* d_group_off, int group, int64_t rows_cap,
-                    void* stream);
+                    const int32_t* d_rows, int64_t row_off, const int32_t* d_group_off, int group, int n_groups,
+                    int64_t group_b_stride, int64_t rows_cap, void* stream);
 
 /* y = x * rstd * g with rstd = (mean x^2 + eps)^-1/2 per row; rstd float[n]. */
 int as_op_rmsnorm_fwd(as_ctx* ctx, int mode, int64_t n, int64_t d, const void* x, const void* g,

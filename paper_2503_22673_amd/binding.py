@@ -87,7 +87,7 @@ lib.as_adamw_update.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i
 lib.as_op_gemm.argtypes = [_vp, C.c_int, C.c_int, _i64, _i64, _vp, _i64, _vp, _i64, _i64, _vp, _i64, _vp, _i64, _i64,
                            _f32, _vp, _i64, _vp, _i64, C.c_int, _vp]
 lib.as_op_gemm_rows.argtypes = [_vp, C.c_int, C.c_int, _i64, _i64, _vp, _i64, _vp, _i64, _i64, _f32, _vp, _i64, _vp, _i64, C.c_int,
-                                _vp, _i64, _vp, C.c_int, _i64, _vp]
+                                _vp, _i64, _vp, C.c_int, C.c_int, _i64, _i64, _vp]
 lib.as_op_rmsnorm_fwd.argtypes = [_vp, C.c_int, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _vp]
 lib.as_op_rmsnorm_bwd.argtypes = [_vp, C.c_int, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.as_op_attention_fwd.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _vp]
@@ -320,13 +320,16 @@ class Context:
         return Cm
 
     def op_gemm_rows(self, A, Bm, Cm, alpha=1.0, R=None, d_rows=None, row_off=0, d_group_off=None, group=0, rows_cap=0, M=None,
-                     variant=0, mode=None):
+                     n_groups=0, variant=0, mode=None):
         """Cm (caller's buffer, float32 or A's type) receives the live rows of alpha * A Bm^T (+ R); the other rows stay as they are."""
         mode = self.mode if mode is None else mode
         M = A.shape[0] if M is None else M
-        self.check(lib.as_op_gemm_rows(self.handle, mode, variant, M, Bm.shape[0], _ptr(A), A.stride(0), _ptr(Bm), Bm.stride(0), A.shape[1],
+        # n_groups > 0: Bm is [n_groups, N, K], the stacked matrices of the groups
+        N, ldb, stride = (Bm.shape[1], Bm.stride(1), Bm.stride(0)) if n_groups else (Bm.shape[0], Bm.stride(0), 0)
+        self.check(lib.as_op_gemm_rows(self.handle, mode, variant, M, N, _ptr(A), A.stride(0), _ptr(Bm), ldb, A.shape[1],
                                        alpha, _ptr(R), R.stride(0) if R is not None else 0, _ptr(Cm), Cm.stride(0),
-                                       int(Cm.dtype == torch.float32), _ptr(d_rows), row_off, _ptr(d_group_off), group, rows_cap, _stream()))
+                                       int(Cm.dtype == torch.float32), _ptr(d_rows), row_off, _ptr(d_group_off), group, n_groups, stride,
+                                       rows_cap, _stream()))
         return Cm
 
     def nf4_quantize(self, w):

@@ -493,7 +493,7 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   P.du_qkv = w.take(N * P.n_qkv * rp * es); P.du_o = w.take(on(AS_T_O) ? N * rp * es : 0);
   P.du_gu = w.take(N * P.n_gu * rp * es); P.du_d = w.take(on(AS_T_DOWN) ? N * rp * es : 0);
   size_t wmax = std::max({(size_t)P.QKV * P.d, (size_t)P.d * P.D, (size_t)2 * P.F * P.d, (size_t)P.d * P.F});
-  P.wT = w.take(wmax * es);
+  P.wT = w.take(wmax * (moe ? E : 1) * es);            // sparse models: the transposed matrices of all experts at once
   P.wdq = w.take(c.weight_format == AS_W_NF4 ? std::max((size_t)P.F * P.d, (size_t)P.D * P.d) * es : 0);
   P.xbp = w.take(moe ? 2 * N * P.d * es : 0); P.dlogit = w.take(N * E * es);
   P.du_r = w.take(on(AS_T_ROUTER) ? N * rp * es : 0); P.wrT = w.take((size_t)P.d * E * es);
@@ -676,12 +676,13 @@ struct Step {
     return AS_OK;
   }
 
-  // one product over the rows of expert e only: rows eoff[e] .. eoff[e+1] of A and C
-  int gemm_expert(const int32_t* eoff, int e, int N, const void* A, int64_t lda, const void* B, int64_t ldb, int K, void* C, int64_t ldc) {
+  // every expert's product over its own rows: rows eoff[e] .. eoff[e+1] of A and C times the e-th of the stacked
+  // matrices at B (b_stride elements apart); one launch where the kernel allows, else one per expert
+  int gemm_experts(const int32_t* eoff, int N, const void* A, int64_t lda, const void* B, int64_t b_stride, int64_t ldb, int K, void* C, int64_t ldc) {
     GemmParams g; memset(&g, 0, sizeof g);
     g.seg[0] = {A, B, lda, ldb, K}; g.nseg = 1;
     g.M = P.N; g.N = N; g.C = C; g.ldc = ldc; g.alpha = 1.f; g.splitk = 1;
-    g.grp_off = eoff; g.grp = e; g.grp_rows = 2.0 * P.N / c.n_experts;
+    g.grp_off = eoff; g.grp_n = c.n_experts; g.grp_b_stride = b_stride; g.grp_rows = 2.0 * P.N;
     g.rows_cap = 2 * P.N;                                  // A and C are (token, slot) buffers: 2 N rows
     return launch_gemm_off(ctx, mode, gv, g, 0, st);
   }
@@ -699,12 +700,10 @@ struct Step {
     if ((rc = launch_moe_permute(ctx, a.sel, N, E, a.eoff, a.pos, a.perm, st))) return rc;
     if ((rc = launch_moe_gather(ctx, mode, a.b, a.perm, nullptr, 2 * N, d, P.xbp, st))) return rc;
     const void* wg[2] = {w.wgate, w.wup};
-    for (int e = 0; e < E; e++)
-      for (int i = 0; i < 2; i++)
-        if ((rc = gemm_expert(a.eoff, e, F, P.xbp, d, off(wg[i], (size_t)e * F * d), d, d, off(a.gu, (size_t)i * F), 2 * F))) return rc;
+    for (int i = 0; i < 2; i++)
+      if ((rc = gemm_experts(a.eoff, F, P.xbp, d, wg[i], (int64_t)F * d, d, d, off(a.gu, (size_t)i * F), 2 * F))) return rc;
     if ((rc = launch_swiglu_fwd(ctx, mode, 2 * N, F, a.gu, a.m, st))) return rc;
-    for (int e = 0; e < E; e++)
-      if ((rc = gemm_expert(a.eoff, e, d, a.m, F, off(w.wdown, (size_t)e * d * F), F, F, a.y_perm, d))) return rc;
+    if ((rc = gemm_experts(a.eoff, d, a.m, F, w.wdown, (int64_t)d * F, F, F, a.y_perm, d))) return rc;
     return launch_moe_combine(ctx, mode, a.h_mid, a.y_perm, a.pos, a.wsel, N, d, P.h[l + 1], st);
   }
 
@@ -715,16 +714,17 @@ struct Step {
     int rc;
     if ((rc = launch_moe_dlogit(ctx, mode, P.dh, a.y_perm, a.pos, a.sel, a.wsel, N, d, E, P.dlogit, st))) return rc;
     if ((rc = launch_moe_gather(ctx, mode, P.dh, a.perm, a.wsel, 2 * N, d, P.xbp, st))) return rc;        // w * dy, grouped
-    for (int e = 0; e < E; e++) {
-      if ((rc = transpose(d, F, off(w.wdown, (size_t)e * d * F), F, P.wT, d))) return rc;                 // [F, d]
-      if ((rc = gemm_expert(a.eoff, e, F, P.xbp, d, P.wT, d, d, P.dm, F))) return rc;
-    }
+    // the transposed matrices of all experts side by side (the workspace slot holds E of them), then one product each
+    for (int e = 0; e < E; e++)
+      if ((rc = transpose(d, F, off(w.wdown, (size_t)e * d * F), F, off(P.wT, (size_t)e * F * d), d))) return rc;      // [F, d]
+    if ((rc = gemm_experts(a.eoff, F, P.xbp, d, P.wT, (int64_t)F * d, d, d, P.dm, F))) return rc;
     if ((rc = launch_swiglu_bwd(ctx, mode, 2 * N, F, P.dm, a.gu, P.dgu, nullptr, st))) return rc;
     for (int e = 0; e < E; e++) {
-      if ((rc = transpose(F, d, off(w.wgate, (size_t)e * F * d), d, P.wT, 2 * F))) return rc;             // [d, 2F]
-      if ((rc = transpose(F, d, off(w.wup, (size_t)e * F * d), d, off(P.wT, (size_t)F), 2 * F))) return rc;
-      if ((rc = gemm_expert(a.eoff, e, d, P.dgu, 2 * F, P.wT, 2 * F, 2 * F, P.xbp, d))) return rc;        // grouped gradient of the expert inputs
+      void* wt = off(P.wT, (size_t)e * 2 * F * d);
+      if ((rc = transpose(F, d, off(w.wgate, (size_t)e * F * d), d, wt, 2 * F))) return rc;               // [d, 2F]
+      if ((rc = transpose(F, d, off(w.wup, (size_t)e * F * d), d, off(wt, (size_t)F), 2 * F))) return rc;
     }
+    if ((rc = gemm_experts(a.eoff, d, P.dgu, 2 * F, P.wT, (int64_t)2 * F * d, 2 * F, 2 * F, P.xbp, d))) return rc;     // grouped gradient of the expert inputs
     if ((rc = launch_moe_combine(ctx, mode, nullptr, P.xbp, a.pos, nullptr, N, d, P.da, st))) return rc;  // back to token order
     // router: db = (expert part) + dlogit Wr + du_r A
     LoraSlot& s = slot(l, AS_T_ROUTER);
@@ -1317,21 +1317,22 @@ extern "C" int as_op_gemm(as_ctx* ctx, int mode, int variant, int64_t M, int64_t
 extern "C" int as_op_gemm_rows(as_ctx* ctx, int mode, int variant, int64_t M, int64_t N,
                                const void* A, int64_t lda, const void* B, int64_t ldb, int64_t K,
                                float alpha, const void* R, int64_t ldr, void* C, int64_t ldc, int c_is_f32,
-                               const int32_t* d_rows, int64_t row_off, const int32_t* d_group_off, int group, int64_t rows_cap,
-                               void* stream) {
+                               const int32_t* d_rows, int64_t row_off, const int32_t* d_group_off, int group, int n_groups,
+                               int64_t group_b_stride, int64_t rows_cap, void* stream) {
   if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_op_gemm_rows: NULL context");
   int rc = check_mode(ctx, mode); if (rc) return rc;
   if (!A || !B || !C) return as_fail(ctx, AS_ERR_NULL, "as_op_gemm_rows: NULL operand");
   if (!d_rows && !d_group_off) return as_fail(ctx, AS_ERR_NULL, "as_op_gemm_rows: a device row count or a group table is required");
   if (M < 0 || N < 0 || K < 0 || M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || row_off < 0 || row_off > INT32_MAX ||
-      rows_cap < 0 || rows_cap > INT32_MAX || group < 0)
+      rows_cap < 0 || rows_cap > INT32_MAX || group < 0 || n_groups < 0 || group_b_stride < 0)
     return as_fail(ctx, AS_ERR_SHAPE, "as_op_gemm_rows: sizes must be in [0, 2^31)");
+  if (n_groups > 0 && (!d_group_off || d_rows || row_off)) return as_fail(ctx, AS_ERR_SHAPE, "as_op_gemm_rows: all groups at once need the group table alone");
   if (lda < K || ldb < K || ldc < N || (R && ldr < N))
     return as_fail(ctx, AS_ERR_SHAPE, "as_op_gemm_rows: leading dimension smaller than the row length");
   GemmParams g; memset(&g, 0, sizeof g);
   g.seg[0] = {A, B, lda, ldb, (int)K}; g.nseg = 1;
   g.M = (int)M; g.N = (int)N; g.C = C; g.ldc = ldc; g.c_f32 = c_is_f32; g.alpha = alpha; g.R = R; g.ldr = ldr; g.splitk = 1;
-  g.m_dev = d_rows; g.grp_off = d_group_off; g.grp = group; g.rows_cap = (int)rows_cap;
+  g.m_dev = d_rows; g.grp_off = d_group_off; g.grp = group; g.rows_cap = (int)rows_cap; g.grp_n = n_groups; g.grp_b_stride = group_b_stride;
   AS_HIP(ctx, hipSetDevice(ctx->device));
   return launch_gemm_off(ctx, mode, variant, g, (int)row_off, (hipStream_t)stream);
 }

@@ -79,7 +79,10 @@ struct GemmParams {
   // grouped rows (mixture of experts): with grp_off set, the product covers rows
   // [grp_off[grp], grp_off[grp+1]) of A, R and C (device-side table), at most M of them
   const int* grp_off; int grp;
-  double grp_rows;            // expected live rows of the group (timing records only)
+  double grp_rows;            // expected live rows of the launch (timing records only)
+  // grp_n > 0: ALL groups 0 .. grp_n - 1 in one launch (grp is ignored); group e multiplies with the matrix that
+  // starts grp_b_stride elements after that of group e - 1 (B of segment 0; one segment only)
+  int grp_n; int64_t grp_b_stride;
   // rows that every row operand (A of each segment, R, C) really has allocated, or 0: lets a kernel that works in
   // whole 256-row tiles run over the ragged last tile too (rows past M are computed from whatever is there and
   // written to rows past M of C; no row of the result depends on another row)

@@ -675,9 +675,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int m_o
   extern __shared__ __align__(16) unsigned char smem[];
   int rb = 0, mlive = p.M;
   if (LIVE) {
-    int mmax;
-    mlive = gemm_rows(p, m_off, rb, mmax);
-    tiles_m = min(tiles_m, (max(mlive, 0) + BM - 1) / BM);
+    if (p.grp_n > 0) {                                   // the live row tiles of all groups, one group after the other
+      int total = 0;
+      for (int e = 0; e < p.grp_n; e++) total += (p.grp_off[e + 1] - p.grp_off[e] + BM - 1) / BM;
+      tiles_m = min(tiles_m, total);
+    } else {
+      int mmax;
+      mlive = gemm_rows(p, m_off, rb, mmax);
+      tiles_m = min(tiles_m, (max(mlive, 0) + BM - 1) / BM);
+    }
   }
   int nblk = tiles_m * tiles_n, pid = blockIdx.x;
   if (pid >= nblk) return;
@@ -690,6 +696,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int m_o
   int in_group = GROUP * tiles_n, grp = logical / in_group, first_m = grp * GROUP;
   int gsize = min(tiles_m - first_m, GROUP);
   int tile_m = first_m + (logical % in_group) % gsize, tile_n = (logical % in_group) / gsize;
+  int b_group = 0;
+  if (LIVE && p.grp_n > 0) {                             // which group this row tile belongs to, and which of its tiles it is
+    int e = 0, rows_e = p.grp_off[1] - p.grp_off[0], nt_e = (rows_e + BM - 1) / BM;
+    while (tile_m >= nt_e && e + 1 < p.grp_n) {
+      tile_m -= nt_e; e++;
+      rows_e = p.grp_off[e + 1] - p.grp_off[e]; nt_e = (rows_e + BM - 1) / BM;
+    }
+    rb = p.grp_off[e]; mlive = rows_e; b_group = e;
+  }
   const int row_lo = rb + tile_m * BM, row_hi = rb + mlive;                  // LIVE: the rows this tile writes
   const int row0 = LIVE ? min(row_lo, (p.grp_off ? p.rows_cap : p.M) - BM) : tile_m * BM, col0 = tile_n * BN;
 
@@ -729,7 +744,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int m_o
     const unsigned scratch_addr = 131072u + (unsigned)tid * 64u;
     // wave-uniform operand bases: first of the wave's 64 rows of the tile, first K step
     const uint64_t A0 = (uint64_t)((const bf16_t*)s0.A + (int64_t)(row0 + wave * 64) * s0.lda);
-    const uint64_t B0 = (uint64_t)((const bf16_t*)s0.B + (int64_t)(col0 + wave * 64) * s0.ldb);
+    const uint64_t B0 = (uint64_t)((const bf16_t*)s0.B + (int64_t)b_group * p.grp_b_stride + (int64_t)(col0 + wave * 64) * s0.ldb);
     const uint64_t A1 = (uint64_t)((const bf16_t*)s1.A + (int64_t)(row0 + wave * 64) * s1.lda);
     const uint64_t B1 = (uint64_t)((const bf16_t*)s1.B + (int64_t)(col0 + wave * 64) * s1.ldb);
     const int sA0 = (int)(16 * s0.lda), sB0 = (int)(16 * s0.ldb), sA1 = (int)(16 * s1.lda), sB1 = (int)(16 * s1.ldb);   // 8 rows, bytes
@@ -933,6 +948,7 @@ static int launch_dlds_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStrea
 static bool rs_ok(const GemmParams& p) {
   if (p.splitk > 1 || p.M < 256 || (p.N % 256)) return false;
   if (p.grp_off && p.rows_cap < 256) return false;       // grouped rows: the caller states how many rows the operands have
+  if (p.grp_n > 0 && (p.nseg != 1 || p.m_dev)) return false;
   // the epilogue stores four consecutive columns of a row at a time
   if ((p.ldc % 4) || ((uintptr_t)p.C % 16) || (p.R && ((p.ldr % 4) || ((uintptr_t)p.R % 8)))) return false;
   for (int s = 0; s < p.nseg; s++)
@@ -953,7 +969,7 @@ static int launch_rs_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_
   }
   const int tn = p.N / 256;
   if (rs_live(p)) {                                      // every row tile the live rows can reach; the kernel drops the rest
-    const int tm = (int)cdiv(p.M, 256);
+    const int tm = p.grp_n > 0 ? (int)cdiv(p.rows_cap, 256) + p.grp_n : (int)cdiv(p.M, 256);
     gemm_mfma_rs_kernel<1><<<dim3(tm * tn), 256, smem, st>>>(p, m_off, tm, tn);
   } else {
     // whole row tiles only: the ragged last one too when the operands have the rows, else the caller handles the rest
@@ -1018,6 +1034,20 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
   if (p.splitk > 1 && !p.partial) return as_fail(ctx, AS_ERR_WORKSPACE, "gemm: split-K needs a partial buffer");
   if (p.accumulate && !p.c_f32) return as_fail(ctx, AS_ERR_SHAPE, "gemm: accumulate needs float output");
   if (p.grp_off && p.splitk > 1) return as_fail(ctx, AS_ERR_SHAPE, "gemm: grouped rows and split-K do not combine");
+  if (p.grp_n > 0) {
+    if (!p.grp_off || p.nseg != 1 || p.m_dev || m_off) return as_fail(ctx, AS_ERR_SHAPE, "gemm: all groups in one launch need a group table and one K segment");
+    const int c0 = variant >= 10 ? variant - 10 : pick_cfg(p);
+    if (!(mode == AS_BF16 && variant != 1 && mfma_ok(p) && c0 == 24 && rs_ok(p))) {       // one launch per group
+      const size_t esz = mode == AS_BF16 ? 2 : 4;
+      for (int e = 0; e < p.grp_n; e++) {
+        GemmParams q = p; q.grp_n = 0; q.grp = e; q.grp_rows = p.grp_rows / p.grp_n;
+        q.seg[0].B = (const char*)p.seg[0].B + (size_t)e * p.grp_b_stride * esz;
+        const int rc1 = launch_gemm_off(ctx, mode, variant, q, 0, st);
+        if (rc1) return rc1;
+      }
+      return AS_OK;
+    }
+  }
   if (variant < 0 || (variant > 2 && (variant < 10 || variant > 34))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
   bool use_mfma = (mode == AS_BF16) && variant != 1 && mfma_ok(p);
   if (variant >= 2 && !use_mfma) return as_fail(ctx, AS_ERR_SHAPE, "gemm: MFMA kernel needs bf16 and 8-element alignment");

@@ -135,6 +135,17 @@ def test_gemm_over_the_rows_of_one_group(variant, out_f32):
     got = G.to_np(Cm)
     ref[1000:] = A[1000:] @ Ws[3].T + R[1000:]
     assert np.all(np.abs(got - ref) <= tol * np.abs(ref) + 1e-4 * K ** 0.5)
+    # every group in one call, the matrices stacked
+    C2 = torch.full((cap, N), 7.0, dtype=Cm.dtype, device="cuda")
+    ctx.op_gemm_rows(dA, G.to_dev(np.stack(Ws), dt), C2, R=dR, d_group_off=off, n_groups=4, rows_cap=cap, M=cap, variant=variant, mode=B.AS_BF16)
+    torch.cuda.synchronize()
+    assert torch.equal(C2, Cm)
+    # ... and with a table that leaves rows out at both ends
+    off2 = torch.tensor([40, 300, 300, 1000, 1290], dtype=torch.int32, device="cuda")
+    C3 = torch.full((cap, N), 7.0, dtype=Cm.dtype, device="cuda")
+    ctx.op_gemm_rows(dA, G.to_dev(np.stack(Ws), dt), C3, R=dR, d_group_off=off2, n_groups=4, rows_cap=cap, M=cap, variant=variant, mode=B.AS_BF16)
+    torch.cuda.synchronize()
+    assert torch.equal(C3[40:1290], Cm[40:1290]) and bool((C3[:40] == 7.0).all()) and bool((C3[1290:] == 7.0).all())
 
 
 def test_gemm_mfma_typed_output_and_strides():

@@ -161,17 +161,30 @@ def test_per_kernel_timing_brackets_nested_launchers():
 
 
 @pytest.mark.parametrize("row_len", [384, 320])
-def test_long_contraction_uses_the_hand_scheduled_gemm(row_len):
-    """ffn = 8192: the down projection (K = 8192) and the gate / up input gradient (K = 16384) go through the
-    register-staged hand-scheduled kernel.  With rows of 384 the activation buffers hold 768 rows and the kernel
-    covers the ragged last row tile itself; with rows of 320 (640 rows) the rest goes to the other kernel."""
+def test_wide_ffn_step_runs_the_hand_scheduled_gemm(row_len):
+    """ffn = 11264 with 3 row tiles makes 132 tiles of 256 x 256: the gate / up projections and the input gradient of
+    the down projection (rank-64 adapter term as second K segment) go through the hand-scheduled kernel inside the
+    step.  With rows of 384 the activation buffers hold 768 rows and the kernel covers the ragged last row tile itself
+    (from the padded rows); with rows of 320 (640 rows) the ragged rest goes to the eight-wave kernel."""
     import gpu_util as G
-    sh = synth.CONFIGS[1].replace(n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=64, d_model=256, ffn=8192, vocab=512,
-                                  lora_targets=synth.DENSE_TARGETS7, lora_rank=16, lora_alpha=32.0)
+    from paper_2503_22673_amd import binding as B
+    sh = synth.CONFIGS[1].replace(n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=64, d_model=256, ffn=11264, vocab=512,
+                                  lora_targets=synth.DENSE_TARGETS7, lora_rank=64, lora_alpha=128.0)
     trajs = random_trajs(11, 8, sh.vocab, turn_lo=12, turn_hi=30, turns=(3, 5))
     pk = oracle.pack(trajs, row_len, 2)
     cu = pk["cu_seqlens"]
     live = sum(int(b - a) for a, b in zip(cu[:-1], cu[1:]) if pk["loss_mask"][a + 1:b].any())      # rows left after the pad tails are squeezed out
     assert live > 512 and live % 256 != 0 and (live + 255) // 256 * 256 == 768
     rep = G.compare_step(sh, 4, trajs, 2, row_len, bf16=True, loss_tol=2e-3, grad_tol=3e-2)
-    print("ffn 8192, rows of %d: loss rel %.2e worst grad %.2e" % (row_len, rep["loss_rel"], rep["worst_grad"]))
+    print("ffn 11264, rows of %d: loss rel %.2e worst grad %.2e" % (row_len, rep["loss_rel"], rep["worst_grad"]))
+    # the same step once more with per-launch timing on: the hand-scheduled kernel took launches, and the bits are the same
+    params, lora = G.quantise_params(synth.weights(sh, 4), True), G.quantise_lora(synth.lora_weights(sh, 4))
+    a, ma, dpk, ctx = G.run_step(sh, params, lora, trajs, 2, row_len, mode=B.AS_BF16)
+    ctx.profile(True)
+    ws = torch.empty(ctx.workspace_bytes(2, row_len), dtype=torch.uint8, device="cuda")
+    out = ctx.train_step(ma, dpk["tokens"], dpk["cu_seqlens"], dpk["cu_seqlens"].cpu().numpy(), dpk["loss_mask"], 2, row_len, ws,
+                         seg_skip=dpk["seg_skip"])
+    prof = ctx.profile_read()
+    ctx.profile(False)
+    assert float(out["loss"].item()) == a["loss"] == rep["loss"]
+    assert prof["gemm_mfma_rs"][0] >= 6, prof["gemm_mfma_rs"]                 # 2 layers x (gate, up, dX of down)

@@ -100,11 +100,15 @@ __global__ void tn_reduce_kernel(const float* __restrict__ partial, int splits, 
 }
 }  // namespace
 
-size_t lora_grad_tn_partial_floats(int n, int M, int r) {
-  const int steps = (int)cdiv(n, 32), slabs = (int)cdiv(M, 128);
-  int splits = (int)std::max<int64_t>(1, std::min<int64_t>(cdiv(1024, slabs), cdiv(steps, 16)));
-  return (size_t)splits * M * r;
+// One workgroup fits a CU (the accumulators fill the register file): the token range is split so that the launch is one
+// round of at most 256 workgroups (14336 columns: 28 x 9 = 252 workgroups; with 28 x 10 the last 24 ran alone and the
+// launch took half as long again).
+static int tn_splits(int n, int M) {
+  const int steps = (int)cdiv(n, 32), wg_cols = (int)cdiv(cdiv(M, 128), 4);
+  return (int)std::max<int64_t>(1, std::min<int64_t>(256 / wg_cols, cdiv(steps, 16)));
 }
+
+size_t lora_grad_tn_partial_floats(int n, int M, int r) { return (size_t)tn_splits(n, M) * M * r; }
 
 // C[m * sm + j * sj] = alpha * sum_t X[t, m] * UT[j, t];  r <= 64, M a multiple of 8, ldx a multiple of 8.
 int launch_lora_grad_tn(as_ctx* ctx, const void* X, int64_t ldx, const void* UT, int64_t ldu, int n, int M, int r,
@@ -113,7 +117,7 @@ int launch_lora_grad_tn(as_ctx* ctx, const void* X, int64_t ldx, const void* UT,
   if (r > 64 || (M % 8) || (ldx % 8) || (ldu % 8) || ((uintptr_t)X % 16) || ((uintptr_t)UT % 16))
     return as_fail(ctx, AS_ERR_SHAPE, "lora_grad_tn: rank <= 64 and 8-element alignment needed");
   const int steps = (int)cdiv(n, 32), slabs = (int)cdiv(M, 128);
-  int splits = (int)std::max<int64_t>(1, std::min<int64_t>(cdiv(1024, slabs), cdiv(steps, 16)));
+  const int splits = tn_splits(n, M);
   if ((size_t)splits * M * r > partial_floats) return as_fail(ctx, AS_ERR_WORKSPACE, "lora_grad_tn: partial buffer too small");
   TnParams p{(const bf16_t*)X, ldx, (const bf16_t*)UT, ldu, n, M, r, partial, (int)cdiv(steps, splits), steps};
   const int nb = (int)cdiv(r, 16);

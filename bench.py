@@ -191,10 +191,15 @@ def main():
     else:
         trajs = synth.workload(args.config, seed=args.seed, rows=(3 if args.bfd else 1) * sh.rows, row_len=sh.row_len)
     flat = synth.flatten_trajectories(trajs)
-    t0 = time.perf_counter()
-    pk = ctx.pack(*flat, sh.row_len, sh.rows, policy=B.AS_PACK_BEST_FIT_DECREASING if args.bfd else None)
-    torch.cuda.synchronize()
-    pack_ms = (time.perf_counter() - t0) * 1e3
+    # the first call also loads the library's code objects; the second is what a training loop pays per batch
+    pack_first_ms = pack_ms = 0.0
+    for i in range(2):
+        t0 = time.perf_counter()
+        pk = ctx.pack(*flat, sh.row_len, sh.rows, policy=B.AS_PACK_BEST_FIT_DECREASING if args.bfd else None)
+        torch.cuda.synchronize()
+        pack_ms = (time.perf_counter() - t0) * 1e3
+        if i == 0:
+            pack_first_ms = pack_ms
     assert pk["n_rows"] == sh.rows, pk["n_rows"]
     hcu = pk["cu_seqlens"].cpu().numpy()
     tok_h = pk["tokens"].cpu().numpy()
@@ -302,7 +307,7 @@ def main():
         "mfu_pct_of_bf16_peak": round(100 * mfu, 2), "hfu_pct_of_bf16_peak": round(100 * hfu, 2),
         "algorithmic_gflop_per_token": round(fl["total"] / n_nonpad / 1e9, 2),
         "layer_weight_gb": round(weight_bytes / 1e9, 2),
-        "loss": round(loss, 5), "pack_ms": round(pack_ms, 2), "adamw_ms": None if adam_ms is None else round(adam_ms, 3),
+        "loss": round(loss, 5), "pack_ms": round(pack_ms, 2), "pack_first_call_ms": round(pack_first_ms, 2), "adamw_ms": None if adam_ms is None else round(adam_ms, 3),
         "wall_s_timed_region": round(wall, 3),
         "kernel_ms_per_step": breakdown,
         "roofline": {"kernel": (GROUPED_KERNEL + " (expert GEMMs over grouped rows, forward + dX)" if sh.n_experts else DOMINANT_KERNEL +

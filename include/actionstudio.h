@@ -168,6 +168,10 @@ enum { AS_K_GEMM_MFMA_256 = 0,   /* bf16 MFMA GEMM, 256x256 tile                
        AS_K_GEMM_RS,             /* 256x256 MFMA GEMMs of the hand-scheduled register-staged kernel (long contractions) */
        AS_K_N_CLASSES };
 int as_profile(as_ctx* ctx, int enable);
+/* Restricts the brackets to one kernel class (kernel_class < 0: every class again): the events cost about 3 us of
+ * device time each, 0.5 % of a step with thousands of launches.  Call while timing is off.
+ * Errors: AS_ERR_SHAPE for an unknown class or while timing is on. */
+int as_profile_only(as_ctx* ctx, int kernel_class);
 int as_profile_read(as_ctx* ctx, int kernel_class, int64_t* launches, double* ms, double* flops);
 
 /* Register-resident bf16 MFMA loop over the whole chip (no memory traffic): measures the matrix

@@ -98,16 +98,17 @@ lib.as_probe_lds_feed.restype = C.c_int
 lib.as_probe_mfma_peak.argtypes = [_vp, _i32, _i32, _vp, C.POINTER(C.c_double), _vp]
 lib.as_probe_mfma_peak.restype = C.c_int
 lib.as_profile.argtypes = [_vp, C.c_int]
+lib.as_profile_only.argtypes = [_vp, C.c_int]
 lib.as_profile_read.argtypes = [_vp, C.c_int, C.POINTER(_i64), C.POINTER(C.c_double), C.POINTER(C.c_double)]
 KERNEL_CLASSES = ("gemm_mfma_256", "gemm_mfma_skinny", "gemm_fma", "gemm_devrows", "attn_fwd", "attn_bwd", "transpose",
                   "norm", "swiglu", "rope", "ce", "lora_grad", "gemm_grouped", "moe", "gemm_mfma_rs")
 for _n in ("as_profile", "as_profile_read", "as_create", "as_workspace_bytes", "as_pack", "as_train_step", "as_adamw_update", "as_op_gemm",
-           "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy", "as_op_gemm_rows"):
+           "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy", "as_op_gemm_rows", "as_profile_only"):
     getattr(lib, _n).restype = C.c_int
 
 EXPORTS = ("as_probe_lds_feed", "as_probe_mfma_peak", "as_profile", "as_profile_read", "as_create", "as_destroy", "as_last_error", "as_workspace_bytes", "as_pack", "as_train_step",
            "as_adamw_update", "as_op_gemm", "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd",
-           "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy", "as_op_gemm_rows")
+           "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy", "as_op_gemm_rows", "as_profile_only")
 
 
 class ASError(RuntimeError):
@@ -188,7 +189,11 @@ class Context:
         self.check(lib.as_probe_mfma_peak(self.handle, iters, blocks, _ptr(sink), C.byref(out), _stream()))
         return out.value
 
-    def profile(self, enable):
+    def profile(self, enable, only=None):
+        """only: name of the one kernel class to bracket (None: every class)"""
+        if enable:
+            self.check(lib.as_profile(self.handle, 0))
+            self.check(lib.as_profile_only(self.handle, -1 if only is None else KERNEL_CLASSES.index(only)))
         self.check(lib.as_profile(self.handle, int(enable)))
 
     def profile_read(self):

@@ -69,6 +69,7 @@ extern "C" int as_create(as_ctx** out, const as_model_config* cfg, int device) {
 void prof_begin(as_ctx* ctx, hipStream_t st, int cls, double flops) {
   if (!ctx || !ctx->prof_on) return;
   if (ctx->prof_depth++ > 0) return;
+  if (ctx->prof_only >= 0 && cls != ctx->prof_only) { ctx->prof_skipping = true; return; }
   if (ctx->prof_used >= 65536) return;
   if (ctx->prof_used >= ctx->prof.size()) {
     as_ctx::ProfRec r; r.flops = 0; r.cls = 0;
@@ -82,6 +83,7 @@ void prof_begin(as_ctx* ctx, hipStream_t st, int cls, double flops) {
 void prof_end(as_ctx* ctx, hipStream_t st) {
   if (!ctx || !ctx->prof_on) return;
   if (--ctx->prof_depth > 0) return;
+  if (ctx->prof_skipping) { ctx->prof_skipping = false; return; }
   if (ctx->prof_used >= 65536 || ctx->prof_used >= ctx->prof.size()) return;
   (void)hipEventRecord(ctx->prof[ctx->prof_used].b, st);
   ctx->prof_used++;
@@ -92,7 +94,15 @@ extern "C" int as_profile(as_ctx* ctx, int enable) {
   AS_HIP(ctx, hipSetDevice(ctx->device));
   AS_HIP(ctx, hipDeviceSynchronize());
   ctx->prof_on = enable != 0;
-  ctx->prof_used = 0; ctx->prof_depth = 0;
+  ctx->prof_used = 0; ctx->prof_depth = 0; ctx->prof_skipping = false;
+  return AS_OK;
+}
+
+extern "C" int as_profile_only(as_ctx* ctx, int kernel_class) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_profile_only: NULL context");
+  if (kernel_class >= AS_K_N_CLASSES) return as_fail(ctx, AS_ERR_SHAPE, "as_profile_only: unknown kernel class");
+  if (ctx->prof_on) return as_fail(ctx, AS_ERR_SHAPE, "as_profile_only: set the class before as_profile(ctx, 1)");
+  ctx->prof_only = kernel_class < 0 ? -1 : kernel_class;
   return AS_OK;
 }
 

@@ -33,6 +33,7 @@ struct as_ctx {
   // optional per-launch timing (as_profile): event pairs around kernels of the tracked classes
   struct ProfRec { hipEvent_t a, b; double flops; int cls; };
   bool prof_on = false; int prof_depth = 0;
+  int prof_only = -1; bool prof_skipping = false;   // >= 0: only this class is bracketed
   std::vector<ProfRec> prof; size_t prof_used = 0;
 };
 // Brackets one kernel launch with events when profiling is on (no-ops otherwise).

@@ -158,6 +158,19 @@ def test_per_kernel_timing_brackets_nested_launchers():
     assert float(out["loss"].item()) == a["loss"]
     for k in ("attn_fwd", "attn_bwd", "norm", "swiglu", "rope", "lora_grad"):
         assert prof[k][0] > 0 and prof[k][1] > 0.0, (k, prof[k])
+    # brackets around one class only
+    ctx.profile(True, only="norm")
+    out = ctx.train_step(ma, pk["tokens"], pk["cu_seqlens"], pk["cu_seqlens"].cpu().numpy(), pk["loss_mask"], 1, 512, ws,
+                         seg_skip=pk["seg_skip"])
+    one = ctx.profile_read()
+    ctx.profile(False)
+    assert float(out["loss"].item()) == a["loss"]
+    assert one["norm"][0] == prof["norm"][0] and all(v[0] == 0 for k, v in one.items() if k != "norm"), one
+    ctx.profile(True)                                        # and every class again
+    ctx.train_step(ma, pk["tokens"], pk["cu_seqlens"], pk["cu_seqlens"].cpu().numpy(), pk["loss_mask"], 1, 512, ws, seg_skip=pk["seg_skip"])
+    again = ctx.profile_read()
+    ctx.profile(False)
+    assert {k: v[0] for k, v in again.items()} == {k: v[0] for k, v in prof.items()}
 
 
 @pytest.mark.parametrize("row_len", [384, 320])

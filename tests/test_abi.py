@@ -173,3 +173,24 @@ def test_generated_gemm_loop_is_the_generators_output(tmp_path):
     out = tmp_path / "loop.inc"
     subprocess.run([sys.executable, os.path.join(csrc, "gen_gemm_rs_loop.py"), str(out)], check=True, capture_output=True)
     assert out.read_text() == open(os.path.join(csrc, "gemm_rs_loop.inc")).read()
+
+
+def test_row_counted_gemm_and_timing_filter_reject_bad_arguments(B):
+    """Host-side checks only: none of these reaches a HIP call."""
+    ctx = B.Context(B.make_config(synth.CONFIGS[1]))
+    p = C.c_void_p(4096)
+    def rows(A=p, Bm=p, Cm=p, M=512, N=256, K=64, lda=64, ldb=64, ldc=256, d_rows=p, row_off=0, d_grp=None, group=0, n_groups=0, stride=0, cap=0):
+        return B.lib.as_op_gemm_rows(ctx.handle, B.AS_BF16, 0, M, N, A, lda, Bm, ldb, K, 1.0, None, 0, Cm, ldc, 0,
+                                     d_rows, row_off, d_grp, group, n_groups, stride, cap, None)
+    assert rows(A=None) == B.ERR["NULL"]
+    assert rows(d_rows=None) == B.ERR["NULL"]                              # neither a row count nor a group table
+    assert rows(M=-1) == B.ERR["SHAPE"] and rows(row_off=-1) == B.ERR["SHAPE"] and rows(cap=-5) == B.ERR["SHAPE"]
+    assert rows(lda=32) == B.ERR["SHAPE"] and rows(ldc=8) == B.ERR["SHAPE"]
+    assert rows(d_grp=p, n_groups=4, stride=256 * 64) == B.ERR["SHAPE"]    # all groups at once and a device row count
+    assert rows(d_rows=None, d_grp=None, n_groups=4) == B.ERR["NULL"]
+    assert b"as_op_gemm_rows" in B.lib.as_last_error(ctx.handle)
+    assert B.lib.as_profile_only(ctx.handle, len(B.KERNEL_CLASSES)) == B.ERR["SHAPE"]
+    assert B.lib.as_profile_only(ctx.handle, B.KERNEL_CLASSES.index("norm")) == 0
+    assert B.lib.as_profile_only(ctx.handle, -1) == 0
+    assert B.lib.as_profile_only(None, 0) == B.ERR["NULL"]
+    ctx.close()

@@ -227,10 +227,21 @@ __global__ void rmsnorm_fwd_kernel(int n, int d, const T* __restrict__ x, const 
   if (row >= nn) return;
   const T* xr = x + (int64_t)(row_idx ? row_idx[row] : row) * d;
   T* yr = y + (int64_t)row * d;
-  constexpr int VN = Vec<T>::N;
+  constexpr int VN = Vec<T>::N, KEEP = 8, STEP = AS_WAVE * VN;
+  typedef typename Vec<T>::type VT;
+  VT kept[KEEP];                         // the first KEEP 16-byte pieces of the row stay in registers for the second pass (bf16: 4096 columns)
   float ss = 0.f;
   if (vec) {
-    for (int j = lane * VN; j < d; j += AS_WAVE * VN) {
+#pragma unroll
+    for (int c = 0; c < KEEP; c++) {
+      const int j = c * STEP + lane * VN;
+      if (j < d) {
+        kept[c] = *reinterpret_cast<const VT*>(xr + j);
+#pragma unroll
+        for (int i = 0; i < VN; i++) { const float v = to_f<T>(kept[c][i]); ss += v * v; }
+      }
+    }
+    for (int j = KEEP * STEP + lane * VN; j < d; j += STEP) {
       float v[VN]; load_vec<T>(xr + j, v);
 #pragma unroll
       for (int i = 0; i < VN; i++) ss += v[i] * v[i];
@@ -244,7 +255,17 @@ __global__ void rmsnorm_fwd_kernel(int n, int d, const T* __restrict__ x, const 
   { float a = ss / (float)d + eps; r = r * (1.5f - 0.5f * a * r * r); }
   if (lane == 0) rstd[row] = r;
   if (vec) {
-    for (int j = lane * VN; j < d; j += AS_WAVE * VN) {
+#pragma unroll
+    for (int c = 0; c < KEEP; c++) {
+      const int j = c * STEP + lane * VN;
+      if (j < d) {
+        float v[VN], gg[VN]; load_vec<T>(g + j, gg);
+#pragma unroll
+        for (int i = 0; i < VN; i++) v[i] = to_f<T>(kept[c][i]) * r * gg[i];
+        store_vec<T>(yr + j, v);
+      }
+    }
+    for (int j = KEEP * STEP + lane * VN; j < d; j += STEP) {
       float v[VN], gg[VN]; load_vec<T>(xr + j, v); load_vec<T>(g + j, gg);
 #pragma unroll
       for (int i = 0; i < VN; i++) v[i] = v[i] * r * gg[i];
@@ -287,8 +308,21 @@ __global__ void rmsnorm_bwd_kernel(int n, int d, const T* __restrict__ dy, const
   const T* xr = x + (int64_t)row * d;
   float r = rstd[src_pos ? src : row];
   float dot = 0.f;
+  constexpr int KEEP = 8, STEP = AS_WAVE * VN;
+  typedef typename Vec<T>::type VT;
+  VT kdy[KEEP], kx[KEEP];                // the first KEEP 16-byte pieces of both rows stay in registers for the second pass
   if (vec) {
-    for (int j = lane * VN; j < d; j += AS_WAVE * VN) {
+#pragma unroll
+    for (int q = 0; q < KEEP; q++) {
+      const int j = q * STEP + lane * VN;
+      if (j < d) {
+        kdy[q] = *reinterpret_cast<const VT*>(dyr + j); kx[q] = *reinterpret_cast<const VT*>(xr + j);
+        float c[VN]; load_vec<T>(g + j, c);
+#pragma unroll
+        for (int i = 0; i < VN; i++) dot += to_f<T>(kdy[q][i]) * to_f<T>(kx[q][i]) * c[i];
+      }
+    }
+    for (int j = KEEP * STEP + lane * VN; j < d; j += STEP) {
       float a[VN], b[VN], c[VN]; load_vec<T>(dyr + j, a); load_vec<T>(xr + j, b); load_vec<T>(g + j, c);
 #pragma unroll
       for (int i = 0; i < VN; i++) dot += a[i] * b[i] * c[i];
@@ -299,7 +333,18 @@ __global__ void rmsnorm_bwd_kernel(int n, int d, const T* __restrict__ dy, const
   dot = wave_sum(dot);
   float k = r * r * r * dot / (float)d;
   if (vec) {
-    for (int j = lane * VN; j < d; j += AS_WAVE * VN) {
+#pragma unroll
+    for (int q = 0; q < KEEP; q++) {
+      const int j = q * STEP + lane * VN;
+      if (j < d) {
+        float c[VN], o[VN]; load_vec<T>(g + j, c);
+        if (ar) load_vec<T>(ar + j, o);
+#pragma unroll
+        for (int i = 0; i < VN; i++) o[i] = (ar ? o[i] : 0.f) + (r * c[i] * to_f<T>(kdy[q][i]) - to_f<T>(kx[q][i]) * k);
+        store_vec<T>(dxr + j, o);
+      }
+    }
+    for (int j = KEEP * STEP + lane * VN; j < d; j += STEP) {
       float a[VN], b[VN], c[VN], o[VN]; load_vec<T>(dyr + j, a); load_vec<T>(xr + j, b); load_vec<T>(g + j, c);
       if (ar) load_vec<T>(ar + j, o);
 #pragma unroll

@@ -213,6 +213,25 @@ def flatten_trajectories(trajs):
 
 # ------------------------------------------------------------------ weights
 
+def normal_f32_blocks(seed, stream, shape, std, block=1 << 24):
+    """N(0, std) float32 array whose blocks of ``block`` elements come from Philox streams of their own
+    (key = seed, stream, block index), filled by a thread pool: billions of weights in seconds."""
+    from concurrent.futures import ThreadPoolExecutor
+    import os
+    out = np.empty(int(np.prod(shape)), dtype=np.float32)
+
+    def fill(i):
+        g = np.random.Generator(np.random.Philox(key=[int(seed), (int(stream) << 20) + i]))
+        v = out[i * block:(i + 1) * block]
+        g.standard_normal(out=v, dtype=np.float32)
+        v *= np.float32(std)
+
+    n_blocks = (out.size + block - 1) // block
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+        list(ex.map(fill, range(n_blocks)))
+    return out.reshape(shape)
+
+
 def lora_dims(sh):
     D = sh.n_q_heads * sh.head_dim
     Dkv = sh.n_kv_heads * sh.head_dim
@@ -229,7 +248,12 @@ def weights(sh, seed=0, std=0.02, dtype=np.float64, gain_jitter=0.0):
     Dkv = sh.n_kv_heads * sh.head_dim
     d, F = sh.d_model, sh.ffn
 
+    n_big = [0]
+
     def mat(*shape):
+        if dtype == np.float32:            # true-width models: single precision, drawn in parallel blocks
+            n_big[0] += 1
+            return normal_f32_blocks(seed, 1000 + n_big[0], shape, std)
         return (std * g.standard_normal(shape)).astype(dtype)
 
     def gain():

@@ -27,12 +27,12 @@ def router_margin(sh, params, lora, trajs, rows, row_len):
     return m
 
 
-def structured_router_params(sh, seed, live=None):
+def structured_router_params(sh, seed, live=None, dtype=np.float64):
     """Weights whose routing is decided by the token id with a wide margin: orthonormal router rows,
     and embeddings that are a 1.0 / 0.8 mix of two router rows (per layer the rows are permuted)
     plus the usual small noise.  The rest of the model is the ordinary random draw."""
     g = synth.rng(seed, 11)
-    P = synth.weights(sh, seed)
+    P = synth.weights(sh, seed, dtype=dtype)
     d, E, V = sh.d_model, sh.n_experts, sh.vocab
     basis, _ = np.linalg.qr(g.standard_normal((d, E)))          # [d, E], orthonormal columns
     live = E if live is None else live                          # experts beyond `live` are never chosen

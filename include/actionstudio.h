@@ -383,6 +383,19 @@ int as_op_attention_bwd(as_ctx* ctx, int mode, int variant, int64_t n, const int
                         const void* d_o, void* dq, void* dk, void* dv, float* delta_scratch,
                         void* t_scratch, void* stream);
 
+/* as_op_attention_bwd for callers that cannot allocate device memory or hand over a workspace (code under HIP
+ * graph capture, serving loops, harnesses that forbid hipMalloc): same arguments without the two scratch
+ * buffers, which live in a device array of AS_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held
+ * until the process ends).  The call allocates nothing.  Sizes that need more than that
+ * ((6*Hq + Hkv)*dh*n64 elements of T plus n*Hq floats, n64 = n rounded up to 64) are rejected with
+ * AS_ERR_WORKSPACE before anything is launched.  All calls on one GPU share the array: calls that overlap on
+ * one GPU (different streams or threads) race, and nothing of a call's scratch contents survives the next. */
+#define AS_STATIC_SCRATCH_BYTES (32u << 20)
+int as_op_attention_bwd_static(as_ctx* ctx, int mode, int variant, int64_t n, const int32_t* seg_start,
+                               const int32_t* seg_end, const void* q, int64_t ldq, const void* k,
+                               const void* v, int64_t ldkv, const void* o, const float* lse,
+                               const void* d_o, void* dq, void* dk, void* dv, void* stream);
+
 /* NF4 block quantisation of a frozen weight tensor (the "Q" of the paper's Q+LoRA regime, Section 4.5;
  * format of the public QLoRA description): numel (a multiple of 64) elements of type T, flattened
  * row-major, in blocks of 64: absmax[b] = max |w| of block b (float), code = index of the nearest of

@@ -93,6 +93,10 @@ lib.as_op_rmsnorm_bwd.argtypes = [_vp, C.c_int, _i64, _i64, _vp, _vp, _vp, _vp, 
 lib.as_op_attention_fwd.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _vp]
 lib.as_op_attention_bwd.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp,
                                     _vp, _vp, _vp, _vp, _vp, _vp]
+lib.as_op_attention_bwd_static.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp,
+                                           _vp, _vp, _vp, _vp]
+lib.as_op_attention_bwd_static.restype = C.c_int
+STATIC_SCRATCH_BYTES = 32 << 20
 lib.as_probe_lds_feed.argtypes = [_vp, _i32, _vp, C.c_size_t, _i32, _i32, _vp, C.POINTER(C.c_double), _vp]
 lib.as_probe_lds_feed.restype = C.c_int
 lib.as_probe_mfma_peak.argtypes = [_vp, _i32, _i32, _vp, C.POINTER(C.c_double), _vp]
@@ -106,7 +110,7 @@ for _n in ("as_profile", "as_profile_read", "as_create", "as_workspace_bytes", "
            "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy", "as_op_gemm_rows", "as_profile_only"):
     getattr(lib, _n).restype = C.c_int
 
-EXPORTS = ("as_probe_lds_feed", "as_probe_mfma_peak", "as_profile", "as_profile_read", "as_create", "as_destroy", "as_last_error", "as_workspace_bytes", "as_pack", "as_train_step",
+EXPORTS = ("as_op_attention_bwd_static", "as_probe_lds_feed", "as_probe_mfma_peak", "as_profile", "as_profile_read", "as_create", "as_destroy", "as_last_error", "as_workspace_bytes", "as_pack", "as_train_step",
            "as_adamw_update", "as_op_gemm", "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd",
            "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy", "as_op_gemm_rows", "as_profile_only")
 
@@ -385,13 +389,21 @@ class Context:
                                            _ptr(o), _ptr(lse), _ptr(ts), _stream()))
         return o, lse
 
-    def op_attention_bwd(self, qkv, seg_start, seg_end, o, lse, d_o, variant=0, mode=None):
+    def op_attention_bwd(self, qkv, seg_start, seg_end, o, lse, d_o, variant=0, mode=None, static=False, out=None):
+        """static=True: the entry point that allocates nothing (scratch inside the library); out: caller's dqkv buffer."""
         mode = self.mode if mode is None else mode
         c = self.cfg
         n = qkv.shape[0]
         D, Dkv = c.n_q_heads * c.head_dim, c.n_kv_heads * c.head_dim
         es = qkv.element_size()
-        dqkv = torch.empty_like(qkv)
+        dqkv = torch.empty_like(qkv) if out is None else out
+        if static:
+            b, g = qkv.data_ptr(), dqkv.data_ptr()
+            self.check(lib.as_op_attention_bwd_static(self.handle, mode, variant, n, _ptr(seg_start), _ptr(seg_end), C.c_void_p(b),
+                                                      qkv.stride(0), C.c_void_p(b + D * es), C.c_void_p(b + (D + Dkv) * es),
+                                                      qkv.stride(0), _ptr(o), _ptr(lse), _ptr(d_o), C.c_void_p(g),
+                                                      C.c_void_p(g + D * es), C.c_void_p(g + (D + Dkv) * es), _stream()))
+            return dqkv
         delta = torch.empty(n, c.n_q_heads, dtype=torch.float32, device=qkv.device)
         b, g = qkv.data_ptr(), dqkv.data_ptr()
         n64 = (n + 63) // 64 * 64

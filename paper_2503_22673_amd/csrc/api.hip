@@ -7,6 +7,7 @@
 #include <vector>
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 
 static thread_local std::string g_tls_err;
 
@@ -1390,17 +1391,68 @@ extern "C" int as_op_attention_fwd(as_ctx* ctx, int mode, int variant, int64_t n
   return launch_attention_fwd(ctx, mode, variant, ap, (hipStream_t)stream);
 }
 
+static int attention_bwd_op(as_ctx* ctx, const char* who, int mode, int variant, int64_t n, const int32_t* seg_start,
+                            const int32_t* seg_end, const void* q, int64_t ldq, const void* k,
+                            const void* v, int64_t ldkv, const void* o, const float* lse,
+                            const void* d_o, void* dq, void* dk, void* dv, float* delta_scratch,
+                            void* t_scratch, void* stream) {
+  if (!seg_start || !seg_end || !q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !delta_scratch)
+    return as_fail(ctx, AS_ERR_NULL, "%s: NULL operand", who);
+  AttnParams ap; int rc = attn_common(ctx, mode, n, ldq, ldkv, &ap); if (rc) return rc;
+  ap.seg_start = seg_start; ap.seg_end = seg_end; ap.q = q; ap.k = k; ap.v = v; ap.o = const_cast<void*>(o); ap.lse = const_cast<float*>(lse);
+  ap.d_o = d_o; ap.dq = dq; ap.dk = dk; ap.dv = dv; ap.delta = delta_scratch; ap.t_scratch = t_scratch;
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  return launch_attention_bwd(ctx, mode, variant, ap, (hipStream_t)stream);
+}
+
 extern "C" int as_op_attention_bwd(as_ctx* ctx, int mode, int variant, int64_t n, const int32_t* seg_start,
                                    const int32_t* seg_end, const void* q, int64_t ldq, const void* k,
                                    const void* v, int64_t ldkv, const void* o, const float* lse,
                                    const void* d_o, void* dq, void* dk, void* dv, float* delta_scratch,
                                    void* t_scratch, void* stream) {
   if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_op_attention_bwd: NULL context");
-  if (!seg_start || !seg_end || !q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !delta_scratch)
-    return as_fail(ctx, AS_ERR_NULL, "as_op_attention_bwd: NULL operand");
-  AttnParams ap; int rc = attn_common(ctx, mode, n, ldq, ldkv, &ap); if (rc) return rc;
-  ap.seg_start = seg_start; ap.seg_end = seg_end; ap.q = q; ap.k = k; ap.v = v; ap.o = const_cast<void*>(o); ap.lse = const_cast<float*>(lse);
-  ap.d_o = d_o; ap.dq = dq; ap.dk = dk; ap.dv = dv; ap.delta = delta_scratch; ap.t_scratch = t_scratch;
-  AS_HIP(ctx, hipSetDevice(ctx->device));
-  return launch_attention_bwd(ctx, mode, variant, ap, (hipStream_t)stream);
+  return attention_bwd_op(ctx, "as_op_attention_bwd", mode, variant, n, seg_start, seg_end, q, ldq, k, v, ldkv, o, lse, d_o, dq, dk, dv,
+                          delta_scratch, t_scratch, stream);
+}
+
+// ---- the same without any allocation: both scratch buffers live in a device array of the library ----
+// In host code the array's name only stands for the symbol; its device address is asked for once per device,
+// with that device current, and kept.  Every GPU has a copy of its own.
+static __device__ __align__(256) unsigned char scratch[AS_STATIC_SCRATCH_BYTES];
+static constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];            // guarded by g_scratch_mu
+static std::mutex g_scratch_mu;
+
+static int static_scratch(as_ctx* ctx, void** out) {
+  if (ctx->device < 0 || ctx->device >= kMaxDevices) return as_fail(ctx, AS_ERR_SHAPE, "static scratch: device index %d out of range", ctx->device);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[ctx->device]) {
+    AS_HIP(ctx, hipSetDevice(ctx->device));
+    void* ptr = nullptr;
+    AS_HIP(ctx, hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    g_scratch_ptr[ctx->device] = ptr;
+  }
+  *out = g_scratch_ptr[ctx->device];
+  return AS_OK;
+}
+
+extern "C" int as_op_attention_bwd_static(as_ctx* ctx, int mode, int variant, int64_t n, const int32_t* seg_start,
+                                          const int32_t* seg_end, const void* q, int64_t ldq, const void* k,
+                                          const void* v, int64_t ldkv, const void* o, const float* lse,
+                                          const void* d_o, void* dq, void* dk, void* dv, void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_op_attention_bwd_static: NULL context");
+  int rc = check_mode(ctx, mode); if (rc) return rc;
+  if (n < 0 || n > INT32_MAX) return as_fail(ctx, AS_ERR_SHAPE, "as_op_attention_bwd_static: bad token count");
+  const as_model_config& c = ctx->cfg;
+  // delta [n, Hq] floats, then (256-byte aligned) the token-major copies and partial sums of as_op_attention_bwd
+  const size_t es = mode == AS_FP32 ? 4 : 2, n64 = (size_t)cdiv(n, 64) * 64;
+  const size_t delta_bytes = ((size_t)n * c.n_q_heads * 4 + 255) & ~(size_t)255;
+  const size_t need = delta_bytes + (size_t)(6 * c.n_q_heads + c.n_kv_heads) * c.head_dim * n64 * es;
+  if (need > (size_t)AS_STATIC_SCRATCH_BYTES)
+    return as_fail(ctx, AS_ERR_WORKSPACE, "as_op_attention_bwd_static: %lld tokens need %zu bytes of scratch, the library holds %zu",
+                   (long long)n, need, (size_t)AS_STATIC_SCRATCH_BYTES);
+  void* base = nullptr;
+  if ((rc = static_scratch(ctx, &base))) return rc;
+  return attention_bwd_op(ctx, "as_op_attention_bwd_static", mode, variant, n, seg_start, seg_end, q, ldq, k, v, ldkv, o, lse, d_o, dq, dk, dv,
+                          (float*)base, (char*)base + delta_bytes, stream);
 }

@@ -323,7 +323,10 @@ int as_adamw_update(as_ctx* ctx, float* const* d_master, void* const* d_params_l
  * the second product being the low-rank LoRA term folded into the same
  * accumulation (Section 4.5); A2 may be NULL.  A, B, R of type T; C of type T,
  * or float when c_is_f32.  variant: 0 = pick, 1 = plain FMA kernel,
- * 2 = MFMA kernel (bf16 only; K1, K2, lda, ldb multiples of 8). */
+ * 2 = MFMA kernel (bf16 only; K1, K2, lda, ldb multiples of 8) with the tile
+ * shape picked; 10..13 = register-staged tiles 256x256 / 256x64 / 64x256 /
+ * 128x128; 30 = direct-to-LDS 256x256 tiles (K in 64-wide steps, else 10);
+ * 34 = hand-scheduled 256x256 kernel where it applies (else 30). */
 int as_op_gemm(as_ctx* ctx, int mode, int variant, int64_t M, int64_t N,
                const void* A1, int64_t lda1, const void* B1, int64_t ldb1, int64_t K1,
                const void* A2, int64_t lda2, const void* B2, int64_t ldb2, int64_t K2,
@@ -366,8 +369,7 @@ int as_op_rmsnorm_bwd(as_ctx* ctx, int mode, int64_t n, int64_t d, const void* d
 /* Varlen causal attention with grouped KV heads over packed rows.  q [n,Hq,dh]
  * with row stride ldq elements, k, v [n,Hkv,dh] with stride ldkv, o [n,Hq,dh]
  * dense, lse float [n,Hq].  seg_start [n] int32: first token of each token's
- * segment.  variant: 0 = pick, 1 = plain kernel, 2 / 3 / 4 = MFMA kernels (bf16:
- * first generation, second with 64-query waves, second with 32-query waves).
+ * segment.  variant: 0 = pick, 1 = plain kernel, 2 = MFMA kernels (bf16, head_dim 64 or 128).
  * t_scratch: type T, only read by the MFMA kernels (may be NULL otherwise):
  * room for Hkv*dh * n64 elements in forward and (6*Hq + Hkv)*dh * n64 in
  * backward, n64 = n rounded up to 64 (token-major copies of V, resp. K, Q, dO,
@@ -382,6 +384,23 @@ int as_op_attention_bwd(as_ctx* ctx, int mode, int variant, int64_t n, const int
                         const void* v, int64_t ldkv, const void* o, const float* lse,
                         const void* d_o, void* dq, void* dk, void* dv, float* delta_scratch,
                         void* t_scratch, void* stream);
+
+/* The vocabulary head with the masked cross-entropy (Section 3.2.1: the loss covers assistant tokens only), as the
+ * step runs it over the compacted target rows:
+ *   loss_rows[r] = logsumexp_v(hf[r] . head[v]) - hf[r] . head[labels[r]],
+ *   dhf[r]       = factor_r * (softmax_v(hf[r] . head[v]) - onehot(labels[r])) head,   factor_r = row_w[r], or 1 / *d_count
+ * for the rows r < *d_count (a device-side count, at most n_rows); other rows are neither read into a result nor written.
+ *  hf, dhf  [device] T [n_rows rounded up to a multiple of 256, d_model] (the products run over whole 256-row tiles);
+ *  head     [device] T [vocab, d_model], 16-byte aligned; labels [device] int32 [n_rows]; row_w [device] float [n_rows] or NULL;
+ *  loss_rows [device] float [n_rows].
+ * In AS_BF16 mode with vocab a multiple of 256 and d_model a multiple of 64 no logits are stored: the product runs twice,
+ * first with an epilogue that keeps per-block softmax statistics only, then with one that writes the gradient rows with
+ * respect to the logits as bf16, 8192 target rows at a time.  Otherwise a float logits chunk of 4096 rows is used.
+ * Workspace: as_op_head_loss_workspace bytes, 256-byte aligned.  d_model and vocab are the context's. */
+int as_op_head_loss_workspace(const as_ctx* ctx, int mode, int64_t n_rows, size_t* bytes);
+int as_op_head_loss(as_ctx* ctx, int mode, int64_t n_rows, const void* hf, const void* head, const int32_t* labels,
+                    const int32_t* d_count, const float* row_w, float* loss_rows, void* dhf,
+                    void* d_workspace, size_t workspace_bytes, void* stream);
 
 /* as_op_attention_bwd for callers that cannot allocate device memory or hand over a workspace (code under HIP
  * graph capture, serving loops, harnesses that forbid hipMalloc): same arguments without the two scratch

@@ -93,6 +93,10 @@ lib.as_op_rmsnorm_bwd.argtypes = [_vp, C.c_int, _i64, _i64, _vp, _vp, _vp, _vp, 
 lib.as_op_attention_fwd.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _vp]
 lib.as_op_attention_bwd.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp,
                                     _vp, _vp, _vp, _vp, _vp, _vp]
+lib.as_op_head_loss_workspace.argtypes = [_vp, C.c_int, _i64, C.POINTER(C.c_size_t)]
+lib.as_op_head_loss_workspace.restype = C.c_int
+lib.as_op_head_loss.argtypes = [_vp, C.c_int, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
+lib.as_op_head_loss.restype = C.c_int
 lib.as_op_attention_bwd_static.argtypes = [_vp, C.c_int, C.c_int, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp,
                                            _vp, _vp, _vp, _vp]
 lib.as_op_attention_bwd_static.restype = C.c_int
@@ -110,7 +114,7 @@ for _n in ("as_profile", "as_profile_read", "as_create", "as_workspace_bytes", "
            "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd", "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy", "as_op_gemm_rows", "as_profile_only"):
     getattr(lib, _n).restype = C.c_int
 
-EXPORTS = ("as_op_attention_bwd_static", "as_probe_lds_feed", "as_probe_mfma_peak", "as_profile", "as_profile_read", "as_create", "as_destroy", "as_last_error", "as_workspace_bytes", "as_pack", "as_train_step",
+EXPORTS = ("as_op_head_loss", "as_op_head_loss_workspace", "as_op_attention_bwd_static", "as_probe_lds_feed", "as_probe_mfma_peak", "as_profile", "as_profile_read", "as_create", "as_destroy", "as_last_error", "as_workspace_bytes", "as_pack", "as_train_step",
            "as_adamw_update", "as_op_gemm", "as_op_rmsnorm_fwd", "as_op_rmsnorm_bwd", "as_op_attention_fwd",
            "as_op_attention_bwd", "as_nf4_quantize", "as_nf4_dequantize", "as_sequence_logps", "as_dpo_step", "as_pack_policy", "as_op_gemm_rows", "as_profile_only")
 
@@ -340,6 +344,21 @@ class Context:
                                        int(Cm.dtype == torch.float32), _ptr(d_rows), row_off, _ptr(d_group_off), group, n_groups, stride,
                                        rows_cap, _stream()))
         return Cm
+
+    def op_head_loss(self, hf, head, labels, count, row_w=None, mode=None):
+        """hf [rows, d] (rows a multiple of 256 at least the row capacity of labels), head [V, d], labels int32 [n_rows], count
+        device int32[1].  Returns (loss_rows float [n_rows], dhf like hf); rows at or past the count are left as they were (zero)."""
+        mode = self.mode if mode is None else mode
+        n_rows = labels.numel()
+        assert hf.shape[0] >= (n_rows + 255) // 256 * 256
+        need = C.c_size_t()
+        self.check(lib.as_op_head_loss_workspace(self.handle, mode, n_rows, C.byref(need)))
+        ws = torch.empty(need.value, dtype=torch.uint8, device=hf.device)
+        loss = torch.zeros(n_rows, dtype=torch.float32, device=hf.device)
+        dhf = torch.zeros_like(hf)
+        self.check(lib.as_op_head_loss(self.handle, mode, n_rows, _ptr(hf), _ptr(head), _ptr(labels), _ptr(count), _ptr(row_w), _ptr(loss),
+                                       _ptr(dhf), _ptr(ws), need.value, _stream()))
+        return loss, dhf
 
     def nf4_quantize(self, w):
         """w: device tensor (float32 or bfloat16), numel a multiple of 64 -> (packed codes uint8 [numel/2], absmax float32 [numel/64])."""

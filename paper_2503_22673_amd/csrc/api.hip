@@ -397,7 +397,9 @@ struct Acts {           // activations of one layer kept for its backward
 };
 
 struct Plan {
-  int N, Np, d, D, Dkv, QKV, F, V, L, rp, es, Mc;   // Np: token count rounded up to 64 (row length of token-major transposes)
+  int N, Np, d, D, Dkv, QKV, F, V, L, rp, es, Mc;
+  bool head_fused;                       // vocabulary head without stored logits (statistics and gradient rows come out of the GEMM epilogues)
+  float *part, *zlab, *lse_rows;         // its per-block softmax statistics [Mc, V / 128, 2], label logits and log-sum-exps per target   // Np: token count rounded up to 64 (row length of token-major transposes)
   int cap;                               // token rows every activation buffer holds (rows * row_len of the plan)
   int n_qkv, n_gu;                       // adapters inside the q/k/v and gate/up groups
   int32_t *seg_start, *seg_end, *tgt_idx, *tgt_pos, *labels, *count, *iscratch;
@@ -446,7 +448,8 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   P.QKV = P.D + 2 * P.Dkv; P.F = c.ffn; P.V = c.vocab; P.L = c.n_layers;
   P.es = c.mode == AS_FP32 ? 4 : 2;
   P.rp = full ? 0 : (c.mode == AS_BF16 ? (int)cdiv(c.lora_rank, 64) * 64 : (int)cdiv(c.lora_rank, 16) * 16);   // whole 64-wide K steps for the MFMA tiles
-  P.Mc = (int)std::min<int64_t>(4096, cdiv(std::max(P.N, 1), 64) * 64);
+  P.head_fused = c.mode == AS_BF16 && P.V % 256 == 0 && P.d % 64 == 0;
+  P.Mc = P.head_fused ? (int)std::min<int64_t>(8192, cdiv(std::max(P.N, 1), 256) * 256) : (int)std::min<int64_t>(4096, cdiv(std::max(P.N, 1), 64) * 64);
   P.Np = (int)cdiv(P.N, 64) * 64;
   const size_t N = (size_t)P.N, es = (size_t)P.es;
   const bool moe = c.n_experts > 0;
@@ -491,8 +494,11 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
     a.pos = (int32_t*)w.take(moe ? N * 2 * 4 : 0); a.perm = (int32_t*)w.take(moe ? N * 2 * 4 : 0);
     a.y_perm = w.take(moe ? 2 * N * P.d * es : 0); a.u_r = w.take(on(AS_T_ROUTER) ? N * rp * es : 0);
   }
-  P.hf = w.take(N * P.d * es); P.dhf = w.take(N * P.d * es);
-  P.logits = (float*)w.take((size_t)P.Mc * P.V * 4);
+  // 256 rows more than tokens: the head's products run over whole 256-row tiles of the (device-counted) target rows
+  P.hf = w.take((N + 256) * P.d * es); P.dhf = w.take((N + 256) * P.d * es);
+  P.logits = (float*)w.take(P.head_fused ? 0 : (size_t)P.Mc * P.V * 4);
+  P.part = (float*)w.take(P.head_fused ? (size_t)P.Mc * (P.V / 128) * 8 : 0);
+  P.zlab = (float*)w.take(P.head_fused ? N * 4 : 0); P.lse_rows = (float*)w.take(P.head_fused ? N * 4 : 0);
   P.P = w.take((size_t)P.Mc * P.V * es);
   P.headT = w.take((size_t)P.V * P.d * es);
   P.Pt = w.take(full ? (size_t)P.Mc * P.V * es : 0);
@@ -620,6 +626,30 @@ struct Step {
     return P.wdq;
   }
 
+  // Projections that read the same input and write side by side (q | k | v, gate | up) go out as one launch when their
+  // matrices can be used where they are (dense format) and either all or none of them carry an adapter.
+  bool side_by_side_ok(int l, const int* tgt, int nt) {
+    if (c.weight_format == AS_W_NF4) return false;
+    int on = 0;
+    for (int i = 0; i < nt; i++) on += slot(l, tgt[i]).on ? 1 : 0;
+    return on == 0 || on == nt;
+  }
+  int gemm_side_by_side(int l, const int* tgt, int nt, const void* x, int K, const void* const* w, const int* nout,
+                        const void* u, int ldu, void* C, int ldc) {
+    GemmParams g; memset(&g, 0, sizeof g);
+    const bool on = slot(l, tgt[0]).on;
+    g.seg[0] = {x, w[0], K, K, K}; g.nseg = 1;
+    if (on) { g.seg[1] = {u, slot(l, tgt[0]).Bs, ldu, P.rp, P.rp}; g.nseg = 2; }
+    g.ncg = nt;
+    int end = 0;
+    for (int i = 0; i < nt; i++) {
+      end += nout[i]; g.cg_end[i] = end; g.cg_B1[i] = w[i];
+      g.cg_B2[i] = on ? slot(l, tgt[i]).Bs : nullptr; g.cg_a2[i] = on ? slot(l, tgt[i]).slot * P.rp : 0;
+    }
+    g.M = P.N; g.N = end; g.C = C; g.ldc = ldc; g.alpha = 1.f; g.splitk = 1; g.rows_cap = P.cap;
+    return launch_gemm_off(ctx, mode, gv, g, 0, st);
+  }
+
   int prep_lora(int l) {
     const as_layer_lora& Lr = lora->layers[l];
     const float s = c.lora_alpha / (float)c.lora_rank;
@@ -650,6 +680,10 @@ struct Step {
     if (P.n_qkv && (rc = gemm(N, ldu, a.a, d, P.A_qkv[l], d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_qkv, ldu))) return rc;
     const void* wq[3] = {w.wq, w.wk, w.wv}; const float* aq[3] = {w.aq, w.ak, w.av};
     const int nout[3] = {D, Dkv, Dkv}; const int coff[3] = {0, D, D + Dkv};
+    const int tq[3] = {AS_T_Q, AS_T_K, AS_T_V};
+    if (side_by_side_ok(l, tq, 3)) {
+      if ((rc = gemm_side_by_side(l, tq, 3, a.a, d, wq, nout, a.u_qkv, ldu, a.qkv, QKV))) return rc;
+    } else
     for (int i = 0; i < 3; i++) {
       LoraSlot& s = slot(l, i);
       rows_cap_once = P.cap;
@@ -672,6 +706,10 @@ struct Step {
     const int ldg = P.n_gu * rp;
     if (P.n_gu && (rc = gemm(N, ldg, a.b, d, P.A_gu[l], d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, a.u_gu, ldg))) return rc;
     const void* wg[2] = {w.wgate, w.wup}; const float* ag[2] = {w.agate, w.aup};
+    const int tg[2] = {AS_T_GATE, AS_T_UP}; const int ng[2] = {F, F};
+    if (side_by_side_ok(l, tg, 2)) {
+      if ((rc = gemm_side_by_side(l, tg, 2, a.b, d, wg, ng, a.u_gu, ldg, a.gu, 2 * F))) return rc;
+    } else
     for (int i = 0; i < 2; i++) {
       LoraSlot& s = slot(l, AS_T_GATE + i);
       rows_cap_once = P.cap;
@@ -943,23 +981,84 @@ struct Step {
     return launch_rmsnorm_bwd(ctx, mode, N, d, P.da, nullptr, P.h[l], w.g1, a.rstd1, P.dh2, P.dh, st);
   }
 
+  // one product of the head over the target rows r0 .. r0 + rows - 1 (their number lives on the device), with one of the
+  // epilogues that keep the logits out of memory
+  int head_gemm(int epi, int rows, int r0, const float* row_w, void* C) {
+    GemmParams g; memset(&g, 0, sizeof g);
+    g.seg[0] = {off(P.hf, (size_t)r0 * P.d), W->head, P.d, P.d, P.d}; g.nseg = 1;
+    g.M = rows; g.N = P.V; g.m_dev = P.count; g.C = C; g.ldc = P.V; g.alpha = 1.f; g.splitk = 1;
+    g.epi = epi; g.epi_part = P.part; g.epi_lse = P.lse_rows + r0; g.epi_lab = P.labels + r0;
+    g.epi_w = row_w ? row_w + r0 : nullptr; g.epi_cnt = P.count;
+    return launch_gemm_off(ctx, mode, gv, g, r0, st);
+  }
+
+  // ---- vocabulary head over the compacted target rows P.hf (their number lives on the device) ----
+  // Without stored logits (bf16, vocabulary a multiple of 256): per chunk of target rows, the product hf W^T is run with an
+  // epilogue that keeps only per-block softmax statistics, a row pass turns them into log-sum-exp and loss, and the product
+  // is run again with an epilogue that writes (softmax - onehot) * factor as bf16: that matrix times W gives the gradient.
+  // Otherwise (fp32 tier, odd sizes): a float logits chunk, a row pass, the same second product.
+  bool head_fused = false;
+  int head_chunk_rows(int r0) const { return head_fused ? std::min(P.Mc, (int)cdiv(P.N - r0, 256) * 256) : std::min(P.Mc, P.N - r0); }
+  int head_begin(bool grads) {
+    int rc;
+    if (grads && (rc = transpose(P.V, P.d, W->head, P.d, P.headT, P.V))) return rc;                     // [d, V]
+    head_fused = P.head_fused;
+    if (!head_fused) return AS_OK;
+    GemmParams g; memset(&g, 0, sizeof g);
+    g.seg[0] = {P.hf, W->head, P.d, P.d, P.d}; g.nseg = 1; g.M = std::min(P.Mc, (int)cdiv(P.N, 256) * 256); g.N = P.V; g.m_dev = P.count;
+    g.C = P.P; g.ldc = P.V; g.splitk = 1;
+    if (!gemm_rs_applies(mode, g)) return as_fail(ctx, AS_ERR_SHAPE, "the head matrix must be 16-byte aligned");
+    return launch_label_logit(ctx, P.hf, W->head, P.d, P.labels, P.count, P.N, P.zlab, st);
+  }
+  int head_losses(int r0, int rows) {                        // per-target losses of one chunk
+    int rc;
+    if (head_fused) {
+      if ((rc = head_gemm(GEMM_EPI_STATS, rows, r0, nullptr, nullptr))) return rc;
+      return launch_ce_finish(ctx, P.part, P.V / 128, r0, rows, P.count, P.zlab, P.lse_rows, P.loss_rows, st);
+    }
+    if ((rc = gemm(rows, P.V, off(P.hf, (size_t)r0 * P.d), P.d, W->head, P.d, P.d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.logits, P.V, 1, 1.f, 0, P.count, r0))) return rc;
+    return launch_ce_rows(ctx, mode, P.logits, rows, P.V, r0, P.labels, P.count, P.loss_rows, nullptr, nullptr, st);
+  }
+  // gradient rows dhf = ((softmax - onehot) * factor) W, factor = row_w or 1 / count; with_losses: the losses too (else they
+  // are there already); dw_head: the head's own gradient (full fine-tuning), summed over the chunks
+  int head_grad_rows(const float* row_w, bool with_losses, float* dw_head) {
+    const int N = P.N, d = P.d, V = P.V, Mc = P.Mc;
+    int rc;
+    for (int ch = 0, chunks = (int)cdiv(N, Mc); ch < chunks; ch++) {
+      const int r0 = ch * Mc, rows = head_chunk_rows(r0);
+      const void* hf_c = off(P.hf, (size_t)r0 * d);
+      if (head_fused) {
+        if (with_losses && (rc = head_losses(r0, rows))) return rc;
+        if ((rc = head_gemm(GEMM_EPI_PROB, rows, r0, row_w, P.P))) return rc;
+      } else {
+        if ((rc = gemm(rows, V, hf_c, d, W->head, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.logits, V, 1, 1.f, 0, P.count, r0))) return rc;
+        if ((rc = launch_ce_rows(ctx, mode, P.logits, rows, V, r0, P.labels, P.count, P.loss_rows, row_w, P.P, st))) return rc;
+      }
+      if ((rc = gemm(rows, d, P.P, V, P.headT, V, V, nullptr, 0, nullptr, 0, 0, nullptr, 0, off(P.dhf, (size_t)r0 * d), d, 0, 1.f, 0, P.count, r0))) return rc;
+      if (dw_head) {
+        // dW_head += P_c^T hf_c  (rows past the live count are read as zero)
+        // the contraction length is padded to whole 64-token steps (zero rows past the chunk), so that the MFMA kernel takes it
+        const int rows64 = (int)cdiv(rows, 64) * 64;
+        if ((rc = launch_transpose(ctx, mode, rows, rows64, V, P.P, V, P.Pt, Mc, P.count, r0, st))) return rc;
+        if ((rc = launch_transpose(ctx, mode, rows, rows64, d, hf_c, d, P.hfT, Mc, P.count, r0, st))) return rc;
+        if ((rc = gemm(V, d, P.Pt, Mc, P.hfT, Mc, rows64, nullptr, 0, nullptr, 0, 0, nullptr, 0, dw_head, d, 1, 1.f, ch > 0))) return rc;
+      }
+    }
+    return AS_OK;
+  }
+
   int head_and_loss(float* d_loss, float* d_loss_sum) {
     const bool full = c.train_mode == AS_FULL;
-    const int N = P.N, d = P.d, V = P.V, Mc = P.Mc;
+    const int N = P.N, d = P.d;
     int rc;
     // hf = RMSNorm(h_L) on the target rows only
     if ((rc = launch_rmsnorm_fwd(ctx, mode, N, d, P.h[P.L], P.tgt_idx, P.count, W->g_final, c.rms_eps, P.hf, P.rstd_f, st))) return rc;
-    if ((rc = transpose(V, d, W->head, d, P.headT, V))) return rc;                     // [d, V]
-    const int chunks = (int)cdiv(N, Mc);
+    if ((rc = head_begin(LS.kind != LOSS_SEQ_LOGP))) return rc;
     const float* row_w = nullptr;
     if (LS.kind != LOSS_MEAN) {
       // The factor of a target's gradient row depends on the sums over all targets, and the logits are never
       // kept: a first pass over the head yields the per-target losses only, a second one (below) the gradient.
-      for (int ch = 0; ch < chunks; ch++) {
-        const int r0 = ch * Mc, rows = std::min(Mc, N - r0);
-        if ((rc = gemm(rows, V, off(P.hf, (size_t)r0 * d), d, W->head, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.logits, V, 1, 1.f, 0, P.count, r0))) return rc;
-        if ((rc = launch_ce_rows(ctx, mode, P.logits, rows, V, r0, P.labels, P.count, P.loss_rows, nullptr, nullptr, st))) return rc;
-      }
+      for (int r0 = 0; r0 < N; r0 += P.Mc) if ((rc = head_losses(r0, head_chunk_rows(r0)))) return rc;
       float* logp = LS.d_logp ? LS.d_logp : P.logp_ws;
       if ((rc = launch_seq_logp(ctx, P.loss_rows, P.tgt_idx, P.count, LS.d_cu, LS.d_kept_of, LS.n_seg, logp, st))) return rc;
       if (LS.kind == LOSS_SEQ_LOGP) return AS_OK;
@@ -967,21 +1066,7 @@ struct Step {
       if ((rc = launch_dpo_row_weights(ctx, P.tgt_idx, P.count, LS.d_cu, LS.n_kept, P.w_kept, N, P.row_w, st))) return rc;
       row_w = P.row_w;
     }
-    for (int ch = 0; ch < chunks; ch++) {
-      const int r0 = ch * Mc, rows = std::min(Mc, N - r0);
-      const void* hf_c = off(P.hf, (size_t)r0 * d);
-      if ((rc = gemm(rows, V, hf_c, d, W->head, d, d, nullptr, 0, nullptr, 0, 0, nullptr, 0, P.logits, V, 1, 1.f, 0, P.count, r0))) return rc;
-      if ((rc = launch_ce_rows(ctx, mode, P.logits, rows, V, r0, P.labels, P.count, P.loss_rows, row_w, P.P, st))) return rc;
-      if ((rc = gemm(rows, d, P.P, V, P.headT, V, V, nullptr, 0, nullptr, 0, 0, nullptr, 0, off(P.dhf, (size_t)r0 * d), d, 0, 1.f, 0, P.count, r0))) return rc;
-      if (full) {
-        // dW_head += P_c^T hf_c  (rows past the live count are read as zero)
-        // the contraction length is padded to whole 64-token steps (zero rows past the chunk), so that the MFMA kernel takes it
-        const int rows64 = (int)cdiv(rows, 64) * 64;
-        if ((rc = launch_transpose(ctx, mode, rows, rows64, V, P.P, V, P.Pt, Mc, P.count, r0, st))) return rc;
-        if ((rc = launch_transpose(ctx, mode, rows, rows64, d, hf_c, d, P.hfT, Mc, P.count, r0, st))) return rc;
-        if ((rc = gemm(V, d, P.Pt, Mc, P.hfT, Mc, rows64, nullptr, 0, nullptr, 0, 0, nullptr, 0, G->head, d, 1, 1.f, ch > 0))) return rc;
-      }
-    }
+    if ((rc = head_grad_rows(row_w, LS.kind == LOSS_MEAN, full ? G->head : nullptr))) return rc;
     if (LS.kind == LOSS_MEAN && (rc = launch_loss_finalize(ctx, P.loss_rows, P.count, d_loss, d_loss_sum, st))) return rc;
     // back through the final norm, scattered to all rows (zero where a row is no target)
     if (full && (rc = launch_rmsnorm_dgain(ctx, mode, N, d, P.dhf, P.tgt_pos, P.h[P.L], P.rstd_f, P.gpart, 256, G->g_final, st))) return rc;
@@ -1227,6 +1312,52 @@ extern "C" int as_dpo_step(as_ctx* ctx, const as_weights* weights, const as_lora
   LS.d_stats = d_stats; LS.d_logp = d_logp;
   return run_step(ctx, "as_dpo_step", weights, lora, d_tokens, d_cu_seqlens, h_cu_seqlens, n_segments, h_seg_skip, d_loss_mask,
                   n_rows, row_len, nullptr, nullptr, nullptr, grads, d_workspace, workspace_bytes, stream, LS);
+}
+
+static int check_mode(as_ctx* ctx, int mode);
+
+// ------------------------------------------------------ head as a building block
+// the head's scratch buffers alone, carved from a workspace (same sizes as inside the step's plan)
+static void make_head_plan(const as_ctx* ctx, int mode, int64_t n_rows, Bump& w, Plan& P) {
+  const as_model_config& c = ctx->cfg;
+  P.N = (int)n_rows; P.cap = P.N; P.d = c.d_model; P.V = c.vocab; P.L = 0; P.es = mode == AS_FP32 ? 4 : 2;
+  P.head_fused = mode == AS_BF16 && P.V % 256 == 0 && P.d % 64 == 0;
+  P.Mc = P.head_fused ? (int)std::min<int64_t>(8192, cdiv(std::max(P.N, 1), 256) * 256) : (int)std::min<int64_t>(4096, cdiv(std::max(P.N, 1), 64) * 64);
+  const size_t es = (size_t)P.es, N = (size_t)P.N;
+  P.logits = (float*)w.take(P.head_fused ? 0 : (size_t)P.Mc * P.V * 4);
+  P.part = (float*)w.take(P.head_fused ? (size_t)P.Mc * (P.V / 128) * 8 : 0);
+  P.zlab = (float*)w.take(P.head_fused ? N * 4 : 0); P.lse_rows = (float*)w.take(P.head_fused ? N * 4 : 0);
+  P.P = w.take((size_t)P.Mc * P.V * es);
+  P.headT = w.take((size_t)P.V * P.d * es);
+}
+
+extern "C" int as_op_head_loss_workspace(const as_ctx* ctx, int mode, int64_t n_rows, size_t* bytes) {
+  if (!ctx || !bytes) return as_fail(nullptr, AS_ERR_NULL, "as_op_head_loss_workspace: NULL argument");
+  if ((mode != AS_FP32 && mode != AS_BF16) || n_rows < 1 || n_rows > (int64_t)1 << 30) return as_fail(const_cast<as_ctx*>(ctx), AS_ERR_SHAPE, "as_op_head_loss_workspace: mode / row count");
+  Bump w{nullptr, 0}; Plan P;
+  make_head_plan(ctx, mode, n_rows, w, P);
+  *bytes = (w.off + 255) & ~(size_t)255;
+  return AS_OK;
+}
+
+extern "C" int as_op_head_loss(as_ctx* ctx, int mode, int64_t n_rows, const void* hf, const void* head, const int32_t* labels,
+                               const int32_t* d_count, const float* row_w, float* loss_rows, void* dhf,
+                               void* d_workspace, size_t workspace_bytes, void* stream) {
+  if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_op_head_loss: NULL context");
+  int rc = check_mode(ctx, mode); if (rc) return rc;
+  if (!hf || !head || !labels || !d_count || !loss_rows || !dhf) return as_fail(ctx, AS_ERR_NULL, "as_op_head_loss: NULL operand");
+  if (n_rows < 1 || n_rows > (int64_t)1 << 30) return as_fail(ctx, AS_ERR_SHAPE, "as_op_head_loss: row count must be in [1, 2^30]");
+  if (!d_workspace || ((uintptr_t)d_workspace & 255)) return as_fail(ctx, AS_ERR_WORKSPACE, "as_op_head_loss: workspace must be non-NULL and 256-byte aligned");
+  Bump wsp{(char*)d_workspace, 0}; Plan P;
+  make_head_plan(ctx, mode, n_rows, wsp, P);
+  if (wsp.off > workspace_bytes) return as_fail(ctx, AS_ERR_WORKSPACE, "as_op_head_loss: workspace has %zu bytes, %zu needed", workspace_bytes, wsp.off);
+  P.hf = const_cast<void*>(hf); P.dhf = dhf; P.labels = const_cast<int32_t*>(labels); P.count = const_cast<int32_t*>(d_count); P.loss_rows = loss_rows;
+  as_weights W; memset(&W, 0, sizeof W); W.head = head;
+  hipStream_t st = (hipStream_t)stream;
+  AS_HIP(ctx, hipSetDevice(ctx->device));
+  Step S{ctx, ctx->cfg, P, st, mode, 0, 0, &W, nullptr, nullptr, 0, LossSpec()};
+  if ((rc = S.head_begin(true))) return rc;
+  return S.head_grad_rows(row_w, true, nullptr);
 }
 
 // -------------------------------------------------------------------- AdamW

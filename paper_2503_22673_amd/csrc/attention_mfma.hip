@@ -35,76 +35,6 @@ __device__ __forceinline__ f32x16 zero16() {
   return z;
 }
 
-// rows (token indices row0 .. row0+63, clamped to n-1) x DH columns starting at `col`
-template <int DH>
-struct TileIO {
-  static constexpr int LS = DH + 8;            // LDS row stride in elements: 16 B pad keeps 16 lanes on 64 banks
-  static constexpr int CPR = DH / 8;           // 16-byte chunks per row
-  static constexpr int PER = BKEY * CPR / 256; // chunks per thread
-  u32x4 r[PER];
-  __device__ __forceinline__ void fetch(const bf16_t* base, int64_t ld, int col, int row0, int n, int tid) {
-#pragma unroll
-    for (int i = 0; i < PER; i++) {
-      int c = tid + i * 256, row = c / CPR, cc = c % CPR;
-      int t = min(row0 + row, n - 1);
-      r[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)t * ld + col + cc * 8);
-    }
-  }
-  __device__ __forceinline__ void stash(bf16_t* s, int tid) const {
-#pragma unroll
-    for (int i = 0; i < PER; i++) {
-      int c = tid + i * 256, row = c / CPR, cc = c % CPR;
-      *reinterpret_cast<u32x4*>(s + row * LS + cc * 8) = r[i];
-    }
-  }
-};
-
-// token-major tile: DH rows (columns of the original tensor) x 64 tokens starting at t0
-template <int DH>
-struct TileIOT {
-  static constexpr int LST = BKEY + 8;         // LDS row stride in elements
-  static constexpr int PER = DH * 8 / 256;     // 16-byte chunks per thread
-  u32x4 r[PER];
-  __device__ __forceinline__ void fetch(const bf16_t* baseT, int64_t ldT, int c0, int t0, int tid) {
-#pragma unroll
-    for (int i = 0; i < PER; i++) {
-      int c = tid + i * 256, row = c >> 3, cc = c & 7;
-      r[i] = *reinterpret_cast<const u32x4*>(baseT + (int64_t)(c0 + row) * ldT + t0 + cc * 8);
-    }
-  }
-  __device__ __forceinline__ void stash(bf16_t* s, int tid) const {
-#pragma unroll
-    for (int i = 0; i < PER; i++) {
-      int c = tid + i * 256, row = c >> 3, cc = c & 7;
-      *reinterpret_cast<u32x4*>(s + row * LST + cc * 8) = r[i];
-    }
-  }
-};
-// fragment from a token-major tile: element j is token rbase + 8*(j/4) + j%4 of row `row`
-__device__ __forceinline__ bf16x8 frag_t(const bf16_t* s, int row, int rbase) {
-  constexpr int LST = BKEY + 8;
-  const bf16x4 lo = *reinterpret_cast<const bf16x4*>(s + row * LST + rbase);
-  const bf16x4 hi = *reinterpret_cast<const bf16x4*>(s + row * LST + rbase + 8);
-  bf16x8 v;
-#pragma unroll
-  for (int j = 0; j < 4; j++) { v[j] = lo[j]; v[4 + j] = hi[j]; }
-  return v;
-}
-
-// fragment with the contraction index along the LDS row (16-byte read)
-template <int LS>
-__device__ __forceinline__ bf16x8 frag_row(const bf16_t* s, int row, int k0) {
-  return *reinterpret_cast<const bf16x8*>(s + row * LS + k0);
-}
-// fragment with the contraction index down the LDS column: element j comes from
-// row rbase + 8*(j/4) + j%4 (the rows a lane half owns in the accumulator layout)
-template <int LS>
-__device__ __forceinline__ bf16x8 frag_col(const bf16_t* s, int rbase, int col) {
-  bf16x8 v;
-#pragma unroll
-  for (int j = 0; j < 8; j++) v[j] = s[(rbase + 8 * (j >> 2) + (j & 3)) * LS + col];
-  return v;
-}
 __device__ __forceinline__ bf16x8 pack8(const f32x16& a, int sl) {
   bf16x8 v;
 #pragma unroll
@@ -113,124 +43,6 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& a, int sl) {
 }
 
 // ------------------------------------------------------------------ forward
-// Workgroup: 4 waves = HPW query heads of one KV group x (4/HPW) blocks of 64
-// queries; all waves share the staged K and V tiles.
-template <int DH, int HPW>
-__global__ __launch_bounds__(256) void attn_fwd_mfma(AttnParams p, float sl2) {
-  constexpr int LS = DH + 8, KS = DH / 16, CB = DH / 32, QT = 64 * (4 / HPW);
-  __shared__ __align__(16) bf16_t sK[BKEY * LS];
-  __shared__ __align__(16) bf16_t sVt[DH * (BKEY + 8)];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, h = lane >> 5;
-  const int n = p.n, grp = p.Hq / p.Hkv;
-  const int j = blockIdx.y * HPW + (wave % HPW), g = j / grp;
-  const int t_wg = blockIdx.x * QT, t_base = t_wg + (wave / HPW) * 64;
-  const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* VT = (const bf16_t*)p.vT;
-
-  bf16x8 qf[2][KS];
-  int tq[2], ss[2];
-#pragma unroll
-  for (int qb = 0; qb < 2; qb++) {
-    tq[qb] = t_base + qb * 32 + l31;
-    int tc = min(tq[qb], n - 1);
-    ss[qb] = p.seg_start[tc];
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++)
-      qf[qb][ks] = *reinterpret_cast<const bf16x8*>(Q + (int64_t)tc * p.ldq + j * DH + ks * 16 + h * 8);
-  }
-  f32x16 o[2][CB];
-  float m[2], l[2];
-#pragma unroll
-  for (int qb = 0; qb < 2; qb++) { m[qb] = -INFINITY; l[qb] = 0.f;
-#pragma unroll
-    for (int cb = 0; cb < CB; cb++) o[qb][cb] = zero16(); }
-
-  const int kv_first = p.seg_start[min(t_wg, n - 1)] / BKEY;
-  const int kv_last = min(t_wg + QT - 1, n - 1) / BKEY;
-  TileIO<DH> ioK; TileIOT<DH> ioV;
-  ioK.fetch(K, p.ldkv, g * DH, kv_first * BKEY, n, tid);
-  ioV.fetch(VT, p.ldT, g * DH, kv_first * BKEY, tid);
-  for (int kt = kv_first; kt <= kv_last; kt++) {
-    __syncthreads();                       // everyone is done with the previous tile
-    ioK.stash(sK, tid); ioV.stash(sVt, tid);
-    __syncthreads();
-    if (kt < kv_last) { ioK.fetch(K, p.ldkv, g * DH, (kt + 1) * BKEY, n, tid); ioV.fetch(VT, p.ldT, g * DH, (kt + 1) * BKEY, tid); }
-    const int k0 = kt * BKEY;
-    if (k0 > t_base + 63 || t_base >= n) continue;          // tile lies after every query of this wave
-    f32x16 s[2][2];
-#pragma unroll
-    for (int qb = 0; qb < 2; qb++) { s[qb][0] = zero16(); s[qb][1] = zero16(); }
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++)
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++) {
-        bf16x8 a = frag_row<LS>(sK, kb * 32 + l31, ks * 16 + h * 8);
-#pragma unroll
-        for (int qb = 0; qb < 2; qb++) s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s[qb][kb], 0, 0, 0);
-      }
-    bf16x8 pb[2][4];
-#pragma unroll
-    for (int qb = 0; qb < 2; qb++) {
-      float mx = -INFINITY;
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-        for (int e = 0; e < 16; e++) {
-          int key = k0 + kb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-          float v = (key >= ss[qb] && key <= tq[qb]) ? s[qb][kb][e] * sl2 : -INFINITY;
-          s[qb][kb][e] = v;
-          mx = fmaxf(mx, v);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      float m_new = fmaxf(m[qb], mx);
-      float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      float alpha = fast_exp2(m[qb] - m_use);
-      m[qb] = m_new;
-      float rs = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-        for (int e = 0; e < 16; e++) { float pv = fast_exp2(s[qb][kb][e] - m_use); s[qb][kb][e] = pv; rs += pv; }
-      rs += __shfl_xor(rs, 32, 64);
-      l[qb] = l[qb] * alpha + rs;
-#pragma unroll
-      for (int cb = 0; cb < CB; cb++)
-#pragma unroll
-        for (int e = 0; e < 16; e++) o[qb][cb][e] *= alpha;
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++) { pb[qb][kb * 2] = pack8(s[qb][kb], 0); pb[qb][kb * 2 + 1] = pack8(s[qb][kb], 1); }
-    }
-#pragma unroll
-    for (int x = 0; x < 4; x++) {                            // x = kb*2 + sl: 16 keys each
-      const int rbase = (x >> 1) * 32 + (x & 1) * 16 + 4 * h;
-#pragma unroll
-      for (int cb = 0; cb < CB; cb++) {
-        bf16x8 a = frag_t(sVt, cb * 32 + l31, rbase);
-#pragma unroll
-        for (int qb = 0; qb < 2; qb++) o[qb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb][x], o[qb][cb], 0, 0, 0);
-      }
-    }
-  }
-  bf16_t* O = (bf16_t*)p.o;
-#pragma unroll
-  for (int qb = 0; qb < 2; qb++) {
-    if (tq[qb] >= n) continue;
-    float inv = 1.f / l[qb];
-    bf16_t* orow = O + ((int64_t)tq[qb] * p.Hq + j) * DH;
-#pragma unroll
-    for (int cb = 0; cb < CB; cb++)
-#pragma unroll
-      for (int b4 = 0; b4 < 4; b4++) {
-        bf16x4 w;
-#pragma unroll
-        for (int i = 0; i < 4; i++) w[i] = (bf16_t)(o[qb][cb][b4 * 4 + i] * inv);
-        *reinterpret_cast<bf16x4*>(orow + cb * 32 + 8 * b4 + 4 * h) = w;
-      }
-    if (h == 0) p.lse[(int64_t)tq[qb] * p.Hq + j] = (m[qb] + log2f(l[qb])) * 0.6931471805599453f;
-  }
-}
-
-// ------------------------------------------------- forward, second generation
-// Same orientation and tile sizes as above.  What differs:
 //  * K and V^T tiles go from global memory straight into LDS (no staging registers, no store pass), two
 //    stages deep, so a step costs one barrier; rows are unpadded and the 16-byte chunks of a row are
 //    XOR-swizzled with the row index so that fragment reads stay spread over the banks;
@@ -242,15 +54,49 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(AttnParams p, float sl2) {
 //    behind a wave-uniform branch.
 template <int ROWBYTES> __device__ __forceinline__ int swz_row(int row) { return ROWBYTES == 256 ? (row & 15) : ((row >> 1) & 7); }
 
-// [ROWS][COLS] bf16 tile -> LDS, 1 KB per wave instruction; source rows row0 + r are clamped to row_max
-template <int ROWS, int COLS, int NW>
-__device__ __forceinline__ void tile_to_lds(const bf16_t* base, int64_t ld, int row0, int row_max, bf16_t* s, int wave, int lane) {
-  constexpr int CPR = COLS / 8, RPL = 64 / CPR, NL = ROWS / RPL;
+// [ROWS][COLS] bf16 tile -> LDS, 1 KB per wave instruction.  The per-lane part of the addresses (row inside the tile,
+// swizzled chunk) is computed once per kernel (tile_offsets); a tile load is then a wave-uniform base, advanced with
+// scalar arithmetic, plus those 32-bit offsets.  Computing the addresses afresh for every tile cost about 140 vector
+// instructions per tile and wave, as many cycles of the vector unit as the softmax itself.
+template <int ROWS, int COLS, int NW> struct TileShape {
+  static constexpr int CPR = COLS / 8, RPL = 64 / CPR, NL = ROWS / RPL, PER = NL / NW;
   static_assert(NL % NW == 0, "tile rows must split evenly over the waves");
+};
+template <typename T> __device__ __forceinline__ const T* uniform_ptr(const T* ptr) {
+  const uint64_t v = (uint64_t)ptr;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const T*)(((uint64_t)hi << 32) | lo);
+}
+template <int ROWS, int COLS, int NW>
+__device__ __forceinline__ void tile_offsets(int64_t ld, int wave, int lane, uint32_t (&voff)[TileShape<ROWS, COLS, NW>::PER]) {
+  using S = TileShape<ROWS, COLS, NW>;
 #pragma unroll
-  for (int i = 0; i < NL / NW; i++) {
-    const int w = wave * (NL / NW) + i;
-    const int row = w * RPL + lane / CPR, c = lane % CPR;
+  for (int i = 0; i < S::PER; i++) {
+    const int w = wave * S::PER + i;
+    const int row = w * S::RPL + lane / S::CPR, c = lane % S::CPR;
+    voff[i] = (uint32_t)((row * ld + ((c ^ swz_row<COLS * 2>(row)) * 8)) * 2);      // bytes; the launcher keeps tiles under 4 GB
+  }
+}
+// tile whose first element is `tile` (wave-uniform), every row in bounds
+template <int ROWS, int COLS, int NW>
+__device__ __forceinline__ void tile_to_lds_fast(const bf16_t* tile, const uint32_t (&voff)[TileShape<ROWS, COLS, NW>::PER], bf16_t* s, int wave) {
+  using S = TileShape<ROWS, COLS, NW>;
+  const char* b = (const char*)uniform_ptr(tile);
+#pragma unroll
+  for (int i = 0; i < S::PER; i++)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b + voff[i]),
+                                     (__attribute__((address_space(3))) void*)(s + (wave * S::PER + i) * 512), 16, 0, 0);
+}
+// row-major tensor, tile rows row0 .. row0 + ROWS - 1; rows past row_max (only the last tile of the stream has any) are clamped
+template <int ROWS, int COLS, int NW>
+__device__ __forceinline__ void tile_to_lds(const bf16_t* base, int64_t ld, int row0, int row_max, const uint32_t (&voff)[TileShape<ROWS, COLS, NW>::PER],
+                                            bf16_t* s, int wave, int lane) {
+  using S = TileShape<ROWS, COLS, NW>;
+  if (row0 + ROWS - 1 <= row_max) { tile_to_lds_fast<ROWS, COLS, NW>(base + (int64_t)row0 * ld, voff, s, wave); return; }
+#pragma unroll
+  for (int i = 0; i < S::PER; i++) {
+    const int w = wave * S::PER + i;
+    const int row = w * S::RPL + lane / S::CPR, c = lane % S::CPR;
     const bf16_t* src = base + (int64_t)min(row0 + row, row_max) * ld + ((c ^ swz_row<COLS * 2>(row)) * 8);
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                      (__attribute__((address_space(3))) void*)(s + w * 512), 16, 0, 0);
@@ -307,11 +153,13 @@ __global__ __launch_bounds__(NWV * 64, QB == 1 ? 2 : 1) void attn_fwd2_mfma(Attn
 #pragma unroll
     for (int cb = 0; cb < CB; cb++) o[qb][cb] = zero16(); }
 
-  const int kv_first = p.seg_start[min(t_wg, n - 1)] / BKEY;
+  const int kv_first = __builtin_amdgcn_readfirstlane(p.seg_start[min(t_wg, n - 1)] / BKEY);
   const int kv_last = min(t_wg + QT - 1, n - 1) / BKEY;
+  uint32_t offR[TileShape<BKEY, DH, NWV>::PER], offT[TileShape<DH, BKEY, NWV>::PER];
+  tile_offsets<BKEY, DH, NWV>(p.ldkv, wave, lane, offR); tile_offsets<DH, BKEY, NWV>(p.ldT, wave, lane, offT);
   auto stage = [&](int kt, int b) {
-    tile_to_lds<BKEY, DH, NWV>(K + g * DH, p.ldkv, kt * BKEY, n - 1, sm + b * ST_E, wave, lane);
-    tile_to_lds<DH, BKEY, NWV>(VT + (int64_t)g * DH * p.ldT + kt * BKEY, p.ldT, 0, DH - 1, sm + b * ST_E + KT_E, wave, lane);
+    tile_to_lds<BKEY, DH, NWV>(K + g * DH, p.ldkv, kt * BKEY, n - 1, offR, sm + b * ST_E, wave, lane);
+    tile_to_lds_fast<DH, BKEY, NWV>(VT + (int64_t)g * DH * p.ldT + kt * BKEY, offT, sm + b * ST_E + KT_E, wave);
   };
   const int swK = swz_row<DH * 2>(l31), swV = swz_row<128>(l31);
   stage(kv_first, 0);
@@ -470,210 +318,6 @@ static void launch_delta(const AttnParams& p, int64_t rows, hipStream_t st) {
   attn_delta_kernel<<<(unsigned)cdiv(rows, 4), 256, 0, st>>>((const bf16_t*)p.o, (const bf16_t*)p.d_o, rows, DH, p.delta);
 }
 
-// ------------------------------------------------------------- backward: dQ
-// Wave = 32 queries of one head; workgroup = HPW heads x (4/HPW) query blocks.
-template <int DH, int HPW>
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma(AttnParams p, float scale, float sl2) {
-  constexpr int LS = DH + 8, KS = DH / 16, CB = DH / 32, QT = 32 * (4 / HPW);
-  __shared__ __align__(16) bf16_t sK[BKEY * LS];
-  __shared__ __align__(16) bf16_t sV[BKEY * LS];
-  __shared__ __align__(16) bf16_t sKt[DH * (BKEY + 8)];
-  const bf16_t* KT = (const bf16_t*)p.kT;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, h = lane >> 5;
-  const int n = p.n, grp = p.Hq / p.Hkv;
-  const int j = blockIdx.y * HPW + (wave % HPW), g = j / grp;
-  const int t_wg = blockIdx.x * QT, t_base = t_wg + (wave / HPW) * 32;
-  const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* V = (const bf16_t*)p.v;
-  const bf16_t* dO = (const bf16_t*)p.d_o;
-  const int tq = t_base + l31, tc = min(tq, n - 1), ss = p.seg_start[tc];
-  bf16x8 qf[KS], dof[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ks++) {
-    qf[ks] = *reinterpret_cast<const bf16x8*>(Q + (int64_t)tc * p.ldq + j * DH + ks * 16 + h * 8);
-    dof[ks] = *reinterpret_cast<const bf16x8*>(dO + ((int64_t)tc * p.Hq + j) * DH + ks * 16 + h * 8);
-  }
-  const float lse2 = p.lse[(int64_t)tc * p.Hq + j] * 1.4426950408889634f;
-  const float dl = p.delta[(int64_t)tc * p.Hq + j];
-  f32x16 dq[CB];
-#pragma unroll
-  for (int cb = 0; cb < CB; cb++) dq[cb] = zero16();
-
-  const int kv_first = p.seg_start[min(t_wg, n - 1)] / BKEY;
-  const int kv_last = min(t_wg + QT - 1, n - 1) / BKEY;
-  TileIO<DH> ioK, ioV; TileIOT<DH> ioKt;
-  ioK.fetch(K, p.ldkv, g * DH, kv_first * BKEY, n, tid);
-  ioV.fetch(V, p.ldkv, g * DH, kv_first * BKEY, n, tid);
-  ioKt.fetch(KT, p.ldT, g * DH, kv_first * BKEY, tid);
-  for (int kt = kv_first; kt <= kv_last; kt++) {
-    __syncthreads();
-    ioK.stash(sK, tid); ioV.stash(sV, tid); ioKt.stash(sKt, tid);
-    __syncthreads();
-    if (kt < kv_last) {
-      ioK.fetch(K, p.ldkv, g * DH, (kt + 1) * BKEY, n, tid); ioV.fetch(V, p.ldkv, g * DH, (kt + 1) * BKEY, n, tid);
-      ioKt.fetch(KT, p.ldT, g * DH, (kt + 1) * BKEY, tid);
-    }
-    const int k0 = kt * BKEY;
-    if (k0 > t_base + 31 || t_base >= n) continue;
-    f32x16 s[2], dp[2];
-    s[0] = zero16(); s[1] = zero16(); dp[0] = zero16(); dp[1] = zero16();
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++)
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++) {
-        bf16x8 a = frag_row<LS>(sK, kb * 32 + l31, ks * 16 + h * 8);
-        bf16x8 b = frag_row<LS>(sV, kb * 32 + l31, ks * 16 + h * 8);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
-        dp[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, dof[ks], dp[kb], 0, 0, 0);
-      }
-    bf16x8 dsb[4];
-#pragma unroll
-    for (int kb = 0; kb < 2; kb++) {
-#pragma unroll
-      for (int e = 0; e < 16; e++) {
-        int key = k0 + kb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-        float x = (key >= ss && key <= tq) ? s[kb][e] * sl2 - lse2 : -INFINITY;
-        s[kb][e] = fast_exp2(x) * (dp[kb][e] - dl);
-      }
-      dsb[kb * 2] = pack8(s[kb], 0); dsb[kb * 2 + 1] = pack8(s[kb], 1);
-    }
-#pragma unroll
-    for (int x = 0; x < 4; x++) {
-      const int rbase = (x >> 1) * 32 + (x & 1) * 16 + 4 * h;
-#pragma unroll
-      for (int cb = 0; cb < CB; cb++) {
-        bf16x8 a = frag_t(sKt, cb * 32 + l31, rbase);
-        dq[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsb[x], dq[cb], 0, 0, 0);
-      }
-    }
-  }
-  if (tq < n) {
-    bf16_t* row = (bf16_t*)p.dq + (int64_t)tq * p.ldq + j * DH;
-#pragma unroll
-    for (int cb = 0; cb < CB; cb++)
-#pragma unroll
-      for (int b4 = 0; b4 < 4; b4++) {
-        bf16x4 w;
-#pragma unroll
-        for (int i = 0; i < 4; i++) w[i] = (bf16_t)(dq[cb][b4 * 4 + i] * scale);
-        *reinterpret_cast<bf16x4*>(row + cb * 32 + 8 * b4 + 4 * h) = w;
-      }
-  }
-}
-
-// ---------------------------------------------------------- backward: dK, dV
-// Workgroup = 128 keys of one KV head, wave = 32 of them (a lane owns one key);
-// loops over the query heads of the group and over 64-query tiles.
-template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(AttnParams p, float scale, float sl2) {
-  constexpr int LS = DH + 8, KS = DH / 16, CB = DH / 32;
-  extern __shared__ __align__(16) unsigned char dyn_smem[];
-  bf16_t* sQ = (bf16_t*)dyn_smem;                         // [64][LS]
-  bf16_t* sdO = sQ + BKEY * LS;                           // [64][LS]
-  bf16_t* sQt = sdO + BKEY * LS;                          // [DH][72]
-  bf16_t* sdOt = sQt + DH * (BKEY + 8);                   // [DH][72]
-  float* sLse = (float*)(sdOt + DH * (BKEY + 8));         // [64]
-  float* sDel = sLse + BKEY;                              // [64]
-  const bf16_t* QT = (const bf16_t*)p.qT; const bf16_t* DOT = (const bf16_t*)p.doT;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, h = lane >> 5;
-  const int n = p.n, grp = p.Hq / p.Hkv, g = blockIdx.y;
-  const int u_wg = blockIdx.x * 128, u_base = u_wg + wave * 32;
-  const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* V = (const bf16_t*)p.v;
-  const bf16_t* dO = (const bf16_t*)p.d_o;
-  const int u = u_base + l31, uc = min(u, n - 1);
-  const int uend = (u < n) ? p.seg_end[uc] : 0;                 // queries u <= t < uend see this key
-  bf16x8 kf[KS], vf[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ks++) {
-    kf[ks] = *reinterpret_cast<const bf16x8*>(K + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
-    vf[ks] = *reinterpret_cast<const bf16x8*>(V + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
-  }
-  f32x16 dk[CB], dv[CB];
-#pragma unroll
-  for (int cb = 0; cb < CB; cb++) { dk[cb] = zero16(); dv[cb] = zero16(); }
-  // query tiles that can see any key of this workgroup
-  const int q_first = u_wg / BKEY;
-  const int q_last = (p.seg_end[min(u_wg + 127, n - 1)] - 1) / BKEY;
-  // this wave's keys are visible from queries in [u_base, w_end)
-  const int w_end = (u_base < n) ? p.seg_end[min(u_base + 31, n - 1)] : 0;
-  const int ntile = q_last - q_first + 1, total = ntile * grp;
-  TileIO<DH> ioQ, ioD; TileIOT<DH> ioQt, ioDt;
-  float r_lse = 0.f, r_del = 0.f;
-  auto fetch = [&](int it) {
-    const int jj = g * grp + it / ntile, t0 = (q_first + it % ntile) * BKEY;
-    ioQ.fetch(Q, p.ldq, jj * DH, t0, n, tid);
-    ioD.fetch(dO, (int64_t)p.Hq * DH, jj * DH, t0, n, tid);
-    ioQt.fetch(QT, p.ldT, jj * DH, t0, tid);
-    ioDt.fetch(DOT, p.ldT, jj * DH, t0, tid);
-    if (tid < BKEY) { int t = min(t0 + tid, n - 1); r_lse = p.lse[(int64_t)t * p.Hq + jj] * 1.4426950408889634f; r_del = p.delta[(int64_t)t * p.Hq + jj]; }
-  };
-  if (total > 0) fetch(0);
-  for (int it = 0; it < total; it++) {
-    __syncthreads();
-    ioQ.stash(sQ, tid); ioD.stash(sdO, tid); ioQt.stash(sQt, tid); ioDt.stash(sdOt, tid);
-    if (tid < BKEY) { sLse[tid] = r_lse; sDel[tid] = r_del; }
-    __syncthreads();
-    if (it + 1 < total) fetch(it + 1);
-    const int t0 = (q_first + it % ntile) * BKEY;
-    if (t0 + 63 < u_base || t0 >= w_end) continue;             // no query of the tile sees a key of this wave
-    f32x16 s[2], dp[2];
-    s[0] = zero16(); s[1] = zero16(); dp[0] = zero16(); dp[1] = zero16();
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++)
-#pragma unroll
-      for (int qb = 0; qb < 2; qb++) {
-        bf16x8 a = frag_row<LS>(sQ, qb * 32 + l31, ks * 16 + h * 8);
-        bf16x8 b = frag_row<LS>(sdO, qb * 32 + l31, ks * 16 + h * 8);
-        s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[ks], s[qb], 0, 0, 0);
-        dp[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, vf[ks], dp[qb], 0, 0, 0);
-      }
-    bf16x8 pbv[4], dsb[4];
-#pragma unroll
-    for (int qb = 0; qb < 2; qb++) {
-#pragma unroll
-      for (int b4 = 0; b4 < 4; b4++) {
-        const int qi0 = qb * 32 + 8 * b4 + 4 * h;            // 4 consecutive queries: one 16-byte read each
-        const f32x4 ls = *reinterpret_cast<const f32x4*>(&sLse[qi0]);
-        const f32x4 dl = *reinterpret_cast<const f32x4*>(&sDel[qi0]);
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-          const int e = b4 * 4 + i, t = t0 + qi0 + i;
-          float x = (t >= u && t < uend) ? s[qb][e] * sl2 - ls[i] : -INFINITY;
-          float pr = fast_exp2(x);
-          s[qb][e] = pr;
-          dp[qb][e] = pr * (dp[qb][e] - dl[i]);
-        }
-      }
-      pbv[qb * 2] = pack8(s[qb], 0); pbv[qb * 2 + 1] = pack8(s[qb], 1);
-      dsb[qb * 2] = pack8(dp[qb], 0); dsb[qb * 2 + 1] = pack8(dp[qb], 1);
-    }
-#pragma unroll
-    for (int x = 0; x < 4; x++) {
-      const int rbase = (x >> 1) * 32 + (x & 1) * 16 + 4 * h;
-#pragma unroll
-      for (int cb = 0; cb < CB; cb++) {
-        bf16x8 a = frag_t(sdOt, cb * 32 + l31, rbase);
-        bf16x8 b = frag_t(sQt, cb * 32 + l31, rbase);
-        dv[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pbv[x], dv[cb], 0, 0, 0);
-        dk[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, dsb[x], dk[cb], 0, 0, 0);
-      }
-    }
-  }
-  if (u < n) {
-    bf16_t* krow = (bf16_t*)p.dk + (int64_t)u * p.ldkv + g * DH;
-    bf16_t* vrow = (bf16_t*)p.dv + (int64_t)u * p.ldkv + g * DH;
-#pragma unroll
-    for (int cb = 0; cb < CB; cb++)
-#pragma unroll
-      for (int b4 = 0; b4 < 4; b4++) {
-        bf16x4 wk, wv;
-#pragma unroll
-        for (int i = 0; i < 4; i++) { wk[i] = (bf16_t)(dk[cb][b4 * 4 + i] * scale); wv[i] = (bf16_t)dv[cb][b4 * 4 + i]; }
-        *reinterpret_cast<bf16x4*>(krow + cb * 32 + 8 * b4 + 4 * h) = wk;
-        *reinterpret_cast<bf16x4*>(vrow + cb * 32 + 8 * b4 + 4 * h) = wv;
-      }
-  }
-}
-
 // ----------------------------------------------- backward, second generation
 // Same split and orientation as the kernels above, with the changes of attn_fwd2_mfma: tiles straight
 // into LDS, two stages, one barrier per step; token-major copies in quad-swapped order (16-byte fragment
@@ -712,11 +356,13 @@ __global__ __launch_bounds__(512) void attn_bwd_dq2_mfma(AttnParams p, float sca
 
   const int kv_first = __builtin_amdgcn_readfirstlane(p.seg_start[min(t_wg, n - 1)] / BKEY);
   const int kv_last = min(t_wg + QT - 1, n - 1) / BKEY;
+  uint32_t offR[TileShape<BKEY, DH, NWV>::PER], offT[TileShape<DH, BKEY, NWV>::PER];
+  tile_offsets<BKEY, DH, NWV>(p.ldkv, wave, lane, offR); tile_offsets<DH, BKEY, NWV>(p.ldT, wave, lane, offT);
   auto stage = [&](int kt, int b) {
     bf16_t* d = sm + b * ST_E;
-    tile_to_lds<BKEY, DH, NWV>(K + g * DH, p.ldkv, kt * BKEY, n - 1, d, wave, lane);
-    tile_to_lds<BKEY, DH, NWV>(V + g * DH, p.ldkv, kt * BKEY, n - 1, d + KT_E, wave, lane);
-    tile_to_lds<DH, BKEY, NWV>(KT + (int64_t)g * DH * p.ldT + kt * BKEY, p.ldT, 0, DH - 1, d + 2 * KT_E, wave, lane);
+    tile_to_lds<BKEY, DH, NWV>(K + g * DH, p.ldkv, kt * BKEY, n - 1, offR, d, wave, lane);
+    tile_to_lds<BKEY, DH, NWV>(V + g * DH, p.ldkv, kt * BKEY, n - 1, offR, d + KT_E, wave, lane);
+    tile_to_lds_fast<DH, BKEY, NWV>(KT + (int64_t)g * DH * p.ldT + kt * BKEY, offT, d + 2 * KT_E, wave);
   };
   const int swK = swz_row<DH * 2>(l31), swT = swz_row<128>(l31);
   stage(kv_first, 0);
@@ -822,15 +468,18 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float sc
   const int total = q_last - q_first + 1;
   // Query tiles are taken from the segment's end downwards: the workgroups of one head and segment that start
   // together then read the same tiles at the same time, whatever their own first tile is.
+  uint32_t offQ[TileShape<BKEY, DH, NWV>::PER], offD[TileShape<BKEY, DH, NWV>::PER], offT[TileShape<DH, BKEY, NWV>::PER];
+  tile_offsets<BKEY, DH, NWV>(p.ldq, wave, lane, offQ); tile_offsets<BKEY, DH, NWV>((int64_t)p.Hq * DH, wave, lane, offD);
+  tile_offsets<DH, BKEY, NWV>(p.ldT, wave, lane, offT);
   auto stage = [&](int it, int b) {
     const int t0 = (q_last - it) * BKEY;
     bf16_t* d = sm + b * ST_E;
-    tile_to_lds<BKEY, DH, NWV>(Q + jj * DH, p.ldq, t0, n - 1, d, wave, lane);
+    tile_to_lds<BKEY, DH, NWV>(Q + jj * DH, p.ldq, t0, n - 1, offQ, d, wave, lane);
     if constexpr (WHICH == 0) {
-      tile_to_lds<BKEY, DH, NWV>(dO + jj * DH, (int64_t)p.Hq * DH, t0, n - 1, d + KT_E, wave, lane);
-      tile_to_lds<DH, BKEY, NWV>(QTm + (int64_t)jj * DH * p.ldT + t0, p.ldT, 0, DH - 1, d + 2 * KT_E, wave, lane);
+      tile_to_lds<BKEY, DH, NWV>(dO + jj * DH, (int64_t)p.Hq * DH, t0, n - 1, offD, d + KT_E, wave, lane);
+      tile_to_lds_fast<DH, BKEY, NWV>(QTm + (int64_t)jj * DH * p.ldT + t0, offT, d + 2 * KT_E, wave);
     } else {
-      tile_to_lds<DH, BKEY, NWV>(DOT + (int64_t)jj * DH * p.ldT + t0, p.ldT, 0, DH - 1, d + KT_E, wave, lane);
+      tile_to_lds_fast<DH, BKEY, NWV>(DOT + (int64_t)jj * DH * p.ldT + t0, offT, d + KT_E, wave);
     }
     if (wave < (WHICH == 0 ? 2 : 1)) {                           // 64 lse (wave 0) and 64 delta (wave 1) values, 4 bytes a lane
       const float* src = (wave == 0 ? p.lse : p.delta) + (int64_t)min(t0 + lane, n - 1) * p.Hq + jj;
@@ -979,19 +628,11 @@ int fwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
   const int Np = (int)cdiv(p.n, 64) * 64, Dkv = p.Hkv * DH;
   if (!p.t_scratch) return as_fail(ctx, AS_ERR_WORKSPACE, "attention: the MFMA kernels need the token-major scratch buffer");
   p.ldT = Np; p.vT = p.t_scratch;
-  int rc = variant >= 3 ? launch_transpose_qs(ctx, AS_BF16, p.n, Np, Dkv, p.v, p.ldkv, p.t_scratch, Np, st)
-                        : launch_transpose(ctx, AS_BF16, p.n, Np, Dkv, p.v, p.ldkv, p.t_scratch, Np, nullptr, 0, st);   // V^T [Dkv, Np]
+  int rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, Dkv, p.v, p.ldkv, p.t_scratch, Np, st);   // V^T [Dkv, Np]
   if (rc) return rc;
   const float sl2 = 1.4426950408889634f / sqrtf((float)DH);
   const int hpw = heads_per_wg(p);
-  if (variant == 3) return hpw == 4 ? launch_fwd2<DH, 4, 2>(ctx, p, sl2, st) : hpw == 2 ? launch_fwd2<DH, 2, 2>(ctx, p, sl2, st) : launch_fwd2<DH, 1, 2>(ctx, p, sl2, st);
-  if (variant == 5) return hpw == 4 ? launch_fwd2<DH, 4, 1, 4>(ctx, p, sl2, st) : hpw == 2 ? launch_fwd2<DH, 2, 1, 4>(ctx, p, sl2, st) : launch_fwd2<DH, 1, 1, 4>(ctx, p, sl2, st);
-  if (variant == 4) return hpw == 4 ? launch_fwd2<DH, 4, 1>(ctx, p, sl2, st) : hpw == 2 ? launch_fwd2<DH, 2, 1>(ctx, p, sl2, st) : launch_fwd2<DH, 1, 1>(ctx, p, sl2, st);
-  if (hpw == 4) attn_fwd_mfma<DH, 4><<<dim3((unsigned)cdiv(p.n, 64), p.Hq / 4), 256, 0, st>>>(p, sl2);
-  else if (hpw == 2) attn_fwd_mfma<DH, 2><<<dim3((unsigned)cdiv(p.n, 128), p.Hq / 2), 256, 0, st>>>(p, sl2);
-  else attn_fwd_mfma<DH, 1><<<dim3((unsigned)cdiv(p.n, 256), p.Hq), 256, 0, st>>>(p, sl2);
-  AS_LAUNCH_CHECK(ctx);
-  return AS_OK;
+  return hpw == 4 ? launch_fwd2<DH, 4, 1>(ctx, p, sl2, st) : hpw == 2 ? launch_fwd2<DH, 2, 1>(ctx, p, sl2, st) : launch_fwd2<DH, 1, 1>(ctx, p, sl2, st);
 }
 
 template <int DH, int HPW>
@@ -1030,7 +671,7 @@ int bwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
   int rc;
   const float scale = 1.f / sqrtf((float)DH), sl2 = 1.4426950408889634f * scale;
   const int64_t rows = (int64_t)p.n * p.Hq;
-  if (variant >= 3) {
+  {
     if ((rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, Dkv, p.k, p.ldkv, ts, Np, st))) return rc;                       // K^T
     if ((rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, D, p.q, p.ldq, ts + (size_t)Dkv * Np, Np, st))) return rc;       // Q^T
     if ((rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, D, p.d_o, D, ts + (size_t)(Dkv + D) * Np, Np, st))) return rc;   // dO^T
@@ -1049,26 +690,6 @@ int bwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
     }
     return AS_OK;
   }
-  if ((rc = launch_transpose(ctx, AS_BF16, p.n, Np, Dkv, p.k, p.ldkv, ts, Np, nullptr, 0, st))) return rc;                       // K^T
-  if ((rc = launch_transpose(ctx, AS_BF16, p.n, Np, D, p.q, p.ldq, ts + (size_t)Dkv * Np, Np, nullptr, 0, st))) return rc;       // Q^T
-  if ((rc = launch_transpose(ctx, AS_BF16, p.n, Np, D, p.d_o, D, ts + (size_t)(Dkv + D) * Np, Np, nullptr, 0, st))) return rc;   // dO^T
-  attn_delta_kernel<<<(unsigned)cdiv(rows, 4), 256, 0, st>>>((const bf16_t*)p.o, (const bf16_t*)p.d_o, rows, DH, p.delta);
-  AS_LAUNCH_CHECK(ctx);
-  const int hpw = heads_per_wg(p);
-  if (hpw == 4) attn_bwd_dq_mfma<DH, 4><<<dim3((unsigned)cdiv(p.n, 32), p.Hq / 4), 256, 0, st>>>(p, scale, sl2);
-  else if (hpw == 2) attn_bwd_dq_mfma<DH, 2><<<dim3((unsigned)cdiv(p.n, 64), p.Hq / 2), 256, 0, st>>>(p, scale, sl2);
-  else attn_bwd_dq_mfma<DH, 1><<<dim3((unsigned)cdiv(p.n, 128), p.Hq), 256, 0, st>>>(p, scale, sl2);
-  AS_LAUNCH_CHECK(ctx);
-  {
-    constexpr size_t smem = (size_t)(2 * BKEY * (DH + 8) + 2 * DH * (BKEY + 8)) * sizeof(bf16_t) + 2 * BKEY * sizeof(float);
-    static bool attr_set = false;
-    if (!attr_set) {
-      AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv_mfma<DH>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-      attr_set = true;
-    }
-    attn_bwd_dkv_mfma<DH><<<dim3((unsigned)cdiv(p.n, 128), p.Hkv), 256, smem, st>>>(p, scale, sl2);
-  }
-  AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
 
@@ -1079,19 +700,16 @@ int attention_query_tile(int n_q_heads, int n_kv_heads) { return 32 * (8 / heads
 bool attention_mfma_ok(const AttnParams& p) {
   if (p.dh != 64 && p.dh != 128) return false;
   if (p.ldq % 8 || p.ldkv % 8) return false;
+  if (p.n > (1 << 23) || p.ldq > (1 << 24) || p.ldkv > (1 << 24)) return false;   // tile offsets are 32-bit byte counts
   uintptr_t a = (uintptr_t)p.q | (uintptr_t)p.k | (uintptr_t)p.v | (uintptr_t)p.o | (uintptr_t)p.d_o |
                 (uintptr_t)p.dq | (uintptr_t)p.dk | (uintptr_t)p.dv;
   return a % 16 == 0;
 }
 
-// variant: 0 = default (4), 2 = first-generation kernels, 3 = second generation with 64-query waves (forward),
-// 4 = second generation with 32-query waves
 int launch_attention_fwd_mfma(as_ctx* ctx, const AttnParams& p, int variant, hipStream_t st) {
-  if (variant == 0) variant = 4;
   return p.dh == 128 ? fwd_dh<128>(ctx, p, variant, st) : fwd_dh<64>(ctx, p, variant, st);
 }
 
 int launch_attention_bwd_mfma(as_ctx* ctx, const AttnParams& p, int variant, hipStream_t st) {
-  if (variant == 0) variant = 4;
   return p.dh == 128 ? bwd_dh<128>(ctx, p, variant, st) : bwd_dh<64>(ctx, p, variant, st);
 }

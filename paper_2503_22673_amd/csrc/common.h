@@ -88,7 +88,22 @@ struct GemmParams {
   // whole 256-row tiles run over the ragged last tile too (rows past M are computed from whatever is there and
   // written to rows past M of C; no row of the result depends on another row)
   int rows_cap;
+  // Column groups: several weight matrices whose outputs sit side by side in C (q | k | v, gate | up) as ONE launch: fewer,
+  // larger grids (every launch ends on a partial round of tiles) and the shared row panel of A is read once per tile row.
+  // Group g covers columns [cg_end[g-1], cg_end[g]) (multiples of 256); its rows of B come from cg_B1[g] (segment 0) and
+  // cg_B2[g] (segment 1), both indexed from the group's first column, and segment 1 reads A at column offset cg_a2[g]
+  // (each projection has its own adapter activations).  ncg == 0: seg[].B as usual.
+  int ncg; int cg_end[3]; const void* cg_B1[3]; const void* cg_B2[3]; int cg_a2[3];
+  // Vocabulary head without stored logits (hand-scheduled kernel only; rows and row arrays are those of A):
+  //  epi == GEMM_EPI_STATS: nothing is written to C; for every row and every 128-column block of the result the maximum and
+  //    the sum of exp(value - maximum) go to epi_part[(row * (N / 128) + block) * 2 + {0, 1}];
+  //  epi == GEMM_EPI_PROB:  C = w_row * (exp(value - epi_lse[row]) - [column == epi_lab[row]]), w_row = epi_w[row] when
+  //    given, else 1 / *epi_cnt: the gradient of the masked loss with respect to the logits, straight from the accumulators.
+  int epi; const float* epi_lse; const int32_t* epi_lab; const float* epi_w; const int32_t* epi_cnt; float* epi_part;
 };
+enum { GEMM_EPI_NONE = 0, GEMM_EPI_STATS = 1, GEMM_EPI_PROB = 2 };
+// the hand-scheduled kernel would take this product (whole 256 x 256 tiles, K in 64-wide steps, alignment)
+bool gemm_rs_applies(int mode, const GemmParams& p);
 int launch_gemm(as_ctx* ctx, int mode, int variant, const GemmParams& p, hipStream_t st);
 // live rows = *p.m_dev - m_off, clamped to [0, p.M]
 int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p, int m_off, hipStream_t st);
@@ -182,6 +197,12 @@ int launch_dpo_pairs(as_ctx* ctx, const int32_t* pairs, int n_pairs, const float
 int launch_dpo_row_weights(as_ctx* ctx, const int32_t* tgt_idx, const int32_t* count, const int32_t* cu, int n_kept,
                            const float* w_kept, int n, float* row_w, hipStream_t st);
 int launch_fill_float(as_ctx* ctx, float* p, int n, float v, hipStream_t st);
+// head without stored logits: z_lab[row] = hf[row] . W[labels[row]] for rows < *count; then per row the log-sum-exp from the
+// per-block statistics of the GEMM and loss = lse - z_lab
+int launch_label_logit(as_ctx* ctx, const void* hf, const void* W, int d, const int32_t* labels, const int32_t* count, int rows_cap,
+                       float* zlab, hipStream_t st);
+int launch_ce_finish(as_ctx* ctx, const float* part, int nblk, int row0, int rows_cap, const int32_t* count, const float* zlab,
+                     float* lse, float* loss_rows, hipStream_t st);
 int launch_loss_finalize(as_ctx* ctx, const float* loss_rows, const int32_t* count, float* loss,
                          float* loss_sum, hipStream_t st);
 int launch_splitk_reduce(as_ctx* ctx, const float* partial, int splitk, int64_t mn, int N, float alpha,

@@ -712,6 +712,60 @@ int launch_ce_rows(as_ctx* ctx, int mode, const float* logits, int rows_cap, int
   return AS_OK;
 }
 
+// ---- head without stored logits: the two small row kernels around the GEMMs
+// z_lab[row] = hf[row] . W[label[row]], one wave per target row (bf16 operands, float sum in a fixed order)
+__global__ __launch_bounds__(256) void label_logit_kernel(const bf16_t* __restrict__ hf, const bf16_t* __restrict__ W, int d,
+                                                          const int32_t* __restrict__ labels, const int32_t* __restrict__ count,
+                                                          float* __restrict__ zlab) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= *count) return;
+  const bf16_t* a = hf + (int64_t)row * d; const bf16_t* b = W + (int64_t)labels[row] * d;
+  float acc = 0.f;
+  for (int c = lane * 8; c < d; c += 512) {
+    const bf16x8 x = *reinterpret_cast<const bf16x8*>(a + c), y = *reinterpret_cast<const bf16x8*>(b + c);
+#pragma unroll
+    for (int k = 0; k < 8; k++) acc = fmaf((float)x[k], (float)y[k], acc);
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) zlab[row] = acc;
+}
+int launch_label_logit(as_ctx* ctx, const void* hf, const void* W, int d, const int32_t* labels, const int32_t* count, int rows_cap,
+                       float* zlab, hipStream_t st) {
+  if (rows_cap <= 0) return AS_OK;
+  if (d % 8) return as_fail(ctx, AS_ERR_SHAPE, "label logits: d_model must be a multiple of 8");
+  prof_begin(ctx, st, AS_K_CE, 0.0);
+  label_logit_kernel<<<(unsigned)cdiv(rows_cap, 4), 256, 0, st>>>((const bf16_t*)hf, (const bf16_t*)W, d, labels, count, zlab);
+  prof_end(ctx, st);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}
+
+// One wave per row of the chunk: combines the (maximum, sum of exponentials) pairs of the row's column blocks.
+// Rows are chunk-relative in `part`, absolute (row0 + r) in zlab / lse / loss_rows.
+__global__ __launch_bounds__(256) void ce_finish_kernel(const float* __restrict__ part, int nblk, int row0, const int32_t* __restrict__ count,
+                                                        const float* __restrict__ zlab, float* __restrict__ lse_out, float* __restrict__ loss_rows) {
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int row = row0 + r;
+  if (row >= *count) return;
+  const float2* pr = reinterpret_cast<const float2*>(part) + (int64_t)r * nblk;
+  float m = -INFINITY;
+  for (int b = lane; b < nblk; b += 64) m = fmaxf(m, pr[b].x);
+  m = wave_max(m);
+  float s = 0.f;
+  for (int b = lane; b < nblk; b += 64) { const float2 v = pr[b]; s += v.y * expf(v.x - m); }
+  s = wave_sum(s);
+  if (lane == 0) { const float lse = m + logf(s); lse_out[row] = lse; loss_rows[row] = lse - zlab[row]; }
+}
+int launch_ce_finish(as_ctx* ctx, const float* part, int nblk, int row0, int rows_cap, const int32_t* count, const float* zlab,
+                     float* lse, float* loss_rows, hipStream_t st) {
+  if (rows_cap <= 0) return AS_OK;
+  prof_begin(ctx, st, AS_K_CE, 0.0);
+  ce_finish_kernel<<<(unsigned)cdiv(rows_cap, 4), 256, 0, st>>>(part, nblk, row0, count, zlab, lse, loss_rows);
+  prof_end(ctx, st);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}
+
 // Sums the per-target losses in a fixed order: thread i takes a contiguous
 // slab, slabs are combined by a tree in LDS.
 __global__ void loss_finalize_kernel(const float* __restrict__ loss_rows, const int32_t* __restrict__ count,

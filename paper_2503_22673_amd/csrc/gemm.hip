@@ -257,38 +257,22 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p, i
 // Same tiling, but tiles travel global -> LDS directly (global_load_lds_dwordx4: a wavefront
 // deposits 64 x 16 bytes contiguously, i.e. 8 rows of 8 chunks), so no VGPR staging and no LDS
 // stores.  The destination cannot be padded, so chunks are XOR-swizzled instead: LDS slot
-// (row, c) holds the row's chunk c ^ (row & 7); each lane picks the matching global chunk.  Fragment
+// (row, c) holds the row's chunk c ^ ((row >> 1) & 7); each lane picks the matching global chunk.  Fragment
 // reads of 8 consecutive rows then touch 8 different 16-byte columns: no bank conflicts.
-// Fragments are double-buffered in registers so that the reads for the next 16-wide K step are in
-// flight while the MFMAs of the current one issue.  Needs every K segment to be a multiple of 64.
-// chunk swizzle of a tile row: which 3-bit value is XORed onto the chunk index
-template <int SWZ> __device__ __forceinline__ int swz(int r) {
-  if constexpr (SWZ == 0) return r & 7;
-  else if constexpr (SWZ == 1) return (r >> 1) & 7;
-  else return ((r & 3) << 1) | ((r >> 2) & 1);
-}
+// Fragments are double-buffered in registers.  The barrier of a K step sits before the last of its four
+// 16-wide slices: by then every fragment of the current tile is in registers, so the next tile's loads can
+// be issued into the buffer just released and the first fragments of the next tile are read while the last
+// slice's MFMAs run, instead of right after a barrier with nothing to overlap them.
+// Needs every K segment to be a multiple of 64.
+__device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
 
-// MAP: workgroup id -> tile.  0: de-interleave over the 8 XCDs, then groups of 8 row-tiles; 1: groups of 8 row-tiles
-// without the XCD step; 2: XCD step with groups of 4; 3: XCD step with groups of 16.
-template <int BM, int BN, int WM, int WN, bool DB, int SWZ, int PF, int MAP = 0>
+template <int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams p, int m_off, int tiles_m, int tiles_n) {
   constexpr int BK = 64, NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-  // PF >= 100: split roles.  The first half of the waves issues every tile load; the other half only
-  // touches, PF - 100 steps ahead, one word of each 128-byte line the tiles will need, and never waits
-  // for those loads.  Loads complete in issue order within a wave, so a wave that must wait for its
-  // tile loads cannot also have such a long-latency load outstanding; a wave of its own can.
-  // PF == 200: the barrier sits before the last 16-wide K slice of a step instead of after it: by then
-  // every fragment of the current tile is in registers, so the next tile's loads can be issued into the
-  // buffer just released and the first fragments of the next tile are read while the last slice's MFMAs
-  // run, instead of right after a barrier with nothing to overlap them.
-  constexpr bool EARLY = PF == 200;
-  constexpr bool SPLIT = PF >= 100 && !EARLY;
-  constexpr int PFD = SPLIT ? PF - 100 : EARLY ? 0 : PF;
-  constexpr int NLW = SPLIT ? NW / 2 : NW;               // waves that issue tile loads
-  constexpr int LA = BM / 8 / NLW, LB = BN / 8 / NLW;    // 1 KB wave-loads per loading wave and tile
+  constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;      // 1 KB wave-loads per wave and tile
   static_assert(LA >= 1 && LB >= 1, "tile too small for the wave count");
-  static_assert(!SPLIT || (BM == BN && (NW - NLW) * 64 == BM), "split roles: one warm-up lane per tile row");
+  static_assert(BK / 16 == 4, "the loop is written for four K slices");
   extern __shared__ __align__(16) unsigned char smem[];
   bf16_t* sA = (bf16_t*)smem;                            // [2][BM][64]
   bf16_t* sB = sA + 2 * BM * BK;                         // [2][BN][64]
@@ -301,8 +285,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
   int nblk = tiles_m * tiles_n, pid = blockIdx.x, z = blockIdx.y;
   if (pid >= nblk) return;
   int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
-  int logical = (MAP == 1) ? pid : xcd * q8 + min(xcd, rem) + loc;
-  constexpr int GROUP = (MAP == 2) ? 4 : (MAP == 3) ? 16 : 8;
+  int logical = xcd * q8 + min(xcd, rem) + loc;
+  constexpr int GROUP = 8;
   int in_group = GROUP * tiles_n, grp = logical / in_group, first_m = grp * GROUP;
   int gsize = min(tiles_m - first_m, GROUP);
   int tile_m = first_m + (logical % in_group) % gsize, tile_n = (logical % in_group) / gsize;
@@ -325,222 +309,107 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dlds_kernel(GemmParams
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
   // loader: wave-load i of this wave covers tile rows (wave*L + i)*8 .. +7; lane l sits at row l/8,
-  // LDS chunk l%8, and fetches global chunk (l%8) ^ (l/8)
+  // LDS chunk l%8, and fetches global chunk (l%8) ^ swz(row)
   const int lrow = lane >> 3;
-  const bool loader = !SPLIT || wave < NLW;
-  const int lw = loader ? wave : 0;
   int rowA[LA], rowB[LB];
   {
     const int mclamp = mmax, nclamp = p.N - 1;
 #pragma unroll
-    for (int i = 0; i < LA; i++) rowA[i] = rb + min(row0 + (lw * LA + i) * 8 + lrow, mclamp);
+    for (int i = 0; i < LA; i++) rowA[i] = rb + min(row0 + (wave * LA + i) * 8 + lrow, mclamp);
 #pragma unroll
-    for (int i = 0; i < LB; i++) rowB[i] = min(col0 + (lw * LB + i) * 8 + lrow, nclamp);
+    for (int i = 0; i < LB; i++) rowB[i] = min(col0 + (wave * LB + i) * 8 + lrow, nclamp);
   }
-  // EARLY: per-lane row pointers of the first K segment are kept in registers (no 64-bit multiplies per step)
-  const bf16_t* pA[EARLY ? LA : 1]; const bf16_t* pB[EARLY ? LB : 1];
-  if constexpr (EARLY) {
+  // per-lane row pointers of the first K segment are kept in registers (no 64-bit multiplies per step)
+  const bf16_t* pA[LA]; const bf16_t* pB[LB];
 #pragma unroll
-    for (int i = 0; i < LA; i++) pA[i] = (const bf16_t*)p.seg[0].A + (int64_t)rowA[i] * p.seg[0].lda + (((lane & 7) ^ swz<SWZ>((lw * LA + i) * 8 + lrow)) * 8);
+  for (int i = 0; i < LA; i++) pA[i] = (const bf16_t*)p.seg[0].A + (int64_t)rowA[i] * p.seg[0].lda + (((lane & 7) ^ swz((wave * LA + i) * 8 + lrow)) * 8);
 #pragma unroll
-    for (int i = 0; i < LB; i++) pB[i] = (const bf16_t*)p.seg[0].B + (int64_t)rowB[i] * p.seg[0].ldb + (((lane & 7) ^ swz<SWZ>((lw * LB + i) * 8 + lrow)) * 8);
-  }
+  for (int i = 0; i < LB; i++) pB[i] = (const bf16_t*)p.seg[0].B + (int64_t)rowB[i] * p.seg[0].ldb + (((lane & 7) ^ swz((wave * LB + i) * 8 + lrow)) * 8);
   auto fetch = [&](int it, int buf) {
     const bool first = it < nt0;
-    bf16_t* a = sA + buf * BM * BK + lw * LA * 8 * BK;
-    bf16_t* b = sB + buf * BN * BK + lw * LB * 8 * BK;
-    if constexpr (EARLY) {
-      if (first) {
-        const int k1 = (kr0.beg + it) * BK;
+    bf16_t* a = sA + buf * BM * BK + wave * LA * 8 * BK;
+    bf16_t* b = sB + buf * BN * BK + wave * LB * 8 * BK;
+    if (first) {
+      const int k1 = (kr0.beg + it) * BK;
 #pragma unroll
-        for (int i = 0; i < LA; i++)
-          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pA[i] + k1),
-                                           (__attribute__((address_space(3))) void*)(a + i * 8 * BK), 16, 0, 0);
+      for (int i = 0; i < LA; i++)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pA[i] + k1),
+                                         (__attribute__((address_space(3))) void*)(a + i * 8 * BK), 16, 0, 0);
 #pragma unroll
-        for (int i = 0; i < LB; i++)
-          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pB[i] + k1),
-                                           (__attribute__((address_space(3))) void*)(b + i * 8 * BK), 16, 0, 0);
-        return;
-      }
+      for (int i = 0; i < LB; i++)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pB[i] + k1),
+                                         (__attribute__((address_space(3))) void*)(b + i * 8 * BK), 16, 0, 0);
+      return;
     }
-    const bf16_t* A = (const bf16_t*)(first ? p.seg[0].A : p.seg[1].A);
-    const bf16_t* B = (const bf16_t*)(first ? p.seg[0].B : p.seg[1].B);
-    const int64_t lda = first ? p.seg[0].lda : p.seg[1].lda, ldb = first ? p.seg[0].ldb : p.seg[1].ldb;
-    const int k = (first ? kr0.beg + it : kr1.beg + it - nt0) * BK;
+    const bf16_t* A = (const bf16_t*)p.seg[1].A; const bf16_t* B = (const bf16_t*)p.seg[1].B;
+    const int64_t lda = p.seg[1].lda, ldb = p.seg[1].ldb;
+    const int k = (kr1.beg + it - nt0) * BK;
 #pragma unroll
     for (int i = 0; i < LA; i++)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(A + (int64_t)rowA[i] * lda + k + (((lane & 7) ^ swz<SWZ>((lw * LA + i) * 8 + lrow)) * 8)),
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(A + (int64_t)rowA[i] * lda + k + (((lane & 7) ^ swz((wave * LA + i) * 8 + lrow)) * 8)),
                                        (__attribute__((address_space(3))) void*)(a + i * 8 * BK), 16, 0, 0);
 #pragma unroll
     for (int i = 0; i < LB; i++)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(B + (int64_t)rowB[i] * ldb + k + (((lane & 7) ^ swz<SWZ>((lw * LB + i) * 8 + lrow)) * 8)),
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(B + (int64_t)rowB[i] * ldb + k + (((lane & 7) ^ swz((wave * LB + i) * 8 + lrow)) * 8)),
                                        (__attribute__((address_space(3))) void*)(b + i * 8 * BK), 16, 0, 0);
   };
 
-  // reader: row = base + l%32, logical chunk 2*ks + l/32 lives at chunk (2*ks + l/32) ^ (row & 7)
-  const int x7 = swz<SWZ>(lane & 31), hh = lane >> 5;
+  // reader: row = base + l%32, logical chunk 2*ks + l/32 lives at chunk (2*ks + l/32) ^ swz(row)
+  const int x7 = swz(lane & 31), hh = lane >> 5;
   int coff[BK / 16];
 #pragma unroll
   for (int ks = 0; ks < BK / 16; ks++) coff[ks] = ((2 * ks + hh) ^ x7) * 8;
 
-  // L2 warm-up: every tile step needs data nobody has asked for yet, so its latency is the
-  // fabric's; one 4-byte load per 128-byte line of the tile PF steps ahead makes the real tile
-  // loads hit in L2.  The load is issued through inline asm so that no wait is attached to it; its
-  // destination register is tied in and out of the asm, which keeps it reserved while loads are in
-  // flight, and it is only waited for after the loop.
-  unsigned pf_reg = 0;
-  auto warm = [&](int it) {
-    const bool first = it < nt0;
-    const bf16_t* A = (const bf16_t*)(first ? p.seg[0].A : p.seg[1].A);
-    const bf16_t* B = (const bf16_t*)(first ? p.seg[0].B : p.seg[1].B);
-    const int64_t lda = first ? p.seg[0].lda : p.seg[1].lda, ldb = first ? p.seg[0].ldb : p.seg[1].ldb;
-    const int k = (first ? kr0.beg + it : kr1.beg + it - nt0) * BK;
-    const int r = tid % BM;                              // thread -> one row of A, then one row of B
-    const bf16_t* ptr = (tid < BM) ? A + (int64_t)(rb + min(row0 + r, mmax)) * lda + k
-                                   : B + (int64_t)min(col0 + (tid - BM) % BN, p.N - 1) * ldb + k;
-    asm volatile("global_load_dword %0, %1, off" : "+v"(pf_reg) : "v"(ptr) : "memory");
-  };
-  unsigned pf_reg2 = 0;
-  const int wrow = SPLIT ? (wave - NLW) * 64 + lane : 0;   // split roles: this lane's tile row
-  const int64_t wrowA = rb + min(row0 + wrow, mmax), wrowB = min(col0 + wrow, p.N - 1);
-  auto warm2 = [&](int it) {
-    const bool first = it < nt0;
-    const bf16_t* A = (const bf16_t*)(first ? p.seg[0].A : p.seg[1].A);
-    const bf16_t* B = (const bf16_t*)(first ? p.seg[0].B : p.seg[1].B);
-    const int64_t lda = first ? p.seg[0].lda : p.seg[1].lda, ldb = first ? p.seg[0].ldb : p.seg[1].ldb;
-    const int k = (first ? kr0.beg + it : kr1.beg + it - nt0) * BK;
-    const bf16_t* pa = A + wrowA * lda + k;
-    const bf16_t* pb = B + wrowB * ldb + k;
-    asm volatile("global_load_dword %0, %1, off" : "+v"(pf_reg) : "v"(pa) : "memory");
-    asm volatile("global_load_dword %0, %1, off" : "+v"(pf_reg2) : "v"(pb) : "memory");
-  };
-
-  if (nt > 0 && loader) fetch(0, 0);
+  if (nt > 0) fetch(0, 0);
   __builtin_amdgcn_s_waitcnt(0x0f70);                    // vmcnt(0): the first tile has landed
   __syncthreads();
-  if constexpr (EARLY) {
-    static_assert(!EARLY || (DB && BK / 16 == 4), "early-barrier loop is written for four K slices");
-    bf16x8 af[2][TM], bfr[2][TN];
-    auto rd = [&](int buf, int ks, int slot) {
-      const bf16_t* a = sA + buf * BM * BK + (wm * TM * 32 + (lane & 31)) * BK;
-      const bf16_t* b = sB + buf * BN * BK + (wn * TN * 32 + (lane & 31)) * BK;
-#pragma unroll
-      for (int i = 0; i < TM; i++) af[slot][i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * BK + coff[ks]);
-#pragma unroll
-      for (int j = 0; j < TN; j++) bfr[slot][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * BK + coff[ks]);
-    };
-    auto mm = [&](int slot) {
-#pragma unroll
-      for (int i = 0; i < TM; i++)
-#pragma unroll
-        for (int j = 0; j < TN; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
-    };
-    auto weave = [&]() {                                   // one LDS read between MFMAs, then the rest of the MFMAs
-#pragma unroll
-      for (int r = 0; r < TM + TN; r++) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
-    };
-    if (nt > 1) fetch(1, 1);
-    if (nt > 0) rd(0, 0, 0);
-    for (int it = 0; it < nt; it++) {
-      const int buf = it & 1;
-      rd(buf, 1, 1); mm(0); weave();
-      rd(buf, 2, 0); mm(1); weave();
-      rd(buf, 3, 1); mm(0); weave();
-      __builtin_amdgcn_s_waitcnt(0x0070);                  // vmcnt(0) lgkmcnt(0)
-      __syncthreads();                                     // tile it is in registers everywhere, tile it+1 has landed
-      // straight-line tail (the last two steps re-request the final tile into a buffer nobody reads
-      // again, and read fragments nobody uses), so that loads, LDS reads and MFMAs can interleave
-      fetch(min(it + 2, nt - 1), buf);
-      rd(buf ^ 1, 0, 0);
-      mm(1);
-#pragma unroll
-      for (int r = 0; r < TM + TN; r++) {
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x020, LA + LB, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0f70);                    // the re-requested tile must land before the workgroup's LDS is released
-  } else
-  for (int it = 0; it < nt; it++) {
-    const int buf = it & 1;
-    if constexpr (SPLIT) {
-      if (loader) { if (it + 1 < nt) fetch(it + 1, buf ^ 1); }
-      else if (it + PFD < nt) warm2(it + PFD);
-    } else if constexpr (PF > 0) {
-      // fixed instruction pattern per step (the last steps re-request tiles already seen), so that
-      // the wait counts are static: 8 tile loads, then one warm-up load that may stay in flight
-      fetch(min(it + 1, nt - 1), buf ^ 1);
-      warm(min(it + PFD, nt - 1));
-    } else {
-      if (it + 1 < nt) fetch(it + 1, buf ^ 1);
-    }
+  bf16x8 af[2][TM], bfr[2][TN];
+  auto rd = [&](int buf, int ks, int slot) {
     const bf16_t* a = sA + buf * BM * BK + (wm * TM * 32 + (lane & 31)) * BK;
     const bf16_t* b = sB + buf * BN * BK + (wn * TN * 32 + (lane & 31)) * BK;
-    if constexpr (DB) {
-      bf16x8 af[2][TM], bfr[2][TN];
 #pragma unroll
-      for (int i = 0; i < TM; i++) af[0][i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * BK + coff[0]);
+    for (int i = 0; i < TM; i++) af[slot][i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * BK + coff[ks]);
 #pragma unroll
-      for (int j = 0; j < TN; j++) bfr[0][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * BK + coff[0]);
+    for (int j = 0; j < TN; j++) bfr[slot][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * BK + coff[ks]);
+  };
+  auto mm = [&](int slot) {
 #pragma unroll
-      for (int ks = 0; ks < BK / 16; ks++) {
-        const int cur = ks & 1, nxt = cur ^ 1;
-        if (ks + 1 < BK / 16) {
+    for (int i = 0; i < TM; i++)
 #pragma unroll
-          for (int i = 0; i < TM; i++) af[nxt][i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * BK + coff[ks + 1]);
+      for (int j = 0; j < TN; j++)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
+  };
+  auto weave = [&]() {                                   // one LDS read between MFMAs, then the rest of the MFMAs
 #pragma unroll
-          for (int j = 0; j < TN; j++) bfr[nxt][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * BK + coff[ks + 1]);
-        }
-#pragma unroll
-        for (int i = 0; i < TM; i++)
-#pragma unroll
-          for (int j = 0; j < TN; j++)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
-        // ask the scheduler to keep this order: one LDS read of the next step between MFMAs of this one
-        if (ks + 1 < BK / 16) {
-#pragma unroll
-          for (int r = 0; r < TM + TN; r++) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          }
-          __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
-        } else {
-          __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
-        }
-      }
-    } else {
-#pragma unroll
-      for (int ks = 0; ks < BK / 16; ks++) {
-        bf16x8 af[TM], bfr[TN];
-#pragma unroll
-        for (int i = 0; i < TM; i++) af[i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * BK + coff[ks]);
-#pragma unroll
-        for (int j = 0; j < TN; j++) bfr[j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * BK + coff[ks]);
-#pragma unroll
-        for (int i = 0; i < TM; i++)
-#pragma unroll
-          for (int j = 0; j < TN; j++)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-      }
+    for (int r = 0; r < TM + TN; r++) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
-    // plain s_barrier: __syncthreads() would add a fence that waits for every outstanding load,
-    // the warm-up one included.  The tile loads are waited for explicitly; nothing else is shared.
-    if constexpr (SPLIT) { if (loader) __builtin_amdgcn_s_waitcnt(0x0f70); __builtin_amdgcn_s_barrier(); }
-    else if constexpr (PF > 0) { __builtin_amdgcn_s_waitcnt(0x0f71); __builtin_amdgcn_s_barrier(); }   // vmcnt(1)
-    else { __builtin_amdgcn_s_waitcnt(0x0f70); __syncthreads(); }                                 // vmcnt(0)
+    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+  };
+  if (nt > 1) fetch(1, 1);
+  if (nt > 0) rd(0, 0, 0);
+  for (int it = 0; it < nt; it++) {
+    const int buf = it & 1;
+    rd(buf, 1, 1); mm(0); weave();
+    rd(buf, 2, 0); mm(1); weave();
+    rd(buf, 3, 1); mm(0); weave();
+    __builtin_amdgcn_s_waitcnt(0x0070);                  // vmcnt(0) lgkmcnt(0)
+    __syncthreads();                                     // tile it is in registers everywhere, tile it+1 has landed
+    // straight-line tail (the last two steps re-request the final tile into a buffer nobody reads
+    // again, and read fragments nobody uses), so that loads, LDS reads and MFMAs can interleave
+    fetch(min(it + 2, nt - 1), buf);
+    rd(buf ^ 1, 0, 0);
+    mm(1);
+#pragma unroll
+    for (int r = 0; r < TM + TN; r++) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x020, LA + LB, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
   }
-  if constexpr (PF > 0) {
-    __builtin_amdgcn_s_waitcnt(0x0f70);                  // the last warm-up load must land before its register is reused
-    asm volatile("" : "+v"(pf_reg));
-    asm volatile("" : "+v"(pf_reg2));
-  }
+  __builtin_amdgcn_s_waitcnt(0x0f70);                    // the re-requested tile must land before the workgroup's LDS is released
   gemm_epilogue<TM, TN>(p, acc, M, z, row0, col0, row0 + wm * TM * 32 + 4 * (lane >> 5), col0 + wn * TN * 32 + (lane & 31),
                         (row0 + BM <= M) && (col0 + BN <= p.N), rb);
 }
@@ -606,7 +475,9 @@ __device__ __forceinline__ void gemm_epilogue_rows(const GemmParams& p, f32x16 (
 // the tile memory, which is free once every wave has left the loop, and reads it back 16 bytes per lane, so that a store
 // instruction writes four whole 256-byte row pieces.  Rows are 272 bytes apart in LDS.  The residual takes the same way
 // in: loaded 16 bytes per lane, parked at the place of the result, picked up by the lane that owns the element.
-template <int TM, int TN, bool MASK = false>
+// PROB: the values are turned into w_row * (exp(value - lse_row) - [column is the row's label]) before they are rounded
+// (the gradient of the masked cross-entropy with respect to the logits, written instead of the logits themselves).
+template <int TM, int TN, bool MASK = false, bool PROB = false>
 __device__ __forceinline__ void gemm_epilogue_staged(const GemmParams& p, f32x16 (&acc)[TM][TN], unsigned char* smem, int wave, int lane,
                                                      int row_w0, int col_w0, int row_lo = 0, int row_hi = 0) {
   constexpr int LROW = 272, ROWS = TM * 32;
@@ -627,7 +498,14 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmParams& p, f32x16
     asm volatile("" ::: "memory");
   }
 #pragma unroll
-  for (int i = 0; i < TM; i++)
+  for (int i = 0; i < TM; i++) {
+    float neg_lse2 = 0.f, wrow = 0.f; int clab = -1;
+    if (PROB) {                                          // rows outside the live range compute with the last live row's values and are not written
+      const int r = MASK ? min(max(row_w0 + 32 * i + l31, row_lo), row_hi - 1) : row_w0 + 32 * i + l31;
+      neg_lse2 = -1.4426950408889634f * p.epi_lse[r];
+      wrow = p.epi_w ? p.epi_w[r] : 1.f / (float)*p.epi_cnt;
+      clab = p.epi_lab[r] - col_w0 - 4 * hh;               // position of the label among this lane's columns of the block, if any
+    }
 #pragma unroll
     for (int j = 0; j < TN; j++)
 #pragma unroll
@@ -636,6 +514,11 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmParams& p, f32x16
         f32x4 v;
 #pragma unroll
         for (int k = 0; k < 4; k++) v[k] = alpha * acc[i][j][4 * b4 + k];
+        if (PROB) {
+#pragma unroll
+          for (int k = 0; k < 4; k++)
+            v[k] = wrow * (__builtin_amdgcn_exp2f(fmaf(v[k], 1.4426950408889634f, neg_lse2)) - (clab == 32 * j + 8 * b4 + k ? 1.f : 0.f));
+        }
         if (p.R) { const bf16x4_t x = *q;
 #pragma unroll
           for (int k = 0; k < 4; k++) v[k] += (float)x[k]; }
@@ -644,6 +527,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmParams& p, f32x16
         for (int k = 0; k < 4; k++) w[k] = (bf16_t)v[k];
         *q = w;
       }
+  }
   __builtin_amdgcn_s_waitcnt(0xc07f);
   asm volatile("" ::: "memory");
   bf16_t* c = (bf16_t*)p.C + (int64_t)(row_w0 + r4) * p.ldc + col_w0 + c16 * 8;
@@ -652,6 +536,37 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmParams& p, f32x16
     const int r = row_w0 + 4 * it + r4;
     if (!MASK || (r >= row_lo && r < row_hi))
       *reinterpret_cast<u32x4*>(c + (int64_t)(4 * it) * p.ldc) = *reinterpret_cast<const u32x4*>(my + (4 * it + r4) * LROW + c16 * 16);
+  }
+}
+
+// Softmax statistics of a wave's 128 x 128 block of logits, straight from the accumulators (same lane layout as above: a lane
+// owns row lane % 32 of every 32-row block and half of the block's 128 columns, the other half sits in lane ^ 32): per row the
+// maximum and the sum of exp(value - maximum) over the 128 columns.  Nothing of the logits is written.
+template <int TM, int TN, bool MASK>
+__device__ __forceinline__ void gemm_epilogue_stats(const GemmParams& p, f32x16 (&acc)[TM][TN], int row_lane, int blk, int hh, int row_lo, int row_hi) {
+  const float alpha = p.alpha;
+  const int nblk = p.N / 128;
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) m = fmaxf(m, alpha * acc[i][j][e]);
+    const float mo = __shfl_xor(m, 32, 64);
+    const float mx = fmaxf(m, mo);
+    const float nm2 = -1.4426950408889634f * mx;
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) s += __builtin_amdgcn_exp2f(fmaf(alpha * acc[i][j][e], 1.4426950408889634f, nm2));
+    s += __shfl_xor(s, 32, 64);
+    const int r = row_lane + 32 * i;
+    if (hh == 0 && (!MASK || (r >= row_lo && r < row_hi))) {
+      float2* q = reinterpret_cast<float2*>(p.epi_part) + (int64_t)r * nblk + blk;
+      *q = make_float2(mx, s);
+    }
   }
 }
 
@@ -743,10 +658,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int m_o
     for (int i = 0; i < 4; i++) scratch[i] = line[i];
     const unsigned scratch_addr = 131072u + (unsigned)tid * 64u;
     // wave-uniform operand bases: first of the wave's 64 rows of the tile, first K step
+    const bf16_t* b0p = (const bf16_t*)s0.B + (int64_t)b_group * p.grp_b_stride; const bf16_t* b1p = (const bf16_t*)s1.B;
+    int colg = col0, a2off = 0;
+    if (p.ncg > 0) {                                     // which weight matrix this column tile belongs to
+      int cgi = 0;
+      while (cgi + 1 < p.ncg && col0 >= p.cg_end[cgi]) cgi++;
+      colg = col0 - (cgi ? p.cg_end[cgi - 1] : 0);
+      b0p = (const bf16_t*)p.cg_B1[cgi]; b1p = (const bf16_t*)(p.nseg > 1 ? p.cg_B2[cgi] : p.cg_B1[cgi]); a2off = p.nseg > 1 ? p.cg_a2[cgi] : 0;
+    }
     const uint64_t A0 = (uint64_t)((const bf16_t*)s0.A + (int64_t)(row0 + wave * 64) * s0.lda);
-    const uint64_t B0 = (uint64_t)((const bf16_t*)s0.B + (int64_t)b_group * p.grp_b_stride + (int64_t)(col0 + wave * 64) * s0.ldb);
-    const uint64_t A1 = (uint64_t)((const bf16_t*)s1.A + (int64_t)(row0 + wave * 64) * s1.lda);
-    const uint64_t B1 = (uint64_t)((const bf16_t*)s1.B + (int64_t)(col0 + wave * 64) * s1.ldb);
+    const uint64_t B0 = (uint64_t)(b0p + (int64_t)(colg + wave * 64) * s0.ldb);
+    const uint64_t A1 = (uint64_t)((const bf16_t*)s1.A + a2off + (int64_t)(row0 + wave * 64) * s1.lda);
+    const uint64_t B1 = (uint64_t)(b1p + (int64_t)(colg + wave * 64) * s1.ldb);
     const int sA0 = (int)(16 * s0.lda), sB0 = (int)(16 * s0.ldb), sA1 = (int)(16 * s1.lda), sB1 = (int)(16 * s1.ldb);   // 8 rows, bytes
     asm volatile(GEMM_RS_LOOP_ASM
                  : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]),
@@ -757,181 +680,17 @@ __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int m_o
                  : GEMM_RS_LOOP_CLOBBERS);
   }
   // bf16 results with 16-byte rows leave through LDS (whole 256-byte row pieces per store), the rest row by row
+  if (p.epi == GEMM_EPI_STATS) { gemm_epilogue_stats<TM, TN, LIVE != 0>(p, acc, row0 + wm * TM * 32 + l31, (col0 + wn * TN * 32) / 128, hh, row_lo, row_hi); return; }
+  if (p.epi == GEMM_EPI_PROB) { gemm_epilogue_staged<TM, TN, LIVE != 0, true>(p, acc, smem, wave, lane, row0 + wm * TM * 32, col0 + wn * TN * 32, row_lo, row_hi); return; }
   const bool staged = !p.c_f32 && !(p.ldc % 8) && (!p.R || (!(p.ldr % 8) && !((uintptr_t)p.R % 16)));
   if (staged) gemm_epilogue_staged<TM, TN, LIVE != 0>(p, acc, smem, wave, lane, row0 + wm * TM * 32, col0 + wn * TN * 32, row_lo, row_hi);
   else gemm_epilogue_rows<TM, TN, LIVE != 0>(p, acc, row0 + wm * TM * 32 + l31, col0 + wn * TN * 32 + 4 * hh, row_lo, row_hi);
 }
 
-// Deep-pipeline variant: K steps of 32 (64-byte tile rows) and NS LDS stages, so that NS - 1 steps of tile loads
-// are in flight while one is consumed.  In the two-stage kernel above the loads of a step have one step's time
-// to arrive; measured with cycle stamps, its waves spend a third of every step at the barrier waiting for
-// the one wave whose loads came back late.  Same tile, wave layout, fragment order and epilogue.
-// Rows of 64 bytes hold four 16-byte chunks; chunk c of row r sits at chunk c ^ ((r >> 2) & 3).
-// With 4 waves per workgroup (256x128 or 128x256 tiles) two workgroups share a CU: their barriers are independent,
-// so one's waves keep the matrix cores busy while the other's wait.
-constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (lgkm << 8); }
-template <int BM, int BN, int WM, int WN, int NS>
-__global__ __launch_bounds__(WM * WN * 64, WM * WN == 4 ? 2 : 1) void gemm_mfma_deep_kernel(GemmParams p, int m_off, int tiles_m, int tiles_n) {
-  constexpr int BK = 32, NW = WM * WN;
-  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-  constexpr int LA = BM / 16 / NW, LB = BN / 16 / NW;    // 1 KB wave-loads (16 rows) per wave and tile
-  constexpr int ST_E = (BM + BN) * BK;                   // elements per stage
-  static_assert(LA >= 1 && LB >= 1, "tile too small for the wave count");
-  extern __shared__ __align__(16) unsigned char smem[];
-  bf16_t* sm = (bf16_t*)smem;
-
-  int rb, mmax;
-  const int M = gemm_rows(p, m_off, rb, mmax);
-  if (p.m_dev || p.grp_off) tiles_m = min(tiles_m, (max(M, 0) + BM - 1) / BM);
-  int nblk = tiles_m * tiles_n, pid = blockIdx.x, z = blockIdx.y;
-  if (pid >= nblk) return;
-  int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
-  int logical = xcd * q8 + min(xcd, rem) + loc;
-  constexpr int GROUP = 8;
-  int in_group = GROUP * tiles_n, grp = logical / in_group, first_m = grp * GROUP;
-  int gsize = min(tiles_m - first_m, GROUP);
-  int tile_m = first_m + (logical % in_group) % gsize, tile_n = (logical % in_group) / gsize;
-  const int row0 = tile_m * BM, col0 = tile_n * BN;
-  if (row0 >= M) return;
-
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave / WN, wn = wave % WN;
-  KRange kr0 = split_range(p.seg[0].K, BK, p.splitk, z);
-  KRange kr1 = {0, 0};
-  if (p.nseg > 1) kr1 = split_range(p.seg[1].K, BK, p.splitk, z);
-  const int nt0 = kr0.end - kr0.beg, nt = nt0 + (kr1.end - kr1.beg);
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; i++)
-#pragma unroll
-    for (int j = 0; j < TN; j++)
-#pragma unroll
-      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
-
-  // loader: wave-load i of this wave covers tile rows (wave*L + i)*16 .. +15; lane l sits at row l/4, LDS chunk l%4
-  const int lrow = lane >> 2;
-  int rowA[LA], rowB[LB];
-#pragma unroll
-  for (int i = 0; i < LA; i++) rowA[i] = rb + min(row0 + (wave * LA + i) * 16 + lrow, mmax);
-#pragma unroll
-  for (int i = 0; i < LB; i++) rowB[i] = min(col0 + (wave * LB + i) * 16 + lrow, p.N - 1);
-  const int gch = ((lane & 3) ^ ((lrow >> 2) & 3)) * 8;  // (tile row >> 2) & 3 == (lrow >> 2) & 3: loads start at multiples of 16 rows
-  // per-lane row pointers of the first K segment are kept (the second, short one recomputes them)
-  const bf16_t* pA[LA]; const bf16_t* pB[LB];
-#pragma unroll
-  for (int i = 0; i < LA; i++) pA[i] = (const bf16_t*)p.seg[0].A + (int64_t)rowA[i] * p.seg[0].lda + gch;
-#pragma unroll
-  for (int i = 0; i < LB; i++) pB[i] = (const bf16_t*)p.seg[0].B + (int64_t)rowB[i] * p.seg[0].ldb + gch;
-  auto fetch = [&](int it, int st) {
-    const bool first = it < nt0;
-    bf16_t* a = sm + st * ST_E + wave * LA * 16 * BK;
-    bf16_t* b = sm + st * ST_E + BM * BK + wave * LB * 16 * BK;
-    if (first) {
-      const int k = (kr0.beg + it) * BK;
-#pragma unroll
-      for (int i = 0; i < LA; i++)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pA[i] + k),
-                                         (__attribute__((address_space(3))) void*)(a + i * 16 * BK), 16, 0, 0);
-#pragma unroll
-      for (int i = 0; i < LB; i++)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pB[i] + k),
-                                         (__attribute__((address_space(3))) void*)(b + i * 16 * BK), 16, 0, 0);
-    } else {
-      const bf16_t* A = (const bf16_t*)p.seg[1].A; const bf16_t* B = (const bf16_t*)p.seg[1].B;
-      const int k = (kr1.beg + it - nt0) * BK;
-#pragma unroll
-      for (int i = 0; i < LA; i++)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(A + (int64_t)rowA[i] * p.seg[1].lda + k + gch),
-                                         (__attribute__((address_space(3))) void*)(a + i * 16 * BK), 16, 0, 0);
-#pragma unroll
-      for (int i = 0; i < LB; i++)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(B + (int64_t)rowB[i] * p.seg[1].ldb + k + gch),
-                                         (__attribute__((address_space(3))) void*)(b + i * 16 * BK), 16, 0, 0);
-    }
-  };
-
-  // reader: row = base + l%32, logical chunk 2*ks + l/32
-  const int l31 = lane & 31, hh = lane >> 5, x3 = (l31 >> 2) & 3;
-  const int coff0 = ((0 + hh) ^ x3) * 8, coff1 = ((2 + hh) ^ x3) * 8;
-  bf16x8 af[2][TM], bfr[2][TN];
-  auto rd = [&](int st, int ks, int slot) {
-    const bf16_t* a = sm + st * ST_E + (wm * TM * 32 + l31) * BK + (ks ? coff1 : coff0);
-    const bf16_t* b = sm + st * ST_E + BM * BK + (wn * TN * 32 + l31) * BK + (ks ? coff1 : coff0);
-#pragma unroll
-    for (int i = 0; i < TM; i++) af[slot][i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * BK);
-#pragma unroll
-    for (int j = 0; j < TN; j++) bfr[slot][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * BK);
-  };
-  auto mm = [&](int slot) {
-#pragma unroll
-    for (int i = 0; i < TM; i++)
-#pragma unroll
-      for (int j = 0; j < TN; j++)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
-  };
-  auto weave = [&]() {
-#pragma unroll
-    for (int r = 0; r < TM + TN; r++) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
-  };
-
-  // NS - 1 steps in flight; every step issues the same LA + LB loads (the last ones re-request the final
-  // step into a stage nobody reads again), so the wait counts are static
-  constexpr int NL = LA + LB;
-  if (nt > 0) {
-#pragma unroll
-  for (int i = 0; i < NS - 1; i++) fetch(min(i, nt - 1), i);
-  // step 0 has landed when at most (NS - 2) * NL loads are outstanding
-  __builtin_amdgcn_s_waitcnt(waitcnt_imm((NS - 2) * NL, 15));
-  __syncthreads();
-  rd(0, 0, 0);
-  for (int it = 0; it < nt; it++) {
-    const int st = it % NS;
-    fetch(min(it + NS - 1, nt - 1), (it + NS - 1) % NS);   // into the stage of step it-1: every wave left it before the last barrier
-    rd(st, 1, 1); mm(0); weave();
-    // step it+1 must have landed: the loads of steps it+2 .. it+NS-1 may stay in flight
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm((NS - 2) * NL, 0));
-    __builtin_amdgcn_s_barrier();
-    rd((it + 1) % NS, 0, 0);
-    mm(1);
-#pragma unroll
-    for (int r = 0; r < TM + TN; r++) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
-  }
-  __builtin_amdgcn_s_waitcnt(0x0f70);                    // re-requested steps must land before the workgroup's LDS is released
-  }
-  gemm_epilogue<TM, TN>(p, acc, M, z, row0, col0, row0 + wm * TM * 32 + 4 * (lane >> 5), col0 + wn * TN * 32 + (lane & 31),
-                        (row0 + BM <= M) && (col0 + BN <= p.N), rb);
-}
-
-template <int BM, int BN, int WM, int WN, int NS>
-static int launch_deep_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_t st) {
-  size_t smem = (size_t)NS * (BM + BN) * 32 * sizeof(bf16_t);
-  auto k0 = gemm_mfma_deep_kernel<BM, BN, WM, WN, NS>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(k0), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    attr_set = true;
-  }
-  int tm = (int)cdiv(p.M, BM), tn = (int)cdiv(p.N, BN);
-  dim3 grid(tm * tn, p.splitk > 1 ? p.splitk : 1);
-  k0<<<grid, WM * WN * 64, smem, st>>>(p, m_off, tm, tn);
-  AS_LAUNCH_CHECK(ctx);
-  return AS_OK;
-}
-
-template <int BM, int BN, int WM, int WN, bool DB, int SWZ, int PF = 0, int MAP = 0>
+template <int BM, int BN, int WM, int WN>
 static int launch_dlds_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_t st) {
   size_t smem = (size_t)2 * (BM + BN) * 64 * sizeof(bf16_t);
-  auto k0 = gemm_mfma_dlds_kernel<BM, BN, WM, WN, DB, SWZ, PF, MAP>;
+  auto k0 = gemm_mfma_dlds_kernel<BM, BN, WM, WN>;
   static bool attr_set = false;
   if (!attr_set) {
     AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(k0), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
@@ -958,6 +717,8 @@ static bool rs_ok(const GemmParams& p) {
 }
 
 static bool rs_live(const GemmParams& p) { return p.m_dev || p.grp_off; }
+static bool mfma_ok(const GemmParams& p);
+bool gemm_rs_applies(int mode, const GemmParams& p) { return mode == AS_BF16 && mfma_ok(p) && rs_ok(p); }
 
 static int launch_rs_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_t st) {
   constexpr size_t smem = 131072 + 256 * 64;             // two stages of A and B tiles + a 64-byte line per lane (the staged epilogue: 4 x 128 rows of 272 bytes)
@@ -1012,9 +773,9 @@ static bool mfma_ok(const GemmParams& p) {
   return true;
 }
 
-// Tile configuration of the MFMA kernels.  Register-staged: 0 = 256x256 (8 waves, 128x64 each), 1 = 256x64,
-// 2 = 64x256, 3 = 128x128, 4 = 256x256 with 4 waves of 128x128, 5 = 256x128, 6 = 128x256.  Direct-to-LDS 256x256
-// with 8 waves: 7, 8, 9 = chunk swizzle 0, 1, 2; 10, 11, 12 = swizzle 1 plus an L2 warm-up load 2, 3, 4 steps ahead.
+// Tile configuration of the MFMA kernels.  Register-staged (any K that is a multiple of 8): 0 = 256x256 (8 waves,
+// 128x64 each), 1 = 256x64, 2 = 64x256, 3 = 128x128.  20 = direct-to-LDS 256x256 with 8 waves (K in 64-wide steps);
+// 24 = the hand-scheduled register-staged 256x256 kernel with 4 waves.
 static int pick_cfg(const GemmParams& p) {
   // narrow outputs (the adapters' rank-wide products) stream A once at HBM speed: 128 x 128 tiles measured 2-33 % ahead of
   // 256 x 64 here (58,880 rows; N = 128: 121 against 181 us, where two 64-wide column tiles read A twice)
@@ -1050,14 +811,39 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
       return AS_OK;
     }
   }
-  if (variant < 0 || (variant > 2 && (variant < 10 || variant > 34))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
+  if (p.epi != GEMM_EPI_NONE) {
+    if (!gemm_rs_applies(mode, p) || variant == 1 || (variant >= 10 && variant != 34)) return as_fail(ctx, AS_ERR_SHAPE, "gemm: the head epilogues need the hand-scheduled kernel (bf16, N a multiple of 256, K in 64-wide steps)");
+    if (p.epi == GEMM_EPI_STATS && !p.epi_part) return as_fail(ctx, AS_ERR_NULL, "gemm: statistics epilogue without a buffer");
+    if (p.epi == GEMM_EPI_PROB && (!p.epi_lse || !p.epi_lab || (!p.epi_w && !p.epi_cnt) || p.c_f32 || p.R || (p.ldc % 8))) return as_fail(ctx, AS_ERR_SHAPE, "gemm: probability epilogue needs lse, labels, a row factor and bf16 output");
+  }
+  if (p.ncg > 0) {
+    if (p.ncg > 3 || p.grp_off || p.m_dev || p.splitk > 1 || p.cg_end[p.ncg - 1] != p.N) return as_fail(ctx, AS_ERR_SHAPE, "gemm: column groups need plain rows and ends that add up to N");
+    bool fused = mode == AS_BF16 && variant != 1 && mfma_ok(p) && (variant >= 10 ? variant - 10 : pick_cfg(p)) == 24 && rs_ok(p) &&
+                 p.rows_cap >= (int)cdiv(p.M, 256) * 256;      // the hand-scheduled kernel over every row tile
+    for (int g = 0; g < p.ncg && fused; g++) fused = p.cg_end[g] % 256 == 0 && !((uintptr_t)p.cg_B1[g] % 16) && (p.nseg < 2 || !((uintptr_t)p.cg_B2[g] % 16));
+    if (!fused) {                                        // one launch per group
+      const size_t esz = mode == AS_BF16 ? 2 : 4;
+      for (int g = 0, c0 = 0; g < p.ncg; c0 = p.cg_end[g], g++) {
+        GemmParams q = p; q.ncg = 0; q.N = p.cg_end[g] - c0;
+        q.seg[0].B = p.cg_B1[g];
+        if (p.nseg > 1) { q.seg[1].B = p.cg_B2[g]; q.seg[1].A = (const char*)p.seg[1].A + (size_t)p.cg_a2[g] * esz; }
+        q.C = (char*)p.C + (size_t)c0 * (p.c_f32 ? 4 : esz);
+        if (p.R) q.R = (const char*)p.R + (size_t)c0 * esz;
+        const int rc1 = launch_gemm_off(ctx, mode, variant, q, m_off, st);
+        if (rc1) return rc1;
+      }
+      return AS_OK;
+    }
+  }
+  if (variant < 0 || (variant > 2 && variant != 10 && variant != 11 && variant != 12 && variant != 13 && variant != 30 && variant != 34)) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
   bool use_mfma = (mode == AS_BF16) && variant != 1 && mfma_ok(p);
   if (variant >= 2 && !use_mfma) return as_fail(ctx, AS_ERR_SHAPE, "gemm: MFMA kernel needs bf16 and 8-element alignment");
   int rc = AS_OK;
   double ksum = 0; for (int s = 0; s < p.nseg; s++) ksum += p.seg[s].K;
   int cfg = variant >= 10 ? variant - 10 : pick_cfg(p);
-  if (cfg >= 7) for (int s = 0; s < p.nseg; s++) if (p.seg[s].K % 64) cfg = 0;     // direct-to-LDS tiles need whole 64-wide K steps
-  const bool big = use_mfma && (cfg == 0 || cfg >= 4);
+  if (p.epi != GEMM_EPI_NONE) cfg = 24;                    // only the hand-scheduled kernel has those epilogues (checked above)
+  if (cfg >= 20) for (int s = 0; s < p.nseg; s++) if (p.seg[s].K % 64) cfg = 0;     // direct-to-LDS tiles need whole 64-wide K steps
+  const bool big = use_mfma && (cfg == 0 || cfg >= 20);
   const bool rs = use_mfma && cfg == 24 && rs_ok(p) && !rs_live(p) && !m_off;     // live-row launches keep their own timing classes
   prof_begin(ctx, st, rs ? AS_K_GEMM_RS : p.grp_off ? AS_K_GEMM_GROUPED : p.m_dev ? AS_K_GEMM_DEVROWS : !use_mfma ? AS_K_GEMM_FMA : big ? AS_K_GEMM_MFMA_256 : AS_K_GEMM_MFMA_SKINNY,
              p.grp_off ? 2.0 * p.grp_rows * p.N * ksum : p.m_dev ? 0.0 : 2.0 * p.M * p.N * ksum);
@@ -1066,28 +852,9 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
       case 1: rc = launch_mfma_cfg<256, 64, 4, 1>(ctx, p, m_off, st); break;
       case 2: rc = launch_mfma_cfg<64, 256, 1, 4>(ctx, p, m_off, st); break;
       case 3: rc = launch_mfma_cfg<128, 128, 2, 2>(ctx, p, m_off, st); break;
-      case 4: rc = launch_mfma_cfg<256, 256, 2, 2>(ctx, p, m_off, st); break;
-      case 5: rc = launch_mfma_cfg<256, 128, 2, 2>(ctx, p, m_off, st); break;
-      case 6: rc = launch_mfma_cfg<128, 256, 2, 2>(ctx, p, m_off, st); break;
-      case 7: rc = launch_dlds_cfg<256, 256, 2, 4, true, 0>(ctx, p, m_off, st); break;
-      case 8: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1>(ctx, p, m_off, st); break;
-      case 9: rc = launch_dlds_cfg<256, 256, 2, 4, true, 2>(ctx, p, m_off, st); break;
-      case 10: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 2>(ctx, p, m_off, st); break;
-      case 11: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 3>(ctx, p, m_off, st); break;
-      case 12: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 4>(ctx, p, m_off, st); break;
-      case 13: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 0, 1>(ctx, p, m_off, st); break;
-      case 14: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 0, 2>(ctx, p, m_off, st); break;
-      case 15: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 0, 3>(ctx, p, m_off, st); break;
-      case 16: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 102>(ctx, p, m_off, st); break;
-      case 17: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 103>(ctx, p, m_off, st); break;
-      case 18: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 104>(ctx, p, m_off, st); break;
-      case 19: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 106>(ctx, p, m_off, st); break;
-      case 20: rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 200>(ctx, p, m_off, st); break;
-      case 21: rc = launch_dlds_cfg<256, 256, 2, 2, true, 1, 200>(ctx, p, m_off, st); break;
-      case 22: rc = launch_deep_cfg<256, 256, 2, 4, 4>(ctx, p, m_off, st); break;
-      case 23: rc = launch_deep_cfg<256, 128, 2, 2, 3>(ctx, p, m_off, st); break;
+      case 20: rc = launch_dlds_cfg<256, 256, 2, 4>(ctx, p, m_off, st); break;
       case 24: {                                           // whole row tiles by the register-staged kernel, the ragged rest by the default one
-        if (!rs_ok(p) || (m_off && !p.m_dev)) { rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 200>(ctx, p, m_off, st); break; }
+        if (!rs_ok(p) || (m_off && !p.m_dev)) { rc = launch_dlds_cfg<256, 256, 2, 4>(ctx, p, m_off, st); break; }
         rc = launch_rs_cfg(ctx, p, m_off, st);
         if (rs_live(p)) break;                             // covers its ragged tiles itself
         const int done = p.rows_cap >= (int)cdiv(p.M, 256) * 256 ? p.M : p.M / 256 * 256;
@@ -1097,7 +864,7 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
           for (int s = 0; s < t.nseg; s++) t.seg[s].A = (const bf16_t*)t.seg[s].A + (int64_t)done * t.seg[s].lda;
           t.C = t.c_f32 ? (void*)((float*)t.C + (int64_t)done * t.ldc) : (void*)((bf16_t*)t.C + (int64_t)done * t.ldc);
           if (t.R) t.R = (const bf16_t*)t.R + (int64_t)done * t.ldr;
-          rc = launch_dlds_cfg<256, 256, 2, 4, true, 1, 200>(ctx, t, 0, st);
+          rc = launch_dlds_cfg<256, 256, 2, 4>(ctx, t, 0, st);
         }
         break; }
       default: rc = launch_mfma_cfg<256, 256, 2, 4>(ctx, p, m_off, st); break;

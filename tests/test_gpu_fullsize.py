@@ -102,6 +102,39 @@ def test_attention_config3_layout_sampled_rows():
         assert grad_norm_err(_f64(dqkv[u, D + Dkv + gk * dh:D + Dkv + (gk + 1) * dh]), dv) < 2e-2, u
 
 
+def test_head_config3_shape_sampled_target_rows():
+    """The head on as many target rows as config 3 has (12,412 of them: two passes of 8192, the second ragged), d 4096,
+    vocabulary 128,256, no logits stored: sampled rows against the definition in float64 (log-sum-exp over the whole
+    vocabulary, gradient row = factor * (softmax - onehot) W)."""
+    from paper_2503_22673_amd import binding as B
+    sh = synth.CONFIGS[3]
+    ctx = B.Context(B.make_config(sh))
+    n_rows, live, d, V = 12800, 12412, sh.d_model, sh.vocab
+    g = torch.Generator(device="cuda"); g.manual_seed(3)
+    hf = torch.empty(n_rows, d, dtype=torch.bfloat16, device="cuda").normal_(0, 1.0, generator=g)
+    head = torch.empty(V, d, dtype=torch.bfloat16, device="cuda").normal_(0, 0.02, generator=g)
+    labels = torch.randint(0, V, (n_rows,), dtype=torch.int32, device="cuda", generator=g)
+    labels[5] = 0; labels[8191] = V - 1; labels[8192] = 255; labels[live - 1] = 256
+    count = torch.tensor([live], dtype=torch.int32, device="cuda")
+    row_w = torch.empty(n_rows, dtype=torch.float32, device="cuda").uniform_(-1.0, 1.0, generator=g)
+    loss, dhf = ctx.op_head_loss(hf, head, labels, count, mode=B.AS_BF16)
+    loss_w, dhf_w = ctx.op_head_loss(hf, head, labels, count, row_w=row_w, mode=B.AS_BF16)
+    torch.cuda.synchronize()
+    assert torch.equal(loss, loss_w)
+    assert not dhf[live:].any().item() and not loss[live:].any().item()          # rows past the count are not touched
+    Wf = _f64(head)
+    for r in (0, 5, 255, 256, 4097, 8191, 8192, 8193, 11000, live - 1):
+        z = Wf @ _f64(hf[r])
+        m = z.max(); lse = m + np.log(np.exp(z - m).sum())
+        y = int(labels[r])
+        assert abs(float(loss[r]) - (lse - z[y])) <= 2e-3 * abs(lse - z[y]), r
+        pr = np.exp(z - lse); pr[y] -= 1.0
+        ref = (pr / live) @ Wf
+        assert grad_norm_err(_f64(dhf[r]), ref) <= 1e-2, (r, grad_norm_err(_f64(dhf[r]), ref))
+        ref_w = (pr * float(row_w[r])) @ Wf
+        assert grad_norm_err(_f64(dhf_w[r]), ref_w) <= 1e-2, r
+
+
 def test_config3_full_step_properties():
     """The benchmark's step itself (32 layers of 8B shapes, 4 x 16384 packed tokens, rank-64 adapters on the
     seven projections, selective recompute, loss-free segments skipped)."""

@@ -175,7 +175,7 @@ def test_per_kernel_timing_brackets_nested_launchers():
 
 @pytest.mark.parametrize("row_len", [384, 320])
 def test_wide_ffn_step_runs_the_hand_scheduled_gemm(row_len):
-    """ffn = 11264 with 3 row tiles makes 132 tiles of 256 x 256: the gate / up projections and the input gradient of
+    """ffn = 11264 with 3 row tiles makes 132 tiles of 256 x 256: the gate | up projection (one launch over both matrices) and the input gradient of
     the down projection (rank-64 adapter term as second K segment) go through the hand-scheduled kernel inside the
     step.  With rows of 384 the activation buffers hold 768 rows and the kernel covers the ragged last row tile itself
     (from the padded rows); with rows of 320 (640 rows) the ragged rest goes to the eight-wave kernel."""
@@ -200,4 +200,4 @@ def test_wide_ffn_step_runs_the_hand_scheduled_gemm(row_len):
     prof = ctx.profile_read()
     ctx.profile(False)
     assert float(out["loss"].item()) == a["loss"] == rep["loss"]
-    assert prof["gemm_mfma_rs"][0] >= 6, prof["gemm_mfma_rs"]                 # 2 layers x (gate, up, dX of down)
+    assert prof["gemm_mfma_rs"][0] >= 4, prof["gemm_mfma_rs"]                 # 2 layers x (gate | up in one launch, dX of down)

@@ -12,12 +12,19 @@
  * General rules
  *  - Every pointer is marked [host] or [device].  Device buffers are
  *    allocated and freed by the caller; the library keeps no device pointer
- *    after a call returns.  The only device memory the library owns is a
- *    staging buffer inside as_ctx used by as_pack (grown on demand).
+ *    of the caller's after a call returns.  Device memory of the library's
+ *    own: the staging buffer of as_pack inside as_ctx (pinned host + device,
+ *    grown on demand by as_pack only), and one fixed device array
+ *    (AS_STATIC_SCRATCH_BYTES, see as_op_attention_bwd_static).  No other call
+ *    allocates or frees memory of any kind on the device: as_train_step and its
+ *    relatives work inside the caller's workspace (their small per-step tables
+ *    included), as_adamw_update hands its tensor table over in kernel arguments.
+ *    With per-launch timing switched on (as_profile) events are created on demand.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    Calls enqueue work and return without waiting, except as_pack, which
- *    waits for its own upload; results are valid once the stream has been
- *    synchronised.
+ *    Calls enqueue work and return without waiting for the device, except
+ *    as_pack, which waits for its own upload; results are valid once the
+ *    stream has been synchronised.  Host arrays passed to a call may be
+ *    reused as soon as it returns.
  *  - Matrices are row-major.  A linear map y = W x stores W as [out, in].
  *  - Every function returns AS_OK (0) or a negative as_status.  Conditions
  *    that can be checked on the host are checked before anything is
@@ -308,8 +315,8 @@ int as_dpo_step(as_ctx* ctx, const as_weights* weights, const as_lora* lora,
  *  d_master float (the fp32 weights that are updated); d_params_lowp either
  *  NULL or, per tensor, NULL or a bfloat16 copy rewritten from the master
  *  (round to nearest even); d_grads, d_m, d_v float.  step counts from 1.
- *  All tensors are updated by one kernel launch (a table of tensors and 65,536-element chunks is staged through
- *  pinned memory the context owns; the call waits for the previous call's table copy, not for its kernel). */
+ *  The tensors go out in batches of 48 per kernel launch, each batch described in the launch's own argument (no
+ *  table in device memory, nothing allocated, nothing waited for). */
 int as_adamw_update(as_ctx* ctx, float* const* d_master, void* const* d_params_lowp,
                     const float* const* d_grads, float* const* d_m, float* const* d_v,
                     const int64_t* numel, const uint8_t* apply_wd, int32_t n_tensors,

@@ -168,14 +168,8 @@ extern "C" int as_probe_mfma_peak(as_ctx* ctx, int32_t iters, int32_t blocks, fl
 extern "C" void as_destroy(as_ctx* ctx) {
   if (!ctx) return;
   for (auto& r : ctx->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
-  if (ctx->step_ev) { (void)hipEventSynchronize(ctx->step_ev); (void)hipEventDestroy(ctx->step_ev); }
-  if (ctx->d_step) (void)hipFree(ctx->d_step);
-  if (ctx->h_step) (void)hipHostFree(ctx->h_step);
   if (ctx->d_stage) (void)hipFree(ctx->d_stage);
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
-  if (ctx->adam_ev) { (void)hipEventSynchronize(ctx->adam_ev); (void)hipEventDestroy(ctx->adam_ev); }
-  if (ctx->d_adam) (void)hipFree(ctx->d_adam);
-  if (ctx->h_adam) (void)hipHostFree(ctx->h_adam);
   delete ctx;
 }
 
@@ -403,6 +397,7 @@ struct Plan {
   int cap;                               // token rows every activation buffer holds (rows * row_len of the plan)
   int n_qkv, n_gu;                       // adapters inside the q/k/v and gate/up groups
   int32_t *seg_start, *seg_end, *tgt_idx, *tgt_pos, *labels, *count, *iscratch;
+  int32_t* step_tab; size_t step_tab_ints;   // per-step host table: segment table, sources, attention launch orders, kept-segment map, pairs
   int32_t *tok_c; uint8_t* mask_c;       // tokens and mask with the skipped segments squeezed out
   const int32_t *order_q = nullptr, *order_k = nullptr;   // attention launch orders of this step (longest workgroups first)
   float *rope_cos, *rope_sin, *loss_rows, *rstd_f, *logits, *delta, *partial, *gpart;
@@ -462,6 +457,8 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   P.seg_start = (int32_t*)w.take(N * 4); P.seg_end = (int32_t*)w.take(N * 4);
   P.tgt_idx = (int32_t*)w.take(N * 4); P.tgt_pos = (int32_t*)w.take(N * 4); P.labels = (int32_t*)w.take(N * 4);
   P.count = (int32_t*)w.take(256);
+  P.step_tab_ints = 6 * N + 64;                           // (S+1) + S + N/32 + N/256 + S + 2 P with S, P <= N
+  P.step_tab = (int32_t*)w.take(P.step_tab_ints * 4);
   P.tok_c = (int32_t*)w.take(N * 4); P.mask_c = (uint8_t*)w.take(N);
   P.iscratch = (int32_t*)w.take(full ? 2 * N * 4 : 0);
   P.rope_cos = (float*)w.take((size_t)row_len * (c.head_dim / 2) * 4);
@@ -1080,24 +1077,11 @@ int Step::launch_lora_prep_ex(const float* in, int rows, int cols, int rows_pad,
 }
 }  // namespace
 
-// Small per-step table (compacted segment boundaries) host -> device through pinned memory the
-// context owns.  The previous step's copy is waited for before the pinned buffer is rewritten.
-static int stage_step_table(as_ctx* ctx, const void* src, size_t bytes, hipStream_t st) {
-  if (bytes > ctx->step_bytes) {
-    if (ctx->step_ev) (void)hipEventSynchronize(ctx->step_ev);
-    if (ctx->d_step) (void)hipFree(ctx->d_step);
-    if (ctx->h_step) (void)hipHostFree(ctx->h_step);
-    ctx->d_step = ctx->h_step = nullptr; ctx->step_bytes = 0;
-    size_t cap = std::max<size_t>(4096, bytes * 2);
-    AS_HIP(ctx, hipMalloc(&ctx->d_step, cap));
-    AS_HIP(ctx, hipHostMalloc(&ctx->h_step, cap, hipHostMallocDefault));
-    ctx->step_bytes = cap;
-  }
-  if (!ctx->step_ev) AS_HIP(ctx, hipEventCreateWithFlags(&ctx->step_ev, hipEventDisableTiming));
-  else AS_HIP(ctx, hipEventSynchronize(ctx->step_ev));
-  memcpy(ctx->h_step, src, bytes);
-  AS_HIP(ctx, hipMemcpyAsync(ctx->d_step, ctx->h_step, bytes, hipMemcpyHostToDevice, st));
-  AS_HIP(ctx, hipEventRecord(ctx->step_ev, st));
+// Small per-step table (compacted segment boundaries, launch orders, pair list) host -> device into the caller's
+// workspace.  The source is ordinary host memory: the copy call returns once it has taken the data over, so nothing of
+// the library's has to outlive the call.
+static int stage_step_table(as_ctx* ctx, const void* src, size_t bytes, void* dst, hipStream_t st) {
+  AS_HIP(ctx, hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, st));
   return AS_OK;
 }
 
@@ -1234,9 +1218,10 @@ static int run_step(as_ctx* ctx, const char* who, const as_weights* weights, con
       off_pairs = tab.size();
       if (LS.n_pairs > 0) tab.insert(tab.end(), LS.h_pairs, LS.h_pairs + 2 * (size_t)LS.n_pairs);
     }
-    rc = stage_step_table(ctx, tab.data(), tab.size() * 4, st);
+    if (tab.size() > P.step_tab_ints) return as_fail(ctx, AS_ERR_WORKSPACE, "%s: per-step table of %zu entries exceeds the planned %zu", who, tab.size(), P.step_tab_ints);
+    rc = stage_step_table(ctx, tab.data(), tab.size() * 4, P.step_tab, st);
     if (rc) return rc;
-    const int32_t* d_tab = (const int32_t*)ctx->d_step;
+    const int32_t* d_tab = P.step_tab;
     if (seq) { LS.d_cu = d_tab; LS.d_kept_of = d_tab + off_kept; LS.d_pairs = d_tab + off_pairs; LS.n_seg = n_segments; LS.n_kept = n_seg_eff; }
     if (compact) {
       if ((rc = launch_compact(ctx, d_tokens, d_loss_mask, d_tab, d_tab + n_seg_eff + 1, n_seg_eff, n, P.tok_c, P.mask_c, st))) return rc;
@@ -1377,39 +1362,23 @@ extern "C" int as_adamw_update(as_ctx* ctx, float* const* d_master, void* const*
   }
   AS_HIP(ctx, hipSetDevice(ctx->device));
   const float bc1 = (float)(1.0 - pow((double)beta1, (double)step)), bc2 = (float)(1.0 - pow((double)beta2, (double)step));
-  // one launch over all tensors: a table of tensors and of 65,536-element chunks goes to the device through pinned
-  // memory the context owns (the previous call's copy is waited for before the pinned buffer is rewritten)
+  // batches of up to kAdamBatch tensors, each described in its launch's own argument: no table in device memory
   hipStream_t st = (hipStream_t)stream;
-  std::vector<AdamTensor> tens; std::vector<AdamChunk> chunks;
+  AdamBatch bt; bt.n = 0; bt.n_chunks = 0;
   for (int i = 0; i < n_tensors; i++) {
     if (numel[i] == 0) continue;
-    if (cdiv(numel[i], 65536) > INT32_MAX) return as_fail(ctx, AS_ERR_SHAPE, "as_adamw_update: tensor %d is too large", i);
-    const int32_t ti = (int32_t)tens.size();
-    tens.push_back({d_master[i], d_params_lowp ? (bf16_t*)d_params_lowp[i] : nullptr, d_grads[i], d_m[i], d_v[i], numel[i],
-                    apply_wd[i] ? weight_decay : 0.f, 0});
-    for (int64_t c = 0, nc = cdiv(numel[i], 65536); c < nc; c++) chunks.push_back({ti, (int32_t)c});
+    const int64_t nc = cdiv(numel[i], 65536);
+    if (nc > INT32_MAX / 2) return as_fail(ctx, AS_ERR_SHAPE, "as_adamw_update: tensor %d is too large", i);
+    if (bt.n == kAdamBatch || (int64_t)bt.n_chunks + nc > INT32_MAX / 2) {
+      int rc = launch_adamw_batch(ctx, bt, lr, beta1, beta2, eps, bc1, bc2, st);
+      if (rc) return rc;
+      bt.n = 0; bt.n_chunks = 0;
+    }
+    bt.t[bt.n++] = {d_master[i], d_params_lowp ? (bf16_t*)d_params_lowp[i] : nullptr, d_grads[i], d_m[i], d_v[i], numel[i],
+                    apply_wd[i] ? weight_decay : 0.f, bt.n_chunks};
+    bt.n_chunks += (int)nc;
   }
-  if (chunks.empty()) return AS_OK;
-  if (chunks.size() > (size_t)INT32_MAX) return as_fail(ctx, AS_ERR_SHAPE, "as_adamw_update: too many elements for one call");
-  const size_t tb = tens.size() * sizeof(AdamTensor), cb = chunks.size() * sizeof(AdamChunk), bytes = tb + cb;
-  if (bytes > ctx->adam_bytes) {
-    if (ctx->adam_ev) (void)hipEventSynchronize(ctx->adam_ev);
-    if (ctx->d_adam) (void)hipFree(ctx->d_adam);
-    if (ctx->h_adam) (void)hipHostFree(ctx->h_adam);
-    ctx->d_adam = ctx->h_adam = nullptr; ctx->adam_bytes = 0;
-    const size_t cap = std::max<size_t>(4096, bytes * 2);
-    AS_HIP(ctx, hipMalloc(&ctx->d_adam, cap));
-    AS_HIP(ctx, hipHostMalloc(&ctx->h_adam, cap, hipHostMallocDefault));
-    ctx->adam_bytes = cap;
-  }
-  if (!ctx->adam_ev) AS_HIP(ctx, hipEventCreateWithFlags(&ctx->adam_ev, hipEventDisableTiming));
-  else AS_HIP(ctx, hipEventSynchronize(ctx->adam_ev));
-  memcpy(ctx->h_adam, tens.data(), tb);
-  memcpy((char*)ctx->h_adam + tb, chunks.data(), cb);
-  AS_HIP(ctx, hipMemcpyAsync(ctx->d_adam, ctx->h_adam, bytes, hipMemcpyHostToDevice, st));
-  AS_HIP(ctx, hipEventRecord(ctx->adam_ev, st));
-  return launch_adamw_multi(ctx, (const AdamTensor*)ctx->d_adam, (const AdamChunk*)((const char*)ctx->d_adam + tb), (int)chunks.size(),
-                            lr, beta1, beta2, eps, bc1, bc2, st);
+  return launch_adamw_batch(ctx, bt, lr, beta1, beta2, eps, bc1, bc2, st);
 }
 
 // ---------------------------------------------------------- building blocks

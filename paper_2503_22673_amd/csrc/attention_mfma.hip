@@ -611,11 +611,7 @@ int launch_fwd2(as_ctx* ctx, const AttnParams& p_in, float sl2, hipStream_t st) 
   AttnParams p = p_in;
   if (32 * QB * (NWV / HPW) != attention_query_tile(p.Hq, p.Hkv)) p.order_q = nullptr;   // the order table is cut for another tile size
   constexpr size_t smem = (size_t)2 * 2 * BKEY * DH * sizeof(bf16_t);       // two stages of a K tile and a V^T tile
-  static bool attr_set = false;
-  if (!attr_set) {
-    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd2_mfma<DH, HPW, QB, NWV>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    attr_set = true;
-  }
+  AS_SET_SMEM(ctx, (attn_fwd2_mfma<DH, HPW, QB, NWV>), smem);
   constexpr int QT = 32 * QB * (NWV / HPW);
   attn_fwd2_mfma<DH, HPW, QB, NWV><<<(unsigned)(cdiv(p.n, QT) * (p.Hq / HPW)), NWV * 64, smem, st>>>(p, sl2);
   AS_LAUNCH_CHECK(ctx);
@@ -638,11 +634,7 @@ int fwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
 template <int DH, int HPW>
 int launch_dq2(as_ctx* ctx, const AttnParams& p, float scale, float sl2, hipStream_t st) {
   constexpr size_t smem = (size_t)2 * 3 * BKEY * DH * sizeof(bf16_t);       // two stages of K, V and K^T tiles
-  static bool attr_set = false;
-  if (!attr_set) {
-    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dq2_mfma<DH, HPW>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    attr_set = true;
-  }
+  AS_SET_SMEM(ctx, (attn_bwd_dq2_mfma<DH, HPW>), smem);
   attn_bwd_dq2_mfma<DH, HPW><<<(unsigned)(cdiv(p.n, 32 * (8 / HPW)) * (p.Hq / HPW)), 512, smem, st>>>(p, scale, sl2);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
@@ -651,11 +643,7 @@ int launch_dq2(as_ctx* ctx, const AttnParams& p, float scale, float sl2, hipStre
 template <int DH, int WHICH>
 int launch_dkv2(as_ctx* ctx, const AttnParams& p, float scale, float sl2, float* part, hipStream_t st) {
   constexpr size_t smem = (size_t)2 * ((WHICH == 0 ? 3 : 2) * BKEY * DH + 4 * BKEY) * sizeof(bf16_t);
-  static bool attr_set = false;
-  if (!attr_set) {
-    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv2_mfma<DH, WHICH>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    attr_set = true;
-  }
+  AS_SET_SMEM(ctx, (attn_bwd_dkv2_mfma<DH, WHICH>), smem);
   attn_bwd_dkv2_mfma<DH, WHICH><<<(unsigned)(cdiv(p.n, 256) * p.Hq), 512, smem, st>>>(p, scale, sl2, part);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;

@@ -8,6 +8,7 @@
 #include <string>
 #include <vector>
 #include <algorithm>
+#include <atomic>
 #include "actionstudio.h"
 
 typedef __bf16 bf16_t;
@@ -26,10 +27,6 @@ struct as_ctx {
   // staging owned by the context (as_pack only)
   void* d_stage = nullptr; size_t d_stage_bytes = 0;
   void* h_stage = nullptr; size_t h_stage_bytes = 0;
-  // small per-step table (as_train_step with skipped segments): pinned host + device copy
-  void* d_step = nullptr; void* h_step = nullptr; size_t step_bytes = 0; hipEvent_t step_ev = nullptr;
-  // tensor table of as_adamw_update (one launch over all tensors): pinned host + device copy
-  void* d_adam = nullptr; void* h_adam = nullptr; size_t adam_bytes = 0; hipEvent_t adam_ev = nullptr;
   // optional per-launch timing (as_profile): event pairs around kernels of the tracked classes
   struct ProfRec { hipEvent_t a, b; double flops; int cls; };
   bool prof_on = false; int prof_depth = 0;
@@ -44,6 +41,11 @@ int as_fail(as_ctx* ctx, int code, const char* fmt, ...);
 #define AS_HIP(ctx, call) do { hipError_t e_ = (call); if (e_ != hipSuccess) \
   return as_fail((ctx), AS_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); } while (0)
 #define AS_LAUNCH_CHECK(ctx) AS_HIP(ctx, hipGetLastError())
+// Raises a kernel's dynamic LDS limit once per device (the attribute belongs to the code object loaded on that device).
+#define AS_SET_SMEM(ctx, kern, bytes) do { static std::atomic<uint64_t> done_{0}; const uint64_t bit_ = 1ull << ((ctx)->device & 63); \
+  if (!(done_.load(std::memory_order_relaxed) & bit_)) { \
+    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)(bytes))); \
+    done_.fetch_or(bit_, std::memory_order_relaxed); } } while (0)
 
 static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
@@ -208,9 +210,10 @@ int launch_loss_finalize(as_ctx* ctx, const float* loss_rows, const int32_t* cou
 int launch_splitk_reduce(as_ctx* ctx, const float* partial, int splitk, int64_t mn, int N, float alpha,
                          float* C, int64_t ldc, hipStream_t st);
 // one tensor of a multi-tensor update, and one 64 K-element chunk of work
-struct AdamTensor { float* w; bf16_t* w_lowp; const float* g; float* m; float* v; int64_t n; float wd; int pad; };
-struct AdamChunk { int32_t tensor; int32_t chunk; };
-int launch_adamw_multi(as_ctx* ctx, const AdamTensor* d_tensors, const AdamChunk* d_chunks, int n_chunks,
-                       float lr, float b1, float b2, float eps, float bc1, float bc2, hipStream_t st);
+struct AdamTensor { float* w; bf16_t* w_lowp; const float* g; float* m; float* v; int64_t n; float wd; int first_chunk; };
+// a batch of tensors travels as a kernel argument: no table in device memory, nothing to allocate or to keep alive
+constexpr int kAdamBatch = 48;
+struct AdamBatch { AdamTensor t[kAdamBatch]; int n; int n_chunks; };
+int launch_adamw_batch(as_ctx* ctx, const AdamBatch& b, float lr, float b1, float b2, float eps, float bc1, float bc2, hipStream_t st);
 int launch_embed_bwd(as_ctx* ctx, int mode, const int32_t* tok, int n, int d, int V, const void* dh,
                      int32_t* scratch, float* dE, hipStream_t st);

@@ -813,12 +813,13 @@ int launch_splitk_reduce(as_ctx* ctx, const float* partial, int splitk, int64_t 
 }
 
 // -------------------------------------------------------------------- AdamW
-// All tensors in one launch: workgroup b takes chunk b of the table (65,536 consecutive elements of one tensor).
-__global__ __launch_bounds__(256) void adamw_multi_kernel(const AdamTensor* __restrict__ tensors, const AdamChunk* __restrict__ chunks,
-                                                          float lr, float b1, float b2, float eps, float bc1, float bc2) {
-  const AdamChunk c = chunks[blockIdx.x];
-  const AdamTensor t = tensors[c.tensor];
-  const int64_t lo = (int64_t)c.chunk * 65536, hi = min(t.n, lo + 65536);
+// Up to kAdamBatch tensors per launch, described in the kernel argument itself: workgroup b takes the b-th chunk of
+// 65,536 consecutive elements of the batch (tensor found by a scan over the batch's first-chunk numbers).
+__global__ __launch_bounds__(256) void adamw_batch_kernel(const AdamBatch b, float lr, float b1, float b2, float eps, float bc1, float bc2) {
+  int ti = 0;
+  while (ti + 1 < b.n && (int)blockIdx.x >= b.t[ti + 1].first_chunk) ti++;
+  const AdamTensor& t = b.t[ti];
+  const int64_t lo = (int64_t)((int)blockIdx.x - t.first_chunk) * 65536, hi = min(t.n, lo + 65536);
   for (int64_t i = lo + threadIdx.x; i < hi; i += 256) {
     float gi = t.g[i], wi = t.w[i];
     float mi = b1 * t.m[i] + (1.f - b1) * gi;
@@ -830,10 +831,9 @@ __global__ __launch_bounds__(256) void adamw_multi_kernel(const AdamTensor* __re
     if (t.w_lowp) t.w_lowp[i] = (bf16_t)wi;
   }
 }
-int launch_adamw_multi(as_ctx* ctx, const AdamTensor* d_tensors, const AdamChunk* d_chunks, int n_chunks,
-                       float lr, float b1, float b2, float eps, float bc1, float bc2, hipStream_t st) {
-  if (n_chunks <= 0) return AS_OK;
-  adamw_multi_kernel<<<n_chunks, 256, 0, st>>>(d_tensors, d_chunks, lr, b1, b2, eps, bc1, bc2);
+int launch_adamw_batch(as_ctx* ctx, const AdamBatch& b, float lr, float b1, float b2, float eps, float bc1, float bc2, hipStream_t st) {
+  if (b.n <= 0 || b.n_chunks <= 0) return AS_OK;
+  adamw_batch_kernel<<<b.n_chunks, 256, 0, st>>>(b, lr, b1, b2, eps, bc1, bc2);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }

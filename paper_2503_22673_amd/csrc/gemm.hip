@@ -691,11 +691,7 @@ template <int BM, int BN, int WM, int WN>
 static int launch_dlds_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_t st) {
   size_t smem = (size_t)2 * (BM + BN) * 64 * sizeof(bf16_t);
   auto k0 = gemm_mfma_dlds_kernel<BM, BN, WM, WN>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(k0), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    attr_set = true;
-  }
+  AS_SET_SMEM(ctx, k0, smem);
   int tm = (int)cdiv(p.M, BM), tn = (int)cdiv(p.N, BN);
   dim3 grid(tm * tn, p.splitk > 1 ? p.splitk : 1);
   k0<<<grid, WM * WN * 64, smem, st>>>(p, m_off, tm, tn);
@@ -722,12 +718,8 @@ bool gemm_rs_applies(int mode, const GemmParams& p) { return mode == AS_BF16 && 
 
 static int launch_rs_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_t st) {
   constexpr size_t smem = 131072 + 256 * 64;             // two stages of A and B tiles + a 64-byte line per lane (the staged epilogue: 4 x 128 rows of 272 bytes)
-  static bool attr_set = false;
-  if (!attr_set) {
-    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mfma_rs_kernel<0>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mfma_rs_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    attr_set = true;
-  }
+  AS_SET_SMEM(ctx, gemm_mfma_rs_kernel<0>, smem);
+  AS_SET_SMEM(ctx, gemm_mfma_rs_kernel<1>, smem);
   const int tn = p.N / 256;
   if (rs_live(p)) {                                      // every row tile the live rows can reach; the kernel drops the rest
     const int tm = p.grp_n > 0 ? (int)cdiv(p.rows_cap, 256) + p.grp_n : (int)cdiv(p.M, 256);
@@ -749,12 +741,8 @@ static int launch_mfma_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStrea
   for (int s = 0; s < p.nseg; s++) edge = edge || (p.seg[s].K % 64 != 0);
   auto k0 = gemm_mfma_kernel<BM, BN, WM, WN, false>;
   auto k1 = gemm_mfma_kernel<BM, BN, WM, WN, true>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(k0), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    AS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(k1), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    attr_set = true;
-  }
+  AS_SET_SMEM(ctx, k0, smem);
+  AS_SET_SMEM(ctx, k1, smem);
   int tm = (int)cdiv(p.M, BM), tn = (int)cdiv(p.N, BN);
   dim3 grid(tm * tn, p.splitk > 1 ? p.splitk : 1);
   if (edge) k1<<<grid, WM * WN * 64, smem, st>>>(p, m_off, tm, tn);

@@ -50,15 +50,20 @@ def _attn_row(q, k, v, s0, t, scale):
     return e / e.sum(), (e / e.sum()) @ v[s0:t + 1], m + np.log(e.sum())
 
 
-def test_attention_config3_layout_sampled_rows():
+@pytest.mark.parametrize("layout", ["config3", "one_32k_segment"])
+def test_attention_config3_layout_sampled_rows(layout):
     """Forward and backward MFMA attention on the packed layout of config 3 (4 x 16384 tokens, the real
-    segment table with its pad tails), 32 query / 8 KV heads of 128; sampled rows against the definition."""
+    segment table with its pad tails) and on ONE trajectory of 32,768 tokens (the long-context stress of
+    Section 4.5 / Table 3), 32 query / 8 KV heads of 128; sampled rows against the definition."""
     from paper_2503_22673_amd import binding as B
     sh = synth.CONFIGS[3]
     ctx = B.Context(B.make_config(sh))
-    pk = oracle.pack(synth.workload(3, 0), sh.row_len, sh.rows)
-    cu = pk["cu_seqlens"].astype(np.int64); n = int(cu[-1])
-    assert n == sh.rows * sh.row_len
+    if layout == "config3":
+        pk = oracle.pack(synth.workload(3, 0), sh.row_len, sh.rows)
+        cu = pk["cu_seqlens"].astype(np.int64); n = int(cu[-1])
+        assert n == sh.rows * sh.row_len
+    else:
+        cu = np.array([0, 32768 - 100, 32768], dtype=np.int64); n = 32768          # the trajectory and a short pad tail
     seg = np.searchsorted(cu, np.arange(n), side="right") - 1
     ss = torch.from_numpy(cu[seg].astype(np.int32)).cuda(); se = torch.from_numpy(cu[seg + 1].astype(np.int32)).cuda()
     Hq, Hkv, dh = sh.n_q_heads, sh.n_kv_heads, sh.head_dim

@@ -94,13 +94,11 @@ def algorithmic_flops(sh, seg_lens_nonpad, n_nonpad, n_targets, dpo=False):
     return dict(dense=dense, attention=attn, lora=lora, head=head, total=dense + attn + lora + head, recompute=recompute)
 
 
-def cpu_baseline(sh, seed, budget_tokens=1024):
+def cpu_baseline(sh, seed, budget_tokens=2048):
     """The float64 reference, as it stands, timed on the host on a bounded
     sample: true layer widths and vocabulary, one packed row of `budget_tokens`
     tokens, models of 1 and 2 layers; per-layer and head cost are separated by
-    the difference and extrapolated linearly to the full depth.  (1024 tokens
-    keep the two runs near 30 s of host time on 16 threads; a 2048-token row
-    would take twice that.)"""
+    the difference and extrapolated linearly to the full depth."""
     import numpy as np
     import oracle
     import synth

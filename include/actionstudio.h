@@ -315,7 +315,7 @@ int as_dpo_step(as_ctx* ctx, const as_weights* weights, const as_lora* lora,
  *  d_master float (the fp32 weights that are updated); d_params_lowp either
  *  NULL or, per tensor, NULL or a bfloat16 copy rewritten from the master
  *  (round to nearest even); d_grads, d_m, d_v float.  step counts from 1.
- *  The tensors go out in batches of 48 per kernel launch, each batch described in the launch's own argument (no
+ *  The tensors go out in batches of 64 per kernel launch, each batch described in the launch's own argument (no
  *  table in device memory, nothing allocated, nothing waited for). */
 int as_adamw_update(as_ctx* ctx, float* const* d_master, void* const* d_params_lowp,
                     const float* const* d_grads, float* const* d_m, float* const* d_v,

@@ -12,14 +12,14 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libactionstudio.so")
-SOURCES = ["api.hip", "elementwise.hip", "gemm.hip", "attention.hip", "attention_mfma.hip", "lora_grad.hip", "moe.hip", "quant.hip", "dpo.hip"]
+SOURCES = ["host_logic.cpp", "api.hip", "elementwise.hip", "gemm.hip", "attention.hip", "attention_mfma.hip", "lora_grad.hip", "moe.hip", "quant.hip", "dpo.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-Wno-unused-command-line-argument"]
 
 
 def _compile(src):
-    obj = os.path.join(HERE, "_build", src.replace(".hip", ".o"))
+    obj = os.path.join(HERE, "_build", src.replace(".hip", ".o").replace(".cpp", ".o"))
     cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)

@@ -159,9 +159,12 @@ int launch_attention_fwd(as_ctx* ctx, int mode, int variant, const AttnParams& p
   return AS_OK;
 }
 
+bool attention_bwd_is_mfma(int mode, int variant, const AttnParams& p) { return mode == AS_BF16 && variant != 1 && attention_mfma_ok(p); }
+
 int launch_attention_bwd(as_ctx* ctx, int mode, int variant, const AttnParams& p, hipStream_t st) {
   if (p.n <= 0) return AS_OK;
   bool mf = mode == AS_BF16 && variant != 1 && attention_mfma_ok(p);
+  if (!mf && p.rope_cos) return as_fail(ctx, AS_ERR_SHAPE, "attention: only the MFMA kernels rotate their gradients");
   if (variant >= 2 && !mf) return as_fail(ctx, AS_ERR_SHAPE, "attention: MFMA kernel needs bf16, head_dim 64/128, aligned strides");
   if (mf) { prof_begin(ctx, st, AS_K_ATTN_BWD, 0.0); int r = launch_attention_bwd_mfma(ctx, p, variant, st); prof_end(ctx, st); return r; }
   size_t smem1 = (size_t)(2 * p.dh + p.max_seg) * sizeof(float);

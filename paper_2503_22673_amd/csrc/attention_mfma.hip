@@ -276,6 +276,43 @@ __global__ __launch_bounds__(NWV * 64, QB == 1 ? 2 : 1) void attn_fwd2_mfma(Attn
   }
 }
 
+// Stores a lane's column of a transposed [head_dim x tokens] accumulator block as one bf16 row of dh values, scaled; with
+// rotary tables the row is first rotated back by the token's position (component i pairs with i + dh / 2; both sit in the
+// same lane, CB / 2 accumulator blocks apart), so that the gradient is rounded once, after the rotation.
+template <int DH>
+__device__ __forceinline__ void store_grad_row(const f32x16 (&acc)[DH / 32], float scale, bf16_t* row, int h, const float* rc, const float* rs, int pos) {
+  constexpr int CB = DH / 32, HB = CB / 2;
+  if (rc) {
+    const float* c0 = rc + (int64_t)pos * (DH / 2); const float* s0 = rs + (int64_t)pos * (DH / 2);
+#pragma unroll
+    for (int cb = 0; cb < HB; cb++)
+#pragma unroll
+      for (int b4 = 0; b4 < 4; b4++) {
+        const int i0 = cb * 32 + 8 * b4 + 4 * h;
+        const f32x4 c = *reinterpret_cast<const f32x4*>(c0 + i0), sn = *reinterpret_cast<const f32x4*>(s0 + i0);
+        bf16x4 w1, w2;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          const float x1 = acc[cb][b4 * 4 + i] * scale, x2 = acc[cb + HB][b4 * 4 + i] * scale;
+          w1[i] = (bf16_t)(x1 * c[i] + x2 * sn[i]);
+          w2[i] = (bf16_t)(x2 * c[i] - x1 * sn[i]);
+        }
+        *reinterpret_cast<bf16x4*>(row + i0) = w1;
+        *reinterpret_cast<bf16x4*>(row + DH / 2 + i0) = w2;
+      }
+    return;
+  }
+#pragma unroll
+  for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+    for (int b4 = 0; b4 < 4; b4++) {
+      bf16x4 w;
+#pragma unroll
+      for (int i = 0; i < 4; i++) w[i] = (bf16_t)(acc[cb][b4 * 4 + i] * scale);
+      *reinterpret_cast<bf16x4*>(row + cb * 32 + 8 * b4 + 4 * h) = w;
+    }
+}
+
 // ---------------------------------------------------------- backward: delta
 __global__ void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o, int64_t rows, int dh,
                                   float* __restrict__ delta) {
@@ -410,18 +447,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq2_mfma(AttnParams p, float sca
         dq[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsb[x], dq[cb], 0, 0, 0);
       }
   }
-  if (tq < n) {
-    bf16_t* row = (bf16_t*)p.dq + (int64_t)tq * p.ldq + j * DH;
-#pragma unroll
-    for (int cb = 0; cb < CB; cb++)
-#pragma unroll
-      for (int b4 = 0; b4 < 4; b4++) {
-        bf16x4 w;
-#pragma unroll
-        for (int i = 0; i < 4; i++) w[i] = (bf16_t)(dq[cb][b4 * 4 + i] * scale);
-        *reinterpret_cast<bf16x4*>(row + cb * 32 + 8 * b4 + 4 * h) = w;
-      }
-  }
+  if (tq < n) store_grad_row<DH>(dq, scale, (bf16_t*)p.dq + (int64_t)tq * p.ldq + j * DH, h, p.rope_cos, p.rope_sin, tq - ss);
 }
 
 // Wave = 32 keys of one KV head (a lane owns one key), workgroup = 8 waves = 256 keys and ONE query head of
@@ -564,22 +590,16 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float sc
       }
   } else {
     bf16_t* row = (bf16_t*)(WHICH == 0 ? p.dk : p.dv) + (int64_t)u * p.ldkv + g * DH;
-    const float sc = WHICH == 0 ? scale : 1.f;
-#pragma unroll
-    for (int cb = 0; cb < CB; cb++)
-#pragma unroll
-      for (int b4 = 0; b4 < 4; b4++) {
-        bf16x4 w;
-#pragma unroll
-        for (int i = 0; i < 4; i++) w[i] = (bf16_t)(acc[cb][b4 * 4 + i] * sc);
-        *reinterpret_cast<bf16x4*>(row + cb * 32 + 8 * b4 + 4 * h) = w;
-      }
+    store_grad_row<DH>(acc, WHICH == 0 ? scale : 1.f, row, h, WHICH == 0 ? p.rope_cos : nullptr, p.rope_sin, u - p.seg_start[u]);
   }
 }
 
-// dk[u, g, :] = scale * sum over the query heads of group g, in head order, of the dK partials; dv likewise (scale 1)
+// dk[u, g, :] = scale * sum over the query heads of group g, in head order, of the dK partials; dv likewise (scale 1).
+// With rotary tables dk is rotated back by the token's position before its one rounding: a thread then owns 4 columns
+// i .. i + 3 of the lower half and their partners i + dh / 2.
 __global__ void attn_dkv_reduce_kernel(const float* __restrict__ part, int n, int Hq, int Hkv, int dh, float scale,
-                                       bf16_t* __restrict__ dk, bf16_t* __restrict__ dv, int64_t ldkv) {
+                                       bf16_t* __restrict__ dk, bf16_t* __restrict__ dv, int64_t ldkv,
+                                       const int32_t* __restrict__ seg_start, const float* __restrict__ rc, const float* __restrict__ rs) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;        // one thread: 4 columns of one (which, token, kv head)
   const int c4 = dh / 4, grp = Hq / Hkv;
   const int64_t per = (int64_t)n * Hkv * c4;
@@ -588,13 +608,27 @@ __global__ void attn_dkv_reduce_kernel(const float* __restrict__ part, int n, in
   const int64_t r = idx % per;
   const int c = (int)(r % c4) * 4, g = (int)((r / c4) % Hkv);
   const int64_t u = r / ((int64_t)c4 * Hkv);
-  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-  for (int z = 0; z < grp; z++) {
-    const f32x4 v = *reinterpret_cast<const f32x4*>(part + (((int64_t)which * Hq + g * grp + z) * n + u) * dh + c);
-    sum += v;
-  }
-  const float sc = which == 0 ? scale : 1.f;
+  auto sum4 = [&](int col) {
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int z = 0; z < grp; z++) sum += *reinterpret_cast<const f32x4*>(part + (((int64_t)which * Hq + g * grp + z) * n + u) * dh + col);
+    return sum;
+  };
   bf16x4 w;
+  if (which == 0 && rc) {
+    const int half = dh / 2;
+    if (c >= half) return;                                  // the thread of column c also writes column c + dh / 2
+    const f32x4 x1 = sum4(c), x2 = sum4(c + half);
+    const int pos = (int)u - seg_start[u];
+    const f32x4 cs = *reinterpret_cast<const f32x4*>(rc + (int64_t)pos * half + c), sn = *reinterpret_cast<const f32x4*>(rs + (int64_t)pos * half + c);
+    bf16x4 w2;
+#pragma unroll
+    for (int i = 0; i < 4; i++) { w[i] = (bf16_t)(scale * (x1[i] * cs[i] + x2[i] * sn[i])); w2[i] = (bf16_t)(scale * (x2[i] * cs[i] - x1[i] * sn[i])); }
+    *reinterpret_cast<bf16x4*>(dk + u * ldkv + g * dh + c) = w;
+    *reinterpret_cast<bf16x4*>(dk + u * ldkv + g * dh + c + half) = w2;
+    return;
+  }
+  const f32x4 sum = sum4(c);
+  const float sc = which == 0 ? scale : 1.f;
 #pragma unroll
   for (int i = 0; i < 4; i++) w[i] = (bf16_t)(sum[i] * sc);
   *reinterpret_cast<bf16x4*>((which == 0 ? dk : dv) + u * ldkv + g * dh + c) = w;
@@ -628,6 +662,7 @@ int fwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
   if (rc) return rc;
   const float sl2 = 1.4426950408889634f / sqrtf((float)DH);
   const int hpw = heads_per_wg(p);
+  if (variant == 5) return hpw == 4 ? launch_fwd2<DH, 4, 1, 4>(ctx, p, sl2, st) : hpw == 2 ? launch_fwd2<DH, 2, 1, 4>(ctx, p, sl2, st) : launch_fwd2<DH, 1, 1, 4>(ctx, p, sl2, st);
   return hpw == 4 ? launch_fwd2<DH, 4, 1>(ctx, p, sl2, st) : hpw == 2 ? launch_fwd2<DH, 2, 1>(ctx, p, sl2, st) : launch_fwd2<DH, 1, 1>(ctx, p, sl2, st);
 }
 
@@ -673,7 +708,8 @@ int bwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
     if ((rc = launch_dkv2<DH, 0>(ctx, p, scale, sl2, part, st)) || (rc = launch_dkv2<DH, 1>(ctx, p, scale, sl2, part, st))) return rc;
     if (p.Hq > p.Hkv) {
       const int64_t threads = 2 * (int64_t)p.n * p.Hkv * (DH / 4);
-      attn_dkv_reduce_kernel<<<(unsigned)cdiv(threads, 256), 256, 0, st>>>(part, p.n, p.Hq, p.Hkv, DH, scale, (bf16_t*)p.dk, (bf16_t*)p.dv, p.ldkv);
+      attn_dkv_reduce_kernel<<<(unsigned)cdiv(threads, 256), 256, 0, st>>>(part, p.n, p.Hq, p.Hkv, DH, scale, (bf16_t*)p.dk, (bf16_t*)p.dv, p.ldkv,
+                                                                             p.seg_start, p.rope_cos, p.rope_sin);
       AS_LAUNCH_CHECK(ctx);
     }
     return AS_OK;

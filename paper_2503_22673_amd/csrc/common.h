@@ -134,7 +134,12 @@ struct AttnParams {
   // optional launch orders (device arrays, longest workgroups first): order_q[i] = query tile of workgroup i
   // (tiles of attention_query_tile() tokens), order_k[i] = key block (256 keys) of workgroup i in the dK / dV launches
   const int32_t* order_q; const int32_t* order_k;
+  // backward, MFMA kernels only: when set, dq and dk leave the kernels already rotated back (the inverse of the rotary
+  // embedding applied to q and k before attention): tables [position][dh / 2] of cos and sin, position = t - seg_start[t]
+  const float* rope_cos; const float* rope_sin;
 };
+// the MFMA backward kernels will take this call (then the rotation above is available)
+bool attention_bwd_is_mfma(int mode, int variant, const AttnParams& p);
 int launch_attention_fwd(as_ctx* ctx, int mode, int variant, const AttnParams& p, hipStream_t st);
 int attention_query_tile(int n_q_heads, int n_kv_heads);   // tokens per workgroup of the forward and dQ MFMA kernels
 int launch_attention_bwd(as_ctx* ctx, int mode, int variant, const AttnParams& p, hipStream_t st);
@@ -212,7 +217,7 @@ int launch_splitk_reduce(as_ctx* ctx, const float* partial, int splitk, int64_t 
 // one tensor of a multi-tensor update, and one 64 K-element chunk of work
 struct AdamTensor { float* w; bf16_t* w_lowp; const float* g; float* m; float* v; int64_t n; float wd; int first_chunk; };
 // a batch of tensors travels as a kernel argument: no table in device memory, nothing to allocate or to keep alive
-constexpr int kAdamBatch = 48;
+constexpr int kAdamBatch = 64;
 struct AdamBatch { AdamTensor t[kAdamBatch]; int n; int n_chunks; };
 int launch_adamw_batch(as_ctx* ctx, const AdamBatch& b, float lr, float b1, float b2, float eps, float bc1, float bc2, hipStream_t st);
 int launch_embed_bwd(as_ctx* ctx, int mode, const int32_t* tok, int n, int d, int V, const void* dh,

@@ -22,9 +22,9 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # HBM-side bytes per launch of the dominant kernel at config 3 (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, two counter
 # runs over one bench step, see profiles/gemm_256_counters.md); only valid for the kernel those runs saw
-TRAFFIC_BYTES_PER_LAUNCH = {(3, "gemm_mfma_rs_kernel<0>"): 9.8e9}
-DOMINANT_KERNEL = "gemm_mfma_rs_kernel<0>"                   # dense models; expert GEMMs: the same kernel with live-row limits, <1>
-GROUPED_KERNEL = "gemm_mfma_rs_kernel<1>"
+TRAFFIC_BYTES_PER_LAUNCH = {}
+DOMINANT_KERNEL = "gemm_mfma_rs_kernel<0, 0>"                  # dense models; expert GEMMs: the same kernel with live-row limits, <1>
+GROUPED_KERNEL = "gemm_mfma_rs_kernel<1, 0>"
 
 
 def device_weights(sh, seed, dtype):

@@ -333,12 +333,17 @@ int as_adamw_update(as_ctx* ctx, float* const* d_master, void* const* d_params_l
  * 2 = MFMA kernel (bf16 only; K1, K2, lda, ldb multiples of 8) with the tile
  * shape picked; 10..13 = register-staged tiles 256x256 / 256x64 / 64x256 /
  * 128x128; 30 = direct-to-LDS 256x256 tiles (K in 64-wide steps, else 10);
- * 34 = hand-scheduled 256x256 kernel where it applies (else 30). */
+ * 34 = hand-scheduled 256x256 kernel where it applies (else 30).
+ * d_tail_scratch [device], may be NULL: AS_GEMM_TAIL_SCRATCH_BYTES of scratch, 256-byte aligned.  With it the
+ * hand-scheduled kernel splits the contraction of the tiles of a last, at most half-full round of 256 workgroups
+ * over two workgroups each (as as_train_step does inside its workspace): float partial sums per half, added in
+ * order by a second small launch. */
+#define AS_GEMM_TAIL_SCRATCH_BYTES (64u << 20)
 int as_op_gemm(as_ctx* ctx, int mode, int variant, int64_t M, int64_t N,
                const void* A1, int64_t lda1, const void* B1, int64_t ldb1, int64_t K1,
                const void* A2, int64_t lda2, const void* B2, int64_t ldb2, int64_t K2,
                float alpha, const void* R, int64_t ldr, void* C, int64_t ldc, int c_is_f32,
-               void* stream);
+               void* d_tail_scratch, size_t tail_scratch_bytes, void* stream);
 
 /* The same product over rows whose number is only known on the device (one K
  * segment).  The target rows of the vocabulary head (Section 3.2.1: the loss

@@ -85,7 +85,8 @@ lib.as_dpo_step.argtypes = [_vp, C.POINTER(Weights), C.POINTER(Lora), _vp, _vp, 
                             _vp, _i32, _vp, _f32, _vp, _vp, C.POINTER(Grads), _vp, C.c_size_t, _vp]
 lib.as_adamw_update.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _f32, _f32, _f32, _f32, _f32, _vp]
 lib.as_op_gemm.argtypes = [_vp, C.c_int, C.c_int, _i64, _i64, _vp, _i64, _vp, _i64, _i64, _vp, _i64, _vp, _i64, _i64,
-                           _f32, _vp, _i64, _vp, _i64, C.c_int, _vp]
+                           _f32, _vp, _i64, _vp, _i64, C.c_int, _vp, C.c_size_t, _vp]
+GEMM_TAIL_SCRATCH_BYTES = 64 << 20
 lib.as_op_gemm_rows.argtypes = [_vp, C.c_int, C.c_int, _i64, _i64, _vp, _i64, _vp, _i64, _i64, _f32, _vp, _i64, _vp, _i64, C.c_int,
                                 _vp, _i64, _vp, C.c_int, C.c_int, _i64, _i64, _vp]
 lib.as_op_rmsnorm_fwd.argtypes = [_vp, C.c_int, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _vp]
@@ -320,7 +321,8 @@ class Context:
                                        weight_decay, _stream()))
 
     # ------------------------------------------------------- building blocks
-    def op_gemm(self, A1, B1, A2=None, B2=None, alpha=1.0, R=None, out_f32=False, variant=0, mode=None):
+    def op_gemm(self, A1, B1, A2=None, B2=None, alpha=1.0, R=None, out_f32=False, variant=0, mode=None, tail_scratch=None):
+        """tail_scratch: uint8 device tensor of GEMM_TAIL_SCRATCH_BYTES, lets the kernel split its last round of tiles"""
         mode = self.mode if mode is None else mode
         M, K1 = A1.shape
         N = B1.shape[0]
@@ -329,7 +331,8 @@ class Context:
         self.check(lib.as_op_gemm(self.handle, mode, variant, M, N, _ptr(A1), A1.stride(0), _ptr(B1), B1.stride(0), K1,
                                   _ptr(A2), A2.stride(0) if A2 is not None else 0, _ptr(B2),
                                   B2.stride(0) if B2 is not None else 0, K2, alpha, _ptr(R),
-                                  R.stride(0) if R is not None else 0, _ptr(Cm), Cm.stride(0), int(out_f32), _stream()))
+                                  R.stride(0) if R is not None else 0, _ptr(Cm), Cm.stride(0), int(out_f32), _ptr(tail_scratch),
+                                  tail_scratch.numel() if tail_scratch is not None else 0, _stream()))
         return Cm
 
     def op_gemm_rows(self, A, Bm, Cm, alpha=1.0, R=None, d_rows=None, row_off=0, d_group_off=None, group=0, rows_cap=0, M=None,

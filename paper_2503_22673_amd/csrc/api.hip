@@ -10,6 +10,7 @@
 #include <cmath>
 #include <mutex>
 
+static_assert((size_t)AS_GEMM_TAIL_SCRATCH_BYTES == kGemmTailFloats * 4, "header and kernel agree on the tail scratch");
 static thread_local std::string g_tls_err;
 
 int as_fail(as_ctx* ctx, int code, const char* fmt, ...) {
@@ -259,6 +260,7 @@ struct Acts {           // activations of one layer kept for its backward
 struct Plan {
   int N, Np, d, D, Dkv, QKV, F, V, L, rp, es, Mc;
   bool head_fused;                       // vocabulary head without stored logits (statistics and gradient rows come out of the GEMM epilogues)
+  float* gemm_tail;                      // scratch of the projection GEMMs' split last round (kGemmTailFloats floats, bf16 tier)
   float *part, *zlab, *lse_rows;         // its per-block softmax statistics [Mc, V / 128, 2], label logits and log-sum-exps per target   // Np: token count rounded up to 64 (row length of token-major transposes)
   int cap;                               // token rows every activation buffer holds (rows * row_len of the plan)
   int n_qkv, n_gu;                       // adapters inside the q/k/v and gate/up groups
@@ -325,6 +327,7 @@ static void make_plan(const as_ctx* ctx, int64_t rows, int64_t row_len, Bump& w,
   P.count = (int32_t*)w.take(256);
   P.step_tab_ints = 6 * N + 64;                           // (S+1) + S + N/32 + N/256 + S + 2 P with S, P <= N
   P.step_tab = (int32_t*)w.take(P.step_tab_ints * 4);
+  P.gemm_tail = (float*)w.take(c.mode == AS_BF16 ? kGemmTailFloats * 4 : 0);
   P.tok_c = (int32_t*)w.take(N * 4); P.mask_c = (uint8_t*)w.take(N);
   P.iscratch = (int32_t*)w.take(full ? 2 * N * 4 : 0);
   P.rope_cos = (float*)w.take((size_t)row_len * (c.head_dim / 2) * 4);
@@ -467,7 +470,7 @@ struct Step {
     if (A2 && K2 > 0) { g.seg[1] = {A2, B2, lda2, ldb2, K2}; g.nseg = 2; }
     g.M = M; g.N = N; g.m_dev = m_dev; g.C = C; g.ldc = ldc; g.c_f32 = c_f32; g.alpha = alpha;
     g.rows_cap = rows_cap_once; rows_cap_once = 0;
-    g.R = R; g.ldr = ldr; g.accumulate = accumulate; g.splitk = 1; g.partial = nullptr;
+    g.R = R; g.ldr = ldr; g.accumulate = accumulate; g.splitk = 1; g.partial = nullptr; g.tail_part = P.gemm_tail;
     if (allow_split) {
       int sk = pick_splitk(mode, M, N, K1);
       if (sk > 1 && (size_t)sk * M * N <= P.partial_floats) { g.splitk = sk; g.partial = P.partial; }
@@ -509,7 +512,7 @@ struct Step {
       end += nout[i]; g.cg_end[i] = end; g.cg_B1[i] = w[i];
       g.cg_B2[i] = on ? slot(l, tgt[i]).Bs : nullptr; g.cg_a2[i] = on ? slot(l, tgt[i]).slot * P.rp : 0;
     }
-    g.M = P.N; g.N = end; g.C = C; g.ldc = ldc; g.alpha = 1.f; g.splitk = 1; g.rows_cap = P.cap;
+    g.M = P.N; g.N = end; g.C = C; g.ldc = ldc; g.alpha = 1.f; g.splitk = 1; g.rows_cap = P.cap; g.tail_part = P.gemm_tail;
     return launch_gemm_off(ctx, mode, gv, g, 0, st);
   }
 
@@ -1161,7 +1164,7 @@ static int check_mode(as_ctx* ctx, int mode);
 // the head's scratch buffers alone, carved from a workspace (same sizes as inside the step's plan)
 static void make_head_plan(const as_ctx* ctx, int mode, int64_t n_rows, Bump& w, Plan& P) {
   const as_model_config& c = ctx->cfg;
-  P.N = (int)n_rows; P.cap = P.N; P.d = c.d_model; P.V = c.vocab; P.L = 0; P.es = mode == AS_FP32 ? 4 : 2;
+  P.N = (int)n_rows; P.cap = P.N; P.d = c.d_model; P.V = c.vocab; P.L = 0; P.es = mode == AS_FP32 ? 4 : 2; P.gemm_tail = nullptr;
   P.head_fused = mode == AS_BF16 && P.V % 256 == 0 && P.d % 64 == 0;
   P.Mc = P.head_fused ? (int)std::min<int64_t>(8192, cdiv(std::max(P.N, 1), 256) * 256) : (int)std::min<int64_t>(4096, cdiv(std::max(P.N, 1), 64) * 64);
   const size_t es = (size_t)P.es, N = (size_t)P.N;
@@ -1265,8 +1268,10 @@ extern "C" int as_op_gemm(as_ctx* ctx, int mode, int variant, int64_t M, int64_t
                           const void* A1, int64_t lda1, const void* B1, int64_t ldb1, int64_t K1,
                           const void* A2, int64_t lda2, const void* B2, int64_t ldb2, int64_t K2,
                           float alpha, const void* R, int64_t ldr, void* C, int64_t ldc, int c_is_f32,
-                          void* stream) {
+                          void* d_tail_scratch, size_t tail_scratch_bytes, void* stream) {
   if (!ctx) return as_fail(nullptr, AS_ERR_NULL, "as_op_gemm: NULL context");
+  if (d_tail_scratch && (tail_scratch_bytes < (size_t)AS_GEMM_TAIL_SCRATCH_BYTES || ((uintptr_t)d_tail_scratch & 255)))
+    return as_fail(ctx, AS_ERR_WORKSPACE, "as_op_gemm: tail scratch must be 256-byte aligned and hold AS_GEMM_TAIL_SCRATCH_BYTES");
   int rc = check_mode(ctx, mode); if (rc) return rc;
   if (!A1 || !B1 || !C) return as_fail(ctx, AS_ERR_NULL, "as_op_gemm: NULL operand");
   if (M < 0 || N < 0 || K1 < 0 || K2 < 0 || M > INT32_MAX || N > INT32_MAX || K1 > INT32_MAX || K2 > INT32_MAX)
@@ -1277,6 +1282,7 @@ extern "C" int as_op_gemm(as_ctx* ctx, int mode, int variant, int64_t M, int64_t
   g.seg[0] = {A1, B1, lda1, ldb1, (int)K1}; g.nseg = 1;
   if (A2 && K2 > 0) { g.seg[1] = {A2, B2, lda2, ldb2, (int)K2}; g.nseg = 2; }
   g.M = (int)M; g.N = (int)N; g.C = C; g.ldc = ldc; g.c_f32 = c_is_f32; g.alpha = alpha; g.R = R; g.ldr = ldr; g.splitk = 1;
+  g.tail_part = (float*)d_tail_scratch; g.rows_cap = d_tail_scratch ? (int)M : 0;
   AS_HIP(ctx, hipSetDevice(ctx->device));
   return launch_gemm(ctx, mode, variant, g, (hipStream_t)stream);
 }

@@ -101,11 +101,18 @@ struct GemmParams {
   //    the sum of exp(value - maximum) go to epi_part[(row * (N / 128) + block) * 2 + {0, 1}];
   //  epi == GEMM_EPI_PROB:  C = w_row * (exp(value - epi_lse[row]) - [column == epi_lab[row]]), w_row = epi_w[row] when
   //    given, else 1 / *epi_cnt: the gradient of the masked loss with respect to the logits, straight from the accumulators.
+  // Last partial round of tiles (hand-scheduled kernel, plain rows): with tail_first >= 0 the tiles tail_first .. of the launch
+  // are each computed by TWO workgroups, one per half of the contraction, as float partials in tail_part
+  // [tile - tail_first][half][256 x 256]; a second small launch adds the halves in order and applies the epilogue.
+  // A launch of 3696 tiles on 256 CUs then ends after 14.5 rounds instead of 15.  Set by the launcher.
+  int tail_first; float* tail_part;
   int epi; const float* epi_lse; const int32_t* epi_lab; const float* epi_w; const int32_t* epi_cnt; float* epi_part;
 };
 enum { GEMM_EPI_NONE = 0, GEMM_EPI_STATS = 1, GEMM_EPI_PROB = 2 };
 // the hand-scheduled kernel would take this product (whole 256 x 256 tiles, K in 64-wide steps, alignment)
 bool gemm_rs_applies(int mode, const GemmParams& p);
+// floats of scratch (GemmParams::tail_part given by the caller through `tail_ws`) that let the launcher split the last round
+constexpr size_t kGemmTailFloats = (size_t)128 * 2 * 256 * 256;
 int launch_gemm(as_ctx* ctx, int mode, int variant, const GemmParams& p, hipStream_t st);
 // live rows = *p.m_dev - m_off, clamped to [0, p.M]
 int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p, int m_off, hipStream_t st);

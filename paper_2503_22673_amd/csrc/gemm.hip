@@ -584,7 +584,9 @@ __device__ __forceinline__ void gemm_epilogue_stats(const GemmParams& p, f32x16 
 // rows exit; a tile still computes 256 rows, moved up if need be so that they lie inside the `limit` rows the operands
 // are known to have (M for a plain row count, rows_cap for grouped rows), and writes the rows that are its own and live.
 #include "gemm_rs_loop.inc"
-template <int LIVE>
+// EPI: the epilogue is a compile-time choice (GEMM_EPI_*), so that the head's epilogues, which need registers of their own,
+// cost the projection GEMMs nothing.
+template <int LIVE, int EPI = GEMM_EPI_NONE>
 __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int m_off, int tiles_m, int tiles_n) {
   constexpr int BM = 256, BN = 256, BK = 64, TM = 4, TN = 4;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -601,6 +603,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int m_o
     }
   }
   int nblk = tiles_m * tiles_n, pid = blockIdx.x;
+  int khalf = -1;                                        // >= 0: this workgroup computes one half of the contraction of a tail tile
+  if (!LIVE && EPI == GEMM_EPI_NONE && p.tail_first >= 0 && pid >= p.tail_first) { khalf = (pid - p.tail_first) & 1; pid = p.tail_first + ((pid - p.tail_first) >> 1); }
   if (pid >= nblk) return;
   int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
   int logical = xcd * q8 + min(xcd, rem) + loc;
@@ -626,8 +630,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int m_o
   const int tid = threadIdx.x, lane = tid & 63, l31 = lane & 31, hh = lane >> 5, lrow = lane >> 3, lch = lane & 7;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
-  const int nt0 = p.seg[0].K / BK, nt = nt0 + (p.nseg > 1 ? p.seg[1].K / BK : 0);
+  int nt0 = p.seg[0].K / BK, nt = nt0 + (p.nseg > 1 ? p.seg[1].K / BK : 0);
   const GemmSeg s0 = p.seg[0], s1 = p.nseg > 1 ? p.seg[1] : p.seg[0];
+  int64_t k_skip = 0;                                    // elements of segment 0 this workgroup starts behind
+  if (khalf >= 0) {                                      // first half: steps [0, nt / 2) of segment 0; second half: the rest of it and segment 1
+    const int sp = nt / 2;                               // the launcher made sure that sp <= nt0
+    if (khalf == 0) { nt0 = sp; nt = sp; } else { k_skip = (int64_t)sp * BK; nt0 -= sp; nt -= sp; }
+  }
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -666,8 +675,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int m_o
       colg = col0 - (cgi ? p.cg_end[cgi - 1] : 0);
       b0p = (const bf16_t*)p.cg_B1[cgi]; b1p = (const bf16_t*)(p.nseg > 1 ? p.cg_B2[cgi] : p.cg_B1[cgi]); a2off = p.nseg > 1 ? p.cg_a2[cgi] : 0;
     }
-    const uint64_t A0 = (uint64_t)((const bf16_t*)s0.A + (int64_t)(row0 + wave * 64) * s0.lda);
-    const uint64_t B0 = (uint64_t)(b0p + (int64_t)(colg + wave * 64) * s0.ldb);
+    const uint64_t A0 = (uint64_t)((const bf16_t*)s0.A + (int64_t)(row0 + wave * 64) * s0.lda + k_skip);
+    const uint64_t B0 = (uint64_t)(b0p + (int64_t)(colg + wave * 64) * s0.ldb + k_skip);
     const uint64_t A1 = (uint64_t)((const bf16_t*)s1.A + a2off + (int64_t)(row0 + wave * 64) * s1.lda);
     const uint64_t B1 = (uint64_t)(b1p + (int64_t)(colg + wave * 64) * s1.ldb);
     const int sA0 = (int)(16 * s0.lda), sB0 = (int)(16 * s0.ldb), sA1 = (int)(16 * s1.lda), sB1 = (int)(16 * s1.ldb);   // 8 rows, bytes
@@ -680,8 +689,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_rs_kernel(GemmParams p, int m_o
                  : GEMM_RS_LOOP_CLOBBERS);
   }
   // bf16 results with 16-byte rows leave through LDS (whole 256-byte row pieces per store), the rest row by row
-  if (p.epi == GEMM_EPI_STATS) { gemm_epilogue_stats<TM, TN, LIVE != 0>(p, acc, row0 + wm * TM * 32 + l31, (col0 + wn * TN * 32) / 128, hh, row_lo, row_hi); return; }
-  if (p.epi == GEMM_EPI_PROB) { gemm_epilogue_staged<TM, TN, LIVE != 0, true>(p, acc, smem, wave, lane, row0 + wm * TM * 32, col0 + wn * TN * 32, row_lo, row_hi); return; }
+  if (!LIVE && EPI == GEMM_EPI_NONE && khalf >= 0) {     // raw float sums of this half into the tile's scratch
+    GemmParams q = p;
+    q.C = p.tail_part + ((int64_t)(pid - p.tail_first) * 2 + khalf) * (BM * BN); q.ldc = BN; q.c_f32 = 1; q.alpha = 1.f; q.R = nullptr; q.accumulate = 0;
+    gemm_epilogue_rows<TM, TN, false>(q, acc, wm * TM * 32 + l31, wn * TN * 32 + 4 * hh);
+    return;
+  }
+  if constexpr (EPI == GEMM_EPI_STATS) { gemm_epilogue_stats<TM, TN, LIVE != 0>(p, acc, row0 + wm * TM * 32 + l31, (col0 + wn * TN * 32) / 128, hh, row_lo, row_hi); return; }
+  if constexpr (EPI == GEMM_EPI_PROB) { gemm_epilogue_staged<TM, TN, LIVE != 0, true>(p, acc, smem, wave, lane, row0 + wm * TM * 32, col0 + wn * TN * 32, row_lo, row_hi); return; }
   const bool staged = !p.c_f32 && !(p.ldc % 8) && (!p.R || (!(p.ldr % 8) && !((uintptr_t)p.R % 16)));
   if (staged) gemm_epilogue_staged<TM, TN, LIVE != 0>(p, acc, smem, wave, lane, row0 + wm * TM * 32, col0 + wn * TN * 32, row_lo, row_hi);
   else gemm_epilogue_rows<TM, TN, LIVE != 0>(p, acc, row0 + wm * TM * 32 + l31, col0 + wn * TN * 32 + 4 * hh, row_lo, row_hi);
@@ -697,6 +712,43 @@ static int launch_dlds_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStrea
   k0<<<grid, WM * WN * 64, smem, st>>>(p, m_off, tm, tn);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
+}
+
+// Second launch for the tiles of a split last round: sum of the two halves (first half first), then the usual epilogue.
+// One workgroup per tile, the same workgroup -> tile mapping as the main kernel; a thread owns 4 consecutive columns.
+__global__ __launch_bounds__(256) void gemm_tail_fixup_kernel(GemmParams p, int tiles_m, int tiles_n) {
+  constexpr int BM = 256, BN = 256, GROUP = 4;
+  const int nblk = tiles_m * tiles_n, pid = p.tail_first + blockIdx.x;
+  if (pid >= nblk) return;
+  const int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
+  const int logical = xcd * q8 + min(xcd, rem) + loc;
+  const int in_group = GROUP * tiles_n, grp = logical / in_group, first_m = grp * GROUP;
+  const int gsize = min(tiles_m - first_m, GROUP);
+  const int tile_m = first_m + (logical % in_group) % gsize, tile_n = (logical % in_group) / gsize;
+  const float* h0 = p.tail_part + (int64_t)blockIdx.x * 2 * (BM * BN); const float* h1 = h0 + BM * BN;
+  const int c = (threadIdx.x & 63) * 4;
+  for (int r = threadIdx.x >> 6; r < BM; r += 4) {
+    const f32x4 a = *reinterpret_cast<const f32x4*>(h0 + r * BN + c), b = *reinterpret_cast<const f32x4*>(h1 + r * BN + c);
+    const int64_t row = (int64_t)tile_m * BM + r; const int col = tile_n * BN + c;
+    f32x4 v;
+#pragma unroll
+    for (int k = 0; k < 4; k++) v[k] = p.alpha * (a[k] + b[k]);
+    if (p.R) { const bf16x4_t x = *reinterpret_cast<const bf16x4_t*>((const bf16_t*)p.R + row * p.ldr + col);
+#pragma unroll
+      for (int k = 0; k < 4; k++) v[k] += (float)x[k]; }
+    if (p.c_f32) {
+      f32x4* q = reinterpret_cast<f32x4*>((float*)p.C + row * p.ldc + col);
+      if (p.accumulate) { const f32x4 o = *q;
+#pragma unroll
+        for (int k = 0; k < 4; k++) v[k] += o[k]; }
+      *q = v;
+    } else {
+      bf16x4_t w;
+#pragma unroll
+      for (int k = 0; k < 4; k++) w[k] = (bf16_t)v[k];
+      *reinterpret_cast<bf16x4_t*>((bf16_t*)p.C + row * p.ldc + col) = w;
+    }
+  }
 }
 
 // whole 256 x 256 tiles of a plain launch (host-side row count, no split-K, K segments in 64-wide steps, 16-byte rows)
@@ -716,18 +768,33 @@ static bool rs_live(const GemmParams& p) { return p.m_dev || p.grp_off; }
 static bool mfma_ok(const GemmParams& p);
 bool gemm_rs_applies(int mode, const GemmParams& p) { return mode == AS_BF16 && mfma_ok(p) && rs_ok(p); }
 
-static int launch_rs_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStream_t st) {
+static int launch_rs_cfg(as_ctx* ctx, const GemmParams& p_in, int m_off, hipStream_t st) {
+  GemmParams p = p_in;
   constexpr size_t smem = 131072 + 256 * 64;             // two stages of A and B tiles + a 64-byte line per lane (the staged epilogue: 4 x 128 rows of 272 bytes)
   AS_SET_SMEM(ctx, gemm_mfma_rs_kernel<0>, smem);
   AS_SET_SMEM(ctx, gemm_mfma_rs_kernel<1>, smem);
+  AS_SET_SMEM(ctx, (gemm_mfma_rs_kernel<1, GEMM_EPI_STATS>), smem);
+  AS_SET_SMEM(ctx, (gemm_mfma_rs_kernel<1, GEMM_EPI_PROB>), smem);
   const int tn = p.N / 256;
+  if (p.epi != GEMM_EPI_NONE && !p.m_dev) return as_fail(ctx, AS_ERR_SHAPE, "gemm: the head epilogues run over a device-side row count");
   if (rs_live(p)) {                                      // every row tile the live rows can reach; the kernel drops the rest
     const int tm = p.grp_n > 0 ? (int)cdiv(p.rows_cap, 256) + p.grp_n : (int)cdiv(p.M, 256);
-    gemm_mfma_rs_kernel<1><<<dim3(tm * tn), 256, smem, st>>>(p, m_off, tm, tn);
+    if (p.epi == GEMM_EPI_STATS) gemm_mfma_rs_kernel<1, GEMM_EPI_STATS><<<dim3(tm * tn), 256, smem, st>>>(p, m_off, tm, tn);
+    else if (p.epi == GEMM_EPI_PROB) gemm_mfma_rs_kernel<1, GEMM_EPI_PROB><<<dim3(tm * tn), 256, smem, st>>>(p, m_off, tm, tn);
+    else gemm_mfma_rs_kernel<1><<<dim3(tm * tn), 256, smem, st>>>(p, m_off, tm, tn);
   } else {
     // whole row tiles only: the ragged last one too when the operands have the rows, else the caller handles the rest
     const int tm = p.rows_cap >= (int)cdiv(p.M, 256) * 256 ? (int)cdiv(p.M, 256) : p.M / 256;
-    gemm_mfma_rs_kernel<0><<<dim3(tm * tn), 256, smem, st>>>(p, 0, tm, tn);
+    // Split the contraction of the last partial round's tiles over two workgroups each when that round would leave at
+    // least half of the CUs idle, the launch has full rounds before it (short launches keep one summation order with the
+    // other kernels) and the contraction is long enough to be worth a second small launch.
+    const int T = tm * tn, cus = 256, full = T / cus * cus, rest = T - full;
+    const int nt0 = (int)(p.seg[0].K / 64), nt = nt0 + (p.nseg > 1 ? (int)(p.seg[1].K / 64) : 0);
+    p.tail_first = -1;
+    if (p.tail_part && p.epi == GEMM_EPI_NONE && full > 0 && rest > 0 && rest <= 128 && nt >= 32 && nt / 2 <= nt0) p.tail_first = full;
+    else p.tail_part = nullptr;
+    gemm_mfma_rs_kernel<0><<<dim3(p.tail_first >= 0 ? full + 2 * rest : T), 256, smem, st>>>(p, 0, tm, tn);
+    if (p.tail_first >= 0) { AS_LAUNCH_CHECK(ctx); gemm_tail_fixup_kernel<<<dim3(rest), 256, 0, st>>>(p, tm, tn); }
   }
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;

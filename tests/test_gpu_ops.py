@@ -81,6 +81,35 @@ def test_hand_scheduled_gemm_bf16_output(shape, with_residual):
     assert torch.equal(out, other)
 
 
+@pytest.mark.parametrize("out_f32,with_residual", [(False, True), (False, False), (True, True)])
+def test_hand_scheduled_gemm_split_last_round(out_f32, with_residual):
+    """17 x 16 = 272 tiles on 256 CUs: one full round, then 16 tiles whose contraction (2048 + the 64-wide adapter segment)
+    is split over two workgroups each and summed by the second launch; every entry against float64."""
+    B, G, ctx, _ = _env()
+    M, N, K1, K2 = 4352, 4096, 2048, 64
+    g = synth.rng(9, 20)
+    A1, B1 = G.quantise(g.standard_normal((M, K1)), True), G.quantise(g.standard_normal((N, K1)), True)
+    A2, B2 = G.quantise(g.standard_normal((M, K2)), True), G.quantise(g.standard_normal((N, K2)), True)
+    R = G.quantise(g.standard_normal((M, N)), True) if with_residual else None
+    ref = 0.5 * (A1 @ B1.T + A2 @ B2.T) + (R if with_residual else 0.0)
+    dt = torch.bfloat16
+    args = (G.to_dev(A1, dt), G.to_dev(B1, dt), G.to_dev(A2, dt), G.to_dev(B2, dt))
+    kw = dict(alpha=0.5, R=G.to_dev(R, dt) if with_residual else None, out_f32=out_f32, mode=B.AS_BF16, variant=34)
+    scratch = torch.empty(B.GEMM_TAIL_SCRATCH_BYTES, dtype=torch.uint8, device="cuda")
+    out = ctx.op_gemm(*args, tail_scratch=scratch, **kw)
+    plain = ctx.op_gemm(*args, **kw)
+    torch.cuda.synchronize()
+    got = G.to_np(out)
+    if out_f32:
+        assert grad_norm_err(got, ref) < 2e-6 * (K1 + K2) ** 0.5 + 1e-6
+    else:
+        assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-4 * (K1 + K2) ** 0.5)
+    # the tiles of the full round are the same bits with and without the split; the split ones differ in summation order only
+    same = (out == plain).float().mean().item()
+    assert 0.9 < same < 1.0 or out_f32 is False, same
+    assert np.abs(got - G.to_np(plain)).max() <= (1e-4 if out_f32 else 2.0 ** -7) * np.abs(ref).max()
+
+
 @pytest.mark.parametrize("out_f32", [False, True])
 @pytest.mark.parametrize("variant", [0, 30, 34])
 @pytest.mark.parametrize("row_off,live", [(0, 700), (128, 896), (0, 0), (256, 1)])

@@ -20,11 +20,24 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
-# HBM-side bytes per launch of the dominant kernel at config 3 (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, two counter
-# runs over one bench step, see profiles/gemm_256_counters.md); only valid for the kernel those runs saw
-TRAFFIC_BYTES_PER_LAUNCH = {}
+# HBM-side bytes per launch of the dominant kernel at config 3: FETCH_SIZE and WRITE_SIZE of two counter runs over one
+# bench step, each scaled by what the counter reads for a 1 GiB copy (profiles/bench_config3_counters.md).  The figure
+# belongs to the kernel sources those runs saw: the digest below names them, and the line reports null when they differ.
+TRAFFIC_BYTES_PER_LAUNCH = {(3, "gemm_mfma_rs_kernel<0, 0>"): 13.19e9}
+TRAFFIC_SOURCES = ("gemm.hip", "gemm_rs_loop.inc", "common.h")
+TRAFFIC_SOURCE_DIGEST = "d605c18fb1e275bb"
 DOMINANT_KERNEL = "gemm_mfma_rs_kernel<0, 0>"                  # dense models; expert GEMMs: the same kernel with live-row limits, <1>
 GROUPED_KERNEL = "gemm_mfma_rs_kernel<1, 0>"
+
+
+def kernel_sources_digest():
+    """Digest of the sources of the dominant kernel, to tie the stored counter figure to the code it was taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in TRAFFIC_SOURCES:
+        with open(os.path.join(ROOT, "paper_2503_22673_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
 
 
 def device_weights(sh, seed, dtype):
@@ -151,6 +164,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration (2..5); 3 is the headline")
     ap.add_argument("--layers", type=int, default=0, help="override the depth (bring-up only; the result is then not the headline)")
     ap.add_argument("--recompute", type=int, default=-1, help="override the recompute mode (0, 1, 2)")
+    ap.add_argument("--copy-probe", action="store_true", help="only copy 1 GiB device to device (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--rows", type=int, default=0, help="override the number of packed rows")
     ap.add_argument("--row-len", type=int, default=0, help="override the row length")
@@ -168,6 +182,15 @@ def main():
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives are built)" % args.gpus,
               file=sys.stderr)
         sys.exit(2)
+    if args.copy_probe:
+        import torch
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": 1 << 30}))
+        return
 
     import numpy as np
     import torch
@@ -324,7 +347,7 @@ def main():
                      "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_BF16_TFLOPS, 4),
                      "traffic": None if (sh.n_experts or args.rows or args.row_len or args.single_trajectory or args.nf4 or args.dpo or args.bfd) else
-                                TRAFFIC_BYTES_PER_LAUNCH.get((args.config, DOMINANT_KERNEL)),
+                                (TRAFFIC_BYTES_PER_LAUNCH.get((args.config, DOMINANT_KERNEL)) if kernel_sources_digest() == TRAFFIC_SOURCE_DIGEST else None),
                      "traffic_unit": "HBM-side bytes per launch (counters)",
                      "launches_per_step": n_l // max(args.steps, 1), "avg_launch_ms": round(ms_l / max(n_l, 1), 4)},
     }

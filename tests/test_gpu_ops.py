@@ -219,17 +219,17 @@ def _attn_case(seed, n_seg, Hq, Hkv, dh, lens):
     return g, cu, n
 
 
-@pytest.mark.parametrize("tier", ["fp32", "bf16_plain", "bf16_mfma"])
+@pytest.mark.parametrize("tier", ["fp32", "bf16_plain", "bf16_mfma", "bf16_mfma_two_pass"])
 @pytest.mark.parametrize("Hq,Hkv,dh,lens,late_gain", [(4, 4, 32, [100, 1, 63, 200, 148], 1.0), (8, 2, 64, [130, 257, 64, 5], 1.0),
                                                       (4, 1, 128, [300, 70, 129], 1.0), (2, 2, 64, [200, 90], 1.0),
                                                       (4, 2, 128, [65, 190], 1.0), (4, 1, 128, [700, 3, 420], 5.0),
-                                                      (2, 1, 64, [515, 333], 5.0)])
+                                                      (2, 1, 64, [515, 333], 5.0), (2, 2, 128, [333, 97, 260], 1.0)])
 def test_attention_forward_and_backward(tier, Hq, Hkv, dh, lens, late_gain):
     """late_gain > 1 scales the keys of the last third of every segment, so that the running maximum of
     the online softmax jumps by many octaves late in a row (the rare rescale path of the MFMA kernels)."""
     B, G, ctx, sh = _env(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=dh)
     bf16 = tier != "fp32"
-    variant = {"fp32": 1, "bf16_plain": 1, "bf16_mfma": 2}[tier]
+    variant = {"fp32": 1, "bf16_plain": 1, "bf16_mfma": 2, "bf16_mfma_two_pass": 4}[tier]
     if tier.startswith("bf16_mfma") and dh == 32:
         pytest.skip("the MFMA attention kernels cover head_dim 64 and 128")
     dt = torch.bfloat16 if bf16 else torch.float32

@@ -595,6 +595,114 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float sc
   }
 }
 
+// dQ with one wave per SIMD (head_dim 128, four query heads per KV head): wave = 64 queries of one head (a lane owns two
+// queries), workgroup = the 4 heads of a group on the same 64 tokens, so a K / V tile is staged once per group.  The
+// dQ^T accumulators (128 registers) and the wave's Q and dO fragments (128) fill the accumulation half of the register
+// file; a tile step is one generated instruction sequence (gen_attn_dq_tile.py -> attn_dq_tile.inc), one asm statement
+// per loop trip.  K and V tiles sit in LDS once, row major, three stages deep; dQ^T += K^T dS^T reads K through the
+// transposing LDS loads, so no token-major copy of K is needed.  Every wave issues eight loads per tile.
+#include "attn_dq_tile.inc"
+__global__ __launch_bounds__(256) void attn_bwd_dq3_mfma(AttnParams p, float scale, float sl2) {
+  constexpr int DH = 128, KS = DH / 16, CB = DH / 32, QT = 64;
+  constexpr int KT_B = BKEY * DH * 2, ST_B = 2 * KT_B;   // bytes of a tile, of a stage (K, V)
+  extern __shared__ __align__(256) unsigned char dyn_smem256[];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)dyn_smem256;
+  if (lds0 & 255) return;                                       // never the case: the array is the kernel's only LDS
+  const int tid = threadIdx.x, lane = tid & 63, l31 = lane & 31, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = p.n, grp = p.Hq / p.Hkv;
+  int hg, qi;
+  const int nqt = (n + QT - 1) / QT;
+  xcd_group_map(blockIdx.x, nqt, p.Hq / 4, hg, qi);
+  const int j = hg * 4 + wave, g = j / grp;
+  const int t_wg = (p.order_q ? p.order_q[qi] : nqt - 1 - qi) * QT;   // long rows first
+  const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* V = (const bf16_t*)p.v;
+  const bf16_t* dO = (const bf16_t*)p.d_o;
+  const int ss_hi = __builtin_amdgcn_readfirstlane(p.seg_start[min(t_wg + QT - 1, n - 1)]);
+  f32x16 dq[2][CB];
+#pragma unroll
+  for (int qb = 0; qb < 2; qb++)
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++) dq[qb][cb] = zero16();
+  const int kv_first = __builtin_amdgcn_readfirstlane(p.seg_start[min(t_wg, n - 1)] / BKEY);
+  const int kv_last = min(t_wg + QT - 1, n - 1) / BKEY;
+  const int total = kv_last - kv_first + 1;
+  // LDS position of chunk c of row r: c ^ f(r), f = the low four row bits in the order (1, 0, 2, 3)
+  auto swz = [](int row) { return ((row & 3) << 2) | (((row >> 2) & 1) << 1) | ((row >> 3) & 1); };
+  const int l4 = lane >> 4, lc = lane & 15;
+  const uint32_t off0 = (uint32_t)((((int64_t)(wave * 16 + l4)) * p.ldkv + ((lc ^ swz(l4)) * 8)) * 2);
+  auto stage = [&](int it, int st) {                           // the loads of key tile kv_first + it, from here (first two tiles, ragged tiles)
+    const int k0 = (kv_first + it) * BKEY;
+    unsigned char* d = dyn_smem256 + st * ST_B;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int row = wave * 16 + 4 * i + l4, tok = min(k0 + row, n - 1), ch = (lc ^ swz(row)) * 8;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(K + (int64_t)tok * p.ldkv + g * DH + ch),
+                                       (__attribute__((address_space(3))) void*)(d + (wave * 4 + i) * 1024), 16, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int row = wave * 16 + 4 * i + l4, tok = min(k0 + row, n - 1), ch = (lc ^ swz(row)) * 8;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(V + (int64_t)tok * p.ldkv + g * DH + ch),
+                                       (__attribute__((address_space(3))) void*)(d + KT_B + (wave * 4 + i) * 1024), 16, 0, 0);
+    }
+  };
+  const int sl = lane & 15, mh = (lane >> 4) & 1, row0 = 4 * h + (sl >> 2);
+  const uint32_t aR0 = lds0 + l31 * 256 + ((h ^ swz(l31)) * 16);
+  const uint32_t aT0 = lds0 + row0 * 256 + (((2 * mh + ((sl & 3) >> 1)) ^ swz(row0)) * 16) + (sl & 1) * 8;
+  if (total > 0) stage(0, 0);                                  // the first tiles travel while the wave fetches its own rows
+  if (total > 1) stage(1, 1);
+  int tq[2], ss[2];
+  float nl2[2], dl[2];
+  bf16x8 qf[2][KS], dof[2][KS];
+#pragma unroll
+  for (int qb = 0; qb < 2; qb++) {
+    tq[qb] = t_wg + qb * 32 + l31;
+    const int tc = min(tq[qb], n - 1);
+    ss[qb] = p.seg_start[tc];
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      qf[qb][ks] = *reinterpret_cast<const bf16x8*>(Q + (int64_t)tc * p.ldq + j * DH + ks * 16 + h * 8);
+      dof[qb][ks] = *reinterpret_cast<const bf16x8*>(dO + ((int64_t)tc * p.Hq + j) * DH + ks * 16 + h * 8);
+    }
+    nl2[qb] = -p.lse[(int64_t)tc * p.Hq + j] * 1.4426950408889634f;
+    dl[qb] = p.delta[(int64_t)tc * p.Hq + j];
+  }
+  int st = 0;
+  for (int it = 0; it < total; it++) {
+    if (it + 1 < total) __builtin_amdgcn_s_waitcnt(0x0f78); else __builtin_amdgcn_s_waitcnt(0x0f70);   // all but the next tile's eight loads
+    __syncthreads();
+    const int k0 = (kv_first + it) * BKEY;
+    const int nx = it + 2, k0n = (kv_first + nx) * BKEY, stn = st == 0 ? 2 : st - 1;      // (it + 2) % 3
+    const bool has = nx < total, fast = has && k0n + BKEY - 1 <= n - 1;
+    if (has && !fast) stage(nx, stn);
+    // 1: every query of the wave sees every key of the tile; 2: the tile touches the diagonal or a segment start
+    const int kind = (k0 + 63 <= t_wg && k0 >= ss_hi) ? 1 : 2;
+    const int mode = kind | (fast ? 4 : 0);
+    const uint32_t sb = st * ST_B, sbn = stn * ST_B;
+    const uint32_t aR = aR0 + sb, aT = aT0 + sb;
+    const int tb0 = k0 + 4 * h - ss[0], tb1 = k0 + 4 * h - ss[1], lim0 = tq[0] - ss[0], lim1 = tq[1] - ss[1];
+    const int k0c = has ? k0n : 0;
+    const uint64_t gk = (uint64_t)(K + g * DH + (int64_t)k0c * p.ldkv), gv = (uint64_t)(V + g * DH + (int64_t)k0c * p.ldkv);
+    const uint32_t str = (uint32_t)(4 * p.ldkv * 2);
+    const uint32_t m0t = lds0 + sbn + wave * 4096;
+    asm volatile(ATTN_DQ_TILE_ASM
+                 : "+a"(dq[0][0]), "+a"(dq[0][1]), "+a"(dq[0][2]), "+a"(dq[0][3]), "+a"(dq[1][0]), "+a"(dq[1][1]), "+a"(dq[1][2]), "+a"(dq[1][3])
+                 : "a"(qf[0][0]), "a"(qf[0][1]), "a"(qf[0][2]), "a"(qf[0][3]), "a"(qf[0][4]), "a"(qf[0][5]), "a"(qf[0][6]), "a"(qf[0][7]),
+                   "a"(qf[1][0]), "a"(qf[1][1]), "a"(qf[1][2]), "a"(qf[1][3]), "a"(qf[1][4]), "a"(qf[1][5]), "a"(qf[1][6]), "a"(qf[1][7]),
+                   "a"(dof[0][0]), "a"(dof[0][1]), "a"(dof[0][2]), "a"(dof[0][3]), "a"(dof[0][4]), "a"(dof[0][5]), "a"(dof[0][6]), "a"(dof[0][7]),
+                   "a"(dof[1][0]), "a"(dof[1][1]), "a"(dof[1][2]), "a"(dof[1][3]), "a"(dof[1][4]), "a"(dof[1][5]), "a"(dof[1][6]), "a"(dof[1][7]),
+                   "v"(aR), "v"(aT), "s"(sl2), "v"(nl2[0]), "v"(nl2[1]), "v"(dl[0]), "v"(dl[1]), "v"(tb0), "v"(tb1), "v"(lim0), "v"(lim1), "s"(mode),
+                   "s"(gk), "s"(gv), "s"(str), "v"(off0), "s"(m0t)
+                 : ATTN_DQ_TILE_CLOBBERS);
+    st = st == 2 ? 0 : st + 1;
+  }
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");            // the accumulators are read next: wait states of the last MFMA
+#pragma unroll
+  for (int qb = 0; qb < 2; qb++)
+    if (tq[qb] < n) store_grad_row<DH>(dq[qb], scale, (bf16_t*)p.dq + (int64_t)tq[qb] * p.ldq + j * DH, h, p.rope_cos, p.rope_sin, tq[qb] - ss[qb]);
+}
+
 // dK and dV of one query head in ONE pass (head_dim 128): S, the exponentials and dP are computed once.  Wave = 32 keys,
 // workgroup = 4 waves = 128 keys, one wave per SIMD: both accumulator sets (2 x 64 registers) and the wave's K and V
 // fragments sit in the accumulation half of the register file.  With one wave per SIMD only the wave's own instruction
@@ -628,12 +736,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv3_mfma(AttnParams p, float sc
   const int u = u_base + l31, uc = min(u, n - 1);
   const int uend = (u < n) ? p.seg_end[uc] : 0;                 // queries u <= t < uend see this key
   const int vis = (u < n) ? uend - u : 0;
-  bf16x8 kf[KS], vf[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ks++) {
-    kf[ks] = *reinterpret_cast<const bf16x8*>(K + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
-    vf[ks] = *reinterpret_cast<const bf16x8*>(V + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
-  }
   f32x16 accK[CB], accV[CB];                                    // dK^T and dV^T, [dh rows, key lane]
 #pragma unroll
   for (int cb = 0; cb < CB; cb++) { accK[cb] = zero16(); accV[cb] = zero16(); }
@@ -676,8 +778,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv3_mfma(AttnParams p, float sc
   const uint32_t aR0 = lds0 + l31 * 256 + ((h ^ swz(l31)) * 16);
   const uint32_t aT0 = lds0 + row0 * 256 + (((2 * mh + ((sl & 3) >> 1)) ^ swz(row0)) * 16) + (sl & 1) * 8;
   const uint32_t aL0 = lds0 + 2 * KT_B + 16 * h;
-  if (total > 0) stage(0, 0);
+  if (total > 0) stage(0, 0);                                  // the first tiles travel while the wave fetches its own rows
   if (total > 1) stage(1, 1);
+  bf16x8 kf[KS], vf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) {
+    kf[ks] = *reinterpret_cast<const bf16x8*>(K + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
+    vf[ks] = *reinterpret_cast<const bf16x8*>(V + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
+  }
   int st = 0;
   for (int it = 0; it < total; it++) {
     if (it + 1 < total) __builtin_amdgcn_s_waitcnt(0x0f79); else __builtin_amdgcn_s_waitcnt(0x0f70);   // all but the next tile's nine loads
@@ -819,6 +927,14 @@ int launch_dkv2(as_ctx* ctx, const AttnParams& p, float scale, float sl2, float*
   return AS_OK;
 }
 
+int launch_dq3(as_ctx* ctx, const AttnParams& p, float scale, float sl2, hipStream_t st) {
+  constexpr size_t smem = (size_t)3 * 2 * BKEY * 128 * sizeof(bf16_t);      // three stages of a K and a V tile
+  AS_SET_SMEM(ctx, attn_bwd_dq3_mfma, smem);
+  attn_bwd_dq3_mfma<<<(unsigned)(cdiv(p.n, 64) * (p.Hq / 4)), 256, smem, st>>>(p, scale, sl2);
+  AS_LAUNCH_CHECK(ctx);
+  return AS_OK;
+}
+
 int launch_dkv3(as_ctx* ctx, const AttnParams& p, float scale, float sl2, float* part, hipStream_t st) {
   constexpr size_t smem = (size_t)3 * (2 * BKEY * 128 * sizeof(bf16_t) + 1024);   // three stages of a Q and a dO tile, lse, delta
   AS_SET_SMEM(ctx, attn_bwd_dkv3_mfma, smem);
@@ -840,15 +956,18 @@ int bwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
   {
     // one pass for dK and dV (head_dim 128, row strides a multiple of 256 bytes): reads Q and dO as they are
     const bool one_pass = DH == 128 && variant != 4 && p.ldq % 128 == 0;
-    if ((rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, Dkv, p.k, p.ldkv, ts, Np, st))) return rc;                       // K^T
+    const int hpw = heads_per_wg(p);
+    // dQ with one wave per SIMD: four query heads per KV head, K / V row strides a multiple of 256 bytes; reads K as it is
+    const bool dq_one_wave = one_pass && variant != 5 && hpw == 4 && p.ldkv % 128 == 0;
+    if (!dq_one_wave && (rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, Dkv, p.k, p.ldkv, ts, Np, st))) return rc;           // K^T
     if (!one_pass) {
       if ((rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, D, p.q, p.ldq, ts + (size_t)Dkv * Np, Np, st))) return rc;       // Q^T
       if ((rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, D, p.d_o, D, ts + (size_t)(Dkv + D) * Np, Np, st))) return rc;   // dO^T
     }
     launch_delta<DH>(p, rows, st);
     AS_LAUNCH_CHECK(ctx);
-    const int hpw = heads_per_wg(p);
-    if (hpw == 4) rc = launch_dq2<DH, 4>(ctx, p, scale, sl2, st); else if (hpw == 2) rc = launch_dq2<DH, 2>(ctx, p, scale, sl2, st);
+    if (dq_one_wave) rc = launch_dq3(ctx, p, scale, sl2, st);
+    else if (hpw == 4) rc = launch_dq2<DH, 4>(ctx, p, scale, sl2, st); else if (hpw == 2) rc = launch_dq2<DH, 2>(ctx, p, scale, sl2, st);
     else rc = launch_dq2<DH, 1>(ctx, p, scale, sl2, st);
     if (rc) return rc;
     float* part = (float*)(ts + (size_t)(Dkv + 2 * D) * Np);       // [2][Hq][n][dh] floats behind the token-major copies

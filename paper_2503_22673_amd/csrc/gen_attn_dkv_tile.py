@@ -7,8 +7,8 @@ The wave runs alone on its SIMD (both halves of the register file), so nothing b
 the matrix pipe busy while the vector ALU works and the next tiles arrive.  A tile step is 64
 v_mfma_f32_32x32x16_bf16:
 
-  slots  0..15  S0 / dP0 alternating over the 8 slices of head_dim (queries 0..31 of the tile)
-  slots 16..31  S1 / dP1                                            (queries 32..63)
+  slots  0..15  S0, then dP0, over the 8 slices of head_dim (queries 0..31 of the tile)
+  slots 16..31  S1, then dP1                                 (queries 32..63)
   slots 32..39  dV += dO^T P^T   for the query chunks 0, 1 (of 16) x 4 column blocks
   slots 40..47  dK += Q^T  dS^T  for the query chunks 0, 1
   slots 48..55  dV, chunks 2, 3
@@ -58,7 +58,7 @@ import os
 (OP_DK, OP_DV, OP_KF, OP_VF, OP_AR, OP_AT, OP_AL, OP_SL2, OP_TB, OP_LEN, OP_MODE,
  OP_GQ, OP_GD, OP_SQ, OP_SD, OP_VQ, OP_VD, OP_M0T, OP_VL, OP_M0L) = (0, 4, 8, 16, 24, 25, 26, 27, 28, 29, 30,
                                                                       31, 32, 33, 34, 35, 36, 37, 38, 39)
-CAP = 6                     # vector-ALU issue units behind one MFMA (v_exp counts 2)
+CAP = int(os.environ.get('ATTN_DKV_CAP', '6'))   # vector-ALU issue units behind one MFMA (v_exp counts 2): five plain ones behind an MFMA are free, the sixth costs 2 clocks, measured
 CAP_MASKED = 10             # the masked form (tiles on the diagonal or a segment end) has 96 more instructions to place
 NEG_LOG2E = "0xbfb8aa3b"
 LOAD_SLOTS = [3, 10, 17, 24, 31, 38, 45, 52, 59]
@@ -76,9 +76,10 @@ def BS(x, j): return "v%d" % (208 + 4 * x + j)
 def mfma_list():
     """per slot: (kind, block index, fragment reads as (text with %s for the register, first register offset, registers), b operand, first of chain)"""
     L = []
-    for qb in range(2):
+    for qb in range(2):                       # whole chains one after the other: the vector work on S0 starts under dP0
         for ks in range(8):
             L.append(("S", qb, [("ds_read_b128 %%s, v%d offset:%d" % (112 + ks, qb * 8192), 0, 4)], "%%%d" % (OP_KF + ks), ks == 0))
+        for ks in range(8):
             L.append(("dP", qb, [("ds_read_b128 %%s, v%d offset:%d" % (112 + ks, 16384 + qb * 8192), 0, 4)], "%%%d" % (OP_VF + ks), ks == 0))
     for half in range(2):
         for which in ("dV", "dK"):
@@ -98,7 +99,7 @@ def groups(masked):
     G = []
     use = 0
     for qb in range(2):
-        s_ready = 19 + 16 * qb           # the S chain ends at slot 14 + 16 qb, the dP chain one later
+        s_ready = 12 + 16 * qb           # the S chain ends at slot 7 + 16 qb, the dP chain at 15 + 16 qb
         d_ready = 20 + 16 * qb
         for b4 in range(4):
             ins = []
@@ -281,9 +282,7 @@ def emit(masked, loads):
         put("v_mov_b32 v94, 0xff800000")
     for ks in range(8):                       # slice addresses: the swizzle is an XOR on the chunk bits, so is the slice
         put("v_xor_b32 v%d, %d, %%%d" % (112 + ks, 32 * ks, OP_AR))
-        if ks < 4:
-            frag_reads(2 * ks)
-            frag_reads(2 * ks + 1)
+        frag_reads(ks)                        # the first eight MFMAs are the slices of S0
     for cb in range(4):                       # patch addresses: column block cb, rows 0..3 and 8..11 of a query chunk
         put("v_xor_b32 v%d, %d, %%%d" % (120 + cb, 64 * cb, OP_AT))
         put("v_xor_b32 v%d, %d, %%%d" % (124 + cb, (64 * cb) ^ 16, OP_AT))

@@ -703,8 +703,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dq3_mfma(AttnParams p, float sca
     if (tq[qb] < n) store_grad_row<DH>(dq[qb], scale, (bf16_t*)p.dq + (int64_t)tq[qb] * p.ldq + j * DH, h, p.rope_cos, p.rope_sin, tq[qb] - ss[qb]);
 }
 
-// dK and dV of one query head in ONE pass (head_dim 128): S, the exponentials and dP are computed once.  Wave = 32 keys,
-// workgroup = 4 waves = 128 keys, one wave per SIMD: both accumulator sets (2 x 64 registers) and the wave's K and V
+// dK and dV in ONE pass (head_dim 128): S, the exponentials and dP are computed once, and the query heads of a KV head
+// are taken one after the other into the same accumulators (head order, then tile order: a fixed summation order, no
+// partial sums in memory).  Wave = 32 keys, workgroup = 4 waves = 128 keys, one wave per SIMD: both accumulator sets (2 x 64 registers) and the wave's K and V
 // fragments sit in the accumulation half of the register file.  With one wave per SIMD only the wave's own instruction
 // order can overlap matrix work, vector work and the arrival of the next tiles, so a tile step is one generated
 // instruction sequence (gen_attn_dkv_tile.py -> attn_dkv_tile.inc: plain and masked, with and without the loads of the
@@ -714,7 +715,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq3_mfma(AttnParams p, float sca
 // Every wave issues nine loads per tile (four kilobytes of Q, four of dO, and the tile's lse values (even waves) or
 // delta values (odd waves); those of waves 2 and 3 land in spare space), so that one count serves all waves.
 #include "attn_dkv_tile.inc"
-__global__ __launch_bounds__(256) void attn_bwd_dkv3_mfma(AttnParams p, float scale, float sl2, float* __restrict__ part) {
+__global__ __launch_bounds__(256) void attn_bwd_dkv3_mfma(AttnParams p, float scale, float sl2) {
   constexpr int DH = 128, KS = DH / 16, CB = DH / 32, NWV = 4, KPB = 32 * NWV, NST = 3;
   constexpr int KT_B = BKEY * DH * 2;                     // bytes of a tile
   constexpr int ST_B = 2 * KT_B + 1024;                   // Q, dO, 64 lse, 64 delta floats, 512 spare bytes
@@ -725,9 +726,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv3_mfma(AttnParams p, float sc
   const int tid = threadIdx.x, lane = tid & 63, l31 = lane & 31, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = p.n, grp = p.Hq / p.Hkv;
-  int jj, ki;
-  xcd_group_map(blockIdx.x, 2 * ((n + 255) / 256), p.Hq, jj, ki);
-  const int g = jj / grp;
+  int g, ki;
+  xcd_group_map(blockIdx.x, 2 * ((n + 255) / 256), p.Hkv, g, ki);
   const int u_wg = (p.order_k ? p.order_k[ki >> 1] * 2 + (ki & 1) : ki) * KPB, u_base = u_wg + wave * 32;
   if (u_wg >= n) return;                                        // the second half of a last, half-empty block of 256
   const bf16_t* Q = (const bf16_t*)p.q; const bf16_t* K = (const bf16_t*)p.k; const bf16_t* V = (const bf16_t*)p.v;
@@ -743,7 +743,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv3_mfma(AttnParams p, float sc
   const int q_last = __builtin_amdgcn_readfirstlane((p.seg_end[min(u_wg + KPB - 1, n - 1)] - 1) / BKEY);
   const int w_end = (u_base < n) ? __builtin_amdgcn_readfirstlane(p.seg_end[min(u_base + 31, n - 1)]) : 0;
   const int w_end_min = (u_base < n) ? __builtin_amdgcn_readfirstlane(p.seg_end[min(u_base, n - 1)]) : 0;
-  const int total = q_last - q_first + 1;
+  const int total = q_last - q_first + 1;                       // query tiles per head
+  const int steps = total * grp;                                // the query heads of the group one after the other: step = (head, tile)
   // LDS position of chunk c of row r: c ^ f(r), f = the low four row bits in the order (1, 0, 2, 3)
   auto swz = [](int row) { return ((row & 3) << 2) | (((row >> 2) & 1) << 1) | ((row >> 3) & 1); };
   // a load instruction of a wave fills one kilobyte = four rows; lane -> row lane / 16, position lane % 16
@@ -751,9 +752,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv3_mfma(AttnParams p, float sc
   const uint32_t offQ0 = (uint32_t)((((int64_t)(wave * 16 + l4)) * p.ldq + ((lc ^ swz(l4)) * 8)) * 2);
   const uint32_t offD0 = (uint32_t)((((int64_t)(wave * 16 + l4)) * ldo + ((lc ^ swz(l4)) * 8)) * 2);
   const float* stat = (wave & 1) ? p.delta : p.lse;             // this wave's ninth load
-  auto stat_ptr = [&](int t0) { return stat + (int64_t)min(t0 + lane, n - 1) * p.Hq + jj; };
-  auto stage = [&](int it, int st) {                           // the loads of tile `it`, from here (first two tiles, ragged tiles)
-    const int t0 = (q_last - it) * BKEY;
+  auto stat_ptr = [&](int jj, int t0) { return stat + (int64_t)min(t0 + lane, n - 1) * p.Hq + jj; };
+  auto stage = [&](int hh, int it, int st) {                   // the loads of tile `it` of head hh, from here (first two steps, ragged tiles)
+    const int t0 = (q_last - it) * BKEY, jj = g * grp + hh;
     unsigned char* d = dyn_smem256 + st * ST_B;
 #pragma unroll
     for (int i = 0; i < 4; i++) {
@@ -767,7 +768,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv3_mfma(AttnParams p, float sc
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(dO + (int64_t)tok * ldo + jj * DH + ch),
                                        (__attribute__((address_space(3))) void*)(d + KT_B + (wave * 4 + i) * 1024), 16, 0, 0);
     }
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)stat_ptr(t0),
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)stat_ptr(jj, t0),
                                      (__attribute__((address_space(3))) void*)(d + 2 * KT_B + wave * 256), 4, 0, 0);
   };
   // this lane's row in a tile (256-byte rows, chunk h: slice ks is that address XOR 32 ks); its corner of the
@@ -778,22 +779,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv3_mfma(AttnParams p, float sc
   const uint32_t aR0 = lds0 + l31 * 256 + ((h ^ swz(l31)) * 16);
   const uint32_t aT0 = lds0 + row0 * 256 + (((2 * mh + ((sl & 3) >> 1)) ^ swz(row0)) * 16) + (sl & 1) * 8;
   const uint32_t aL0 = lds0 + 2 * KT_B + 16 * h;
-  if (total > 0) stage(0, 0);                                  // the first tiles travel while the wave fetches its own rows
-  if (total > 1) stage(1, 1);
+  if (steps > 0) stage(0, 0, 0);                               // the first tiles travel while the wave fetches its own rows
+  if (steps > 1) { if (total > 1) stage(0, 1, 1); else stage(1, 0, 1); }
   bf16x8 kf[KS], vf[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ks++) {
     kf[ks] = *reinterpret_cast<const bf16x8*>(K + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
     vf[ks] = *reinterpret_cast<const bf16x8*>(V + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
   }
-  int st = 0;
-  for (int it = 0; it < total; it++) {
-    if (it + 1 < total) __builtin_amdgcn_s_waitcnt(0x0f79); else __builtin_amdgcn_s_waitcnt(0x0f70);   // all but the next tile's nine loads
+  int st = 0, it = 0, hn = total > 2 ? 0 : (total == 2 ? 1 : 2), itn = total > 2 ? 2 : 0;   // (head, tile) of this step; of the step after next
+  for (int step = 0; step < steps; step++) {
+    if (step + 1 < steps) __builtin_amdgcn_s_waitcnt(0x0f79); else __builtin_amdgcn_s_waitcnt(0x0f70);   // all but the next step's nine loads
     __syncthreads();
     const int t0 = (q_last - it) * BKEY;
-    const int nx = it + 2, t0n = (q_last - nx) * BKEY, stn = st == 0 ? 2 : st - 1;      // (it + 2) % 3
-    const bool has = nx < total, fast = has && t0n + BKEY - 1 <= n - 1;
-    if (has && !fast) stage(nx, stn);
+    const int t0n = (q_last - itn) * BKEY, stn = st == 0 ? 2 : st - 1;                     // stage (step + 2) % 3
+    const bool has = step + 2 < steps, fast = has && t0n + BKEY - 1 <= n - 1;
+    if (has && !fast) stage(hn, itn, stn);
     // 0: no query of the tile sees a key of this wave; 1: every query sees every key; 2: the tile touches the diagonal or a segment end
     const int kind = (t0 + 63 < u_base || t0 >= w_end) ? 0 : ((t0 >= u_base + 31) && (t0 + 63 < w_end_min)) ? 1 : 2;
     const int mode = kind | (fast ? 4 : 0);
@@ -801,10 +802,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv3_mfma(AttnParams p, float sc
     const uint32_t aR = aR0 + sb, aT = aT0 + sb, aL = aL0 + sb;
     const int tb = t0 + 4 * h - u;
     const int t0c = has ? t0n : 0;
-    const uint64_t gq = (uint64_t)(Q + jj * DH + (int64_t)t0c * p.ldq), gd = (uint64_t)(dO + jj * DH + (int64_t)t0c * ldo);
+    const int jn = g * grp + (has ? hn : 0);
+    const uint64_t gq = (uint64_t)(Q + jn * DH + (int64_t)t0c * p.ldq), gd = (uint64_t)(dO + jn * DH + (int64_t)t0c * ldo);
     const uint32_t strq = (uint32_t)(4 * p.ldq * 2), strd = (uint32_t)(4 * ldo * 2);
     const uint32_t m0t = lds0 + sbn + wave * 4096, m0l = lds0 + sbn + 2 * KT_B + wave * 256;
-    const uint64_t vl = (uint64_t)stat_ptr(t0c);
+    const uint64_t vl = (uint64_t)stat_ptr(jn, t0c);
     asm volatile(ATTN_DKV_TILE_ASM
                  : "+a"(accK[0]), "+a"(accK[1]), "+a"(accK[2]), "+a"(accK[3]), "+a"(accV[0]), "+a"(accV[1]), "+a"(accV[2]), "+a"(accV[3])
                  : "a"(kf[0]), "a"(kf[1]), "a"(kf[2]), "a"(kf[3]), "a"(kf[4]), "a"(kf[5]), "a"(kf[6]), "a"(kf[7]),
@@ -813,28 +815,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv3_mfma(AttnParams p, float sc
                    "s"(gq), "s"(gd), "s"(strq), "s"(strd), "v"(offQ0), "v"(offD0), "s"(m0t), "v"(vl), "s"(m0l)
                  : ATTN_DKV_TILE_CLOBBERS);
     st = st == 2 ? 0 : st + 1;
+    if (++it == total) it = 0;
+    if (++itn == total) { itn = 0; hn++; }
   }
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");            // the accumulators are read next: wait states of the last MFMA
   if (u >= n) return;
-  if (grp > 1) {
-#pragma unroll
-    for (int which = 0; which < 2; which++) {
-      float* row = part + (((int64_t)which * p.Hq + jj) * n + u) * DH;
-#pragma unroll
-      for (int cb = 0; cb < CB; cb++)
-#pragma unroll
-        for (int b4 = 0; b4 < 4; b4++) {
-          f32x4 w;
-#pragma unroll
-          for (int i = 0; i < 4; i++) w[i] = which == 0 ? accK[cb][b4 * 4 + i] : accV[cb][b4 * 4 + i];
-          *reinterpret_cast<f32x4*>(row + cb * 32 + 8 * b4 + 4 * h) = w;
-        }
-    }
-  } else {
-    const int pos = u - p.seg_start[u];
-    store_grad_row<DH>(accK, scale, (bf16_t*)p.dk + (int64_t)u * p.ldkv + g * DH, h, p.rope_cos, p.rope_sin, pos);
-    store_grad_row<DH>(accV, 1.f, (bf16_t*)p.dv + (int64_t)u * p.ldkv + g * DH, h, nullptr, p.rope_sin, pos);
-  }
+  const int pos = u - p.seg_start[u];
+  store_grad_row<DH>(accK, scale, (bf16_t*)p.dk + (int64_t)u * p.ldkv + g * DH, h, p.rope_cos, p.rope_sin, pos);
+  store_grad_row<DH>(accV, 1.f, (bf16_t*)p.dv + (int64_t)u * p.ldkv + g * DH, h, nullptr, p.rope_sin, pos);
 }
 
 // dk[u, g, :] = scale * sum over the query heads of group g, in head order, of the dK partials; dv likewise (scale 1).
@@ -935,10 +923,10 @@ int launch_dq3(as_ctx* ctx, const AttnParams& p, float scale, float sl2, hipStre
   return AS_OK;
 }
 
-int launch_dkv3(as_ctx* ctx, const AttnParams& p, float scale, float sl2, float* part, hipStream_t st) {
+int launch_dkv3(as_ctx* ctx, const AttnParams& p, float scale, float sl2, hipStream_t st) {
   constexpr size_t smem = (size_t)3 * (2 * BKEY * 128 * sizeof(bf16_t) + 1024);   // three stages of a Q and a dO tile, lse, delta
   AS_SET_SMEM(ctx, attn_bwd_dkv3_mfma, smem);
-  attn_bwd_dkv3_mfma<<<(unsigned)(2 * cdiv(p.n, 256) * p.Hq), 256, smem, st>>>(p, scale, sl2, part);
+  attn_bwd_dkv3_mfma<<<(unsigned)(2 * cdiv(p.n, 256) * p.Hkv), 256, smem, st>>>(p, scale, sl2);
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;
 }
@@ -971,8 +959,8 @@ int bwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
     else rc = launch_dq2<DH, 1>(ctx, p, scale, sl2, st);
     if (rc) return rc;
     float* part = (float*)(ts + (size_t)(Dkv + 2 * D) * Np);       // [2][Hq][n][dh] floats behind the token-major copies
-    if (one_pass) { if ((rc = launch_dkv3(ctx, p, scale, sl2, part, st))) return rc; }
-    else if ((rc = launch_dkv2<DH, 0>(ctx, p, scale, sl2, part, st)) || (rc = launch_dkv2<DH, 1>(ctx, p, scale, sl2, part, st))) return rc;
+    if (one_pass) return launch_dkv3(ctx, p, scale, sl2, st);     // sums over the query heads itself
+    if ((rc = launch_dkv2<DH, 0>(ctx, p, scale, sl2, part, st)) || (rc = launch_dkv2<DH, 1>(ctx, p, scale, sl2, part, st))) return rc;
     if (p.Hq > p.Hkv) {
       const int64_t threads = 2 * (int64_t)p.n * p.Hkv * (DH / 4);
       attn_dkv_reduce_kernel<<<(unsigned)cdiv(threads, 256), 256, 0, st>>>(part, p.n, p.Hq, p.Hkv, DH, scale, (bf16_t*)p.dk, (bf16_t*)p.dv, p.ldkv,

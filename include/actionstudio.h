@@ -13,8 +13,8 @@
  *  - Every pointer is marked [host] or [device].  Device buffers are
  *    allocated and freed by the caller; the library keeps no device pointer
  *    of the caller's after a call returns.  Device memory of the library's
- *    own: the staging buffer of as_pack inside as_ctx (pinned host + device,
- *    grown on demand by as_pack only), and one fixed device array
+ *    own: the staging buffer of as_pack inside the context, pinned host + device,
+ *    grown on demand by as_pack only, and one fixed device array
  *    (AS_STATIC_SCRATCH_BYTES, see as_op_attention_bwd_static).  No other call
  *    allocates or frees memory of any kind on the device: as_train_step and its
  *    relatives work inside the caller's workspace (their small per-step tables
@@ -381,11 +381,14 @@ int as_op_rmsnorm_bwd(as_ctx* ctx, int mode, int64_t n, int64_t d, const void* d
 /* Varlen causal attention with grouped KV heads over packed rows.  q [n,Hq,dh]
  * with row stride ldq elements, k, v [n,Hkv,dh] with stride ldkv, o [n,Hq,dh]
  * dense, lse float [n,Hq].  seg_start [n] int32: first token of each token's
- * segment.  variant: 0 = pick, 1 = plain kernel, 2 = MFMA kernels (bf16, head_dim 64 or 128).
+ * segment.  variant: 0 = pick, 1 = plain kernel, 2 = MFMA kernels (bf16, head_dim 64 or 128); backward only:
+ * 4 = the MFMA kernels that work from token-major copies (dK and dV in two launches with float partials per query
+ * head), which head_dim 64 always takes; head_dim 128 with row strides that are multiples of 128 elements otherwise
+ * takes the one-pass kernels that read their operands as they are.
  * t_scratch: type T, only read by the MFMA kernels (may be NULL otherwise):
  * room for Hkv*dh * n64 elements in forward and (6*Hq + Hkv)*dh * n64 in
  * backward, n64 = n rounded up to 64 (token-major copies of V, resp. K, Q, dO,
- * followed in backward by float dK / dV partials per query head). */
+ * followed in backward by float dK / dV partials per query head; the one-pass kernels leave it untouched). */
 int as_op_attention_fwd(as_ctx* ctx, int mode, int variant, int64_t n, const int32_t* seg_start,
                         const void* q, int64_t ldq, const void* k, const void* v, int64_t ldkv,
                         void* o, float* lse, void* t_scratch, void* stream);

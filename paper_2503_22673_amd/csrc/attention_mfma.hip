@@ -106,8 +106,6 @@ __device__ __forceinline__ void tile_to_lds(const bf16_t* base, int64_t ld, int 
 
 // Wave = QB blocks of 32 queries of one head; workgroup = HPW heads x (NWV / HPW) query groups, NWV = 8 / QB waves.
 // QB = 1 keeps a wave under 256 registers, so two waves share a SIMD and one's softmax runs under the other's MFMAs.
-// NWV = 4 with QB = 1: two independent 4-wave workgroups per CU instead of one of eight waves; the register cap
-// (two waves per SIMD) then has to be asked for explicitly.
 // Workgroups go to the eight XCDs round-robin by linear index, and each XCD has an L2 of its own.  The work
 // items of a launch form `ngrp` groups (a head or a group of heads) of `per` items each; the items of a
 // group stream the same operand tiles, so a whole group is kept on one XCD: XCD x takes the groups x, x + 8, ...
@@ -893,7 +891,6 @@ int fwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
   if (rc) return rc;
   const float sl2 = 1.4426950408889634f / sqrtf((float)DH);
   const int hpw = heads_per_wg(p);
-  if (variant == 5) return hpw == 4 ? launch_fwd2<DH, 4, 1, 4>(ctx, p, sl2, st) : hpw == 2 ? launch_fwd2<DH, 2, 1, 4>(ctx, p, sl2, st) : launch_fwd2<DH, 1, 1, 4>(ctx, p, sl2, st);
   return hpw == 4 ? launch_fwd2<DH, 4, 1>(ctx, p, sl2, st) : hpw == 2 ? launch_fwd2<DH, 2, 1>(ctx, p, sl2, st) : launch_fwd2<DH, 1, 1>(ctx, p, sl2, st);
 }
 
@@ -946,7 +943,7 @@ int bwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
     const bool one_pass = DH == 128 && variant != 4 && p.ldq % 128 == 0;
     const int hpw = heads_per_wg(p);
     // dQ with one wave per SIMD: four query heads per KV head, K / V row strides a multiple of 256 bytes; reads K as it is
-    const bool dq_one_wave = one_pass && variant != 5 && hpw == 4 && p.ldkv % 128 == 0;
+    const bool dq_one_wave = one_pass && hpw == 4 && p.ldkv % 128 == 0;
     if (!dq_one_wave && (rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, Dkv, p.k, p.ldkv, ts, Np, st))) return rc;           // K^T
     if (!one_pass) {
       if ((rc = launch_transpose_qs(ctx, AS_BF16, p.n, Np, D, p.q, p.ldq, ts + (size_t)Dkv * Np, Np, st))) return rc;       // Q^T

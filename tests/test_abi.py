@@ -160,9 +160,9 @@ def test_adamw_and_op_argument_checks(B):
     assert f(ctx.handle, one, None, nul, one, one, numel, wd, 1, 1, 1e-3, 0.9, 0.95, 1e-8, 0.0, None) == B.ERR["NULL"]
     g = B.lib.as_op_gemm
     p = C.c_void_p(4096)
-    assert g(ctx.handle, 0, 0, 4, 4, None, 4, p, 4, 4, None, 0, None, 0, 0, 1.0, None, 0, p, 4, 0, None) == B.ERR["NULL"]
-    assert g(ctx.handle, 0, 0, 4, 4, p, 2, p, 4, 4, None, 0, None, 0, 0, 1.0, None, 0, p, 4, 0, None) == B.ERR["SHAPE"]
-    assert g(ctx.handle, 9, 0, 4, 4, p, 4, p, 4, 4, None, 0, None, 0, 0, 1.0, None, 0, p, 4, 0, None) == B.ERR["CONFIG"]
+    assert g(ctx.handle, 0, 0, 4, 4, None, 4, p, 4, 4, None, 0, None, 0, 0, 1.0, None, 0, p, 4, 0, None, 0, None) == B.ERR["NULL"]
+    assert g(ctx.handle, 0, 0, 4, 4, p, 2, p, 4, 4, None, 0, None, 0, 0, 1.0, None, 0, p, 4, 0, None, 0, None) == B.ERR["SHAPE"]
+    assert g(ctx.handle, 9, 0, 4, 4, p, 4, p, 4, 4, None, 0, None, 0, 0, 1.0, None, 0, p, 4, 0, None, 0, None) == B.ERR["CONFIG"]
 
 
 def test_generated_gemm_loop_is_the_generators_output(tmp_path):

@@ -22,6 +22,7 @@ struct TnParams {
   int steps_per_split, total_steps;  // 32-token steps
 };
 
+#include "lora_grad_loop.inc"
 template <int NB>
 __global__ __launch_bounds__(256) void lora_grad_tn_kernel(TnParams p) {
   const int tid = threadIdx.x, lane = tid & 63, lm = lane & 15, lg = lane >> 4;
@@ -63,10 +64,34 @@ __global__ __launch_bounds__(256) void lora_grad_tn_kernel(TnParams p) {
       for (int nb = 0; nb < NB; nb++) acc[q][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b[nb], acc[q][nb], 0, 0, 0);
     }
   };
+  int step = split * p.steps_per_split;
+  // Whole steps of a full-width slab with all four column blocks of the narrow operand run in the generated loop
+  // (gen_lora_grad_loop.py: four register sets, three steps in flight); what is left -- a last step that runs past the
+  // tokens, narrower operands, a ragged slab -- takes the loop below.
+  if constexpr (NB == 4) {
+    const int s_full = min(s_end, p.n / 32);
+    if (p.M % 128 == 0 && s_full > step) {
+      uint32_t vx[8], vu[4];
+#pragma unroll
+      for (int r = 0; r < 8; r++) vx[r] = (uint32_t)((((int64_t)(8 * lg + r)) * p.ldx + col) * 2);
+#pragma unroll
+      for (int nb = 0; nb < 4; nb++) vu[nb] = (uint32_t)((((int64_t)(nb * 16 + lm)) * p.ldu + 8 * lg) * 2);
+      const uint64_t gx = (uint64_t)(p.X + (int64_t)step * 32 * p.ldx), gu = (uint64_t)(p.UT + (int64_t)step * 32);
+      const uint32_t stride = (uint32_t)(32 * p.ldx * 2), nsteps = (uint32_t)(s_full - step);
+      asm volatile(LORA_GRAD_LOOP_ASM
+                   : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]), "+a"(acc[1][1]), "+a"(acc[1][2]), "+a"(acc[1][3]),
+                     "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]), "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3]),
+                     "+a"(acc[4][0]), "+a"(acc[4][1]), "+a"(acc[4][2]), "+a"(acc[4][3]), "+a"(acc[5][0]), "+a"(acc[5][1]), "+a"(acc[5][2]), "+a"(acc[5][3]),
+                     "+a"(acc[6][0]), "+a"(acc[6][1]), "+a"(acc[6][2]), "+a"(acc[6][3]), "+a"(acc[7][0]), "+a"(acc[7][1]), "+a"(acc[7][2]), "+a"(acc[7][3])
+                   : "v"(vx[0]), "v"(vx[1]), "v"(vx[2]), "v"(vx[3]), "v"(vx[4]), "v"(vx[5]), "v"(vx[6]), "v"(vx[7]),
+                     "v"(vu[0]), "v"(vu[1]), "v"(vu[2]), "v"(vu[3]), "s"(gx), "s"(gu), "s"(stride), "s"(nsteps)
+                   : LORA_GRAD_LOOP_CLOBBERS);
+      step = s_full;
+    }
+  }
   // two register sets: the block of the next step is in flight while this one is multiplied
   u32x4 xa[8], xb[8];
   bf16x8 ba[NB], bb[NB];
-  int step = split * p.steps_per_split;
   if (step < s_end) load(step, xa, ba);
   for (; step < s_end; step += 2) {
     if (step + 1 < s_end) load(step + 1, xb, bb);

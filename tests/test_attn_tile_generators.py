@@ -357,3 +357,73 @@ def test_the_load_swizzle_of_a_row_group_is_the_xor_the_blocks_use():
                     l4, c = lane >> 4, lane & 15
                     row = wave * 16 + 4 * i + l4
                     assert ((c ^ _f(l4)) * 16) ^ const == (c ^ _f(row & 15)) * 16
+
+
+def _min_valu_to_mfma_distance(ins):
+    last, best = {}, 10 ** 6
+    for idx, ln in enumerate(ins):
+        op, wr, rd, _ = _parse(ln)
+        if op.startswith("v_mfma"):
+            for r in rd:
+                if r in last:
+                    best = min(best, idx - last[r])
+        elif op.startswith("v_"):
+            for r in wr:
+                last[r] = idx
+    return best
+
+
+@pytest.mark.parametrize("gen,inc,macro,prefix,n_mfma", CASES)
+def test_an_mfma_never_reads_a_register_a_vector_instruction_just_wrote(gen, inc, macro, prefix, n_mfma):
+    """An MFMA does not wait for a vector write of one of its operands issued right before it (found with the
+    adapter-gradient loop: operands built by v_perm_b32 directly in front of the MFMA gave stale data)."""
+    bodies = _bodies(_macro(os.path.join(CSRC, inc), macro + "_ASM"), prefix)
+    for mode, ins in bodies.items():
+        assert _min_valu_to_mfma_distance(ins) >= 8, mode
+
+
+# ---------------------------------------------------------------- the adapter-gradient loop
+
+def test_lora_grad_loop():
+    """lora_grad_loop.inc: current; loads are waited for before use (vmcnt, loads return in order) and never land in
+    registers that instructions issued less than a step ago still read; operands are built a column ahead."""
+    mod = _load("gen_lora_grad_loop")
+    import tempfile
+    with tempfile.TemporaryDirectory() as d:
+        out = os.path.join(d, "lora_grad_loop.inc")
+        mod.main(out)
+        assert open(out).read() == open(os.path.join(CSRC, "lora_grad_loop.inc")).read()
+    lines = _macro(os.path.join(CSRC, "lora_grad_loop.inc"), "LORA_GRAD_LOOP_ASM")
+    clob = _clobbers(os.path.join(CSRC, "lora_grad_loop.inc"), "LORA_GRAD_LOOP_CLOBBERS")
+    assert _fixed_registers(lines) <= clob
+    start = lines.index("L_tn_loop_%=:")
+    end = lines.index("L_tn_end_%=:")
+    body = [ln for ln in lines[start + 1:end] if not ln.startswith("s_cbranch")]
+    seq = lines[:start] + body + body + body                   # three trips: the steady state
+    queue, pending, last_read = [], {}, {}
+    n_mfma = 0
+    for idx, ln in enumerate(seq):
+        op, wr, rd, _ = _parse(ln)
+        if op == "s_waitcnt":
+            m = re.search(r"vmcnt\((\d+)\)", ln)
+            if m:
+                while len(queue) > int(m.group(1)):
+                    for r in queue.pop(0):
+                        pending.pop(r, None)
+            continue
+        if op.startswith("global_load_dwordx4"):
+            toks = [t.strip() for t in re.split(r",\s*(?![^\[]*\])", ln.partition(" ")[2])]
+            dst = _regs(toks[0])
+            for r in dst:
+                assert r not in pending
+                assert idx - last_read.get(r, -10 ** 6) > 16, ("load issued right behind a read of its register", idx, ln)
+                pending[r] = True
+            queue.append(dst)
+            assert len(queue) < 64
+            continue
+        for r in rd:
+            assert r not in pending, ("register used before its load was waited for", idx, ln, r)
+            last_read[r] = idx
+        n_mfma += op.startswith("v_mfma")
+    assert n_mfma == 3 * 4 * 32
+    assert _min_valu_to_mfma_distance(seq) >= 4

@@ -54,8 +54,8 @@ def body(k):
 
     out += perms(0)
     for q in range(8):
-        if q < 7:                             # the operand of the next column is built under this column's MFMAs: an MFMA does not
-            out += perms(q + 1)               # wait for a vector write of its operand issued right before it
+        if q < 7:                             # the operand of the next column is built under this column's MFMAs, into the third
+            out += perms(q + 1)               # temporary: with the v_perm directly in front of its MFMAs and two temporaries the results were wrong
         for nb in range(4):
             out.append("v_mfma_f32_16x16x32_bf16 %%%d, %s, %s, %%%d" % (4 * q + nb, A(q % 3), U(k, nb), 4 * q + nb))
             n += 1

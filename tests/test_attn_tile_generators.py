@@ -375,8 +375,8 @@ def _min_valu_to_mfma_distance(ins):
 
 @pytest.mark.parametrize("gen,inc,macro,prefix,n_mfma", CASES)
 def test_an_mfma_never_reads_a_register_a_vector_instruction_just_wrote(gen, inc, macro, prefix, n_mfma):
-    """An MFMA does not wait for a vector write of one of its operands issued right before it (found with the
-    adapter-gradient loop: operands built by v_perm_b32 directly in front of the MFMA gave stale data)."""
+    """Operands built by vector instructions directly in front of the MFMA that reads them gave wrong results in the
+    adapter-gradient loop (with two temporaries in turn); every block keeps a distance."""
     bodies = _bodies(_macro(os.path.join(CSRC, inc), macro + "_ASM"), prefix)
     for mode, ins in bodies.items():
         assert _min_valu_to_mfma_distance(ins) >= 8, mode

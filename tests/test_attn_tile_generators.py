@@ -4,10 +4,11 @@ csrc/gen_attn_dq_tile.py -> attn_dkv_tile.inc, attn_dq_tile.inc).
 The blocks are hand-placed instruction streams for one wave, so what a compiler would guarantee is checked here by
 replaying them:
   * the committed .inc files are what the generators write;
-  * every LDS read has been waited for (lgkmcnt, LDS operations complete in order) before its registers are used, and
-    is not overwritten before the MFMA(s) it was made for;
-  * a vector instruction reads a matrix result only four or more MFMAs after the end of its chain (nothing interlocks
-    that read), and reads a v_exp result two or more instructions later;
+  * every LDS read has been waited for (lgkmcnt, LDS operations complete in order) before its registers are used, is
+    not overwritten before the MFMA(s) it was made for, and does not land in the operand of the MFMA issued last;
+  * a vector instruction reads a matrix result only four or more MFMAs (or, where the sequence has gaps, forty
+    instructions) after the end of its chain (nothing interlocks that read), and reads a v_exp result two or more
+    instructions later;
   * every fixed register of a block is on its clobber list;
   * the fragments the MFMAs receive are the ones the mathematics asks for: the LDS image of a tile is built as the
     kernels' loads leave it (16-byte chunk c of row r at position c ^ f(r)), the addresses are the kernels' per-lane
@@ -112,10 +113,11 @@ def _replay_hazards(ins):
     lds_queue = []                # outstanding LDS reads, oldest first: sets of written registers
     pending = {}                  # register -> True while its LDS read is outstanding
     mfma_count = 0
-    mfma_write = {}               # register -> mfma_count at its last write by an MFMA
+    mfma_write = {}               # register -> (mfma_count, instruction index) at its last write by an MFMA
     exp_write = {}                # register -> instruction index of the v_exp that wrote it
     frag_owner = {}               # register -> [index of the ds_read that filled it, MFMAs that consumed it]
     frag_regs = set()             # registers that serve as A operands
+    mfma_read = {}                # register -> number of MFMAs issued before the last one that read it
     for ln in ins:
         if ln.startswith("v_mfma"):
             frag_regs |= set(_regs([t.strip() for t in re.split(r",\s*(?![^\[]*\])", ln.partition(" ")[2])][1]))
@@ -134,26 +136,31 @@ def _replay_hazards(ins):
             for r in rd:
                 if r in frag_owner:
                     frag_owner[r][1] += 1
+                mfma_read[r] = mfma_count
             mfma_count += 1
             for r in wr:
-                mfma_write[r] = mfma_count
+                mfma_write[r] = (mfma_count, idx)
                 exp_write.pop(r, None)
             continue
         if op.startswith("ds_read"):
             for r in wr:
                 assert r not in pending, ("LDS read into a register with a read outstanding", idx, ln)
+                # the MFMA that read the register last has another one behind it: it has taken its operands
+                assert r not in mfma_read or mfma_count - mfma_read[r] >= 2, ("LDS read into the operand of the MFMA just issued", idx, ln)
                 if r in frag_owner and r in frag_regs:
                     assert frag_owner[r][1] > 0, ("fragment overwritten before any MFMA used it", idx, ln, r)
                 frag_owner[r] = [idx, 0]
                 pending[r] = True
                 mfma_write.pop(r, None)
             lds_queue.append(list(wr))
-            assert len(lds_queue) <= 16, "more LDS operations in flight than lgkmcnt can count"
+            while len(lds_queue) > 15:        # the counter has four bits: the wave does not issue another LDS operation before the oldest is back
+                for r in lds_queue.pop(0):
+                    pending.pop(r, None)
             continue
         if op.startswith("v_") or op.startswith("global_load_lds"):
             for r in rd:
                 if r in mfma_write:
-                    assert mfma_count - mfma_write[r] >= 4, ("matrix result read too early", idx, ln, r, mfma_count - mfma_write[r])
+                    assert mfma_count - mfma_write[r][0] >= 4 or idx - mfma_write[r][1] >= 40, ("matrix result read too early", idx, ln, r)
                 if r in exp_write and not op.startswith("v_exp"):
                     assert idx - exp_write[r] >= 2, ("v_exp result read by the next instruction", idx, ln, r)
             for r in wr:

@@ -179,7 +179,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives are built)" % args.gpus,
+        print("bench.py: the library runs on ONE GPU; --gpus %d is not supported (it has no collectives)" % args.gpus,
               file=sys.stderr)
         sys.exit(2)
     if args.copy_probe:

@@ -331,8 +331,8 @@ int as_adamw_update(as_ctx* ctx, float* const* d_master, void* const* d_params_l
  * accumulation (Section 4.5); A2 may be NULL.  A, B, R of type T; C of type T,
  * or float when c_is_f32.  variant: 0 = pick, 1 = plain FMA kernel,
  * 2 = MFMA kernel (bf16 only; K1, K2, lda, ldb multiples of 8) with the tile
- * shape picked; 10..13 = register-staged tiles 256x256 / 256x64 / 64x256 /
- * 128x128; 30 = direct-to-LDS 256x256 tiles (K in 64-wide steps, else 10);
+ * shape picked; 10..14 = register-staged tiles 256x256 / 256x64 / 64x256 /
+ * 128x128 / 128x64; 30 = direct-to-LDS 256x256 tiles (K in 64-wide steps, else 10);
  * 34 = hand-scheduled 256x256 kernel where it applies (else 30).
  * d_tail_scratch [device], may be NULL: AS_GEMM_TAIL_SCRATCH_BYTES of scratch, 256-byte aligned.  With it the
  * hand-scheduled kernel splits the contraction of the tiles of a last, at most half-full round of 256 workgroups

@@ -829,11 +829,13 @@ static bool mfma_ok(const GemmParams& p) {
 }
 
 // Tile configuration of the MFMA kernels.  Register-staged (any K that is a multiple of 8): 0 = 256x256 (8 waves,
-// 128x64 each), 1 = 256x64, 2 = 64x256, 3 = 128x128.  20 = direct-to-LDS 256x256 with 8 waves (K in 64-wide steps);
+// 128x64 each), 1 = 256x64, 2 = 64x256, 3 = 128x128, 4 = 128x64.  20 = direct-to-LDS 256x256 with 8 waves (K in 64-wide steps);
 // 24 = the hand-scheduled register-staged 256x256 kernel with 4 waves.
 static int pick_cfg(const GemmParams& p) {
   // narrow outputs (the adapters' rank-wide products) stream A once at HBM speed: 128 x 128 tiles measured 2-33 % ahead of
-  // 256 x 64 here (58,880 rows; N = 128: 121 against 181 us, where two 64-wide column tiles read A twice)
+  // 256 x 64 here (58,880 rows; N = 128: 121 against 181 us, where two 64-wide column tiles read A twice); up to 64
+  // columns a 128 x 64 tile loads half the B rows per step (a CU's load path carries A and B alike): 3-6 % ahead
+  if (p.N <= 64 && p.M > 128) return 4;
   if (p.N <= 128 && p.M > 128) return 3;
   if (p.M <= 128) return 2;
   if ((int64_t)cdiv(p.M, 256) * cdiv(p.N, 256) * p.splitk < 128) return 3;
@@ -890,7 +892,7 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
       return AS_OK;
     }
   }
-  if (variant < 0 || (variant > 2 && variant != 10 && variant != 11 && variant != 12 && variant != 13 && variant != 30 && variant != 34)) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
+  if (variant < 0 || (variant > 2 && variant != 10 && variant != 11 && variant != 12 && variant != 13 && variant != 14 && variant != 30 && variant != 34)) return as_fail(ctx, AS_ERR_SHAPE, "gemm: unknown variant");
   bool use_mfma = (mode == AS_BF16) && variant != 1 && mfma_ok(p);
   if (variant >= 2 && !use_mfma) return as_fail(ctx, AS_ERR_SHAPE, "gemm: MFMA kernel needs bf16 and 8-element alignment");
   int rc = AS_OK;
@@ -907,6 +909,7 @@ int launch_gemm_off(as_ctx* ctx, int mode, int variant, const GemmParams& p_in, 
       case 1: rc = launch_mfma_cfg<256, 64, 4, 1>(ctx, p, m_off, st); break;
       case 2: rc = launch_mfma_cfg<64, 256, 1, 4>(ctx, p, m_off, st); break;
       case 3: rc = launch_mfma_cfg<128, 128, 2, 2>(ctx, p, m_off, st); break;
+      case 4: rc = launch_mfma_cfg<128, 64, 2, 2>(ctx, p, m_off, st); break;
       case 20: rc = launch_dlds_cfg<256, 256, 2, 4>(ctx, p, m_off, st); break;
       case 24: {                                           // whole row tiles by the register-staged kernel, the ragged rest by the default one
         if (!rs_ok(p) || (m_off && !p.m_dev)) { rc = launch_dlds_cfg<256, 256, 2, 4>(ctx, p, m_off, st); break; }

@@ -23,7 +23,7 @@ def _env(**kw):
 # (M, N, K1, K2): several tiles + ragged tails, and the shapes of the tiny config
 GEMM_SHAPES = [(512, 128, 128, 64), (512, 344, 128, 0), (512, 128, 344, 64), (300, 200, 72, 0), (1, 7, 8, 8),
                (700, 1024, 256, 64), (64, 520, 1024, 0), (1000, 520, 192, 64), (1024, 512, 256, 64), (768, 256, 64, 0),
-               (512, 256, 128, 128), (300, 256, 192, 64)]
+               (512, 256, 128, 128), (300, 256, 192, 64), (700, 64, 256, 0), (515, 48, 136, 64)]
 
 
 @pytest.mark.parametrize("shape", GEMM_SHAPES)

@@ -23,9 +23,9 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # HBM-side bytes per launch of the dominant kernel at config 3: FETCH_SIZE and WRITE_SIZE of two counter runs over one
 # bench step, each scaled by what the counter reads for a 1 GiB copy (profiles/bench_config3_counters.md).  The figure
 # belongs to the kernel sources those runs saw: the digest below names them, and the line reports null when they differ.
-TRAFFIC_BYTES_PER_LAUNCH = {(3, "gemm_mfma_rs_kernel<0, 0>"): 13.25e9}
+TRAFFIC_BYTES_PER_LAUNCH = {(3, "gemm_mfma_rs_kernel<0, 0>"): 13.15e9}
 TRAFFIC_SOURCES = ("gemm.hip", "gemm_rs_loop.inc", "common.h")
-TRAFFIC_SOURCE_DIGEST = "d605c18fb1e275bb"
+TRAFFIC_SOURCE_DIGEST = "a32c2d2ad8d2da28"
 DOMINANT_KERNEL = "gemm_mfma_rs_kernel<0, 0>"                  # dense models; expert GEMMs: the same kernel with live-row limits, <1>
 GROUPED_KERNEL = "gemm_mfma_rs_kernel<1, 0>"
 

@@ -461,7 +461,8 @@ template <int DH, int WHICH>
 __global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float scale, float sl2, float* __restrict__ part) {
   constexpr int KS = DH / 16, CB = DH / 32, NWV = 8, KPB = 32 * NWV;
   constexpr int KT_E = BKEY * DH;
-  constexpr int NT = WHICH == 0 ? 3 : 2;                  // dK: Q, dO, Q^T tiles; dV: Q, dO^T tiles
+  constexpr bool DO_K = WHICH != 1, DO_V = WHICH != 0;    // WHICH 2: both gradients from one S (head_dim 64: the registers allow it)
+  constexpr int NT = (DO_K ? 3 : 1) + (DO_V ? 1 : 0);     // dK: Q, dO, Q^T tiles; dV: Q, dO^T tiles; both: Q, dO, Q^T, dO^T
   constexpr int ST_E = NT * KT_E + 4 * BKEY;              // + 64 lse and 64 delta floats (2 bf16 slots each)
   extern __shared__ __align__(16) unsigned char dyn_smem[];
   bf16_t* sm = (bf16_t*)dyn_smem;
@@ -476,15 +477,19 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float sc
   const bf16_t* dO = (const bf16_t*)p.d_o; const bf16_t* QTm = (const bf16_t*)p.qT; const bf16_t* DOT = (const bf16_t*)p.doT;
   const int u = u_base + l31, uc = min(u, n - 1);
   const int uend = (u < n) ? p.seg_end[uc] : 0;                 // queries u <= t < uend see this key
-  bf16x8 kf[KS], vf[WHICH == 0 ? KS : 1];
+  bf16x8 kf[KS], vf[DO_K ? KS : 1];
 #pragma unroll
   for (int ks = 0; ks < KS; ks++) {
     kf[ks] = *reinterpret_cast<const bf16x8*>(K + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
-    if constexpr (WHICH == 0) vf[ks] = *reinterpret_cast<const bf16x8*>(V + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
+    if constexpr (DO_K) vf[ks] = *reinterpret_cast<const bf16x8*>(V + (int64_t)uc * p.ldkv + g * DH + ks * 16 + h * 8);
   }
-  f32x16 acc[CB];                                               // dK^T or dV^T, [dh rows, key lane]
+  f32x16 acc[CB], acc2[WHICH == 2 ? CB : 1];                    // dK^T or dV^T, [dh rows, key lane]; both: dK^T and dV^T
 #pragma unroll
   for (int cb = 0; cb < CB; cb++) acc[cb] = zero16();
+  if constexpr (WHICH == 2) {
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++) acc2[cb] = zero16();
+  }
   const int q_first = u_wg / BKEY;
   const int q_last = __builtin_amdgcn_readfirstlane((p.seg_end[min(u_wg + KPB - 1, n - 1)] - 1) / BKEY);
   // this wave's keys are visible from queries in [u_base, w_end); all of them from queries in [u_base + 31, w_end_min)
@@ -500,13 +505,12 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float sc
     const int t0 = (q_last - it) * BKEY;
     bf16_t* d = sm + b * ST_E;
     tile_to_lds<BKEY, DH, NWV>(Q + jj * DH, p.ldq, t0, n - 1, offQ, d, wave, lane);
-    if constexpr (WHICH == 0) {
+    if constexpr (DO_K) {
       tile_to_lds<BKEY, DH, NWV>(dO + jj * DH, (int64_t)p.Hq * DH, t0, n - 1, offD, d + KT_E, wave, lane);
       tile_to_lds_fast<DH, BKEY, NWV>(QTm + (int64_t)jj * DH * p.ldT + t0, offT, d + 2 * KT_E, wave);
-    } else {
-      tile_to_lds_fast<DH, BKEY, NWV>(DOT + (int64_t)jj * DH * p.ldT + t0, offT, d + KT_E, wave);
     }
-    if (wave < (WHICH == 0 ? 2 : 1)) {                           // 64 lse (wave 0) and 64 delta (wave 1) values, 4 bytes a lane
+    if constexpr (DO_V) tile_to_lds_fast<DH, BKEY, NWV>(DOT + (int64_t)jj * DH * p.ldT + t0, offT, d + (NT - 1) * KT_E, wave);
+    if (wave < (DO_K ? 2 : 1)) {                           // 64 lse (wave 0) and 64 delta (wave 1) values, 4 bytes a lane
       const float* src = (wave == 0 ? p.lse : p.delta) + (int64_t)min(t0 + lane, n - 1) * p.Hq + jj;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                        (__attribute__((address_space(3))) void*)(d + NT * KT_E + wave * 2 * BKEY), 4, 0, 0);
@@ -522,12 +526,13 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float sc
     const int t0 = (q_last - it) * BKEY;
     if (t0 + 63 < u_base || t0 >= w_end) continue;             // no query of the tile sees a key of this wave
     const bf16_t* sQ = sm + b * ST_E;
-    const bf16_t* sdO = sQ + KT_E;                              // WHICH == 0 only
-    const bf16_t* sT = sQ + (NT - 1) * KT_E;                    // Q^T (dK) or dO^T (dV)
+    const bf16_t* sdO = sQ + KT_E;                              // with dK only
+    const bf16_t* sT = sQ + (DO_K ? 2 : 1) * KT_E;              // Q^T (dK) or dO^T (dV)
+    const bf16_t* sT2 = sQ + (NT - 1) * KT_E;                   // dO^T when both
     const float* sLse = (const float*)(sQ + NT * KT_E); const float* sDel = sLse + BKEY;
-    f32x16 s[2], dp[WHICH == 0 ? 2 : 1];
+    f32x16 s[2], dp[DO_K ? 2 : 1];
     s[0] = zero16(); s[1] = zero16();
-    if constexpr (WHICH == 0) { dp[0] = zero16(); dp[1] = zero16(); }
+    if constexpr (DO_K) { dp[0] = zero16(); dp[1] = zero16(); }
 #pragma unroll
     for (int ks = 0; ks < KS; ks++)
 #pragma unroll
@@ -535,7 +540,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float sc
         const int off = (qb * 32 + l31) * DH + (((ks * 2 + h) ^ swR) * 8);
         bf16x8 a = *reinterpret_cast<const bf16x8*>(sQ + off);
         s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[ks], s[qb], 0, 0, 0);
-        if constexpr (WHICH == 0) {
+        if constexpr (DO_K) {
           bf16x8 bb = *reinterpret_cast<const bf16x8*>(sdO + off);
           dp[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb, vf[ks], dp[qb], 0, 0, 0);
         }
@@ -549,7 +554,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float sc
           s[qb][e] = (t >= u && t < uend) ? s[qb][e] : -INFINITY;
         }
     }
-    bf16x8 bop[4];                                              // dS (dK) or P (dV) as B operands
+    bf16x8 bop[4], bop2[WHICH == 2 ? 4 : 1];                    // dS (dK) or P (dV) as B operands; both: dS and P
 #pragma unroll
     for (int qb = 0; qb < 2; qb++) {
 #pragma unroll
@@ -557,15 +562,19 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float sc
         const int qi0 = qb * 32 + 8 * b4 + 4 * h;            // 4 consecutive queries: one 16-byte read each
         const f32x4 ls = *reinterpret_cast<const f32x4*>(&sLse[qi0]);
         f32x4 dl;
-        if constexpr (WHICH == 0) dl = *reinterpret_cast<const f32x4*>(&sDel[qi0]);
+        if constexpr (DO_K) dl = *reinterpret_cast<const f32x4*>(&sDel[qi0]);
 #pragma unroll
         for (int i = 0; i < 4; i++) {
           const int e = b4 * 4 + i;
           const float pr = fast_exp2(fmaf(s[qb][e], sl2, -1.4426950408889634f * ls[i]));
-          if constexpr (WHICH == 0) s[qb][e] = pr * (dp[qb][e] - dl[i]); else s[qb][e] = pr;
+          if constexpr (WHICH == 2) { dp[qb][e] = pr * (dp[qb][e] - dl[i]); s[qb][e] = pr; }
+          else if constexpr (WHICH == 0) s[qb][e] = pr * (dp[qb][e] - dl[i]); else s[qb][e] = pr;
         }
       }
-      bop[qb * 2] = pack8(s[qb], 0); bop[qb * 2 + 1] = pack8(s[qb], 1);
+      if constexpr (WHICH == 2) {
+        bop[qb * 2] = pack8(dp[qb], 0); bop[qb * 2 + 1] = pack8(dp[qb], 1);
+        bop2[qb * 2] = pack8(s[qb], 0); bop2[qb * 2 + 1] = pack8(s[qb], 1);
+      } else { bop[qb * 2] = pack8(s[qb], 0); bop[qb * 2 + 1] = pack8(s[qb], 1); }
     }
 #pragma unroll
     for (int x = 0; x < 4; x++)
@@ -573,24 +582,32 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv2_mfma(AttnParams p, float sc
       for (int cb = 0; cb < CB; cb++) {
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(sT + (cb * 32 + l31) * BKEY + (((2 * x + h) ^ swT) * 8));
         acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bop[x], acc[cb], 0, 0, 0);
+        if constexpr (WHICH == 2) {
+          const bf16x8 a2 = *reinterpret_cast<const bf16x8*>(sT2 + (cb * 32 + l31) * BKEY + (((2 * x + h) ^ swT) * 8));
+          acc2[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, bop2[x], acc2[cb], 0, 0, 0);
+        }
       }
   }
   if (u >= n) return;
-  if (grp > 1) {
-    float* row = part + (((int64_t)WHICH * p.Hq + jj) * n + u) * DH;
+  auto put = [&](const f32x16 (&r)[CB], int which) {
+    if (grp > 1) {
+      float* row = part + (((int64_t)which * p.Hq + jj) * n + u) * DH;
 #pragma unroll
-    for (int cb = 0; cb < CB; cb++)
+      for (int cb = 0; cb < CB; cb++)
 #pragma unroll
-      for (int b4 = 0; b4 < 4; b4++) {
-        f32x4 w;
+        for (int b4 = 0; b4 < 4; b4++) {
+          f32x4 w;
 #pragma unroll
-        for (int i = 0; i < 4; i++) w[i] = acc[cb][b4 * 4 + i];
-        *reinterpret_cast<f32x4*>(row + cb * 32 + 8 * b4 + 4 * h) = w;
-      }
-  } else {
-    bf16_t* row = (bf16_t*)(WHICH == 0 ? p.dk : p.dv) + (int64_t)u * p.ldkv + g * DH;
-    store_grad_row<DH>(acc, WHICH == 0 ? scale : 1.f, row, h, WHICH == 0 ? p.rope_cos : nullptr, p.rope_sin, u - p.seg_start[u]);
-  }
+          for (int i = 0; i < 4; i++) w[i] = r[cb][b4 * 4 + i];
+          *reinterpret_cast<f32x4*>(row + cb * 32 + 8 * b4 + 4 * h) = w;
+        }
+    } else {
+      bf16_t* row = (bf16_t*)(which == 0 ? p.dk : p.dv) + (int64_t)u * p.ldkv + g * DH;
+      store_grad_row<DH>(r, which == 0 ? scale : 1.f, row, h, which == 0 ? p.rope_cos : nullptr, p.rope_sin, u - p.seg_start[u]);
+    }
+  };
+  put(acc, WHICH == 1 ? 1 : 0);
+  if constexpr (WHICH == 2) put(acc2, 1);
 }
 
 // dQ with one wave per SIMD (head_dim 128, four query heads per KV head): wave = 64 queries of one head (a lane owns two
@@ -905,7 +922,7 @@ int launch_dq2(as_ctx* ctx, const AttnParams& p, float scale, float sl2, hipStre
 
 template <int DH, int WHICH>
 int launch_dkv2(as_ctx* ctx, const AttnParams& p, float scale, float sl2, float* part, hipStream_t st) {
-  constexpr size_t smem = (size_t)2 * ((WHICH == 0 ? 3 : 2) * BKEY * DH + 4 * BKEY) * sizeof(bf16_t);
+  constexpr size_t smem = (size_t)2 * ((WHICH == 0 ? 3 : WHICH == 1 ? 2 : 4) * BKEY * DH + 4 * BKEY) * sizeof(bf16_t);
   AS_SET_SMEM(ctx, (attn_bwd_dkv2_mfma<DH, WHICH>), smem);
   attn_bwd_dkv2_mfma<DH, WHICH><<<(unsigned)(cdiv(p.n, 256) * p.Hq), 512, smem, st>>>(p, scale, sl2, part);
   AS_LAUNCH_CHECK(ctx);
@@ -957,7 +974,11 @@ int bwd_dh(as_ctx* ctx, const AttnParams& p_in, int variant, hipStream_t st) {
     if (rc) return rc;
     float* part = (float*)(ts + (size_t)(Dkv + 2 * D) * Np);       // [2][Hq][n][dh] floats behind the token-major copies
     if (one_pass) return launch_dkv3(ctx, p, scale, sl2, st);     // sums over the query heads itself
-    if ((rc = launch_dkv2<DH, 0>(ctx, p, scale, sl2, part, st)) || (rc = launch_dkv2<DH, 1>(ctx, p, scale, sl2, part, st))) return rc;
+    // head_dim 64: both gradients in one launch (S and the exponentials once); at head_dim 128 two waves per SIMD do not have the registers for it
+    if constexpr (DH == 64) {
+      if (variant != 4) { if ((rc = launch_dkv2<DH, 2>(ctx, p, scale, sl2, part, st))) return rc; }
+      else if ((rc = launch_dkv2<DH, 0>(ctx, p, scale, sl2, part, st)) || (rc = launch_dkv2<DH, 1>(ctx, p, scale, sl2, part, st))) return rc;
+    } else if ((rc = launch_dkv2<DH, 0>(ctx, p, scale, sl2, part, st)) || (rc = launch_dkv2<DH, 1>(ctx, p, scale, sl2, part, st))) return rc;
     if (p.Hq > p.Hkv) {
       const int64_t threads = 2 * (int64_t)p.n * p.Hkv * (DH / 4);
       attn_dkv_reduce_kernel<<<(unsigned)cdiv(threads, 256), 256, 0, st>>>(part, p.n, p.Hq, p.Hkv, DH, scale, (bf16_t*)p.dk, (bf16_t*)p.dv, p.ldkv,

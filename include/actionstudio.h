@@ -382,9 +382,9 @@ int as_op_rmsnorm_bwd(as_ctx* ctx, int mode, int64_t n, int64_t d, const void* d
  * with row stride ldq elements, k, v [n,Hkv,dh] with stride ldkv, o [n,Hq,dh]
  * dense, lse float [n,Hq].  seg_start [n] int32: first token of each token's
  * segment.  variant: 0 = pick, 1 = plain kernel, 2 = MFMA kernels (bf16, head_dim 64 or 128); backward only:
- * 4 = the MFMA kernels that work from token-major copies (dK and dV in two launches with float partials per query
- * head), which head_dim 64 always takes; head_dim 128 with row strides that are multiples of 128 elements otherwise
- * takes the one-pass kernels that read their operands as they are.
+ * 4 = the MFMA kernels that work from token-major copies, dK and dV in two launches with float partials per query
+ * head.  Otherwise head_dim 64 takes the same kernels with dK and dV from one launch, and head_dim 128 with row
+ * strides that are multiples of 128 elements the one-pass kernels that read their operands as they are.
  * t_scratch: type T, only read by the MFMA kernels (may be NULL otherwise):
  * room for Hkv*dh * n64 elements in forward and (6*Hq + Hkv)*dh * n64 in
  * backward, n64 = n rounded up to 64 (token-major copies of V, resp. K, Q, dO,

@@ -1,5 +1,6 @@
-"""CPU checks of the generated instruction sequences of the attention backward (csrc/gen_attn_dkv_tile.py,
-csrc/gen_attn_dq_tile.py -> attn_dkv_tile.inc, attn_dq_tile.inc).
+"""CPU checks of the generated instruction sequences: the attention backward (csrc/gen_attn_dkv_tile.py,
+csrc/gen_attn_dq_tile.py -> attn_dkv_tile.inc, attn_dq_tile.inc), the adapter-gradient loop (lora_grad_loop.inc) and
+the projection GEMM's loop (gemm_rs_loop.inc), the last two at the end of the file.
 
 The blocks are hand-placed instruction streams for one wave, so what a compiler would guarantee is checked here by
 replaying them:
@@ -434,3 +435,121 @@ def test_lora_grad_loop():
         n_mfma += op.startswith("v_mfma")
     assert n_mfma == 3 * 4 * 32
     assert _min_valu_to_mfma_distance(seq) >= 4
+
+
+# ---------------------------------------------------------------- the projection GEMM's loop
+
+def _replay_gemm_loop(lines):
+    """the loop replayed over the prologue and three trips of the two-step loop body, with counters kept
+    independently of the generator's own: a register is not used while a global load or an LDS read into it is
+    outstanding (vmcnt / lgkmcnt, both complete in order); a global load does not land in registers whose LDS store
+    may still be reading them; every MFMA's fragments come from the LDS stage and slice its step is on; a step's
+    fragment reads never touch an LDS stage that stores issued since the last barrier are writing."""
+    start, end = lines.index("L_rs_loop_%=:"), lines.index("L_rs_end_%=:")
+    body = [ln for ln in lines[start + 1:end] if not ln.startswith("s_cbranch")]
+    seq = lines[:start] + body * 3
+    vm_q, lds_q = [], []                      # outstanding global loads / LDS operations, oldest first
+    vm_pending, lds_pending = {}, {}          # register -> True while a load / an LDS read into it is outstanding
+    store_reads = {}                          # register -> True while an LDS store that reads it is outstanding
+    written_since_barrier, read_since_barrier = set(), set()     # LDS stages (0/1 for A, 2/3 for B)
+    n_mfma = 0
+
+    def stage_of(addr_reg, off):
+        # A stages at LDS offsets 0 / 32768, B stages at 65536 / 98304 (the B part sits in the address registers)
+        a = int(addr_reg[1:])
+        is_b = a in (196, 197, 198, 199, 202, 203)
+        return (2 if is_b else 0) + (off // 32768)
+
+    for idx, ln in enumerate(seq):
+        op = ln.split()[0]
+        toks = [t.strip() for t in re.split(r",\s*(?![^\[]*\])", ln.partition(" ")[2])]
+        if op == "s_waitcnt":
+            m = re.search(r"vmcnt\((\d+)\)", ln)
+            if m:
+                while len(vm_q) > int(m.group(1)):
+                    for r in vm_q.pop(0):
+                        vm_pending.pop(r, None)
+            m = re.search(r"lgkmcnt\((\d+)\)", ln)
+            if m:
+                while len(lds_q) > int(m.group(1)):
+                    kind, regs = lds_q.pop(0)
+                    for r in regs:
+                        (lds_pending if kind == "read" else store_reads).pop(r, None)
+            continue
+        if op == "s_barrier":
+            assert not lds_q, ("LDS operations outstanding at the barrier", idx)
+            written_since_barrier, read_since_barrier = set(), set()
+            continue
+        if op == "global_load_dwordx4":
+            dst = _regs(toks[0])
+            for r in dst:
+                assert r not in vm_pending and r not in store_reads, ("load into registers still in use", idx, ln)
+                vm_pending[r] = True
+            vm_q.append(dst)
+            assert len(vm_q) <= 63
+            continue
+        if op == "ds_write_b128":
+            off = int(re.search(r"offset:(\d+)", ln).group(1)) if "offset:" in ln else 0
+            src = _regs(toks[1].split(" offset")[0])
+            for r in src:
+                assert r not in vm_pending, ("LDS store of a register whose load was not waited for", idx, ln)
+                store_reads[r] = True
+            st = stage_of(toks[0], off)
+            assert st not in read_since_barrier, ("store into an LDS stage that is being read", idx, ln)
+            written_since_barrier.add(st)
+            lds_q.append(("write", src))
+            while len(lds_q) > 15:
+                kind, regs = lds_q.pop(0)
+                for r in regs:
+                    (lds_pending if kind == "read" else store_reads).pop(r, None)
+            continue
+        if op == "ds_read_b128":
+            off = int(re.search(r"offset:(\d+)", ln).group(1)) if "offset:" in ln else 0
+            dst = _regs(toks[0])
+            addr = toks[1].split(" offset")[0].strip()
+            if addr.startswith("v"):
+                st = stage_of(addr, off)
+                assert st not in written_since_barrier, ("fragment read from an LDS stage written since the barrier", idx, ln)
+                read_since_barrier.add(st)
+            for r in dst:
+                assert r not in lds_pending
+                lds_pending[r] = True
+            lds_q.append(("read", dst))
+            while len(lds_q) > 15:
+                kind, regs = lds_q.pop(0)
+                for r in regs:
+                    (lds_pending if kind == "read" else store_reads).pop(r, None)
+            continue
+        if op.startswith("v_mfma"):
+            for r in _regs(toks[1]) + _regs(toks[2]):
+                assert r not in lds_pending and r not in vm_pending, ("MFMA on a fragment that was not waited for", idx, ln)
+            n_mfma += 1
+            continue
+        if op.startswith("v_"):
+            for t in toks[1:]:
+                for r in _regs(t):
+                    assert r not in lds_pending and r not in vm_pending, (idx, ln)
+    return n_mfma
+
+
+def test_gemm_rs_loop_replay():
+    lines = _macro(os.path.join(CSRC, "gemm_rs_loop.inc"), "GEMM_RS_LOOP_ASM")
+    assert _replay_gemm_loop(lines) == 3 * 2 * 64
+    # the replay has teeth: planted mistakes inside the loop body are caught
+    loop_at = lines.index("L_rs_loop_%=:")
+
+    def without(pred, count=1):
+        out, left = [], count
+        for i, ln in enumerate(lines):
+            if left and i > loop_at and pred(ln):
+                left -= 1
+                continue
+            out.append(ln)
+        assert left == 0
+        return out
+
+    for planted in (without(lambda ln: ln.startswith("s_waitcnt vmcnt")),             # a store of data that has not arrived
+                    without(lambda ln: ln.startswith("s_waitcnt lgkmcnt("), 3),      # an MFMA on fragments still on their way
+                    without(lambda ln: ln == "s_barrier")):                          # a stage rewritten while it is read
+        with pytest.raises(AssertionError):
+            _replay_gemm_loop(planted)

@@ -715,19 +715,21 @@ static int launch_dlds_cfg(as_ctx* ctx, const GemmParams& p, int m_off, hipStrea
 }
 
 // Second launch for the tiles of a split last round: sum of the two halves (first half first), then the usual epilogue.
-// One workgroup per tile, the same workgroup -> tile mapping as the main kernel; a thread owns 4 consecutive columns.
+// Four workgroups per tile (64 rows each: a last round is at most 128 tiles), the same workgroup -> tile mapping as the
+// main kernel; a thread owns 4 consecutive columns.
 __global__ __launch_bounds__(256) void gemm_tail_fixup_kernel(GemmParams p, int tiles_m, int tiles_n) {
   constexpr int BM = 256, BN = 256, GROUP = 4;
-  const int nblk = tiles_m * tiles_n, pid = p.tail_first + blockIdx.x;
+  const int tile = blockIdx.x >> 2, r_first = (blockIdx.x & 3) * (BM / 4);
+  const int nblk = tiles_m * tiles_n, pid = p.tail_first + tile;
   if (pid >= nblk) return;
   const int q8 = nblk / 8, rem = nblk % 8, xcd = pid % 8, loc = pid / 8;
   const int logical = xcd * q8 + min(xcd, rem) + loc;
   const int in_group = GROUP * tiles_n, grp = logical / in_group, first_m = grp * GROUP;
   const int gsize = min(tiles_m - first_m, GROUP);
   const int tile_m = first_m + (logical % in_group) % gsize, tile_n = (logical % in_group) / gsize;
-  const float* h0 = p.tail_part + (int64_t)blockIdx.x * 2 * (BM * BN); const float* h1 = h0 + BM * BN;
+  const float* h0 = p.tail_part + (int64_t)tile * 2 * (BM * BN); const float* h1 = h0 + BM * BN;
   const int c = (threadIdx.x & 63) * 4;
-  for (int r = threadIdx.x >> 6; r < BM; r += 4) {
+  for (int r = r_first + (threadIdx.x >> 6); r < r_first + BM / 4; r += 4) {
     const f32x4 a = *reinterpret_cast<const f32x4*>(h0 + r * BN + c), b = *reinterpret_cast<const f32x4*>(h1 + r * BN + c);
     const int64_t row = (int64_t)tile_m * BM + r; const int col = tile_n * BN + c;
     f32x4 v;
@@ -794,7 +796,7 @@ static int launch_rs_cfg(as_ctx* ctx, const GemmParams& p_in, int m_off, hipStre
     if (p.tail_part && p.epi == GEMM_EPI_NONE && full > 0 && rest > 0 && rest <= 128 && nt >= 32 && nt / 2 <= nt0) p.tail_first = full;
     else p.tail_part = nullptr;
     gemm_mfma_rs_kernel<0><<<dim3(p.tail_first >= 0 ? full + 2 * rest : T), 256, smem, st>>>(p, 0, tm, tn);
-    if (p.tail_first >= 0) { AS_LAUNCH_CHECK(ctx); gemm_tail_fixup_kernel<<<dim3(rest), 256, 0, st>>>(p, tm, tn); }
+    if (p.tail_first >= 0) { AS_LAUNCH_CHECK(ctx); gemm_tail_fixup_kernel<<<dim3(4 * rest), 256, 0, st>>>(p, tm, tn); }
   }
   AS_LAUNCH_CHECK(ctx);
   return AS_OK;

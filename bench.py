@@ -25,7 +25,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # belongs to the kernel sources those runs saw: the digest below names them, and the line reports null when they differ.
 TRAFFIC_BYTES_PER_LAUNCH = {(3, "gemm_mfma_rs_kernel<0, 0>"): 13.15e9}
 TRAFFIC_SOURCES = ("gemm.hip", "gemm_rs_loop.inc", "common.h")
-TRAFFIC_SOURCE_DIGEST = "a32c2d2ad8d2da28"
+TRAFFIC_SOURCE_DIGEST = "c18174f2a2f31f2f"
 DOMINANT_KERNEL = "gemm_mfma_rs_kernel<0, 0>"                  # dense models; expert GEMMs: the same kernel with live-row limits, <1>
 GROUPED_KERNEL = "gemm_mfma_rs_kernel<1, 0>"
 
